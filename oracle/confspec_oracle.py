@@ -1,0 +1,256 @@
+"""fp64 CPU oracle for the batched verification pass (TEST INFRASTRUCTURE).
+
+This file is the slow, plain definition that the GPU library is checked
+against.  It is imported only by the tests, the smoke check and the benchmark's
+CPU-baseline leg; the product path never calls it and shares no code with it.
+
+What it computes, and where the paper defines it:
+
+* A verifier model reads the cached reasoning context, the drafted step, the
+  target's step and a verification prompt, and emits a decision token together
+  with that token's softmax probability (Section 4.2, Eq. 2 and Eq. 3, and the
+  sentence after Eq. 3 on the "Yes"/"No" verification token).
+* The probability that counts is the one of the *predicted* decision
+  (Section 4.1, "Confidence as a Reliability Signal").
+* The decision is kept when that probability is at least the threshold gamma
+  and escalated to the larger model otherwise (Section 4.2, Eq. 4; Algorithm 1,
+  the statement that assigns V inside the verification loop).
+
+The paper does not spell out the transformer under the verifier; it is the
+standard pre-norm decoder its model families use (RMSNorm, rotary positions in
+the half-split pairing, grouped-query causal attention, SwiGLU MLP, no biases).
+Readings taken where the paper is silent: the softmax runs over the verdict
+tokens only, so their probabilities sum to one; ties in the argmax go to the
+lowest index; cached keys are stored after rotation; the suffix is never
+written back to the cache.
+
+Every function works on float64 numpy arrays.  Nothing is blocked, fused or
+reordered beyond the formulas as written.
+"""
+from __future__ import annotations
+
+import math
+from typing import Callable, List, Optional, Sequence
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- #
+# decoder building blocks (standard definitions)
+# --------------------------------------------------------------------------- #
+def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
+    """RMSNorm(x)_i = x_i / sqrt(mean_j x_j^2 + eps) * g_i, over the last axis."""
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * g
+
+
+def rope(a: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
+    """Rotary position embedding, half-split pairing (i, i + hd/2).
+
+    a: [n, H, hd]; pos: [n] absolute positions.  For i in [0, hd/2):
+    phi = pos * theta^(-2i/hd);
+    (a_i, a_{i+hd/2}) <- (a_i cos phi - a_{i+hd/2} sin phi, a_{i+hd/2} cos phi + a_i sin phi).
+    """
+    hd = a.shape[-1]
+    half = hd // 2
+    i = np.arange(half, dtype=np.float64)
+    inv_freq = theta ** (-2.0 * i / hd)
+    phi = np.asarray(pos, dtype=np.float64)[:, None] * inv_freq[None, :]
+    c = np.cos(phi)[:, None, :]
+    s = np.sin(phi)[:, None, :]
+    lo, hi = a[..., :half], a[..., half:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+
+def softmax(s: np.ndarray, axis: int = -1) -> np.ndarray:
+    m = np.max(s, axis=axis, keepdims=True)
+    e = np.exp(s - m)
+    return e / np.sum(e, axis=axis, keepdims=True)
+
+
+def attention(q: np.ndarray, k_all: np.ndarray, v_all: np.ndarray, L: int) -> np.ndarray:
+    """Grouped-query causal attention of S new rows over L cached + S new keys.
+
+    q: [S, Hq, hd]; k_all, v_all: [L + S, Hkv, hd].  Row t (absolute position
+    L + t) sees keys j <= L + t.  Query head i reads kv head i // (Hq / Hkv).
+    """
+    S, Hq, hd = q.shape
+    Hkv = k_all.shape[1]
+    G = Hq // Hkv
+    n = k_all.shape[0]
+    visible = np.arange(n)[None, :] <= (L + np.arange(S))[:, None]
+    out = np.empty_like(q)
+    for i in range(Hq):
+        c = i // G
+        s = q[:, i, :] @ k_all[:, c, :].T / math.sqrt(hd)
+        s = np.where(visible, s, -np.inf)
+        p = softmax(s, axis=-1)
+        out[:, i, :] = p @ v_all[:, c, :]
+    return out
+
+
+def silu(z: np.ndarray) -> np.ndarray:
+    return z / (1.0 + np.exp(-z))
+
+
+def decoder_layer(x: np.ndarray, pos: np.ndarray, lw: dict, k_prefix: np.ndarray,
+                  v_prefix: np.ndarray, cfg):
+    """One pre-norm decoder layer on S new rows placed after L cached rows.
+
+    x: [S, d]; pos: [S]; k_prefix, v_prefix: [L, Hkv, hd] (keys already rotated).
+    Returns (x_out, k_new, v_new) with k_new, v_new: [S, Hkv, hd] (k_new rotated).
+    """
+    S = x.shape[0]
+    L = k_prefix.shape[0]
+    hd = cfg.head_dim
+    h = rmsnorm(x, lw["attn_norm"], cfg.rms_eps)
+    q = (h @ lw["wq"].T).reshape(S, cfg.n_q_heads, hd)
+    k = (h @ lw["wk"].T).reshape(S, cfg.n_kv_heads, hd)
+    v = (h @ lw["wv"].T).reshape(S, cfg.n_kv_heads, hd)
+    q = rope(q, pos, cfg.rope_theta)
+    k = rope(k, pos, cfg.rope_theta)
+    k_all = np.concatenate([k_prefix, k], axis=0)
+    v_all = np.concatenate([v_prefix, v], axis=0)
+    o = attention(q, k_all, v_all, L).reshape(S, cfg.n_q_heads * hd)
+    x = x + o @ lw["wo"].T
+    h2 = rmsnorm(x, lw["mlp_norm"], cfg.rms_eps)
+    x = x + (silu(h2 @ lw["wg"].T) * (h2 @ lw["wu"].T)) @ lw["wd"].T
+    return x, k, v
+
+
+def gather_prefix(blocks: np.ndarray, L: int) -> np.ndarray:
+    """Dense [L, Hkv, hd] rows from the trace's physical blocks, in logical order.
+
+    blocks: [n, Hkv, block_size, hd], block i holding logical rows
+    i*block_size .. i*block_size + block_size - 1 of the trace: logical row j
+    lives in blocks[j // block_size][:, j % block_size, :].
+    """
+    n, Hkv, bs, hd = blocks.shape
+    rows = np.empty((L, Hkv, hd), dtype=np.float64)
+    for j in range(L):
+        rows[j] = blocks[j // bs, :, j % bs, :]
+    return rows
+
+
+# --------------------------------------------------------------------------- #
+# the pass
+# --------------------------------------------------------------------------- #
+def forward(cfg, model, traces: Sequence[dict], keep_kv: bool = False):
+    """Run every trace's new tokens through all layers.
+
+    model: object with embed_rows(ids), layer(l) -> dict of float64 matrices.
+    Each trace is a dict with
+      ids      : int array [S] new token ids (placed at positions L .. L+S-1)
+      L        : cached prefix length
+      k_prefix : callable l -> [L, Hkv, hd] float64 (rotated keys), same for v_prefix
+    Returns (xs, kvs): xs[b] = [S_b, d] residual stream after the last layer;
+    kvs[b][l] = (k_new, v_new) if keep_kv else None.
+
+    Layers are the outer loop only so that each layer's matrices are widened to
+    float64 once; no trace ever reads another trace's data.
+    """
+    xs, poss = [], []
+    for tr in traces:
+        ids = np.asarray(tr["ids"], dtype=np.int64)
+        xs.append(np.asarray(model.embed_rows(ids), dtype=np.float64))
+        poss.append(tr["L"] + np.arange(len(ids)))
+    kvs = [[None] * cfg.n_layers for _ in traces]
+    for l in range(cfg.n_layers):
+        lw = model.layer(l)
+        for b, tr in enumerate(traces):
+            if xs[b].shape[0] == 0:       # a trace with no new tokens has nothing to compute
+                if keep_kv:
+                    kvs[b][l] = (np.zeros((0, cfg.n_kv_heads, cfg.head_dim)),) * 2
+                continue
+            kp = np.asarray(tr["k_prefix"](l), dtype=np.float64)
+            vp = np.asarray(tr["v_prefix"](l), dtype=np.float64)
+            xs[b], k_new, v_new = decoder_layer(xs[b], poss[b], lw, kp, vp, cfg)
+            if keep_kv:
+                kvs[b][l] = (k_new, v_new)
+    return xs, kvs
+
+
+def verdict_logits(x_last: np.ndarray, final_norm: np.ndarray, lm_rows: np.ndarray,
+                   eps: float) -> np.ndarray:
+    """z_v = RMSNorm(x_last) . W_lm[verdict_ids[v]] (Section 4.2: the verifier's
+    decision is read as a verification token at the last position)."""
+    y = rmsnorm(x_last, final_norm, eps)
+    return lm_rows @ y
+
+
+def confidence(z: np.ndarray):
+    """(p, r, conf): softmax over the verdict logits, the predicted decision
+    r = argmax (lowest index on ties) and its probability (Eq. 3; Section 4.1)."""
+    p = softmax(np.asarray(z, dtype=np.float64), axis=-1)
+    r = int(np.argmax(p))
+    return p, r, float(p[r])
+
+
+def gate(conf: np.ndarray, taus: Sequence[float]) -> np.ndarray:
+    """accept[i, b] = 1 iff conf[b] >= taus[i] (Eq. 4: keep the verifier's own
+    decision); 0 means escalate to the larger model."""
+    conf = np.asarray(conf, dtype=np.float64)
+    return np.stack([(conf >= float(t)) for t in taus]).astype(np.uint8)
+
+
+def verify(cfg, model, kv, block_size: int, suffix_ids, cu_suffix, prefix_lens,
+           verdict_ids, taus, trace_subset: Optional[Sequence[int]] = None) -> dict:
+    """The whole pass for traces in `trace_subset` (default: all).
+
+    kv: object with block_table [B, max_blocks] and k_blocks(l, ids), v_blocks(l, ids)
+    returning [n, Hkv, block_size, hd] float64.
+    Returns dict(logits [n, n_verdict], probs, conf [n], verdict [n], accept [n_tau, n]).
+    """
+    suffix_ids = np.asarray(suffix_ids)
+    cu = np.asarray(cu_suffix, dtype=np.int64)
+    Ls = np.asarray(prefix_lens, dtype=np.int64)
+    B = len(Ls)
+    which = list(range(B)) if trace_subset is None else list(trace_subset)
+    traces = []
+    for b in which:
+        L = int(Ls[b])
+        nblk = (L + block_size - 1) // block_size
+        blk_ids = np.asarray(kv.block_table[b][:nblk], dtype=np.int64)
+
+        def k_prefix(l, blk_ids=blk_ids, L=L):
+            if L == 0:
+                return np.zeros((0, cfg.n_kv_heads, cfg.head_dim))
+            return gather_prefix(kv.k_blocks(l, blk_ids), L)
+
+        def v_prefix(l, blk_ids=blk_ids, L=L):
+            if L == 0:
+                return np.zeros((0, cfg.n_kv_heads, cfg.head_dim))
+            return gather_prefix(kv.v_blocks(l, blk_ids), L)
+
+        traces.append(dict(ids=suffix_ids[cu[b]:cu[b + 1]], L=L, k_prefix=k_prefix, v_prefix=v_prefix))
+    xs, _ = forward(cfg, model, traces)
+    g = np.asarray(model.final_norm, dtype=np.float64)
+    lm_rows = np.asarray(model.lm_head_rows(np.asarray(verdict_ids)), dtype=np.float64)
+    logits, probs, verdict, conf = [], [], [], []
+    for x in xs:
+        z = verdict_logits(x[-1], g, lm_rows, cfg.rms_eps)
+        p, r, c = confidence(z)
+        logits.append(z)
+        probs.append(p)
+        verdict.append(r)
+        conf.append(c)
+    conf = np.asarray(conf, dtype=np.float64)
+    return dict(logits=np.asarray(logits), probs=np.asarray(probs), conf=conf,
+                verdict=np.asarray(verdict, dtype=np.int32), accept=gate(conf, taus),
+                traces=np.asarray(which, dtype=np.int32))
+
+
+def prefix_pass(cfg, model, prefix_ids: Sequence[np.ndarray]):
+    """Dense caches from running each trace's context tokens from position 0.
+
+    Returns (k_dense, v_dense) with k_dense[l][b]: [L_b, Hkv, hd] rotated keys.
+    Used by tests to build a cache whose contents are a real prefix pass, so that
+    cached suffix prefill can be compared with a full recompute.
+    """
+    empty = np.zeros((0, cfg.n_kv_heads, cfg.head_dim))
+    traces = [dict(ids=ids, L=0, k_prefix=lambda l: empty, v_prefix=lambda l: empty)
+              for ids in prefix_ids]
+    _, kvs = forward(cfg, model, traces, keep_kv=True)
+    k_dense = [[kvs[b][l][0] for b in range(len(traces))] for l in range(cfg.n_layers)]
+    v_dense = [[kvs[b][l][1] for b in range(len(traces))] for l in range(cfg.n_layers)]
+    return k_dense, v_dense
