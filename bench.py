@@ -1,0 +1,132 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched verification pass on one MI355X.
+
+One step = one confspec_verify call (every kernel of the pass) over one synthetic batch that is
+already resident in HBM.  Prints one JSON line: verified steps/s, the MFMA roofline of the dominant
+kernel (the gate/up projection GEMM with its SwiGLU epilogue) measured live with HIP events, and the
+CPU oracle timed on a bounded sample of the same workload as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload: 2 (default, the metric's config), 3, 4 or 5")
+    ap.add_argument("--cpu-baseline-traces", type=int, default=6,
+                    help="traces of the workload the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (traces are independent; more GPUs would each take a "
+              "share of the traces with a replica of the weights, no collectives) - rerun with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import confspec_workloads as W
+    from paper_2602_18447_amd import binding as cb
+    from paper_2602_18447_amd.runner import Verifier
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    wl = W.config(args.config)
+    m = wl.model
+    weights = W.make_weights(m, wl.seed, dev)
+    batch = W.make_batch(wl, dev)
+    kv = W.make_seeded_kv(wl, batch, dev)
+    vids = W.draw_verdict_ids(wl)
+    taus = list(wl.taus)
+    ver = Verifier(m, weights)
+    outs = ver.alloc_outputs(wl.B, len(vids), len(taus))
+    ver.workspace(wl.T, wl.B)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        ver.verify(kv, batch, vids, taus, outputs=outs)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        ver.verify(kv, batch, vids, taus, outputs=outs)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    steps_per_s = wl.B / (ms_per_step * 1e-3)
+    accept_counts = outs[3].cpu().numpy().sum(axis=1).tolist()
+
+    # ---- roofline of the dominant kernel: gate/up GEMM + SwiGLU, same shape and launch as in the pass
+    T, d, F = wl.T, m.d_model, m.d_ffn
+    h = (torch.randn(T, d, device=dev) * 0.5).to(torch.bfloat16)
+    act = torch.empty(T, F, dtype=torch.bfloat16, device=dev)
+    packed_ptrs = ver._packed_ptrs
+
+    class _Raw:   # pointer of one layer's packed gate/up matrix
+        def __init__(self, p):
+            self.p = p
+
+        def data_ptr(self):
+            return self.p
+
+    n_launch = max(args.steps, 1) * m.n_layers
+    for l in range(m.n_layers):
+        cb.confspec_op_gemm(ver.ctx, h, _Raw(packed_ptrs[l]), act, T, 2 * F, d, cb.EPI_SWIGLU)
+    torch.cuda.synchronize()
+    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g0.record()
+    for i in range(n_launch):
+        cb.confspec_op_gemm(ver.ctx, h, _Raw(packed_ptrs[i % m.n_layers]), act, T, 2 * F, d, cb.EPI_SWIGLU)
+    g1.record()
+    torch.cuda.synchronize()
+    gemm_ms = g0.elapsed_time(g1) / n_launch
+    gemm_flops = 2.0 * T * (2 * F) * d
+    achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel="gemm_bf16_kernel<256,256,SWIGLU> (gate/up projection)",
+                    achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    flops_per_launch=gemm_flops, avg_launch_ms=round(gemm_ms, 5))
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported baseline only)
+    cpu = None
+    if args.cpu_baseline_traces > 0:
+        from oracle import confspec_oracle as O
+
+        n = min(args.cpu_baseline_traces, wl.B)
+        t0 = time.time()
+        ora = O.verify(m, W.OracleModelView(weights), W.OracleKVView(kv, batch), wl.block_size,
+                       batch.suffix_ids.cpu().numpy(), batch.h_cu_suffix, batch.h_prefix_lens, vids, taus,
+                       trace_subset=list(range(n)))
+        dt = time.time() - t0
+        dl = float(np.abs(outs[0].cpu().numpy()[:n] - ora["logits"]).max())
+        cpu = dict(value=round(n / dt, 4), unit="verified steps/s", cores=torch.get_num_threads(), kind="oracle",
+                   sample=f"first {n} of {wl.B} traces of {wl.name}, fp64 numpy, {dt:.1f} s",
+                   max_abs_dlogit_vs_gpu=dl)
+
+    print(json.dumps({
+        "metric": "verified steps/sec (batched verify pass)", "value": round(steps_per_s, 1),
+        "unit": "verified steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": m.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "T": wl.T, "sum_prefix_len": int(sum(wl.prefix_lens)),
+                   "layers": m.n_layers, "d_model": m.d_model, "taus": taus, "accept_counts": accept_counts},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,66 @@
+/*
+ * confspec_ops.h - single-step entry points of the verification pass.
+ *
+ * confspec_verify() (confspec.h) is the product call.  The functions here run one step of it at a
+ * time through the same kernels, so that each step can be checked and timed on its own: the
+ * projection GEMMs with their epilogues, RMSNorm, the paged grouped-query attention, and the
+ * verdict head with the confidence gate (Section 4.2, Eq. 3 and Eq. 4 of the paper for the last
+ * one; the others are the decoder the verifier model runs on).  Same conventions as confspec.h:
+ * dev pointers are caller-owned device memory, nothing is allocated, nothing synchronises.
+ */
+#ifndef CONFSPEC_OPS_H
+#define CONFSPEC_OPS_H
+
+#include "confspec.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CONFSPEC_EPI_STORE_F32 0  /* out fp32 [M,N] = A . W^T                                   */
+#define CONFSPEC_EPI_RESID_F32 1  /* out fp32 [M,N] += A . W^T (in place)                       */
+#define CONFSPEC_EPI_SWIGLU 2     /* W rows gate/up interleaved (confspec_pack_weights order);   */
+                                  /* out (model dtype) [M, N/2] = silu(gate) * up                */
+
+/* C[M,N] = A[M,K] . W[N,K]^T with one of the epilogues above.  A and W are dev arrays of the
+ * context's dtype (row-major, K contiguous).  Requires N % 128 == 0 and K % 64 == 0 for bf16,
+ * N % 64 == 0 and K % 16 == 0 for fp32; any M >= 1. */
+int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, void *dev_out, int32_t M,
+                     int32_t N, int32_t K, int32_t epilogue, confspec_stream stream);
+
+/* out[t,:] = x[t,:] / sqrt(mean(x[t,:]^2) + rms_eps) * g, x fp32 [n_rows, d_model], g and out in the
+ * context's dtype. */
+int confspec_op_rmsnorm(confspec_ctx *ctx, const float *dev_x, const void *dev_g, void *dev_out,
+                        int32_t n_rows, confspec_stream stream);
+
+/* Rotary embedding + split of a fp32 QKV projection [T, (Hq + 2 Hkv) hd] into q [T,Hq,hd],
+ * k [T,Hkv,hd], v [T,Hkv,hd] (context dtype); positions are L_b + t from the batch. */
+int confspec_op_rope_split(confspec_ctx *ctx, const confspec_batch *batch, int32_t max_prefix_len,
+                           const float *dev_qkv, void *dev_q, void *dev_k, void *dev_v, void *dev_workspace,
+                           size_t workspace_bytes, confspec_stream stream);
+
+/* Attention of one layer: softmax over keys j <= L_b + t of q . k_j / sqrt(hd), keys and values
+ * 0..L_b-1 from the paged cache of `layer`, the rest from dev_k_suffix / dev_v_suffix.
+ * q [T,Hq,hd], k/v suffix [T,Hkv,hd], out [T,Hq*hd], all in the context's dtype. */
+int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confspec_batch *batch, int32_t layer,
+                          const void *dev_q, const void *dev_k_suffix, const void *dev_v_suffix, void *dev_out,
+                          void *dev_workspace, size_t workspace_bytes, confspec_stream stream);
+
+/* Verdict head and gate on a residual stream x fp32 [T, d_model]: for each trace the last suffix
+ * row is normalised, dotted with the verdict rows of lm_head, soft-maxed over the verdicts and
+ * compared with every tau.  Outputs as in confspec_verify. */
+int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, const float *dev_x,
+                             const void *dev_final_norm, const void *dev_lm_head, const int32_t *h_verdict_ids,
+                             int32_t n_verdict, const float *h_tau, int32_t n_tau, void *dev_workspace,
+                             size_t workspace_bytes, float *dev_verdict_logits, float *dev_conf,
+                             int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream);
+
+/* Launch-shape tunables for measurements: key "gemm_tile" (0 heuristic, 1 = 128x128, 2 = 256x256,
+ * 3 = 256x128), "attn_target_items", "attn_min_chunks".  Returns CONFSPEC_E_INVALID_ARG for an
+ * unknown key.  Process-wide. */
+int confspec_tune(const char *key, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONFSPEC_OPS_H */

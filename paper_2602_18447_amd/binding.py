@@ -1,0 +1,249 @@
+"""ctypes binding of libconfspec.so: argument marshalling only.
+
+Every function mirrors the C entry point of the same name (include/confspec.h,
+include/confspec_ops.h).  Torch appears only as the owner of device memory and
+of the stream handle; every step of the pass runs in the library's kernels.
+There is no CPU fallback: if the shared library is missing, importing this
+module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libconfspec.so")
+
+OK, E_INVALID_ARG, E_UNSUPPORTED, E_WORKSPACE, E_OUT_OF_RANGE, E_HIP = 0, -1, -2, -3, -4, -5
+DTYPE_FP32, DTYPE_BF16 = 0, 1
+EPI_STORE_F32, EPI_RESID_F32, EPI_SWIGLU = 0, 1, 2
+ERROR_NAMES = {OK: "OK", E_INVALID_ARG: "INVALID_ARG", E_UNSUPPORTED: "UNSUPPORTED", E_WORKSPACE: "WORKSPACE",
+               E_OUT_OF_RANGE: "OUT_OF_RANGE", E_HIP: "HIP"}
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
+                ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32)]
+
+
+class Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("attn_norm", C.POINTER(C.c_void_p)), ("wqkv", C.POINTER(C.c_void_p)),
+                ("wo", C.POINTER(C.c_void_p)), ("mlp_norm", C.POINTER(C.c_void_p)),
+                ("w_gate_up", C.POINTER(C.c_void_p)), ("w_down", C.POINTER(C.c_void_p)), ("packed", C.c_int32)]
+
+
+class KV(C.Structure):
+    _fields_ = [("k_pages", C.c_void_p), ("v_pages", C.c_void_p), ("n_blocks", C.c_int32),
+                ("block_size", C.c_int32), ("block_table", C.c_void_p), ("max_blocks_per_seq", C.c_int32)]
+
+
+class Batch(C.Structure):
+    _fields_ = [("B", C.c_int32), ("T", C.c_int32), ("suffix_ids", C.c_void_p), ("cu_suffix", C.c_void_p),
+                ("prefix_lens", C.c_void_p), ("h_cu_suffix", C.POINTER(C.c_int32)),
+                ("h_prefix_lens", C.POINTER(C.c_int32))]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    P = C.POINTER
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    lib.confspec_version.restype = C.c_char_p
+    lib.confspec_version.argtypes = []
+    lib.confspec_create.restype = C.c_int
+    lib.confspec_create.argtypes = [P(ModelCfg), C.c_int, P(vp)]
+    lib.confspec_destroy.restype = None
+    lib.confspec_destroy.argtypes = [vp]
+    lib.confspec_last_error.restype = C.c_char_p
+    lib.confspec_last_error.argtypes = [vp]
+    lib.confspec_workspace_bytes.restype = C.c_int
+    lib.confspec_workspace_bytes.argtypes = [vp, i32, i32, C.c_int64, P(sz)]
+    lib.confspec_packed_bytes.restype = C.c_int
+    lib.confspec_packed_bytes.argtypes = [vp, P(sz)]
+    lib.confspec_pack_weights.restype = C.c_int
+    lib.confspec_pack_weights.argtypes = [vp, P(Weights), vp, sz, P(vp), P(Weights), vp]
+    lib.confspec_verify.restype = C.c_int
+    lib.confspec_verify.argtypes = [vp, P(Weights), P(KV), P(Batch), P(i32), i32, P(C.c_float), i32, vp, sz,
+                                    vp, vp, vp, vp, vp]
+    lib.confspec_op_gemm.restype = C.c_int
+    lib.confspec_op_gemm.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    lib.confspec_op_rmsnorm.restype = C.c_int
+    lib.confspec_op_rmsnorm.argtypes = [vp, vp, vp, vp, i32, vp]
+    lib.confspec_op_rope_split.restype = C.c_int
+    lib.confspec_op_rope_split.argtypes = [vp, P(Batch), i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.confspec_op_attention.restype = C.c_int
+    lib.confspec_op_attention.argtypes = [vp, P(KV), P(Batch), i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.confspec_op_verdict_gate.restype = C.c_int
+    lib.confspec_op_verdict_gate.argtypes = [vp, P(Batch), vp, vp, vp, P(i32), i32, P(C.c_float), i32, vp, sz,
+                                             vp, vp, vp, vp, vp]
+    lib.confspec_tune.restype = C.c_int
+    lib.confspec_tune.argtypes = [C.c_char_p, i32]
+    return lib
+
+
+lib = _load()
+
+EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec_last_error",
+            "confspec_workspace_bytes", "confspec_packed_bytes", "confspec_pack_weights", "confspec_verify",
+            "confspec_op_gemm", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_attention",
+            "confspec_op_verdict_gate", "confspec_tune"]
+
+
+class ConfSpecError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"confspec error {ERROR_NAMES.get(code, code)}: {msg}")
+        self.code = code
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a torch tensor, None for None."""
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    h = getattr(stream, "cuda_stream", stream)
+    return h if h else None
+
+
+def _check(ctx, rc: int):
+    if rc != OK:
+        msg = lib.confspec_last_error(ctx).decode() if ctx else ""
+        raise ConfSpecError(rc, msg)
+
+
+# --------------------------------------------------------------------------- #
+# thin wrappers, one per C entry point
+# --------------------------------------------------------------------------- #
+def confspec_version() -> str:
+    return lib.confspec_version().decode()
+
+
+def confspec_create(cfg: ModelCfg, device: int = 0) -> C.c_void_p:
+    out = C.c_void_p()
+    rc = lib.confspec_create(C.byref(cfg), device, C.byref(out))
+    if rc != OK:
+        raise ConfSpecError(rc, "confspec_create rejected the model configuration")
+    return out
+
+
+def confspec_destroy(ctx) -> None:
+    lib.confspec_destroy(ctx)
+
+
+def confspec_last_error(ctx) -> str:
+    return lib.confspec_last_error(ctx).decode()
+
+
+def confspec_workspace_bytes(ctx, max_T: int, max_B: int, max_sum_L: int = 0) -> int:
+    out = C.c_size_t()
+    _check(ctx, lib.confspec_workspace_bytes(ctx, max_T, max_B, max_sum_L, C.byref(out)))
+    return out.value
+
+
+def confspec_packed_bytes(ctx) -> int:
+    out = C.c_size_t()
+    _check(ctx, lib.confspec_packed_bytes(ctx, C.byref(out)))
+    return out.value
+
+
+def confspec_pack_weights(ctx, w_in: Weights, dev_dst, dst_bytes: int, h_ptr_storage, w_out: Weights,
+                          stream=None) -> None:
+    _check(ctx, lib.confspec_pack_weights(ctx, C.byref(w_in), _ptr(dev_dst), dst_bytes, h_ptr_storage,
+                                          C.byref(w_out), _stream_handle(stream)))
+
+
+def confspec_verify(ctx, w: Weights, kv: KV, batch: Batch, verdict_ids: Sequence[int], taus: Sequence[float],
+                    workspace, logits, conf, verdict, accept, stream=None) -> None:
+    nv, nt = len(verdict_ids), len(taus)
+    ids = (C.c_int32 * max(nv, 1))(*[int(v) for v in verdict_ids])
+    tau = (C.c_float * max(nt, 1))(*[float(t) for t in taus])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(ctx, lib.confspec_verify(ctx, C.byref(w), C.byref(kv), C.byref(batch), ids, nv, tau, nt,
+                                    _ptr(workspace), ws_bytes, _ptr(logits), _ptr(conf), _ptr(verdict),
+                                    _ptr(accept), _stream_handle(stream)))
+
+
+def confspec_op_gemm(ctx, A, W, out, M: int, N: int, K: int, epilogue: int, stream=None) -> None:
+    _check(ctx, lib.confspec_op_gemm(ctx, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, _stream_handle(stream)))
+
+
+def confspec_op_rmsnorm(ctx, x, g, out, n_rows: int, stream=None) -> None:
+    _check(ctx, lib.confspec_op_rmsnorm(ctx, _ptr(x), _ptr(g), _ptr(out), n_rows, _stream_handle(stream)))
+
+
+def confspec_op_rope_split(ctx, batch: Batch, max_prefix_len: int, qkv, q, k, v, workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(ctx, lib.confspec_op_rope_split(ctx, C.byref(batch), max_prefix_len, _ptr(qkv), _ptr(q), _ptr(k), _ptr(v),
+                                           _ptr(workspace), ws_bytes, _stream_handle(stream)))
+
+
+def confspec_op_attention(ctx, kv: KV, batch: Batch, layer: int, q, k_suffix, v_suffix, out, workspace,
+                          stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(ctx, lib.confspec_op_attention(ctx, C.byref(kv), C.byref(batch), layer, _ptr(q), _ptr(k_suffix),
+                                          _ptr(v_suffix), _ptr(out), _ptr(workspace), ws_bytes,
+                                          _stream_handle(stream)))
+
+
+def confspec_op_verdict_gate(ctx, batch: Batch, x, final_norm, lm_head, verdict_ids, taus, workspace, logits, conf,
+                             verdict, accept, stream=None) -> None:
+    nv, nt = len(verdict_ids), len(taus)
+    ids = (C.c_int32 * max(nv, 1))(*[int(v) for v in verdict_ids])
+    tau = (C.c_float * max(nt, 1))(*[float(t) for t in taus])
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(ctx, lib.confspec_op_verdict_gate(ctx, C.byref(batch), _ptr(x), _ptr(final_norm), _ptr(lm_head), ids, nv,
+                                             tau, nt, _ptr(workspace), ws_bytes, _ptr(logits), _ptr(conf),
+                                             _ptr(verdict), _ptr(accept), _stream_handle(stream)))
+
+
+def confspec_tune(key: str, value: int) -> None:
+    rc = lib.confspec_tune(key.encode(), int(value))
+    if rc != OK:
+        raise ConfSpecError(rc, f"confspec_tune({key!r}, {value})")
+
+
+# --------------------------------------------------------------------------- #
+# struct builders from torch tensors (pointer plumbing)
+# --------------------------------------------------------------------------- #
+def make_model_cfg(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, rope_theta, rms_eps,
+                   dtype: str) -> ModelCfg:
+    return ModelCfg(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, float(rope_theta),
+                    float(rms_eps), {"fp32": DTYPE_FP32, "bf16": DTYPE_BF16}[dtype])
+
+
+def _ptr_array(tensors) -> "C.Array":
+    arr = (C.c_void_p * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def make_weights(embed, lm_head, final_norm, attn_norm, wqkv, wo, mlp_norm, w_gate_up, w_down, packed=0):
+    """Returns (Weights, keepalive): keepalive holds the host pointer arrays the struct points into."""
+    arrays = [_ptr_array(x) for x in (attn_norm, wqkv, wo, mlp_norm, w_gate_up, w_down)]
+    w = Weights(embed.data_ptr(), lm_head.data_ptr(), final_norm.data_ptr(),
+                *[C.cast(a, C.POINTER(C.c_void_p)) for a in arrays], packed)
+    return w, arrays
+
+
+def make_kv(k_pages, v_pages, block_table, n_blocks: int, block_size: int, max_blocks_per_seq: int) -> KV:
+    return KV(_ptr(k_pages), _ptr(v_pages), n_blocks, block_size, _ptr(block_table), max_blocks_per_seq)
+
+
+def make_batch(suffix_ids, cu_suffix, prefix_lens, h_cu_suffix, h_prefix_lens):
+    """h_cu_suffix / h_prefix_lens: int32 numpy arrays.  Returns (Batch, keepalive)."""
+    import numpy as np
+    hc = np.ascontiguousarray(h_cu_suffix, dtype=np.int32)
+    hp = np.ascontiguousarray(h_prefix_lens, dtype=np.int32)
+    B = len(hp)
+    b = Batch(B, int(hc[-1]) if len(hc) else 0, _ptr(suffix_ids), _ptr(cu_suffix), _ptr(prefix_lens),
+              hc.ctypes.data_as(C.POINTER(C.c_int32)), hp.ctypes.data_as(C.POINTER(C.c_int32)))
+    return b, (hc, hp)

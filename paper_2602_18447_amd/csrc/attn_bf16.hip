@@ -1,0 +1,441 @@
+// Grouped-query causal attention of suffix queries over the paged prefix cache plus the suffix's own
+// keys, bf16 operands on the gfx950 matrix cores, fp32 online softmax.
+//
+// Decomposition.  All G query heads that share one kv head are folded into the row dimension: a
+// trace with S suffix tokens contributes G*S rows per kv head, flattened position-major
+// (row = t*G + g), cut into tiles of 128 rows; one wavefront owns 32 rows.  The key range of a tile
+// is cut into 64-key chunks, and - to balance ragged batches and fill 256 CUs - into several work
+// items whose partial (max, sum, unnormalised output) results are merged by a second kernel in a
+// fixed order.
+//
+// Per chunk a workgroup stages K as [key][hd] and V transposed as [hd][key] in LDS.  Scores are
+// computed transposed, S^T = K . Q^T (keys on MFMA rows, queries on columns), so each lane owns one
+// query column: the running max / sum and the rescale of the output accumulator are lane-local
+// apart from one exchange between lane l and l+32.  The rows of each 32-key block are fed to the
+// MFMA in a permuted order chosen so that the probabilities a lane ends up holding are 8
+// consecutive keys per k-step: they are used as the B operand of O^T += V^T . P^T straight from
+// registers, and the matching A operand is a single 16-byte read of the transposed V tile.
+#include "kernels.h"
+
+namespace cs {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int HD = 128;
+constexpr int K_STRIDE = 136;             // elements per K row in LDS (128 + 8 pad = 272 bytes)
+constexpr int VT_STRIDE = 72;             // elements per V^T row in LDS (64 + 8 pad = 144 bytes)
+constexpr int K_TILE = ATTN_BN * K_STRIDE;
+constexpr int VT_TILE = HD * VT_STRIDE;
+constexpr int ATTN_STAGE = K_TILE + VT_TILE;   // elements per stage
+constexpr int ATTN_SMEM_BYTES = 2 * ATTN_STAGE * 2;
+
+__host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// launch-shape tunables (process-wide)
+static int g_target_items = ATTN_TARGET_ITEMS;
+static int g_min_chunks = ATTN_MIN_CHUNKS_PER_ITEM;
+void attn_set_tune(int target_items, int min_chunks) { g_target_items = target_items; g_min_chunks = min_chunks; }
+void attn_get_tune(int *target_items, int *min_chunks) { *target_items = g_target_items; *min_chunks = g_min_chunks; }
+
+// ---- planning: identical arithmetic on host (counts only) and device (counts + lists) ----
+struct TracePlan {
+    int n_qt;      // q-row tiles per kv head
+    int n_split;   // key-range splits of every tile of this trace
+    int nc_max;    // chunks of the trace's last tile
+};
+__host__ __device__ inline TracePlan trace_plan(int L, int S, int G, int cpi) {
+    TracePlan p;
+    p.n_qt = S > 0 ? ceil_div(G * S, ATTN_BM) : 0;
+    p.nc_max = ceil_div(L + S, ATTN_BN);
+    p.n_split = p.nc_max > cpi ? ceil_div(p.nc_max, cpi) : 1;
+    return p;
+}
+__host__ __device__ inline int tile_chunks(int L, int S, int G, int m) {
+    int r_last = min(m * ATTN_BM + ATTN_BM - 1, G * S - 1);
+    return ceil_div(L + r_last / G + 1, ATTN_BN);
+}
+
+void attn_plan_capacity(int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles, int64_t *max_items) {
+    int64_t tiles = (int64_t)Hkv * ((G * max_T + ATTN_BM - 1) / ATTN_BM + max_B);
+    *max_tiles = tiles;
+    *max_items = tiles + g_target_items;
+}
+
+AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv) {
+    AttnPlanCounts r = {};
+    int64_t total = 0;
+    for (int b = 0; b < B; ++b) {
+        int S = h_cu[b + 1] - h_cu[b], L = h_plens[b];
+        TracePlan p = trace_plan(L, S, G, 1 << 30);
+        total += (int64_t)Hkv * p.n_qt * p.nc_max;
+    }
+    int64_t cpi = (total + g_target_items - 1) / g_target_items;
+    if (cpi < g_min_chunks) cpi = g_min_chunks;
+    r.chunks_per_item = (int32_t)cpi;
+    r.total_chunks = total;
+    for (int b = 0; b < B; ++b) {
+        int S = h_cu[b + 1] - h_cu[b], L = h_plens[b];
+        TracePlan p = trace_plan(L, S, G, r.chunks_per_item);
+        int64_t tiles = (int64_t)Hkv * p.n_qt;
+        r.n_tiles += tiles;
+        r.n_items += tiles * p.n_split;
+        if (p.n_split > 1) r.n_part_slots += tiles * p.n_split;
+    }
+    return r;
+}
+
+__global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restrict__ cu,
+                                                         const int32_t *__restrict__ plens, int B, int T, int max_L,
+                                                         int G, int Hkv, int cpi, int max_tiles, int max_items,
+                                                         AttnTile *__restrict__ tiles, AttnItem *__restrict__ items,
+                                                         int32_t *__restrict__ counts) {
+    __shared__ int s_tiles[257], s_items[257], s_slots[257];
+    __shared__ int carry[3];
+    int tid = threadIdx.x;
+    if (tid == 0) carry[0] = carry[1] = carry[2] = 0;
+    __syncthreads();
+    for (int base = 0; base < B; base += 256) {
+        int b = base + tid;
+        int L = 0, S = 0;
+        TracePlan p = {0, 1, 0};
+        if (b < B) {
+            int c0 = min(max(cu[b], 0), T), c1 = min(max(cu[b + 1], 0), T);
+            S = max(c1 - c0, 0);
+            L = min(max(plens[b], 0), max_L);
+            p = trace_plan(L, S, G, cpi);
+        }
+        int my_tiles = Hkv * p.n_qt, my_items = my_tiles * p.n_split;
+        s_tiles[tid + 1] = my_tiles;
+        s_items[tid + 1] = my_items;
+        s_slots[tid + 1] = p.n_split > 1 ? my_items : 0;
+        __syncthreads();
+        if (tid == 0) {  // serial exclusive scan of at most 256 entries
+            s_tiles[0] = carry[0];
+            s_items[0] = carry[1];
+            s_slots[0] = carry[2];
+            for (int i = 1; i <= 256; ++i) {
+                s_tiles[i] += s_tiles[i - 1];
+                s_items[i] += s_items[i - 1];
+                s_slots[i] += s_slots[i - 1];
+            }
+        }
+        __syncthreads();
+        int tile_base = s_tiles[tid], item_base = s_items[tid], slot_base = s_slots[tid];
+        if (b < B) {
+            for (int c = 0; c < Hkv; ++c)
+                for (int m = 0; m < p.n_qt; ++m) {
+                    int ti = tile_base + c * p.n_qt + m;
+                    int pbase = p.n_split > 1 ? slot_base + (c * p.n_qt + m) * p.n_split : -1;
+                    if (ti < max_tiles) {
+                        AttnTile t;
+                        t.b = b; t.c = c; t.row0 = m * ATTN_BM; t.part_base = pbase; t.n_splits = p.n_split;
+                        t.pad[0] = t.pad[1] = t.pad[2] = 0;
+                        tiles[ti] = t;
+                    }
+                    int nc = tile_chunks(L, S, G, m);
+                    for (int sp = 0; sp < p.n_split; ++sp) {
+                        int idx = item_base + (c * p.n_split + sp) * p.n_qt + m;
+                        if (idx >= max_items || pbase + sp >= max_items) continue;
+                        AttnItem it;
+                        it.b = b; it.c = c; it.row0 = m * ATTN_BM;
+                        it.chunk_begin = (int)(((long)sp * nc) / p.n_split);
+                        it.chunk_end = (int)(((long)(sp + 1) * nc) / p.n_split);
+                        it.part_slot = p.n_split > 1 ? pbase + sp : -1;
+                        it.tile = ti; it.pad = 0;
+                        items[idx] = it;
+                    }
+                }
+        }
+        __syncthreads();
+        if (tid == 0) { carry[0] = s_tiles[256]; carry[1] = s_items[256]; carry[2] = s_slots[256]; }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        counts[0] = min(carry[0], max_tiles);
+        counts[1] = min(carry[1], max_items);
+    }
+}
+
+hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int T, int max_L, int G, int Hkv,
+                            int chunks_per_item, int max_tiles, int max_items, AttnTile *tiles, AttnItem *items,
+                            int32_t *counts, hipStream_t s) {
+    attn_plan_kernel<<<1, 256, 0, s>>>(cu, plens, B, T, max_L, G, Hkv, chunks_per_item, max_tiles, max_items, tiles,
+                                       items, counts);
+    return hipGetLastError();
+}
+
+// ---- the attention kernel ----
+__device__ __forceinline__ const bf16 *kv_row_ptr(const AttnArgs &a, const bf16 *pages, const bf16 *suf, int b,
+                                                  int c, int L, int S, int cu_b, int j) {
+    // nullptr: key j is past the end of the trace (zero-filled, always masked)
+    if (j < L) {
+        int blk = a.block_table[(size_t)b * a.max_blocks + (j >> 4)];
+        blk = min(max(blk, 0), a.n_blocks - 1);
+        return pages + (((size_t)blk * a.Hkv + c) * 16 + (j & 15)) * HD;
+    }
+    if (j < L + S) return suf + ((size_t)(cu_b + (j - L)) * a.Hkv + c) * HD;
+    return nullptr;
+}
+
+__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnItem *__restrict__ items,
+                                                         const int32_t *__restrict__ counts, int n_items_host,
+                                                         float *__restrict__ part_o, float *__restrict__ part_ml) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
+
+    int n_items = min(counts[1], n_items_host);
+    int per = gridDim.x >> 3;  // grid is a multiple of 8: one contiguous item range per XCD
+    int it_idx = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+    if (it_idx >= n_items) return;
+    AttnItem item = items[it_idx];
+
+    int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int half = lane >> 5, lq = lane & 31;
+    int G = a.Hq / a.Hkv;
+    int b = min(max(item.b, 0), a.B - 1), c = min(max(item.c, 0), a.Hkv - 1);
+    int cu_b = min(max(a.cu[b], 0), a.T - 1);
+    int S = min(max(a.cu[b + 1] - cu_b, 1), a.T - cu_b);
+    int L = min(max(a.plens[b], 0), a.max_blocks * 16);
+    int n_rows = G * S;
+
+    int r = item.row0 + wave * 32 + lq;
+    bool row_valid = r < n_rows;
+    int rc = min(r, n_rows - 1);
+    int t = rc / G, g = rc - t * G;
+    int limit = L + t;                                          // last visible key of this lane's query
+    int wave_first_limit = L + min(item.row0 + wave * 32, n_rows - 1) / G;
+
+    const bf16 *q_row = reinterpret_cast<const bf16 *>(a.q) + ((size_t)(cu_b + t) * a.Hq + c * G + g) * HD;
+    bf16x8 qf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(q_row + ks * 16 + half * 8);
+
+    const bf16 *kp = reinterpret_cast<const bf16 *>(a.k_pages), *vp = reinterpret_cast<const bf16 *>(a.v_pages);
+    const bf16 *ks_ = reinterpret_cast<const bf16 *>(a.ksuf), *vs_ = reinterpret_cast<const bf16 *>(a.vsuf);
+
+    // loader roles
+    int k_key[4], k_dst[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int v = tid + 256 * i;
+        k_key[i] = v >> 4;
+        k_dst[i] = (v >> 4) * K_STRIDE + (v & 15) * 8;
+    }
+    int v_kq = lane & 15, v_g = wave * 4 + (lane >> 4);        // keys 4*v_kq..+3, hd 8*v_g..+7
+    int v_dst = K_TILE + (8 * v_g) * VT_STRIDE + 4 * v_kq;
+
+    uint4 k_reg[4], v_reg[4];
+    auto load_chunk = [&](int ch) {
+        int j0 = ch * ATTN_BN;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bf16 *p = kv_row_ptr(a, kp, ks_, b, c, L, S, cu_b, j0 + k_key[i]);
+            k_reg[i] = p ? *reinterpret_cast<const uint4 *>(p + (tid & 15) * 8) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bf16 *p = kv_row_ptr(a, vp, vs_, b, c, L, S, cu_b, j0 + 4 * v_kq + i);
+            v_reg[i] = p ? *reinterpret_cast<const uint4 *>(p + v_g * 8) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_chunk = [&](int stage) {
+        __bf16 *base = smem + stage * ATTN_STAGE;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(base + k_dst[i]) = k_reg[i];
+        // 4 keys x 8 hd  ->  8 rows of 4 keys
+        const unsigned *r0 = reinterpret_cast<const unsigned *>(&v_reg[0]);
+        const unsigned *r1 = reinterpret_cast<const unsigned *>(&v_reg[1]);
+        const unsigned *r2 = reinterpret_cast<const unsigned *>(&v_reg[2]);
+        const unsigned *r3 = reinterpret_cast<const unsigned *>(&v_reg[3]);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint2 lo, hi;
+            lo.x = (r0[d] & 0xffffu) | (r1[d] << 16);
+            lo.y = (r2[d] & 0xffffu) | (r3[d] << 16);
+            hi.x = (r0[d] >> 16) | (r1[d] & 0xffff0000u);
+            hi.y = (r2[d] >> 16) | (r3[d] & 0xffff0000u);
+            *reinterpret_cast<uint2 *>(base + v_dst + (2 * d) * VT_STRIDE) = lo;
+            *reinterpret_cast<uint2 *>(base + v_dst + (2 * d + 1) * VT_STRIDE) = hi;
+        }
+    };
+
+    f32x16 acc_o[4];
+#pragma unroll
+    for (int hb = 0; hb < 4; ++hb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_o[hb][e] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const float sc = a.scale * 1.44269504088896340736f;   // scores in log2 units
+
+    // K operand row (key) for MFMA row lq, see the header comment: pi(m)
+    int pi_m = 16 * (lq >> 4) + 8 * ((lq >> 2) & 1) + 4 * ((lq >> 3) & 1) + (lq & 3);
+    int k_frag = pi_m * K_STRIDE + half * 8;
+    int v_frag = K_TILE + lq * VT_STRIDE + half * 8;
+
+    int ch0 = item.chunk_begin, ch1 = item.chunk_end;
+    if (ch0 < ch1) {
+        load_chunk(ch0);
+        store_chunk(0);
+    }
+    __syncthreads();
+    for (int ch = ch0; ch < ch1; ++ch) {
+        int stage = (ch - ch0) & 1;
+        bool more = ch + 1 < ch1;
+        if (more) load_chunk(ch + 1);
+        const __bf16 *base = smem + stage * ATTN_STAGE;
+
+        f32x16 acc_s[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc_s[kb][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                bf16x8 kf = *reinterpret_cast<const bf16x8 *>(base + kb * 32 * K_STRIDE + k_frag + ks * 16);
+                acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kb], 0, 0, 0);
+            }
+        }
+        // register e of block kb holds key  ch*64 + 32*kb + 16*(e>>3) + 8*half + (e&7)
+        int key0 = ch * ATTN_BN + 8 * half;
+        bool need_mask = ch * ATTN_BN + ATTN_BN - 1 > wave_first_limit;
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float v = acc_s[kb][e] * sc;
+                if (need_mask) {
+                    int key = key0 + 32 * kb + 16 * (e >> 3) + (e & 7);
+                    if (key > limit) v = -INFINITY;
+                }
+                acc_s[kb][e] = v;
+                mloc = fmaxf(mloc, v);
+            }
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+        float m_new = fmaxf(m_run, mloc);
+        float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+        float psum = 0.f;
+        bf16x8 pf[2][2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float p = __builtin_amdgcn_exp2f(acc_s[kb][e] - m_use);
+                psum += p;
+                pf[kb][e >> 3][e & 7] = (__bf16)p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int hb = 0; hb < 4; ++hb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc_o[hb][e] *= alpha;
+#pragma unroll
+        for (int hb = 0; hb < 4; ++hb)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    bf16x8 vf = *reinterpret_cast<const bf16x8 *>(base + v_frag + hb * 32 * VT_STRIDE + kb * 32 + s2 * 16);
+                    acc_o[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][s2], acc_o[hb], 0, 0, 0);
+                }
+        if (more) store_chunk(stage ^ 1);
+        __syncthreads();
+    }
+
+    float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    // acc_o[hb][e]: hd = 32*hb + 8*(e>>2) + 4*half + (e&3), query = lq
+    if (item.part_slot < 0) {
+        if (row_valid) {
+            float inv = 1.0f / l_tot;
+            bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + ((size_t)(cu_b + t) * a.Hq + c * G + g) * HD;
+#pragma unroll
+            for (int hb = 0; hb < 4; ++hb)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    union { bf16 h[4]; uint2 u; } pk;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) pk.h[j] = __float2bfloat16(acc_o[hb][q4 * 4 + j] * inv);
+                    *reinterpret_cast<uint2 *>(o_row + 32 * hb + 8 * q4 + 4 * half) = pk.u;
+                }
+        }
+    } else {
+        size_t row_slot = (size_t)item.part_slot * ATTN_BM + wave * 32 + lq;
+        float *po = part_o + row_slot * HD;
+#pragma unroll
+        for (int hb = 0; hb < 4; ++hb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                float4 v = make_float4(acc_o[hb][q4 * 4], acc_o[hb][q4 * 4 + 1], acc_o[hb][q4 * 4 + 2],
+                                       acc_o[hb][q4 * 4 + 3]);
+                *reinterpret_cast<float4 *>(po + 32 * hb + 8 * q4 + 4 * half) = v;
+            }
+        if (half == 0) {
+            part_ml[row_slot * 2] = m_run;
+            part_ml[row_slot * 2 + 1] = l_tot;
+        }
+    }
+}
+
+// Merge the splits of each tile in split order (fixed order: results are run-to-run identical).
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnTile *__restrict__ tiles,
+                                                          const int32_t *__restrict__ counts, int n_tiles_host,
+                                                          const float *__restrict__ part_o,
+                                                          const float *__restrict__ part_ml) {
+    int n_tiles = min(counts[0], n_tiles_host);
+    if ((int)blockIdx.x >= n_tiles) return;
+    AttnTile tile = tiles[blockIdx.x];
+    if (tile.n_splits <= 1 || tile.part_base < 0) return;
+    int G = a.Hq / a.Hkv;
+    int b = min(max(tile.b, 0), a.B - 1), c = min(max(tile.c, 0), a.Hkv - 1);
+    int cu_b = min(max(a.cu[b], 0), a.T - 1);
+    int S = min(max(a.cu[b + 1] - cu_b, 1), a.T - cu_b);
+    int n_rows = G * S;
+    for (int idx = threadIdx.x; idx < ATTN_BM * (HD / 4); idx += 256) {
+        int row = idx >> 5, hv = idx & 31;
+        int r = tile.row0 + row;
+        if (r >= n_rows) continue;
+        float m_tot = -INFINITY;
+        for (int s = 0; s < tile.n_splits; ++s)
+            m_tot = fmaxf(m_tot, part_ml[((size_t)(tile.part_base + s) * ATTN_BM + row) * 2]);
+        float l = 0.f;
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s = 0; s < tile.n_splits; ++s) {
+            size_t rs = (size_t)(tile.part_base + s) * ATTN_BM + row;
+            float m_s = part_ml[rs * 2], l_s = part_ml[rs * 2 + 1];
+            float w = (m_s == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_s - m_tot);
+            float4 v = *reinterpret_cast<const float4 *>(part_o + rs * HD + hv * 4);
+            l += w * l_s;
+            o.x += w * v.x; o.y += w * v.y; o.z += w * v.z; o.w += w * v.w;
+        }
+        float inv = 1.0f / l;
+        int t = r / G, g = r - t * G;
+        bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + ((size_t)(cu_b + t) * a.Hq + c * G + g) * HD;
+        union { bf16 h[4]; uint2 u; } pk;
+        pk.h[0] = __float2bfloat16(o.x * inv); pk.h[1] = __float2bfloat16(o.y * inv);
+        pk.h[2] = __float2bfloat16(o.z * inv); pk.h[3] = __float2bfloat16(o.w * inv);
+        *reinterpret_cast<uint2 *>(o_row + hv * 4) = pk.u;
+    }
+}
+
+hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
+                            int n_items_host, int n_tiles_host, float *part_o, float *part_ml, hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_SMEM_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (n_items_host <= 0) return hipSuccess;
+    int grid = ((n_items_host + 7) / 8) * 8;
+    attn_bf16_kernel<<<grid, 256, ATTN_SMEM_BYTES, s>>>(a, items, counts, n_items_host, part_o, part_ml);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    attn_merge_kernel<<<n_tiles_host, 256, 0, s>>>(a, tiles, counts, n_tiles_host, part_o, part_ml);
+    return hipGetLastError();
+}
+
+}  // namespace cs

@@ -1,0 +1,464 @@
+// Host side of the C ABI: argument validation, workspace carving and the launch sequence of the
+// batched verification pass.  No device memory is allocated here and the stream is never
+// synchronised; every check that can be made from host-visible arguments happens before the first
+// launch.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/confspec.h"
+#include "../../include/confspec_ops.h"
+#include "kernels.h"
+
+namespace cs {
+void gemm_set_tile(int t);
+void attn_set_tune(int target_items, int min_chunks);
+void attn_get_tune(int *target_items, int *min_chunks);
+}  // namespace cs
+
+struct confspec_ctx {
+    confspec_model_cfg cfg;
+    int device;
+    std::string err;
+};
+
+namespace {
+
+int fail(const confspec_ctx *ctx, int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) const_cast<confspec_ctx *>(ctx)->err = buf;
+    return code;
+}
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+size_t elem_bytes(int dtype) { return dtype == CONFSPEC_DTYPE_FP32 ? 4 : 2; }
+
+// Workspace layout for a batch of at most T tokens and B traces.
+struct WsLayout {
+    size_t tok_trace, tok_pos, last_row, rope_cos, rope_sin, x, h, qkv, q, ksuf, vsuf, attn, act;
+    size_t plan_counts, plan_tiles, plan_items, part_o, part_ml;
+    size_t total;
+    int64_t max_tiles, max_items;
+};
+
+WsLayout ws_layout(const confspec_model_cfg &c, int64_t T, int64_t B) {
+    WsLayout w = {};
+    size_t at = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = at;
+        at = align_up(at + bytes);
+        return o;
+    };
+    size_t eb = elem_bytes(c.dtype);
+    size_t qw = (size_t)c.n_q_heads * c.head_dim, kw = (size_t)c.n_kv_heads * c.head_dim;
+    w.tok_trace = take(T * 4);
+    w.tok_pos = take(T * 4);
+    w.last_row = take(B * 4);
+    w.rope_cos = take((size_t)T * (c.head_dim / 2) * 4);
+    w.rope_sin = take((size_t)T * (c.head_dim / 2) * 4);
+    w.x = take((size_t)T * c.d_model * 4);
+    w.h = take((size_t)T * c.d_model * eb);
+    w.qkv = take((size_t)T * (qw + 2 * kw) * 4);
+    w.q = take((size_t)T * qw * eb);
+    w.ksuf = take((size_t)T * kw * eb);
+    w.vsuf = take((size_t)T * kw * eb);
+    w.attn = take((size_t)T * qw * eb);
+    w.act = take((size_t)T * c.d_ffn * eb);
+    if (c.dtype == CONFSPEC_DTYPE_BF16) {
+        cs::attn_plan_capacity(T, B, c.n_q_heads / c.n_kv_heads, c.n_kv_heads, &w.max_tiles, &w.max_items);
+        w.plan_counts = take(256);
+        w.plan_tiles = take((size_t)w.max_tiles * sizeof(cs::AttnTile));
+        w.plan_items = take((size_t)w.max_items * sizeof(cs::AttnItem));
+        w.part_o = take((size_t)w.max_items * cs::ATTN_BM * c.head_dim * 4);
+        w.part_ml = take((size_t)w.max_items * cs::ATTN_BM * 2 * 4);
+    }
+    w.total = at;
+    return w;
+}
+
+int check_batch(const confspec_ctx *ctx, const confspec_batch *b, int64_t max_prefix, int *max_L_out) {
+    if (!b) return fail(ctx, CONFSPEC_E_INVALID_ARG, "batch is null");
+    if (b->B < 1 || b->B > (1 << 16)) return fail(ctx, CONFSPEC_E_INVALID_ARG, "B = %d outside [1, 65536]", b->B);
+    if (b->T < 1 || b->T > (1 << 22)) return fail(ctx, CONFSPEC_E_INVALID_ARG, "T = %d outside [1, 2^22]", b->T);
+    if (!b->suffix_ids || !b->cu_suffix || !b->prefix_lens || !b->h_cu_suffix || !b->h_prefix_lens)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "batch has a null array pointer");
+    if (b->h_cu_suffix[0] != 0) return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "cu_suffix[0] = %d, expected 0", b->h_cu_suffix[0]);
+    int max_L = 0;
+    for (int i = 0; i < b->B; ++i) {
+        if (b->h_cu_suffix[i + 1] <= b->h_cu_suffix[i])
+            return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "cu_suffix not strictly increasing at trace %d (every trace needs >= 1 suffix token)", i);
+        int L = b->h_prefix_lens[i];
+        if (L < 0 || (int64_t)L > max_prefix)
+            return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "prefix_lens[%d] = %d outside [0, %lld] (block table capacity)", i, L, (long long)max_prefix);
+        if (L > max_L) max_L = L;
+    }
+    if (b->h_cu_suffix[b->B] != b->T)
+        return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "cu_suffix[B] = %d but T = %d", b->h_cu_suffix[b->B], b->T);
+    if (max_L_out) *max_L_out = max_L;
+    return CONFSPEC_OK;
+}
+
+int check_kv(const confspec_ctx *ctx, const confspec_kv *kv, bool any_prefix) {
+    if (!kv) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv is null");
+    if (kv->block_size < 1 || kv->max_blocks_per_seq < 1 || kv->n_blocks < 1)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv: block_size, max_blocks_per_seq and n_blocks must be >= 1");
+    if (ctx->cfg.dtype == CONFSPEC_DTYPE_BF16 && kv->block_size != 16)
+        return fail(ctx, CONFSPEC_E_UNSUPPORTED, "bf16 attention supports block_size 16 only (got %d)", kv->block_size);
+    if (!kv->block_table) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv.block_table is null");
+    if (any_prefix && (!kv->k_pages || !kv->v_pages)) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv pages are null");
+    return CONFSPEC_OK;
+}
+
+int check_verdict(const confspec_ctx *ctx, const int32_t *ids, int n, const float *tau, int n_tau,
+                  cs::VerdictArgs *va) {
+    if (!ids || !tau) return fail(ctx, CONFSPEC_E_INVALID_ARG, "verdict ids or tau pointer is null");
+    if (n < 2 || n > CONFSPEC_MAX_VERDICT)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "n_verdict = %d outside [2, %d]", n, CONFSPEC_MAX_VERDICT);
+    if (n_tau < 1 || n_tau > CONFSPEC_MAX_TAU)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "n_tau = %d outside [1, %d]", n_tau, CONFSPEC_MAX_TAU);
+    memset(va, 0, sizeof *va);
+    for (int i = 0; i < n; ++i) {
+        if (ids[i] < 0 || ids[i] >= ctx->cfg.vocab)
+            return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "verdict id %d = %d outside [0, %d)", i, ids[i], ctx->cfg.vocab);
+        for (int j = 0; j < i; ++j)
+            if (ids[j] == ids[i]) return fail(ctx, CONFSPEC_E_INVALID_ARG, "verdict ids %d and %d are equal", j, i);
+        va->ids[i] = ids[i];
+    }
+    for (int i = 0; i < n_tau; ++i) {
+        if (!(tau[i] >= 0.0f && tau[i] <= 1.0f))
+            return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "tau[%d] = %g outside [0, 1]", i, (double)tau[i]);
+        va->tau[i] = tau[i];
+    }
+    va->n_verdict = n;
+    va->n_tau = n_tau;
+    return CONFSPEC_OK;
+}
+
+int check_ws(const confspec_ctx *ctx, const void *ws, size_t have, size_t need) {
+    if (!ws) return fail(ctx, CONFSPEC_E_INVALID_ARG, "workspace is null");
+    if (((uintptr_t)ws & 255) != 0) return fail(ctx, CONFSPEC_E_WORKSPACE, "workspace is not 256-byte aligned");
+    if (have < need)
+        return fail(ctx, CONFSPEC_E_WORKSPACE, "workspace has %zu bytes, %zu needed", have, need);
+    return CONFSPEC_OK;
+}
+
+#define HIP_TRY(expr)                                                                                   \
+    do {                                                                                                \
+        hipError_t e__ = (expr);                                                                        \
+        if (e__ != hipSuccess) return fail(ctx, CONFSPEC_E_HIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+    } while (0)
+
+int run_gemm(confspec_ctx *ctx, const void *A, const void *W, void *out, int M, int N, int K, int epi,
+             hipStream_t s) {
+    if (ctx->cfg.dtype == CONFSPEC_DTYPE_FP32) {
+        HIP_TRY(cs::launch_gemm_f32((const float *)A, (const float *)W, out, M, N, K, epi, s));
+    } else {
+        HIP_TRY(cs::launch_gemm_bf16((const cs::bf16 *)A, (const cs::bf16 *)W, out, M, N, K, epi, s));
+    }
+    return CONFSPEC_OK;
+}
+
+cs::AttnArgs make_attn_args(const confspec_model_cfg &c, const confspec_kv *kv, const confspec_batch *b, int layer,
+                            const void *q, const void *ksuf, const void *vsuf, void *out) {
+    cs::AttnArgs a = {};
+    size_t layer_elems = (size_t)kv->n_blocks * c.n_kv_heads * kv->block_size * c.head_dim;
+    size_t off = layer_elems * layer * elem_bytes(c.dtype);
+    a.q = q; a.ksuf = ksuf; a.vsuf = vsuf; a.out = out;
+    a.k_pages = kv->k_pages ? (const char *)kv->k_pages + off : nullptr;
+    a.v_pages = kv->v_pages ? (const char *)kv->v_pages + off : nullptr;
+    a.block_table = kv->block_table;
+    a.cu = b->cu_suffix;
+    a.plens = b->prefix_lens;
+    a.B = b->B; a.T = b->T; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.hd = c.head_dim;
+    a.n_blocks = kv->n_blocks; a.block_size = kv->block_size; a.max_blocks = kv->max_blocks_per_seq;
+    a.scale = 1.0f / sqrtf((float)c.head_dim);
+    return a;
+}
+
+// Attention of one layer on an already planned batch.
+int run_attention(confspec_ctx *ctx, const cs::AttnArgs &a, char *ws, const WsLayout &L,
+                  const cs::AttnPlanCounts &pc, hipStream_t s) {
+    if (ctx->cfg.dtype == CONFSPEC_DTYPE_FP32) {
+        HIP_TRY(cs::launch_attn_f32(a, (const int32_t *)(ws + L.tok_trace), (const int32_t *)(ws + L.tok_pos), s));
+    } else {
+        HIP_TRY(cs::launch_attn_bf16(a, (const cs::AttnItem *)(ws + L.plan_items), (const cs::AttnTile *)(ws + L.plan_tiles),
+                                     (const int32_t *)(ws + L.plan_counts), (int)pc.n_items, (int)pc.n_tiles,
+                                     (float *)(ws + L.part_o), (float *)(ws + L.part_ml), s));
+    }
+    return CONFSPEC_OK;
+}
+
+// prep + (bf16) attention plan; fills pc.
+int run_plan(confspec_ctx *ctx, const confspec_batch *b, int max_L, char *ws, const WsLayout &L,
+             cs::AttnPlanCounts *pc, hipStream_t s) {
+    const confspec_model_cfg &c = ctx->cfg;
+    HIP_TRY(cs::launch_prep(b->cu_suffix, b->prefix_lens, b->B, b->T, max_L, (int32_t *)(ws + L.tok_trace),
+                            (int32_t *)(ws + L.tok_pos), (int32_t *)(ws + L.last_row), s));
+    *pc = cs::AttnPlanCounts{};
+    if (c.dtype == CONFSPEC_DTYPE_BF16) {
+        int G = c.n_q_heads / c.n_kv_heads;
+        *pc = cs::attn_plan_counts(b->h_cu_suffix, b->h_prefix_lens, b->B, G, c.n_kv_heads);
+        if (pc->n_tiles > L.max_tiles || pc->n_items > L.max_items)
+            return fail(ctx, CONFSPEC_E_WORKSPACE, "attention plan (%lld tiles, %lld items) exceeds workspace capacity",
+                        (long long)pc->n_tiles, (long long)pc->n_items);
+        HIP_TRY(cs::launch_attn_plan(b->cu_suffix, b->prefix_lens, b->B, b->T, max_L, G, c.n_kv_heads,
+                                     pc->chunks_per_item, (int)L.max_tiles, (int)L.max_items,
+                                     (cs::AttnTile *)(ws + L.plan_tiles), (cs::AttnItem *)(ws + L.plan_items),
+                                     (int32_t *)(ws + L.plan_counts), s));
+    }
+    return CONFSPEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *confspec_version(void) { return "0.1"; }
+
+int confspec_create(const confspec_model_cfg *cfg, int device, confspec_ctx **out) {
+    if (!cfg || !out) return CONFSPEC_E_INVALID_ARG;
+    *out = nullptr;
+    const confspec_model_cfg &c = *cfg;
+    if (c.n_layers < 0 || c.d_model < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.head_dim < 1 || c.d_ffn < 1 ||
+        c.vocab < 1 || !(c.rope_theta > 0.f) || !(c.rms_eps >= 0.f) || device < 0)
+        return CONFSPEC_E_INVALID_ARG;
+    if (c.dtype != CONFSPEC_DTYPE_FP32 && c.dtype != CONFSPEC_DTYPE_BF16) return CONFSPEC_E_UNSUPPORTED;
+    if (c.n_q_heads % c.n_kv_heads != 0) return CONFSPEC_E_UNSUPPORTED;
+    int qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, qw = c.n_q_heads * c.head_dim;
+    if (c.dtype == CONFSPEC_DTYPE_BF16) {
+        if (c.head_dim != 128) return CONFSPEC_E_UNSUPPORTED;
+        if (c.d_model % 128 || c.d_ffn % 64 || qkv % 128 || qw % 64) return CONFSPEC_E_UNSUPPORTED;
+    } else {
+        if (c.head_dim != 64 && c.head_dim != 128) return CONFSPEC_E_UNSUPPORTED;
+        if (c.d_model % 64 || c.d_ffn % 32 || qkv % 64 || qw % 16) return CONFSPEC_E_UNSUPPORTED;
+    }
+    confspec_ctx *ctx = new (std::nothrow) confspec_ctx();
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    ctx->cfg = c;
+    ctx->device = device;
+    *out = ctx;
+    return CONFSPEC_OK;
+}
+
+void confspec_destroy(confspec_ctx *ctx) { delete ctx; }
+
+const char *confspec_last_error(const confspec_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int confspec_workspace_bytes(const confspec_ctx *ctx, int32_t max_T, int32_t max_B, int64_t max_sum_L,
+                             size_t *out_bytes) {
+    if (!ctx || !out_bytes) return CONFSPEC_E_INVALID_ARG;
+    if (max_T < 1 || max_B < 1 || max_sum_L < 0) return fail(ctx, CONFSPEC_E_INVALID_ARG, "max_T, max_B must be >= 1, max_sum_L >= 0");
+    *out_bytes = ws_layout(ctx->cfg, max_T, max_B).total;
+    return CONFSPEC_OK;
+}
+
+int confspec_packed_bytes(const confspec_ctx *ctx, size_t *out_bytes) {
+    if (!ctx || !out_bytes) return CONFSPEC_E_INVALID_ARG;
+    const confspec_model_cfg &c = ctx->cfg;
+    *out_bytes = (size_t)c.n_layers * align_up((size_t)2 * c.d_ffn * c.d_model * elem_bytes(c.dtype));
+    return CONFSPEC_OK;
+}
+
+int confspec_pack_weights(confspec_ctx *ctx, const confspec_weights *in, void *dev_dst, size_t dst_bytes,
+                          const void **h_ptr_storage, confspec_weights *out, confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!in || !out || !h_ptr_storage) return fail(ctx, CONFSPEC_E_INVALID_ARG, "null argument");
+    if (in->packed != 0) return fail(ctx, CONFSPEC_E_INVALID_ARG, "input weights are already packed");
+    const confspec_model_cfg &c = ctx->cfg;
+    if (c.d_ffn % 32) return fail(ctx, CONFSPEC_E_UNSUPPORTED, "d_ffn must be a multiple of 32");
+    size_t need;
+    confspec_packed_bytes(ctx, &need);
+    if (!dev_dst || ((uintptr_t)dev_dst & 255)) return fail(ctx, CONFSPEC_E_WORKSPACE, "dev_dst null or not 256-byte aligned");
+    if (dst_bytes < need) return fail(ctx, CONFSPEC_E_WORKSPACE, "dev_dst has %zu bytes, %zu needed", dst_bytes, need);
+    if (c.n_layers > 0 && !in->w_gate_up) return fail(ctx, CONFSPEC_E_INVALID_ARG, "w_gate_up is null");
+    size_t per = need / (c.n_layers > 0 ? c.n_layers : 1);
+    hipStream_t s = (hipStream_t)stream;
+    for (int l = 0; l < c.n_layers; ++l) {
+        if (!in->w_gate_up[l]) return fail(ctx, CONFSPEC_E_INVALID_ARG, "w_gate_up[%d] is null", l);
+        void *dst = (char *)dev_dst + per * l;
+        HIP_TRY(cs::launch_pack_gate_up(c.dtype, in->w_gate_up[l], dst, c.d_ffn, c.d_model, s));
+        h_ptr_storage[l] = dst;
+    }
+    *out = *in;
+    out->w_gate_up = h_ptr_storage;
+    out->packed = 1;
+    return CONFSPEC_OK;
+}
+
+int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
+                    const confspec_batch *batch, const int32_t *h_verdict_ids, int32_t n_verdict,
+                    const float *h_tau, int32_t n_tau, void *dev_workspace, size_t workspace_bytes,
+                    float *dev_verdict_logits, float *dev_conf, int32_t *dev_verdict, uint8_t *dev_accept,
+                    confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    const confspec_model_cfg &c = ctx->cfg;
+    if (!w) return fail(ctx, CONFSPEC_E_INVALID_ARG, "weights is null");
+    if (!dev_verdict_logits || !dev_conf || !dev_verdict || !dev_accept)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "an output pointer is null");
+    if (w->packed != 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "weights must be packed with confspec_pack_weights");
+    if (!w->embed || !w->lm_head || !w->final_norm) return fail(ctx, CONFSPEC_E_INVALID_ARG, "embed, lm_head or final_norm is null");
+    if (c.n_layers > 0 && (!w->attn_norm || !w->wqkv || !w->wo || !w->mlp_norm || !w->w_gate_up || !w->w_down))
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "a per-layer weight array is null");
+    for (int l = 0; l < c.n_layers; ++l)
+        if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->mlp_norm[l] || !w->w_gate_up[l] || !w->w_down[l])
+            return fail(ctx, CONFSPEC_E_INVALID_ARG, "layer %d has a null weight pointer", l);
+    int rc;
+    if (!kv) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv is null");
+    int max_L = 0;
+    int64_t max_prefix = (int64_t)kv->max_blocks_per_seq * kv->block_size;
+    if ((rc = check_batch(ctx, batch, max_prefix, &max_L)) != CONFSPEC_OK) return rc;
+    if ((rc = check_kv(ctx, kv, max_L > 0)) != CONFSPEC_OK) return rc;
+    cs::VerdictArgs va;
+    if ((rc = check_verdict(ctx, h_verdict_ids, n_verdict, h_tau, n_tau, &va)) != CONFSPEC_OK) return rc;
+    WsLayout L = ws_layout(c, batch->T, batch->B);
+    if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
+
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)dev_workspace;
+    int T = batch->T, B = batch->B, d = c.d_model;
+    int qw = c.n_q_heads * c.head_dim, kw = c.n_kv_heads * c.head_dim;
+    float *x = (float *)(ws + L.x);
+    void *h = ws + L.h;
+    float *qkv = (float *)(ws + L.qkv);
+
+    cs::AttnPlanCounts pc;
+    if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
+    HIP_TRY(cs::launch_rope_table((const int32_t *)(ws + L.tok_pos), T, c.head_dim, c.rope_theta,
+                                  (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
+    HIP_TRY(cs::launch_embed(c.dtype, batch->suffix_ids, w->embed, x, T, d, c.vocab, s));
+    for (int l = 0; l < c.n_layers; ++l) {
+        HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, s));
+        if ((rc = run_gemm(ctx, h, w->wqkv[l], qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, s))) return rc;
+        HIP_TRY(cs::launch_rope_split(c.dtype, qkv, (const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin),
+                                      ws + L.q, ws + L.ksuf, ws + L.vsuf, T, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
+        cs::AttnArgs a = make_attn_args(c, kv, batch, l, ws + L.q, ws + L.ksuf, ws + L.vsuf, ws + L.attn);
+        if ((rc = run_attention(ctx, a, ws, L, pc, s))) return rc;
+        if ((rc = run_gemm(ctx, ws + L.attn, w->wo[l], x, T, d, qw, cs::EPI_RESID_F32, s))) return rc;
+        HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->mlp_norm[l], h, T, d, c.rms_eps, s));
+        if ((rc = run_gemm(ctx, h, w->w_gate_up[l], ws + L.act, T, 2 * c.d_ffn, d, cs::EPI_SWIGLU, s))) return rc;
+        if ((rc = run_gemm(ctx, ws + L.act, w->w_down[l], x, T, d, c.d_ffn, cs::EPI_RESID_F32, s))) return rc;
+    }
+    HIP_TRY(cs::launch_verdict(c.dtype, x, (const int32_t *)(ws + L.last_row), w->final_norm, w->lm_head, va, B, T, d,
+                               c.rms_eps, dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
+    return CONFSPEC_OK;
+}
+
+// ---- single-step entry points ------------------------------------------------------------------
+int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, void *dev_out, int32_t M, int32_t N,
+                     int32_t K, int32_t epilogue, confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!dev_A || !dev_W || !dev_out) return fail(ctx, CONFSPEC_E_INVALID_ARG, "null operand");
+    if (M < 1 || N < 1 || K < 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "M, N, K must be >= 1");
+    if (epilogue < 0 || epilogue > 2) return fail(ctx, CONFSPEC_E_INVALID_ARG, "unknown epilogue %d", epilogue);
+    if (ctx->cfg.dtype == CONFSPEC_DTYPE_BF16) {
+        if (N % 128 || K % 64) return fail(ctx, CONFSPEC_E_UNSUPPORTED, "bf16 GEMM needs N %% 128 == 0 and K %% 64 == 0");
+    } else if (N % 64 || K % 16) {
+        return fail(ctx, CONFSPEC_E_UNSUPPORTED, "fp32 GEMM needs N %% 64 == 0 and K %% 16 == 0");
+    }
+    return run_gemm(ctx, dev_A, dev_W, dev_out, M, N, K, epilogue, (hipStream_t)stream);
+}
+
+int confspec_op_rmsnorm(confspec_ctx *ctx, const float *dev_x, const void *dev_g, void *dev_out, int32_t n_rows,
+                        confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!dev_x || !dev_g || !dev_out || n_rows < 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "bad argument");
+    HIP_TRY(cs::launch_rmsnorm(ctx->cfg.dtype, dev_x, dev_g, dev_out, n_rows, ctx->cfg.d_model, ctx->cfg.rms_eps,
+                               (hipStream_t)stream));
+    return CONFSPEC_OK;
+}
+
+int confspec_op_rope_split(confspec_ctx *ctx, const confspec_batch *batch, int32_t max_prefix_len,
+                           const float *dev_qkv, void *dev_q, void *dev_k, void *dev_v, void *dev_workspace,
+                           size_t workspace_bytes, confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!dev_qkv || !dev_q || !dev_k || !dev_v) return fail(ctx, CONFSPEC_E_INVALID_ARG, "null operand");
+    int rc, max_L = 0;
+    if ((rc = check_batch(ctx, batch, max_prefix_len, &max_L)) != CONFSPEC_OK) return rc;
+    const confspec_model_cfg &c = ctx->cfg;
+    WsLayout L = ws_layout(c, batch->T, batch->B);
+    if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
+    char *ws = (char *)dev_workspace;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(cs::launch_prep(batch->cu_suffix, batch->prefix_lens, batch->B, batch->T, max_L, (int32_t *)(ws + L.tok_trace),
+                            (int32_t *)(ws + L.tok_pos), (int32_t *)(ws + L.last_row), s));
+    HIP_TRY(cs::launch_rope_table((const int32_t *)(ws + L.tok_pos), batch->T, c.head_dim, c.rope_theta,
+                                  (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
+    HIP_TRY(cs::launch_rope_split(c.dtype, dev_qkv, (const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin),
+                                  dev_q, dev_k, dev_v, batch->T, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
+    return CONFSPEC_OK;
+}
+
+int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confspec_batch *batch, int32_t layer,
+                          const void *dev_q, const void *dev_k_suffix, const void *dev_v_suffix, void *dev_out,
+                          void *dev_workspace, size_t workspace_bytes, confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!dev_q || !dev_k_suffix || !dev_v_suffix || !dev_out) return fail(ctx, CONFSPEC_E_INVALID_ARG, "null operand");
+    if (!kv) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv is null");
+    if (layer < 0 || layer >= (ctx->cfg.n_layers > 0 ? ctx->cfg.n_layers : 1))
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "layer %d out of range", layer);
+    int rc, max_L = 0;
+    if ((rc = check_batch(ctx, batch, (int64_t)kv->max_blocks_per_seq * kv->block_size, &max_L)) != CONFSPEC_OK) return rc;
+    if ((rc = check_kv(ctx, kv, max_L > 0)) != CONFSPEC_OK) return rc;
+    WsLayout L = ws_layout(ctx->cfg, batch->T, batch->B);
+    if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
+    char *ws = (char *)dev_workspace;
+    hipStream_t s = (hipStream_t)stream;
+    cs::AttnPlanCounts pc;
+    if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
+    cs::AttnArgs a = make_attn_args(ctx->cfg, kv, batch, layer, dev_q, dev_k_suffix, dev_v_suffix, dev_out);
+    return run_attention(ctx, a, ws, L, pc, s);
+}
+
+int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, const float *dev_x,
+                             const void *dev_final_norm, const void *dev_lm_head, const int32_t *h_verdict_ids,
+                             int32_t n_verdict, const float *h_tau, int32_t n_tau, void *dev_workspace,
+                             size_t workspace_bytes, float *dev_verdict_logits, float *dev_conf,
+                             int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!dev_x || !dev_final_norm || !dev_lm_head || !dev_verdict_logits || !dev_conf || !dev_verdict || !dev_accept)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "null operand");
+    int rc, max_L = 0;
+    if ((rc = check_batch(ctx, batch, INT32_MAX, &max_L)) != CONFSPEC_OK) return rc;
+    cs::VerdictArgs va;
+    if ((rc = check_verdict(ctx, h_verdict_ids, n_verdict, h_tau, n_tau, &va)) != CONFSPEC_OK) return rc;
+    const confspec_model_cfg &c = ctx->cfg;
+    WsLayout L = ws_layout(c, batch->T, batch->B);
+    if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
+    char *ws = (char *)dev_workspace;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(cs::launch_prep(batch->cu_suffix, batch->prefix_lens, batch->B, batch->T, max_L, (int32_t *)(ws + L.tok_trace),
+                            (int32_t *)(ws + L.tok_pos), (int32_t *)(ws + L.last_row), s));
+    HIP_TRY(cs::launch_verdict(c.dtype, dev_x, (const int32_t *)(ws + L.last_row), dev_final_norm, dev_lm_head, va,
+                               batch->B, batch->T, c.d_model, c.rms_eps, dev_verdict_logits, dev_conf, dev_verdict,
+                               dev_accept, s));
+    return CONFSPEC_OK;
+}
+
+int confspec_tune(const char *key, int32_t value) {
+    if (!key) return CONFSPEC_E_INVALID_ARG;
+    int ti, mc;
+    cs::attn_get_tune(&ti, &mc);
+    if (!strcmp(key, "gemm_tile")) {
+        if (value < 0 || value > 3) return CONFSPEC_E_INVALID_ARG;
+        cs::gemm_set_tile(value);
+    } else if (!strcmp(key, "attn_target_items")) {
+        if (value < 1 || value > 65536) return CONFSPEC_E_INVALID_ARG;
+        cs::attn_set_tune(value, mc);
+    } else if (!strcmp(key, "attn_min_chunks")) {
+        if (value < 1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
+        cs::attn_set_tune(ti, value);
+    } else {
+        return CONFSPEC_E_INVALID_ARG;
+    }
+    return CONFSPEC_OK;
+}
+
+}  // extern "C"

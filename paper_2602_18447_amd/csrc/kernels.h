@@ -1,0 +1,102 @@
+// Internal launch interface between the host API and the gfx950 kernels.
+// Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+
+namespace cs {
+
+typedef __hip_bfloat16 bf16;
+
+// ---- attention work description (built on the device by plan_attention) ----
+// One item = one q-row tile of one (trace, kv head) over one range of 64-key chunks.
+struct AttnItem {
+    int32_t b;            // trace
+    int32_t c;            // kv head
+    int32_t row0;         // first row of the tile in the trace's flattened (t * G + g) row space
+    int32_t chunk_begin;  // first 64-key chunk (inclusive)
+    int32_t chunk_end;    // last chunk (exclusive)
+    int32_t part_slot;    // >= 0: write fp32 partials to this slot; -1: write the final output
+    int32_t tile;         // index into the tile list
+    int32_t pad;
+};
+struct AttnTile {
+    int32_t b, c, row0;
+    int32_t part_base;    // first partial slot of this tile
+    int32_t n_splits;     // number of items covering this tile
+    int32_t pad[3];
+};
+
+constexpr int ATTN_BM = 128;      // q rows per tile (bf16 MFMA kernel)
+constexpr int ATTN_BN = 64;       // keys per chunk
+constexpr int ATTN_TARGET_ITEMS = 1024;
+constexpr int ATTN_MIN_CHUNKS_PER_ITEM = 4;
+
+// Host-side mirror of the planner's counting pass (same arithmetic as the device code).
+struct AttnPlanCounts {
+    int64_t n_tiles, n_items, n_part_slots, total_chunks;
+    int32_t chunks_per_item;
+};
+AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv);
+// Upper bounds used to size the workspace.
+void attn_plan_capacity(int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles, int64_t *max_items);
+
+enum Epilogue : int { EPI_STORE_F32 = 0, EPI_RESID_F32 = 1, EPI_SWIGLU = 2 };
+
+// ---- small kernels (templated on storage type: float or bf16) ----
+hipError_t launch_prep(const int32_t *cu, const int32_t *plens, int B, int T, int max_L,
+                       int32_t *tok_trace, int32_t *tok_pos, int32_t *last_row, hipStream_t s);
+hipError_t launch_rope_table(const int32_t *tok_pos, int T, int hd, float theta, float *cos_t, float *sin_t,
+                             hipStream_t s);
+hipError_t launch_embed(int dtype, const int32_t *ids, const void *E, float *x, int T, int d, int vocab,
+                        hipStream_t s);
+// x fp32 [T,d] -> out (storage dtype) [T,d]
+hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, int T, int d, float eps,
+                          hipStream_t s);
+// qkv fp32 [T, (Hq+2Hkv) hd] -> q [T,Hq,hd], ksuf [T,Hkv,hd], vsuf [T,Hkv,hd] (storage dtype), q and k rotated
+hipError_t launch_rope_split(int dtype, const float *qkv, const float *cos_t, const float *sin_t, void *q,
+                             void *ksuf, void *vsuf, int T, int Hq, int Hkv, int hd, hipStream_t s);
+hipError_t launch_pack_gate_up(int dtype, const void *src, void *dst, int F, int d, hipStream_t s);
+
+struct VerdictArgs {
+    int32_t ids[8];
+    float tau[8];
+    int32_t n_verdict, n_tau;
+};
+hipError_t launch_verdict(int dtype, const float *x, const int32_t *last_row, const void *final_norm,
+                          const void *lm_head, VerdictArgs va, int B, int T, int d, float eps, float *logits,
+                          float *conf, int32_t *verdict, uint8_t *accept, hipStream_t s);
+
+// ---- GEMM: C[M,N] = A[M,K] . W[N,K]^T with an epilogue ----
+//  EPI_STORE_F32: out fp32 [M,N]
+//  EPI_RESID_F32: out fp32 [M,N] += result (in place)
+//  EPI_SWIGLU   : W rows are gate/up interleaved in groups of 32; out (storage dtype) [M, N/2]
+hipError_t launch_gemm_f32(const float *A, const float *W, void *out, int M, int N, int K, int epi,
+                           hipStream_t s);
+hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi,
+                            hipStream_t s);
+
+// ---- attention ----
+struct AttnArgs {
+    const void *q;          // [T, Hq, hd]
+    const void *ksuf;       // [T, Hkv, hd] suffix keys (rotated)
+    const void *vsuf;       // [T, Hkv, hd]
+    const void *k_pages;    // this layer's pages [n_blocks, Hkv, bs, hd]
+    const void *v_pages;
+    const int32_t *block_table;  // [B, max_blocks]
+    const int32_t *cu;           // [B+1]
+    const int32_t *plens;        // [B]
+    void *out;              // [T, Hq*hd] storage dtype
+    int32_t B, T, Hq, Hkv, hd, n_blocks, block_size, max_blocks;
+    float scale;            // 1/sqrt(hd)
+};
+hipError_t launch_attn_f32(const AttnArgs &a, const int32_t *tok_trace, const int32_t *tok_pos, hipStream_t s);
+
+hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int T, int max_L, int G, int Hkv,
+                            int chunks_per_item, int max_tiles, int max_items, AttnTile *tiles, AttnItem *items,
+                            int32_t *counts /*[2]: n_tiles, n_items*/, hipStream_t s);
+hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
+                            int n_items_host, int n_tiles_host, float *part_o, float *part_ml, hipStream_t s);
+
+}  // namespace cs

@@ -1,0 +1,253 @@
+// Bandwidth-bound helper kernels of the verification pass: token bookkeeping, rotary table,
+// embedding gather, RMSNorm, rotary split of the QKV projection, gate/up row interleave and the
+// fused last-position verdict head (norm + verdict-row dots + softmax + threshold gate).
+#include "kernels.h"
+
+namespace cs {
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16>(bf16 v) { return __bfloat162float(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return __float2bfloat16(v); }  // RNE
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// token -> (trace, absolute position); last suffix row of each trace.  All indices are clamped to
+// the host-validated bounds so that inconsistent device arrays cannot cause out-of-range accesses.
+__global__ void prep_kernel(const int32_t *__restrict__ cu, const int32_t *__restrict__ plens, int B, int T,
+                            int max_L, int32_t *__restrict__ tok_trace, int32_t *__restrict__ tok_pos,
+                            int32_t *__restrict__ last_row) {
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < T) {
+        int lo = 0, hi = B - 1;  // largest b with cu[b] <= t
+        while (lo < hi) {
+            int mid = (lo + hi + 1) >> 1;
+            if (cu[mid] <= t) lo = mid; else hi = mid - 1;
+        }
+        int L = min(max(plens[lo], 0), max_L);
+        int off = min(max(t - cu[lo], 0), T - 1);
+        tok_trace[t] = lo;
+        tok_pos[t] = L + off;
+    }
+    if (t < B) last_row[t] = min(max(cu[t + 1] - 1, 0), T - 1);
+}
+
+hipError_t launch_prep(const int32_t *cu, const int32_t *plens, int B, int T, int max_L, int32_t *tok_trace,
+                       int32_t *tok_pos, int32_t *last_row, hipStream_t s) {
+    int n = T > B ? T : B;
+    prep_kernel<<<(n + 255) / 256, 256, 0, s>>>(cu, plens, B, T, max_L, tok_trace, tok_pos, last_row);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// cos/sin of pos * theta^(-2i/hd), evaluated in double so that positions in the tens of thousands
+// keep full fp32 accuracy after the final rounding.
+__global__ void rope_table_kernel(const int32_t *__restrict__ tok_pos, int T, int half, double log_theta,
+                                  float *__restrict__ cos_t, float *__restrict__ sin_t) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= T * half) return;
+    int t = idx / half, i = idx - t * half;
+    double inv_freq = exp(-log_theta * (double)i / (double)half);  // theta^(-2i/hd), hd = 2*half
+    double phi = (double)tok_pos[t] * inv_freq;
+    double sv, cv;
+    sincos(phi, &sv, &cv);
+    cos_t[idx] = (float)cv;
+    sin_t[idx] = (float)sv;
+}
+
+hipError_t launch_rope_table(const int32_t *tok_pos, int T, int hd, float theta, float *cos_t, float *sin_t,
+                             hipStream_t s) {
+    int half = hd / 2;
+    int n = T * half;
+    rope_table_kernel<<<(n + 255) / 256, 256, 0, s>>>(tok_pos, T, half, log((double)theta), cos_t, sin_t);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void embed_kernel(const int32_t *__restrict__ ids, const T *__restrict__ E, float *__restrict__ x,
+                             int n_tok, int d, int vocab) {
+    int t = blockIdx.x;
+    int id = min(max(ids[t], 0), vocab - 1);
+    const T *row = E + (size_t)id * d;
+    float *dst = x + (size_t)t * d;
+    for (int j = threadIdx.x; j < d; j += blockDim.x) dst[j] = to_f32<T>(row[j]);
+}
+
+hipError_t launch_embed(int dtype, const int32_t *ids, const void *E, float *x, int T, int d, int vocab,
+                        hipStream_t s) {
+    if (dtype == 0) embed_kernel<float><<<T, 256, 0, s>>>(ids, (const float *)E, x, T, d, vocab);
+    else embed_kernel<bf16><<<T, 256, 0, s>>>(ids, (const bf16 *)E, x, T, d, vocab);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// RMSNorm: one wavefront per row, fp32 statistics, output rounded to the storage type.
+template <typename T>
+__global__ void rmsnorm_kernel(const float *__restrict__ x, const T *__restrict__ g, T *__restrict__ out,
+                               int n_rows, int d, float eps) {
+    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int row = blockIdx.x * (blockDim.x >> 6) + wave;
+    if (row >= n_rows) return;
+    const float4 *xr = (const float4 *)(x + (size_t)row * d);
+    int nv = d >> 2;
+    float ss = 0.f;
+    for (int j = lane; j < nv; j += 64) {
+        float4 v = xr[j];
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    ss = wave_sum(ss);
+    float r = 1.0f / sqrtf(ss / (float)d + eps);
+    T *o = out + (size_t)row * d;
+    for (int j = lane; j < nv; j += 64) {
+        float4 v = xr[j];
+        int c = j << 2;
+        o[c + 0] = from_f32<T>(v.x * r * to_f32<T>(g[c + 0]));
+        o[c + 1] = from_f32<T>(v.y * r * to_f32<T>(g[c + 1]));
+        o[c + 2] = from_f32<T>(v.z * r * to_f32<T>(g[c + 2]));
+        o[c + 3] = from_f32<T>(v.w * r * to_f32<T>(g[c + 3]));
+    }
+}
+
+hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, int T, int d, float eps,
+                          hipStream_t s) {
+    int blocks = (T + 3) / 4;
+    if (dtype == 0) rmsnorm_kernel<float><<<blocks, 256, 0, s>>>(x, (const float *)g, (float *)out, T, d, eps);
+    else rmsnorm_kernel<bf16><<<blocks, 256, 0, s>>>(x, (const bf16 *)g, (bf16 *)out, T, d, eps);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Rotate q and k heads (half-split pairing) and split the fp32 QKV projection into q, suffix-k and
+// suffix-v buffers of the storage type.
+template <typename T>
+__global__ void rope_split_kernel(const float *__restrict__ qkv, const float *__restrict__ cos_t,
+                                  const float *__restrict__ sin_t, T *__restrict__ q, T *__restrict__ ksuf,
+                                  T *__restrict__ vsuf, int n_tok, int Hq, int Hkv, int hd) {
+    int half = hd >> 1;
+    int heads = Hq + 2 * Hkv;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long total = (long)n_tok * heads * half;
+    if (idx >= total) return;
+    int i = (int)(idx % half);
+    int h = (int)((idx / half) % heads);
+    int t = (int)(idx / ((long)half * heads));
+    const float *src = qkv + ((size_t)t * heads + h) * hd;
+    float lo = src[i], hi = src[i + half];
+    T *dst;
+    if (h < Hq) dst = q + ((size_t)t * Hq + h) * hd;
+    else if (h < Hq + Hkv) dst = ksuf + ((size_t)t * Hkv + (h - Hq)) * hd;
+    else dst = vsuf + ((size_t)t * Hkv + (h - Hq - Hkv)) * hd;
+    if (h < Hq + Hkv) {
+        float c = cos_t[(size_t)t * half + i], sn = sin_t[(size_t)t * half + i];
+        float a = lo * c - hi * sn;
+        float b = hi * c + lo * sn;
+        lo = a;
+        hi = b;
+    }
+    dst[i] = from_f32<T>(lo);
+    dst[i + half] = from_f32<T>(hi);
+}
+
+hipError_t launch_rope_split(int dtype, const float *qkv, const float *cos_t, const float *sin_t, void *q,
+                             void *ksuf, void *vsuf, int T, int Hq, int Hkv, int hd, hipStream_t s) {
+    long total = (long)T * (Hq + 2 * Hkv) * (hd / 2);
+    int blocks = (int)((total + 255) / 256);
+    if (dtype == 0)
+        rope_split_kernel<float><<<blocks, 256, 0, s>>>(qkv, cos_t, sin_t, (float *)q, (float *)ksuf, (float *)vsuf,
+                                                        T, Hq, Hkv, hd);
+    else
+        rope_split_kernel<bf16><<<blocks, 256, 0, s>>>(qkv, cos_t, sin_t, (bf16 *)q, (bf16 *)ksuf, (bf16 *)vsuf, T,
+                                                       Hq, Hkv, hd);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Gate/up interleave: packed row p holds gate row f = 32*(p/64) + p%32 when p%64 < 32, else the up
+// row of the same f.  A 64-column output tile slice then carries 32 (gate, up) pairs.
+template <typename T>
+__global__ void pack_gate_up_kernel(const T *__restrict__ src, T *__restrict__ dst, int F, int d) {
+    int p = blockIdx.x;
+    int blk = p >> 6, w = p & 63;
+    int f = (blk << 5) + (w & 31);
+    const T *s = src + (size_t)((w < 32) ? f : F + f) * d;
+    T *o = dst + (size_t)p * d;
+    for (int j = threadIdx.x; j < d; j += blockDim.x) o[j] = s[j];
+}
+
+hipError_t launch_pack_gate_up(int dtype, const void *src, void *dst, int F, int d, hipStream_t s) {
+    if (dtype == 0) pack_gate_up_kernel<float><<<2 * F, 256, 0, s>>>((const float *)src, (float *)dst, F, d);
+    else pack_gate_up_kernel<bf16><<<2 * F, 256, 0, s>>>((const bf16 *)src, (bf16 *)dst, F, d);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Verdict head: for each trace, RMSNorm of the last suffix row, dot with the n_verdict LM-head rows,
+// softmax over those logits, argmax (lowest index on ties), confidence and the threshold gate.
+// The [vocab, d] LM-head GEMM is never formed.
+template <typename T>
+__global__ void verdict_kernel(const float *__restrict__ x, const int32_t *__restrict__ last_row,
+                               const T *__restrict__ g, const T *__restrict__ lm, VerdictArgs va, int B, int n_tok,
+                               int d, float eps, float *__restrict__ logits, float *__restrict__ conf,
+                               int32_t *__restrict__ verdict, uint8_t *__restrict__ accept) {
+    __shared__ float red[4];
+    __shared__ float z_s[8];
+    int b = blockIdx.x;
+    int row = min(max(last_row[b], 0), n_tok - 1);
+    const float *xr = x + (size_t)row * d;
+    int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float ss = 0.f;
+    for (int j = threadIdx.x; j < d; j += blockDim.x) ss += xr[j] * xr[j];
+    ss = wave_sum(ss);
+    if (lane == 0) red[wave] = ss;
+    __syncthreads();
+    float tot = red[0] + red[1] + red[2] + red[3];
+    float r = 1.0f / sqrtf(tot / (float)d + eps);
+    __syncthreads();
+    for (int v = 0; v < va.n_verdict; ++v) {
+        const T *wr = lm + (size_t)va.ids[v] * d;
+        float acc = 0.f;
+        for (int j = threadIdx.x; j < d; j += blockDim.x) acc += (xr[j] * r * to_f32<T>(g[j])) * to_f32<T>(wr[j]);
+        acc = wave_sum(acc);
+        if (lane == 0) red[wave] = acc;
+        __syncthreads();
+        if (threadIdx.x == 0) z_s[v] = red[0] + red[1] + red[2] + red[3];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        int best = 0;
+        float zmax = z_s[0];
+        for (int v = 1; v < va.n_verdict; ++v)
+            if (z_s[v] > zmax) { zmax = z_s[v]; best = v; }
+        float den = 0.f;
+        for (int v = 0; v < va.n_verdict; ++v) {
+            logits[(size_t)b * va.n_verdict + v] = z_s[v];
+            den += expf(z_s[v] - zmax);
+        }
+        float c = 1.0f / den;  // probability of the argmax entry
+        conf[b] = c;
+        verdict[b] = best;
+        for (int i = 0; i < va.n_tau; ++i) accept[(size_t)i * B + b] = (c >= va.tau[i]) ? 1 : 0;
+    }
+}
+
+hipError_t launch_verdict(int dtype, const float *x, const int32_t *last_row, const void *final_norm,
+                          const void *lm_head, VerdictArgs va, int B, int T, int d, float eps, float *logits,
+                          float *conf, int32_t *verdict, uint8_t *accept, hipStream_t s) {
+    if (dtype == 0)
+        verdict_kernel<float><<<B, 256, 0, s>>>(x, last_row, (const float *)final_norm, (const float *)lm_head, va, B,
+                                                T, d, eps, logits, conf, verdict, accept);
+    else
+        verdict_kernel<bf16><<<B, 256, 0, s>>>(x, last_row, (const bf16 *)final_norm, (const bf16 *)lm_head, va, B, T,
+                                               d, eps, logits, conf, verdict, accept);
+    return hipGetLastError();
+}
+
+}  // namespace cs

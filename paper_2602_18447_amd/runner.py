@@ -1,0 +1,79 @@
+"""Device-memory plumbing around the C ABI: owns the context, the packed gate/up
+weights, the workspace and the output tensors.  No arithmetic happens here."""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Sequence
+
+import numpy as np
+import torch
+
+from . import binding as cb
+
+
+class Verifier:
+    """One model shape on one GPU.
+
+    weights: any object with tensors embed, lm_head, final_norm and per-layer lists attn_norm, wqkv,
+    wo, mlp_norm, w_gate_up ([2F, d], gate rows then up rows), w_down - already on the GPU, in the
+    model's storage dtype.
+    """
+
+    def __init__(self, model_cfg, weights, device: int = 0):
+        m = model_cfg
+        self.model = m
+        self.device = torch.device("cuda", device)
+        self.cfg = cb.make_model_cfg(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ffn,
+                                     m.vocab, m.rope_theta, m.rms_eps, m.dtype)
+        self.ctx = cb.confspec_create(self.cfg, device)
+        self._weights = weights  # keeps the tensors alive
+        w_in, self._keep_in = cb.make_weights(weights.embed, weights.lm_head, weights.final_norm, weights.attn_norm,
+                                              weights.wqkv, weights.wo, weights.mlp_norm, weights.w_gate_up,
+                                              weights.w_down, packed=0)
+        nbytes = cb.confspec_packed_bytes(self.ctx)
+        self._packed = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+        self._packed_ptrs = (C.c_void_p * max(m.n_layers, 1))()
+        self.w = cb.Weights()
+        cb.confspec_pack_weights(self.ctx, w_in, self._packed, nbytes, self._packed_ptrs, self.w)
+        torch.cuda.synchronize(self.device)
+        self._ws = None
+
+    def close(self):
+        if self.ctx is not None:
+            cb.confspec_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace(self, T: int, B: int) -> torch.Tensor:
+        need = cb.confspec_workspace_bytes(self.ctx, T, B, 0)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def bind(self, kv, batch):
+        """Builds the KV / batch structs for tensors that already live on the GPU."""
+        kvs = cb.make_kv(kv.k_pages, kv.v_pages, batch.block_table, batch.n_blocks, batch.block_size,
+                         batch.max_blocks_per_seq)
+        bs, keep = cb.make_batch(batch.suffix_ids, batch.cu_suffix, batch.prefix_lens, batch.h_cu_suffix,
+                                 batch.h_prefix_lens)
+        return kvs, bs, keep
+
+    def alloc_outputs(self, B: int, n_verdict: int, n_tau: int):
+        dev = self.device
+        return (torch.empty(B, n_verdict, dtype=torch.float32, device=dev),
+                torch.empty(B, dtype=torch.float32, device=dev),
+                torch.empty(B, dtype=torch.int32, device=dev),
+                torch.empty(n_tau, B, dtype=torch.uint8, device=dev))
+
+    def verify(self, kv, batch, verdict_ids: Sequence[int], taus: Sequence[float], outputs=None, stream=None):
+        """Enqueues one pass; returns (logits, conf, verdict, accept) device tensors (not synchronised)."""
+        kvs, bs, keep = self.bind(kv, batch)
+        ws = self.workspace(bs.T, bs.B)
+        outs = outputs or self.alloc_outputs(bs.B, len(verdict_ids), len(taus))
+        cb.confspec_verify(self.ctx, self.w, kvs, bs, verdict_ids, taus, ws, *outs, stream=stream)
+        return outs

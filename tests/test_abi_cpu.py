@@ -1,0 +1,152 @@
+"""C-ABI checks that need no GPU: the library loads, exports every declared symbol, and rejects bad
+arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2602_18447_amd import binding as cb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    names = set()
+    for hdr in ("confspec.h", "confspec_ops.h"):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(confspec_[a-z_0-9]+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    declared = _declared_symbols()
+    assert {"confspec_create", "confspec_verify", "confspec_pack_weights", "confspec_workspace_bytes",
+            "confspec_op_gemm", "confspec_op_attention", "confspec_op_verdict_gate"} <= declared
+    for name in declared:
+        assert hasattr(cb.lib, name), f"{name} declared in include/ but not exported"
+    assert set(cb.EXPORTED) == declared
+    assert cb.confspec_version() == "0.1"
+
+
+def _cfg(dtype="bf16", **kw):
+    base = dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ffn=512, vocab=1000,
+                rope_theta=1e6, rms_eps=1e-6, dtype=dtype)
+    base.update(kw)
+    return cb.make_model_cfg(**base)
+
+
+def test_create_rejects_unsupported_shapes():
+    for bad in (dict(head_dim=64), dict(n_q_heads=5), dict(d_model=200), dict(d_ffn=100)):
+        with pytest.raises(cb.ConfSpecError) as e:
+            cb.confspec_create(_cfg(**bad))
+        assert e.value.code == cb.E_UNSUPPORTED
+    with pytest.raises(cb.ConfSpecError) as e:
+        cb.confspec_create(_cfg(vocab=0))
+    assert e.value.code == cb.E_INVALID_ARG
+    ctx = cb.confspec_create(_cfg("fp32", head_dim=64, n_kv_heads=4))
+    cb.confspec_destroy(ctx)
+
+
+def test_workspace_size_is_monotone_and_aligned():
+    ctx = cb.confspec_create(_cfg())
+    a = cb.confspec_workspace_bytes(ctx, 64, 2)
+    b = cb.confspec_workspace_bytes(ctx, 128, 2)
+    c = cb.confspec_workspace_bytes(ctx, 128, 8)
+    assert a % 256 == 0 and a < b <= c
+    with pytest.raises(cb.ConfSpecError):
+        cb.confspec_workspace_bytes(ctx, 0, 1)
+    cb.confspec_destroy(ctx)
+
+
+class _FakeDev:
+    """Stands in for a device tensor: a fixed fake address, never dereferenced because every call in
+    this file must fail validation before the first launch."""
+
+    def __init__(self, addr=0x10000, nbytes=1 << 40):
+        self._a, self._n = addr, nbytes
+
+    def data_ptr(self):
+        return self._a
+
+    def numel(self):
+        return self._n
+
+    def element_size(self):
+        return 1
+
+
+def _verify_args(ctx_cfg, B=2, S=(3, 2), L=(5, 0), block_size=16):
+    fake = _FakeDev()
+    n_layers = ctx_cfg.n_layers
+    ptrs = [fake] * n_layers
+    w, keep_w = cb.make_weights(fake, fake, fake, ptrs, ptrs, ptrs, ptrs, ptrs, ptrs, packed=1)
+    kv = cb.make_kv(fake, fake, fake, 8, block_size, 4)
+    cu = np.concatenate([[0], np.cumsum(S)]).astype(np.int32)
+    batch, keep_b = cb.make_batch(fake, fake, fake, cu, np.asarray(L, dtype=np.int32))
+    return fake, w, kv, batch, (keep_w, keep_b)
+
+
+def _expect(ctx, code, fn):
+    with pytest.raises(cb.ConfSpecError) as e:
+        fn()
+    assert e.value.code == code, str(e.value)
+    assert cb.confspec_last_error(ctx) != ""
+
+
+def test_verify_validates_before_any_launch():
+    cfg = _cfg()
+    ctx = cb.confspec_create(cfg)
+    fake, w, kv, batch, keep = _verify_args(cfg)
+    out = (fake, fake, fake, fake)
+    ok = dict(verdict_ids=[1, 2], taus=[0.9])
+
+    def call(w=w, kv=kv, batch=batch, ws=fake, out=out, **kw):
+        a = dict(ok)
+        a.update(kw)
+        return cb.confspec_verify(ctx, w, kv, batch, a["verdict_ids"], a["taus"], ws, *out, stream=0)
+
+    _expect(ctx, cb.E_INVALID_ARG, lambda: call(verdict_ids=[1]))
+    _expect(ctx, cb.E_INVALID_ARG, lambda: call(verdict_ids=list(range(9))))
+    _expect(ctx, cb.E_INVALID_ARG, lambda: call(verdict_ids=[3, 3]))
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call(verdict_ids=[1, 1000]))
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call(verdict_ids=[-1, 5]))
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call(taus=[1.5]))
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call(taus=[float("nan")]))
+    _expect(ctx, cb.E_INVALID_ARG, lambda: call(taus=[]))
+    _expect(ctx, cb.E_INVALID_ARG, lambda: call(out=(None, fake, fake, fake)))
+    _expect(ctx, cb.E_INVALID_ARG, lambda: call(ws=None))
+    _expect(ctx, cb.E_WORKSPACE, lambda: call(ws=_FakeDev(0x10000, 1024)))
+    _expect(ctx, cb.E_WORKSPACE, lambda: call(ws=_FakeDev(0x10010)))
+    # unpacked weights are refused
+    w2, k2 = cb.make_weights(fake, fake, fake, *[[fake] * 2] * 6, packed=0)
+    _expect(ctx, cb.E_INVALID_ARG, lambda: call(w=w2))
+    # batch problems
+    _, _, _, bad, k3 = _verify_args(cfg, S=(3, 0))
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call(batch=bad))            # empty suffix
+    _, _, _, bad, k4 = _verify_args(cfg, L=(65, 0))
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call(batch=bad))            # prefix longer than the block table
+    _, _, _, bad, k5 = _verify_args(cfg, L=(-1, 0))
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call(batch=bad))
+    bad_T = cb.Batch(batch.B, batch.T + 1, batch.suffix_ids, batch.cu_suffix, batch.prefix_lens,
+                     batch.h_cu_suffix, batch.h_prefix_lens)
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call(batch=bad_T))
+    # bf16 attention is written for 16-token pages
+    _, _, kv8, _, k6 = _verify_args(cfg, block_size=8)
+    _expect(ctx, cb.E_UNSUPPORTED, lambda: call(kv=kv8))
+    cb.confspec_destroy(ctx)
+
+
+def test_op_gemm_and_tune_validation():
+    ctx = cb.confspec_create(_cfg())
+    fake = _FakeDev()
+    _expect(ctx, cb.E_UNSUPPORTED, lambda: cb.confspec_op_gemm(ctx, fake, fake, fake, 8, 100, 64, 0, stream=0))
+    _expect(ctx, cb.E_UNSUPPORTED, lambda: cb.confspec_op_gemm(ctx, fake, fake, fake, 8, 128, 40, 0, stream=0))
+    _expect(ctx, cb.E_INVALID_ARG, lambda: cb.confspec_op_gemm(ctx, fake, fake, fake, 0, 128, 64, 0, stream=0))
+    _expect(ctx, cb.E_INVALID_ARG, lambda: cb.confspec_op_gemm(ctx, fake, fake, fake, 8, 128, 64, 7, stream=0))
+    with pytest.raises(cb.ConfSpecError):
+        cb.confspec_tune("no_such_key", 1)
+    cb.confspec_tune("gemm_tile", 0)
+    cb.confspec_destroy(ctx)

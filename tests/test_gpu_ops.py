@@ -1,0 +1,285 @@
+"""Per-step GPU parity: each kernel of the pass against the matching oracle sub-step, through the C ABI.
+
+Inputs are rounded to the storage dtype first and the oracle reads exactly those values (widened to
+fp64), so differences come from the kernels' own arithmetic only.  Tolerances: fp32 steps accumulate
+in fp32 (1e-5 relative to the result scale); bf16 GEMMs accumulate in fp32, so an fp32 output carries
+about sqrt(K) * 2^-24 of the product scale and a bf16 output one rounding (2^-9 relative); bf16
+attention additionally rounds the probabilities to bf16 before P.V.
+"""
+import numpy as np
+import pytest
+import torch
+
+import confspec_workloads as W
+from oracle import confspec_oracle as O
+from paper_2602_18447_amd import binding as cb
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def f64(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def _ctx(dtype, **kw):
+    base = dict(n_layers=1, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ffn=256, vocab=512,
+                rope_theta=1e6, rms_eps=1e-6, dtype=dtype)
+    base.update(kw)
+    return cb.confspec_create(cb.make_model_cfg(**base)), base
+
+
+def _rand(shape, dtype, seed, scale=1.0):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    return (torch.randn(shape, generator=g, device=DEV, dtype=torch.float32) * scale).to(dtype)
+
+
+def _pack_rows(F):
+    p = np.arange(2 * F)
+    blk, w = p // 64, p % 64
+    f = blk * 32 + (w % 32)
+    return np.where(w < 32, f, F + f)
+
+
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("M,N,K", [(300, 512, 192), (1, 256, 64), (257, 768, 1024), (512, 256, 320)])
+def test_gemm_bf16_store_and_residual(tile, M, N, K):
+    print(f"gemm bf16 tile={tile} M={M} N={N} K={K}", flush=True)
+    ctx, _ = _ctx("bf16")
+    cb.confspec_tune("gemm_tile", tile)
+    A = _rand((M, K), torch.bfloat16, 1)
+    Wt = _rand((N, K), torch.bfloat16, 2, 0.05)
+    ref = f64(A) @ f64(Wt).T
+    scale = np.abs(ref).max()
+    out = torch.full((M + 3, N), 7.0, dtype=torch.float32, device=DEV)       # 3 guard rows
+    cb.confspec_op_gemm(ctx, A, Wt, out, M, N, K, cb.EPI_STORE_F32)
+    torch.cuda.synchronize()
+    assert np.abs(f64(out[:M]) - ref).max() <= 2e-5 * scale
+    assert torch.all(out[M:] == 7.0)
+    x0 = _rand((M, N), torch.float32, 3)
+    x = x0.clone()
+    cb.confspec_op_gemm(ctx, A, Wt, x, M, N, K, cb.EPI_RESID_F32)
+    torch.cuda.synchronize()
+    assert np.abs(f64(x) - (f64(x0) + ref)).max() <= 2e-5 * max(scale, 4.0)
+    cb.confspec_tune("gemm_tile", 0)
+    cb.confspec_destroy(ctx)
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3])
+def test_gemm_bf16_swiglu_epilogue(tile):
+    print(f"gemm bf16 swiglu tile={tile}", flush=True)
+    ctx, _ = _ctx("bf16")
+    cb.confspec_tune("gemm_tile", tile)
+    M, F, K = 200, 384, 256
+    A = _rand((M, K), torch.bfloat16, 4)
+    Wgu = _rand((2 * F, K), torch.bfloat16, 5, 0.1)           # gate rows, then up rows
+    packed = Wgu[torch.as_tensor(_pack_rows(F), device=DEV)].contiguous()
+    out = torch.zeros((M, F), dtype=torch.bfloat16, device=DEV)
+    cb.confspec_op_gemm(ctx, A, packed, out, M, 2 * F, K, cb.EPI_SWIGLU)
+    torch.cuda.synchronize()
+    g = f64(A) @ f64(Wgu[:F]).T
+    u = f64(A) @ f64(Wgu[F:]).T
+    ref = O.silu(g) * u
+    err = np.abs(f64(out) - ref)
+    assert np.all(err <= 2.0 ** -8 * np.abs(ref) + 1e-4 * np.abs(ref).max())
+    cb.confspec_tune("gemm_tile", 0)
+    cb.confspec_destroy(ctx)
+
+
+def test_gemm_fp32_all_epilogues():
+    print("gemm fp32", flush=True)
+    ctx, _ = _ctx("fp32", head_dim=64, n_kv_heads=4)
+    M, N, K = 77, 192, 80
+    A = _rand((M, K), torch.float32, 6)
+    Wt = _rand((N, K), torch.float32, 7, 0.1)
+    ref = f64(A) @ f64(Wt).T
+    out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    cb.confspec_op_gemm(ctx, A, Wt, out, M, N, K, cb.EPI_STORE_F32)
+    x0 = _rand((M, N), torch.float32, 8)
+    x = x0.clone()
+    cb.confspec_op_gemm(ctx, A, Wt, x, M, N, K, cb.EPI_RESID_F32)
+    F = N // 2
+    packed = Wt[torch.as_tensor(_pack_rows(F), device=DEV)].contiguous()
+    act = torch.zeros((M, F), dtype=torch.float32, device=DEV)
+    cb.confspec_op_gemm(ctx, A, packed, act, M, N, K, cb.EPI_SWIGLU)
+    torch.cuda.synchronize()
+    s = np.abs(ref).max()
+    assert np.abs(f64(out) - ref).max() <= 1e-5 * s
+    assert np.abs(f64(x) - (f64(x0) + ref)).max() <= 1e-5 * max(s, 4.0)
+    ref_act = O.silu(ref[:, :F]) * ref[:, F:]
+    assert np.abs(f64(act) - ref_act).max() <= 1e-5 * np.abs(ref_act).max()
+    cb.confspec_destroy(ctx)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 1536), ("fp32", 256), ("bf16", 5120)])
+def test_rmsnorm(dtype, d):
+    print(f"rmsnorm {dtype} d={d}", flush=True)
+    ctx, base = _ctx(dtype, d_model=d, head_dim=128 if dtype == "bf16" else 64, n_kv_heads=2 if dtype == "bf16" else 4)
+    td = W.torch_dtype(dtype)
+    x = _rand((37, d), torch.float32, 9, 3.0)
+    g = (1 + 0.1 * _rand((d,), torch.float32, 10)).to(td)
+    out = torch.zeros((37, d), dtype=td, device=DEV)
+    cb.confspec_op_rmsnorm(ctx, x, g, out, 37)
+    torch.cuda.synchronize()
+    ref = O.rmsnorm(f64(x), f64(g), base["rms_eps"])
+    tol = 2.0 ** -8 if dtype == "bf16" else 1e-6
+    assert np.all(np.abs(f64(out) - ref) <= tol * np.abs(ref) + 1e-6)
+    cb.confspec_destroy(ctx)
+
+
+def _batch_structs(wl, batch_dev):
+    bs, keep = cb.make_batch(batch_dev.suffix_ids, batch_dev.cu_suffix, batch_dev.prefix_lens,
+                             batch_dev.h_cu_suffix, batch_dev.h_prefix_lens)
+    return bs, keep
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_rope_split_positions_reach_tens_of_thousands(dtype):
+    print(f"rope_split {dtype}", flush=True)
+    hd = 128 if dtype == "bf16" else 64
+    wl = W.tiny_workload("rope", 3, dtype=dtype, n_q_heads=4, n_kv_heads=2, head_dim=hd, d_model=256,
+                         prefix_lens=(16383, 0, 700), suffix_lens=(5, 3, 9), block_size=16)
+    m = wl.model
+    ctx, _ = _ctx(dtype, head_dim=hd)
+    batch = W.make_batch(wl, DEV)
+    bs, keep = _batch_structs(wl, batch)
+    T = wl.T
+    heads = m.n_q_heads + 2 * m.n_kv_heads
+    qkv = _rand((T, heads * hd), torch.float32, 11)
+    td = W.torch_dtype(dtype)
+    q = torch.zeros((T, m.n_q_heads, hd), dtype=td, device=DEV)
+    k = torch.zeros((T, m.n_kv_heads, hd), dtype=td, device=DEV)
+    v = torch.zeros((T, m.n_kv_heads, hd), dtype=td, device=DEV)
+    ws = torch.empty(cb.confspec_workspace_bytes(ctx, T, wl.B), dtype=torch.uint8, device=DEV)
+    cb.confspec_op_rope_split(ctx, bs, 16384, qkv, q, k, v, ws)
+    torch.cuda.synchronize()
+    a = f64(qkv).reshape(T, heads, hd)
+    pos = np.concatenate([L + np.arange(S) for L, S in zip(wl.prefix_lens, wl.suffix_lens)])
+    rq = O.rope(a[:, :m.n_q_heads], pos, m.rope_theta)
+    rk = O.rope(a[:, m.n_q_heads:m.n_q_heads + m.n_kv_heads], pos, m.rope_theta)
+    rv = a[:, m.n_q_heads + m.n_kv_heads:]
+    tol = 2.0 ** -8 if dtype == "bf16" else 2e-6
+    for got, ref in ((q, rq), (k, rk), (v, rv)):
+        assert np.abs(f64(got) - ref).max() <= tol * np.abs(ref).max()
+    cb.confspec_destroy(ctx)
+
+
+def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16, seed=20):
+    wl = W.tiny_workload("attn", seed, dtype=dtype, n_layers=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd,
+                         d_model=256, prefix_lens=prefix_lens, suffix_lens=suffix_lens, block_size=block_size)
+    m = wl.model
+    ctx, _ = _ctx(dtype, n_layers=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd)
+    batch = W.make_batch(wl, DEV)
+    kv = W.make_seeded_kv(wl, batch, DEV)
+    td = W.torch_dtype(dtype)
+    T = wl.T
+    q = _rand((T, hq, hd), td, seed + 1)
+    ks = _rand((T, hkv, hd), td, seed + 2, 0.5)
+    vs = _rand((T, hkv, hd), td, seed + 3, 0.5)
+    out = torch.zeros((T, hq * hd), dtype=td, device=DEV)
+    kvs = cb.make_kv(kv.k_pages, kv.v_pages, batch.block_table, batch.n_blocks, block_size, batch.max_blocks_per_seq)
+    bs, keep = _batch_structs(wl, batch)
+    ws = torch.empty(cb.confspec_workspace_bytes(ctx, T, wl.B), dtype=torch.uint8, device=DEV)
+    layer = 1
+    cb.confspec_op_attention(ctx, kvs, bs, layer, q, ks, vs, out, ws)
+    torch.cuda.synchronize()
+    view = W.OracleKVView(kv, batch)
+    got = f64(out).reshape(T, hq, hd)
+    worst = 0.0
+    for b, (L, S) in enumerate(zip(prefix_lens, suffix_lens)):
+        lo = int(batch.h_cu_suffix[b])
+        nblk = (L + block_size - 1) // block_size
+        ids = batch.block_table[b, :nblk].cpu().numpy()
+        if L:
+            kp = O.gather_prefix(view.k_blocks(layer, ids), L)
+            vp = O.gather_prefix(view.v_blocks(layer, ids), L)
+        else:
+            kp = vp = np.zeros((0, hkv, hd))
+        k_all = np.concatenate([kp, f64(ks[lo:lo + S])])
+        v_all = np.concatenate([vp, f64(vs[lo:lo + S])])
+        ref = O.attention(f64(q[lo:lo + S]), k_all, v_all, L)
+        worst = max(worst, np.abs(got[lo:lo + S] - ref).max())
+    cb.confspec_destroy(ctx)
+    return worst
+
+
+@pytest.mark.parametrize("prefix_lens,suffix_lens", [
+    ((128,) * 3, (32,) * 3),                 # whole chunks
+    ((0, 5, 77, 200, 1), (1, 7, 33, 64, 100)),   # ragged: empty prefix, page tails, chunk straddling
+    ((1000, 17), (96, 130)),                 # several q tiles per trace, long prefix
+])
+def test_attention_fp32(prefix_lens, suffix_lens):
+    print(f"attention fp32 L={prefix_lens} S={suffix_lens}", flush=True)
+    err = _attention_case("fp32", 4, 4, 64, prefix_lens, suffix_lens)
+    assert err <= 2e-5
+    err = _attention_case("fp32", 4, 2, 128, prefix_lens, suffix_lens, block_size=8)
+    assert err <= 2e-5
+
+
+@pytest.mark.parametrize("hq,hkv", [(12, 2), (5, 1), (4, 4)])
+@pytest.mark.parametrize("prefix_lens,suffix_lens", [
+    ((128,) * 3, (32,) * 3),
+    ((0, 5, 77, 200, 1), (1, 7, 33, 64, 100)),
+    ((1000, 17), (96, 130)),
+])
+def test_attention_bf16(hq, hkv, prefix_lens, suffix_lens):
+    print(f"attention bf16 hq={hq} hkv={hkv} L={prefix_lens} S={suffix_lens}", flush=True)
+    err = _attention_case("bf16", hq, hkv, 128, prefix_lens, suffix_lens)
+    print("  max abs err", err, flush=True)
+    assert err <= 6e-3
+
+
+def test_attention_bf16_split_kv_merge_matches_unsplit():
+    """Force many key-range splits: the merged result must meet the same bound."""
+    print("attention bf16 forced splits", flush=True)
+    cb.confspec_tune("attn_min_chunks", 1)
+    cb.confspec_tune("attn_target_items", 4096)
+    try:
+        err = _attention_case("bf16", 12, 2, 128, (700, 64, 0, 3000), (40, 96, 20, 7))
+    finally:
+        cb.confspec_tune("attn_min_chunks", 4)
+        cb.confspec_tune("attn_target_items", 1024)
+    print("  max abs err", err, flush=True)
+    assert err <= 6e-3
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_verdict_head_and_gate(dtype):
+    print(f"verdict gate {dtype}", flush=True)
+    d, V = 256, 512
+    hd = 128 if dtype == "bf16" else 64
+    ctx, base = _ctx(dtype, d_model=d, vocab=V, head_dim=hd)
+    wl = W.tiny_workload("vg", 31, dtype=dtype, d_model=d, vocab=V, head_dim=hd, n_q_heads=4, n_kv_heads=2,
+                         prefix_lens=(3,) * 40, suffix_lens=tuple(1 + (i % 5) for i in range(40)), block_size=16)
+    batch = W.make_batch(wl, DEV)
+    bs, keep = _batch_structs(wl, batch)
+    td = W.torch_dtype(dtype)
+    T, B = wl.T, wl.B
+    x = _rand((T, d), torch.float32, 32, 2.0)
+    g = (1 + 0.1 * _rand((d,), torch.float32, 33)).to(td)
+    lm = _rand((V, d), td, 34, 0.08)
+    vids, taus = [7, 300, 12], [0.0, 0.4, 0.6, 0.9, 1.0]
+    logits = torch.zeros((B, 3), dtype=torch.float32, device=DEV)
+    conf = torch.zeros(B, dtype=torch.float32, device=DEV)
+    verdict = torch.zeros(B, dtype=torch.int32, device=DEV)
+    accept = torch.zeros((5, B), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(cb.confspec_workspace_bytes(ctx, T, B), dtype=torch.uint8, device=DEV)
+    cb.confspec_op_verdict_gate(ctx, bs, x, g, lm, vids, taus, ws, logits, conf, verdict, accept)
+    torch.cuda.synchronize()
+    xs, gs, lms = f64(x), f64(g), f64(lm)
+    for b in range(B):
+        last = int(batch.h_cu_suffix[b + 1]) - 1
+        z = O.verdict_logits(xs[last], gs, lms[vids], base["rms_eps"])
+        p, r, c = O.confidence(z)
+        assert np.abs(f64(logits[b]) - z).max() <= 2e-5 * max(1.0, np.abs(z).max())
+        assert abs(float(conf[b]) - c) <= 1e-5
+        if np.sort(z)[-1] - np.sort(z)[-2] > 1e-4:
+            assert int(verdict[b]) == r
+        want = O.gate(np.array([c]), taus)[:, 0]
+        for i, t in enumerate(taus):
+            if abs(c - t) > 1e-5:
+                assert int(accept[i, b]) == int(want[i])
+    assert accept[0].all() and accept.cpu().numpy()[:-1].sum() > accept.cpu().numpy()[-1].sum()
+    cb.confspec_destroy(ctx)

@@ -1,0 +1,118 @@
+"""End-to-end GPU parity of confspec_verify against the CPU oracle.
+
+Small cases are compared on every trace; the full-size configurations run the GPU pass at full size
+(the launch configuration the benchmark times) and compare a sample of traces the oracle can
+compute in seconds - traces are independent, so a sampled trace checks the same code paths as any
+other.  Bounds: see tests/gpu_cases.TOL.
+"""
+import numpy as np
+import pytest
+import torch
+
+import confspec_workloads as W
+from oracle import confspec_oracle as O
+from paper_2602_18447_amd.runner import Verifier
+from tests import gpu_cases as G
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config1_tiny_fp32_cache_from_prefix_pass():
+    print("config 1", flush=True)
+    wl = W.config(1)
+    taus = [0.5, 0.52, 0.55, 0.6, 0.9]           # 0.9 alone is all-escalate at this width
+    s, gpu, ora = G.parity_case(wl, taus=taus)
+    assert s["traces"] == 4
+    # cached suffix prefill on the GPU equals the oracle's full recompute over prefix + suffix
+    weights, batch, kv = G.build_inputs(wl)
+    model = W.OracleModelView(weights)
+    pre = W.make_prefix_ids(wl)
+    ids = batch.suffix_ids.cpu().numpy()
+    e = np.zeros((0, wl.model.n_kv_heads, wl.model.head_dim))
+    for b in range(wl.B):
+        suf = ids[batch.h_cu_suffix[b]:batch.h_cu_suffix[b + 1]]
+        xs, _ = O.forward(wl.model, model, [dict(ids=np.concatenate([pre[b], suf]), L=0,
+                                                 k_prefix=lambda l: e, v_prefix=lambda l: e)])
+        z = O.verdict_logits(xs[0][-1], model.final_norm, model.lm_head_rows(gpu["vids"]), wl.model.rms_eps)
+        assert np.abs(gpu["logits"][b] - z).max() <= 1e-4
+
+
+def _small_bf16(name, seed, prefix_lens, suffix_lens, **kw):
+    base = dict(dtype="bf16", n_layers=3, d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ffn=768,
+                vocab=1024, block_size=16, taus=(0.5, 0.55, 0.6, 0.9))
+    base.update(kw)
+    return W.tiny_workload(name, seed, prefix_lens=prefix_lens, suffix_lens=suffix_lens, **base)
+
+
+def test_small_bf16_ragged_every_trace():
+    print("small bf16 ragged", flush=True)
+    wl = _small_bf16("small_ragged", 2001, (0, 5, 77, 300, 1, 1000, 130), (1, 7, 33, 64, 100, 96, 250))
+    s, _, _ = G.parity_case(wl)
+    assert s["traces"] == 7
+
+
+def test_small_bf16_gqa6_cache_from_prefix_pass():
+    """Draft-like head grouping (6 q heads per kv head); bf16 cache built by the oracle's prefix pass."""
+    print("small bf16 gqa6 prefix-pass", flush=True)
+    wl = _small_bf16("small_gqa6", 2002, (40, 129), (20, 70), n_q_heads=12, n_kv_heads=2, d_model=768,
+                     d_ffn=1024, kv_source="prefix_pass", n_layers=2)
+    G.parity_case(wl)
+
+
+def test_edge_single_token_no_prefix_and_max_verdicts_and_taus():
+    print("edge cases", flush=True)
+    wl = _small_bf16("edge", 2003, (0,), (1,), n_verdict=8, taus=(0.0, 0.125, 0.13, 0.2, 0.5, 0.9, 0.99, 1.0))
+    s, gpu, _ = G.parity_case(wl)
+    assert gpu["accept"][0].all()
+    wl = _small_bf16("edge_fp32", 2004, (0, 31), (1, 2), dtype="fp32", head_dim=64, n_kv_heads=4, d_model=256)
+    G.parity_case(wl)
+
+
+def test_results_are_run_to_run_identical_and_independent_of_batch_composition():
+    print("determinism / batch independence", flush=True)
+    wl = _small_bf16("det", 2005, (700, 64, 0, 3000), (40, 96, 20, 7))
+    weights, batch, kv = G.build_inputs(wl)
+    ver = Verifier(wl.model, weights)
+    a = G.run_gpu(wl, weights, batch, kv, verifier=ver)
+    b = G.run_gpu(wl, weights, batch, kv, verifier=ver)
+    assert np.array_equal(a["logits"], b["logits"]) and np.array_equal(a["accept"], b["accept"])
+    # each trace alone: same numbers up to fp32 rounding (tile boundaries move with the packing)
+    ids = batch.suffix_ids.cpu().numpy()
+    for t in range(wl.B):
+        one = W.tiny_workload("one", wl.seed, dtype="bf16", n_layers=3, d_model=512, n_q_heads=4, n_kv_heads=2,
+                              head_dim=128, d_ffn=768, vocab=1024, block_size=16, taus=wl.taus,
+                              prefix_lens=(wl.prefix_lens[t],), suffix_lens=(wl.suffix_lens[t],))
+        b1 = W.make_batch(one, G.DEV)
+        lo, hi = batch.h_cu_suffix[t], batch.h_cu_suffix[t + 1]
+        b1.suffix_ids = torch.as_tensor(ids[lo:hi]).to(G.DEV)
+        nb = (wl.prefix_lens[t] + 15) // 16
+        b1.block_table = batch.block_table[t:t + 1, :max(nb, 1)].contiguous()
+        b1.n_blocks, b1.max_blocks_per_seq = batch.n_blocks, max(nb, 1)
+        r = G.run_gpu(wl, weights, b1, kv, verifier=ver)
+        assert np.abs(r["logits"][0] - a["logits"][t]).max() <= 1e-3
+    ver.close()
+
+
+def test_config2_draft_shape_full_size_sampled_traces():
+    print("config 2", flush=True)
+    G.parity_case(W.config(2), traces=[0, 13, 31])
+
+
+def test_config3_long_cot_tau_sweep_sampled_traces():
+    print("config 3", flush=True)
+    s, gpu, _ = G.parity_case(W.config(3), traces=[5, 63])
+    assert len(gpu["taus"]) == 3
+
+
+def test_config4_ragged_sampled_traces():
+    print("config 4", flush=True)
+    wl = W.config(4)
+    L = np.asarray(wl.prefix_lens)
+    S = np.asarray(wl.suffix_lens)
+    pick = sorted({int(np.argmin(L)), int(np.argmax(L)), int(np.argmin(S)), 77})
+    G.parity_case(wl, traces=pick)
+
+
+def test_config5_target_shape_sampled_trace():
+    print("config 5", flush=True)
+    G.parity_case(W.config(5), traces=[9])
