@@ -22,16 +22,23 @@ extern "C" {
 #define CONFSPEC_EPI_SWIGLU 2     /* W rows gate/up interleaved (confspec_pack_weights order);   */
                                   /* out (model dtype) [M, N/2] = silu(gate) * up                */
 
-/* C[M,N] = A[M,K] . W[N,K]^T with one of the epilogues above.  A and W are dev arrays of the
- * context's dtype (row-major, K contiguous).  Requires N % 128 == 0 and K % 64 == 0 for bf16,
- * N % 64 == 0 and K % 16 == 0 for fp32; any M >= 1. */
-int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, void *dev_out, int32_t M,
-                     int32_t N, int32_t K, int32_t epilogue, confspec_stream stream);
+/* Two-term activations (bf16 contexts only).  A bf16 activation matrix [M, K] may be carried as
+ * [M, 2K] = hi | lo, hi = bf16(v) and lo = bf16(v - hi), which keeps 16 mantissa bits through a bf16
+ * MFMA GEMM at twice the k-loop length.  `a_terms` / `out_terms` are 1 (plain) or 2 (hi | lo).
+ * confspec_verify uses the two-term form in the first "split_layers" layers (see confspec_tune). */
 
-/* out[t,:] = x[t,:] / sqrt(mean(x[t,:]^2) + rms_eps) * g, x fp32 [n_rows, d_model], g and out in the
- * context's dtype. */
+/* C[M,N] = A[M,K] . W[N,K]^T with one of the epilogues above.  A ([M, a_terms*K]) and W are dev
+ * arrays of the context's dtype (row-major, K contiguous).  Requires N % 128 == 0 and K % 64 == 0 for
+ * bf16, N % 64 == 0 and K % 16 == 0 for fp32; any M >= 1.  out_terms == 2 is valid with the SwiGLU
+ * epilogue only (out is then [M, 2 * N/2]). */
+int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, void *dev_out, int32_t M,
+                     int32_t N, int32_t K, int32_t epilogue, int32_t a_terms, int32_t out_terms,
+                     confspec_stream stream);
+
+/* out[t,:] = x[t,:] / sqrt(mean(x[t,:]^2) + rms_eps) * g, x fp32 [n_rows, d_model], g in the context's
+ * dtype, out [n_rows, out_terms * d_model] in the context's dtype. */
 int confspec_op_rmsnorm(confspec_ctx *ctx, const float *dev_x, const void *dev_g, void *dev_out,
-                        int32_t n_rows, confspec_stream stream);
+                        int32_t n_rows, int32_t out_terms, confspec_stream stream);
 
 /* Rotary embedding + split of a fp32 QKV projection [T, (Hq + 2 Hkv) hd] into q [T,Hq,hd],
  * k [T,Hkv,hd], v [T,Hkv,hd] (context dtype); positions are L_b + t from the batch. */
@@ -41,10 +48,10 @@ int confspec_op_rope_split(confspec_ctx *ctx, const confspec_batch *batch, int32
 
 /* Attention of one layer: softmax over keys j <= L_b + t of q . k_j / sqrt(hd), keys and values
  * 0..L_b-1 from the paged cache of `layer`, the rest from dev_k_suffix / dev_v_suffix.
- * q [T,Hq,hd], k/v suffix [T,Hkv,hd], out [T,Hq*hd], all in the context's dtype. */
+ * q [T,Hq,hd], k/v suffix [T,Hkv,hd], out [T, out_terms*Hq*hd], all in the context's dtype. */
 int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confspec_batch *batch, int32_t layer,
                           const void *dev_q, const void *dev_k_suffix, const void *dev_v_suffix, void *dev_out,
-                          void *dev_workspace, size_t workspace_bytes, confspec_stream stream);
+                          int32_t out_terms, void *dev_workspace, size_t workspace_bytes, confspec_stream stream);
 
 /* Verdict head and gate on a residual stream x fp32 [T, d_model]: for each trace the last suffix
  * row is normalised, dotted with the verdict rows of lm_head, soft-maxed over the verdicts and
@@ -55,9 +62,11 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
                              size_t workspace_bytes, float *dev_verdict_logits, float *dev_conf,
                              int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream);
 
-/* Launch-shape tunables for measurements: key "gemm_tile" (0 heuristic, 1 = 128x128, 2 = 256x256,
- * 3 = 256x128), "attn_target_items", "attn_min_chunks".  Returns CONFSPEC_E_INVALID_ARG for an
- * unknown key.  Process-wide. */
+/* Process-wide settings.  "split_layers" (default 4): number of leading layers in which
+ * confspec_verify carries the GEMM activations as two bf16 terms.  Launch-shape tunables for
+ * measurements: "gemm_tile" (0 heuristic, 1 = 128x128, 2 = 256x256, 3 = 256x128),
+ * "attn_target_items", "attn_min_chunks".  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a
+ * value out of range. */
 int confspec_tune(const char *key, int32_t value);
 
 #ifdef __cplusplus

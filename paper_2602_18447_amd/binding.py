@@ -71,13 +71,13 @@ def _load() -> C.CDLL:
     lib.confspec_verify.argtypes = [vp, P(Weights), P(KV), P(Batch), P(i32), i32, P(C.c_float), i32, vp, sz,
                                     vp, vp, vp, vp, vp]
     lib.confspec_op_gemm.restype = C.c_int
-    lib.confspec_op_gemm.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    lib.confspec_op_gemm.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
     lib.confspec_op_rmsnorm.restype = C.c_int
-    lib.confspec_op_rmsnorm.argtypes = [vp, vp, vp, vp, i32, vp]
+    lib.confspec_op_rmsnorm.argtypes = [vp, vp, vp, vp, i32, i32, vp]
     lib.confspec_op_rope_split.restype = C.c_int
     lib.confspec_op_rope_split.argtypes = [vp, P(Batch), i32, vp, vp, vp, vp, vp, sz, vp]
     lib.confspec_op_attention.restype = C.c_int
-    lib.confspec_op_attention.argtypes = [vp, P(KV), P(Batch), i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.confspec_op_attention.argtypes = [vp, P(KV), P(Batch), i32, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.confspec_op_verdict_gate.restype = C.c_int
     lib.confspec_op_verdict_gate.argtypes = [vp, P(Batch), vp, vp, vp, P(i32), i32, P(C.c_float), i32, vp, sz,
                                              vp, vp, vp, vp, vp]
@@ -171,12 +171,15 @@ def confspec_verify(ctx, w: Weights, kv: KV, batch: Batch, verdict_ids: Sequence
                                     _ptr(accept), _stream_handle(stream)))
 
 
-def confspec_op_gemm(ctx, A, W, out, M: int, N: int, K: int, epilogue: int, stream=None) -> None:
-    _check(ctx, lib.confspec_op_gemm(ctx, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, _stream_handle(stream)))
+def confspec_op_gemm(ctx, A, W, out, M: int, N: int, K: int, epilogue: int, a_terms: int = 1, out_terms: int = 1,
+                     stream=None) -> None:
+    _check(ctx, lib.confspec_op_gemm(ctx, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, a_terms, out_terms,
+                                     _stream_handle(stream)))
 
 
-def confspec_op_rmsnorm(ctx, x, g, out, n_rows: int, stream=None) -> None:
-    _check(ctx, lib.confspec_op_rmsnorm(ctx, _ptr(x), _ptr(g), _ptr(out), n_rows, _stream_handle(stream)))
+def confspec_op_rmsnorm(ctx, x, g, out, n_rows: int, out_terms: int = 1, stream=None) -> None:
+    _check(ctx, lib.confspec_op_rmsnorm(ctx, _ptr(x), _ptr(g), _ptr(out), n_rows, out_terms,
+                                        _stream_handle(stream)))
 
 
 def confspec_op_rope_split(ctx, batch: Batch, max_prefix_len: int, qkv, q, k, v, workspace, stream=None) -> None:
@@ -186,10 +189,10 @@ def confspec_op_rope_split(ctx, batch: Batch, max_prefix_len: int, qkv, q, k, v,
 
 
 def confspec_op_attention(ctx, kv: KV, batch: Batch, layer: int, q, k_suffix, v_suffix, out, workspace,
-                          stream=None) -> None:
+                          out_terms: int = 1, stream=None) -> None:
     ws_bytes = workspace.numel() * workspace.element_size()
     _check(ctx, lib.confspec_op_attention(ctx, C.byref(kv), C.byref(batch), layer, _ptr(q), _ptr(k_suffix),
-                                          _ptr(v_suffix), _ptr(out), _ptr(workspace), ws_bytes,
+                                          _ptr(v_suffix), _ptr(out), out_terms, _ptr(workspace), ws_bytes,
                                           _stream_handle(stream)))
 
 

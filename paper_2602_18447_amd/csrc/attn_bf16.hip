@@ -21,6 +21,7 @@ namespace cs {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int HD = 128;
 constexpr int K_STRIDE = 136;             // elements per K row in LDS (128 + 8 pad = 272 bytes)
@@ -166,18 +167,6 @@ hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int 
 }
 
 // ---- the attention kernel ----
-__device__ __forceinline__ const bf16 *kv_row_ptr(const AttnArgs &a, const bf16 *pages, const bf16 *suf, int b,
-                                                  int c, int L, int S, int cu_b, int j) {
-    // nullptr: key j is past the end of the trace (zero-filled, always masked)
-    if (j < L) {
-        int blk = a.block_table[(size_t)b * a.max_blocks + (j >> 4)];
-        blk = min(max(blk, 0), a.n_blocks - 1);
-        return pages + (((size_t)blk * a.Hkv + c) * 16 + (j & 15)) * HD;
-    }
-    if (j < L + S) return suf + ((size_t)(cu_b + (j - L)) * a.Hkv + c) * HD;
-    return nullptr;
-}
-
 __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnItem *__restrict__ items,
                                                          const int32_t *__restrict__ counts, int n_items_host,
                                                          float *__restrict__ part_o, float *__restrict__ part_ml) {
@@ -191,6 +180,15 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnIt
     AttnItem item = items[it_idx];
 
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (item.chunk_begin >= item.chunk_end) {
+        // a split that received no chunks: mark its rows as "nothing seen" for the merge
+        if (item.part_slot >= 0 && tid < ATTN_BM) {
+            size_t row_slot = (size_t)item.part_slot * ATTN_BM + tid;
+            part_ml[row_slot * 2] = -INFINITY;
+            part_ml[row_slot * 2 + 1] = 0.f;
+        }
+        return;
+    }
     int half = lane >> 5, lq = lane & 31;
     int G = a.Hq / a.Hkv;
     int b = min(max(item.b, 0), a.B - 1), c = min(max(item.c, 0), a.Hkv - 1);
@@ -215,46 +213,81 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnIt
     const bf16 *ks_ = reinterpret_cast<const bf16 *>(a.ksuf), *vs_ = reinterpret_cast<const bf16 *>(a.vsuf);
 
     // loader roles
-    int k_key[4], k_dst[4];
+    // K: load i of a thread takes key slot tid/16 of page i of the chunk, 16-byte vector tid%16.
+    // V: a thread takes keys 4*v_kq..+3 (one page) x hd 8*v_g..+7, to be transposed on the way into LDS.
+    int k_dst[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int v = tid + 256 * i;
-        k_key[i] = v >> 4;
-        k_dst[i] = (v >> 4) * K_STRIDE + (v & 15) * 8;
-    }
-    int v_kq = lane & 15, v_g = wave * 4 + (lane >> 4);        // keys 4*v_kq..+3, hd 8*v_g..+7
+    for (int i = 0; i < 4; ++i) k_dst[i] = ((tid >> 4) + 16 * i) * K_STRIDE + (tid & 15) * 8;
+    int v_kq = lane & 15, v_g = wave * 4 + (lane >> 4);
     int v_dst = K_TILE + (8 * v_g) * VT_STRIDE + 4 * v_kq;
+    const int32_t *bt = a.block_table + (size_t)b * a.max_blocks;        // wave-uniform
+    const size_t page_elems = (size_t)a.Hkv * 16 * HD;
+    const int k_in_page = (c * 16 + (tid >> 4)) * HD + (tid & 15) * 8;
+    const int v_in_page = (c * 16 + 4 * (v_kq & 3)) * HD + v_g * 8;
+    const int v_page_sel = v_kq >> 2;
+    const int max_page = a.max_blocks - 1;
 
-    uint4 k_reg[4], v_reg[4];
+    // Physical block ids of the 4 pages of a chunk, fetched two chunks ahead: lanes 0..3 each load one
+    // table entry into ids_v, the ids are broadcast with readlane right before the chunk's loads.
+    int ids_v = 0;
+    int ids[4];
+    auto fetch_ids = [&](int ch) {
+        int pg = min(4 * ch + (lane & 3), max_page);
+        ids_v = bt[pg];
+    };
+    auto bcast_ids = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            ids[i] = min(max(__builtin_amdgcn_readlane(ids_v, i), 0), a.n_blocks - 1);
+    };
+    // Row of key j for chunks that touch the suffix or the end of the trace: page row for j < L, else
+    // suffix row (clamped to the last one: such keys are masked for every query).
+    auto row_general = [&](const bf16 *pages, const bf16 *suf, int j) -> const bf16 * {
+        int jp = min(j, max(L - 1, 0));
+        int id = min(max(bt[min(jp >> 4, max_page)], 0), a.n_blocks - 1);
+        const bf16 *pp = pages + ((size_t)id * a.Hkv + c) * 16 * HD + (jp & 15) * HD;
+        int ts = min(max(j - L, 0), S - 1);
+        const bf16 *sp = suf + ((size_t)(cu_b + ts) * a.Hkv + c) * HD;
+        return j < L ? pp : sp;
+    };
+
+    u32x4 k_reg[4], v_reg[4];
     auto load_chunk = [&](int ch) {
         int j0 = ch * ATTN_BN;
+        if (j0 + ATTN_BN <= L) {          // uniform: the whole chunk lies in the cached prefix
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const bf16 *p = kv_row_ptr(a, kp, ks_, b, c, L, S, cu_b, j0 + k_key[i]);
-            k_reg[i] = p ? *reinterpret_cast<const uint4 *>(p + (tid & 15) * 8) : make_uint4(0, 0, 0, 0);
-        }
+            for (int i = 0; i < 4; ++i)
+                k_reg[i] = *reinterpret_cast<const u32x4 *>(kp + (size_t)ids[i] * page_elems + k_in_page);
+            int vid = v_page_sel == 0 ? ids[0] : v_page_sel == 1 ? ids[1] : v_page_sel == 2 ? ids[2] : ids[3];
+            const bf16 *vb = vp + (size_t)vid * page_elems + v_in_page;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const bf16 *p = kv_row_ptr(a, vp, vs_, b, c, L, S, cu_b, j0 + 4 * v_kq + i);
-            v_reg[i] = p ? *reinterpret_cast<const uint4 *>(p + v_g * 8) : make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < 4; ++i) v_reg[i] = *reinterpret_cast<const u32x4 *>(vb + i * HD);
+        } else {
+            const bf16 *kr[4], *vr[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                kr[i] = row_general(kp, ks_, j0 + (tid >> 4) + 16 * i) + (tid & 15) * 8;
+                vr[i] = row_general(vp, vs_, j0 + 4 * v_kq + i) + v_g * 8;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                k_reg[i] = *reinterpret_cast<const u32x4 *>(kr[i]);
+                v_reg[i] = *reinterpret_cast<const u32x4 *>(vr[i]);
+            }
         }
     };
     auto store_chunk = [&](int stage) {
         __bf16 *base = smem + stage * ATTN_STAGE;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(base + k_dst[i]) = k_reg[i];
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(base + k_dst[i]) = k_reg[i];
         // 4 keys x 8 hd  ->  8 rows of 4 keys
-        const unsigned *r0 = reinterpret_cast<const unsigned *>(&v_reg[0]);
-        const unsigned *r1 = reinterpret_cast<const unsigned *>(&v_reg[1]);
-        const unsigned *r2 = reinterpret_cast<const unsigned *>(&v_reg[2]);
-        const unsigned *r3 = reinterpret_cast<const unsigned *>(&v_reg[3]);
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             uint2 lo, hi;
-            lo.x = (r0[d] & 0xffffu) | (r1[d] << 16);
-            lo.y = (r2[d] & 0xffffu) | (r3[d] << 16);
-            hi.x = (r0[d] >> 16) | (r1[d] & 0xffff0000u);
-            hi.y = (r2[d] >> 16) | (r3[d] & 0xffff0000u);
+            lo.x = (v_reg[0][d] & 0xffffu) | (v_reg[1][d] << 16);
+            lo.y = (v_reg[2][d] & 0xffffu) | (v_reg[3][d] << 16);
+            hi.x = (v_reg[0][d] >> 16) | (v_reg[1][d] & 0xffff0000u);
+            hi.y = (v_reg[2][d] >> 16) | (v_reg[3][d] & 0xffff0000u);
             *reinterpret_cast<uint2 *>(base + v_dst + (2 * d) * VT_STRIDE) = lo;
             *reinterpret_cast<uint2 *>(base + v_dst + (2 * d + 1) * VT_STRIDE) = hi;
         }
@@ -274,28 +307,36 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnIt
     int v_frag = K_TILE + lq * VT_STRIDE + half * 8;
 
     int ch0 = item.chunk_begin, ch1 = item.chunk_end;
-    if (ch0 < ch1) {
-        load_chunk(ch0);
-        store_chunk(0);
-    }
+    fetch_ids(ch0);
+    bcast_ids();
+    load_chunk(ch0);
+    fetch_ids(ch0 + 1);
+    store_chunk(0);      // waits for every load issued so far, the Q fragments included
     __syncthreads();
     for (int ch = ch0; ch < ch1; ++ch) {
         int stage = (ch - ch0) & 1;
         bool more = ch + 1 < ch1;
-        if (more) load_chunk(ch + 1);
+        if (more) {
+            bcast_ids();            // ids of chunk ch+1, fetched during the previous iteration
+            load_chunk(ch + 1);
+            fetch_ids(ch + 2);
+        }
+        // keep the consumers of these loads (the LDS stores below) behind the MFMA work of this chunk
+        __builtin_amdgcn_sched_barrier(0);
         const __bf16 *base = smem + stage * ATTN_STAGE;
 
         f32x16 acc_s[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc_s[kb][e] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
                 bf16x8 kf = *reinterpret_cast<const bf16x8 *>(base + kb * 32 * K_STRIDE + k_frag + ks * 16);
                 acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kb], 0, 0, 0);
             }
-        }
         // register e of block kb holds key  ch*64 + 32*kb + 16*(e>>3) + 8*half + (e&7)
         int key0 = ch * ATTN_BN + 8 * half;
         bool need_mask = ch * ATTN_BN + ATTN_BN - 1 > wave_first_limit;
@@ -333,14 +374,15 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnIt
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc_o[hb][e] *= alpha;
 #pragma unroll
-        for (int hb = 0; hb < 4; ++hb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) {
+                for (int hb = 0; hb < 4; ++hb) {
                     bf16x8 vf = *reinterpret_cast<const bf16x8 *>(base + v_frag + hb * 32 * VT_STRIDE + kb * 32 + s2 * 16);
                     acc_o[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][s2], acc_o[hb], 0, 0, 0);
                 }
+        __builtin_amdgcn_sched_barrier(0);
         if (more) store_chunk(stage ^ 1);
         __syncthreads();
     }
@@ -350,15 +392,21 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnIt
     if (item.part_slot < 0) {
         if (row_valid) {
             float inv = 1.0f / l_tot;
-            bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + ((size_t)(cu_b + t) * a.Hq + c * G + g) * HD;
+            size_t row_w = (size_t)a.Hq * HD;
+            bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + (size_t)(cu_b + t) * row_w * a.out_terms + (c * G + g) * HD;
 #pragma unroll
             for (int hb = 0; hb < 4; ++hb)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
-                    union { bf16 h[4]; uint2 u; } pk;
+                    union { bf16 h[4]; uint2 u; } pk, pl;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) pk.h[j] = __float2bfloat16(acc_o[hb][q4 * 4 + j] * inv);
+                    for (int j = 0; j < 4; ++j) {
+                        float v = acc_o[hb][q4 * 4 + j] * inv;
+                        pk.h[j] = __float2bfloat16(v);
+                        pl.h[j] = __float2bfloat16(v - __bfloat162float(pk.h[j]));
+                    }
                     *reinterpret_cast<uint2 *>(o_row + 32 * hb + 8 * q4 + 4 * half) = pk.u;
+                    if (a.out_terms == 2) *reinterpret_cast<uint2 *>(o_row + row_w + 32 * hb + 8 * q4 + 4 * half) = pl.u;
                 }
         }
     } else {
@@ -405,18 +453,25 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnT
         for (int s = 0; s < tile.n_splits; ++s) {
             size_t rs = (size_t)(tile.part_base + s) * ATTN_BM + row;
             float m_s = part_ml[rs * 2], l_s = part_ml[rs * 2 + 1];
-            float w = (m_s == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_s - m_tot);
+            if (m_s == -INFINITY) continue;   // this split saw no visible key for the row
+            float w = __builtin_amdgcn_exp2f(m_s - m_tot);
             float4 v = *reinterpret_cast<const float4 *>(part_o + rs * HD + hv * 4);
             l += w * l_s;
             o.x += w * v.x; o.y += w * v.y; o.z += w * v.z; o.w += w * v.w;
         }
         float inv = 1.0f / l;
         int t = r / G, g = r - t * G;
-        bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + ((size_t)(cu_b + t) * a.Hq + c * G + g) * HD;
-        union { bf16 h[4]; uint2 u; } pk;
-        pk.h[0] = __float2bfloat16(o.x * inv); pk.h[1] = __float2bfloat16(o.y * inv);
-        pk.h[2] = __float2bfloat16(o.z * inv); pk.h[3] = __float2bfloat16(o.w * inv);
+        size_t row_w = (size_t)a.Hq * HD;
+        bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + (size_t)(cu_b + t) * row_w * a.out_terms + (c * G + g) * HD;
+        float vals[4] = {o.x * inv, o.y * inv, o.z * inv, o.w * inv};
+        union { bf16 h[4]; uint2 u; } pk, pl;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            pk.h[j] = __float2bfloat16(vals[j]);
+            pl.h[j] = __float2bfloat16(vals[j] - __bfloat162float(pk.h[j]));
+        }
         *reinterpret_cast<uint2 *>(o_row + hv * 4) = pk.u;
+        if (a.out_terms == 2) *reinterpret_cast<uint2 *>(o_row + row_w + hv * 4) = pl.u;
     }
 }
 

@@ -25,6 +25,9 @@ struct confspec_ctx {
     std::string err;
 };
 
+// Number of leading layers whose GEMM activations are carried as two bf16 terms (process-wide).
+static int g_split_layers = 4;
+
 namespace {
 
 int fail(const confspec_ctx *ctx, int code, const char *fmt, ...) {
@@ -65,13 +68,14 @@ WsLayout ws_layout(const confspec_model_cfg &c, int64_t T, int64_t B) {
     w.rope_cos = take((size_t)T * (c.head_dim / 2) * 4);
     w.rope_sin = take((size_t)T * (c.head_dim / 2) * 4);
     w.x = take((size_t)T * c.d_model * 4);
-    w.h = take((size_t)T * c.d_model * eb);
+    size_t terms = c.dtype == CONFSPEC_DTYPE_BF16 ? 2 : 1;   // room for hi | lo activations
+    w.h = take((size_t)T * c.d_model * eb * terms);
     w.qkv = take((size_t)T * (qw + 2 * kw) * 4);
     w.q = take((size_t)T * qw * eb);
     w.ksuf = take((size_t)T * kw * eb);
     w.vsuf = take((size_t)T * kw * eb);
-    w.attn = take((size_t)T * qw * eb);
-    w.act = take((size_t)T * c.d_ffn * eb);
+    w.attn = take((size_t)T * qw * eb * terms);
+    w.act = take((size_t)T * c.d_ffn * eb * terms);
     if (c.dtype == CONFSPEC_DTYPE_BF16) {
         cs::attn_plan_capacity(T, B, c.n_q_heads / c.n_kv_heads, c.n_kv_heads, &w.max_tiles, &w.max_items);
         w.plan_counts = take(256);
@@ -157,17 +161,17 @@ int check_ws(const confspec_ctx *ctx, const void *ws, size_t have, size_t need) 
     } while (0)
 
 int run_gemm(confspec_ctx *ctx, const void *A, const void *W, void *out, int M, int N, int K, int epi,
-             hipStream_t s) {
+             int a_terms, int out_terms, hipStream_t s) {
     if (ctx->cfg.dtype == CONFSPEC_DTYPE_FP32) {
         HIP_TRY(cs::launch_gemm_f32((const float *)A, (const float *)W, out, M, N, K, epi, s));
     } else {
-        HIP_TRY(cs::launch_gemm_bf16((const cs::bf16 *)A, (const cs::bf16 *)W, out, M, N, K, epi, s));
+        HIP_TRY(cs::launch_gemm_bf16((const cs::bf16 *)A, (const cs::bf16 *)W, out, M, N, K, epi, a_terms, out_terms, s));
     }
     return CONFSPEC_OK;
 }
 
 cs::AttnArgs make_attn_args(const confspec_model_cfg &c, const confspec_kv *kv, const confspec_batch *b, int layer,
-                            const void *q, const void *ksuf, const void *vsuf, void *out) {
+                            const void *q, const void *ksuf, const void *vsuf, void *out, int out_terms) {
     cs::AttnArgs a = {};
     size_t layer_elems = (size_t)kv->n_blocks * c.n_kv_heads * kv->block_size * c.head_dim;
     size_t off = layer_elems * layer * elem_bytes(c.dtype);
@@ -180,6 +184,7 @@ cs::AttnArgs make_attn_args(const confspec_model_cfg &c, const confspec_kv *kv, 
     a.B = b->B; a.T = b->T; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.hd = c.head_dim;
     a.n_blocks = kv->n_blocks; a.block_size = kv->block_size; a.max_blocks = kv->max_blocks_per_seq;
     a.scale = 1.0f / sqrtf((float)c.head_dim);
+    a.out_terms = out_terms;
     return a;
 }
 
@@ -335,16 +340,18 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
                                   (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
     HIP_TRY(cs::launch_embed(c.dtype, batch->suffix_ids, w->embed, x, T, d, c.vocab, s));
     for (int l = 0; l < c.n_layers; ++l) {
-        HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, s));
-        if ((rc = run_gemm(ctx, h, w->wqkv[l], qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, s))) return rc;
+        // The first layers' GEMM activations travel as two bf16 terms (see gemm_bf16.hip).
+        int tm = (c.dtype == CONFSPEC_DTYPE_BF16 && l < g_split_layers) ? 2 : 1;
+        HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, tm, s));
+        if ((rc = run_gemm(ctx, h, w->wqkv[l], qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, tm, 1, s))) return rc;
         HIP_TRY(cs::launch_rope_split(c.dtype, qkv, (const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin),
                                       ws + L.q, ws + L.ksuf, ws + L.vsuf, T, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
-        cs::AttnArgs a = make_attn_args(c, kv, batch, l, ws + L.q, ws + L.ksuf, ws + L.vsuf, ws + L.attn);
+        cs::AttnArgs a = make_attn_args(c, kv, batch, l, ws + L.q, ws + L.ksuf, ws + L.vsuf, ws + L.attn, tm);
         if ((rc = run_attention(ctx, a, ws, L, pc, s))) return rc;
-        if ((rc = run_gemm(ctx, ws + L.attn, w->wo[l], x, T, d, qw, cs::EPI_RESID_F32, s))) return rc;
-        HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->mlp_norm[l], h, T, d, c.rms_eps, s));
-        if ((rc = run_gemm(ctx, h, w->w_gate_up[l], ws + L.act, T, 2 * c.d_ffn, d, cs::EPI_SWIGLU, s))) return rc;
-        if ((rc = run_gemm(ctx, ws + L.act, w->w_down[l], x, T, d, c.d_ffn, cs::EPI_RESID_F32, s))) return rc;
+        if ((rc = run_gemm(ctx, ws + L.attn, w->wo[l], x, T, d, qw, cs::EPI_RESID_F32, tm, 1, s))) return rc;
+        HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->mlp_norm[l], h, T, d, c.rms_eps, tm, s));
+        if ((rc = run_gemm(ctx, h, w->w_gate_up[l], ws + L.act, T, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s))) return rc;
+        if ((rc = run_gemm(ctx, ws + L.act, w->w_down[l], x, T, d, c.d_ffn, cs::EPI_RESID_F32, tm, 1, s))) return rc;
     }
     HIP_TRY(cs::launch_verdict(c.dtype, x, (const int32_t *)(ws + L.last_row), w->final_norm, w->lm_head, va, B, T, d,
                                c.rms_eps, dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
@@ -352,26 +359,38 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
 }
 
 // ---- single-step entry points ------------------------------------------------------------------
+static int check_terms(confspec_ctx *ctx, int terms, const char *what) {
+    if (terms != 1 && !(terms == 2 && ctx->cfg.dtype == CONFSPEC_DTYPE_BF16))
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "%s must be 1, or 2 for a bf16 context (got %d)", what, terms);
+    return CONFSPEC_OK;
+}
+
 int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, void *dev_out, int32_t M, int32_t N,
-                     int32_t K, int32_t epilogue, confspec_stream stream) {
+                     int32_t K, int32_t epilogue, int32_t a_terms, int32_t out_terms, confspec_stream stream) {
     if (!ctx) return CONFSPEC_E_INVALID_ARG;
     if (!dev_A || !dev_W || !dev_out) return fail(ctx, CONFSPEC_E_INVALID_ARG, "null operand");
     if (M < 1 || N < 1 || K < 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "M, N, K must be >= 1");
     if (epilogue < 0 || epilogue > 2) return fail(ctx, CONFSPEC_E_INVALID_ARG, "unknown epilogue %d", epilogue);
+    int rc;
+    if ((rc = check_terms(ctx, a_terms, "a_terms")) || (rc = check_terms(ctx, out_terms, "out_terms"))) return rc;
+    if (out_terms == 2 && epilogue != CONFSPEC_EPI_SWIGLU)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "out_terms == 2 needs the SwiGLU epilogue");
     if (ctx->cfg.dtype == CONFSPEC_DTYPE_BF16) {
         if (N % 128 || K % 64) return fail(ctx, CONFSPEC_E_UNSUPPORTED, "bf16 GEMM needs N %% 128 == 0 and K %% 64 == 0");
     } else if (N % 64 || K % 16) {
         return fail(ctx, CONFSPEC_E_UNSUPPORTED, "fp32 GEMM needs N %% 64 == 0 and K %% 16 == 0");
     }
-    return run_gemm(ctx, dev_A, dev_W, dev_out, M, N, K, epilogue, (hipStream_t)stream);
+    return run_gemm(ctx, dev_A, dev_W, dev_out, M, N, K, epilogue, a_terms, out_terms, (hipStream_t)stream);
 }
 
 int confspec_op_rmsnorm(confspec_ctx *ctx, const float *dev_x, const void *dev_g, void *dev_out, int32_t n_rows,
-                        confspec_stream stream) {
+                        int32_t out_terms, confspec_stream stream) {
     if (!ctx) return CONFSPEC_E_INVALID_ARG;
     if (!dev_x || !dev_g || !dev_out || n_rows < 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "bad argument");
+    int rc;
+    if ((rc = check_terms(ctx, out_terms, "out_terms"))) return rc;
     HIP_TRY(cs::launch_rmsnorm(ctx->cfg.dtype, dev_x, dev_g, dev_out, n_rows, ctx->cfg.d_model, ctx->cfg.rms_eps,
-                               (hipStream_t)stream));
+                               out_terms, (hipStream_t)stream));
     return CONFSPEC_OK;
 }
 
@@ -398,8 +417,9 @@ int confspec_op_rope_split(confspec_ctx *ctx, const confspec_batch *batch, int32
 
 int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confspec_batch *batch, int32_t layer,
                           const void *dev_q, const void *dev_k_suffix, const void *dev_v_suffix, void *dev_out,
-                          void *dev_workspace, size_t workspace_bytes, confspec_stream stream) {
+                          int32_t out_terms, void *dev_workspace, size_t workspace_bytes, confspec_stream stream) {
     if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (int rt = check_terms(ctx, out_terms, "out_terms")) return rt;
     if (!dev_q || !dev_k_suffix || !dev_v_suffix || !dev_out) return fail(ctx, CONFSPEC_E_INVALID_ARG, "null operand");
     if (!kv) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv is null");
     if (layer < 0 || layer >= (ctx->cfg.n_layers > 0 ? ctx->cfg.n_layers : 1))
@@ -413,7 +433,7 @@ int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confsp
     hipStream_t s = (hipStream_t)stream;
     cs::AttnPlanCounts pc;
     if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
-    cs::AttnArgs a = make_attn_args(ctx->cfg, kv, batch, layer, dev_q, dev_k_suffix, dev_v_suffix, dev_out);
+    cs::AttnArgs a = make_attn_args(ctx->cfg, kv, batch, layer, dev_q, dev_k_suffix, dev_v_suffix, dev_out, out_terms);
     return run_attention(ctx, a, ws, L, pc, s);
 }
 
@@ -449,6 +469,9 @@ int confspec_tune(const char *key, int32_t value) {
     if (!strcmp(key, "gemm_tile")) {
         if (value < 0 || value > 3) return CONFSPEC_E_INVALID_ARG;
         cs::gemm_set_tile(value);
+    } else if (!strcmp(key, "split_layers")) {
+        if (value < 0 || value > 4096) return CONFSPEC_E_INVALID_ARG;
+        g_split_layers = value;
     } else if (!strcmp(key, "attn_target_items")) {
         if (value < 1 || value > 65536) return CONFSPEC_E_INVALID_ARG;
         cs::attn_set_tune(value, mc);

@@ -10,6 +10,12 @@
 //
 // Epilogues: plain fp32 store, fp32 residual add in place, or SwiGLU on interleaved gate/up columns
 // with a bf16 result.
+//
+// Two-term activations.  With a_terms == 2 the A operand is [M, 2K]: columns 0..K-1 hold the bf16
+// rounding of the activation ("hi") and K..2K-1 the bf16 rounding of what that rounding lost
+// ("lo"); the k loop then runs over both halves against the same W, so the fp32 accumulator receives
+// (hi + lo) . W - the product with a 16-bit-mantissa activation.  With out_terms == 2 the SwiGLU
+// epilogue writes its result in the same [M, 2F] hi | lo form for the next GEMM.
 #include "kernels.h"
 
 namespace cs {
@@ -30,7 +36,7 @@ void gemm_set_tile(int t) { g_gemm_tune.tile = t; }
 template <int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W,
                                                          void *__restrict__ out_v, int M, int N, int K,
-                                                         int tiles_m, int tiles_n) {
+                                                         int tiles_m, int tiles_n, int a_terms, int out_terms) {
     constexpr int WM = BM / 2, WN = BN / 2;     // 2 x 2 waves
     constexpr int MI = WM / 32, NI = WN / 32;   // 32x32 MFMA blocks per wave
     constexpr int A_VEC = BM / 32, B_VEC = BN / 32;  // 16-byte vectors per thread per k-tile
@@ -58,7 +64,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
     for (int i = 0; i < A_VEC; ++i) {
         int v = tid + 256 * i, r = v >> 3, kv = v & 7;
         int row = min(m0 + r, M - 1);
-        a_src[i] = reinterpret_cast<const u32x4 *>(A + (size_t)row * K + kv * 8);
+        a_src[i] = reinterpret_cast<const u32x4 *>(A + (size_t)row * K * a_terms + kv * 8);
         a_dst[i] = r * GEMM_LDS_STRIDE + kv * 8;
     }
 #pragma unroll
@@ -77,7 +83,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     u32x4 a_reg[A_VEC], b_reg[B_VEC];
-    int nk = K / GEMM_BK;
+    int nk_w = K / GEMM_BK;        // k-tiles of W
+    int nk = nk_w * a_terms;       // k-tiles of A: hi half, then lo half
     // prologue: k-tile 0 -> stage 0
 #pragma unroll
     for (int i = 0; i < A_VEC; ++i) a_reg[i] = a_src[i][0];
@@ -96,11 +103,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
         int cur = (kt & 1) * STAGE, nxt = ((kt + 1) & 1) * STAGE;
         bool more = kt + 1 < nk;
         if (more) {
-            int ko = (kt + 1) * (GEMM_BK / 8);  // in u32x4 units
+            int ka = kt + 1, kw = ka >= nk_w ? ka - nk_w : ka;   // W wraps around for the lo half
+            int ko = ka * (GEMM_BK / 8), kwo = kw * (GEMM_BK / 8);  // in u32x4 units
 #pragma unroll
             for (int i = 0; i < A_VEC; ++i) a_reg[i] = a_src[i][ko];
 #pragma unroll
-            for (int i = 0; i < B_VEC; ++i) b_reg[i] = b_src[i][ko];
+            for (int i = 0; i < B_VEC; ++i) b_reg[i] = b_src[i][kwo];
         }
 #pragma unroll
         for (int ks = 0; ks < GEMM_BK / 16; ++ks) {
@@ -142,7 +150,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
                     float gte = acc[i][j][e], up = acc[i][j + 1][e];
                     float act = gte / (1.0f + __expf(-gte)) * up;
                     int f = ((n0 + wx * WN + j * 32) >> 1) + col_l;
-                    out[(size_t)m * Fo + f] = __float2bfloat16(act);
+                    bf16 hi = __float2bfloat16(act);
+                    size_t o = (size_t)m * Fo * out_terms + f;
+                    out[o] = hi;
+                    if (out_terms == 2) out[o + Fo] = __float2bfloat16(act - __bfloat162float(hi));
                 }
             } else {
                 float *out = reinterpret_cast<float *>(out_v);
@@ -158,7 +169,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
 }
 
 template <int BM, int BN, int EPI>
-static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, hipStream_t s) {
+static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
+                              int out_terms, hipStream_t s) {
     constexpr int smem = 2 * (BM + BN) * GEMM_LDS_STRIDE * 2;
     static bool attr_set = false;
     auto kern = gemm_bf16_kernel<BM, BN, EPI>;
@@ -171,27 +183,28 @@ static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, in
     int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
     int n_tiles = tiles_m * tiles_n;
     int grid = ((n_tiles + 7) / 8) * 8;
-    kern<<<grid, 256, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n);
+    kern<<<grid, 256, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n, a_terms, out_terms);
     return hipGetLastError();
 }
 
 template <int EPI>
-static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, hipStream_t s) {
+static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
+                             int out_terms, hipStream_t s) {
     int tile = g_gemm_tune.tile;
     if (tile == 0) {
         long t256 = (long)((M + 255) / 256) * (N / 256);
         tile = (N % 256 == 0 && t256 >= 192) ? 2 : 1;
     }
-    if (tile == 2 && N % 256 == 0) return launch_tile<256, 256, EPI>(A, W, out, M, N, K, s);
-    if (tile == 3) return launch_tile<256, 128, EPI>(A, W, out, M, N, K, s);
-    return launch_tile<128, 128, EPI>(A, W, out, M, N, K, s);
+    if (tile == 2 && N % 256 == 0) return launch_tile<256, 256, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+    if (tile == 3) return launch_tile<256, 128, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+    return launch_tile<128, 128, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
 }
 
-hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi,
-                            hipStream_t s) {
-    if (epi == EPI_STORE_F32) return launch_epi<EPI_STORE_F32>(A, W, out, M, N, K, s);
-    if (epi == EPI_RESID_F32) return launch_epi<EPI_RESID_F32>(A, W, out, M, N, K, s);
-    return launch_epi<EPI_SWIGLU>(A, W, out, M, N, K, s);
+hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
+                            int out_terms, hipStream_t s) {
+    if (epi == EPI_STORE_F32) return launch_epi<EPI_STORE_F32>(A, W, out, M, N, K, a_terms, out_terms, s);
+    if (epi == EPI_RESID_F32) return launch_epi<EPI_RESID_F32>(A, W, out, M, N, K, a_terms, out_terms, s);
+    return launch_epi<EPI_SWIGLU>(A, W, out, M, N, K, a_terms, out_terms, s);
 }
 
 }  // namespace cs

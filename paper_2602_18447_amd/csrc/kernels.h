@@ -51,9 +51,9 @@ hipError_t launch_rope_table(const int32_t *tok_pos, int T, int hd, float theta,
                              hipStream_t s);
 hipError_t launch_embed(int dtype, const int32_t *ids, const void *E, float *x, int T, int d, int vocab,
                         hipStream_t s);
-// x fp32 [T,d] -> out (storage dtype) [T,d]
+// x fp32 [T,d] -> out (storage dtype) [T, terms*d]; terms == 2 (bf16 only): hi | lo two-term form
 hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, int T, int d, float eps,
-                          hipStream_t s);
+                          int terms, hipStream_t s);
 // qkv fp32 [T, (Hq+2Hkv) hd] -> q [T,Hq,hd], ksuf [T,Hkv,hd], vsuf [T,Hkv,hd] (storage dtype), q and k rotated
 hipError_t launch_rope_split(int dtype, const float *qkv, const float *cos_t, const float *sin_t, void *q,
                              void *ksuf, void *vsuf, int T, int Hq, int Hkv, int hd, hipStream_t s);
@@ -74,8 +74,10 @@ hipError_t launch_verdict(int dtype, const float *x, const int32_t *last_row, co
 //  EPI_SWIGLU   : W rows are gate/up interleaved in groups of 32; out (storage dtype) [M, N/2]
 hipError_t launch_gemm_f32(const float *A, const float *W, void *out, int M, int N, int K, int epi,
                            hipStream_t s);
-hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi,
-                            hipStream_t s);
+// a_terms == 2: A is [M, 2K] = hi | lo two-term activations; out_terms == 2 (SwiGLU only): the
+// result is written as [M, 2 * N/2] = hi | lo.
+hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
+                            int out_terms, hipStream_t s);
 
 // ---- attention ----
 struct AttnArgs {
@@ -87,9 +89,10 @@ struct AttnArgs {
     const int32_t *block_table;  // [B, max_blocks]
     const int32_t *cu;           // [B+1]
     const int32_t *plens;        // [B]
-    void *out;              // [T, Hq*hd] storage dtype
+    void *out;              // [T, out_terms * Hq*hd] storage dtype (out_terms == 2: hi | lo, bf16 only)
     int32_t B, T, Hq, Hkv, hd, n_blocks, block_size, max_blocks;
     float scale;            // 1/sqrt(hd)
+    int32_t out_terms;
 };
 hipError_t launch_attn_f32(const AttnArgs &a, const int32_t *tok_trace, const int32_t *tok_pos, hipStream_t s);
 

@@ -89,10 +89,18 @@ hipError_t launch_embed(int dtype, const int32_t *ids, const void *E, float *x, 
 }
 
 // ------------------------------------------------------------------------------------------------
-// RMSNorm: one wavefront per row, fp32 statistics, output rounded to the storage type.
+// RMSNorm: one wavefront per row, fp32 statistics, output rounded to the storage type.  With
+// terms == 2 the row is written as hi | lo: the rounded value, then the rounding of the remainder.
+template <typename T>
+__device__ __forceinline__ void store_terms(T *o, int c, int d, int terms, float v) {
+    T hi = from_f32<T>(v);
+    o[c] = hi;
+    if (terms == 2) o[d + c] = from_f32<T>(v - to_f32<T>(hi));
+}
+
 template <typename T>
 __global__ void rmsnorm_kernel(const float *__restrict__ x, const T *__restrict__ g, T *__restrict__ out,
-                               int n_rows, int d, float eps) {
+                               int n_rows, int d, float eps, int terms) {
     int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     int row = blockIdx.x * (blockDim.x >> 6) + wave;
     if (row >= n_rows) return;
@@ -105,22 +113,22 @@ __global__ void rmsnorm_kernel(const float *__restrict__ x, const T *__restrict_
     }
     ss = wave_sum(ss);
     float r = 1.0f / sqrtf(ss / (float)d + eps);
-    T *o = out + (size_t)row * d;
+    T *o = out + (size_t)row * d * terms;
     for (int j = lane; j < nv; j += 64) {
         float4 v = xr[j];
         int c = j << 2;
-        o[c + 0] = from_f32<T>(v.x * r * to_f32<T>(g[c + 0]));
-        o[c + 1] = from_f32<T>(v.y * r * to_f32<T>(g[c + 1]));
-        o[c + 2] = from_f32<T>(v.z * r * to_f32<T>(g[c + 2]));
-        o[c + 3] = from_f32<T>(v.w * r * to_f32<T>(g[c + 3]));
+        store_terms<T>(o, c + 0, d, terms, v.x * r * to_f32<T>(g[c + 0]));
+        store_terms<T>(o, c + 1, d, terms, v.y * r * to_f32<T>(g[c + 1]));
+        store_terms<T>(o, c + 2, d, terms, v.z * r * to_f32<T>(g[c + 2]));
+        store_terms<T>(o, c + 3, d, terms, v.w * r * to_f32<T>(g[c + 3]));
     }
 }
 
 hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, int T, int d, float eps,
-                          hipStream_t s) {
+                          int terms, hipStream_t s) {
     int blocks = (T + 3) / 4;
-    if (dtype == 0) rmsnorm_kernel<float><<<blocks, 256, 0, s>>>(x, (const float *)g, (float *)out, T, d, eps);
-    else rmsnorm_kernel<bf16><<<blocks, 256, 0, s>>>(x, (const bf16 *)g, (bf16 *)out, T, d, eps);
+    if (dtype == 0) rmsnorm_kernel<float><<<blocks, 256, 0, s>>>(x, (const float *)g, (float *)out, T, d, eps, 1);
+    else rmsnorm_kernel<bf16><<<blocks, 256, 0, s>>>(x, (const bf16 *)g, (bf16 *)out, T, d, eps, terms);
     return hipGetLastError();
 }
 

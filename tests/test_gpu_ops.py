@@ -88,6 +88,47 @@ def test_gemm_bf16_swiglu_epilogue(tile):
     cb.confspec_destroy(ctx)
 
 
+def test_two_term_activations_through_gemm_rmsnorm_and_swiglu():
+    """hi | lo operands: the GEMM must return (hi + lo) . W^T, i.e. the product with the activation
+    kept to 16 mantissa bits, and the producers must emit hi = bf16(v), lo = bf16(v - hi)."""
+    print("two-term activations", flush=True)
+    d = 512
+    ctx, base = _ctx("bf16", d_model=d)
+    M, N, K = 150, 512, d
+    x = _rand((M, d), torch.float32, 40, 2.0)
+    g = (1 + 0.1 * _rand((d,), torch.float32, 41)).to(torch.bfloat16)
+    h2 = torch.zeros((M, 2 * d), dtype=torch.bfloat16, device=DEV)
+    cb.confspec_op_rmsnorm(ctx, x, g, h2, M, out_terms=2)
+    torch.cuda.synchronize()
+    ref_h = O.rmsnorm(f64(x), f64(g), base["rms_eps"])
+    hi, lo = f64(h2[:, :d]), f64(h2[:, d:])
+    assert np.all(np.abs(hi - ref_h) <= 2.0 ** -8 * np.abs(ref_h) + 1e-7)
+    assert np.all(np.abs(hi + lo - ref_h) <= 2.0 ** -15 * np.abs(ref_h) + 1e-6)   # fp32 evaluation of the norm
+    Wt = _rand((N, K), torch.bfloat16, 42, 0.05)
+    out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    cb.confspec_op_gemm(ctx, h2, Wt, out, M, N, K, cb.EPI_STORE_F32, a_terms=2)
+    torch.cuda.synchronize()
+    ref = (hi + lo) @ f64(Wt).T
+    assert np.abs(f64(out) - ref).max() <= 2e-5 * np.abs(ref).max()
+    one = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    cb.confspec_op_gemm(ctx, h2[:, :d].contiguous(), Wt, one, M, N, K, cb.EPI_STORE_F32)
+    torch.cuda.synchronize()
+    exact = ref_h @ f64(Wt).T
+    assert np.abs(f64(out) - exact).max() < 0.1 * np.abs(f64(one) - exact).max()
+    # SwiGLU epilogue producing hi | lo
+    F = 256
+    Wgu = _rand((2 * F, K), torch.bfloat16, 43, 0.1)
+    packed = Wgu[torch.as_tensor(_pack_rows(F), device=DEV)].contiguous()
+    act2 = torch.zeros((M, 2 * F), dtype=torch.bfloat16, device=DEV)
+    cb.confspec_op_gemm(ctx, h2, packed, act2, M, 2 * F, K, cb.EPI_SWIGLU, a_terms=2, out_terms=2)
+    torch.cuda.synchronize()
+    gate, up = (hi + lo) @ f64(Wgu[:F]).T, (hi + lo) @ f64(Wgu[F:]).T
+    ref_act = O.silu(gate) * up
+    got = f64(act2[:, :F]) + f64(act2[:, F:])
+    assert np.abs(got - ref_act).max() <= 3e-5 * np.abs(ref_act).max()
+    cb.confspec_destroy(ctx)
+
+
 def test_gemm_fp32_all_epilogues():
     print("gemm fp32", flush=True)
     ctx, _ = _ctx("fp32", head_dim=64, n_kv_heads=4)
@@ -166,7 +207,7 @@ def test_rope_split_positions_reach_tens_of_thousands(dtype):
     cb.confspec_destroy(ctx)
 
 
-def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16, seed=20):
+def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16, seed=20, out_terms=1):
     wl = W.tiny_workload("attn", seed, dtype=dtype, n_layers=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd,
                          d_model=256, prefix_lens=prefix_lens, suffix_lens=suffix_lens, block_size=block_size)
     m = wl.model
@@ -178,15 +219,18 @@ def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16,
     q = _rand((T, hq, hd), td, seed + 1)
     ks = _rand((T, hkv, hd), td, seed + 2, 0.5)
     vs = _rand((T, hkv, hd), td, seed + 3, 0.5)
-    out = torch.zeros((T, hq * hd), dtype=td, device=DEV)
+    out = torch.zeros((T, out_terms * hq * hd), dtype=td, device=DEV)
     kvs = cb.make_kv(kv.k_pages, kv.v_pages, batch.block_table, batch.n_blocks, block_size, batch.max_blocks_per_seq)
     bs, keep = _batch_structs(wl, batch)
     ws = torch.empty(cb.confspec_workspace_bytes(ctx, T, wl.B), dtype=torch.uint8, device=DEV)
     layer = 1
-    cb.confspec_op_attention(ctx, kvs, bs, layer, q, ks, vs, out, ws)
+    cb.confspec_op_attention(ctx, kvs, bs, layer, q, ks, vs, out, ws, out_terms=out_terms)
     torch.cuda.synchronize()
     view = W.OracleKVView(kv, batch)
-    got = f64(out).reshape(T, hq, hd)
+    got = f64(out)
+    if out_terms == 2:
+        got = got[:, :hq * hd] + got[:, hq * hd:]
+    got = got.reshape(T, hq, hd)
     worst = 0.0
     for b, (L, S) in enumerate(zip(prefix_lens, suffix_lens)):
         lo = int(batch.h_cu_suffix[b])
@@ -231,6 +275,14 @@ def test_attention_bf16(hq, hkv, prefix_lens, suffix_lens):
     assert err <= 6e-3
 
 
+def test_attention_bf16_two_term_output():
+    print("attention bf16 two-term output", flush=True)
+    plain = _attention_case("bf16", 12, 2, 128, (300, 17), (96, 130))
+    two = _attention_case("bf16", 12, 2, 128, (300, 17), (96, 130), out_terms=2)
+    print("  plain", plain, "two-term", two, flush=True)
+    assert two <= plain and two <= 6e-3
+
+
 def test_attention_bf16_split_kv_merge_matches_unsplit():
     """Force many key-range splits: the merged result must meet the same bound."""
     print("attention bf16 forced splits", flush=True)
@@ -238,6 +290,8 @@ def test_attention_bf16_split_kv_merge_matches_unsplit():
     cb.confspec_tune("attn_target_items", 4096)
     try:
         err = _attention_case("bf16", 12, 2, 128, (700, 64, 0, 3000), (40, 96, 20, 7))
+        err2 = _attention_case("bf16", 12, 2, 128, (700, 64, 0, 3000), (40, 96, 20, 7), out_terms=2)
+        assert err2 <= 6e-3
     finally:
         cb.confspec_tune("attn_min_chunks", 4)
         cb.confspec_tune("attn_target_items", 1024)
