@@ -13,7 +13,7 @@ import os
 from typing import List, Optional, Sequence
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(PKG_DIR, "libconfspec.so")
+LIB_PATH = os.environ.get("CONFSPEC_LIB_PATH") or os.path.join(PKG_DIR, "libconfspec.so")
 
 OK, E_INVALID_ARG, E_UNSUPPORTED, E_WORKSPACE, E_OUT_OF_RANGE, E_HIP = 0, -1, -2, -3, -4, -5
 DTYPE_FP32, DTYPE_BF16 = 0, 1
@@ -50,6 +50,10 @@ def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
                           "(there is no fallback path)")
+    # torch first: it brings its own HIP runtime, and the library must bind to that same copy so that
+    # device pointers and streams handed over from torch tensors belong to the runtime that launches.
+    import torch  # noqa: F401
+
     lib = C.CDLL(LIB_PATH)
     P = C.POINTER
     vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t

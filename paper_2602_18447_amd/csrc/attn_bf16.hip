@@ -60,20 +60,38 @@ __host__ __device__ inline int tile_chunks(int L, int S, int G, int m) {
 void attn_plan_capacity(int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles, int64_t *max_items) {
     int64_t tiles = (int64_t)Hkv * ((G * max_T + ATTN_BM - 1) / ATTN_BM + max_B);
     *max_tiles = tiles;
-    *max_items = tiles + g_target_items;
+    *max_items = 3 * tiles + 4 * g_target_items;     // see the split rule in attn_plan_counts
 }
 
+// Split rule.  Every tile's key range is cut into pieces of at most `cpi` chunks.  cpi comes from a
+// uniform split factor s in 1..4 applied to the average tile: the estimated makespan on
+// `g_target_items` concurrent workgroups, ceil(tiles * s / slots) * (avg / s + 1) (+ 2 chunk-times for
+// the merge when s > 1), is minimised; s is limited so that tiles * s <= max(2 * tiles, 4 * slots).
+// Long tiles of a ragged batch then get proportionally more pieces than short ones.
 AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv) {
     AttnPlanCounts r = {};
-    int64_t total = 0;
+    int64_t total = 0, n_tiles = 0;
     for (int b = 0; b < B; ++b) {
         int S = h_cu[b + 1] - h_cu[b], L = h_plens[b];
         TracePlan p = trace_plan(L, S, G, 1 << 30);
         total += (int64_t)Hkv * p.n_qt * p.nc_max;
+        n_tiles += (int64_t)Hkv * p.n_qt;
     }
-    int64_t cpi = (total + g_target_items - 1) / g_target_items;
+    double avg = n_tiles > 0 ? (double)total / (double)n_tiles : 1.0;
+    int64_t slots = g_target_items;
+    int best_s = 1;
+    double best = 1e300;
+    for (int sp = 1; sp <= 4; ++sp) {
+        if (sp > 1 && n_tiles * sp > (2 * n_tiles > 4 * slots ? 2 * n_tiles : 4 * slots)) break;
+        if (sp > 1 && avg / sp < g_min_chunks) break;
+        double rounds = (double)((n_tiles * sp + slots - 1) / slots);
+        double est = rounds * (avg / sp + 1.0) + (sp > 1 ? 2.0 : 0.0);
+        if (est < best) { best = est; best_s = sp; }
+    }
+    int64_t cpi = (int64_t)((avg + best_s - 1) / best_s);
+    if (best_s == 1) cpi = 1 << 30;            // no splitting at all
     if (cpi < g_min_chunks) cpi = g_min_chunks;
-    r.chunks_per_item = (int32_t)cpi;
+    r.chunks_per_item = (int32_t)(cpi > (1 << 30) ? (1 << 30) : cpi);
     r.total_chunks = total;
     for (int b = 0; b < B; ++b) {
         int S = h_cu[b + 1] - h_cu[b], L = h_plens[b];
@@ -167,9 +185,10 @@ hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int 
 }
 
 // ---- the attention kernel ----
-__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnItem *__restrict__ items,
-                                                         const int32_t *__restrict__ counts, int n_items_host,
-                                                         float *__restrict__ part_o, float *__restrict__ part_ml) {
+__global__ __launch_bounds__(ATTN_THREADS, 2) void attn_bf16_kernel(AttnArgs a, const AttnItem *__restrict__ items,
+                                                                  const int32_t *__restrict__ counts, int n_items_host,
+                                                                  float *__restrict__ part_o,
+                                                                  float *__restrict__ part_ml) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
 
@@ -197,12 +216,16 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnIt
     int L = min(max(a.plens[b], 0), a.max_blocks * 16);
     int n_rows = G * S;
 
-    int r = item.row0 + wave * 32 + lq;
+    // Four wavefronts of 32 query rows each.  A wave whose rows all lie past the end of the trace
+    // still loads and synchronises with the others but skips the matrix work.
+    int wave_row0 = item.row0 + wave * 32;
+    bool wave_active = wave_row0 < n_rows;             // wave-uniform
+    int r = wave_row0 + lq;
     bool row_valid = r < n_rows;
     int rc = min(r, n_rows - 1);
     int t = rc / G, g = rc - t * G;
     int limit = L + t;                                          // last visible key of this lane's query
-    int wave_first_limit = L + min(item.row0 + wave * 32, n_rows - 1) / G;
+    int wave_first_limit = L + min(wave_row0, n_rows - 1) / G;
 
     const bf16 *q_row = reinterpret_cast<const bf16 *>(a.q) + ((size_t)(cu_b + t) * a.Hq + c * G + g) * HD;
     bf16x8 qf[8];
@@ -212,9 +235,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnIt
     const bf16 *kp = reinterpret_cast<const bf16 *>(a.k_pages), *vp = reinterpret_cast<const bf16 *>(a.v_pages);
     const bf16 *ks_ = reinterpret_cast<const bf16 *>(a.ksuf), *vs_ = reinterpret_cast<const bf16 *>(a.vsuf);
 
-    // loader roles
+    // Loader roles (every thread stages 4 K vectors and 4 V vectors per chunk).
     // K: load i of a thread takes key slot tid/16 of page i of the chunk, 16-byte vector tid%16.
-    // V: a thread takes keys 4*v_kq..+3 (one page) x hd 8*v_g..+7, to be transposed on the way into LDS.
+    // V: a thread takes keys 4*v_kq..+3 (one page) x hd 8*v_g..+7, transposed on the way into LDS.
     int k_dst[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) k_dst[i] = ((tid >> 4) + 16 * i) * K_STRIDE + (tid & 15) * 8;
@@ -298,7 +321,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnIt
     for (int hb = 0; hb < 4; ++hb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc_o[hb][e] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, m_ref = -INFINITY, l_run = 0.f;   // true max, exponent reference, sum (vs m_ref)
     const float sc = a.scale * 1.44269504088896340736f;   // scores in log2 units
 
     // K operand row (key) for MFMA row lq, see the header comment: pi(m)
@@ -325,63 +348,72 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnIt
         __builtin_amdgcn_sched_barrier(0);
         const __bf16 *base = smem + stage * ATTN_STAGE;
 
-        f32x16 acc_s[2];
+        if (wave_active) {
+            f32x16 acc_s[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc_s[kb][e] = 0.f;
+                for (int e = 0; e < 16; ++e) acc_s[kb][e] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+            for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                bf16x8 kf = *reinterpret_cast<const bf16x8 *>(base + kb * 32 * K_STRIDE + k_frag + ks * 16);
-                acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kb], 0, 0, 0);
-            }
-        // register e of block kb holds key  ch*64 + 32*kb + 16*(e>>3) + 8*half + (e&7)
-        int key0 = ch * ATTN_BN + 8 * half;
-        bool need_mask = ch * ATTN_BN + ATTN_BN - 1 > wave_first_limit;
-        float mloc = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float v = acc_s[kb][e] * sc;
-                if (need_mask) {
-                    int key = key0 + 32 * kb + 16 * (e >> 3) + (e & 7);
-                    if (key > limit) v = -INFINITY;
+                for (int kb = 0; kb < 2; ++kb) {
+                    bf16x8 kf = *reinterpret_cast<const bf16x8 *>(base + kb * 32 * K_STRIDE + k_frag + ks * 16);
+                    acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kb], 0, 0, 0);
                 }
-                acc_s[kb][e] = v;
-                mloc = fmaxf(mloc, v);
+            // register e of block kb holds key  ch*64 + 32*kb + 16*(e>>3) + 8*half + (e&7)
+            if (ch * ATTN_BN + ATTN_BN - 1 > wave_first_limit) {      // wave-uniform: causal mask needed
+                int key0 = ch * ATTN_BN + 8 * half;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (key0 + 32 * kb + 16 * (e >> 3) + (e & 7) > limit) acc_s[kb][e] = -INFINITY;
             }
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-        float m_new = fmaxf(m_run, mloc);
-        float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-        m_run = m_new;
-        float psum = 0.f;
-        bf16x8 pf[2][2];
+            float mloc = -INFINITY;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float p = __builtin_amdgcn_exp2f(acc_s[kb][e] - m_use);
-                psum += p;
-                pf[kb][e >> 3][e & 7] = (__bf16)p;
+                for (int e = 0; e < 16; ++e) mloc = fmaxf(mloc, acc_s[kb][e]);
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+            float m_new = fmaxf(m_run, mloc * sc);     // true running max, log2 units
+            m_run = m_new;
+            // Lazy rescale: the exponent reference m_ref only follows the running max when some query of
+            // the wave has moved more than 8 (a factor 256) above it; until then probabilities may exceed
+            // 1, which bf16 / fp32 hold without loss, and the accumulators need no per-chunk rescale.
+            if (__builtin_amdgcn_ballot_w64(m_new > m_ref + 8.0f) != 0) {
+                float off_old = (m_ref == -INFINITY) ? 0.f : m_ref;
+                float off_new = (m_new == -INFINITY) ? 0.f : m_new;
+                float alpha = __builtin_amdgcn_exp2f(off_old - off_new);
+                m_ref = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int hb = 0; hb < 4; ++hb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc_o[hb][e] *= alpha;
             }
-        l_run = l_run * alpha + psum;
+            float neg_off = (m_ref == -INFINITY) ? 0.f : -m_ref;
+            float psum = 0.f;
+            bf16x8 pf[2][2];
 #pragma unroll
-        for (int hb = 0; hb < 4; ++hb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc_o[hb][e] *= alpha;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-                for (int hb = 0; hb < 4; ++hb) {
-                    bf16x8 vf = *reinterpret_cast<const bf16x8 *>(base + v_frag + hb * 32 * VT_STRIDE + kb * 32 + s2 * 16);
-                    acc_o[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][s2], acc_o[hb], 0, 0, 0);
+                for (int e = 0; e < 16; ++e) {
+                    float p = __builtin_amdgcn_exp2f(fmaf(acc_s[kb][e], sc, neg_off));
+                    psum += p;
+                    pf[kb][e >> 3][e & 7] = (__bf16)p;
                 }
+            l_run += psum;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                    for (int hb = 0; hb < 4; ++hb) {
+                        bf16x8 vf = *reinterpret_cast<const bf16x8 *>(base + v_frag + hb * 32 * VT_STRIDE + kb * 32 + s2 * 16);
+                        acc_o[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][s2], acc_o[hb], 0, 0, 0);
+                    }
+        }
         __builtin_amdgcn_sched_barrier(0);
         if (more) store_chunk(stage ^ 1);
         __syncthreads();
@@ -411,17 +443,19 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, const AttnIt
         }
     } else {
         size_t row_slot = (size_t)item.part_slot * ATTN_BM + wave * 32 + lq;
-        float *po = part_o + row_slot * HD;
+        if (wave_active) {
+            float *po = part_o + row_slot * HD;
 #pragma unroll
-        for (int hb = 0; hb < 4; ++hb)
+            for (int hb = 0; hb < 4; ++hb)
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                float4 v = make_float4(acc_o[hb][q4 * 4], acc_o[hb][q4 * 4 + 1], acc_o[hb][q4 * 4 + 2],
-                                       acc_o[hb][q4 * 4 + 3]);
-                *reinterpret_cast<float4 *>(po + 32 * hb + 8 * q4 + 4 * half) = v;
-            }
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    float4 v = make_float4(acc_o[hb][q4 * 4], acc_o[hb][q4 * 4 + 1], acc_o[hb][q4 * 4 + 2],
+                                           acc_o[hb][q4 * 4 + 3]);
+                    *reinterpret_cast<float4 *>(po + 32 * hb + 8 * q4 + 4 * half) = v;
+                }
+        }
         if (half == 0) {
-            part_ml[row_slot * 2] = m_run;
+            part_ml[row_slot * 2] = wave_active ? m_ref : -INFINITY;
             part_ml[row_slot * 2 + 1] = l_tot;
         }
     }
@@ -441,7 +475,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnT
     int cu_b = min(max(a.cu[b], 0), a.T - 1);
     int S = min(max(a.cu[b + 1] - cu_b, 1), a.T - cu_b);
     int n_rows = G * S;
-    for (int idx = threadIdx.x; idx < ATTN_BM * (HD / 4); idx += 256) {
+    for (int idx = threadIdx.x; idx < ATTN_BM * (HD / 4); idx += blockDim.x) {
         int row = idx >> 5, hv = idx & 31;
         int r = tile.row0 + row;
         if (r >= n_rows) continue;
@@ -486,7 +520,7 @@ hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const Attn
     }
     if (n_items_host <= 0) return hipSuccess;
     int grid = ((n_items_host + 7) / 8) * 8;
-    attn_bf16_kernel<<<grid, 256, ATTN_SMEM_BYTES, s>>>(a, items, counts, n_items_host, part_o, part_ml);
+    attn_bf16_kernel<<<grid, ATTN_THREADS, ATTN_SMEM_BYTES, s>>>(a, items, counts, n_items_host, part_o, part_ml);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     attn_merge_kernel<<<n_tiles_host, 256, 0, s>>>(a, tiles, counts, n_tiles_host, part_o, part_ml);

@@ -1,12 +1,16 @@
 // bf16 x bf16 -> fp32 GEMM on the gfx950 matrix cores: C[M,N] = A[M,K] . W[N,K]^T.
 //
 // Both operands are K-contiguous, which is exactly the per-lane operand shape of
-// v_mfma_f32_32x32x16_bf16 (lane l supplies 8 consecutive k of row/column l%32, k-group l/32), so
-// tiles go global -> registers -> LDS as 16-byte vectors and come back out of LDS as 16-byte MFMA
-// operands with no shuffling.  LDS rows are padded from 128 to 144 bytes so that the 16 lanes of one
-// ds_read_b128 phase hit 16 different 4-bank groups.  Two LDS stages: the global loads of k-tile
-// i+1 are issued before the MFMAs of k-tile i and written to the other stage afterwards, one
-// barrier per k-tile.
+// v_mfma_f32_32x32x16_bf16 (lane l supplies 8 consecutive k of row/column l%32, k-group l/32).
+//
+// Data path.  Operand tiles travel global -> LDS directly (global_load_lds_dwordx4): no staging
+// registers, no ds_write instructions, the wave keeps issuing MFMAs while the data lands.  One such
+// instruction fills 1 KiB of LDS in lane order, i.e. 8 tile rows of 64 k (128 bytes) each.  Rows are
+// unpadded; instead the 16-byte k-vector g of row r is kept at position g ^ ((r >> 1) & 7) of its row
+// (the lane that fills a position fetches the matching global vector), so the 16 lanes of one
+// ds_read_b128 phase - 16 consecutive rows, same k-vector - hit 16 different 4-bank groups.
+// Two LDS stages: the loads of k-tile i+1 are issued right after the barrier that frees their stage
+// and have the whole MFMA phase of k-tile i to complete; one vmcnt wait + barrier per k-tile.
 //
 // Epilogues: plain fp32 store, fp32 residual add in place, or SwiGLU on interleaved gate/up columns
 // with a bf16 result.
@@ -22,27 +26,31 @@ namespace cs {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+#define CS_GLOBAL_AS __attribute__((address_space(1)))
+#define CS_LDS_AS __attribute__((address_space(3)))
 
 constexpr int GEMM_BK = 64;
-constexpr int GEMM_LDS_STRIDE = 72;  // elements per LDS row: 64 + 8 pad (144 bytes)
+constexpr int GEMM_ROW_BYTES = GEMM_BK * 2;   // one tile row in LDS
 
 struct GemmTune {
-    int tile;   // 0 = heuristic, 1 = 128x128, 2 = 256x256, 3 = 256x128
+    int tile;   // 0 = heuristic, 1 = 128x128 (4 waves), 2 = 256x256 (4 waves), 3 = 256x128 (4 waves),
+                // 4 = 256x256 (8 waves), 5 = 128x128 (2 waves)
 };
 static GemmTune g_gemm_tune = {0};
 void gemm_set_tile(int t) { g_gemm_tune.tile = t; }
 
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W,
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W,
                                                          void *__restrict__ out_v, int M, int N, int K,
                                                          int tiles_m, int tiles_n, int a_terms, int out_terms) {
-    constexpr int WM = BM / 2, WN = BN / 2;     // 2 x 2 waves
-    constexpr int MI = WM / 32, NI = WN / 32;   // 32x32 MFMA blocks per wave
-    constexpr int A_VEC = BM / 32, B_VEC = BN / 32;  // 16-byte vectors per thread per k-tile
-    constexpr int STAGE = (BM + BN) * GEMM_LDS_STRIDE;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wave tile
+    constexpr int MI = WM / 32, NI = WN / 32;             // 32x32 MFMA blocks per wave
+    constexpr int A_DMA = BM / (8 * NW), B_DMA = BN / (8 * NW);  // 1 KiB direct loads per wave per k-tile
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && WN % 64 == 0, "tile shape");
+    constexpr int STAGE = (BM + BN) * GEMM_ROW_BYTES;   // bytes
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give each XCD a
     // contiguous range of tiles; inside a range tile_m runs fastest, so neighbours share a W tile.
@@ -55,24 +63,41 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
     int m0 = tm * BM, n0 = tn * BN;
 
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int wy = wave >> 1, wx = wave & 1;
+    int wy = wave / WAVES_N, wx = wave % WAVES_N;
 
-    const u32x4 *a_src[A_VEC];
-    const u32x4 *b_src[B_VEC];
-    int a_dst[A_VEC], b_dst[B_VEC];
+    // Direct-load roles: instruction j of wave w fills rows 8*(w + NW*j) .. +7 of an operand tile; lane
+    // s sits at row s/8, position s%8 and fetches k-vector (s%8) ^ swizzle(row).  A rows past M are
+    // clamped (fetched twice, never stored to the output).
+    const int rl = lane >> 3, ph = lane & 7;
+    const int lda = K * a_terms;
+    const char *a_src[A_DMA], *b_src[B_DMA];
 #pragma unroll
-    for (int i = 0; i < A_VEC; ++i) {
-        int v = tid + 256 * i, r = v >> 3, kv = v & 7;
-        int row = min(m0 + r, M - 1);
-        a_src[i] = reinterpret_cast<const u32x4 *>(A + (size_t)row * K * a_terms + kv * 8);
-        a_dst[i] = r * GEMM_LDS_STRIDE + kv * 8;
+    for (int j = 0; j < A_DMA; ++j) {
+        int row = 8 * (wave + NW * j) + rl;
+        int g = ph ^ ((row >> 1) & 7);
+        a_src[j] = reinterpret_cast<const char *>(A + (size_t)min(m0 + row, M - 1) * lda + g * 8);
     }
 #pragma unroll
-    for (int i = 0; i < B_VEC; ++i) {
-        int v = tid + 256 * i, r = v >> 3, kv = v & 7;
-        b_src[i] = reinterpret_cast<const u32x4 *>(W + (size_t)(n0 + r) * K + kv * 8);
-        b_dst[i] = BM * GEMM_LDS_STRIDE + r * GEMM_LDS_STRIDE + kv * 8;
+    for (int j = 0; j < B_DMA; ++j) {
+        int row = 8 * (wave + NW * j) + rl;
+        int g = ph ^ ((row >> 1) & 7);
+        b_src[j] = reinterpret_cast<const char *>(W + (size_t)(n0 + row) * K + g * 8);
     }
+    int nk_w = K / GEMM_BK;        // k-tiles of W
+    int nk = nk_w * a_terms;       // k-tiles of A: hi half, then lo half
+    auto issue_loads = [&](int stage, int kt) {
+        int kw = kt >= nk_w ? kt - nk_w : kt;     // W wraps around for the lo half
+        unsigned char *base = smem + stage * STAGE;
+#pragma unroll
+        for (int j = 0; j < A_DMA; ++j)
+            __builtin_amdgcn_global_load_lds((const CS_GLOBAL_AS void *)(a_src[j] + (size_t)kt * GEMM_ROW_BYTES),
+                                             (CS_LDS_AS void *)(base + (wave + NW * j) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < B_DMA; ++j)
+            __builtin_amdgcn_global_load_lds((const CS_GLOBAL_AS void *)(b_src[j] + (size_t)kw * GEMM_ROW_BYTES),
+                                             (CS_LDS_AS void *)(base + BM * GEMM_ROW_BYTES + (wave + NW * j) * 1024), 16,
+                                             0, 0);
+    };
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -82,56 +107,40 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    u32x4 a_reg[A_VEC], b_reg[B_VEC];
-    int nk_w = K / GEMM_BK;        // k-tiles of W
-    int nk = nk_w * a_terms;       // k-tiles of A: hi half, then lo half
-    // prologue: k-tile 0 -> stage 0
-#pragma unroll
-    for (int i = 0; i < A_VEC; ++i) a_reg[i] = a_src[i][0];
-#pragma unroll
-    for (int i = 0; i < B_VEC; ++i) b_reg[i] = b_src[i][0];
-#pragma unroll
-    for (int i = 0; i < A_VEC; ++i) *reinterpret_cast<u32x4 *>(smem + a_dst[i]) = a_reg[i];
-#pragma unroll
-    for (int i = 0; i < B_VEC; ++i) *reinterpret_cast<u32x4 *>(smem + b_dst[i]) = b_reg[i];
+    // MFMA operand reads: row (lane % 32) of each 32-row block, k-vector 2 ks + lane / 32
+    const int half = lane >> 5;
+    const int arow = wy * WM + (lane & 31), brow = wx * WN + (lane & 31);
+    const int a_base = arow * GEMM_ROW_BYTES, a_sw = (arow >> 1) & 7;
+    const int b_base = BM * GEMM_ROW_BYTES + brow * GEMM_ROW_BYTES, b_sw = (brow >> 1) & 7;
+
+    issue_loads(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0): the direct loads have been written to LDS
     __syncthreads();
-
-    int a_frag = (wy * WM + (lane & 31)) * GEMM_LDS_STRIDE + (lane >> 5) * 8;
-    int b_frag = BM * GEMM_LDS_STRIDE + (wx * WN + (lane & 31)) * GEMM_LDS_STRIDE + (lane >> 5) * 8;
-
     for (int kt = 0; kt < nk; ++kt) {
-        int cur = (kt & 1) * STAGE, nxt = ((kt + 1) & 1) * STAGE;
-        bool more = kt + 1 < nk;
-        if (more) {
-            int ka = kt + 1, kw = ka >= nk_w ? ka - nk_w : ka;   // W wraps around for the lo half
-            int ko = ka * (GEMM_BK / 8), kwo = kw * (GEMM_BK / 8);  // in u32x4 units
-#pragma unroll
-            for (int i = 0; i < A_VEC; ++i) a_reg[i] = a_src[i][ko];
-#pragma unroll
-            for (int i = 0; i < B_VEC; ++i) b_reg[i] = b_src[i][kwo];
-        }
-#pragma unroll
-        for (int ks = 0; ks < GEMM_BK / 16; ++ks) {
-            bf16x8 af[MI], bfr[NI];
+        const unsigned char *cur = smem + (kt & 1) * STAGE;
+        if (kt + 1 < nk) issue_loads((kt + 1) & 1, kt + 1);
+        bf16x8 af[2][MI], bfr[2][NI];
+        auto read_frags = [&](int buf, int ks) {
+            int ga = ((2 * ks + half) ^ a_sw) * 16, gb = ((2 * ks + half) ^ b_sw) * 16;
 #pragma unroll
             for (int i = 0; i < MI; ++i)
-                af[i] = *reinterpret_cast<const bf16x8 *>(smem + cur + a_frag + i * 32 * GEMM_LDS_STRIDE + ks * 16);
+                af[buf][i] = *reinterpret_cast<const bf16x8 *>(cur + a_base + i * 32 * GEMM_ROW_BYTES + ga);
 #pragma unroll
             for (int j = 0; j < NI; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8 *>(smem + cur + b_frag + j * 32 * GEMM_LDS_STRIDE + ks * 16);
+                bfr[buf][j] = *reinterpret_cast<const bf16x8 *>(cur + b_base + j * 32 * GEMM_ROW_BYTES + gb);
+        };
+        read_frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < GEMM_BK / 16; ++ks) {
+            if (ks + 1 < GEMM_BK / 16) read_frags((ks + 1) & 1, ks + 1);   // next k-step's operands
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
         }
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < A_VEC; ++i) *reinterpret_cast<u32x4 *>(smem + nxt + a_dst[i]) = a_reg[i];
-#pragma unroll
-            for (int i = 0; i < B_VEC; ++i) *reinterpret_cast<u32x4 *>(smem + nxt + b_dst[i]) = b_reg[i];
-        }
-        __syncthreads();
+        __builtin_amdgcn_s_waitcnt(0x0070);   // next tile is in LDS ...
+        __syncthreads();                      // ... for every wave, and this tile's stage is free
     }
 
     // C layout of one 32x32 block: lane holds column lane%32, rows 8*(e/4) + 4*(lane/32) + e%4.
@@ -168,12 +177,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16 *__restrict__
     }
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
 static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
                               int out_terms, hipStream_t s) {
-    constexpr int smem = 2 * (BM + BN) * GEMM_LDS_STRIDE * 2;
+    constexpr int smem = 2 * (BM + BN) * GEMM_ROW_BYTES;
     static bool attr_set = false;
-    auto kern = gemm_bf16_kernel<BM, BN, EPI>;
+    auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -183,7 +192,7 @@ static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, in
     int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
     int n_tiles = tiles_m * tiles_n;
     int grid = ((n_tiles + 7) / 8) * 8;
-    kern<<<grid, 256, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n, a_terms, out_terms);
+    kern<<<grid, 64 * WAVES_M * WAVES_N, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n, a_terms, out_terms);
     return hipGetLastError();
 }
 
@@ -193,11 +202,14 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
     int tile = g_gemm_tune.tile;
     if (tile == 0) {
         long t256 = (long)((M + 255) / 256) * (N / 256);
-        tile = (N % 256 == 0 && t256 >= 192) ? 2 : 1;
+        tile = (N % 256 == 0 && t256 >= 192) ? 4 : 1;
     }
-    if (tile == 2 && N % 256 == 0) return launch_tile<256, 256, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-    if (tile == 3) return launch_tile<256, 128, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-    return launch_tile<128, 128, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+    if ((tile == 2 || tile == 4) && N % 256 != 0) tile = 1;
+    if (tile == 4) return launch_tile<256, 256, 2, 4, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+    if (tile == 2) return launch_tile<256, 256, 2, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+    if (tile == 3) return launch_tile<256, 128, 2, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+    if (tile == 5) return launch_tile<128, 128, 2, 1, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+    return launch_tile<128, 128, 2, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
 }
 
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,

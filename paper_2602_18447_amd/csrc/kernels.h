@@ -28,10 +28,11 @@ struct AttnTile {
     int32_t pad[3];
 };
 
-constexpr int ATTN_BM = 128;      // q rows per tile (bf16 MFMA kernel)
+constexpr int ATTN_BM = 128;      // q rows per tile (bf16 MFMA kernel): 4 wavefronts x 32 rows
+constexpr int ATTN_THREADS = 256;
 constexpr int ATTN_BN = 64;       // keys per chunk
-constexpr int ATTN_TARGET_ITEMS = 1024;
-constexpr int ATTN_MIN_CHUNKS_PER_ITEM = 4;
+constexpr int ATTN_TARGET_ITEMS = 512;
+constexpr int ATTN_MIN_CHUNKS_PER_ITEM = 8;
 
 // Host-side mirror of the planner's counting pass (same arithmetic as the device code).
 struct AttnPlanCounts {
