@@ -65,7 +65,8 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
 /* Process-wide settings.  "split_layers" (default 4): number of leading layers in which
  * confspec_verify carries the GEMM activations as two bf16 terms.  Launch-shape tunables for
  * measurements: "gemm_tile" (0 heuristic, 1 = 128x128, 2 = 256x256, 3 = 256x128),
- * "attn_target_items", "attn_min_chunks".  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a
+ * "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
+ * "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = fixed key-range split factor).  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a
  * value out of range. */
 int confspec_tune(const char *key, int32_t value);
 

@@ -36,6 +36,8 @@ __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; 
 // launch-shape tunables (process-wide)
 static int g_target_items = ATTN_TARGET_ITEMS;
 static int g_min_chunks = ATTN_MIN_CHUNKS_PER_ITEM;
+static int g_force_split = 0;   // 0 = choose by the makespan estimate, 1..4 = fixed split factor
+void attn_set_split(int s) { g_force_split = s; }
 void attn_set_tune(int target_items, int min_chunks) { g_target_items = target_items; g_min_chunks = min_chunks; }
 void attn_get_tune(int *target_items, int *min_chunks) { *target_items = g_target_items; *min_chunks = g_min_chunks; }
 
@@ -65,7 +67,7 @@ void attn_plan_capacity(int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *m
 
 // Split rule.  Every tile's key range is cut into pieces of at most `cpi` chunks.  cpi comes from a
 // uniform split factor s in 1..4 applied to the average tile: the estimated makespan on
-// `g_target_items` concurrent workgroups, ceil(tiles * s / slots) * (avg / s + 1) (+ 2 chunk-times for
+// `g_target_items` concurrent workgroups, ceil(tiles * s / slots) * (avg / s + 1) (+ 4 chunk-times for
 // the merge when s > 1), is minimised; s is limited so that tiles * s <= max(2 * tiles, 4 * slots).
 // Long tiles of a ragged batch then get proportionally more pieces than short ones.
 AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv) {
@@ -85,9 +87,10 @@ AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int
         if (sp > 1 && n_tiles * sp > (2 * n_tiles > 4 * slots ? 2 * n_tiles : 4 * slots)) break;
         if (sp > 1 && avg / sp < g_min_chunks) break;
         double rounds = (double)((n_tiles * sp + slots - 1) / slots);
-        double est = rounds * (avg / sp + 1.0) + (sp > 1 ? 2.0 : 0.0);
+        double est = rounds * (avg / sp + 1.0) + (sp > 1 ? 4.0 : 0.0);
         if (est < best) { best = est; best_s = sp; }
     }
+    if (g_force_split > 0) best_s = g_force_split;
     int64_t cpi = (int64_t)((avg + best_s - 1) / best_s);
     if (best_s == 1) cpi = 1 << 30;            // no splitting at all
     if (cpi < g_min_chunks) cpi = g_min_chunks;
@@ -466,19 +469,23 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnT
                                                           const int32_t *__restrict__ counts, int n_tiles_host,
                                                           const float *__restrict__ part_o,
                                                           const float *__restrict__ part_ml) {
+    // One workgroup merges 8 rows of a tile: thread = (row, 4-float column), so every load of a
+    // split's partial is independent of the others.
+    constexpr int ROWS_PER_WG = 8, WGS_PER_TILE = ATTN_BM / ROWS_PER_WG;
     int n_tiles = min(counts[0], n_tiles_host);
-    if ((int)blockIdx.x >= n_tiles) return;
-    AttnTile tile = tiles[blockIdx.x];
+    int tile_idx = blockIdx.x / WGS_PER_TILE;
+    if (tile_idx >= n_tiles) return;
+    AttnTile tile = tiles[tile_idx];
     if (tile.n_splits <= 1 || tile.part_base < 0) return;
     int G = a.Hq / a.Hkv;
     int b = min(max(tile.b, 0), a.B - 1), c = min(max(tile.c, 0), a.Hkv - 1);
     int cu_b = min(max(a.cu[b], 0), a.T - 1);
     int S = min(max(a.cu[b + 1] - cu_b, 1), a.T - cu_b);
     int n_rows = G * S;
-    for (int idx = threadIdx.x; idx < ATTN_BM * (HD / 4); idx += blockDim.x) {
-        int row = idx >> 5, hv = idx & 31;
+    {
+        int row = (blockIdx.x % WGS_PER_TILE) * ROWS_PER_WG + (threadIdx.x >> 5), hv = threadIdx.x & 31;
         int r = tile.row0 + row;
-        if (r >= n_rows) continue;
+        if (r >= n_rows) return;
         float m_tot = -INFINITY;
         for (int s = 0; s < tile.n_splits; ++s)
             m_tot = fmaxf(m_tot, part_ml[((size_t)(tile.part_base + s) * ATTN_BM + row) * 2]);
@@ -510,7 +517,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnT
 }
 
 hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
-                            int n_items_host, int n_tiles_host, float *part_o, float *part_ml, hipStream_t s) {
+                            int n_items_host, int n_tiles_host, bool any_split, float *part_o, float *part_ml,
+                            hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel),
@@ -523,7 +531,8 @@ hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const Attn
     attn_bf16_kernel<<<grid, ATTN_THREADS, ATTN_SMEM_BYTES, s>>>(a, items, counts, n_items_host, part_o, part_ml);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    attn_merge_kernel<<<n_tiles_host, 256, 0, s>>>(a, tiles, counts, n_tiles_host, part_o, part_ml);
+    if (any_split)
+        attn_merge_kernel<<<n_tiles_host * (ATTN_BM / 8), 256, 0, s>>>(a, tiles, counts, n_tiles_host, part_o, part_ml);
     return hipGetLastError();
 }
 

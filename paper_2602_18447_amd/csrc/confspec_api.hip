@@ -17,6 +17,7 @@ namespace cs {
 void gemm_set_tile(int t);
 void attn_set_tune(int target_items, int min_chunks);
 void attn_get_tune(int *target_items, int *min_chunks);
+void attn_set_split(int s);
 }  // namespace cs
 
 struct confspec_ctx {
@@ -195,7 +196,7 @@ int run_attention(confspec_ctx *ctx, const cs::AttnArgs &a, char *ws, const WsLa
         HIP_TRY(cs::launch_attn_f32(a, (const int32_t *)(ws + L.tok_trace), (const int32_t *)(ws + L.tok_pos), s));
     } else {
         HIP_TRY(cs::launch_attn_bf16(a, (const cs::AttnItem *)(ws + L.plan_items), (const cs::AttnTile *)(ws + L.plan_tiles),
-                                     (const int32_t *)(ws + L.plan_counts), (int)pc.n_items, (int)pc.n_tiles,
+                                     (const int32_t *)(ws + L.plan_counts), (int)pc.n_items, (int)pc.n_tiles, pc.n_part_slots > 0,
                                      (float *)(ws + L.part_o), (float *)(ws + L.part_ml), s));
     }
     return CONFSPEC_OK;
@@ -475,6 +476,9 @@ int confspec_tune(const char *key, int32_t value) {
     } else if (!strcmp(key, "attn_target_items")) {
         if (value < 1 || value > 65536) return CONFSPEC_E_INVALID_ARG;
         cs::attn_set_tune(value, mc);
+    } else if (!strcmp(key, "attn_split")) {
+        if (value < 0 || value > 4) return CONFSPEC_E_INVALID_ARG;
+        cs::attn_set_split(value);
     } else if (!strcmp(key, "attn_min_chunks")) {
         if (value < 1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
         cs::attn_set_tune(ti, value);

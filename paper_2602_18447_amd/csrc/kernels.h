@@ -101,6 +101,7 @@ hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int 
                             int chunks_per_item, int max_tiles, int max_items, AttnTile *tiles, AttnItem *items,
                             int32_t *counts /*[2]: n_tiles, n_items*/, hipStream_t s);
 hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
-                            int n_items_host, int n_tiles_host, float *part_o, float *part_ml, hipStream_t s);
+                            int n_items_host, int n_tiles_host, bool any_split, float *part_o, float *part_ml,
+                            hipStream_t s);
 
 }  // namespace cs
