@@ -41,17 +41,24 @@ int confspec_op_rmsnorm(confspec_ctx *ctx, const float *dev_x, const void *dev_g
                         int32_t n_rows, int32_t out_terms, confspec_stream stream);
 
 /* Rotary embedding + split of a fp32 QKV projection [T, (Hq + 2 Hkv) hd] into q [T,Hq,hd],
- * k [T,Hkv,hd], v [T,Hkv,hd] (context dtype); positions are L_b + t from the batch. */
+ * k [T,Hkv,hd], v [T,Hkv,hd] (context dtype); positions are L_b + t from the batch.
+ * dev_q_lo / dev_k_lo / dev_v_lo (bf16 contexts; all three or none, NULL = none) receive the second
+ * bf16 term bf16(value - bf16(value)) in the same layouts. */
 int confspec_op_rope_split(confspec_ctx *ctx, const confspec_batch *batch, int32_t max_prefix_len,
-                           const float *dev_qkv, void *dev_q, void *dev_k, void *dev_v, void *dev_workspace,
-                           size_t workspace_bytes, confspec_stream stream);
+                           const float *dev_qkv, void *dev_q, void *dev_k, void *dev_v, void *dev_q_lo,
+                           void *dev_k_lo, void *dev_v_lo, void *dev_workspace, size_t workspace_bytes,
+                           confspec_stream stream);
 
 /* Attention of one layer: softmax over keys j <= L_b + t of q . k_j / sqrt(hd), keys and values
  * 0..L_b-1 from the paged cache of `layer`, the rest from dev_k_suffix / dev_v_suffix.
- * q [T,Hq,hd], k/v suffix [T,Hkv,hd], out [T, out_terms*Hq*hd], all in the context's dtype. */
+ * q [T,Hq,hd], k/v suffix [T,Hkv,hd], out [T, out_terms*Hq*hd], all in the context's dtype.
+ * With dev_q_lo / dev_k_lo / dev_v_lo given (bf16 contexts; all three or none) q and the suffix keys /
+ * values are hi + lo two-term values and the kernel also carries its probabilities as two terms;
+ * confspec_verify does this in the first "attn_precise_layers" layers. */
 int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confspec_batch *batch, int32_t layer,
-                          const void *dev_q, const void *dev_k_suffix, const void *dev_v_suffix, void *dev_out,
-                          int32_t out_terms, void *dev_workspace, size_t workspace_bytes, confspec_stream stream);
+                          const void *dev_q, const void *dev_k_suffix, const void *dev_v_suffix, const void *dev_q_lo,
+                          const void *dev_k_lo, const void *dev_v_lo, void *dev_out, int32_t out_terms,
+                          void *dev_workspace, size_t workspace_bytes, confspec_stream stream);
 
 /* Verdict head and gate on a residual stream x fp32 [T, d_model]: for each trace the last suffix
  * row is normalised, dotted with the verdict rows of lm_head, soft-maxed over the verdicts and
@@ -62,8 +69,9 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
                              size_t workspace_bytes, float *dev_verdict_logits, float *dev_conf,
                              int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream);
 
-/* Process-wide settings.  "split_layers" (default 4): number of leading layers in which
- * confspec_verify carries the GEMM activations as two bf16 terms.  Launch-shape tunables for
+/* Process-wide settings.  "split_layers": number of leading layers in which confspec_verify carries
+ * the GEMM activations as two bf16 terms (default -1 = ceil(n_layers / 7), doubled when d_model > 4096).  "attn_precise_layers"
+ * (default 1): number of leading layers whose attention runs the two-term variant.  Launch-shape tunables for
  * measurements: "gemm_tile" (0 heuristic, 1 = 128x128, 2 = 256x256, 3 = 256x128),
  * "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
  * "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = fixed key-range split factor).  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a

@@ -79,9 +79,9 @@ def _load() -> C.CDLL:
     lib.confspec_op_rmsnorm.restype = C.c_int
     lib.confspec_op_rmsnorm.argtypes = [vp, vp, vp, vp, i32, i32, vp]
     lib.confspec_op_rope_split.restype = C.c_int
-    lib.confspec_op_rope_split.argtypes = [vp, P(Batch), i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.confspec_op_rope_split.argtypes = [vp, P(Batch), i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.confspec_op_attention.restype = C.c_int
-    lib.confspec_op_attention.argtypes = [vp, P(KV), P(Batch), i32, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.confspec_op_attention.argtypes = [vp, P(KV), P(Batch), i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.confspec_op_verdict_gate.restype = C.c_int
     lib.confspec_op_verdict_gate.argtypes = [vp, P(Batch), vp, vp, vp, P(i32), i32, P(C.c_float), i32, vp, sz,
                                              vp, vp, vp, vp, vp]
@@ -186,18 +186,20 @@ def confspec_op_rmsnorm(ctx, x, g, out, n_rows: int, out_terms: int = 1, stream=
                                         _stream_handle(stream)))
 
 
-def confspec_op_rope_split(ctx, batch: Batch, max_prefix_len: int, qkv, q, k, v, workspace, stream=None) -> None:
+def confspec_op_rope_split(ctx, batch: Batch, max_prefix_len: int, qkv, q, k, v, workspace, q_lo=None, k_lo=None,
+                           v_lo=None, stream=None) -> None:
     ws_bytes = workspace.numel() * workspace.element_size()
     _check(ctx, lib.confspec_op_rope_split(ctx, C.byref(batch), max_prefix_len, _ptr(qkv), _ptr(q), _ptr(k), _ptr(v),
-                                           _ptr(workspace), ws_bytes, _stream_handle(stream)))
+                                           _ptr(q_lo), _ptr(k_lo), _ptr(v_lo), _ptr(workspace), ws_bytes,
+                                           _stream_handle(stream)))
 
 
 def confspec_op_attention(ctx, kv: KV, batch: Batch, layer: int, q, k_suffix, v_suffix, out, workspace,
-                          out_terms: int = 1, stream=None) -> None:
+                          out_terms: int = 1, q_lo=None, k_lo=None, v_lo=None, stream=None) -> None:
     ws_bytes = workspace.numel() * workspace.element_size()
     _check(ctx, lib.confspec_op_attention(ctx, C.byref(kv), C.byref(batch), layer, _ptr(q), _ptr(k_suffix),
-                                          _ptr(v_suffix), _ptr(out), out_terms, _ptr(workspace), ws_bytes,
-                                          _stream_handle(stream)))
+                                          _ptr(v_suffix), _ptr(q_lo), _ptr(k_lo), _ptr(v_lo), _ptr(out), out_terms,
+                                          _ptr(workspace), ws_bytes, _stream_handle(stream)))
 
 
 def confspec_op_verdict_gate(ctx, batch: Batch, x, final_norm, lm_head, verdict_ids, taus, workspace, logits, conf,

@@ -188,12 +188,18 @@ hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int 
 }
 
 // ---- the attention kernel ----
-__global__ __launch_bounds__(ATTN_THREADS, 2) void attn_bf16_kernel(AttnArgs a, const AttnItem *__restrict__ items,
+// PRECISE: q, the suffix keys / values and the probabilities are each carried as two bf16 terms
+// (hi + lo); products hi*hi, hi*lo and lo*hi are accumulated (lo*lo is below fp32 resolution of the
+// sum).  Cached prefix keys / values are exact bf16 values and need no second term.  Used for the
+// first layer(s), where score noise from rounding q and k is amplified by every later layer.
+template <bool PRECISE>
+__global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kernel(AttnArgs a, const AttnItem *__restrict__ items,
                                                                   const int32_t *__restrict__ counts, int n_items_host,
                                                                   float *__restrict__ part_o,
                                                                   float *__restrict__ part_ml) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
+    constexpr int STAGE = PRECISE ? 2 * ATTN_STAGE : ATTN_STAGE;   // PRECISE: [K | Vt | K_lo | Vt_lo]
 
     int n_items = min(counts[1], n_items_host);
     int per = gridDim.x >> 3;  // grid is a multiple of 8: one contiguous item range per XCD
@@ -234,6 +240,12 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_bf16_kernel(AttnArgs a, 
     bf16x8 qf[8];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(q_row + ks * 16 + half * 8);
+    bf16x8 qf_lo[PRECISE ? 8 : 1];
+    if constexpr (PRECISE) {
+        const bf16 *ql_row = reinterpret_cast<const bf16 *>(a.q_lo) + ((size_t)(cu_b + t) * a.Hq + c * G + g) * HD;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf_lo[ks] = *reinterpret_cast<const bf16x8 *>(ql_row + ks * 16 + half * 8);
+    }
 
     const bf16 *kp = reinterpret_cast<const bf16 *>(a.k_pages), *vp = reinterpret_cast<const bf16 *>(a.v_pages);
     const bf16 *ks_ = reinterpret_cast<const bf16 *>(a.ksuf), *vs_ = reinterpret_cast<const bf16 *>(a.vsuf);
@@ -278,6 +290,15 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_bf16_kernel(AttnArgs a, 
     };
 
     u32x4 k_reg[4], v_reg[4];
+    u32x4 kl_reg[PRECISE ? 4 : 1], vl_reg[PRECISE ? 4 : 1];
+    const bf16 *ksl_ = reinterpret_cast<const bf16 *>(a.ksuf_lo), *vsl_ = reinterpret_cast<const bf16 *>(a.vsuf_lo);
+    // lo term of key / value row j: zero for cached rows, the lo plane of the suffix otherwise
+    auto load_lo = [&](const bf16 *suf_lo, int j, int vec_off) -> u32x4 {
+        u32x4 z = {0u, 0u, 0u, 0u};
+        if (j < L) return z;
+        int ts = min(j - L, S - 1);
+        return *reinterpret_cast<const u32x4 *>(suf_lo + ((size_t)(cu_b + ts) * a.Hkv + c) * HD + vec_off);
+    };
     auto load_chunk = [&](int ch) {
         int j0 = ch * ATTN_BN;
         if (j0 + ATTN_BN <= L) {          // uniform: the whole chunk lies in the cached prefix
@@ -300,22 +321,36 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_bf16_kernel(AttnArgs a, 
                 k_reg[i] = *reinterpret_cast<const u32x4 *>(kr[i]);
                 v_reg[i] = *reinterpret_cast<const u32x4 *>(vr[i]);
             }
+            if constexpr (PRECISE) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    kl_reg[i] = load_lo(ksl_, j0 + (tid >> 4) + 16 * i, (tid & 15) * 8);
+                    vl_reg[i] = load_lo(vsl_, j0 + 4 * v_kq + i, v_g * 8);
+                }
+            }
         }
     };
-    auto store_chunk = [&](int stage) {
-        __bf16 *base = smem + stage * ATTN_STAGE;
+    auto store_tiles = [&](__bf16 *base, const u32x4 (&kr)[4], const u32x4 (&vr)[4]) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(base + k_dst[i]) = k_reg[i];
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(base + k_dst[i]) = kr[i];
         // 4 keys x 8 hd  ->  8 rows of 4 keys
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             uint2 lo, hi;
-            lo.x = (v_reg[0][d] & 0xffffu) | (v_reg[1][d] << 16);
-            lo.y = (v_reg[2][d] & 0xffffu) | (v_reg[3][d] << 16);
-            hi.x = (v_reg[0][d] >> 16) | (v_reg[1][d] & 0xffff0000u);
-            hi.y = (v_reg[2][d] >> 16) | (v_reg[3][d] & 0xffff0000u);
+            lo.x = (vr[0][d] & 0xffffu) | (vr[1][d] << 16);
+            lo.y = (vr[2][d] & 0xffffu) | (vr[3][d] << 16);
+            hi.x = (vr[0][d] >> 16) | (vr[1][d] & 0xffff0000u);
+            hi.y = (vr[2][d] >> 16) | (vr[3][d] & 0xffff0000u);
             *reinterpret_cast<uint2 *>(base + v_dst + (2 * d) * VT_STRIDE) = lo;
             *reinterpret_cast<uint2 *>(base + v_dst + (2 * d + 1) * VT_STRIDE) = hi;
+        }
+    };
+    // ch: the chunk held in the registers (its lo tiles exist only if it touches the suffix)
+    auto store_chunk = [&](int stage, int ch) {
+        __bf16 *base = smem + stage * STAGE;
+        store_tiles(base, k_reg, v_reg);
+        if constexpr (PRECISE) {
+            if (ch * ATTN_BN + ATTN_BN > L) store_tiles(base + ATTN_STAGE, kl_reg, vl_reg);
         }
     };
 
@@ -337,7 +372,7 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_bf16_kernel(AttnArgs a, 
     bcast_ids();
     load_chunk(ch0);
     fetch_ids(ch0 + 1);
-    store_chunk(0);      // waits for every load issued so far, the Q fragments included
+    store_chunk(0, ch0);      // waits for every load issued so far, the Q fragments included
     __syncthreads();
     for (int ch = ch0; ch < ch1; ++ch) {
         int stage = (ch - ch0) & 1;
@@ -349,7 +384,8 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_bf16_kernel(AttnArgs a, 
         }
         // keep the consumers of these loads (the LDS stores below) behind the MFMA work of this chunk
         __builtin_amdgcn_sched_barrier(0);
-        const __bf16 *base = smem + stage * ATTN_STAGE;
+        const __bf16 *base = smem + stage * STAGE;
+        const bool has_lo = PRECISE && (ch * ATTN_BN + ATTN_BN > L);   // uniform
 
         if (wave_active) {
             f32x16 acc_s[2];
@@ -363,7 +399,18 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_bf16_kernel(AttnArgs a, 
                 for (int kb = 0; kb < 2; ++kb) {
                     bf16x8 kf = *reinterpret_cast<const bf16x8 *>(base + kb * 32 * K_STRIDE + k_frag + ks * 16);
                     acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kb], 0, 0, 0);
+                    if constexpr (PRECISE)
+                        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf_lo[ks], acc_s[kb], 0, 0, 0);
                 }
+            if (has_lo) {
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb) {
+                        bf16x8 kf = *reinterpret_cast<const bf16x8 *>(base + ATTN_STAGE + kb * 32 * K_STRIDE + k_frag + ks * 16);
+                        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kb], 0, 0, 0);
+                    }
+            }
             // register e of block kb holds key  ch*64 + 32*kb + 16*(e>>3) + 8*half + (e&7)
             if (ch * ATTN_BN + ATTN_BN - 1 > wave_first_limit) {      // wave-uniform: causal mask needed
                 int key0 = ch * ATTN_BN + 8 * half;
@@ -398,13 +445,16 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_bf16_kernel(AttnArgs a, 
             float neg_off = (m_ref == -INFINITY) ? 0.f : -m_ref;
             float psum = 0.f;
             bf16x8 pf[2][2];
+            bf16x8 pf_lo[PRECISE ? 2 : 1][2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     float p = __builtin_amdgcn_exp2f(fmaf(acc_s[kb][e], sc, neg_off));
                     psum += p;
-                    pf[kb][e >> 3][e & 7] = (__bf16)p;
+                    __bf16 ph = (__bf16)p;
+                    pf[kb][e >> 3][e & 7] = ph;
+                    if constexpr (PRECISE) pf_lo[kb][e >> 3][e & 7] = (__bf16)(p - (float)ph);
                 }
             l_run += psum;
 #pragma unroll
@@ -415,10 +465,23 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_bf16_kernel(AttnArgs a, 
                     for (int hb = 0; hb < 4; ++hb) {
                         bf16x8 vf = *reinterpret_cast<const bf16x8 *>(base + v_frag + hb * 32 * VT_STRIDE + kb * 32 + s2 * 16);
                         acc_o[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][s2], acc_o[hb], 0, 0, 0);
+                        if constexpr (PRECISE)
+                            acc_o[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo[kb][s2], acc_o[hb], 0, 0, 0);
                     }
+            if (has_lo) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                        for (int hb = 0; hb < 4; ++hb) {
+                            bf16x8 vf = *reinterpret_cast<const bf16x8 *>(base + ATTN_STAGE + v_frag + hb * 32 * VT_STRIDE + kb * 32 + s2 * 16);
+                            acc_o[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][s2], acc_o[hb], 0, 0, 0);
+                        }
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (more) store_chunk(stage ^ 1);
+        if (more) store_chunk(stage ^ 1, ch + 1);
         __syncthreads();
     }
 
@@ -516,20 +579,29 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnT
     }
 }
 
-hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
-                            int n_items_host, int n_tiles_host, bool any_split, float *part_o, float *part_ml,
-                            hipStream_t s) {
+template <bool PRECISE>
+static hipError_t launch_attn_variant(const AttnArgs &a, const AttnItem *items, const int32_t *counts, int n_items_host,
+                                      float *part_o, float *part_ml, hipStream_t s) {
+    constexpr int smem = PRECISE ? 2 * ATTN_SMEM_BYTES : ATTN_SMEM_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_SMEM_BYTES);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel<PRECISE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    if (n_items_host <= 0) return hipSuccess;
     int grid = ((n_items_host + 7) / 8) * 8;
-    attn_bf16_kernel<<<grid, ATTN_THREADS, ATTN_SMEM_BYTES, s>>>(a, items, counts, n_items_host, part_o, part_ml);
-    hipError_t e = hipGetLastError();
+    attn_bf16_kernel<PRECISE><<<grid, ATTN_THREADS, smem, s>>>(a, items, counts, n_items_host, part_o, part_ml);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
+                            int n_items_host, int n_tiles_host, bool any_split, float *part_o, float *part_ml,
+                            hipStream_t s) {
+    if (n_items_host <= 0) return hipSuccess;
+    bool precise = a.q_lo && a.ksuf_lo && a.vsuf_lo;
+    hipError_t e = precise ? launch_attn_variant<true>(a, items, counts, n_items_host, part_o, part_ml, s)
+                           : launch_attn_variant<false>(a, items, counts, n_items_host, part_o, part_ml, s);
     if (e != hipSuccess) return e;
     if (any_split)
         attn_merge_kernel<<<n_tiles_host * (ATTN_BM / 8), 256, 0, s>>>(a, tiles, counts, n_tiles_host, part_o, part_ml);

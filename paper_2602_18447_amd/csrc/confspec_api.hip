@@ -26,8 +26,18 @@ struct confspec_ctx {
     std::string err;
 };
 
-// Number of leading layers whose GEMM activations are carried as two bf16 terms (process-wide).
-static int g_split_layers = 4;
+// Number of leading layers whose GEMM activations are carried as two bf16 terms (process-wide);
+// -1 = derive from the model: ceil(n_layers / 7), doubled for d_model > 4096 (the logit scale, and
+// with it the absolute effect of a relative rounding error, grows with the width).
+static int g_split_layers = -1;
+// Number of leading layers whose attention runs the two-term variant (q, suffix k / v, probabilities).
+static int g_attn_precise_layers = 1;
+
+static int split_layers_for(const confspec_model_cfg &c) {
+    if (g_split_layers >= 0) return g_split_layers;
+    int depth = (c.n_layers + 6) / 7;
+    return c.d_model > 4096 ? 2 * depth : depth;
+}
 
 namespace {
 
@@ -47,7 +57,7 @@ size_t elem_bytes(int dtype) { return dtype == CONFSPEC_DTYPE_FP32 ? 4 : 2; }
 
 // Workspace layout for a batch of at most T tokens and B traces.
 struct WsLayout {
-    size_t tok_trace, tok_pos, last_row, rope_cos, rope_sin, x, h, qkv, q, ksuf, vsuf, attn, act;
+    size_t tok_trace, tok_pos, last_row, rope_cos, rope_sin, x, h, qkv, q, ksuf, vsuf, q_lo, ksuf_lo, vsuf_lo, attn, act;
     size_t plan_counts, plan_tiles, plan_items, part_o, part_ml;
     size_t total;
     int64_t max_tiles, max_items;
@@ -75,6 +85,11 @@ WsLayout ws_layout(const confspec_model_cfg &c, int64_t T, int64_t B) {
     w.q = take((size_t)T * qw * eb);
     w.ksuf = take((size_t)T * kw * eb);
     w.vsuf = take((size_t)T * kw * eb);
+    if (c.dtype == CONFSPEC_DTYPE_BF16) {   // second terms for the two-term attention variant
+        w.q_lo = take((size_t)T * qw * eb);
+        w.ksuf_lo = take((size_t)T * kw * eb);
+        w.vsuf_lo = take((size_t)T * kw * eb);
+    }
     w.attn = take((size_t)T * qw * eb * terms);
     w.act = take((size_t)T * c.d_ffn * eb * terms);
     if (c.dtype == CONFSPEC_DTYPE_BF16) {
@@ -172,11 +187,13 @@ int run_gemm(confspec_ctx *ctx, const void *A, const void *W, void *out, int M, 
 }
 
 cs::AttnArgs make_attn_args(const confspec_model_cfg &c, const confspec_kv *kv, const confspec_batch *b, int layer,
-                            const void *q, const void *ksuf, const void *vsuf, void *out, int out_terms) {
+                            const void *q, const void *ksuf, const void *vsuf, const void *q_lo, const void *ksuf_lo,
+                            const void *vsuf_lo, void *out, int out_terms) {
     cs::AttnArgs a = {};
     size_t layer_elems = (size_t)kv->n_blocks * c.n_kv_heads * kv->block_size * c.head_dim;
     size_t off = layer_elems * layer * elem_bytes(c.dtype);
     a.q = q; a.ksuf = ksuf; a.vsuf = vsuf; a.out = out;
+    a.q_lo = q_lo; a.ksuf_lo = ksuf_lo; a.vsuf_lo = vsuf_lo;
     a.k_pages = kv->k_pages ? (const char *)kv->k_pages + off : nullptr;
     a.v_pages = kv->v_pages ? (const char *)kv->v_pages + off : nullptr;
     a.block_table = kv->block_table;
@@ -342,12 +359,16 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
     HIP_TRY(cs::launch_embed(c.dtype, batch->suffix_ids, w->embed, x, T, d, c.vocab, s));
     for (int l = 0; l < c.n_layers; ++l) {
         // The first layers' GEMM activations travel as two bf16 terms (see gemm_bf16.hip).
-        int tm = (c.dtype == CONFSPEC_DTYPE_BF16 && l < g_split_layers) ? 2 : 1;
+        int tm = (c.dtype == CONFSPEC_DTYPE_BF16 && l < split_layers_for(c)) ? 2 : 1;
+        bool prec = c.dtype == CONFSPEC_DTYPE_BF16 && l < g_attn_precise_layers;
         HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, tm, s));
         if ((rc = run_gemm(ctx, h, w->wqkv[l], qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, tm, 1, s))) return rc;
         HIP_TRY(cs::launch_rope_split(c.dtype, qkv, (const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin),
-                                      ws + L.q, ws + L.ksuf, ws + L.vsuf, T, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
-        cs::AttnArgs a = make_attn_args(c, kv, batch, l, ws + L.q, ws + L.ksuf, ws + L.vsuf, ws + L.attn, tm);
+                                      ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
+                                      prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, T, c.n_q_heads,
+                                      c.n_kv_heads, c.head_dim, s));
+        cs::AttnArgs a = make_attn_args(c, kv, batch, l, ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
+                                        prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, ws + L.attn, tm);
         if ((rc = run_attention(ctx, a, ws, L, pc, s))) return rc;
         if ((rc = run_gemm(ctx, ws + L.attn, w->wo[l], x, T, d, qw, cs::EPI_RESID_F32, tm, 1, s))) return rc;
         HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->mlp_norm[l], h, T, d, c.rms_eps, tm, s));
@@ -395,11 +416,21 @@ int confspec_op_rmsnorm(confspec_ctx *ctx, const float *dev_x, const void *dev_g
     return CONFSPEC_OK;
 }
 
+static int check_lo(confspec_ctx *ctx, const void *a, const void *b, const void *c3) {
+    int n = (a != nullptr) + (b != nullptr) + (c3 != nullptr);
+    if (n != 0 && n != 3) return fail(ctx, CONFSPEC_E_INVALID_ARG, "second-term pointers must be all set or all null");
+    if (n == 3 && ctx->cfg.dtype != CONFSPEC_DTYPE_BF16)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "second-term operands need a bf16 context");
+    return CONFSPEC_OK;
+}
+
 int confspec_op_rope_split(confspec_ctx *ctx, const confspec_batch *batch, int32_t max_prefix_len,
-                           const float *dev_qkv, void *dev_q, void *dev_k, void *dev_v, void *dev_workspace,
-                           size_t workspace_bytes, confspec_stream stream) {
+                           const float *dev_qkv, void *dev_q, void *dev_k, void *dev_v, void *dev_q_lo,
+                           void *dev_k_lo, void *dev_v_lo, void *dev_workspace, size_t workspace_bytes,
+                           confspec_stream stream) {
     if (!ctx) return CONFSPEC_E_INVALID_ARG;
     if (!dev_qkv || !dev_q || !dev_k || !dev_v) return fail(ctx, CONFSPEC_E_INVALID_ARG, "null operand");
+    if (int rl = check_lo(ctx, dev_q_lo, dev_k_lo, dev_v_lo)) return rl;
     int rc, max_L = 0;
     if ((rc = check_batch(ctx, batch, max_prefix_len, &max_L)) != CONFSPEC_OK) return rc;
     const confspec_model_cfg &c = ctx->cfg;
@@ -412,14 +443,17 @@ int confspec_op_rope_split(confspec_ctx *ctx, const confspec_batch *batch, int32
     HIP_TRY(cs::launch_rope_table((const int32_t *)(ws + L.tok_pos), batch->T, c.head_dim, c.rope_theta,
                                   (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
     HIP_TRY(cs::launch_rope_split(c.dtype, dev_qkv, (const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin),
-                                  dev_q, dev_k, dev_v, batch->T, c.n_q_heads, c.n_kv_heads, c.head_dim, s));
+                                  dev_q, dev_k, dev_v, dev_q_lo, dev_k_lo, dev_v_lo, batch->T, c.n_q_heads, c.n_kv_heads,
+                                  c.head_dim, s));
     return CONFSPEC_OK;
 }
 
 int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confspec_batch *batch, int32_t layer,
-                          const void *dev_q, const void *dev_k_suffix, const void *dev_v_suffix, void *dev_out,
-                          int32_t out_terms, void *dev_workspace, size_t workspace_bytes, confspec_stream stream) {
+                          const void *dev_q, const void *dev_k_suffix, const void *dev_v_suffix, const void *dev_q_lo,
+                          const void *dev_k_lo, const void *dev_v_lo, void *dev_out, int32_t out_terms,
+                          void *dev_workspace, size_t workspace_bytes, confspec_stream stream) {
     if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (int rl = check_lo(ctx, dev_q_lo, dev_k_lo, dev_v_lo)) return rl;
     if (int rt = check_terms(ctx, out_terms, "out_terms")) return rt;
     if (!dev_q || !dev_k_suffix || !dev_v_suffix || !dev_out) return fail(ctx, CONFSPEC_E_INVALID_ARG, "null operand");
     if (!kv) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv is null");
@@ -434,7 +468,8 @@ int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confsp
     hipStream_t s = (hipStream_t)stream;
     cs::AttnPlanCounts pc;
     if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
-    cs::AttnArgs a = make_attn_args(ctx->cfg, kv, batch, layer, dev_q, dev_k_suffix, dev_v_suffix, dev_out, out_terms);
+    cs::AttnArgs a = make_attn_args(ctx->cfg, kv, batch, layer, dev_q, dev_k_suffix, dev_v_suffix, dev_q_lo, dev_k_lo,
+                                    dev_v_lo, dev_out, out_terms);
     return run_attention(ctx, a, ws, L, pc, s);
 }
 
@@ -471,8 +506,11 @@ int confspec_tune(const char *key, int32_t value) {
         if (value < 0 || value > 5) return CONFSPEC_E_INVALID_ARG;
         cs::gemm_set_tile(value);
     } else if (!strcmp(key, "split_layers")) {
-        if (value < 0 || value > 4096) return CONFSPEC_E_INVALID_ARG;
+        if (value < -1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
         g_split_layers = value;
+    } else if (!strcmp(key, "attn_precise_layers")) {
+        if (value < 0 || value > 4096) return CONFSPEC_E_INVALID_ARG;
+        g_attn_precise_layers = value;
     } else if (!strcmp(key, "attn_target_items")) {
         if (value < 1 || value > 65536) return CONFSPEC_E_INVALID_ARG;
         cs::attn_set_tune(value, mc);

@@ -56,8 +56,10 @@ hipError_t launch_embed(int dtype, const int32_t *ids, const void *E, float *x, 
 hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, int T, int d, float eps,
                           int terms, hipStream_t s);
 // qkv fp32 [T, (Hq+2Hkv) hd] -> q [T,Hq,hd], ksuf [T,Hkv,hd], vsuf [T,Hkv,hd] (storage dtype), q and k rotated
+// q_lo / k_lo / v_lo (bf16 only, all or none): receive bf16(value - bf16(value))
 hipError_t launch_rope_split(int dtype, const float *qkv, const float *cos_t, const float *sin_t, void *q,
-                             void *ksuf, void *vsuf, int T, int Hq, int Hkv, int hd, hipStream_t s);
+                             void *ksuf, void *vsuf, void *q_lo, void *k_lo, void *v_lo, int T, int Hq, int Hkv,
+                             int hd, hipStream_t s);
 hipError_t launch_pack_gate_up(int dtype, const void *src, void *dst, int F, int d, hipStream_t s);
 
 struct VerdictArgs {
@@ -85,6 +87,9 @@ struct AttnArgs {
     const void *q;          // [T, Hq, hd]
     const void *ksuf;       // [T, Hkv, hd] suffix keys (rotated)
     const void *vsuf;       // [T, Hkv, hd]
+    const void *q_lo;       // second bf16 terms of q / ksuf / vsuf (same layouts), or nullptr: when all
+    const void *ksuf_lo;    // three are given the bf16 kernel runs its two-term variant (q, suffix k/v
+    const void *vsuf_lo;    // and the probabilities each carried as hi + lo)
     const void *k_pages;    // this layer's pages [n_blocks, Hkv, bs, hd]
     const void *v_pages;
     const int32_t *block_table;  // [B, max_blocks]

@@ -138,7 +138,8 @@ hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, i
 template <typename T>
 __global__ void rope_split_kernel(const float *__restrict__ qkv, const float *__restrict__ cos_t,
                                   const float *__restrict__ sin_t, T *__restrict__ q, T *__restrict__ ksuf,
-                                  T *__restrict__ vsuf, int n_tok, int Hq, int Hkv, int hd) {
+                                  T *__restrict__ vsuf, T *__restrict__ q_lo, T *__restrict__ k_lo,
+                                  T *__restrict__ v_lo, int n_tok, int Hq, int Hkv, int hd) {
     int half = hd >> 1;
     int heads = Hq + 2 * Hkv;
     long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -149,10 +150,17 @@ __global__ void rope_split_kernel(const float *__restrict__ qkv, const float *__
     int t = (int)(idx / ((long)half * heads));
     const float *src = qkv + ((size_t)t * heads + h) * hd;
     float lo = src[i], hi = src[i + half];
-    T *dst;
-    if (h < Hq) dst = q + ((size_t)t * Hq + h) * hd;
-    else if (h < Hq + Hkv) dst = ksuf + ((size_t)t * Hkv + (h - Hq)) * hd;
-    else dst = vsuf + ((size_t)t * Hkv + (h - Hq - Hkv)) * hd;
+    T *dst, *dst_lo;
+    if (h < Hq) {
+        size_t o = ((size_t)t * Hq + h) * hd;
+        dst = q + o; dst_lo = q_lo ? q_lo + o : nullptr;
+    } else if (h < Hq + Hkv) {
+        size_t o = ((size_t)t * Hkv + (h - Hq)) * hd;
+        dst = ksuf + o; dst_lo = k_lo ? k_lo + o : nullptr;
+    } else {
+        size_t o = ((size_t)t * Hkv + (h - Hq - Hkv)) * hd;
+        dst = vsuf + o; dst_lo = v_lo ? v_lo + o : nullptr;
+    }
     if (h < Hq + Hkv) {
         float c = cos_t[(size_t)t * half + i], sn = sin_t[(size_t)t * half + i];
         float a = lo * c - hi * sn;
@@ -160,20 +168,26 @@ __global__ void rope_split_kernel(const float *__restrict__ qkv, const float *__
         lo = a;
         hi = b;
     }
-    dst[i] = from_f32<T>(lo);
-    dst[i + half] = from_f32<T>(hi);
+    T r0 = from_f32<T>(lo), r1 = from_f32<T>(hi);
+    dst[i] = r0;
+    dst[i + half] = r1;
+    if (dst_lo) {
+        dst_lo[i] = from_f32<T>(lo - to_f32<T>(r0));
+        dst_lo[i + half] = from_f32<T>(hi - to_f32<T>(r1));
+    }
 }
 
 hipError_t launch_rope_split(int dtype, const float *qkv, const float *cos_t, const float *sin_t, void *q,
-                             void *ksuf, void *vsuf, int T, int Hq, int Hkv, int hd, hipStream_t s) {
+                             void *ksuf, void *vsuf, void *q_lo, void *k_lo, void *v_lo, int T, int Hq, int Hkv,
+                             int hd, hipStream_t s) {
     long total = (long)T * (Hq + 2 * Hkv) * (hd / 2);
     int blocks = (int)((total + 255) / 256);
     if (dtype == 0)
         rope_split_kernel<float><<<blocks, 256, 0, s>>>(qkv, cos_t, sin_t, (float *)q, (float *)ksuf, (float *)vsuf,
-                                                        T, Hq, Hkv, hd);
+                                                        nullptr, nullptr, nullptr, T, Hq, Hkv, hd);
     else
-        rope_split_kernel<bf16><<<blocks, 256, 0, s>>>(qkv, cos_t, sin_t, (bf16 *)q, (bf16 *)ksuf, (bf16 *)vsuf, T,
-                                                       Hq, Hkv, hd);
+        rope_split_kernel<bf16><<<blocks, 256, 0, s>>>(qkv, cos_t, sin_t, (bf16 *)q, (bf16 *)ksuf, (bf16 *)vsuf,
+                                                       (bf16 *)q_lo, (bf16 *)k_lo, (bf16 *)v_lo, T, Hq, Hkv, hd);
     return hipGetLastError();
 }
 

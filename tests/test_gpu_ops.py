@@ -207,7 +207,8 @@ def test_rope_split_positions_reach_tens_of_thousands(dtype):
     cb.confspec_destroy(ctx)
 
 
-def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16, seed=20, out_terms=1):
+def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16, seed=20, out_terms=1,
+                    precise=False):
     wl = W.tiny_workload("attn", seed, dtype=dtype, n_layers=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd,
                          d_model=256, prefix_lens=prefix_lens, suffix_lens=suffix_lens, block_size=block_size)
     m = wl.model
@@ -216,15 +217,27 @@ def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16,
     kv = W.make_seeded_kv(wl, batch, DEV)
     td = W.torch_dtype(dtype)
     T = wl.T
-    q = _rand((T, hq, hd), td, seed + 1)
-    ks = _rand((T, hkv, hd), td, seed + 2, 0.5)
-    vs = _rand((T, hkv, hd), td, seed + 3, 0.5)
+    lo = {}
+    if precise:     # two-term operands: hi = bf16(x), lo = bf16(x - hi); the oracle sees hi + lo
+        full = dict(q=_rand((T, hq, hd), torch.float32, seed + 1), k=_rand((T, hkv, hd), torch.float32, seed + 2, 0.5),
+                    v=_rand((T, hkv, hd), torch.float32, seed + 3, 0.5))
+        hi = {n: x.to(td) for n, x in full.items()}
+        lo = {n: (full[n] - hi[n].float()).to(td) for n in full}
+        q, ks, vs = hi["q"], hi["k"], hi["v"]
+    else:
+        q = _rand((T, hq, hd), td, seed + 1)
+        ks = _rand((T, hkv, hd), td, seed + 2, 0.5)
+        vs = _rand((T, hkv, hd), td, seed + 3, 0.5)
     out = torch.zeros((T, out_terms * hq * hd), dtype=td, device=DEV)
     kvs = cb.make_kv(kv.k_pages, kv.v_pages, batch.block_table, batch.n_blocks, block_size, batch.max_blocks_per_seq)
     bs, keep = _batch_structs(wl, batch)
     ws = torch.empty(cb.confspec_workspace_bytes(ctx, T, wl.B), dtype=torch.uint8, device=DEV)
     layer = 1
-    cb.confspec_op_attention(ctx, kvs, bs, layer, q, ks, vs, out, ws, out_terms=out_terms)
+    cb.confspec_op_attention(ctx, kvs, bs, layer, q, ks, vs, out, ws, out_terms=out_terms, q_lo=lo.get("q"),
+                             k_lo=lo.get("k"), v_lo=lo.get("v"))
+    qo = f64(q) + (f64(lo["q"]) if precise else 0.0)
+    ko = f64(ks) + (f64(lo["k"]) if precise else 0.0)
+    vo = f64(vs) + (f64(lo["v"]) if precise else 0.0)
     torch.cuda.synchronize()
     view = W.OracleKVView(kv, batch)
     got = f64(out)
@@ -233,7 +246,7 @@ def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16,
     got = got.reshape(T, hq, hd)
     worst = 0.0
     for b, (L, S) in enumerate(zip(prefix_lens, suffix_lens)):
-        lo = int(batch.h_cu_suffix[b])
+        lo0 = int(batch.h_cu_suffix[b])
         nblk = (L + block_size - 1) // block_size
         ids = batch.block_table[b, :nblk].cpu().numpy()
         if L:
@@ -241,10 +254,10 @@ def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16,
             vp = O.gather_prefix(view.v_blocks(layer, ids), L)
         else:
             kp = vp = np.zeros((0, hkv, hd))
-        k_all = np.concatenate([kp, f64(ks[lo:lo + S])])
-        v_all = np.concatenate([vp, f64(vs[lo:lo + S])])
-        ref = O.attention(f64(q[lo:lo + S]), k_all, v_all, L)
-        worst = max(worst, np.abs(got[lo:lo + S] - ref).max())
+        k_all = np.concatenate([kp, ko[lo0:lo0 + S]])
+        v_all = np.concatenate([vp, vo[lo0:lo0 + S]])
+        ref = O.attention(qo[lo0:lo0 + S], k_all, v_all, L)
+        worst = max(worst, np.abs(got[lo0:lo0 + S] - ref).max())
     cb.confspec_destroy(ctx)
     return worst
 
@@ -281,6 +294,18 @@ def test_attention_bf16_two_term_output():
     two = _attention_case("bf16", 12, 2, 128, (300, 17), (96, 130), out_terms=2)
     print("  plain", plain, "two-term", two, flush=True)
     assert two <= plain and two <= 6e-3
+
+
+@pytest.mark.parametrize("prefix_lens,suffix_lens", [((300, 17, 0), (96, 130, 5)), ((64, 2049), (64, 33))])
+def test_attention_bf16_two_term_operands(prefix_lens, suffix_lens):
+    """q, suffix k / v and the probabilities as hi + lo pairs: the result must track the fp64 attention
+    of the 16-bit-mantissa operands far more closely than a single bf16 rounding allows."""
+    print(f"attention bf16 precise L={prefix_lens} S={suffix_lens}", flush=True)
+    err = _attention_case("bf16", 12, 2, 128, prefix_lens, suffix_lens, out_terms=2, precise=True)
+    print("  max abs err", err, flush=True)
+    assert err <= 2e-4
+    err5 = _attention_case("bf16", 5, 1, 128, prefix_lens, suffix_lens, out_terms=2, precise=True)
+    assert err5 <= 2e-4
 
 
 def test_attention_bf16_split_kv_merge_matches_unsplit():
