@@ -72,7 +72,7 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
 /* Process-wide settings.  "split_layers": number of leading layers in which confspec_verify carries
  * the GEMM activations as two bf16 terms (default -1 = ceil(n_layers / 7), doubled when d_model > 4096).  "attn_precise_layers"
  * (default 1): number of leading layers whose attention runs the two-term variant.  Launch-shape tunables for
- * measurements: "gemm_tile" (0 heuristic, 1 = 128x128, 2 = 256x256, 3 = 256x128),
+ * measurements: "gemm_tile" (0 heuristic, 1..8 = fixed workgroup tile / pipeline shape of the bf16 GEMM),
  * "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
  * "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = fixed key-range split factor).  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a
  * value out of range. */

@@ -503,7 +503,7 @@ int confspec_tune(const char *key, int32_t value) {
     int ti, mc;
     cs::attn_get_tune(&ti, &mc);
     if (!strcmp(key, "gemm_tile")) {
-        if (value < 0 || value > 5) return CONFSPEC_E_INVALID_ARG;
+        if (value < 0 || value > 8) return CONFSPEC_E_INVALID_ARG;
         cs::gemm_set_tile(value);
     } else if (!strcmp(key, "split_layers")) {
         if (value < -1 || value > 4096) return CONFSPEC_E_INVALID_ARG;

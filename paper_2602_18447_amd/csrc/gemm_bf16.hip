@@ -30,26 +30,34 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 #define CS_GLOBAL_AS __attribute__((address_space(1)))
 #define CS_LDS_AS __attribute__((address_space(3)))
 
-constexpr int GEMM_BK = 64;
-constexpr int GEMM_ROW_BYTES = GEMM_BK * 2;   // one tile row in LDS
-
 struct GemmTune {
-    int tile;   // 0 = heuristic, 1 = 128x128 (4 waves), 2 = 256x256 (4 waves), 3 = 256x128 (4 waves),
-                // 4 = 256x256 (8 waves), 5 = 128x128 (2 waves)
+    int tile;   // 0 = heuristic; see launch_epi for the ids
 };
 static GemmTune g_gemm_tune = {0};
 void gemm_set_tile(int t) { g_gemm_tune.tile = t; }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+// vmcnt(n) only (expcnt / lgkmcnt left unconstrained), gfx9 encoding of s_waitcnt
+#define CS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+// BK: k extent of one LDS stage (64 or 32 elements); NS: number of LDS stages.  NS - 1 k-tiles are
+// kept in flight: (64, 2) has the fewest barriers, (32, 4) the deepest prefetch for the same LDS budget.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W,
                                                          void *__restrict__ out_v, int M, int N, int K,
                                                          int tiles_m, int tiles_n, int a_terms, int out_terms) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wave tile
     constexpr int MI = WM / 32, NI = WN / 32;             // 32x32 MFMA blocks per wave
-    constexpr int A_DMA = BM / (8 * NW), B_DMA = BN / (8 * NW);  // 1 KiB direct loads per wave per k-tile
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && WN % 64 == 0, "tile shape");
-    constexpr int STAGE = (BM + BN) * GEMM_ROW_BYTES;   // bytes
+    constexpr int ROWB = BK * 2;                          // bytes of one tile row in LDS
+    constexpr int VPR = ROWB / 16;                        // 16-byte k-vectors per row (8 or 4)
+    constexpr int RPD = 1024 / ROWB;                      // rows filled by one 1 KiB direct load (8 or 16)
+    constexpr int A_DMA = BM / (RPD * NW), B_DMA = BN / (RPD * NW);   // direct loads per wave per k-tile
+    constexpr int PER_TILE = A_DMA + B_DMA;
+    constexpr int STAGE = (BM + BN) * ROWB;               // bytes
+    static_assert(BK == 64 || BK == 32, "BK");
+    static_assert(BM % (RPD * NW) == 0 && BN % (RPD * NW) == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
+    static_assert(EPI != EPI_SWIGLU || WN % 64 == 0, "SwiGLU needs a gate/up column pair inside one wave tile");
+    static_assert(NS >= 2 && NS <= 4, "stages");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give each XCD a
@@ -65,38 +73,40 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int wy = wave / WAVES_N, wx = wave % WAVES_N;
 
-    // Direct-load roles: instruction j of wave w fills rows 8*(w + NW*j) .. +7 of an operand tile; lane
-    // s sits at row s/8, position s%8 and fetches k-vector (s%8) ^ swizzle(row).  A rows past M are
-    // clamped (fetched twice, never stored to the output).
-    const int rl = lane >> 3, ph = lane & 7;
+    // Direct-load roles: instruction j of wave w fills rows RPD*(w + NW*j) .. of an operand tile; lane s
+    // sits at row s / VPR, position s % VPR and fetches the k-vector that the swizzle puts there.
+    // Swizzle: position = k-vector ^ ((row >> 1) & 7) for 128-byte rows, ^ ((row >> 2) & 3) for 64-byte
+    // rows; either way 16 consecutive rows at one k-vector cover all 64 banks once.  A rows past M
+    // are clamped (fetched twice, never stored to the output).
+    auto swz = [](int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
+    const int rl = lane / VPR, ph = lane % VPR;
     const int lda = K * a_terms;
     const char *a_src[A_DMA], *b_src[B_DMA];
 #pragma unroll
     for (int j = 0; j < A_DMA; ++j) {
-        int row = 8 * (wave + NW * j) + rl;
-        int g = ph ^ ((row >> 1) & 7);
+        int row = RPD * (wave + NW * j) + rl;
+        int g = ph ^ swz(row);
         a_src[j] = reinterpret_cast<const char *>(A + (size_t)min(m0 + row, M - 1) * lda + g * 8);
     }
 #pragma unroll
     for (int j = 0; j < B_DMA; ++j) {
-        int row = 8 * (wave + NW * j) + rl;
-        int g = ph ^ ((row >> 1) & 7);
+        int row = RPD * (wave + NW * j) + rl;
+        int g = ph ^ swz(row);
         b_src[j] = reinterpret_cast<const char *>(W + (size_t)(n0 + row) * K + g * 8);
     }
-    int nk_w = K / GEMM_BK;        // k-tiles of W
+    int nk_w = K / BK;             // k-tiles of W
     int nk = nk_w * a_terms;       // k-tiles of A: hi half, then lo half
     auto issue_loads = [&](int stage, int kt) {
         int kw = kt >= nk_w ? kt - nk_w : kt;     // W wraps around for the lo half
         unsigned char *base = smem + stage * STAGE;
 #pragma unroll
         for (int j = 0; j < A_DMA; ++j)
-            __builtin_amdgcn_global_load_lds((const CS_GLOBAL_AS void *)(a_src[j] + (size_t)kt * GEMM_ROW_BYTES),
+            __builtin_amdgcn_global_load_lds((const CS_GLOBAL_AS void *)(a_src[j] + (size_t)kt * ROWB),
                                              (CS_LDS_AS void *)(base + (wave + NW * j) * 1024), 16, 0, 0);
 #pragma unroll
         for (int j = 0; j < B_DMA; ++j)
-            __builtin_amdgcn_global_load_lds((const CS_GLOBAL_AS void *)(b_src[j] + (size_t)kw * GEMM_ROW_BYTES),
-                                             (CS_LDS_AS void *)(base + BM * GEMM_ROW_BYTES + (wave + NW * j) * 1024), 16,
-                                             0, 0);
+            __builtin_amdgcn_global_load_lds((const CS_GLOBAL_AS void *)(b_src[j] + (size_t)kw * ROWB),
+                                             (CS_LDS_AS void *)(base + BM * ROWB + (wave + NW * j) * 1024), 16, 0, 0);
     };
 
     f32x16 acc[MI][NI];
@@ -110,37 +120,44 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     // MFMA operand reads: row (lane % 32) of each 32-row block, k-vector 2 ks + lane / 32
     const int half = lane >> 5;
     const int arow = wy * WM + (lane & 31), brow = wx * WN + (lane & 31);
-    const int a_base = arow * GEMM_ROW_BYTES, a_sw = (arow >> 1) & 7;
-    const int b_base = BM * GEMM_ROW_BYTES + brow * GEMM_ROW_BYTES, b_sw = (brow >> 1) & 7;
+    const int a_base = arow * ROWB, a_sw = swz(arow);          // rows 32 apart share the swizzle value
+    const int b_base = BM * ROWB + brow * ROWB, b_sw = swz(brow);
 
-    issue_loads(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0): the direct loads have been written to LDS
-    __syncthreads();
+    // Pipeline: k-tiles kt+1 .. kt+NS-1 are in flight while k-tile kt is multiplied.  Direct loads
+    // complete in order per wave, so "at most PER_TILE * r outstanding" means this wave's part of tile
+    // kt has landed when r tiles were issued after it; the barrier extends that to every wave and also
+    // tells that everybody is done with the stage the next loads will overwrite.
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t)
+        if (t < nk) issue_loads(t, t);
     for (int kt = 0; kt < nk; ++kt) {
-        const unsigned char *cur = smem + (kt & 1) * STAGE;
-        if (kt + 1 < nk) issue_loads((kt + 1) & 1, kt + 1);
+        int after = min(NS - 2, nk - 1 - kt);
+        if (after >= 2) CS_WAIT_VMCNT(2 * PER_TILE);
+        else if (after == 1) CS_WAIT_VMCNT(PER_TILE);
+        else CS_WAIT_VMCNT(0);
+        __syncthreads();
+        if (kt + NS - 1 < nk) issue_loads((kt + NS - 1) % NS, kt + NS - 1);
+        const unsigned char *cur = smem + (kt % NS) * STAGE;
         bf16x8 af[2][MI], bfr[2][NI];
         auto read_frags = [&](int buf, int ks) {
             int ga = ((2 * ks + half) ^ a_sw) * 16, gb = ((2 * ks + half) ^ b_sw) * 16;
 #pragma unroll
             for (int i = 0; i < MI; ++i)
-                af[buf][i] = *reinterpret_cast<const bf16x8 *>(cur + a_base + i * 32 * GEMM_ROW_BYTES + ga);
+                af[buf][i] = *reinterpret_cast<const bf16x8 *>(cur + a_base + i * 32 * ROWB + ga);
 #pragma unroll
             for (int j = 0; j < NI; ++j)
-                bfr[buf][j] = *reinterpret_cast<const bf16x8 *>(cur + b_base + j * 32 * GEMM_ROW_BYTES + gb);
+                bfr[buf][j] = *reinterpret_cast<const bf16x8 *>(cur + b_base + j * 32 * ROWB + gb);
         };
         read_frags(0, 0);
 #pragma unroll
-        for (int ks = 0; ks < GEMM_BK / 16; ++ks) {
-            if (ks + 1 < GEMM_BK / 16) read_frags((ks + 1) & 1, ks + 1);   // next k-step's operands
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, ks + 1);   // next k-step's operands
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
         }
-        __builtin_amdgcn_s_waitcnt(0x0070);   // next tile is in LDS ...
-        __syncthreads();                      // ... for every wave, and this tile's stage is free
     }
 
     // C layout of one 32x32 block: lane holds column lane%32, rows 8*(e/4) + 4*(lane/32) + e%4.
@@ -177,12 +194,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI>
 static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
                               int out_terms, hipStream_t s) {
-    constexpr int smem = 2 * (BM + BN) * GEMM_ROW_BYTES;
+    constexpr int smem = NS * (BM + BN) * BK * 2;
     static bool attr_set = false;
-    auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI>;
+    auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -196,6 +213,9 @@ static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, in
     return hipGetLastError();
 }
 
+// Tile ids: 1 = 128x128 / 4 waves, 2 = 256x256 / 4 waves, 3 = 256x128 / 4 waves, 4 = 256x256 / 8 waves,
+// 5 = 128x128 / 4 waves / BK 32 x 4 stages, 6 = 256x256 / 8 waves / BK 32 x 4 stages,
+// 7 = 128x128 / 4 waves / BK 64 x 3 stages, 8 = 256x128 / 8 waves / BK 64 x 3 stages.
 template <int EPI>
 static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
                              int out_terms, hipStream_t s) {
@@ -204,12 +224,18 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
         long t256 = (long)((M + 255) / 256) * (N / 256);
         tile = (N % 256 == 0 && t256 >= 192) ? 4 : 1;
     }
-    if ((tile == 2 || tile == 4) && N % 256 != 0) tile = 1;
-    if (tile == 4) return launch_tile<256, 256, 2, 4, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-    if (tile == 2) return launch_tile<256, 256, 2, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-    if (tile == 3) return launch_tile<256, 128, 2, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-    if (tile == 5) return launch_tile<128, 128, 2, 1, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-    return launch_tile<128, 128, 2, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+    if ((tile == 2 || tile == 4 || tile == 6) && N % 256 != 0) tile = 1;
+    if (K % 64 != 0 && (tile == 5 || tile == 6)) tile = 1;
+    switch (tile) {
+        case 2: return launch_tile<256, 256, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+        case 3: return launch_tile<256, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+        case 4: return launch_tile<256, 256, 2, 4, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+        case 5: return launch_tile<128, 128, 2, 2, 32, 4, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+        case 6: return launch_tile<256, 256, 2, 4, 32, 4, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+        case 7: return launch_tile<128, 128, 2, 2, 64, 3, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+        case 8: return launch_tile<256, 128, 4, 2, 64, 3, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+        default: return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+    }
 }
 
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,

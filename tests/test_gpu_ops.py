@@ -43,7 +43,7 @@ def _pack_rows(F):
 
 
 # --------------------------------------------------------------------------- #
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("M,N,K", [(300, 512, 192), (1, 256, 64), (257, 768, 1024), (512, 256, 320)])
 def test_gemm_bf16_store_and_residual(tile, M, N, K):
     print(f"gemm bf16 tile={tile} M={M} N={N} K={K}", flush=True)
@@ -67,7 +67,7 @@ def test_gemm_bf16_store_and_residual(tile, M, N, K):
     cb.confspec_destroy(ctx)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_gemm_bf16_swiglu_epilogue(tile):
     print(f"gemm bf16 swiglu tile={tile}", flush=True)
     ctx, _ = _ctx("bf16")
