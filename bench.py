@@ -17,6 +17,38 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+GEMM_SOURCE = os.path.join(ROOT, "paper_2602_18447_amd", "csrc", "gemm_bf16.hip")
+HBM_COUNTERS = os.path.join(ROOT, "paper_2602_18447_amd", "hbm_counters.json")
+
+
+def _hbm_traffic():
+    """HBM bytes per launch of the gate/up GEMM from the stored hardware-counter runs, or None when
+    there is no record or the kernel source has changed since the counters were taken."""
+    import hashlib
+
+    try:
+        with open(HBM_COUNTERS) as f:
+            rec = json.load(f)
+        with open(GEMM_SOURCE, "rb") as f:
+            sha = hashlib.sha256(f.read()).hexdigest()
+    except OSError:
+        return None
+    if rec.get("gemm_source_sha256") != sha:
+        return None
+    return rec.get("gate_up_gemm")
+
+
+def _blas_threads():
+    """Threads the oracle's BLAS calls run on (numpy's pool), not the machine's core count."""
+    try:
+        from threadpoolctl import threadpool_info
+
+        n = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+        if n:
+            return max(n)
+    except Exception:
+        pass
+    return os.cpu_count()
 
 
 def main():
@@ -26,6 +58,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="workload: 2 (default, the metric's config), 3, 4 or 5")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP-graph replays")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the plain copy kernel (1 GiB, 5 times): the yardstick for HBM byte counters")
     ap.add_argument("--cpu-baseline-traces", type=int, default=6,
                     help="traces of the workload the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -129,10 +163,33 @@ def main():
     gemm_ms = g0.elapsed_time(g1) / n_launch
     gemm_flops = 2.0 * T * (2 * F) * d
     achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
-    roofline = dict(bound="mfma", kernel="gemm_bf16_kernel<256,256,SWIGLU> (gate/up projection)",
+    traffic = _hbm_traffic() if args.config == 2 else None   # the counters were taken on config 2's shape
+    roofline = dict(bound="mfma", kernel="gemm_bf16_kernel<256,256,2,4,64,2,SWIGLU,1> (gate/up projection)",
                     achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
-                    flops_per_launch=gemm_flops, avg_launch_ms=round(gemm_ms, 5))
+                    frac=round(achieved / PEAK_BF16_TFLOPS, 4),
+                    traffic=None if traffic is None else traffic["hbm_bytes"],
+                    traffic_detail=traffic, flops_per_launch=gemm_flops,
+                    algorithmic_bytes_per_launch=2 * (T * d + 2 * F * d + T * F),
+                    avg_launch_ms=round(gemm_ms, 5), launches_timed=n_launch)
+
+    copy_info = None
+    if args.calibrate_copy:
+        nbytes = 1 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        cb.confspec_op_copy(src, dst, nbytes)
+        torch.cuda.synchronize()
+        g0.record()
+        for _ in range(5):
+            cb.confspec_op_copy(src, dst, nbytes)
+        g1.record()
+        torch.cuda.synchronize()
+        copy_ms = g0.elapsed_time(g1) / 5
+        if not torch.equal(src, dst):
+            raise RuntimeError("copy kernel result differs from its source")
+        copy_info = dict(bytes_read=nbytes, bytes_written=nbytes, avg_ms=round(copy_ms, 4),
+                         GBps=round(2 * nbytes / (copy_ms * 1e-3) / 1e9, 1))
+        del src, dst
 
     # ---- CPU oracle on a bounded sample of the same workload (reported baseline only)
     cpu = None
@@ -146,7 +203,7 @@ def main():
                        trace_subset=list(range(n)))
         dt = time.time() - t0
         dl = float(np.abs(outs[0].cpu().numpy()[:n] - ora["logits"]).max())
-        cpu = dict(value=round(n / dt, 4), unit="verified steps/s", cores=torch.get_num_threads(), kind="oracle",
+        cpu = dict(value=round(n / dt, 4), unit="verified steps/s", cores=_blas_threads(), kind="oracle",
                    sample=f"first {n} of {wl.B} traces of {wl.name}, fp64 numpy, {dt:.1f} s",
                    max_abs_dlogit_vs_gpu=dl)
 
@@ -158,7 +215,7 @@ def main():
         "config": {"workload": wl.name, "B": wl.B, "T": wl.T, "sum_prefix_len": int(sum(wl.prefix_lens)),
                    "layers": m.n_layers, "d_model": m.d_model, "taus": taus, "accept_counts": accept_counts,
                    "launch": "hip_graph_replay" if graph_ok else "eager", "eager_ms_per_step": round(eager_ms, 4)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, **({"copy_calibration": copy_info} if copy_info else {}),
     }))
 
 

@@ -69,10 +69,16 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
                              size_t workspace_bytes, float *dev_verdict_logits, float *dev_conf,
                              int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream);
 
+/* Measurement aid, not a step of the method: a plain device-to-device copy kernel (16 bytes per lane per
+ * step) of `bytes` bytes, a multiple of 16, both pointers 16-byte aligned and the ranges disjoint.  It reads
+ * and writes exactly `bytes` each, which makes it the yardstick that hardware HBM byte counters of the other
+ * kernels are scaled by.  Returns CONFSPEC_E_INVALID_ARG on a null, misaligned or empty argument. */
+int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_stream stream);
+
 /* Process-wide settings.  "split_layers": number of leading layers in which confspec_verify carries
  * the GEMM activations as two bf16 terms (default -1 = ceil(n_layers / 7), doubled when d_model > 4096).  "attn_precise_layers"
  * (default 1): number of leading layers whose attention runs the two-term variant.  Launch-shape tunables for
- * measurements: "gemm_tile" (0 heuristic, 1..8 = fixed workgroup tile / pipeline shape of the bf16 GEMM),
+ * measurements: "gemm_tile" (0 heuristic, 1..6 = fixed workgroup tile / pipeline shape of the bf16 GEMM),
  * "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
  * "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = fixed key-range split factor).  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a
  * value out of range. */

@@ -85,6 +85,8 @@ def _load() -> C.CDLL:
     lib.confspec_op_verdict_gate.restype = C.c_int
     lib.confspec_op_verdict_gate.argtypes = [vp, P(Batch), vp, vp, vp, P(i32), i32, P(C.c_float), i32, vp, sz,
                                              vp, vp, vp, vp, vp]
+    lib.confspec_op_copy.restype = C.c_int
+    lib.confspec_op_copy.argtypes = [vp, vp, sz, vp]
     lib.confspec_tune.restype = C.c_int
     lib.confspec_tune.argtypes = [C.c_char_p, i32]
     return lib
@@ -95,7 +97,7 @@ lib = _load()
 EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec_last_error",
             "confspec_workspace_bytes", "confspec_packed_bytes", "confspec_pack_weights", "confspec_verify",
             "confspec_op_gemm", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_attention",
-            "confspec_op_verdict_gate", "confspec_tune"]
+            "confspec_op_verdict_gate", "confspec_op_copy", "confspec_tune"]
 
 
 class ConfSpecError(RuntimeError):
@@ -211,6 +213,12 @@ def confspec_op_verdict_gate(ctx, batch: Batch, x, final_norm, lm_head, verdict_
     _check(ctx, lib.confspec_op_verdict_gate(ctx, C.byref(batch), _ptr(x), _ptr(final_norm), _ptr(lm_head), ids, nv,
                                              tau, nt, _ptr(workspace), ws_bytes, _ptr(logits), _ptr(conf),
                                              _ptr(verdict), _ptr(accept), _stream_handle(stream)))
+
+
+def confspec_op_copy(src, dst, nbytes: int, stream=None) -> None:
+    rc = lib.confspec_op_copy(_ptr(src), _ptr(dst), int(nbytes), _stream_handle(stream))
+    if rc != OK:
+        raise ConfSpecError(rc, f"confspec_op_copy({nbytes})")
 
 
 def confspec_tune(key: str, value: int) -> None:

@@ -498,12 +498,19 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
     return CONFSPEC_OK;
 }
 
+int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_stream stream) {
+    if (!dev_src || !dev_dst || bytes == 0 || bytes % 16 != 0) return CONFSPEC_E_INVALID_ARG;
+    if (((uintptr_t)dev_src | (uintptr_t)dev_dst) & 15) return CONFSPEC_E_INVALID_ARG;
+    if (cs::launch_copy16(dev_src, dev_dst, bytes / 16, (hipStream_t)stream) != hipSuccess) return CONFSPEC_E_HIP;
+    return CONFSPEC_OK;
+}
+
 int confspec_tune(const char *key, int32_t value) {
     if (!key) return CONFSPEC_E_INVALID_ARG;
     int ti, mc;
     cs::attn_get_tune(&ti, &mc);
     if (!strcmp(key, "gemm_tile")) {
-        if (value < 0 || value > 8) return CONFSPEC_E_INVALID_ARG;
+        if (value < 0 || value > 6) return CONFSPEC_E_INVALID_ARG;
         cs::gemm_set_tile(value);
     } else if (!strcmp(key, "split_layers")) {
         if (value < -1 || value > 4096) return CONFSPEC_E_INVALID_ARG;

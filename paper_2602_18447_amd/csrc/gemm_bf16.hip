@@ -41,10 +41,10 @@ void gemm_set_tile(int t) { g_gemm_tune.tile = t; }
 
 // BK: k extent of one LDS stage (64 or 32 elements); NS: number of LDS stages.  NS - 1 k-tiles are
 // kept in flight: (64, 2) has the fewest barriers, (32, 4) the deepest prefetch for the same LDS budget.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_TERMS>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W,
                                                          void *__restrict__ out_v, int M, int N, int K,
-                                                         int tiles_m, int tiles_n, int a_terms, int out_terms) {
+                                                         int tiles_m, int tiles_n, int out_terms) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wave tile
     constexpr int MI = WM / 32, NI = WN / 32;             // 32x32 MFMA blocks per wave
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     // are clamped (fetched twice, never stored to the output).
     auto swz = [](int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
     const int rl = lane / VPR, ph = lane % VPR;
-    const int lda = K * a_terms;
+    const int lda = K * A_TERMS;
     const char *a_src[A_DMA], *b_src[B_DMA];
 #pragma unroll
     for (int j = 0; j < A_DMA; ++j) {
@@ -95,9 +95,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         b_src[j] = reinterpret_cast<const char *>(W + (size_t)(n0 + row) * K + g * 8);
     }
     int nk_w = K / BK;             // k-tiles of W
-    int nk = nk_w * a_terms;       // k-tiles of A: hi half, then lo half
+    int nk = nk_w * A_TERMS;       // k-tiles of A: hi half, then lo half
     auto issue_loads = [&](int stage, int kt) {
-        int kw = kt >= nk_w ? kt - nk_w : kt;     // W wraps around for the lo half
+        int kw = (A_TERMS == 2 && kt >= nk_w) ? kt - nk_w : kt;     // W wraps around for the lo half
         unsigned char *base = smem + stage * STAGE;
 #pragma unroll
         for (int j = 0; j < A_DMA; ++j)
@@ -194,12 +194,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI>
-static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
-                              int out_terms, hipStream_t s) {
+// The number of activation terms is a template parameter, so the one-term and the two-term launches
+// are different kernels (and show up under different names in a kernel trace).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_TERMS>
+static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int out_terms,
+                              hipStream_t s) {
     constexpr int smem = NS * (BM + BN) * BK * 2;
     static bool attr_set = false;
-    auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI>;
+    auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, A_TERMS>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -209,13 +211,21 @@ static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, in
     int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
     int n_tiles = tiles_m * tiles_n;
     int grid = ((n_tiles + 7) / 8) * 8;
-    kern<<<grid, 64 * WAVES_M * WAVES_N, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n, a_terms, out_terms);
+    kern<<<grid, 64 * WAVES_M * WAVES_N, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n, out_terms);
     return hipGetLastError();
 }
 
-// Tile ids: 1 = 128x128 / 4 waves, 2 = 256x256 / 4 waves, 3 = 256x128 / 4 waves, 4 = 256x256 / 8 waves,
-// 5 = 128x128 / 4 waves / BK 32 x 4 stages, 6 = 256x256 / 8 waves / BK 32 x 4 stages,
-// 7 = 128x128 / 4 waves / BK 64 x 3 stages, 8 = 256x128 / 8 waves / BK 64 x 3 stages.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI>
+static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
+                              int out_terms, hipStream_t s) {
+    if (a_terms == 2) return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(A, W, out, M, N, K, out_terms, s);
+    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(A, W, out, M, N, K, out_terms, s);
+}
+
+// Tile ids: 1 = 128x128 / 4 waves, 2 = 256x256 / 4 waves, 3 = 256x128 / 4 waves, 4 = 256x256 / 8 waves
+// (all BK 64 x 2 stages); 5 = 128x128 / 4 waves and 6 = 256x256 / 8 waves with BK 32 x 4 stages.
+// Measured on the draft-model shapes: 4 is the fastest for the wide gate/up projection, 1 for the
+// others; the deeper pipelines (5, 6) pay more barriers than they hide latency.
 template <int EPI>
 static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
                              int out_terms, hipStream_t s) {
@@ -225,15 +235,12 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
         tile = (N % 256 == 0 && t256 >= 192) ? 4 : 1;
     }
     if ((tile == 2 || tile == 4 || tile == 6) && N % 256 != 0) tile = 1;
-    if (K % 64 != 0 && (tile == 5 || tile == 6)) tile = 1;
     switch (tile) {
         case 2: return launch_tile<256, 256, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
         case 3: return launch_tile<256, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
         case 4: return launch_tile<256, 256, 2, 4, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
         case 5: return launch_tile<128, 128, 2, 2, 32, 4, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
         case 6: return launch_tile<256, 256, 2, 4, 32, 4, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-        case 7: return launch_tile<128, 128, 2, 2, 64, 3, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-        case 8: return launch_tile<256, 128, 4, 2, 64, 3, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
         default: return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
     }
 }

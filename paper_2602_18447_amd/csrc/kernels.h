@@ -60,6 +60,7 @@ hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, i
 hipError_t launch_rope_split(int dtype, const float *qkv, const float *cos_t, const float *sin_t, void *q,
                              void *ksuf, void *vsuf, void *q_lo, void *k_lo, void *v_lo, int T, int Hq, int Hkv,
                              int hd, hipStream_t s);
+hipError_t launch_copy16(const void *src, void *dst, size_t n16, hipStream_t s);
 hipError_t launch_pack_gate_up(int dtype, const void *src, void *dst, int F, int d, hipStream_t s);
 
 struct VerdictArgs {

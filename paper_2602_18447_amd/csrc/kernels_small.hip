@@ -5,6 +5,8 @@
 
 namespace cs {
 
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+
 template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f32<bf16>(bf16 v) { return __bfloat162float(v); }
@@ -129,6 +131,21 @@ hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, i
     int blocks = (T + 3) / 4;
     if (dtype == 0) rmsnorm_kernel<float><<<blocks, 256, 0, s>>>(x, (const float *)g, (float *)out, T, d, eps, 1);
     else rmsnorm_kernel<bf16><<<blocks, 256, 0, s>>>(x, (const bf16 *)g, (bf16 *)out, T, d, eps, terms);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Plain copy, 16 bytes per lane per step: reads n16 * 16 bytes and writes as many.  Its known
+// traffic is the yardstick that hardware byte counters of the other kernels are scaled by.
+__global__ void copy16_kernel(const u32x4_t *__restrict__ src, u32x4_t *__restrict__ dst, size_t n16) {
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy16(const void *src, void *dst, size_t n16, hipStream_t s) {
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    copy16_kernel<<<(unsigned)blocks, 256, 0, s>>>((const u32x4_t *)src, (u32x4_t *)dst, n16);
     return hipGetLastError();
 }
 

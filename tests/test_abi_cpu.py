@@ -149,4 +149,11 @@ def test_op_gemm_and_tune_validation():
     with pytest.raises(cb.ConfSpecError):
         cb.confspec_tune("no_such_key", 1)
     cb.confspec_tune("gemm_tile", 0)
+    with pytest.raises(cb.ConfSpecError):
+        cb.confspec_tune("gemm_tile", 99)
+    for src, dst, n in [(None, fake, 64), (fake, None, 64), (fake, fake, 0), (fake, fake, 24),
+                        (_FakeDev(0x10008), fake, 64)]:
+        with pytest.raises(cb.ConfSpecError) as ei:
+            cb.confspec_op_copy(src, dst, n, stream=0)
+        assert ei.value.code == cb.E_INVALID_ARG
     cb.confspec_destroy(ctx)

@@ -43,7 +43,7 @@ def _pack_rows(F):
 
 
 # --------------------------------------------------------------------------- #
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("M,N,K", [(300, 512, 192), (1, 256, 64), (257, 768, 1024), (512, 256, 320)])
 def test_gemm_bf16_store_and_residual(tile, M, N, K):
     print(f"gemm bf16 tile={tile} M={M} N={N} K={K}", flush=True)
@@ -67,7 +67,7 @@ def test_gemm_bf16_store_and_residual(tile, M, N, K):
     cb.confspec_destroy(ctx)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
 def test_gemm_bf16_swiglu_epilogue(tile):
     print(f"gemm bf16 swiglu tile={tile}", flush=True)
     ctx, _ = _ctx("bf16")
@@ -362,3 +362,13 @@ def test_verdict_head_and_gate(dtype):
                 assert int(accept[i, b]) == int(want[i])
     assert accept[0].all() and accept.cpu().numpy()[:-1].sum() > accept.cpu().numpy()[-1].sum()
     cb.confspec_destroy(ctx)
+
+
+def test_copy_kernel_is_exact():
+    print("copy kernel", flush=True)
+    n = (1 << 22) + 16 * 37                       # not a multiple of the grid's stride
+    src = torch.empty(n, dtype=torch.uint8, device=DEV).random_(0, 255)
+    dst = torch.zeros(n + 16, dtype=torch.uint8, device=DEV)
+    cb.confspec_op_copy(src, dst, n)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], src) and int(dst[n:].sum()) == 0
