@@ -79,6 +79,7 @@ int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_
  * the GEMM activations as two bf16 terms (default -1 = ceil(n_layers / 7), doubled when d_model > 4096).  "attn_precise_layers"
  * (default 1): number of leading layers whose attention runs the two-term variant.  Launch-shape tunables for
  * measurements: "gemm_tile" (0 heuristic, 1..6 = fixed workgroup tile / pipeline shape of the bf16 GEMM),
+ * "gemm_group_m" (0 heuristic, else tile rows per band of the GEMM's tile order),
  * "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
  * "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = fixed key-range split factor).  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a
  * value out of range. */

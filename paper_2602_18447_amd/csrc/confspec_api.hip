@@ -15,6 +15,7 @@
 
 namespace cs {
 void gemm_set_tile(int t);
+void gemm_set_group_m(int g);
 void attn_set_tune(int target_items, int min_chunks);
 void attn_get_tune(int *target_items, int *min_chunks);
 void attn_set_split(int s);
@@ -512,6 +513,9 @@ int confspec_tune(const char *key, int32_t value) {
     if (!strcmp(key, "gemm_tile")) {
         if (value < 0 || value > 6) return CONFSPEC_E_INVALID_ARG;
         cs::gemm_set_tile(value);
+    } else if (!strcmp(key, "gemm_group_m")) {
+        if (value < 0 || value > 65536) return CONFSPEC_E_INVALID_ARG;
+        cs::gemm_set_group_m(value);
     } else if (!strcmp(key, "split_layers")) {
         if (value < -1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
         g_split_layers = value;

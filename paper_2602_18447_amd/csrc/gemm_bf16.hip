@@ -13,7 +13,8 @@
 // and have the whole MFMA phase of k-tile i to complete; one vmcnt wait + barrier per k-tile.
 //
 // Epilogues: plain fp32 store, fp32 residual add in place, or SwiGLU on interleaved gate/up columns
-// with a bf16 result.
+// with a bf16 result; each wavefront transposes its accumulators through LDS so that global memory is
+// touched in 16-byte pieces per lane.
 //
 // Two-term activations.  With a_terms == 2 the A operand is [M, 2K]: columns 0..K-1 hold the bf16
 // rounding of the activation ("hi") and K..2K-1 the bf16 rounding of what that rounding lost
@@ -21,20 +22,26 @@
 // (hi + lo) . W - the product with a 16-bit-mantissa activation.  With out_terms == 2 the SwiGLU
 // epilogue writes its result in the same [M, 2F] hi | lo form for the next GEMM.
 #include "kernels.h"
+#include <algorithm>
+#include <cmath>
 
 namespace cs {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 #define CS_GLOBAL_AS __attribute__((address_space(1)))
 #define CS_LDS_AS __attribute__((address_space(3)))
 
 struct GemmTune {
-    int tile;   // 0 = heuristic; see launch_epi for the ids
+    int tile;      // 0 = heuristic; see launch_epi for the ids
+    int group_m;   // 0 = heuristic; otherwise tile rows per band of the tile order
 };
-static GemmTune g_gemm_tune = {0};
+static GemmTune g_gemm_tune = {0, 0};
 void gemm_set_tile(int t) { g_gemm_tune.tile = t; }
+void gemm_set_group_m(int g) { g_gemm_tune.group_m = g; }
 
 // vmcnt(n) only (expcnt / lgkmcnt left unconstrained), gfx9 encoding of s_waitcnt
 #define CS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
@@ -44,7 +51,7 @@ void gemm_set_tile(int t) { g_gemm_tune.tile = t; }
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_TERMS>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W,
                                                          void *__restrict__ out_v, int M, int N, int K,
-                                                         int tiles_m, int tiles_n, int out_terms) {
+                                                         int tiles_m, int tiles_n, int n_base, int group_m, int out_terms) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wave tile
     constexpr int MI = WM / 32, NI = WN / 32;             // 32x32 MFMA blocks per wave
@@ -58,17 +65,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     static_assert(BM % (RPD * NW) == 0 && BN % (RPD * NW) == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
     static_assert(EPI != EPI_SWIGLU || WN % 64 == 0, "SwiGLU needs a gate/up column pair inside one wave tile");
     static_assert(NS >= 2 && NS <= 4, "stages");
+    static_assert(MI * NI >= 2, "a k-step has at least two MFMAs");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give each XCD a
-    // contiguous range of tiles; inside a range tile_m runs fastest, so neighbours share a W tile.
+    // contiguous range of the tile list.  The list walks the tile grid in bands of group_m tile rows,
+    // tile_m fastest inside a band, so the workgroups that share one L2 at any time cover a roughly
+    // square block of tiles (group_m x resident/group_m): what they fetch together is
+    // group_m A panels + resident/group_m W panels, the minimum for that many tiles.
     int n_tiles = tiles_m * tiles_n;
     int bid = blockIdx.x;
     int per = (n_tiles + 7) >> 3;
     int lid = (bid & 7) * per + (bid >> 3);
     if (lid >= n_tiles) return;   // uniform per workgroup: no barrier is skipped by a subset
-    int tm = lid % tiles_m, tn = lid / tiles_m;
-    int m0 = tm * BM, n0 = tn * BN;
+    int band = lid / (group_m * tiles_n), in_band = lid - band * group_m * tiles_n;
+    int band_rows = min(group_m, tiles_m - band * group_m);
+    int tm = band * group_m + in_band % band_rows, tn = in_band / band_rows;
+    int m0 = tm * BM, n0 = n_base + tn * BN;   // a launch may cover the column range [n_base, n_base + tiles_n * BN) only
 
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int wy = wave / WAVES_N, wx = wave % WAVES_N;
@@ -136,7 +149,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         else if (after == 1) CS_WAIT_VMCNT(PER_TILE);
         else CS_WAIT_VMCNT(0);
         __syncthreads();
-        if (kt + NS - 1 < nk) issue_loads((kt + NS - 1) % NS, kt + NS - 1);
         const unsigned char *cur = smem + (kt % NS) * STAGE;
         bf16x8 af[2][MI], bfr[2][NI];
         auto read_frags = [&](int buf, int ks) {
@@ -148,57 +160,124 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
             for (int j = 0; j < NI; ++j)
                 bfr[buf][j] = *reinterpret_cast<const bf16x8 *>(cur + b_base + j * 32 * ROWB + gb);
         };
+        // The first operands of this k-tile are requested before the next tile's loads are issued, so
+        // their LDS latency passes under the address arithmetic of those loads.  Inside a k-step the
+        // operands of the next step are requested after the first MFMAs and have the rest of the step to
+        // arrive: the one wait in front of a step's first MFMA then only covers reads issued most of a
+        // step earlier.  The scheduling barriers pin that order (left alone, the compiler sinks the reads
+        // to save registers, and every group of MFMAs waits out its own LDS latency).
         read_frags(0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + NS - 1 < nk) issue_loads((kt + NS - 1) % NS, kt + NS - 1);
+        constexpr int EARLY = 2;   // MFMAs of a k-step issued before the next step's operand reads
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, ks + 1);   // next k-step's operands
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+            for (int q = 0; q < EARLY; ++q)
+                acc[q / NI][q % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][q / NI], bfr[ks & 1][q % NI],
+                                                                              acc[q / NI][q % NI], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, ks + 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+            for (int q = EARLY; q < MI * NI; ++q)
+                acc[q / NI][q % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][q / NI], bfr[ks & 1][q % NI],
+                                                                              acc[q / NI][q % NI], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
 
-    // C layout of one 32x32 block: lane holds column lane%32, rows 8*(e/4) + 4*(lane/32) + e%4.
-    int col_l = lane & 31, row_l = (lane >> 5) * 4;
+    // ---- epilogue.  The accumulator layout of a 32x32 block gives a lane one column and 16 rows, so
+    // stores straight from it are 2- or 4-byte pieces per lane, and the store path retires a wavefront
+    // instruction in about 16 cycles whatever its width.  Each wavefront therefore transposes one 32-row
+    // block at a time through a private piece of LDS (the operand stages are dead by now) and moves
+    // 16 bytes per lane to and from global memory.
+    constexpr int WNO = (EPI == EPI_SWIGLU) ? WN / 2 : WN;   // output columns of a wave tile
+    constexpr int SROW = WNO + 8;                            // staging row stride in words; 4 * SROW % 64 == 32,
+                                                             // so the two row groups of a write hit disjoint banks
+    static_assert(NW * 32 * SROW * 4 <= NS * STAGE, "epilogue staging does not fit the operand stages");
+    __syncthreads();                                         // every wavefront is done with the operand stages
+    float *stg = reinterpret_cast<float *>(smem) + wave * 32 * SROW;
+    const int col_l = lane & 31, row_l = (lane >> 5) * 4;    // C layout: column lane%32, rows 8*(e/4) + 4*(lane/32) + e%4
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            int m = m0 + wy * WM + i * 32 + (e >> 2) * 8 + row_l + (e & 3);
-            if (m >= M) continue;
+            float *srow = stg + ((e >> 2) * 8 + row_l + (e & 3)) * SROW + col_l;
             if (EPI == EPI_SWIGLU) {
-                bf16 *out = reinterpret_cast<bf16 *>(out_v);
-                int Fo = N >> 1;
 #pragma unroll
                 for (int j = 0; j < NI; j += 2) {
+                    // silu(g) * u with the hardware reciprocal (1 ulp): far below the bf16 rounding of the result,
+                    // and a third of the instructions of an IEEE division
                     float gte = acc[i][j][e], up = acc[i][j + 1][e];
-                    float act = gte / (1.0f + __expf(-gte)) * up;
-                    int f = ((n0 + wx * WN + j * 32) >> 1) + col_l;
-                    bf16 hi = __float2bfloat16(act);
-                    size_t o = (size_t)m * Fo * out_terms + f;
-                    out[o] = hi;
-                    if (out_terms == 2) out[o + Fo] = __float2bfloat16(act - __bfloat162float(hi));
+                    srow[(j >> 1) * 32] = gte * __builtin_amdgcn_rcpf(1.0f + __expf(-gte)) * up;
                 }
             } else {
-                float *out = reinterpret_cast<float *>(out_v);
 #pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    size_t o = (size_t)m * N + n0 + wx * WN + j * 32 + col_l;
-                    if (EPI == EPI_RESID_F32) out[o] += acc[i][j][e];
-                    else out[o] = acc[i][j][e];
+                for (int j = 0; j < NI; ++j) srow[j * 32] = acc[i][j][e];
+            }
+        }
+        // LDS operations of one wavefront execute in order; the fence keeps the compiler from moving the
+        // reads of other lanes' values above the writes.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int mrow0 = m0 + wy * WM + i * 32;
+        if (EPI == EPI_SWIGLU) {
+            constexpr int LPR = WNO / 8, RP = 64 / LPR;      // lanes per output row (8 bf16 each), rows per pass
+            bf16 *out = reinterpret_cast<bf16 *>(out_v);
+            const int Fo = N >> 1;
+            const int f0 = ((n0 + wx * WN) >> 1) + (lane % LPR) * 8;
+#pragma unroll
+            for (int p = 0; p < 32 / RP; ++p) {
+                int r = p * RP + lane / LPR, m = mrow0 + r;
+                const f32x4 *src = reinterpret_cast<const f32x4 *>(stg + r * SROW + (lane % LPR) * 8);
+                f32x4 v0 = src[0], v1 = src[1];
+                float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+                if (m < M) {
+                    bf16 *dst = out + (size_t)m * Fo * out_terms + f0;
+                    unsigned hi[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) hi[q] = __bfloat16_as_ushort(__float2bfloat16(v[q]));
+                    u32x4 ph = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)};
+                    *reinterpret_cast<u32x4 *>(dst) = ph;
+                    if (out_terms == 2) {
+                        unsigned lo[8];
+#pragma unroll
+                        for (int q = 0; q < 8; ++q)
+                            lo[q] = __bfloat16_as_ushort(
+                                __float2bfloat16(v[q] - __bfloat162float(__ushort_as_bfloat16((unsigned short)hi[q]))));
+                        u32x4 pl = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)};
+                        *reinterpret_cast<u32x4 *>(dst + Fo) = pl;
+                    }
+                }
+            }
+        } else {
+            constexpr int LPR = WNO / 4, RP = 64 / LPR;      // lanes per output row (4 floats each), rows per pass
+            float *out = reinterpret_cast<float *>(out_v);
+#pragma unroll
+            for (int p = 0; p < 32 / RP; ++p) {
+                int r = p * RP + lane / LPR, m = mrow0 + r;
+                f32x4 v = *reinterpret_cast<const f32x4 *>(stg + r * SROW + (lane % LPR) * 4);
+                if (m < M) {
+                    f32x4 *dst = reinterpret_cast<f32x4 *>(out + (size_t)m * N + n0 + wx * WN + (lane % LPR) * 4);
+                    if (EPI == EPI_RESID_F32) v += *dst;
+                    *dst = v;
                 }
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
 // The number of activation terms is a template parameter, so the one-term and the two-term launches
 // are different kernels (and show up under different names in a kernel trace).
+// Launches the kernel on the column range [n_base, n_base + n_cols) of the N columns.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_TERMS>
-static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int out_terms,
-                              hipStream_t s) {
+static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base, int n_cols,
+                              int out_terms, hipStream_t s) {
     constexpr int smem = NS * (BM + BN) * BK * 2;
     static bool attr_set = false;
     auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, A_TERMS>;
@@ -208,18 +287,29 @@ static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, in
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    int tiles_m = (M + BM - 1) / BM, tiles_n = n_cols / BN;
     int n_tiles = tiles_m * tiles_n;
     int grid = ((n_tiles + 7) / 8) * 8;
-    kern<<<grid, 64 * WAVES_M * WAVES_N, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n, out_terms);
+    // Workgroups of one XCD that run at the same time: its share of the tiles, at most 32 CUs x the
+    // workgroups that fit one CU's 160 KiB of LDS.  A square block of that many tiles, weighted by the
+    // tile's aspect, has sqrt(resident * BN / BM) rows.
+    int group_m = g_gemm_tune.group_m;
+    if (group_m <= 0) {
+        int fit = 160 * 1024 / smem;
+        int resident = std::min((n_tiles + 7) / 8, 32 * std::max(fit, 1));
+        group_m = (int)std::lround(std::sqrt((double)resident * BN / BM));
+    }
+    group_m = std::max(1, std::min(group_m, tiles_m));
+    kern<<<grid, 64 * WAVES_M * WAVES_N, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n, n_base, group_m, out_terms);
     return hipGetLastError();
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI>
-static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
-                              int out_terms, hipStream_t s) {
-    if (a_terms == 2) return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(A, W, out, M, N, K, out_terms, s);
-    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(A, W, out, M, N, K, out_terms, s);
+static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base, int n_cols,
+                              int a_terms, int out_terms, hipStream_t s) {
+    if (a_terms == 2)
+        return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(A, W, out, M, N, K, n_base, n_cols, out_terms, s);
+    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(A, W, out, M, N, K, n_base, n_cols, out_terms, s);
 }
 
 // Tile ids: 1 = 128x128 / 4 waves, 2 = 256x256 / 4 waves, 3 = 256x128 / 4 waves, 4 = 256x256 / 8 waves
@@ -231,17 +321,36 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
                              int out_terms, hipStream_t s) {
     int tile = g_gemm_tune.tile;
     if (tile == 0) {
-        long t256 = (long)((M + 255) / 256) * (N / 256);
-        tile = (N % 256 == 0 && t256 >= 192) ? 4 : 1;
+        // Wide outputs take 256x256 tiles, one workgroup per CU, in rounds of 256 tiles.  A last round
+        // that would be less than half full costs as much as a full one, so those columns are cut off
+        // and done by a second launch with 128x128 tiles (two workgroups per CU), which is shorter.
+        int tm = (M + 255) / 256, tn = N / 256;
+        long t256 = (long)tm * tn;
+        if (N % 256 != 0 || t256 < 192)
+            return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        long rounds = t256 / 256;
+        int n1 = tn;
+        if (rounds >= 1 && t256 - rounds * 256 > 0) {
+            int full = (int)(rounds * 256 / tm);             // tile columns that fill whole rounds
+            if ((long)(tn - full) * tm <= 128) n1 = full;
+        }
+        if (n1 > 0) {
+            hipError_t e = launch_tile<256, 256, 2, 4, 64, 2, EPI>(A, W, out, M, N, K, 0, n1 * 256, a_terms, out_terms, s);
+            if (e != hipSuccess) return e;
+        }
+        if (n1 < tn)
+            return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, n1 * 256, N - n1 * 256, a_terms,
+                                                           out_terms, s);
+        return hipSuccess;
     }
     if ((tile == 2 || tile == 4 || tile == 6) && N % 256 != 0) tile = 1;
     switch (tile) {
-        case 2: return launch_tile<256, 256, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-        case 3: return launch_tile<256, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-        case 4: return launch_tile<256, 256, 2, 4, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-        case 5: return launch_tile<128, 128, 2, 2, 32, 4, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-        case 6: return launch_tile<256, 256, 2, 4, 32, 4, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
-        default: return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, a_terms, out_terms, s);
+        case 2: return launch_tile<256, 256, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        case 3: return launch_tile<256, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        case 4: return launch_tile<256, 256, 2, 4, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        case 5: return launch_tile<128, 128, 2, 2, 32, 4, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        case 6: return launch_tile<256, 256, 2, 4, 32, 4, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        default: return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
     }
 }
 

@@ -364,6 +364,38 @@ def test_verdict_head_and_gate(dtype):
     cb.confspec_destroy(ctx)
 
 
+@pytest.mark.parametrize("epi", ["store", "resid", "swiglu"])
+def test_gemm_bf16_wide_output_split_into_two_launches(epi):
+    """Default tile choice on an output wide enough for 256x256 tiles whose last round of 256 tiles
+    would be nearly empty: the trailing columns go to a second launch with 128x128 tiles."""
+    print(f"gemm bf16 wide split {epi}", flush=True)
+    ctx, _ = _ctx("bf16")
+    cb.confspec_tune("gemm_tile", 0)
+    M, N, K = 700, 256 * 90, 128                      # 3 x 90 tiles of 256: one full round + 14 tiles
+    A = _rand((M, K), torch.bfloat16, 11)
+    Wt = _rand((N, K), torch.bfloat16, 12, 0.05)
+    ref = f64(A) @ f64(Wt).T
+    if epi == "swiglu":
+        F = N // 2
+        out = torch.zeros((M + 2, F), dtype=torch.bfloat16, device=DEV)
+        cb.confspec_op_gemm(ctx, A, Wt, out, M, N, K, cb.EPI_SWIGLU)
+        torch.cuda.synchronize()
+        r3 = ref.reshape(M, N // 64, 2, 32)           # packed layout: 32 gate columns, then their 32 up columns
+        want = (O.silu(r3[:, :, 0, :]) * r3[:, :, 1, :]).reshape(M, F)
+        err = np.abs(f64(out[:M]) - want)
+        assert np.all(err <= 2.0 ** -8 * np.abs(want) + 1e-4 * np.abs(want).max())
+        assert torch.all(out[M:] == 0)
+    else:
+        x0 = _rand((M + 2, N), torch.float32, 13)
+        x = x0.clone()
+        cb.confspec_op_gemm(ctx, A, Wt, x, M, N, K, cb.EPI_RESID_F32 if epi == "resid" else cb.EPI_STORE_F32)
+        torch.cuda.synchronize()
+        want = ref + (f64(x0[:M]) if epi == "resid" else 0.0)
+        assert np.abs(f64(x[:M]) - want).max() <= 2e-5 * max(np.abs(ref).max(), 4.0)
+        assert torch.equal(x[M:], x0[M:])
+    cb.confspec_destroy(ctx)
+
+
 def test_copy_kernel_is_exact():
     print("copy kernel", flush=True)
     n = (1 << 22) + 16 * 37                       # not a multiple of the grid's stride
