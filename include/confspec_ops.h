@@ -81,7 +81,8 @@ int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_
  * measurements: "gemm_tile" (0 heuristic, 1..6 = fixed workgroup tile / pipeline shape of the bf16 GEMM),
  * "gemm_group_m" (0 heuristic, else tile rows per band of the GEMM's tile order),
  * "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
- * "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = fixed key-range split factor).  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a
+ * "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = equal key-range pieces with that split factor,
+ * 5 = front-loaded pieces).  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a
  * value out of range. */
 int confspec_tune(const char *key, int32_t value);
 

@@ -16,6 +16,10 @@
 // consecutive keys per k-step: they are used as the B operand of O^T += V^T . P^T straight from
 // registers, and the matching A operand is a single 16-byte read of the transposed V tile.
 #include "kernels.h"
+#include <algorithm>
+#include <cmath>
+#include <queue>
+#include <vector>
 
 namespace cs {
 
@@ -42,148 +46,291 @@ void attn_set_tune(int target_items, int min_chunks) { g_target_items = target_i
 void attn_get_tune(int *target_items, int *min_chunks) { *target_items = g_target_items; *min_chunks = g_min_chunks; }
 
 // ---- planning: identical arithmetic on host (counts only) and device (counts + lists) ----
+// Every tile of a trace is cut into n_split pieces of `piece` chunks (the last piece takes what is
+// left and may be empty for the trace's shorter tiles).  Two ways to choose the pieces:
+//   equal pieces : n_split = ceil(nc / cpi), piece = ceil(nc / n_split);
+//   front-loaded : piece = cpi, so that the first pieces are long and a short remainder follows.
+// The item list is built per XCD (workgroup id % 8 selects the XCD, each XCD takes a contiguous range
+// of tiles so that the row tiles of one trace and kv head share an L2): first the first pieces of all
+// its tiles, then all the other pieces.  Workgroups are dispatched in id order, so the long pieces
+// start first and the short ones fill the gaps when slots free up (longest-first list scheduling).
+constexpr int ATTN_MAX_SPLIT = 32;
 struct TracePlan {
     int n_qt;      // q-row tiles per kv head
-    int n_split;   // key-range splits of every tile of this trace
+    int n_split;   // pieces of every tile of this trace
     int nc_max;    // chunks of the trace's last tile
+    int piece;     // chunks per piece
 };
-__host__ __device__ inline TracePlan trace_plan(int L, int S, int G, int cpi) {
+__host__ __device__ inline TracePlan trace_plan(int L, int S, int G, int cpi, int equalize) {
     TracePlan p;
     p.n_qt = S > 0 ? ceil_div(G * S, ATTN_BM) : 0;
     p.nc_max = ceil_div(L + S, ATTN_BN);
-    p.n_split = p.nc_max > cpi ? ceil_div(p.nc_max, cpi) : 1;
+    int n = p.nc_max > cpi ? ceil_div(p.nc_max, cpi) : 1;
+    bool clamped = n > ATTN_MAX_SPLIT;
+    p.n_split = clamped ? ATTN_MAX_SPLIT : n;
+    p.piece = (equalize || clamped) ? ceil_div(max(p.nc_max, 1), p.n_split) : cpi;
     return p;
 }
 __host__ __device__ inline int tile_chunks(int L, int S, int G, int m) {
     int r_last = min(m * ATTN_BM + ATTN_BM - 1, G * S - 1);
     return ceil_div(L + r_last / G + 1, ATTN_BN);
 }
+// XCD x takes the contiguous range of tiles [tile_lo[x], tile_lo[x+1]); the cuts are placed where the
+// running sum of chunks (every tile of a trace counted with the trace's longest) passes x/8 of the total.
+// A cut that falls inside (or at the end of) this trace's tiles is written here, together with the number
+// of items in front of it: the tiles before it plus their pieces other than the first.
+__host__ __device__ inline void plan_xcd_starts(const TracePlan &p, int Hkv, int tile_base, int rest_base,
+                                                long long work_base, long long work_total, int *tile_lo,
+                                                int *seg_base) {
+    int my_tiles = Hkv * p.n_qt;
+    if (my_tiles <= 0 || p.nc_max <= 0) return;
+    long long work_end = work_base + (long long)my_tiles * p.nc_max;
+    for (int x = 1; x < 8; ++x) {
+        long long target = (x * work_total + 7) / 8;
+        if (target > work_base && target <= work_end) {
+            int j = (int)((target - work_base + p.nc_max - 1) / p.nc_max);   // 1 .. my_tiles
+            tile_lo[x] = tile_base + j;
+            seg_base[x] = tile_base + j + rest_base + j * (p.n_split - 1);
+        }
+    }
+}
+
+// Tiles and items of one trace.  tile_base / rest_base / slot_base: tiles, pieces other than the first,
+// and partial slots of all earlier traces.
+__host__ __device__ inline void plan_emit_trace(int b, int L, int S, int G, int Hkv, const TracePlan &p, int tile_base,
+                                                int rest_base, int slot_base, const int *tile_lo, const int *seg_base,
+                                                int max_tiles, int max_items, AttnTile *tiles, AttnItem *items) {
+    for (int c = 0; c < Hkv; ++c)
+        for (int m = 0; m < p.n_qt; ++m) {
+            int local = c * p.n_qt + m;
+            int ti = tile_base + local;
+            int pbase = p.n_split > 1 ? slot_base + local * p.n_split : -1;
+            if (ti < max_tiles) {
+                AttnTile t;
+                t.b = b; t.c = c; t.row0 = m * ATTN_BM; t.part_base = pbase; t.n_splits = p.n_split;
+                t.pad[0] = t.pad[1] = t.pad[2] = 0;
+                tiles[ti] = t;
+            }
+            int x = 7;
+            while (x > 0 && tile_lo[x] > ti) --x;
+            int lo = tile_lo[x], hi = tile_lo[x + 1];
+            int rest_before = rest_base + local * (p.n_split - 1);   // other pieces of all earlier tiles
+            int rest_lo = seg_base[x] - lo;                          // the same count at the start of the range
+            int nc = tile_chunks(L, S, G, m);
+            for (int sp = 0; sp < p.n_split; ++sp) {
+                int idx = sp == 0 ? seg_base[x] + (ti - lo) : seg_base[x] + (hi - lo) + (rest_before - rest_lo) + sp - 1;
+                if (idx < 0 || idx >= max_items || pbase + sp >= max_items) continue;
+                AttnItem it;
+                it.b = b; it.c = c; it.row0 = m * ATTN_BM;
+                it.chunk_begin = min(sp * p.piece, nc);
+                it.chunk_end = sp == p.n_split - 1 ? nc : min((sp + 1) * p.piece, nc);
+                it.part_slot = p.n_split > 1 ? pbase + sp : -1;
+                it.tile = ti; it.pad = 0;
+                items[idx] = it;
+            }
+        }
+}
 
 void attn_plan_capacity(int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles, int64_t *max_items) {
     int64_t tiles = (int64_t)Hkv * ((G * max_T + ATTN_BM - 1) / ATTN_BM + max_B);
     *max_tiles = tiles;
-    *max_items = 3 * tiles + 4 * g_target_items;     // see the split rule in attn_plan_counts
+    *max_items = 3 * tiles + 4 * g_target_items;     // candidates that need more are not considered
 }
 
-// Split rule.  Every tile's key range is cut into pieces of at most `cpi` chunks.  cpi comes from a
-// uniform split factor s in 1..4 applied to the average tile: the estimated makespan on
-// `g_target_items` concurrent workgroups, ceil(tiles * s / slots) * (avg / s + 1) (+ 4 chunk-times for
-// the merge when s > 1), is minimised; s is limited so that tiles * s <= max(2 * tiles, 4 * slots).
-// Long tiles of a ragged batch then get proportionally more pieces than short ones.
+namespace {
+struct TraceShape { int tiles, nc; };
+struct Candidate { int cpi, equalize; };
+
+// Items, partial slots and the largest per-XCD item count of a candidate; lens (optional) receives the
+// per-XCD piece lengths in dispatch order.  Same arithmetic as the device planner.
+void candidate_counts(const std::vector<TraceShape> &tr, Candidate cd, int64_t n_tiles, int64_t work_total,
+                      AttnPlanCounts *r, std::vector<int> *lens /* [8] */) {
+    r->n_items = 0; r->n_part_slots = 0; r->max_xcd_items = 0;
+    int tile_lo[9] = {0}, seg_base[9] = {0};
+    int tile_base = 0, rest_base = 0;
+    long long work_base = 0;
+    std::vector<TracePlan> plans;
+    plans.reserve(tr.size());
+    for (const TraceShape &t : tr) {
+        TracePlan p;
+        p.n_qt = t.tiles; p.nc_max = t.nc;       // n_qt holds Hkv * n_qt here (Hkv = 1 below)
+        int n = t.nc > cd.cpi ? ceil_div(t.nc, cd.cpi) : 1;
+        bool clamped = n > ATTN_MAX_SPLIT;
+        p.n_split = clamped ? ATTN_MAX_SPLIT : n;
+        p.piece = (cd.equalize || clamped) ? ceil_div(std::max(t.nc, 1), p.n_split) : cd.cpi;
+        plans.push_back(p);
+        plan_xcd_starts(p, 1, tile_base, rest_base, work_base, work_total, tile_lo, seg_base);
+        r->n_items += (int64_t)t.tiles * p.n_split;
+        if (p.n_split > 1) r->n_part_slots += (int64_t)t.tiles * p.n_split;
+        tile_base += t.tiles; rest_base += t.tiles * (p.n_split - 1);
+        work_base += (long long)t.tiles * t.nc;
+    }
+    tile_lo[8] = (int)n_tiles;
+    seg_base[8] = (int)r->n_items;
+    for (int x = 0; x < 8; ++x) r->max_xcd_items = std::max<int64_t>(r->max_xcd_items, seg_base[x + 1] - seg_base[x]);
+    if (!lens) return;
+    std::vector<int> rest_lens[8];
+    int ti = 0;
+    for (size_t i = 0; i < tr.size(); ++i)
+        for (int j = 0; j < tr[i].tiles; ++j, ++ti) {
+            int x = 7;
+            while (x > 0 && tile_lo[x] > ti) --x;
+            const TracePlan &p = plans[i];
+            lens[x].push_back(std::min(p.piece, p.nc_max));
+            for (int sp = 1; sp < p.n_split; ++sp)
+                rest_lens[x].push_back(std::max(0, std::min(p.piece, p.nc_max - sp * p.piece)));
+        }
+    for (int x = 0; x < 8; ++x) lens[x].insert(lens[x].end(), rest_lens[x].begin(), rest_lens[x].end());
+}
+
+// Makespan of longest-first list scheduling on slots/8 workgroup slots per XCD, in chunk-times.
+double simulate(const std::vector<int> *lens, int slots) {
+    int per_xcd = std::max(1, slots / 8);
+    double worst = 0;
+    for (int x = 0; x < 8; ++x) {
+        std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+        for (int i = 0; i < per_xcd; ++i) free_at.push(0.0);
+        double end = 0;
+        for (int len : lens[x]) {
+            double t0 = free_at.top();
+            free_at.pop();
+            double t1 = t0 + len + 1.5;          // 1.5: loading q, writing the result
+            free_at.push(t1);
+            end = std::max(end, t1);
+        }
+        worst = std::max(worst, end);
+    }
+    return worst;
+}
+}  // namespace
+
+// Choice of the pieces: equal pieces with a split factor 1..4 of the average tile, or front-loaded
+// pieces of 1.07x / 1.2x the per-slot share of all chunks; the candidate with the smallest simulated
+// makespan (+ 8 chunk-times for the merge pass when anything is split) wins.
 AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv) {
     AttnPlanCounts r = {};
+    std::vector<TraceShape> tr;
+    tr.reserve(B);
     int64_t total = 0, n_tiles = 0;
+    int nc_longest = 0;
     for (int b = 0; b < B; ++b) {
         int S = h_cu[b + 1] - h_cu[b], L = h_plens[b];
-        TracePlan p = trace_plan(L, S, G, 1 << 30);
+        TracePlan p = trace_plan(L, S, G, 1 << 30, 1);
+        tr.push_back({Hkv * p.n_qt, p.nc_max});
         total += (int64_t)Hkv * p.n_qt * p.nc_max;
         n_tiles += (int64_t)Hkv * p.n_qt;
+        if (p.n_qt > 0) nc_longest = std::max(nc_longest, p.nc_max);
     }
+    r.n_tiles = n_tiles;
+    r.total_chunks = total;
     double avg = n_tiles > 0 ? (double)total / (double)n_tiles : 1.0;
     int64_t slots = g_target_items;
-    int best_s = 1;
+    int64_t cap_items = 3 * n_tiles + 4 * slots;
+    std::vector<Candidate> cands;
+    auto equal_cpi = [&](int sp) { return sp == 1 ? (1 << 30) : std::max<int>(g_min_chunks, (int)((avg + sp - 1) / sp)); };
+    auto front_cpi = [&](double f) { return std::max<int>(g_min_chunks, (int)std::ceil(f * (double)total / (double)slots)); };
+    if (g_force_split >= 1 && g_force_split <= 4) cands.push_back({equal_cpi(g_force_split), 1});
+    else if (g_force_split == 5) cands.push_back({front_cpi(1.07), 0});
+    else {
+        for (int sp = 1; sp <= 4; ++sp) {
+            if (sp > 1 && avg / sp < g_min_chunks) break;
+            cands.push_back({equal_cpi(sp), 1});
+        }
+        for (double f : {1.07, 1.2})
+            if (front_cpi(f) < nc_longest) cands.push_back({front_cpi(f), 0});
+    }
     double best = 1e300;
-    for (int sp = 1; sp <= 4; ++sp) {
-        if (sp > 1 && n_tiles * sp > (2 * n_tiles > 4 * slots ? 2 * n_tiles : 4 * slots)) break;
-        if (sp > 1 && avg / sp < g_min_chunks) break;
-        double rounds = (double)((n_tiles * sp + slots - 1) / slots);
-        double est = rounds * (avg / sp + 1.0) + (sp > 1 ? 4.0 : 0.0);
-        if (est < best) { best = est; best_s = sp; }
+    Candidate pick = {1 << 30, 1};
+    for (size_t i = 0; i < cands.size(); ++i) {
+        AttnPlanCounts c = {};
+        std::vector<int> lens[8];
+        candidate_counts(tr, cands[i], n_tiles, total, &c, lens);
+        if (c.n_items > cap_items && cands.size() > 1 && cands[i].cpi != (1 << 30)) continue;
+        double est = simulate(lens, (int)slots) + (c.n_part_slots > 0 ? 8.0 : 0.0);
+        if (est < best) { best = est; pick = cands[i]; }
     }
-    if (g_force_split > 0) best_s = g_force_split;
-    int64_t cpi = (int64_t)((avg + best_s - 1) / best_s);
-    if (best_s == 1) cpi = 1 << 30;            // no splitting at all
-    if (cpi < g_min_chunks) cpi = g_min_chunks;
-    r.chunks_per_item = (int32_t)(cpi > (1 << 30) ? (1 << 30) : cpi);
-    r.total_chunks = total;
-    for (int b = 0; b < B; ++b) {
-        int S = h_cu[b + 1] - h_cu[b], L = h_plens[b];
-        TracePlan p = trace_plan(L, S, G, r.chunks_per_item);
-        int64_t tiles = (int64_t)Hkv * p.n_qt;
-        r.n_tiles += tiles;
-        r.n_items += tiles * p.n_split;
-        if (p.n_split > 1) r.n_part_slots += tiles * p.n_split;
-    }
+    r.chunks_per_item = pick.cpi;
+    r.equalize = pick.equalize;
+    candidate_counts(tr, pick, n_tiles, total, &r, nullptr);
     return r;
 }
 
+// counts[0] = tiles, counts[1] = items, counts[2 + x] = first item of XCD x (x = 0..8; [10] = items)
 __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restrict__ cu,
                                                          const int32_t *__restrict__ plens, int B, int T, int max_L,
-                                                         int G, int Hkv, int cpi, int max_tiles, int max_items,
-                                                         AttnTile *__restrict__ tiles, AttnItem *__restrict__ items,
-                                                         int32_t *__restrict__ counts) {
-    __shared__ int s_tiles[257], s_items[257], s_slots[257];
+                                                         int G, int Hkv, int cpi, int equalize, int max_tiles,
+                                                         int max_items, AttnTile *__restrict__ tiles,
+                                                         AttnItem *__restrict__ items, int32_t *__restrict__ counts) {
+    __shared__ int s_tiles[257], s_rest[257], s_slots[257];
+    __shared__ long long s_work[257];
     __shared__ int carry[3];
+    __shared__ long long carry_work;
+    __shared__ int tile_lo[9], seg_base[9];
     int tid = threadIdx.x;
-    if (tid == 0) carry[0] = carry[1] = carry[2] = 0;
-    __syncthreads();
-    for (int base = 0; base < B; base += 256) {
-        int b = base + tid;
-        int L = 0, S = 0;
-        TracePlan p = {0, 1, 0};
-        if (b < B) {
-            int c0 = min(max(cu[b], 0), T), c1 = min(max(cu[b + 1], 0), T);
-            S = max(c1 - c0, 0);
-            L = min(max(plens[b], 0), max_L);
-            p = trace_plan(L, S, G, cpi);
-        }
-        int my_tiles = Hkv * p.n_qt, my_items = my_tiles * p.n_split;
-        s_tiles[tid + 1] = my_tiles;
-        s_items[tid + 1] = my_items;
-        s_slots[tid + 1] = p.n_split > 1 ? my_items : 0;
+    // pass 0 adds up tiles and chunks (the XCD cuts depend on the totals), pass 1 places the cuts and
+    // finds where each XCD's items start, pass 2 writes the lists
+    long long work_total = 0;
+    for (int pass = 0; pass < 3; ++pass) {
+        if (tid == 0) { carry[0] = carry[1] = carry[2] = 0; carry_work = 0; }
         __syncthreads();
-        if (tid == 0) {  // serial exclusive scan of at most 256 entries
-            s_tiles[0] = carry[0];
-            s_items[0] = carry[1];
-            s_slots[0] = carry[2];
-            for (int i = 1; i <= 256; ++i) {
-                s_tiles[i] += s_tiles[i - 1];
-                s_items[i] += s_items[i - 1];
-                s_slots[i] += s_slots[i - 1];
+        for (int base = 0; base < B; base += 256) {
+            int b = base + tid;
+            int L = 0, S = 0;
+            TracePlan p = {0, 1, 0, 1};
+            if (b < B) {
+                int c0 = min(max(cu[b], 0), T), c1 = min(max(cu[b + 1], 0), T);
+                S = max(c1 - c0, 0);
+                L = min(max(plens[b], 0), max_L);
+                p = trace_plan(L, S, G, cpi, equalize);
             }
-        }
-        __syncthreads();
-        int tile_base = s_tiles[tid], item_base = s_items[tid], slot_base = s_slots[tid];
-        if (b < B) {
-            for (int c = 0; c < Hkv; ++c)
-                for (int m = 0; m < p.n_qt; ++m) {
-                    int ti = tile_base + c * p.n_qt + m;
-                    int pbase = p.n_split > 1 ? slot_base + (c * p.n_qt + m) * p.n_split : -1;
-                    if (ti < max_tiles) {
-                        AttnTile t;
-                        t.b = b; t.c = c; t.row0 = m * ATTN_BM; t.part_base = pbase; t.n_splits = p.n_split;
-                        t.pad[0] = t.pad[1] = t.pad[2] = 0;
-                        tiles[ti] = t;
-                    }
-                    int nc = tile_chunks(L, S, G, m);
-                    for (int sp = 0; sp < p.n_split; ++sp) {
-                        int idx = item_base + (c * p.n_split + sp) * p.n_qt + m;
-                        if (idx >= max_items || pbase + sp >= max_items) continue;
-                        AttnItem it;
-                        it.b = b; it.c = c; it.row0 = m * ATTN_BM;
-                        it.chunk_begin = (int)(((long)sp * nc) / p.n_split);
-                        it.chunk_end = (int)(((long)(sp + 1) * nc) / p.n_split);
-                        it.part_slot = p.n_split > 1 ? pbase + sp : -1;
-                        it.tile = ti; it.pad = 0;
-                        items[idx] = it;
-                    }
+            int my_tiles = Hkv * p.n_qt;
+            s_tiles[tid + 1] = my_tiles;
+            s_rest[tid + 1] = my_tiles * (p.n_split - 1);
+            s_slots[tid + 1] = p.n_split > 1 ? my_tiles * p.n_split : 0;
+            s_work[tid + 1] = (long long)my_tiles * p.nc_max;
+            __syncthreads();
+            if (tid == 0) {  // serial exclusive scan of at most 256 entries
+                s_tiles[0] = carry[0];
+                s_rest[0] = carry[1];
+                s_slots[0] = carry[2];
+                s_work[0] = carry_work;
+                for (int i = 1; i <= 256; ++i) {
+                    s_tiles[i] += s_tiles[i - 1];
+                    s_rest[i] += s_rest[i - 1];
+                    s_slots[i] += s_slots[i - 1];
+                    s_work[i] += s_work[i - 1];
                 }
+            }
+            __syncthreads();
+            int tile_base = s_tiles[tid], rest_base = s_rest[tid], slot_base = s_slots[tid];
+            if (pass == 1 && b < B)
+                plan_xcd_starts(p, Hkv, tile_base, rest_base, s_work[tid], work_total, tile_lo, seg_base);
+            if (pass == 2 && b < B)
+                plan_emit_trace(b, L, S, G, Hkv, p, tile_base, rest_base, slot_base, tile_lo, seg_base, max_tiles,
+                                max_items, tiles, items);
+            __syncthreads();
+            if (tid == 0) { carry[0] = s_tiles[256]; carry[1] = s_rest[256]; carry[2] = s_slots[256]; carry_work = s_work[256]; }
+            __syncthreads();
         }
-        __syncthreads();
-        if (tid == 0) { carry[0] = s_tiles[256]; carry[1] = s_items[256]; carry[2] = s_slots[256]; }
+        if (pass == 0) {
+            work_total = carry_work;
+            if (tid < 9) { tile_lo[tid] = 0; seg_base[tid] = 0; }
+        }
+        if (pass == 1 && tid == 0) { tile_lo[8] = carry[0]; seg_base[8] = carry[0] + carry[1]; }
         __syncthreads();
     }
     if (tid == 0) {
         counts[0] = min(carry[0], max_tiles);
-        counts[1] = min(carry[1], max_items);
+        counts[1] = min(carry[0] + carry[1], max_items);
     }
+    if (tid < 9) counts[2 + tid] = min(seg_base[tid], max_items);
 }
 
 hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int T, int max_L, int G, int Hkv,
-                            int chunks_per_item, int max_tiles, int max_items, AttnTile *tiles, AttnItem *items,
-                            int32_t *counts, hipStream_t s) {
-    attn_plan_kernel<<<1, 256, 0, s>>>(cu, plens, B, T, max_L, G, Hkv, chunks_per_item, max_tiles, max_items, tiles,
-                                       items, counts);
+                            int chunks_per_item, int equalize, int max_tiles, int max_items, AttnTile *tiles,
+                            AttnItem *items, int32_t *counts, hipStream_t s) {
+    attn_plan_kernel<<<1, 256, 0, s>>>(cu, plens, B, T, max_L, G, Hkv, chunks_per_item, equalize, max_tiles,
+                                       max_items, tiles, items, counts);
     return hipGetLastError();
 }
 
@@ -201,10 +348,11 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
     constexpr int STAGE = PRECISE ? 2 * ATTN_STAGE : ATTN_STAGE;   // PRECISE: [K | Vt | K_lo | Vt_lo]
 
+    // workgroup id % 8 is the XCD; each XCD walks its own range of the item list in order
     int n_items = min(counts[1], n_items_host);
-    int per = gridDim.x >> 3;  // grid is a multiple of 8: one contiguous item range per XCD
-    int it_idx = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-    if (it_idx >= n_items) return;
+    int xcd = blockIdx.x & 7;
+    int it_idx = counts[2 + xcd] + (blockIdx.x >> 3);
+    if (it_idx >= min(counts[3 + xcd], n_items)) return;
     AttnItem item = items[it_idx];
 
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -581,7 +729,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnT
 
 template <bool PRECISE>
 static hipError_t launch_attn_variant(const AttnArgs &a, const AttnItem *items, const int32_t *counts, int n_items_host,
-                                      float *part_o, float *part_ml, hipStream_t s) {
+                                      int max_xcd_items, float *part_o, float *part_ml, hipStream_t s) {
     constexpr int smem = PRECISE ? 2 * ATTN_SMEM_BYTES : ATTN_SMEM_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
@@ -590,18 +738,18 @@ static hipError_t launch_attn_variant(const AttnArgs &a, const AttnItem *items, 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    int grid = ((n_items_host + 7) / 8) * 8;
+    int grid = 8 * max_xcd_items;
     attn_bf16_kernel<PRECISE><<<grid, ATTN_THREADS, smem, s>>>(a, items, counts, n_items_host, part_o, part_ml);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
-                            int n_items_host, int n_tiles_host, bool any_split, float *part_o, float *part_ml,
-                            hipStream_t s) {
-    if (n_items_host <= 0) return hipSuccess;
+                            int n_items_host, int max_xcd_items, int n_tiles_host, bool any_split, float *part_o,
+                            float *part_ml, hipStream_t s) {
+    if (n_items_host <= 0 || max_xcd_items <= 0) return hipSuccess;
     bool precise = a.q_lo && a.ksuf_lo && a.vsuf_lo;
-    hipError_t e = precise ? launch_attn_variant<true>(a, items, counts, n_items_host, part_o, part_ml, s)
-                           : launch_attn_variant<false>(a, items, counts, n_items_host, part_o, part_ml, s);
+    hipError_t e = precise ? launch_attn_variant<true>(a, items, counts, n_items_host, max_xcd_items, part_o, part_ml, s)
+                           : launch_attn_variant<false>(a, items, counts, n_items_host, max_xcd_items, part_o, part_ml, s);
     if (e != hipSuccess) return e;
     if (any_split)
         attn_merge_kernel<<<n_tiles_host * (ATTN_BM / 8), 256, 0, s>>>(a, tiles, counts, n_tiles_host, part_o, part_ml);

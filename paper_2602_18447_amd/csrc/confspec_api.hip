@@ -214,7 +214,8 @@ int run_attention(confspec_ctx *ctx, const cs::AttnArgs &a, char *ws, const WsLa
         HIP_TRY(cs::launch_attn_f32(a, (const int32_t *)(ws + L.tok_trace), (const int32_t *)(ws + L.tok_pos), s));
     } else {
         HIP_TRY(cs::launch_attn_bf16(a, (const cs::AttnItem *)(ws + L.plan_items), (const cs::AttnTile *)(ws + L.plan_tiles),
-                                     (const int32_t *)(ws + L.plan_counts), (int)pc.n_items, (int)pc.n_tiles, pc.n_part_slots > 0,
+                                     (const int32_t *)(ws + L.plan_counts), (int)pc.n_items, (int)pc.max_xcd_items, (int)pc.n_tiles,
+                                     pc.n_part_slots > 0,
                                      (float *)(ws + L.part_o), (float *)(ws + L.part_ml), s));
     }
     return CONFSPEC_OK;
@@ -234,7 +235,7 @@ int run_plan(confspec_ctx *ctx, const confspec_batch *b, int max_L, char *ws, co
             return fail(ctx, CONFSPEC_E_WORKSPACE, "attention plan (%lld tiles, %lld items) exceeds workspace capacity",
                         (long long)pc->n_tiles, (long long)pc->n_items);
         HIP_TRY(cs::launch_attn_plan(b->cu_suffix, b->prefix_lens, b->B, b->T, max_L, G, c.n_kv_heads,
-                                     pc->chunks_per_item, (int)L.max_tiles, (int)L.max_items,
+                                     pc->chunks_per_item, pc->equalize, (int)L.max_tiles, (int)L.max_items,
                                      (cs::AttnTile *)(ws + L.plan_tiles), (cs::AttnItem *)(ws + L.plan_items),
                                      (int32_t *)(ws + L.plan_counts), s));
     }
@@ -526,7 +527,7 @@ int confspec_tune(const char *key, int32_t value) {
         if (value < 1 || value > 65536) return CONFSPEC_E_INVALID_ARG;
         cs::attn_set_tune(value, mc);
     } else if (!strcmp(key, "attn_split")) {
-        if (value < 0 || value > 4) return CONFSPEC_E_INVALID_ARG;
+        if (value < 0 || value > 5) return CONFSPEC_E_INVALID_ARG;
         cs::attn_set_split(value);
     } else if (!strcmp(key, "attn_min_chunks")) {
         if (value < 1 || value > 4096) return CONFSPEC_E_INVALID_ARG;

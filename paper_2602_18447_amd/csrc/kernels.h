@@ -37,7 +37,9 @@ constexpr int ATTN_MIN_CHUNKS_PER_ITEM = 8;
 // Host-side mirror of the planner's counting pass (same arithmetic as the device code).
 struct AttnPlanCounts {
     int64_t n_tiles, n_items, n_part_slots, total_chunks;
+    int64_t max_xcd_items;      // largest number of items any of the 8 XCDs gets
     int32_t chunks_per_item;
+    int32_t equalize;           // 1: equal pieces per tile, 0: pieces of chunks_per_item, remainder last
 };
 AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv);
 // Upper bounds used to size the workspace.
@@ -104,10 +106,11 @@ struct AttnArgs {
 hipError_t launch_attn_f32(const AttnArgs &a, const int32_t *tok_trace, const int32_t *tok_pos, hipStream_t s);
 
 hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int T, int max_L, int G, int Hkv,
-                            int chunks_per_item, int max_tiles, int max_items, AttnTile *tiles, AttnItem *items,
-                            int32_t *counts /*[2]: n_tiles, n_items*/, hipStream_t s);
-hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
-                            int n_items_host, int n_tiles_host, bool any_split, float *part_o, float *part_ml,
+                            int chunks_per_item, int equalize, int max_tiles, int max_items, AttnTile *tiles,
+                            AttnItem *items, int32_t *counts /*[11]: tiles, items, first item of XCD 0..8*/,
                             hipStream_t s);
+hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
+                            int n_items_host, int max_xcd_items, int n_tiles_host, bool any_split, float *part_o,
+                            float *part_ml, hipStream_t s);
 
 }  // namespace cs

@@ -308,18 +308,23 @@ def test_attention_bf16_two_term_operands(prefix_lens, suffix_lens):
     assert err5 <= 2e-4
 
 
-def test_attention_bf16_split_kv_merge_matches_unsplit():
-    """Force many key-range splits: the merged result must meet the same bound."""
-    print("attention bf16 forced splits", flush=True)
+@pytest.mark.parametrize("split", [0, 2, 3, 4, 5])
+def test_attention_bf16_split_kv_merge_matches_unsplit(split):
+    """Force many key-range pieces (planner's choice, equal pieces, front-loaded pieces): the merged
+    result must meet the same bound as the unsplit one."""
+    print(f"attention bf16 forced splits, mode {split}", flush=True)
     cb.confspec_tune("attn_min_chunks", 1)
     cb.confspec_tune("attn_target_items", 1024)
+    cb.confspec_tune("attn_split", split)
     try:
         err = _attention_case("bf16", 12, 2, 128, (700, 64, 0, 3000), (40, 96, 20, 7))
         err2 = _attention_case("bf16", 12, 2, 128, (700, 64, 0, 3000), (40, 96, 20, 7), out_terms=2)
-        assert err2 <= 6e-3
+        err3 = _attention_case("bf16", 8, 8, 128, (130, 2500, 17, 900, 64, 1, 333, 1200, 5), (33, 5, 129, 64, 1, 200, 16, 77, 250))
+        assert err2 <= 6e-3 and err3 <= 6e-3
     finally:
         cb.confspec_tune("attn_min_chunks", 8)
         cb.confspec_tune("attn_target_items", 512)
+        cb.confspec_tune("attn_split", 0)
     print("  max abs err", err, flush=True)
     assert err <= 6e-3
 
