@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="workload: 2 (default, the metric's config), 3, 4 or 5")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP-graph replays")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="confspec_tune setting applied before the run (repeatable), for measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the plain copy kernel (1 GiB, 5 times): the yardstick for HBM byte counters")
     ap.add_argument("--cpu-baseline-traces", type=int, default=6,
@@ -80,6 +82,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dev = "cuda:0"
+    for kv_ in args.tune:
+        key, _, val = kv_.partition("=")
+        cb.confspec_tune(key, int(val))
     wl = W.config(args.config)
     m = wl.model
     weights = W.make_weights(m, wl.seed, dev)
@@ -214,7 +219,8 @@ def main():
         "dtype": m.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "T": wl.T, "sum_prefix_len": int(sum(wl.prefix_lens)),
                    "layers": m.n_layers, "d_model": m.d_model, "taus": taus, "accept_counts": accept_counts,
-                   "launch": "hip_graph_replay" if graph_ok else "eager", "eager_ms_per_step": round(eager_ms, 4)},
+                   "launch": "hip_graph_replay" if graph_ok else "eager", "eager_ms_per_step": round(eager_ms, 4),
+                   **({"tune": args.tune} if args.tune else {})},
         "roofline": roofline, "cpu_baseline": cpu, **({"copy_calibration": copy_info} if copy_info else {}),
     }))
 

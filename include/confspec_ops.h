@@ -30,10 +30,16 @@ extern "C" {
 /* C[M,N] = A[M,K] . W[N,K]^T with one of the epilogues above.  A ([M, a_terms*K]) and W are dev
  * arrays of the context's dtype (row-major, K contiguous).  Requires N % 128 == 0 and K % 64 == 0 for
  * bf16, N % 64 == 0 and K % 16 == 0 for fp32; any M >= 1.  out_terms == 2 is valid with the SwiGLU
- * epilogue only (out is then [M, 2 * N/2]). */
+ * epilogue only (out is then [M, 2 * N/2]).  dev_scratch (may be NULL) is dev memory the call may use for
+ * partial products: with at least confspec_op_gemm_scratch_bytes() bytes a bf16 GEMM with M <= 128 cuts
+ * the k range into slices that run as separate workgroups and are added in a fixed order; without it
+ * such a GEMM runs one workgroup per 128 output columns.  16-byte aligned. */
 int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, void *dev_out, int32_t M,
                      int32_t N, int32_t K, int32_t epilogue, int32_t a_terms, int32_t out_terms,
-                     confspec_stream stream);
+                     void *dev_scratch, size_t scratch_bytes, confspec_stream stream);
+
+/* Scratch bytes with which confspec_op_gemm takes its split-K path for this shape (0: it never does). */
+size_t confspec_op_gemm_scratch_bytes(const confspec_ctx *ctx, int32_t M, int32_t N, int32_t K, int32_t a_terms);
 
 /* out[t,:] = x[t,:] / sqrt(mean(x[t,:]^2) + rms_eps) * g, x fp32 [n_rows, d_model], g in the context's
  * dtype, out [n_rows, out_terms * d_model] in the context's dtype. */
@@ -77,7 +83,9 @@ int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_
 
 /* Process-wide settings.  "split_layers": number of leading layers in which confspec_verify carries
  * the GEMM activations as two bf16 terms (default -1 = ceil(n_layers / 7), doubled when d_model > 4096).  "attn_precise_layers"
- * (default 1): number of leading layers whose attention runs the two-term variant.  Launch-shape tunables for
+ * (default 1): number of leading layers whose attention runs the two-term variant.  "prune_last_layer" (default 1):
+ * in the last layer, compute attention rows, output projection and MLP for the last position of each trace only
+ * (the only rows the verdict head reads; 0 computes every row).  Launch-shape tunables for
  * measurements: "gemm_tile" (0 heuristic, 1..6 = fixed workgroup tile / pipeline shape of the bf16 GEMM),
  * "gemm_group_m" (0 heuristic, else tile rows per band of the GEMM's tile order),
  * "attn_target_items" (concurrent workgroup slots assumed by the attention planner),

@@ -75,7 +75,9 @@ def _load() -> C.CDLL:
     lib.confspec_verify.argtypes = [vp, P(Weights), P(KV), P(Batch), P(i32), i32, P(C.c_float), i32, vp, sz,
                                     vp, vp, vp, vp, vp]
     lib.confspec_op_gemm.restype = C.c_int
-    lib.confspec_op_gemm.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
+    lib.confspec_op_gemm.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, sz, vp]
+    lib.confspec_op_gemm_scratch_bytes.restype = sz
+    lib.confspec_op_gemm_scratch_bytes.argtypes = [vp, i32, i32, i32, i32]
     lib.confspec_op_rmsnorm.restype = C.c_int
     lib.confspec_op_rmsnorm.argtypes = [vp, vp, vp, vp, i32, i32, vp]
     lib.confspec_op_rope_split.restype = C.c_int
@@ -96,7 +98,7 @@ lib = _load()
 
 EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec_last_error",
             "confspec_workspace_bytes", "confspec_packed_bytes", "confspec_pack_weights", "confspec_verify",
-            "confspec_op_gemm", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_attention",
+            "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_attention",
             "confspec_op_verdict_gate", "confspec_op_copy", "confspec_tune"]
 
 
@@ -178,9 +180,14 @@ def confspec_verify(ctx, w: Weights, kv: KV, batch: Batch, verdict_ids: Sequence
 
 
 def confspec_op_gemm(ctx, A, W, out, M: int, N: int, K: int, epilogue: int, a_terms: int = 1, out_terms: int = 1,
-                     stream=None) -> None:
+                     scratch=None, stream=None) -> None:
+    nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
     _check(ctx, lib.confspec_op_gemm(ctx, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, a_terms, out_terms,
-                                     _stream_handle(stream)))
+                                     _ptr(scratch), nbytes, _stream_handle(stream)))
+
+
+def confspec_op_gemm_scratch_bytes(ctx, M: int, N: int, K: int, a_terms: int = 1) -> int:
+    return int(lib.confspec_op_gemm_scratch_bytes(ctx, M, N, K, a_terms))
 
 
 def confspec_op_rmsnorm(ctx, x, g, out, n_rows: int, out_terms: int = 1, stream=None) -> None:

@@ -61,9 +61,11 @@ struct TracePlan {
     int nc_max;    // chunks of the trace's last tile
     int piece;     // chunks per piece
 };
-__host__ __device__ inline TracePlan trace_plan(int L, int S, int G, int cpi, int equalize) {
+// last_only: the plan covers the last suffix position of each trace only (its G rows per kv head form
+// one tile that starts at row (S-1)*G), which is all the last decoder layer has to produce.
+__host__ __device__ inline TracePlan trace_plan(int L, int S, int G, int cpi, int equalize, int last_only) {
     TracePlan p;
-    p.n_qt = S > 0 ? ceil_div(G * S, ATTN_BM) : 0;
+    p.n_qt = S > 0 ? (last_only ? 1 : ceil_div(G * S, ATTN_BM)) : 0;
     p.nc_max = ceil_div(L + S, ATTN_BN);
     int n = p.nc_max > cpi ? ceil_div(p.nc_max, cpi) : 1;
     bool clamped = n > ATTN_MAX_SPLIT;
@@ -99,15 +101,17 @@ __host__ __device__ inline void plan_xcd_starts(const TracePlan &p, int Hkv, int
 // and partial slots of all earlier traces.
 __host__ __device__ inline void plan_emit_trace(int b, int L, int S, int G, int Hkv, const TracePlan &p, int tile_base,
                                                 int rest_base, int slot_base, const int *tile_lo, const int *seg_base,
-                                                int max_tiles, int max_items, AttnTile *tiles, AttnItem *items) {
+                                                int last_only, int max_tiles, int max_items, AttnTile *tiles,
+                                                AttnItem *items) {
     for (int c = 0; c < Hkv; ++c)
         for (int m = 0; m < p.n_qt; ++m) {
             int local = c * p.n_qt + m;
             int ti = tile_base + local;
             int pbase = p.n_split > 1 ? slot_base + local * p.n_split : -1;
+            int row0 = last_only ? (S - 1) * G : m * ATTN_BM;
             if (ti < max_tiles) {
                 AttnTile t;
-                t.b = b; t.c = c; t.row0 = m * ATTN_BM; t.part_base = pbase; t.n_splits = p.n_split;
+                t.b = b; t.c = c; t.row0 = row0; t.part_base = pbase; t.n_splits = p.n_split;
                 t.pad[0] = t.pad[1] = t.pad[2] = 0;
                 tiles[ti] = t;
             }
@@ -116,12 +120,12 @@ __host__ __device__ inline void plan_emit_trace(int b, int L, int S, int G, int 
             int lo = tile_lo[x], hi = tile_lo[x + 1];
             int rest_before = rest_base + local * (p.n_split - 1);   // other pieces of all earlier tiles
             int rest_lo = seg_base[x] - lo;                          // the same count at the start of the range
-            int nc = tile_chunks(L, S, G, m);
+            int nc = last_only ? p.nc_max : tile_chunks(L, S, G, m);
             for (int sp = 0; sp < p.n_split; ++sp) {
                 int idx = sp == 0 ? seg_base[x] + (ti - lo) : seg_base[x] + (hi - lo) + (rest_before - rest_lo) + sp - 1;
                 if (idx < 0 || idx >= max_items || pbase + sp >= max_items) continue;
                 AttnItem it;
-                it.b = b; it.c = c; it.row0 = m * ATTN_BM;
+                it.b = b; it.c = c; it.row0 = row0;
                 it.chunk_begin = min(sp * p.piece, nc);
                 it.chunk_end = sp == p.n_split - 1 ? nc : min((sp + 1) * p.piece, nc);
                 it.part_slot = p.n_split > 1 ? pbase + sp : -1;
@@ -207,7 +211,7 @@ double simulate(const std::vector<int> *lens, int slots) {
 // Choice of the pieces: equal pieces with a split factor 1..4 of the average tile, or front-loaded
 // pieces of 1.07x / 1.2x the per-slot share of all chunks; the candidate with the smallest simulated
 // makespan (+ 8 chunk-times for the merge pass when anything is split) wins.
-AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv) {
+AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv, int last_only) {
     AttnPlanCounts r = {};
     std::vector<TraceShape> tr;
     tr.reserve(B);
@@ -215,7 +219,7 @@ AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int
     int nc_longest = 0;
     for (int b = 0; b < B; ++b) {
         int S = h_cu[b + 1] - h_cu[b], L = h_plens[b];
-        TracePlan p = trace_plan(L, S, G, 1 << 30, 1);
+        TracePlan p = trace_plan(L, S, G, 1 << 30, 1, last_only);
         tr.push_back({Hkv * p.n_qt, p.nc_max});
         total += (int64_t)Hkv * p.n_qt * p.nc_max;
         n_tiles += (int64_t)Hkv * p.n_qt;
@@ -258,8 +262,8 @@ AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int
 // counts[0] = tiles, counts[1] = items, counts[2 + x] = first item of XCD x (x = 0..8; [10] = items)
 __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restrict__ cu,
                                                          const int32_t *__restrict__ plens, int B, int T, int max_L,
-                                                         int G, int Hkv, int cpi, int equalize, int max_tiles,
-                                                         int max_items, AttnTile *__restrict__ tiles,
+                                                         int G, int Hkv, int cpi, int equalize, int last_only,
+                                                         int max_tiles, int max_items, AttnTile *__restrict__ tiles,
                                                          AttnItem *__restrict__ items, int32_t *__restrict__ counts) {
     __shared__ int s_tiles[257], s_rest[257], s_slots[257];
     __shared__ long long s_work[257];
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
                 int c0 = min(max(cu[b], 0), T), c1 = min(max(cu[b + 1], 0), T);
                 S = max(c1 - c0, 0);
                 L = min(max(plens[b], 0), max_L);
-                p = trace_plan(L, S, G, cpi, equalize);
+                p = trace_plan(L, S, G, cpi, equalize, last_only);
             }
             int my_tiles = Hkv * p.n_qt;
             s_tiles[tid + 1] = my_tiles;
@@ -306,8 +310,8 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
             if (pass == 1 && b < B)
                 plan_xcd_starts(p, Hkv, tile_base, rest_base, s_work[tid], work_total, tile_lo, seg_base);
             if (pass == 2 && b < B)
-                plan_emit_trace(b, L, S, G, Hkv, p, tile_base, rest_base, slot_base, tile_lo, seg_base, max_tiles,
-                                max_items, tiles, items);
+                plan_emit_trace(b, L, S, G, Hkv, p, tile_base, rest_base, slot_base, tile_lo, seg_base, last_only,
+                                max_tiles, max_items, tiles, items);
             __syncthreads();
             if (tid == 0) { carry[0] = s_tiles[256]; carry[1] = s_rest[256]; carry[2] = s_slots[256]; carry_work = s_work[256]; }
             __syncthreads();
@@ -327,10 +331,10 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
 }
 
 hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int T, int max_L, int G, int Hkv,
-                            int chunks_per_item, int equalize, int max_tiles, int max_items, AttnTile *tiles,
-                            AttnItem *items, int32_t *counts, hipStream_t s) {
-    attn_plan_kernel<<<1, 256, 0, s>>>(cu, plens, B, T, max_L, G, Hkv, chunks_per_item, equalize, max_tiles,
-                                       max_items, tiles, items, counts);
+                            int chunks_per_item, int equalize, int last_only, int max_tiles, int max_items,
+                            AttnTile *tiles, AttnItem *items, int32_t *counts, hipStream_t s) {
+    attn_plan_kernel<<<1, 256, 0, s>>>(cu, plens, B, T, max_L, G, Hkv, chunks_per_item, equalize, last_only,
+                                       max_tiles, max_items, tiles, items, counts);
     return hipGetLastError();
 }
 

@@ -33,6 +33,8 @@ struct confspec_ctx {
 static int g_split_layers = -1;
 // Number of leading layers whose attention runs the two-term variant (q, suffix k / v, probabilities).
 static int g_attn_precise_layers = 1;
+// 1: the last layer's attention rows, output projection and MLP run on the last position of each trace only
+static int g_prune_last_layer = 1;
 
 static int split_layers_for(const confspec_model_cfg &c) {
     if (g_split_layers >= 0) return g_split_layers;
@@ -60,8 +62,10 @@ size_t elem_bytes(int dtype) { return dtype == CONFSPEC_DTYPE_FP32 ? 4 : 2; }
 struct WsLayout {
     size_t tok_trace, tok_pos, last_row, rope_cos, rope_sin, x, h, qkv, q, ksuf, vsuf, q_lo, ksuf_lo, vsuf_lo, attn, act;
     size_t plan_counts, plan_tiles, plan_items, part_o, part_ml;
+    size_t x_last, h_last, attn_last, act_last, plan2_counts, plan2_tiles, plan2_items;   // last layer, last rows only
+    size_t splitk, splitk_bytes;                                                        // split-K partial products
     size_t total;
-    int64_t max_tiles, max_items;
+    int64_t max_tiles, max_items, max_tiles2, max_items2;
 };
 
 WsLayout ws_layout(const confspec_model_cfg &c, int64_t T, int64_t B) {
@@ -100,6 +104,27 @@ WsLayout ws_layout(const confspec_model_cfg &c, int64_t T, int64_t B) {
         w.plan_items = take((size_t)w.max_items * sizeof(cs::AttnItem));
         w.part_o = take((size_t)w.max_items * cs::ATTN_BM * c.head_dim * 4);
         w.part_ml = take((size_t)w.max_items * cs::ATTN_BM * 2 * 4);
+        // the last layer works on the last position of each trace only: B rows, one attention tile per
+        // trace and kv head (its items fit the partial buffers above: max_items2 <= max_items)
+        w.x_last = take((size_t)B * c.d_model * 4);
+        w.h_last = take((size_t)B * c.d_model * eb * terms);
+        w.attn_last = take((size_t)B * qw * eb * terms);
+        w.act_last = take((size_t)B * c.d_ffn * eb * terms);
+        w.max_tiles2 = (int64_t)B * c.n_kv_heads;
+        w.max_items2 = std::min<int64_t>(w.max_items, 3 * w.max_tiles2 + (w.max_items - 3 * w.max_tiles));
+        w.plan2_counts = take(256);
+        w.plan2_tiles = take((size_t)w.max_tiles2 * sizeof(cs::AttnTile));
+        w.plan2_items = take((size_t)w.max_items2 * sizeof(cs::AttnItem));
+        // partial products of the split-K GEMMs those B rows go through (both activation forms)
+        int Bi = (int)B;
+        size_t sk = 0;
+        for (int t = 1; t <= 2; ++t) {
+            sk = std::max(sk, cs::gemm_splitk_bytes(Bi, c.d_model, (int)qw * t));
+            sk = std::max(sk, cs::gemm_splitk_bytes(Bi, 2 * c.d_ffn, c.d_model * t));
+            sk = std::max(sk, cs::gemm_splitk_bytes(Bi, c.d_model, c.d_ffn * t));
+        }
+        w.splitk_bytes = sk;
+        w.splitk = take(std::max<size_t>(sk, 256));
     }
     w.total = at;
     return w;
@@ -178,11 +203,12 @@ int check_ws(const confspec_ctx *ctx, const void *ws, size_t have, size_t need) 
     } while (0)
 
 int run_gemm(confspec_ctx *ctx, const void *A, const void *W, void *out, int M, int N, int K, int epi,
-             int a_terms, int out_terms, hipStream_t s) {
+             int a_terms, int out_terms, hipStream_t s, float *splitk_ws = nullptr, size_t splitk_bytes = 0) {
     if (ctx->cfg.dtype == CONFSPEC_DTYPE_FP32) {
         HIP_TRY(cs::launch_gemm_f32((const float *)A, (const float *)W, out, M, N, K, epi, s));
     } else {
-        HIP_TRY(cs::launch_gemm_bf16((const cs::bf16 *)A, (const cs::bf16 *)W, out, M, N, K, epi, a_terms, out_terms, s));
+        HIP_TRY(cs::launch_gemm_bf16((const cs::bf16 *)A, (const cs::bf16 *)W, out, M, N, K, epi, a_terms, out_terms,
+                                     splitk_ws, splitk_bytes, s));
     }
     return CONFSPEC_OK;
 }
@@ -207,38 +233,47 @@ cs::AttnArgs make_attn_args(const confspec_model_cfg &c, const confspec_kv *kv, 
     return a;
 }
 
-// Attention of one layer on an already planned batch.
+// Attention of one layer on an already planned batch; last_only selects the plan of the last positions.
 int run_attention(confspec_ctx *ctx, const cs::AttnArgs &a, char *ws, const WsLayout &L,
-                  const cs::AttnPlanCounts &pc, hipStream_t s) {
+                  const cs::AttnPlanCounts &pc, bool last_only, hipStream_t s) {
     if (ctx->cfg.dtype == CONFSPEC_DTYPE_FP32) {
         HIP_TRY(cs::launch_attn_f32(a, (const int32_t *)(ws + L.tok_trace), (const int32_t *)(ws + L.tok_pos), s));
     } else {
-        HIP_TRY(cs::launch_attn_bf16(a, (const cs::AttnItem *)(ws + L.plan_items), (const cs::AttnTile *)(ws + L.plan_tiles),
-                                     (const int32_t *)(ws + L.plan_counts), (int)pc.n_items, (int)pc.max_xcd_items, (int)pc.n_tiles,
-                                     pc.n_part_slots > 0,
-                                     (float *)(ws + L.part_o), (float *)(ws + L.part_ml), s));
+        size_t items = last_only ? L.plan2_items : L.plan_items, tiles = last_only ? L.plan2_tiles : L.plan_tiles;
+        size_t counts = last_only ? L.plan2_counts : L.plan_counts;
+        HIP_TRY(cs::launch_attn_bf16(a, (const cs::AttnItem *)(ws + items), (const cs::AttnTile *)(ws + tiles),
+                                     (const int32_t *)(ws + counts), (int)pc.n_items, (int)pc.max_xcd_items, (int)pc.n_tiles,
+                                     pc.n_part_slots > 0, (float *)(ws + L.part_o), (float *)(ws + L.part_ml), s));
     }
     return CONFSPEC_OK;
 }
 
-// prep + (bf16) attention plan; fills pc.
+// One attention plan (bf16 only): all suffix rows, or the last position of each trace.
+int run_attn_plan(confspec_ctx *ctx, const confspec_batch *b, int max_L, char *ws, const WsLayout &L, bool last_only,
+                  cs::AttnPlanCounts *pc, hipStream_t s) {
+    const confspec_model_cfg &c = ctx->cfg;
+    int G = c.n_q_heads / c.n_kv_heads;
+    int64_t cap_tiles = last_only ? L.max_tiles2 : L.max_tiles, cap_items = last_only ? L.max_items2 : L.max_items;
+    *pc = cs::attn_plan_counts(b->h_cu_suffix, b->h_prefix_lens, b->B, G, c.n_kv_heads, last_only ? 1 : 0);
+    if (pc->n_tiles > cap_tiles || pc->n_items > cap_items)
+        return fail(ctx, CONFSPEC_E_WORKSPACE, "attention plan (%lld tiles, %lld items) exceeds workspace capacity",
+                    (long long)pc->n_tiles, (long long)pc->n_items);
+    HIP_TRY(cs::launch_attn_plan(b->cu_suffix, b->prefix_lens, b->B, b->T, max_L, G, c.n_kv_heads, pc->chunks_per_item,
+                                 pc->equalize, last_only ? 1 : 0, (int)cap_tiles, (int)cap_items,
+                                 (cs::AttnTile *)(ws + (last_only ? L.plan2_tiles : L.plan_tiles)),
+                                 (cs::AttnItem *)(ws + (last_only ? L.plan2_items : L.plan_items)),
+                                 (int32_t *)(ws + (last_only ? L.plan2_counts : L.plan_counts)), s));
+    return CONFSPEC_OK;
+}
+
+// prep + (bf16) attention plan of all rows; fills pc.
 int run_plan(confspec_ctx *ctx, const confspec_batch *b, int max_L, char *ws, const WsLayout &L,
              cs::AttnPlanCounts *pc, hipStream_t s) {
     const confspec_model_cfg &c = ctx->cfg;
     HIP_TRY(cs::launch_prep(b->cu_suffix, b->prefix_lens, b->B, b->T, max_L, (int32_t *)(ws + L.tok_trace),
                             (int32_t *)(ws + L.tok_pos), (int32_t *)(ws + L.last_row), s));
     *pc = cs::AttnPlanCounts{};
-    if (c.dtype == CONFSPEC_DTYPE_BF16) {
-        int G = c.n_q_heads / c.n_kv_heads;
-        *pc = cs::attn_plan_counts(b->h_cu_suffix, b->h_prefix_lens, b->B, G, c.n_kv_heads);
-        if (pc->n_tiles > L.max_tiles || pc->n_items > L.max_items)
-            return fail(ctx, CONFSPEC_E_WORKSPACE, "attention plan (%lld tiles, %lld items) exceeds workspace capacity",
-                        (long long)pc->n_tiles, (long long)pc->n_items);
-        HIP_TRY(cs::launch_attn_plan(b->cu_suffix, b->prefix_lens, b->B, b->T, max_L, G, c.n_kv_heads,
-                                     pc->chunks_per_item, pc->equalize, (int)L.max_tiles, (int)L.max_items,
-                                     (cs::AttnTile *)(ws + L.plan_tiles), (cs::AttnItem *)(ws + L.plan_items),
-                                     (int32_t *)(ws + L.plan_counts), s));
-    }
+    if (c.dtype == CONFSPEC_DTYPE_BF16) return run_attn_plan(ctx, b, max_L, ws, L, false, pc, s);
     return CONFSPEC_OK;
 }
 
@@ -354,15 +389,22 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
     void *h = ws + L.h;
     float *qkv = (float *)(ws + L.qkv);
 
-    cs::AttnPlanCounts pc;
+    cs::AttnPlanCounts pc, pc_last;
     if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
+    // Only the last position of each trace feeds the verdict head, so everything of the last layer that
+    // comes after its keys and values - attention rows, output projection, MLP - runs on those B rows.
+    const bool prune = c.dtype == CONFSPEC_DTYPE_BF16 && g_prune_last_layer && c.n_layers > 0;
+    if (prune && (rc = run_attn_plan(ctx, batch, max_L, ws, L, true, &pc_last, s)) != CONFSPEC_OK) return rc;
     HIP_TRY(cs::launch_rope_table((const int32_t *)(ws + L.tok_pos), T, c.head_dim, c.rope_theta,
                                   (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
     HIP_TRY(cs::launch_embed(c.dtype, batch->suffix_ids, w->embed, x, T, d, c.vocab, s));
+    const int32_t *last_row = (const int32_t *)(ws + L.last_row);
+    size_t eb = elem_bytes(c.dtype);
     for (int l = 0; l < c.n_layers; ++l) {
         // The first layers' GEMM activations travel as two bf16 terms (see gemm_bf16.hip).
         int tm = (c.dtype == CONFSPEC_DTYPE_BF16 && l < split_layers_for(c)) ? 2 : 1;
         bool prec = c.dtype == CONFSPEC_DTYPE_BF16 && l < g_attn_precise_layers;
+        bool last = prune && l == c.n_layers - 1;
         HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, tm, s));
         if ((rc = run_gemm(ctx, h, w->wqkv[l], qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, tm, 1, s))) return rc;
         HIP_TRY(cs::launch_rope_split(c.dtype, qkv, (const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin),
@@ -371,14 +413,30 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
                                       c.n_kv_heads, c.head_dim, s));
         cs::AttnArgs a = make_attn_args(c, kv, batch, l, ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
                                         prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, ws + L.attn, tm);
-        if ((rc = run_attention(ctx, a, ws, L, pc, s))) return rc;
-        if ((rc = run_gemm(ctx, ws + L.attn, w->wo[l], x, T, d, qw, cs::EPI_RESID_F32, tm, 1, s))) return rc;
-        HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->mlp_norm[l], h, T, d, c.rms_eps, tm, s));
-        if ((rc = run_gemm(ctx, h, w->w_gate_up[l], ws + L.act, T, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s))) return rc;
-        if ((rc = run_gemm(ctx, ws + L.act, w->w_down[l], x, T, d, c.d_ffn, cs::EPI_RESID_F32, tm, 1, s))) return rc;
+        if ((rc = run_attention(ctx, a, ws, L, last ? pc_last : pc, last, s))) return rc;
+        float *xr = x;             // residual stream the rest of the layer works on
+        const void *attn = ws + L.attn;
+        void *hr = h, *act = ws + L.act;
+        int rows = T;
+        if (last) {
+            xr = (float *)(ws + L.x_last); hr = ws + L.h_last; act = ws + L.act_last; rows = B;
+            HIP_TRY(cs::launch_gather_rows(x, xr, last_row, B, T, (size_t)d * 4, s));
+            HIP_TRY(cs::launch_gather_rows(ws + L.attn, ws + L.attn_last, last_row, B, T, (size_t)qw * eb * tm, s));
+            attn = ws + L.attn_last;
+        }
+        float *sk = last ? (float *)(ws + L.splitk) : nullptr;     // short outputs take the split-K path
+        size_t skb = last ? L.splitk_bytes : 0;
+        if ((rc = run_gemm(ctx, attn, w->wo[l], xr, rows, d, qw, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
+        HIP_TRY(cs::launch_rmsnorm(c.dtype, xr, w->mlp_norm[l], hr, rows, d, c.rms_eps, tm, s));
+        if ((rc = run_gemm(ctx, hr, w->w_gate_up[l], act, rows, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s, sk, skb))) return rc;
+        if ((rc = run_gemm(ctx, act, w->w_down[l], xr, rows, d, c.d_ffn, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
     }
-    HIP_TRY(cs::launch_verdict(c.dtype, x, (const int32_t *)(ws + L.last_row), w->final_norm, w->lm_head, va, B, T, d,
-                               c.rms_eps, dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
+    if (prune)
+        HIP_TRY(cs::launch_verdict(c.dtype, (const float *)(ws + L.x_last), nullptr, w->final_norm, w->lm_head, va, B, B, d,
+                                   c.rms_eps, dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
+    else
+        HIP_TRY(cs::launch_verdict(c.dtype, x, last_row, w->final_norm, w->lm_head, va, B, T, d, c.rms_eps,
+                                   dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
     return CONFSPEC_OK;
 }
 
@@ -390,9 +448,13 @@ static int check_terms(confspec_ctx *ctx, int terms, const char *what) {
 }
 
 int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, void *dev_out, int32_t M, int32_t N,
-                     int32_t K, int32_t epilogue, int32_t a_terms, int32_t out_terms, confspec_stream stream) {
+                     int32_t K, int32_t epilogue, int32_t a_terms, int32_t out_terms, void *dev_scratch,
+                     size_t scratch_bytes, confspec_stream stream) {
     if (!ctx) return CONFSPEC_E_INVALID_ARG;
     if (!dev_A || !dev_W || !dev_out) return fail(ctx, CONFSPEC_E_INVALID_ARG, "null operand");
+    if (dev_scratch && ((uintptr_t)dev_scratch & 15)) return fail(ctx, CONFSPEC_E_WORKSPACE, "scratch is not 16-byte aligned");
+    if (((uintptr_t)dev_A | (uintptr_t)dev_W | (uintptr_t)dev_out) & 15)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "operands must be 16-byte aligned");
     if (M < 1 || N < 1 || K < 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "M, N, K must be >= 1");
     if (epilogue < 0 || epilogue > 2) return fail(ctx, CONFSPEC_E_INVALID_ARG, "unknown epilogue %d", epilogue);
     int rc;
@@ -404,7 +466,13 @@ int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, vo
     } else if (N % 64 || K % 16) {
         return fail(ctx, CONFSPEC_E_UNSUPPORTED, "fp32 GEMM needs N %% 64 == 0 and K %% 16 == 0");
     }
-    return run_gemm(ctx, dev_A, dev_W, dev_out, M, N, K, epilogue, a_terms, out_terms, (hipStream_t)stream);
+    return run_gemm(ctx, dev_A, dev_W, dev_out, M, N, K, epilogue, a_terms, out_terms, (hipStream_t)stream,
+                    (float *)dev_scratch, dev_scratch ? scratch_bytes : 0);
+}
+
+size_t confspec_op_gemm_scratch_bytes(const confspec_ctx *ctx, int32_t M, int32_t N, int32_t K, int32_t a_terms) {
+    if (!ctx || ctx->cfg.dtype != CONFSPEC_DTYPE_BF16 || M < 1 || N < 1 || K < 1 || a_terms < 1 || a_terms > 2) return 0;
+    return cs::gemm_splitk_bytes(M, N, K * a_terms);
 }
 
 int confspec_op_rmsnorm(confspec_ctx *ctx, const float *dev_x, const void *dev_g, void *dev_out, int32_t n_rows,
@@ -472,7 +540,7 @@ int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confsp
     if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
     cs::AttnArgs a = make_attn_args(ctx->cfg, kv, batch, layer, dev_q, dev_k_suffix, dev_v_suffix, dev_q_lo, dev_k_lo,
                                     dev_v_lo, dev_out, out_terms);
-    return run_attention(ctx, a, ws, L, pc, s);
+    return run_attention(ctx, a, ws, L, pc, false, s);
 }
 
 int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, const float *dev_x,
@@ -520,6 +588,9 @@ int confspec_tune(const char *key, int32_t value) {
     } else if (!strcmp(key, "split_layers")) {
         if (value < -1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
         g_split_layers = value;
+    } else if (!strcmp(key, "prune_last_layer")) {
+        if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
+        g_prune_last_layer = value;
     } else if (!strcmp(key, "attn_precise_layers")) {
         if (value < 0 || value > 4096) return CONFSPEC_E_INVALID_ARG;
         g_attn_precise_layers = value;

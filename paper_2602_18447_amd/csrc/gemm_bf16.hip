@@ -50,7 +50,7 @@ void gemm_set_group_m(int g) { g_gemm_tune.group_m = g; }
 // kept in flight: (64, 2) has the fewest barriers, (32, 4) the deepest prefetch for the same LDS budget.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_TERMS>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W,
-                                                         void *__restrict__ out_v, int M, int N, int K,
+                                                         void *out_v, int M, int N, int K,
                                                          int tiles_m, int tiles_n, int n_base, int group_m, int out_terms) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wave tile
@@ -108,7 +108,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         b_src[j] = reinterpret_cast<const char *>(W + (size_t)(n0 + row) * K + g * 8);
     }
     int nk_w = K / BK;             // k-tiles of W
-    int nk = nk_w * A_TERMS;       // k-tiles of A: hi half, then lo half
+    int nk_all = nk_w * A_TERMS;   // k-tiles of A: hi half, then lo half
+    // Split-K launches (gridDim.y > 1, plain-store epilogue only): slice y takes the k-tiles [kb, kb + nk)
+    // and writes its partial product to the y-th [M, N] plane of the output.
+    const int kb = (int)(((long)blockIdx.y * nk_all) / gridDim.y);
+    const int nk = (int)(((long)(blockIdx.y + 1) * nk_all) / gridDim.y) - kb;
+    if (EPI == EPI_STORE_F32) out_v = reinterpret_cast<float *>(out_v) + (size_t)blockIdx.y * M * N;
     auto issue_loads = [&](int stage, int kt) {
         int kw = (A_TERMS == 2 && kt >= nk_w) ? kt - nk_w : kt;     // W wraps around for the lo half
         unsigned char *base = smem + stage * STAGE;
@@ -142,14 +147,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     // tells that everybody is done with the stage the next loads will overwrite.
 #pragma unroll
     for (int t = 0; t < NS - 1; ++t)
-        if (t < nk) issue_loads(t, t);
-    for (int kt = 0; kt < nk; ++kt) {
-        int after = min(NS - 2, nk - 1 - kt);
+        if (t < nk) issue_loads(t, kb + t);
+    for (int ki = 0; ki < nk; ++ki) {
+        const int kt = kb + ki;
+        int after = min(NS - 2, nk - 1 - ki);
         if (after >= 2) CS_WAIT_VMCNT(2 * PER_TILE);
         else if (after == 1) CS_WAIT_VMCNT(PER_TILE);
         else CS_WAIT_VMCNT(0);
         __syncthreads();
-        const unsigned char *cur = smem + (kt % NS) * STAGE;
+        const unsigned char *cur = smem + (ki % NS) * STAGE;
         bf16x8 af[2][MI], bfr[2][NI];
         auto read_frags = [&](int buf, int ks) {
             int ga = ((2 * ks + half) ^ a_sw) * 16, gb = ((2 * ks + half) ^ b_sw) * 16;
@@ -168,7 +174,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         // to save registers, and every group of MFMAs waits out its own LDS latency).
         read_frags(0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (kt + NS - 1 < nk) issue_loads((kt + NS - 1) % NS, kt + NS - 1);
+        if (ki + NS - 1 < nk) issue_loads((ki + NS - 1) % NS, kt + NS - 1);
         constexpr int EARLY = 2;   // MFMAs of a k-step issued before the next step's operand reads
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
@@ -354,8 +360,98 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
     }
 }
 
+// ---- split-K for short outputs -----------------------------------------------------------------
+// With M <= 128 there is one tile row, so a [M, N] output gives N / 128 workgroups, each walking all of
+// K: a few CUs work for a long time.  Instead the k range is cut into slices, every (tile, slice) pair
+// is a workgroup that stores its partial product, and a second kernel adds the slices in a fixed order
+// and applies the epilogue.
+int gemm_splitk_factor(int M, int N, int K_total) {
+    if (M > 128 || N % 128 != 0) return 1;
+    int tiles_n = N / 128, nk = K_total / 64;
+    int want = (384 + tiles_n / 2) / tiles_n;            // about 384 workgroups
+    int s = std::min(want, nk / 4);                      // at least 4 k-tiles per slice
+    return std::max(1, std::min(s, 64));
+}
+size_t gemm_splitk_bytes(int M, int N, int K_total) {
+    int s = gemm_splitk_factor(M, N, K_total);
+    return s > 1 ? (size_t)s * M * N * 4 : 0;
+}
+
+template <int EPI>
+__global__ void splitk_reduce_kernel(const float *__restrict__ part, int splits, int M, int N, void *__restrict__ out_v,
+                                     int out_terms) {
+    // one thread per 4 output columns of one row
+    int n_out = EPI == EPI_SWIGLU ? N / 2 : N;
+    int c4 = (blockIdx.x * blockDim.x + threadIdx.x) * 4, r = blockIdx.y;
+    if (c4 >= n_out) return;
+    size_t plane = (size_t)M * N;
+    if (EPI == EPI_SWIGLU) {
+        int gc = 64 * (c4 / 32) + c4 % 32;               // packed column of the gate value; its up value is 32 further
+        f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = g;
+#pragma unroll 4
+        for (int sp = 0; sp < splits; ++sp) {
+            const float *p = part + sp * plane + (size_t)r * N + gc;
+            g += *reinterpret_cast<const f32x4 *>(p);
+            u += *reinterpret_cast<const f32x4 *>(p + 32);
+        }
+        bf16 *out = reinterpret_cast<bf16 *>(out_v) + (size_t)r * n_out * out_terms + c4;
+        unsigned hi[4], lo[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float act = g[q] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[q])) * u[q];
+            bf16 h = __float2bfloat16(act);
+            hi[q] = __bfloat16_as_ushort(h);
+            lo[q] = __bfloat16_as_ushort(__float2bfloat16(act - __bfloat162float(h)));
+        }
+        uint2 ph = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+        *reinterpret_cast<uint2 *>(out) = ph;
+        if (out_terms == 2) {
+            uint2 pl = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+            *reinterpret_cast<uint2 *>(out + n_out) = pl;
+        }
+    } else {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+        for (int sp = 0; sp < splits; ++sp)
+            acc += *reinterpret_cast<const f32x4 *>(part + sp * plane + (size_t)r * N + c4);
+        f32x4 *dst = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(out_v) + (size_t)r * N + c4);
+        if (EPI == EPI_RESID_F32) acc += *dst;
+        *dst = acc;
+    }
+}
+
+template <int A_TERMS>
+static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, int M, int N, int K, int splits,
+                                     hipStream_t s) {
+    constexpr int smem = 2 * (128 + 128) * 64 * 2;
+    static bool attr_set = false;
+    auto kern = gemm_bf16_kernel<128, 128, 2, 2, 64, 2, EPI_STORE_F32, A_TERMS>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    int tiles_n = N / 128;
+    dim3 grid(((tiles_n + 7) / 8) * 8, splits);
+    kern<<<grid, 256, smem, s>>>(A, W, part, M, N, K, 1, tiles_n, 0, 1, 1);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
-                            int out_terms, hipStream_t s) {
+                            int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s) {
+    int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, K * a_terms) : 1;
+    if (splits > 1 && splitk_ws && gemm_splitk_bytes(M, N, K * a_terms) <= splitk_ws_bytes) {
+        hipError_t e = a_terms == 2 ? launch_splitk_main<2>(A, W, splitk_ws, M, N, K, splits, s)
+                                    : launch_splitk_main<1>(A, W, splitk_ws, M, N, K, splits, s);
+        if (e != hipSuccess) return e;
+        int n_out = epi == EPI_SWIGLU ? N / 2 : N;
+        dim3 grid((n_out / 4 + 255) / 256, M);
+        if (epi == EPI_STORE_F32) splitk_reduce_kernel<EPI_STORE_F32><<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, out, out_terms);
+        else if (epi == EPI_RESID_F32) splitk_reduce_kernel<EPI_RESID_F32><<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, out, out_terms);
+        else splitk_reduce_kernel<EPI_SWIGLU><<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, out, out_terms);
+        return hipGetLastError();
+    }
     if (epi == EPI_STORE_F32) return launch_epi<EPI_STORE_F32>(A, W, out, M, N, K, a_terms, out_terms, s);
     if (epi == EPI_RESID_F32) return launch_epi<EPI_RESID_F32>(A, W, out, M, N, K, a_terms, out_terms, s);
     return launch_epi<EPI_SWIGLU>(A, W, out, M, N, K, a_terms, out_terms, s);

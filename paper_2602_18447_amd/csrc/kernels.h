@@ -41,7 +41,8 @@ struct AttnPlanCounts {
     int32_t chunks_per_item;
     int32_t equalize;           // 1: equal pieces per tile, 0: pieces of chunks_per_item, remainder last
 };
-AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv);
+// last_only: plan the last suffix position of each trace only (one tile of G rows per trace and kv head)
+AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv, int last_only);
 // Upper bounds used to size the workspace.
 void attn_plan_capacity(int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles, int64_t *max_items);
 
@@ -62,6 +63,9 @@ hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, i
 hipError_t launch_rope_split(int dtype, const float *qkv, const float *cos_t, const float *sin_t, void *q,
                              void *ksuf, void *vsuf, void *q_lo, void *k_lo, void *v_lo, int T, int Hq, int Hkv,
                              int hd, hipStream_t s);
+// dst row b = src row rows[b] (rows == nullptr: row b), row_bytes a multiple of 16
+hipError_t launch_gather_rows(const void *src, void *dst, const int32_t *rows, int n_rows, int n_src_rows,
+                              size_t row_bytes, hipStream_t s);
 hipError_t launch_copy16(const void *src, void *dst, size_t n16, hipStream_t s);
 hipError_t launch_pack_gate_up(int dtype, const void *src, void *dst, int F, int d, hipStream_t s);
 
@@ -70,6 +74,7 @@ struct VerdictArgs {
     float tau[8];
     int32_t n_verdict, n_tau;
 };
+// last_row == nullptr: trace b reads row b of x
 hipError_t launch_verdict(int dtype, const float *x, const int32_t *last_row, const void *final_norm,
                           const void *lm_head, VerdictArgs va, int B, int T, int d, float eps, float *logits,
                           float *conf, int32_t *verdict, uint8_t *accept, hipStream_t s);
@@ -82,8 +87,12 @@ hipError_t launch_gemm_f32(const float *A, const float *W, void *out, int M, int
                            hipStream_t s);
 // a_terms == 2: A is [M, 2K] = hi | lo two-term activations; out_terms == 2 (SwiGLU only): the
 // result is written as [M, 2 * N/2] = hi | lo.
+// splitk_ws (may be null): scratch for the split-K path that short outputs (M <= 128) take; it needs
+// gemm_splitk_bytes(M, N, K * a_terms) bytes, otherwise the call falls back to one workgroup per tile.
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
-                            int out_terms, hipStream_t s);
+                            int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
+int gemm_splitk_factor(int M, int N, int K_total);
+size_t gemm_splitk_bytes(int M, int N, int K_total);
 
 // ---- attention ----
 struct AttnArgs {
@@ -106,8 +115,8 @@ struct AttnArgs {
 hipError_t launch_attn_f32(const AttnArgs &a, const int32_t *tok_trace, const int32_t *tok_pos, hipStream_t s);
 
 hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int T, int max_L, int G, int Hkv,
-                            int chunks_per_item, int equalize, int max_tiles, int max_items, AttnTile *tiles,
-                            AttnItem *items, int32_t *counts /*[11]: tiles, items, first item of XCD 0..8*/,
+                            int chunks_per_item, int equalize, int last_only, int max_tiles, int max_items,
+                            AttnTile *tiles, AttnItem *items, int32_t *counts /*[11]: tiles, items, first item of XCD 0..8*/,
                             hipStream_t s);
 hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
                             int n_items_host, int max_xcd_items, int n_tiles_host, bool any_split, float *part_o,

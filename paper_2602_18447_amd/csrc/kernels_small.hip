@@ -135,6 +135,21 @@ hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, i
 }
 
 // ------------------------------------------------------------------------------------------------
+// Row gather: dst row b = src row rows[b]; one workgroup per row, 16 bytes per lane per step.
+__global__ void gather_rows_kernel(const u32x4_t *__restrict__ src, u32x4_t *__restrict__ dst,
+                                   const int32_t *__restrict__ rows, int n_src_rows, size_t row16) {
+    int b = blockIdx.x;
+    int r = min(max(rows ? rows[b] : b, 0), n_src_rows - 1);
+    for (size_t i = threadIdx.x; i < row16; i += blockDim.x) dst[(size_t)b * row16 + i] = src[(size_t)r * row16 + i];
+}
+
+hipError_t launch_gather_rows(const void *src, void *dst, const int32_t *rows, int n_rows, int n_src_rows,
+                              size_t row_bytes, hipStream_t s) {
+    gather_rows_kernel<<<n_rows, 256, 0, s>>>((const u32x4_t *)src, (u32x4_t *)dst, rows, n_src_rows, row_bytes / 16);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // Plain copy, 16 bytes per lane per step: reads n16 * 16 bytes and writes as many.  Its known
 // traffic is the yardstick that hardware byte counters of the other kernels are scaled by.
 __global__ void copy16_kernel(const u32x4_t *__restrict__ src, u32x4_t *__restrict__ dst, size_t n16) {
@@ -239,7 +254,7 @@ __global__ void verdict_kernel(const float *__restrict__ x, const int32_t *__res
     __shared__ float red[4];
     __shared__ float z_s[8];
     int b = blockIdx.x;
-    int row = min(max(last_row[b], 0), n_tok - 1);
+    int row = min(max(last_row ? last_row[b] : b, 0), n_tok - 1);
     const float *xr = x + (size_t)row * d;
     int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float ss = 0.f;

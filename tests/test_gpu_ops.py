@@ -401,6 +401,52 @@ def test_gemm_bf16_wide_output_split_into_two_launches(epi):
     cb.confspec_destroy(ctx)
 
 
+@pytest.mark.parametrize("M", [1, 32, 128])
+@pytest.mark.parametrize("epi,a_terms", [("store", 1), ("resid", 1), ("swiglu", 1), ("resid", 2), ("swiglu", 2)])
+def test_gemm_bf16_split_k_for_short_outputs(M, epi, a_terms):
+    """M <= 128 with scratch: k slices as separate workgroups, added in a fixed order."""
+    print(f"gemm bf16 split-K M={M} {epi} a_terms={a_terms}", flush=True)
+    ctx, _ = _ctx("bf16")
+    N, K = 512, 2240                                  # 35 k-tiles: slices of unequal length
+    full = _rand((M, K), torch.float32, 21)
+    if a_terms == 2:
+        hi = full.to(torch.bfloat16)
+        lo = (full - hi.float()).to(torch.bfloat16)
+        A = torch.cat([hi, lo], dim=1).contiguous()
+        a64 = f64(hi) + f64(lo)
+    else:
+        A = full.to(torch.bfloat16)
+        a64 = f64(A)
+    Wt = _rand((N, K), torch.bfloat16, 22, 0.05)
+    ref = a64 @ f64(Wt).T
+    nbytes = cb.confspec_op_gemm_scratch_bytes(ctx, M, N, K, a_terms)
+    assert nbytes > 0
+    scratch = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    if epi == "swiglu":
+        F = N // 2
+        out = torch.zeros((M + 1, F), dtype=torch.bfloat16, device=DEV)
+        cb.confspec_op_gemm(ctx, A, Wt, out, M, N, K, cb.EPI_SWIGLU, a_terms=a_terms, scratch=scratch)
+        torch.cuda.synchronize()
+        r3 = ref.reshape(M, N // 64, 2, 32)
+        want = (O.silu(r3[:, :, 0, :]) * r3[:, :, 1, :]).reshape(M, F)
+        assert np.all(np.abs(f64(out[:M]) - want) <= 2.0 ** -8 * np.abs(want) + 1e-4 * np.abs(want).max())
+        assert torch.all(out[M:] == 0)
+        again = torch.zeros_like(out)
+        cb.confspec_op_gemm(ctx, A, Wt, again, M, N, K, cb.EPI_SWIGLU, a_terms=a_terms, scratch=scratch)
+        torch.cuda.synchronize()
+        assert torch.equal(out, again)                # fixed summation order
+    else:
+        x0 = _rand((M + 1, N), torch.float32, 23)
+        x = x0.clone()
+        cb.confspec_op_gemm(ctx, A, Wt, x, M, N, K, cb.EPI_RESID_F32 if epi == "resid" else cb.EPI_STORE_F32,
+                            a_terms=a_terms, scratch=scratch)
+        torch.cuda.synchronize()
+        want = ref + (f64(x0[:M]) if epi == "resid" else 0.0)
+        assert np.abs(f64(x[:M]) - want).max() <= 2e-5 * max(np.abs(ref).max(), 4.0)
+        assert torch.equal(x[M:], x0[M:])
+    cb.confspec_destroy(ctx)
+
+
 def test_copy_kernel_is_exact():
     print("copy kernel", flush=True)
     n = (1 << 22) + 16 * 37                       # not a multiple of the grid's stride

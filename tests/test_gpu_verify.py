@@ -11,6 +11,7 @@ import torch
 
 import confspec_workloads as W
 from oracle import confspec_oracle as O
+from paper_2602_18447_amd import binding as cb
 from paper_2602_18447_amd.runner import Verifier
 from tests import gpu_cases as G
 
@@ -92,6 +93,27 @@ def test_results_are_run_to_run_identical_and_independent_of_batch_composition()
         b1.n_blocks, b1.max_blocks_per_seq = batch.n_blocks, max(nb, 1)
         r = G.run_gpu(wl, weights, b1, kv, verifier=ver)
         assert np.abs(r["logits"][0] - a["logits"][t]).max() <= 6e-3
+    ver.close()
+
+
+def test_last_layer_pruning_changes_nothing_but_rounding():
+    """The last layer computed for every row and for the last position of each trace only: same verdict
+    logits up to the rounding differences of differently cut attention pieces."""
+    print("last-layer pruning on / off", flush=True)
+    wl = _small_bf16("prune", 2006, (700, 64, 0, 3000, 129), (40, 96, 20, 7, 1))
+    weights, batch, kv = G.build_inputs(wl)
+    ver = Verifier(wl.model, weights)
+    res = {}
+    try:
+        for flag in (0, 1):
+            cb.confspec_tune("prune_last_layer", flag)
+            res[flag] = G.run_gpu(wl, weights, batch, kv, verifier=ver)
+    finally:
+        cb.confspec_tune("prune_last_layer", 1)
+    assert np.abs(res[0]["logits"] - res[1]["logits"]).max() <= 6e-3
+    ora = G.run_oracle(wl, weights, batch, kv, res[1]["taus"], res[1]["vids"])
+    for flag in (0, 1):
+        G.compare(wl, res[flag], ora, f"prune_last_layer={flag}")
     ver.close()
 
 
