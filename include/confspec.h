@@ -81,6 +81,15 @@ typedef struct {
     const void *const *w_gate_up;
     const void *const *w_down;
     int32_t packed;
+    /* Filled by confspec_pack_weights, ignored (may be anything) when packed == 0: IEEE-half copies of
+     * the four matrices of the first n_f16_layers layers (host arrays of n_layers dev pointers, entries
+     * past n_f16_layers are NULL).  confspec_verify runs those layers' GEMMs on fp16 operands, which
+     * carry three more mantissa bits than bf16 at the same cost; see confspec_tune "first_layers_f16". */
+    int32_t n_f16_layers;
+    const void *const *wqkv_f16;
+    const void *const *wo_f16;
+    const void *const *w_gate_up_f16;
+    const void *const *w_down_f16;
 } confspec_weights;
 
 /* Paged context cache, dev, read-only, element type = cfg.dtype.
@@ -124,15 +133,19 @@ int confspec_create(const confspec_model_cfg *cfg, int device, confspec_ctx **ou
 int confspec_workspace_bytes(const confspec_ctx *ctx, int32_t max_T, int32_t max_B, int64_t max_sum_L,
                              size_t *out_bytes);
 
-/* Bytes of device memory confspec_pack_weights writes (all layers' reordered gate/up matrices). */
+/* Bytes of device memory confspec_pack_weights writes: all layers' reordered gate/up matrices and, for
+ * a bf16 model, the fp16 copies of the first layers' matrices. */
 int confspec_packed_bytes(const confspec_ctx *ctx, size_t *out_bytes);
 
 /* One-time reordering of the gate/up rows so that one GEMM output tile holds a gate column and its
  * up column side by side (the SwiGLU product is then taken in the GEMM epilogue).  Reads in->w_gate_up
  * (packed == 0), writes dev_dst (256-byte aligned, >= confspec_packed_bytes), and fills *out with a
  * weights record whose w_gate_up pointers point into dev_dst and whose other members equal *in's.
- * h_ptr_storage: host array of n_layers pointers that *out's w_gate_up member will point to; it must
- * outlive *out.  Enqueued on `stream`. */
+ * For a bf16 model it also writes IEEE-half copies of the four matrices of the first layers (the number
+ * confspec_verify would otherwise run with two-term activations), converted element by element: exact for
+ * |w| >= 2^-14, rounded to the half subnormal grid (absolute error <= 2^-25) below that.
+ * h_ptr_storage: host array of 5 * n_layers pointers that the pointer-array members of *out set by this
+ * call will point into; it must outlive *out.  Enqueued on `stream`. */
 int confspec_pack_weights(confspec_ctx *ctx, const confspec_weights *in, void *dev_dst, size_t dst_bytes,
                           const void **h_ptr_storage, confspec_weights *out, confspec_stream stream);
 

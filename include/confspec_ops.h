@@ -22,15 +22,18 @@ extern "C" {
 #define CONFSPEC_EPI_SWIGLU 2     /* W rows gate/up interleaved (confspec_pack_weights order);   */
                                   /* out (model dtype) [M, N/2] = silu(gate) * up                */
 
-/* Two-term activations (bf16 contexts only).  A bf16 activation matrix [M, K] may be carried as
- * [M, 2K] = hi | lo, hi = bf16(v) and lo = bf16(v - hi), which keeps 16 mantissa bits through a bf16
- * MFMA GEMM at twice the k-loop length.  `a_terms` / `out_terms` are 1 (plain) or 2 (hi | lo).
- * confspec_verify uses the two-term form in the first "split_layers" layers (see confspec_tune). */
+/* Activation formats (bf16 contexts only beyond 1).  `a_terms` / `out_terms` are
+ *   1  the context's dtype;
+ *   2  two bf16 terms: an activation matrix [M, K] is carried as [M, 2K] = hi | lo, hi = bf16(v) and
+ *      lo = bf16(v - hi), which keeps 16 mantissa bits through a bf16 MFMA GEMM at twice the k-loop length;
+ *   3  IEEE half: 11 mantissa bits at the cost of a bf16 GEMM; in a GEMM both A and W then hold half values.
+ * confspec_verify runs the first "split_layers" layers (see confspec_tune) in format 3 when the packed
+ * weights carry half copies of those layers' matrices, else in format 2. */
 
 /* C[M,N] = A[M,K] . W[N,K]^T with one of the epilogues above.  A ([M, a_terms*K]) and W are dev
  * arrays of the context's dtype (row-major, K contiguous).  Requires N % 128 == 0 and K % 64 == 0 for
- * bf16, N % 64 == 0 and K % 16 == 0 for fp32; any M >= 1.  out_terms == 2 is valid with the SwiGLU
- * epilogue only (out is then [M, 2 * N/2]).  dev_scratch (may be NULL) is dev memory the call may use for
+ * bf16, N % 64 == 0 and K % 16 == 0 for fp32; any M >= 1.  out_terms != 1 is valid with the SwiGLU
+ * epilogue only (2: out is [M, 2 * N/2]; 3: out holds half values).  dev_scratch (may be NULL) is dev memory the call may use for
  * partial products: with at least confspec_op_gemm_scratch_bytes() bytes a bf16 GEMM with M <= 128 cuts
  * the k range into slices that run as separate workgroups and are added in a fixed order; without it
  * such a GEMM runs one workgroup per 128 output columns.  16-byte aligned. */
@@ -83,7 +86,8 @@ int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_
 
 /* Process-wide settings.  "split_layers": number of leading layers in which confspec_verify carries
  * the GEMM activations as two bf16 terms (default -1 = ceil(n_layers / 7), doubled when d_model > 4096).  "attn_precise_layers"
- * (default 1): number of leading layers whose attention runs the two-term variant.  "prune_last_layer" (default 1):
+ * (default 1): number of leading layers whose attention runs the two-term variant.  "first_layers_f16" (default 1; read by
+ * confspec_pack_weights, which then makes the half copies, and by confspec_verify).  "prune_last_layer" (default 1):
  * in the last layer, compute attention rows, output projection and MLP for the last position of each trace only
  * (the only rows the verdict head reads; 0 computes every row).  Launch-shape tunables for
  * measurements: "gemm_tile" (0 heuristic, 1..6 = fixed workgroup tile / pipeline shape of the bf16 GEMM),

@@ -32,7 +32,9 @@ class Weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
                 ("attn_norm", C.POINTER(C.c_void_p)), ("wqkv", C.POINTER(C.c_void_p)),
                 ("wo", C.POINTER(C.c_void_p)), ("mlp_norm", C.POINTER(C.c_void_p)),
-                ("w_gate_up", C.POINTER(C.c_void_p)), ("w_down", C.POINTER(C.c_void_p)), ("packed", C.c_int32)]
+                ("w_gate_up", C.POINTER(C.c_void_p)), ("w_down", C.POINTER(C.c_void_p)), ("packed", C.c_int32),
+                ("n_f16_layers", C.c_int32), ("wqkv_f16", C.POINTER(C.c_void_p)), ("wo_f16", C.POINTER(C.c_void_p)),
+                ("w_gate_up_f16", C.POINTER(C.c_void_p)), ("w_down_f16", C.POINTER(C.c_void_p))]
 
 
 class KV(C.Structure):

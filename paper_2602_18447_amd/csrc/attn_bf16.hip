@@ -338,6 +338,26 @@ hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int 
     return hipGetLastError();
 }
 
+// Four consecutive output values in the requested activation format: 1 = bf16, 2 = bf16 hi at o and the
+// bf16 remainder row_w elements further, 3 = IEEE half.
+__device__ __forceinline__ void store_out4(bf16 *o, size_t row_w, int fmt, const float *v) {
+    if (fmt == 3) {
+        union { __half h[4]; uint2 u; } ph;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ph.h[j] = __float2half_rn(v[j]);
+        *reinterpret_cast<uint2 *>(o) = ph.u;
+        return;
+    }
+    union { bf16 h[4]; uint2 u; } pk, pl;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        pk.h[j] = __float2bfloat16(v[j]);
+        pl.h[j] = __float2bfloat16(v[j] - __bfloat162float(pk.h[j]));
+    }
+    *reinterpret_cast<uint2 *>(o) = pk.u;
+    if (fmt == 2) *reinterpret_cast<uint2 *>(o + row_w) = pl.u;
+}
+
 // ---- the attention kernel ----
 // PRECISE: q, the suffix keys / values and the probabilities are each carried as two bf16 terms
 // (hi + lo); products hi*hi, hi*lo and lo*hi are accumulated (lo*lo is below fp32 resolution of the
@@ -643,20 +663,16 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
         if (row_valid) {
             float inv = 1.0f / l_tot;
             size_t row_w = (size_t)a.Hq * HD;
-            bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + (size_t)(cu_b + t) * row_w * a.out_terms + (c * G + g) * HD;
+            bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + (size_t)(cu_b + t) * row_w * (a.out_terms == 2 ? 2 : 1) +
+                          (c * G + g) * HD;
 #pragma unroll
             for (int hb = 0; hb < 4; ++hb)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
-                    union { bf16 h[4]; uint2 u; } pk, pl;
+                    float v4[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        float v = acc_o[hb][q4 * 4 + j] * inv;
-                        pk.h[j] = __float2bfloat16(v);
-                        pl.h[j] = __float2bfloat16(v - __bfloat162float(pk.h[j]));
-                    }
-                    *reinterpret_cast<uint2 *>(o_row + 32 * hb + 8 * q4 + 4 * half) = pk.u;
-                    if (a.out_terms == 2) *reinterpret_cast<uint2 *>(o_row + row_w + 32 * hb + 8 * q4 + 4 * half) = pl.u;
+                    for (int j = 0; j < 4; ++j) v4[j] = acc_o[hb][q4 * 4 + j] * inv;
+                    store_out4(o_row + 32 * hb + 8 * q4 + 4 * half, row_w, a.out_terms, v4);
                 }
         }
     } else {
@@ -718,16 +734,10 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnT
         float inv = 1.0f / l;
         int t = r / G, g = r - t * G;
         size_t row_w = (size_t)a.Hq * HD;
-        bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + (size_t)(cu_b + t) * row_w * a.out_terms + (c * G + g) * HD;
+        bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + (size_t)(cu_b + t) * row_w * (a.out_terms == 2 ? 2 : 1) +
+                      (c * G + g) * HD;
         float vals[4] = {o.x * inv, o.y * inv, o.z * inv, o.w * inv};
-        union { bf16 h[4]; uint2 u; } pk, pl;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            pk.h[j] = __float2bfloat16(vals[j]);
-            pl.h[j] = __float2bfloat16(vals[j] - __bfloat162float(pk.h[j]));
-        }
-        *reinterpret_cast<uint2 *>(o_row + hv * 4) = pk.u;
-        if (a.out_terms == 2) *reinterpret_cast<uint2 *>(o_row + row_w + hv * 4) = pl.u;
+        store_out4(o_row + hv * 4, row_w, a.out_terms, vals);
     }
 }
 

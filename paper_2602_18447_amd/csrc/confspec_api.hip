@@ -35,6 +35,9 @@ static int g_split_layers = -1;
 static int g_attn_precise_layers = 1;
 // 1: the last layer's attention rows, output projection and MLP run on the last position of each trace only
 static int g_prune_last_layer = 1;
+// 1: the first layers (the split_layers rule) run their GEMMs on fp16 operands when the packed weights carry
+// fp16 copies; 0: they use two-term bf16 activations against the bf16 weights
+static int g_first_layers_f16 = 1;
 
 static int split_layers_for(const confspec_model_cfg &c) {
     if (g_split_layers >= 0) return g_split_layers;
@@ -320,10 +323,36 @@ int confspec_workspace_bytes(const confspec_ctx *ctx, int32_t max_T, int32_t max
     return CONFSPEC_OK;
 }
 
+namespace {
+// fp16 copies are made for the layers that would otherwise run with two-term activations
+int f16_layers_for(const confspec_model_cfg &c) {
+    if (c.dtype != CONFSPEC_DTYPE_BF16 || !g_first_layers_f16) return 0;
+    return std::min(c.n_layers, split_layers_for(c));
+}
+struct PackLayout {
+    size_t gate_up;        // bytes of one packed gate/up matrix (aligned)
+    size_t f16[4];         // bytes of the fp16 copies of wqkv, wo, gate/up, down (aligned)
+    size_t elems[4];
+    size_t total;
+};
+PackLayout pack_layout(const confspec_model_cfg &c) {
+    PackLayout p = {};
+    size_t qw = (size_t)c.n_q_heads * c.head_dim, kw = (size_t)c.n_kv_heads * c.head_dim;
+    p.gate_up = align_up((size_t)2 * c.d_ffn * c.d_model * elem_bytes(c.dtype));
+    p.elems[0] = (qw + 2 * kw) * c.d_model;
+    p.elems[1] = (size_t)c.d_model * qw;
+    p.elems[2] = (size_t)2 * c.d_ffn * c.d_model;
+    p.elems[3] = (size_t)c.d_model * c.d_ffn;
+    size_t per16 = 0;
+    for (int i = 0; i < 4; ++i) { p.f16[i] = align_up(p.elems[i] * 2); per16 += p.f16[i]; }
+    p.total = (size_t)c.n_layers * p.gate_up + (size_t)f16_layers_for(c) * per16;
+    return p;
+}
+}  // namespace
+
 int confspec_packed_bytes(const confspec_ctx *ctx, size_t *out_bytes) {
     if (!ctx || !out_bytes) return CONFSPEC_E_INVALID_ARG;
-    const confspec_model_cfg &c = ctx->cfg;
-    *out_bytes = (size_t)c.n_layers * align_up((size_t)2 * c.d_ffn * c.d_model * elem_bytes(c.dtype));
+    *out_bytes = pack_layout(ctx->cfg).total;
     return CONFSPEC_OK;
 }
 
@@ -334,22 +363,42 @@ int confspec_pack_weights(confspec_ctx *ctx, const confspec_weights *in, void *d
     if (in->packed != 0) return fail(ctx, CONFSPEC_E_INVALID_ARG, "input weights are already packed");
     const confspec_model_cfg &c = ctx->cfg;
     if (c.d_ffn % 32) return fail(ctx, CONFSPEC_E_UNSUPPORTED, "d_ffn must be a multiple of 32");
-    size_t need;
-    confspec_packed_bytes(ctx, &need);
+    PackLayout P = pack_layout(c);
     if (!dev_dst || ((uintptr_t)dev_dst & 255)) return fail(ctx, CONFSPEC_E_WORKSPACE, "dev_dst null or not 256-byte aligned");
-    if (dst_bytes < need) return fail(ctx, CONFSPEC_E_WORKSPACE, "dev_dst has %zu bytes, %zu needed", dst_bytes, need);
+    if (dst_bytes < P.total) return fail(ctx, CONFSPEC_E_WORKSPACE, "dev_dst has %zu bytes, %zu needed", dst_bytes, P.total);
     if (c.n_layers > 0 && !in->w_gate_up) return fail(ctx, CONFSPEC_E_INVALID_ARG, "w_gate_up is null");
-    size_t per = need / (c.n_layers > 0 ? c.n_layers : 1);
-    hipStream_t s = (hipStream_t)stream;
+    int n16 = f16_layers_for(c);
+    if (n16 > 0 && (!in->wqkv || !in->wo || !in->w_down)) return fail(ctx, CONFSPEC_E_INVALID_ARG, "a per-layer weight array is null");
     for (int l = 0; l < c.n_layers; ++l) {
         if (!in->w_gate_up[l]) return fail(ctx, CONFSPEC_E_INVALID_ARG, "w_gate_up[%d] is null", l);
-        void *dst = (char *)dev_dst + per * l;
-        HIP_TRY(cs::launch_pack_gate_up(c.dtype, in->w_gate_up[l], dst, c.d_ffn, c.d_model, s));
-        h_ptr_storage[l] = dst;
+        if (l < n16 && (!in->wqkv[l] || !in->wo[l] || !in->w_down[l]))
+            return fail(ctx, CONFSPEC_E_INVALID_ARG, "layer %d has a null weight pointer", l);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const int n = c.n_layers;
+    for (int i = 0; i < 5 * n; ++i) h_ptr_storage[i] = nullptr;
+    char *at = (char *)dev_dst;
+    for (int l = 0; l < n; ++l) {
+        HIP_TRY(cs::launch_pack_gate_up(c.dtype, in->w_gate_up[l], at, c.d_ffn, c.d_model, s));
+        h_ptr_storage[l] = at;
+        at += P.gate_up;
+    }
+    for (int l = 0; l < n16; ++l) {
+        const void *src[4] = {in->wqkv[l], in->wo[l], h_ptr_storage[l] /* packed order */, in->w_down[l]};
+        for (int i = 0; i < 4; ++i) {
+            HIP_TRY(cs::launch_bf16_to_f16(src[i], at, P.elems[i], s));
+            h_ptr_storage[(1 + i) * n + l] = at;
+            at += P.f16[i];
+        }
     }
     *out = *in;
     out->w_gate_up = h_ptr_storage;
     out->packed = 1;
+    out->n_f16_layers = n16;
+    out->wqkv_f16 = h_ptr_storage + n;
+    out->wo_f16 = h_ptr_storage + 2 * n;
+    out->w_gate_up_f16 = h_ptr_storage + 3 * n;
+    out->w_down_f16 = h_ptr_storage + 4 * n;
     return CONFSPEC_OK;
 }
 
@@ -401,12 +450,23 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
     const int32_t *last_row = (const int32_t *)(ws + L.last_row);
     size_t eb = elem_bytes(c.dtype);
     for (int l = 0; l < c.n_layers; ++l) {
-        // The first layers' GEMM activations travel as two bf16 terms (see gemm_bf16.hip).
-        int tm = (c.dtype == CONFSPEC_DTYPE_BF16 && l < split_layers_for(c)) ? 2 : 1;
+        // Activation format of this layer's GEMMs (see gemm_bf16.hip): the first layers run on fp16 operands
+        // when the packed weights carry fp16 copies, else with two bf16 terms; the rest is plain bf16.
+        int tm = 1;
+        const void *wqkv = w->wqkv[l], *wo = w->wo[l], *wgu = w->w_gate_up[l], *wdn = w->w_down[l];
+        if (c.dtype == CONFSPEC_DTYPE_BF16 && l < split_layers_for(c)) {
+            tm = 2;
+            if (g_first_layers_f16 && l < w->n_f16_layers && w->wqkv_f16 && w->wo_f16 && w->w_gate_up_f16 && w->w_down_f16 &&
+                w->wqkv_f16[l] && w->wo_f16[l] && w->w_gate_up_f16[l] && w->w_down_f16[l]) {
+                tm = 3;
+                wqkv = w->wqkv_f16[l]; wo = w->wo_f16[l]; wgu = w->w_gate_up_f16[l]; wdn = w->w_down_f16[l];
+            }
+        }
+        const int wide = tm == 2 ? 2 : 1;      // buffer width multiplier of the activation format
         bool prec = c.dtype == CONFSPEC_DTYPE_BF16 && l < g_attn_precise_layers;
         bool last = prune && l == c.n_layers - 1;
         HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, tm, s));
-        if ((rc = run_gemm(ctx, h, w->wqkv[l], qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, tm, 1, s))) return rc;
+        if ((rc = run_gemm(ctx, h, wqkv, qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, tm, 1, s))) return rc;
         HIP_TRY(cs::launch_rope_split(c.dtype, qkv, (const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin),
                                       ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
                                       prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, T, c.n_q_heads,
@@ -421,15 +481,15 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
         if (last) {
             xr = (float *)(ws + L.x_last); hr = ws + L.h_last; act = ws + L.act_last; rows = B;
             HIP_TRY(cs::launch_gather_rows(x, xr, last_row, B, T, (size_t)d * 4, s));
-            HIP_TRY(cs::launch_gather_rows(ws + L.attn, ws + L.attn_last, last_row, B, T, (size_t)qw * eb * tm, s));
+            HIP_TRY(cs::launch_gather_rows(ws + L.attn, ws + L.attn_last, last_row, B, T, (size_t)qw * eb * wide, s));
             attn = ws + L.attn_last;
         }
         float *sk = last ? (float *)(ws + L.splitk) : nullptr;     // short outputs take the split-K path
         size_t skb = last ? L.splitk_bytes : 0;
-        if ((rc = run_gemm(ctx, attn, w->wo[l], xr, rows, d, qw, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
+        if ((rc = run_gemm(ctx, attn, wo, xr, rows, d, qw, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
         HIP_TRY(cs::launch_rmsnorm(c.dtype, xr, w->mlp_norm[l], hr, rows, d, c.rms_eps, tm, s));
-        if ((rc = run_gemm(ctx, hr, w->w_gate_up[l], act, rows, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s, sk, skb))) return rc;
-        if ((rc = run_gemm(ctx, act, w->w_down[l], xr, rows, d, c.d_ffn, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
+        if ((rc = run_gemm(ctx, hr, wgu, act, rows, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s, sk, skb))) return rc;
+        if ((rc = run_gemm(ctx, act, wdn, xr, rows, d, c.d_ffn, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
     }
     if (prune)
         HIP_TRY(cs::launch_verdict(c.dtype, (const float *)(ws + L.x_last), nullptr, w->final_norm, w->lm_head, va, B, B, d,
@@ -442,8 +502,8 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
 
 // ---- single-step entry points ------------------------------------------------------------------
 static int check_terms(confspec_ctx *ctx, int terms, const char *what) {
-    if (terms != 1 && !(terms == 2 && ctx->cfg.dtype == CONFSPEC_DTYPE_BF16))
-        return fail(ctx, CONFSPEC_E_INVALID_ARG, "%s must be 1, or 2 for a bf16 context (got %d)", what, terms);
+    if (terms != 1 && !((terms == 2 || terms == 3) && ctx->cfg.dtype == CONFSPEC_DTYPE_BF16))
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "%s must be 1, or 2 / 3 for a bf16 context (got %d)", what, terms);
     return CONFSPEC_OK;
 }
 
@@ -459,8 +519,8 @@ int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, vo
     if (epilogue < 0 || epilogue > 2) return fail(ctx, CONFSPEC_E_INVALID_ARG, "unknown epilogue %d", epilogue);
     int rc;
     if ((rc = check_terms(ctx, a_terms, "a_terms")) || (rc = check_terms(ctx, out_terms, "out_terms"))) return rc;
-    if (out_terms == 2 && epilogue != CONFSPEC_EPI_SWIGLU)
-        return fail(ctx, CONFSPEC_E_INVALID_ARG, "out_terms == 2 needs the SwiGLU epilogue");
+    if (out_terms != 1 && epilogue != CONFSPEC_EPI_SWIGLU)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "out_terms != 1 needs the SwiGLU epilogue");
     if (ctx->cfg.dtype == CONFSPEC_DTYPE_BF16) {
         if (N % 128 || K % 64) return fail(ctx, CONFSPEC_E_UNSUPPORTED, "bf16 GEMM needs N %% 128 == 0 and K %% 64 == 0");
     } else if (N % 64 || K % 16) {
@@ -471,8 +531,8 @@ int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, vo
 }
 
 size_t confspec_op_gemm_scratch_bytes(const confspec_ctx *ctx, int32_t M, int32_t N, int32_t K, int32_t a_terms) {
-    if (!ctx || ctx->cfg.dtype != CONFSPEC_DTYPE_BF16 || M < 1 || N < 1 || K < 1 || a_terms < 1 || a_terms > 2) return 0;
-    return cs::gemm_splitk_bytes(M, N, K * a_terms);
+    if (!ctx || ctx->cfg.dtype != CONFSPEC_DTYPE_BF16 || M < 1 || N < 1 || K < 1 || a_terms < 1 || a_terms > 3) return 0;
+    return cs::gemm_splitk_bytes(M, N, K * (a_terms == 2 ? 2 : 1));
 }
 
 int confspec_op_rmsnorm(confspec_ctx *ctx, const float *dev_x, const void *dev_g, void *dev_out, int32_t n_rows,
@@ -588,6 +648,9 @@ int confspec_tune(const char *key, int32_t value) {
     } else if (!strcmp(key, "split_layers")) {
         if (value < -1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
         g_split_layers = value;
+    } else if (!strcmp(key, "first_layers_f16")) {
+        if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
+        g_first_layers_f16 = value;
     } else if (!strcmp(key, "prune_last_layer")) {
         if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
         g_prune_last_layer = value;

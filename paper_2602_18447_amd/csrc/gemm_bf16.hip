@@ -21,6 +21,10 @@
 // ("lo"); the k loop then runs over both halves against the same W, so the fp32 accumulator receives
 // (hi + lo) . W - the product with a 16-bit-mantissa activation.  With out_terms == 2 the SwiGLU
 // epilogue writes its result in the same [M, 2F] hi | lo form for the next GEMM.
+//
+// Operand formats.  The activation format a_fmt / out_fmt is 1 (bf16), 2 (two bf16 terms, above) or
+// 3 (fp16: both A and W hold IEEE half values and the f16 MFMA is used; three more mantissa bits than
+// bf16 at the same cost, for layers whose weights have been converted).
 #include "kernels.h"
 #include <algorithm>
 #include <cmath>
@@ -28,6 +32,7 @@
 namespace cs {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
@@ -43,16 +48,28 @@ static GemmTune g_gemm_tune = {0, 0};
 void gemm_set_tile(int t) { g_gemm_tune.tile = t; }
 void gemm_set_group_m(int g) { g_gemm_tune.group_m = g; }
 
+// one 32x32x16 MFMA on 16-bit operands held as bf16x8 bit patterns: bf16 or (F16) IEEE half
+template <bool F16>
+__device__ inline f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
 // vmcnt(n) only (expcnt / lgkmcnt left unconstrained), gfx9 encoding of s_waitcnt
 #define CS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
 // BK: k extent of one LDS stage (64 or 32 elements); NS: number of LDS stages.  NS - 1 k-tiles are
 // kept in flight: (64, 2) has the fewest barriers, (32, 4) the deepest prefetch for the same LDS budget.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_TERMS>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_FMT>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W,
                                                          void *out_v, int M, int N, int K,
-                                                         int tiles_m, int tiles_n, int n_base, int group_m, int out_terms) {
+                                                         int tiles_m, int tiles_n, int n_base, int group_m, int out_fmt) {
     constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int A_TERMS = A_FMT == 2 ? 2 : 1;
+    constexpr bool F16 = A_FMT == 3;
+    const int out_terms = out_fmt == 2 ? 2 : 1;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wave tile
     constexpr int MI = WM / 32, NI = WN / 32;             // 32x32 MFMA blocks per wave
     constexpr int ROWB = BK * 2;                          // bytes of one tile row in LDS
@@ -181,15 +198,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = 0; q < EARLY; ++q)
-                acc[q / NI][q % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][q / NI], bfr[ks & 1][q % NI],
-                                                                              acc[q / NI][q % NI], 0, 0, 0);
+                acc[q / NI][q % NI] = mma<F16>(af[ks & 1][q / NI], bfr[ks & 1][q % NI], acc[q / NI][q % NI]);
             __builtin_amdgcn_sched_barrier(0);
             if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, ks + 1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = EARLY; q < MI * NI; ++q)
-                acc[q / NI][q % NI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][q / NI], bfr[ks & 1][q % NI],
-                                                                              acc[q / NI][q % NI], 0, 0, 0);
+                acc[q / NI][q % NI] = mma<F16>(af[ks & 1][q / NI], bfr[ks & 1][q % NI], acc[q / NI][q % NI]);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -244,11 +259,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
                 if (m < M) {
                     bf16 *dst = out + (size_t)m * Fo * out_terms + f0;
                     unsigned hi[8];
+                    if (out_fmt == 3) {
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) hi[q] = __bfloat16_as_ushort(__float2bfloat16(v[q]));
+                        for (int q = 0; q < 8; ++q) hi[q] = __half_as_ushort(__float2half_rn(v[q]));
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) hi[q] = __bfloat16_as_ushort(__float2bfloat16(v[q]));
+                    }
                     u32x4 ph = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)};
                     *reinterpret_cast<u32x4 *>(dst) = ph;
-                    if (out_terms == 2) {
+                    if (out_fmt == 2) {
                         unsigned lo[8];
 #pragma unroll
                         for (int q = 0; q < 8; ++q)
@@ -281,12 +301,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
 // The number of activation terms is a template parameter, so the one-term and the two-term launches
 // are different kernels (and show up under different names in a kernel trace).
 // Launches the kernel on the column range [n_base, n_base + n_cols) of the N columns.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_TERMS>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_FMT>
 static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base, int n_cols,
                               int out_terms, hipStream_t s) {
     constexpr int smem = NS * (BM + BN) * BK * 2;
     static bool attr_set = false;
-    auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, A_TERMS>;
+    auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, A_FMT>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -312,10 +332,19 @@ static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, in
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI>
 static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base, int n_cols,
-                              int a_terms, int out_terms, hipStream_t s) {
-    if (a_terms == 2)
-        return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(A, W, out, M, N, K, n_base, n_cols, out_terms, s);
-    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(A, W, out, M, N, K, n_base, n_cols, out_terms, s);
+                              int a_fmt, int out_fmt, hipStream_t s) {
+    if (a_fmt == 2)
+        return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s);
+    if (a_fmt == 3) {
+        // fp16 operands: built for the two tile shapes the default choice uses
+        constexpr bool has_f16 = BK == 64 && NS == 2 && ((BM == 128 && BN == 128 && WAVES_M == 2 && WAVES_N == 2) ||
+                                                           (BM == 256 && BN == 256 && WAVES_M == 2 && WAVES_N == 4));
+        if constexpr (has_f16)
+            return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 3>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s);
+        else
+            return hipErrorInvalidValue;
+    }
+    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s);
 }
 
 // Tile ids: 1 = 128x128 / 4 waves, 2 = 256x256 / 4 waves, 3 = 256x128 / 4 waves, 4 = 256x256 / 8 waves
@@ -326,6 +355,7 @@ template <int EPI>
 static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
                              int out_terms, hipStream_t s) {
     int tile = g_gemm_tune.tile;
+    if (a_terms == 3 && tile != 1 && tile != 4) tile = 0;   // fp16 operands exist for the default shapes only
     if (tile == 0) {
         // Wide outputs take 256x256 tiles, one workgroup per CU, in rounds of 256 tiles.  A last round
         // that would be less than half full costs as much as a full one, so those columns are cut off
@@ -394,14 +424,19 @@ __global__ void splitk_reduce_kernel(const float *__restrict__ part, int splits,
             g += *reinterpret_cast<const f32x4 *>(p);
             u += *reinterpret_cast<const f32x4 *>(p + 32);
         }
-        bf16 *out = reinterpret_cast<bf16 *>(out_v) + (size_t)r * n_out * out_terms + c4;
+        bf16 *out = reinterpret_cast<bf16 *>(out_v) + (size_t)r * n_out * (out_terms == 2 ? 2 : 1) + c4;
         unsigned hi[4], lo[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             float act = g[q] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[q])) * u[q];
-            bf16 h = __float2bfloat16(act);
-            hi[q] = __bfloat16_as_ushort(h);
-            lo[q] = __bfloat16_as_ushort(__float2bfloat16(act - __bfloat162float(h)));
+            if (out_terms == 3) {
+                hi[q] = __half_as_ushort(__float2half_rn(act));
+                lo[q] = 0;
+            } else {
+                bf16 h = __float2bfloat16(act);
+                hi[q] = __bfloat16_as_ushort(h);
+                lo[q] = __bfloat16_as_ushort(__float2bfloat16(act - __bfloat162float(h)));
+            }
         }
         uint2 ph = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
         *reinterpret_cast<uint2 *>(out) = ph;
@@ -420,12 +455,12 @@ __global__ void splitk_reduce_kernel(const float *__restrict__ part, int splits,
     }
 }
 
-template <int A_TERMS>
+template <int A_FMT>
 static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, int M, int N, int K, int splits,
                                      hipStream_t s) {
     constexpr int smem = 2 * (128 + 128) * 64 * 2;
     static bool attr_set = false;
-    auto kern = gemm_bf16_kernel<128, 128, 2, 2, 64, 2, EPI_STORE_F32, A_TERMS>;
+    auto kern = gemm_bf16_kernel<128, 128, 2, 2, 64, 2, EPI_STORE_F32, A_FMT>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -440,10 +475,12 @@ static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, 
 
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
                             int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s) {
-    int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, K * a_terms) : 1;
-    if (splits > 1 && splitk_ws && gemm_splitk_bytes(M, N, K * a_terms) <= splitk_ws_bytes) {
-        hipError_t e = a_terms == 2 ? launch_splitk_main<2>(A, W, splitk_ws, M, N, K, splits, s)
-                                    : launch_splitk_main<1>(A, W, splitk_ws, M, N, K, splits, s);
+    int k_total = K * (a_terms == 2 ? 2 : 1);
+    int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, k_total) : 1;
+    if (splits > 1 && splitk_ws && gemm_splitk_bytes(M, N, k_total) <= splitk_ws_bytes) {
+        hipError_t e = a_terms == 2   ? launch_splitk_main<2>(A, W, splitk_ws, M, N, K, splits, s)
+                       : a_terms == 3 ? launch_splitk_main<3>(A, W, splitk_ws, M, N, K, splits, s)
+                                      : launch_splitk_main<1>(A, W, splitk_ws, M, N, K, splits, s);
         if (e != hipSuccess) return e;
         int n_out = epi == EPI_SWIGLU ? N / 2 : N;
         dim3 grid((n_out / 4 + 255) / 256, M);

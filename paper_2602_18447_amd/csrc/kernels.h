@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 
 namespace cs {
@@ -55,7 +56,8 @@ hipError_t launch_rope_table(const int32_t *tok_pos, int T, int hd, float theta,
                              hipStream_t s);
 hipError_t launch_embed(int dtype, const int32_t *ids, const void *E, float *x, int T, int d, int vocab,
                         hipStream_t s);
-// x fp32 [T,d] -> out (storage dtype) [T, terms*d]; terms == 2 (bf16 only): hi | lo two-term form
+// x fp32 [T,d] -> out (storage dtype) [T, d]; terms == 2 (bf16 only): [T, 2d] hi | lo two-term form;
+// terms == 3 (bf16 only): IEEE half values
 hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, int T, int d, float eps,
                           int terms, hipStream_t s);
 // qkv fp32 [T, (Hq+2Hkv) hd] -> q [T,Hq,hd], ksuf [T,Hkv,hd], vsuf [T,Hkv,hd] (storage dtype), q and k rotated
@@ -67,6 +69,7 @@ hipError_t launch_rope_split(int dtype, const float *qkv, const float *cos_t, co
 hipError_t launch_gather_rows(const void *src, void *dst, const int32_t *rows, int n_rows, int n_src_rows,
                               size_t row_bytes, hipStream_t s);
 hipError_t launch_copy16(const void *src, void *dst, size_t n16, hipStream_t s);
+hipError_t launch_bf16_to_f16(const void *src, void *dst, size_t n, hipStream_t s);
 hipError_t launch_pack_gate_up(int dtype, const void *src, void *dst, int F, int d, hipStream_t s);
 
 struct VerdictArgs {
@@ -85,8 +88,9 @@ hipError_t launch_verdict(int dtype, const float *x, const int32_t *last_row, co
 //  EPI_SWIGLU   : W rows are gate/up interleaved in groups of 32; out (storage dtype) [M, N/2]
 hipError_t launch_gemm_f32(const float *A, const float *W, void *out, int M, int N, int K, int epi,
                            hipStream_t s);
-// a_terms == 2: A is [M, 2K] = hi | lo two-term activations; out_terms == 2 (SwiGLU only): the
-// result is written as [M, 2 * N/2] = hi | lo.
+// Activation formats (a_terms / out_terms): 1 = bf16; 2 = two bf16 terms, A is [M, 2K] = hi | lo and a
+// SwiGLU result is written as [M, 2 * N/2] = hi | lo; 3 = fp16 (A and W hold IEEE half values, a SwiGLU
+// result is written as fp16).
 // splitk_ws (may be null): scratch for the split-K path that short outputs (M <= 128) take; it needs
 // gemm_splitk_bytes(M, N, K * a_terms) bytes, otherwise the call falls back to one workgroup per tile.
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
@@ -107,7 +111,8 @@ struct AttnArgs {
     const int32_t *block_table;  // [B, max_blocks]
     const int32_t *cu;           // [B+1]
     const int32_t *plens;        // [B]
-    void *out;              // [T, out_terms * Hq*hd] storage dtype (out_terms == 2: hi | lo, bf16 only)
+    void *out;              // [T, Hq*hd] in activation format out_terms: 1 storage dtype, 2 bf16 hi | lo
+                            // ([T, 2*Hq*hd]), 3 IEEE half
     int32_t B, T, Hq, Hkv, hd, n_blocks, block_size, max_blocks;
     float scale;            // 1/sqrt(hd)
     int32_t out_terms;

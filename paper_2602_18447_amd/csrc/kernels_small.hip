@@ -92,9 +92,14 @@ hipError_t launch_embed(int dtype, const int32_t *ids, const void *E, float *x, 
 
 // ------------------------------------------------------------------------------------------------
 // RMSNorm: one wavefront per row, fp32 statistics, output rounded to the storage type.  With
-// terms == 2 the row is written as hi | lo: the rounded value, then the rounding of the remainder.
+// terms == 2 the row is written as hi | lo: the rounded value, then the rounding of the remainder;
+// with terms == 3 (16-bit storage only) it is written as IEEE half values.
 template <typename T>
 __device__ __forceinline__ void store_terms(T *o, int c, int d, int terms, float v) {
+    if (sizeof(T) == 2 && terms == 3) {
+        reinterpret_cast<__half *>(o)[c] = __float2half_rn(v);
+        return;
+    }
     T hi = from_f32<T>(v);
     o[c] = hi;
     if (terms == 2) o[d + c] = from_f32<T>(v - to_f32<T>(hi));
@@ -115,7 +120,7 @@ __global__ void rmsnorm_kernel(const float *__restrict__ x, const T *__restrict_
     }
     ss = wave_sum(ss);
     float r = 1.0f / sqrtf(ss / (float)d + eps);
-    T *o = out + (size_t)row * d * terms;
+    T *o = out + (size_t)row * d * (terms == 2 ? 2 : 1);
     for (int j = lane; j < nv; j += 64) {
         float4 v = xr[j];
         int c = j << 2;
@@ -239,6 +244,25 @@ __global__ void pack_gate_up_kernel(const T *__restrict__ src, T *__restrict__ d
 hipError_t launch_pack_gate_up(int dtype, const void *src, void *dst, int F, int d, hipStream_t s) {
     if (dtype == 0) pack_gate_up_kernel<float><<<2 * F, 256, 0, s>>>((const float *)src, (float *)dst, F, d);
     else pack_gate_up_kernel<bf16><<<2 * F, 256, 0, s>>>((const bf16 *)src, (bf16 *)dst, F, d);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// bf16 -> IEEE half, element by element (every bf16 value inside the half range converts exactly; smaller
+// magnitudes land on the half subnormal grid, larger ones saturate to the largest finite half).
+__global__ void bf16_to_f16_kernel(const bf16 *__restrict__ src, __half *__restrict__ dst, size_t n) {
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        float v = __bfloat162float(src[i]);
+        v = fminf(fmaxf(v, -65504.f), 65504.f);
+        dst[i] = __float2half_rn(v);
+    }
+}
+
+hipError_t launch_bf16_to_f16(const void *src, void *dst, size_t n, hipStream_t s) {
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    bf16_to_f16_kernel<<<(unsigned)blocks, 256, 0, s>>>((const bf16 *)src, (__half *)dst, n);
     return hipGetLastError();
 }
 

@@ -228,7 +228,7 @@ def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16,
         q = _rand((T, hq, hd), td, seed + 1)
         ks = _rand((T, hkv, hd), td, seed + 2, 0.5)
         vs = _rand((T, hkv, hd), td, seed + 3, 0.5)
-    out = torch.zeros((T, out_terms * hq * hd), dtype=td, device=DEV)
+    out = torch.zeros((T, (2 if out_terms == 2 else 1) * hq * hd), dtype=td, device=DEV)
     kvs = cb.make_kv(kv.k_pages, kv.v_pages, batch.block_table, batch.n_blocks, block_size, batch.max_blocks_per_seq)
     bs, keep = _batch_structs(wl, batch)
     ws = torch.empty(cb.confspec_workspace_bytes(ctx, T, wl.B), dtype=torch.uint8, device=DEV)
@@ -240,7 +240,7 @@ def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16,
     vo = f64(vs) + (f64(lo["v"]) if precise else 0.0)
     torch.cuda.synchronize()
     view = W.OracleKVView(kv, batch)
-    got = f64(out)
+    got = f64(out.view(torch.float16)) if out_terms == 3 else f64(out)
     if out_terms == 2:
         got = got[:, :hq * hd] + got[:, hq * hd:]
     got = got.reshape(T, hq, hd)
@@ -445,6 +445,66 @@ def test_gemm_bf16_split_k_for_short_outputs(M, epi, a_terms):
         assert np.abs(f64(x[:M]) - want).max() <= 2e-5 * max(np.abs(ref).max(), 4.0)
         assert torch.equal(x[M:], x0[M:])
     cb.confspec_destroy(ctx)
+
+
+@pytest.mark.parametrize("M,N,K,scratch", [(300, 512, 192, False), (700, 256 * 90, 128, False), (32, 512, 2240, True)])
+def test_gemm_fp16_operands_all_epilogues(M, N, K, scratch):
+    """Activation format 3: A and W hold IEEE half values, the SwiGLU result is written as half."""
+    print(f"gemm fp16 operands M={M} N={N} K={K} scratch={scratch}", flush=True)
+    ctx, _ = _ctx("bf16")
+    A = _rand((M, K), torch.float32, 51).to(torch.float16)
+    Wt = _rand((N, K), torch.float32, 52, 0.05).to(torch.float16)
+    ref = f64(A) @ f64(Wt).T
+    sc = None
+    if scratch:
+        sc = torch.empty(cb.confspec_op_gemm_scratch_bytes(ctx, M, N, K, 3), dtype=torch.uint8, device=DEV)
+        assert sc.numel() > 0
+    x0 = _rand((M + 1, N), torch.float32, 53)
+    st = torch.zeros((M + 1, N), dtype=torch.float32, device=DEV)
+    x = x0.clone()
+    cb.confspec_op_gemm(ctx, A, Wt, st, M, N, K, cb.EPI_STORE_F32, a_terms=3, scratch=sc)
+    cb.confspec_op_gemm(ctx, A, Wt, x, M, N, K, cb.EPI_RESID_F32, a_terms=3, scratch=sc)
+    F = N // 2
+    act = torch.zeros((M + 1, F), dtype=torch.float16, device=DEV)
+    cb.confspec_op_gemm(ctx, A, Wt, act, M, N, K, cb.EPI_SWIGLU, a_terms=3, out_terms=3, scratch=sc)
+    torch.cuda.synchronize()
+    scale = max(np.abs(ref).max(), 4.0)
+    assert np.abs(f64(st[:M]) - ref).max() <= 2e-5 * scale and torch.all(st[M:] == 0)
+    assert np.abs(f64(x[:M]) - (f64(x0[:M]) + ref)).max() <= 2e-5 * scale and torch.equal(x[M:], x0[M:])
+    r3 = ref.reshape(M, N // 64, 2, 32)
+    want = (O.silu(r3[:, :, 0, :]) * r3[:, :, 1, :]).reshape(M, F)
+    assert np.all(np.abs(f64(act[:M]) - want) <= 2.0 ** -11 * np.abs(want) + 1e-4 * np.abs(want).max())
+    assert torch.all(act[M:] == 0)
+    cb.confspec_destroy(ctx)
+
+
+def test_rmsnorm_fp16_output():
+    print("rmsnorm fp16 output", flush=True)
+    d = 1536
+    ctx, base = _ctx("bf16", d_model=d)
+    x = _rand((37, d), torch.float32, 9, 3.0)
+    g = (1 + 0.1 * _rand((d,), torch.float32, 10)).to(torch.bfloat16)
+    out = torch.zeros((38, d), dtype=torch.float16, device=DEV)
+    cb.confspec_op_rmsnorm(ctx, x, g, out, 37, out_terms=3)
+    torch.cuda.synchronize()
+    ref = O.rmsnorm(f64(x), f64(g), base["rms_eps"])
+    assert np.all(np.abs(f64(out[:37]) - ref) <= 2.0 ** -11 * np.abs(ref) + 1e-6)
+    assert torch.all(out[37] == 0)
+    cb.confspec_destroy(ctx)
+
+
+def test_attention_bf16_fp16_output():
+    print("attention fp16 output", flush=True)
+    err = _attention_case("bf16", 12, 2, 128, (300, 17, 0), (96, 130, 5), out_terms=3)
+    assert err <= 6e-3
+    cb.confspec_tune("attn_min_chunks", 1)
+    cb.confspec_tune("attn_split", 3)
+    try:
+        err = _attention_case("bf16", 12, 2, 128, (700, 64), (40, 96), out_terms=3)     # through the merge kernel
+    finally:
+        cb.confspec_tune("attn_min_chunks", 8)
+        cb.confspec_tune("attn_split", 0)
+    assert err <= 6e-3
 
 
 def test_copy_kernel_is_exact():

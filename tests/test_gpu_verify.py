@@ -117,6 +117,26 @@ def test_last_layer_pruning_changes_nothing_but_rounding():
     ver.close()
 
 
+def test_first_layers_fp16_and_two_term_both_meet_the_bound():
+    """The first layers' GEMMs on fp16 operands (default) or with two-term bf16 activations."""
+    print("first layers: fp16 operands / two bf16 terms", flush=True)
+    wl = _small_bf16("f16", 2007, (700, 64, 0, 3000, 129), (40, 96, 20, 7, 1), n_layers=8)
+    weights, batch, kv = G.build_inputs(wl)
+    res = {}
+    try:
+        for flag in (0, 1):
+            cb.confspec_tune("first_layers_f16", flag)     # read when the weights are packed and by the pass
+            ver = Verifier(wl.model, weights)
+            assert ver.w.n_f16_layers == (2 if flag else 0)
+            res[flag] = G.run_gpu(wl, weights, batch, kv, verifier=ver)
+            ver.close()
+    finally:
+        cb.confspec_tune("first_layers_f16", 1)
+    ora = G.run_oracle(wl, weights, batch, kv, res[1]["taus"], res[1]["vids"])
+    for flag in (0, 1):
+        G.compare(wl, res[flag], ora, f"first_layers_f16={flag}")
+
+
 def test_config2_draft_shape_full_size_sampled_traces():
     print("config 2", flush=True)
     G.parity_case(W.config(2), traces=[0, 13, 31])
