@@ -86,7 +86,9 @@ typedef struct {
      * past n_f16_layers are NULL).  confspec_verify runs those layers' GEMMs on fp16 operands, which
      * carry three more mantissa bits than bf16 at the same cost; see confspec_tune "first_layers_f16". */
     int32_t n_f16_layers;
-    const void *const *wqkv_f16;
+    const void *const *wqkv_perm;  /* bf16 models: wqkv with the row blocks of every head reordered for the
+                                      projection kernel that applies the rotary embedding itself (all layers) */
+    const void *const *wqkv_f16;   /* half copy of wqkv_perm */
     const void *const *wo_f16;
     const void *const *w_gate_up_f16;
     const void *const *w_down_f16;
@@ -134,7 +136,7 @@ int confspec_workspace_bytes(const confspec_ctx *ctx, int32_t max_T, int32_t max
                              size_t *out_bytes);
 
 /* Bytes of device memory confspec_pack_weights writes: all layers' reordered gate/up matrices and, for
- * a bf16 model, the fp16 copies of the first layers' matrices. */
+ * a bf16 model, the reordered wqkv matrices and the fp16 copies of the first layers' matrices. */
 int confspec_packed_bytes(const confspec_ctx *ctx, size_t *out_bytes);
 
 /* One-time reordering of the gate/up rows so that one GEMM output tile holds a gate column and its
@@ -144,7 +146,9 @@ int confspec_packed_bytes(const confspec_ctx *ctx, size_t *out_bytes);
  * For a bf16 model it also writes IEEE-half copies of the four matrices of the first layers (the number
  * confspec_verify would otherwise run with two-term activations), converted element by element: exact for
  * |w| >= 2^-14, rounded to the half subnormal grid (absolute error <= 2^-25) below that.
- * h_ptr_storage: host array of 5 * n_layers pointers that the pointer-array members of *out set by this
+ * For a bf16 model it further writes, for every layer, a copy of wqkv whose rows are reordered inside each head
+ * (blocks of 32 rows in the order 0, 2, 1, 3) for the projection kernel that rotates q and k in its epilogue.
+ * h_ptr_storage: host array of 6 * n_layers pointers that the pointer-array members of *out set by this
  * call will point into; it must outlive *out.  Enqueued on `stream`. */
 int confspec_pack_weights(confspec_ctx *ctx, const confspec_weights *in, void *dev_dst, size_t dst_bytes,
                           const void **h_ptr_storage, confspec_weights *out, confspec_stream stream);

@@ -58,6 +58,16 @@ int confspec_op_rope_split(confspec_ctx *ctx, const confspec_batch *batch, int32
                            void *dev_k_lo, void *dev_v_lo, void *dev_workspace, size_t workspace_bytes,
                            confspec_stream stream);
 
+/* QKV projection with the rotary embedding and the split in its epilogue (bf16 contexts, head_dim 128): the
+ * same q, k, v (and second terms) as confspec_op_gemm into fp32 followed by confspec_op_rope_split, in one kernel.
+ * dev_h: normalised activations [T, d_model] in activation format a_terms (1 bf16, 2 hi | lo, 3 half).
+ * dev_wqkv_perm: wqkv with the 32-row blocks of every 128-row head in the order 0, 2, 1, 3 (what
+ * confspec_pack_weights produces as wqkv_perm), bf16, or half values when a_terms == 3. */
+int confspec_op_qkv_rope(confspec_ctx *ctx, const confspec_batch *batch, int32_t max_prefix_len, const void *dev_h,
+                         int32_t a_terms, const void *dev_wqkv_perm, void *dev_q, void *dev_k, void *dev_v,
+                         void *dev_q_lo, void *dev_k_lo, void *dev_v_lo, void *dev_workspace, size_t workspace_bytes,
+                         confspec_stream stream);
+
 /* Attention of one layer: softmax over keys j <= L_b + t of q . k_j / sqrt(hd), keys and values
  * 0..L_b-1 from the paged cache of `layer`, the rest from dev_k_suffix / dev_v_suffix.
  * q [T,Hq,hd], k/v suffix [T,Hkv,hd], out [T, out_terms*Hq*hd], all in the context's dtype.
@@ -87,7 +97,8 @@ int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_
 /* Process-wide settings.  "split_layers": number of leading layers in which confspec_verify carries
  * the GEMM activations as two bf16 terms (default -1 = ceil(n_layers / 7), doubled when d_model > 4096).  "attn_precise_layers"
  * (default 1): number of leading layers whose attention runs the two-term variant.  "first_layers_f16" (default 1; read by
- * confspec_pack_weights, which then makes the half copies, and by confspec_verify).  "prune_last_layer" (default 1):
+ * confspec_pack_weights, which then makes the half copies, and by confspec_verify).  "fuse_rope" (default 1): confspec_verify runs the QKV projection of a bf16 model with the rotary
+ * embedding in its epilogue (0: projection to fp32, then a separate kernel).  "prune_last_layer" (default 1):
  * in the last layer, compute attention rows, output projection and MLP for the last position of each trace only
  * (the only rows the verdict head reads; 0 computes every row).  Launch-shape tunables for
  * measurements: "gemm_tile" (0 heuristic, 1..6 = fixed workgroup tile / pipeline shape of the bf16 GEMM),

@@ -33,7 +33,8 @@ class Weights(C.Structure):
                 ("attn_norm", C.POINTER(C.c_void_p)), ("wqkv", C.POINTER(C.c_void_p)),
                 ("wo", C.POINTER(C.c_void_p)), ("mlp_norm", C.POINTER(C.c_void_p)),
                 ("w_gate_up", C.POINTER(C.c_void_p)), ("w_down", C.POINTER(C.c_void_p)), ("packed", C.c_int32),
-                ("n_f16_layers", C.c_int32), ("wqkv_f16", C.POINTER(C.c_void_p)), ("wo_f16", C.POINTER(C.c_void_p)),
+                ("n_f16_layers", C.c_int32), ("wqkv_perm", C.POINTER(C.c_void_p)),
+                ("wqkv_f16", C.POINTER(C.c_void_p)), ("wo_f16", C.POINTER(C.c_void_p)),
                 ("w_gate_up_f16", C.POINTER(C.c_void_p)), ("w_down_f16", C.POINTER(C.c_void_p))]
 
 
@@ -84,6 +85,8 @@ def _load() -> C.CDLL:
     lib.confspec_op_rmsnorm.argtypes = [vp, vp, vp, vp, i32, i32, vp]
     lib.confspec_op_rope_split.restype = C.c_int
     lib.confspec_op_rope_split.argtypes = [vp, P(Batch), i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.confspec_op_qkv_rope.restype = C.c_int
+    lib.confspec_op_qkv_rope.argtypes = [vp, P(Batch), i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.confspec_op_attention.restype = C.c_int
     lib.confspec_op_attention.argtypes = [vp, P(KV), P(Batch), i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.confspec_op_verdict_gate.restype = C.c_int
@@ -100,7 +103,7 @@ lib = _load()
 
 EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec_last_error",
             "confspec_workspace_bytes", "confspec_packed_bytes", "confspec_pack_weights", "confspec_verify",
-            "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_attention",
+            "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_qkv_rope", "confspec_op_attention",
             "confspec_op_verdict_gate", "confspec_op_copy", "confspec_tune"]
 
 
@@ -203,6 +206,13 @@ def confspec_op_rope_split(ctx, batch: Batch, max_prefix_len: int, qkv, q, k, v,
     _check(ctx, lib.confspec_op_rope_split(ctx, C.byref(batch), max_prefix_len, _ptr(qkv), _ptr(q), _ptr(k), _ptr(v),
                                            _ptr(q_lo), _ptr(k_lo), _ptr(v_lo), _ptr(workspace), ws_bytes,
                                            _stream_handle(stream)))
+
+
+def confspec_op_qkv_rope(ctx, batch: Batch, max_prefix_len: int, h, a_terms: int, wqkv_perm, q, k, v, workspace,
+                         q_lo=None, k_lo=None, v_lo=None, stream=None) -> None:
+    _check(ctx, lib.confspec_op_qkv_rope(ctx, C.byref(batch), max_prefix_len, _ptr(h), a_terms, _ptr(wqkv_perm), _ptr(q),
+                                         _ptr(k), _ptr(v), _ptr(q_lo), _ptr(k_lo), _ptr(v_lo), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream_handle(stream)))
 
 
 def confspec_op_attention(ctx, kv: KV, batch: Batch, layer: int, q, k_suffix, v_suffix, out, workspace,

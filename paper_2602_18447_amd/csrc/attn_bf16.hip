@@ -293,17 +293,19 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
             s_slots[tid + 1] = p.n_split > 1 ? my_tiles * p.n_split : 0;
             s_work[tid + 1] = (long long)my_tiles * p.nc_max;
             __syncthreads();
-            if (tid == 0) {  // serial exclusive scan of at most 256 entries
+            if (tid == 0) {  // serial exclusive scan of the entries of this batch of traces (at most 256)
                 s_tiles[0] = carry[0];
                 s_rest[0] = carry[1];
                 s_slots[0] = carry[2];
                 s_work[0] = carry_work;
-                for (int i = 1; i <= 256; ++i) {
+                int n = min(256, B - base);
+                for (int i = 1; i <= n; ++i) {
                     s_tiles[i] += s_tiles[i - 1];
                     s_rest[i] += s_rest[i - 1];
                     s_slots[i] += s_slots[i - 1];
                     s_work[i] += s_work[i - 1];
                 }
+                s_tiles[256] = s_tiles[n]; s_rest[256] = s_rest[n]; s_slots[256] = s_slots[n]; s_work[256] = s_work[n];
             }
             __syncthreads();
             int tile_base = s_tiles[tid], rest_base = s_rest[tid], slot_base = s_slots[tid];

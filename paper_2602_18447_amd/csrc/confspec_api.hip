@@ -38,6 +38,8 @@ static int g_prune_last_layer = 1;
 // 1: the first layers (the split_layers rule) run their GEMMs on fp16 operands when the packed weights carry
 // fp16 copies; 0: they use two-term bf16 activations against the bf16 weights
 static int g_first_layers_f16 = 1;
+// 1: bf16 models run the QKV projection with the rotary embedding in its epilogue (reordered weight rows)
+static int g_fuse_rope = 1;
 
 static int split_layers_for(const confspec_model_cfg &c) {
     if (g_split_layers >= 0) return g_split_layers;
@@ -331,6 +333,7 @@ int f16_layers_for(const confspec_model_cfg &c) {
 }
 struct PackLayout {
     size_t gate_up;        // bytes of one packed gate/up matrix (aligned)
+    size_t qkv_perm;       // bytes of one reordered wqkv matrix (aligned; bf16 models only, else 0)
     size_t f16[4];         // bytes of the fp16 copies of wqkv, wo, gate/up, down (aligned)
     size_t elems[4];
     size_t total;
@@ -345,7 +348,8 @@ PackLayout pack_layout(const confspec_model_cfg &c) {
     p.elems[3] = (size_t)c.d_model * c.d_ffn;
     size_t per16 = 0;
     for (int i = 0; i < 4; ++i) { p.f16[i] = align_up(p.elems[i] * 2); per16 += p.f16[i]; }
-    p.total = (size_t)c.n_layers * p.gate_up + (size_t)f16_layers_for(c) * per16;
+    p.qkv_perm = c.dtype == CONFSPEC_DTYPE_BF16 ? align_up(p.elems[0] * 2) : 0;
+    p.total = (size_t)c.n_layers * (p.gate_up + p.qkv_perm) + (size_t)f16_layers_for(c) * per16;
     return p;
 }
 }  // namespace
@@ -368,23 +372,32 @@ int confspec_pack_weights(confspec_ctx *ctx, const confspec_weights *in, void *d
     if (dst_bytes < P.total) return fail(ctx, CONFSPEC_E_WORKSPACE, "dev_dst has %zu bytes, %zu needed", dst_bytes, P.total);
     if (c.n_layers > 0 && !in->w_gate_up) return fail(ctx, CONFSPEC_E_INVALID_ARG, "w_gate_up is null");
     int n16 = f16_layers_for(c);
-    if (n16 > 0 && (!in->wqkv || !in->wo || !in->w_down)) return fail(ctx, CONFSPEC_E_INVALID_ARG, "a per-layer weight array is null");
+    const bool bf = c.dtype == CONFSPEC_DTYPE_BF16;
+    if (c.n_layers > 0 && ((bf && !in->wqkv) || (n16 > 0 && (!in->wo || !in->w_down))))
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "a per-layer weight array is null");
     for (int l = 0; l < c.n_layers; ++l) {
         if (!in->w_gate_up[l]) return fail(ctx, CONFSPEC_E_INVALID_ARG, "w_gate_up[%d] is null", l);
-        if (l < n16 && (!in->wqkv[l] || !in->wo[l] || !in->w_down[l]))
+        if ((bf && !in->wqkv[l]) || (l < n16 && (!in->wo[l] || !in->w_down[l])))
             return fail(ctx, CONFSPEC_E_INVALID_ARG, "layer %d has a null weight pointer", l);
     }
     hipStream_t s = (hipStream_t)stream;
     const int n = c.n_layers;
-    for (int i = 0; i < 5 * n; ++i) h_ptr_storage[i] = nullptr;
+    for (int i = 0; i < 6 * n; ++i) h_ptr_storage[i] = nullptr;
     char *at = (char *)dev_dst;
     for (int l = 0; l < n; ++l) {
         HIP_TRY(cs::launch_pack_gate_up(c.dtype, in->w_gate_up[l], at, c.d_ffn, c.d_model, s));
         h_ptr_storage[l] = at;
         at += P.gate_up;
     }
+    if (bf)
+        for (int l = 0; l < n; ++l) {
+            HIP_TRY(cs::launch_permute_heads(in->wqkv[l], at, c.n_q_heads + 2 * c.n_kv_heads, c.d_model, s));
+            h_ptr_storage[5 * n + l] = at;
+            at += P.qkv_perm;
+        }
     for (int l = 0; l < n16; ++l) {
-        const void *src[4] = {in->wqkv[l], in->wo[l], h_ptr_storage[l] /* packed order */, in->w_down[l]};
+        const void *src[4] = {h_ptr_storage[5 * n + l] /* reordered */, in->wo[l], h_ptr_storage[l] /* packed order */,
+                              in->w_down[l]};
         for (int i = 0; i < 4; ++i) {
             HIP_TRY(cs::launch_bf16_to_f16(src[i], at, P.elems[i], s));
             h_ptr_storage[(1 + i) * n + l] = at;
@@ -399,6 +412,7 @@ int confspec_pack_weights(confspec_ctx *ctx, const confspec_weights *in, void *d
     out->wo_f16 = h_ptr_storage + 2 * n;
     out->w_gate_up_f16 = h_ptr_storage + 3 * n;
     out->w_down_f16 = h_ptr_storage + 4 * n;
+    out->wqkv_perm = bf ? h_ptr_storage + 5 * n : nullptr;
     return CONFSPEC_OK;
 }
 
@@ -454,9 +468,13 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
         // when the packed weights carry fp16 copies, else with two bf16 terms; the rest is plain bf16.
         int tm = 1;
         const void *wqkv = w->wqkv[l], *wo = w->wo[l], *wgu = w->w_gate_up[l], *wdn = w->w_down[l];
+        // the projection kernel that rotates q and k itself reads wqkv with reordered rows (the half copy has
+        // that order too, so fp16 layers depend on it)
+        const bool rope_fused = c.dtype == CONFSPEC_DTYPE_BF16 && g_fuse_rope && c.head_dim == 128 && w->wqkv_perm &&
+                                w->wqkv_perm[l];
         if (c.dtype == CONFSPEC_DTYPE_BF16 && l < split_layers_for(c)) {
             tm = 2;
-            if (g_first_layers_f16 && l < w->n_f16_layers && w->wqkv_f16 && w->wo_f16 && w->w_gate_up_f16 && w->w_down_f16 &&
+            if (rope_fused && g_first_layers_f16 && l < w->n_f16_layers && w->wqkv_f16 && w->wo_f16 && w->w_gate_up_f16 && w->w_down_f16 &&
                 w->wqkv_f16[l] && w->wo_f16[l] && w->w_gate_up_f16[l] && w->w_down_f16[l]) {
                 tm = 3;
                 wqkv = w->wqkv_f16[l]; wo = w->wo_f16[l]; wgu = w->w_gate_up_f16[l]; wdn = w->w_down_f16[l];
@@ -466,11 +484,19 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
         bool prec = c.dtype == CONFSPEC_DTYPE_BF16 && l < g_attn_precise_layers;
         bool last = prune && l == c.n_layers - 1;
         HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, tm, s));
-        if ((rc = run_gemm(ctx, h, wqkv, qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, tm, 1, s))) return rc;
-        HIP_TRY(cs::launch_rope_split(c.dtype, qkv, (const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin),
-                                      ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
-                                      prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, T, c.n_q_heads,
-                                      c.n_kv_heads, c.head_dim, s));
+        if (rope_fused) {
+            cs::RopeArgs ra = {(const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin), ws + L.q, ws + L.ksuf,
+                               ws + L.vsuf, prec ? ws + L.q_lo : nullptr, prec ? ws + L.ksuf_lo : nullptr,
+                               prec ? ws + L.vsuf_lo : nullptr, c.n_q_heads, c.n_kv_heads};
+            HIP_TRY(cs::launch_gemm_bf16_rope((const cs::bf16 *)h, (const cs::bf16 *)(tm == 3 ? wqkv : w->wqkv_perm[l]), T,
+                                              qw + 2 * kw, d, tm, ra, s));
+        } else {
+            if ((rc = run_gemm(ctx, h, wqkv, qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, tm, 1, s))) return rc;
+            HIP_TRY(cs::launch_rope_split(c.dtype, qkv, (const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin),
+                                          ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
+                                          prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, T, c.n_q_heads,
+                                          c.n_kv_heads, c.head_dim, s));
+        }
         cs::AttnArgs a = make_attn_args(c, kv, batch, l, ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
                                         prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, ws + L.attn, tm);
         if ((rc = run_attention(ctx, a, ws, L, last ? pc_last : pc, last, s))) return rc;
@@ -578,6 +604,34 @@ int confspec_op_rope_split(confspec_ctx *ctx, const confspec_batch *batch, int32
     return CONFSPEC_OK;
 }
 
+int confspec_op_qkv_rope(confspec_ctx *ctx, const confspec_batch *batch, int32_t max_prefix_len, const void *dev_h,
+                         int32_t a_terms, const void *dev_wqkv_perm, void *dev_q, void *dev_k, void *dev_v,
+                         void *dev_q_lo, void *dev_k_lo, void *dev_v_lo, void *dev_workspace, size_t workspace_bytes,
+                         confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    const confspec_model_cfg &c = ctx->cfg;
+    if (c.dtype != CONFSPEC_DTYPE_BF16 || c.head_dim != 128)
+        return fail(ctx, CONFSPEC_E_UNSUPPORTED, "the rotating projection kernel needs a bf16 context with head_dim 128");
+    if (!dev_h || !dev_wqkv_perm || !dev_q || !dev_k || !dev_v) return fail(ctx, CONFSPEC_E_INVALID_ARG, "null operand");
+    if (int rl = check_lo(ctx, dev_q_lo, dev_k_lo, dev_v_lo)) return rl;
+    int rc, max_L = 0;
+    if ((rc = check_terms(ctx, a_terms, "a_terms"))) return rc;
+    if ((rc = check_batch(ctx, batch, max_prefix_len, &max_L)) != CONFSPEC_OK) return rc;
+    WsLayout L = ws_layout(c, batch->T, batch->B);
+    if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
+    char *ws = (char *)dev_workspace;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(cs::launch_prep(batch->cu_suffix, batch->prefix_lens, batch->B, batch->T, max_L, (int32_t *)(ws + L.tok_trace),
+                            (int32_t *)(ws + L.tok_pos), (int32_t *)(ws + L.last_row), s));
+    HIP_TRY(cs::launch_rope_table((const int32_t *)(ws + L.tok_pos), batch->T, c.head_dim, c.rope_theta,
+                                  (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
+    cs::RopeArgs ra = {(const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin), dev_q, dev_k, dev_v,
+                       dev_q_lo, dev_k_lo, dev_v_lo, c.n_q_heads, c.n_kv_heads};
+    HIP_TRY(cs::launch_gemm_bf16_rope((const cs::bf16 *)dev_h, (const cs::bf16 *)dev_wqkv_perm, batch->T,
+                                      (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, c.d_model, a_terms, ra, s));
+    return CONFSPEC_OK;
+}
+
 int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confspec_batch *batch, int32_t layer,
                           const void *dev_q, const void *dev_k_suffix, const void *dev_v_suffix, const void *dev_q_lo,
                           const void *dev_k_lo, const void *dev_v_lo, void *dev_out, int32_t out_terms,
@@ -648,6 +702,9 @@ int confspec_tune(const char *key, int32_t value) {
     } else if (!strcmp(key, "split_layers")) {
         if (value < -1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
         g_split_layers = value;
+    } else if (!strcmp(key, "fuse_rope")) {
+        if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
+        g_fuse_rope = value;
     } else if (!strcmp(key, "first_layers_f16")) {
         if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
         g_first_layers_f16 = value;

@@ -65,7 +65,7 @@ __device__ inline f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_FMT>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W,
                                                          void *out_v, int M, int N, int K,
-                                                         int tiles_m, int tiles_n, int n_base, int group_m, int out_fmt) {
+                                                         int tiles_m, int tiles_n, int n_base, int group_m, int out_fmt, RopeArgs rope) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int A_TERMS = A_FMT == 2 ? 2 : 1;
     constexpr bool F16 = A_FMT == 3;
@@ -81,6 +81,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     static_assert(BK == 64 || BK == 32, "BK");
     static_assert(BM % (RPD * NW) == 0 && BN % (RPD * NW) == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
     static_assert(EPI != EPI_SWIGLU || WN % 64 == 0, "SwiGLU needs a gate/up column pair inside one wave tile");
+    static_assert(EPI != EPI_ROPE || WN == 64, "the rotation pairs of a head half fill a 64-column wave tile");
     static_assert(NS >= 2 && NS <= 4, "stages");
     static_assert(MI * NI >= 2, "a k-step has at least two MFMAs");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -279,6 +280,63 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
                     }
                 }
             }
+        } else if (EPI == EPI_ROPE) {
+            // Staged columns 0..31 are columns c0..c0+31 of a head and columns 32..63 their rotation partners
+            // c0+64.. (c0 = 0 or 32).  A lane takes 8 columns of a row and the 8 partners.
+            const int n_w = n0 + wx * WN;
+            const int head = n_w >> 7, c0 = ((n_w >> 6) & 1) * 32 + (lane & 3) * 8;
+            const bool is_q = head < rope.Hq, is_v = head >= rope.Hq + rope.Hkv;
+            const int hh = is_q ? head : is_v ? head - rope.Hq - rope.Hkv : head - rope.Hq;
+            const int heads = is_q ? rope.Hq : rope.Hkv;
+            bf16 *dst_hi = reinterpret_cast<bf16 *>(is_q ? rope.q : is_v ? rope.v : rope.k);
+            bf16 *dst_lo = reinterpret_cast<bf16 *>(is_q ? rope.q_lo : is_v ? rope.v_lo : rope.k_lo);
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                int r = p * 16 + (lane >> 2), m = mrow0 + r;
+                const f32x4 *sa = reinterpret_cast<const f32x4 *>(stg + r * SROW + (lane & 3) * 8);
+                const f32x4 *sb = reinterpret_cast<const f32x4 *>(stg + r * SROW + 32 + (lane & 3) * 8);
+                f32x4 a0 = sa[0], a1 = sa[1], b0 = sb[0], b1 = sb[1];
+                if (m < M) {
+                    float va[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+                    float vb[8] = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+                    if (!is_v) {
+                        const f32x4 *cp = reinterpret_cast<const f32x4 *>(rope.cos_t + (size_t)m * 64 + c0);
+                        const f32x4 *sp = reinterpret_cast<const f32x4 *>(rope.sin_t + (size_t)m * 64 + c0);
+                        f32x4 c_0 = cp[0], c_1 = cp[1], s_0 = sp[0], s_1 = sp[1];
+                        float cs[8] = {c_0[0], c_0[1], c_0[2], c_0[3], c_1[0], c_1[1], c_1[2], c_1[3]};
+                        float sn[8] = {s_0[0], s_0[1], s_0[2], s_0[3], s_1[0], s_1[1], s_1[2], s_1[3]};
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) {
+                            float lo_ = va[q], hi_ = vb[q];
+                            va[q] = lo_ * cs[q] - hi_ * sn[q];
+                            vb[q] = hi_ * cs[q] + lo_ * sn[q];
+                        }
+                    }
+                    size_t o = ((size_t)m * heads + hh) * 128 + c0;
+                    unsigned ha[8], hb[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        ha[q] = __bfloat16_as_ushort(__float2bfloat16(va[q]));
+                        hb[q] = __bfloat16_as_ushort(__float2bfloat16(vb[q]));
+                    }
+                    u32x4 pa = {ha[0] | (ha[1] << 16), ha[2] | (ha[3] << 16), ha[4] | (ha[5] << 16), ha[6] | (ha[7] << 16)};
+                    u32x4 pb = {hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16), hb[4] | (hb[5] << 16), hb[6] | (hb[7] << 16)};
+                    *reinterpret_cast<u32x4 *>(dst_hi + o) = pa;
+                    *reinterpret_cast<u32x4 *>(dst_hi + o + 64) = pb;
+                    if (dst_lo) {
+                        unsigned la[8], lb[8];
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) {
+                            la[q] = __bfloat16_as_ushort(__float2bfloat16(va[q] - __bfloat162float(__ushort_as_bfloat16((unsigned short)ha[q]))));
+                            lb[q] = __bfloat16_as_ushort(__float2bfloat16(vb[q] - __bfloat162float(__ushort_as_bfloat16((unsigned short)hb[q]))));
+                        }
+                        u32x4 qa = {la[0] | (la[1] << 16), la[2] | (la[3] << 16), la[4] | (la[5] << 16), la[6] | (la[7] << 16)};
+                        u32x4 qb = {lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16), lb[4] | (lb[5] << 16), lb[6] | (lb[7] << 16)};
+                        *reinterpret_cast<u32x4 *>(dst_lo + o) = qa;
+                        *reinterpret_cast<u32x4 *>(dst_lo + o + 64) = qb;
+                    }
+                }
+            }
         } else {
             constexpr int LPR = WNO / 4, RP = 64 / LPR;      // lanes per output row (4 floats each), rows per pass
             float *out = reinterpret_cast<float *>(out_v);
@@ -303,7 +361,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
 // Launches the kernel on the column range [n_base, n_base + n_cols) of the N columns.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_FMT>
 static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base, int n_cols,
-                              int out_terms, hipStream_t s) {
+                              int out_terms, hipStream_t s, const RopeArgs *rope = nullptr) {
     constexpr int smem = NS * (BM + BN) * BK * 2;
     static bool attr_set = false;
     auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, A_FMT>;
@@ -326,25 +384,26 @@ static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, in
         group_m = (int)std::lround(std::sqrt((double)resident * BN / BM));
     }
     group_m = std::max(1, std::min(group_m, tiles_m));
-    kern<<<grid, 64 * WAVES_M * WAVES_N, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n, n_base, group_m, out_terms);
+    kern<<<grid, 64 * WAVES_M * WAVES_N, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n, n_base, group_m, out_terms,
+                                                    rope ? *rope : RopeArgs{});
     return hipGetLastError();
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI>
 static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base, int n_cols,
-                              int a_fmt, int out_fmt, hipStream_t s) {
+                              int a_fmt, int out_fmt, hipStream_t s, const RopeArgs *rope = nullptr) {
     if (a_fmt == 2)
-        return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s);
+        return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope);
     if (a_fmt == 3) {
         // fp16 operands: built for the two tile shapes the default choice uses
         constexpr bool has_f16 = BK == 64 && NS == 2 && ((BM == 128 && BN == 128 && WAVES_M == 2 && WAVES_N == 2) ||
                                                            (BM == 256 && BN == 256 && WAVES_M == 2 && WAVES_N == 4));
         if constexpr (has_f16)
-            return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 3>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s);
+            return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 3>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope);
         else
             return hipErrorInvalidValue;
     }
-    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s);
+    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope);
 }
 
 // Tile ids: 1 = 128x128 / 4 waves, 2 = 256x256 / 4 waves, 3 = 256x128 / 4 waves, 4 = 256x256 / 8 waves
@@ -469,7 +528,7 @@ static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, 
     }
     int tiles_n = N / 128;
     dim3 grid(((tiles_n + 7) / 8) * 8, splits);
-    kern<<<grid, 256, smem, s>>>(A, W, part, M, N, K, 1, tiles_n, 0, 1, 1);
+    kern<<<grid, 256, smem, s>>>(A, W, part, M, N, K, 1, tiles_n, 0, 1, 1, RopeArgs{});
     return hipGetLastError();
 }
 
@@ -492,6 +551,16 @@ hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int 
     if (epi == EPI_STORE_F32) return launch_epi<EPI_STORE_F32>(A, W, out, M, N, K, a_terms, out_terms, s);
     if (epi == EPI_RESID_F32) return launch_epi<EPI_RESID_F32>(A, W, out, M, N, K, a_terms, out_terms, s);
     return launch_epi<EPI_SWIGLU>(A, W, out, M, N, K, a_terms, out_terms, s);
+}
+
+// QKV projection with the rotation in the epilogue (see RopeArgs): the default tile choice, both shapes
+// have 64-column wave tiles.
+hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms, const RopeArgs &rope,
+                                 hipStream_t s) {
+    int tm = (M + 255) / 256, tn = N / 256;
+    if (N % 256 == 0 && (long)tm * tn >= 192)
+        return launch_tile<256, 256, 2, 4, 64, 2, EPI_ROPE>(A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
+    return launch_tile<128, 128, 2, 2, 64, 2, EPI_ROPE>(A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
 }
 
 }  // namespace cs

@@ -47,7 +47,18 @@ AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int
 // Upper bounds used to size the workspace.
 void attn_plan_capacity(int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles, int64_t *max_items);
 
-enum Epilogue : int { EPI_STORE_F32 = 0, EPI_RESID_F32 = 1, EPI_SWIGLU = 2 };
+enum Epilogue : int { EPI_STORE_F32 = 0, EPI_RESID_F32 = 1, EPI_SWIGLU = 2, EPI_ROPE = 3 };
+
+// EPI_ROPE (bf16 model, head_dim 128): the GEMM is the QKV projection with the rows of every head of W
+// reordered [0..31, 64..95, 32..63, 96..127], so that a wavefront's 64 output columns hold 32 rotation pairs
+// (i, i + 64).  The epilogue rotates q and k heads by the token's position and writes q, k and v in the natural
+// head layout, in bf16; the *_lo buffers (all or none) receive bf16(value - bf16(value)).
+struct RopeArgs {
+    const float *cos_t, *sin_t;   // [M, 64]
+    void *q, *k, *v;              // [M, Hq, 128], [M, Hkv, 128], [M, Hkv, 128]
+    void *q_lo, *k_lo, *v_lo;
+    int32_t Hq, Hkv;
+};
 
 // ---- small kernels (templated on storage type: float or bf16) ----
 hipError_t launch_prep(const int32_t *cu, const int32_t *plens, int B, int T, int max_L,
@@ -70,6 +81,8 @@ hipError_t launch_gather_rows(const void *src, void *dst, const int32_t *rows, i
                               size_t row_bytes, hipStream_t s);
 hipError_t launch_copy16(const void *src, void *dst, size_t n16, hipStream_t s);
 hipError_t launch_bf16_to_f16(const void *src, void *dst, size_t n, hipStream_t s);
+// dst rows = src rows with the two middle 32-row blocks of every 128-row head swapped (n_heads * 128 rows of d elements)
+hipError_t launch_permute_heads(const void *src, void *dst, int n_heads, int d, hipStream_t s);
 hipError_t launch_pack_gate_up(int dtype, const void *src, void *dst, int F, int d, hipStream_t s);
 
 struct VerdictArgs {
@@ -95,6 +108,8 @@ hipError_t launch_gemm_f32(const float *A, const float *W, void *out, int M, int
 // gemm_splitk_bytes(M, N, K * a_terms) bytes, otherwise the call falls back to one workgroup per tile.
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
                             int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
+hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms, const RopeArgs &rope,
+                                 hipStream_t s);
 int gemm_splitk_factor(int M, int N, int K_total);
 size_t gemm_splitk_bytes(int M, int N, int K_total);
 

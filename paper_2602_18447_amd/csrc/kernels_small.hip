@@ -248,6 +248,23 @@ hipError_t launch_pack_gate_up(int dtype, const void *src, void *dst, int F, int
 }
 
 // ------------------------------------------------------------------------------------------------
+// Row order of the QKV weight for the GEMM epilogue that rotates in registers: inside every 128-row head
+// the blocks of 32 rows go [0, 2, 1, 3], i.e. new row p holds old row p for p in [0,32) and [96,128),
+// old row p + 32 for p in [32,64) and old row p - 32 for p in [64,96).
+__global__ void permute_heads_kernel(const bf16 *__restrict__ src, bf16 *__restrict__ dst, int d) {
+    int p = blockIdx.x, in_head = p & 127, blk = in_head >> 5;
+    int q = (blk == 1) ? p + 32 : (blk == 2) ? p - 32 : p;
+    const u32x4_t *s = reinterpret_cast<const u32x4_t *>(src + (size_t)q * d);
+    u32x4_t *o = reinterpret_cast<u32x4_t *>(dst + (size_t)p * d);
+    for (int j = threadIdx.x; j < d / 8; j += blockDim.x) o[j] = s[j];
+}
+
+hipError_t launch_permute_heads(const void *src, void *dst, int n_heads, int d, hipStream_t s) {
+    permute_heads_kernel<<<n_heads * 128, 256, 0, s>>>((const bf16 *)src, (bf16 *)dst, d);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // bf16 -> IEEE half, element by element (every bf16 value inside the half range converts exactly; smaller
 // magnitudes land on the half subnormal grid, larger ones saturate to the largest finite half).
 __global__ void bf16_to_f16_kernel(const bf16 *__restrict__ src, __half *__restrict__ dst, size_t n) {

@@ -32,7 +32,7 @@ class Verifier:
                                               weights.w_down, packed=0)
         nbytes = cb.confspec_packed_bytes(self.ctx)
         self._packed = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
-        self._packed_ptrs = (C.c_void_p * max(5 * m.n_layers, 1))()   # pointer arrays of the packed record
+        self._packed_ptrs = (C.c_void_p * max(6 * m.n_layers, 1))()   # pointer arrays of the packed record
         self.w = cb.Weights()
         cb.confspec_pack_weights(self.ctx, w_in, self._packed, nbytes, self._packed_ptrs, self.w)
         torch.cuda.synchronize(self.device)

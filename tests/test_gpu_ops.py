@@ -207,6 +207,60 @@ def test_rope_split_positions_reach_tens_of_thousands(dtype):
     cb.confspec_destroy(ctx)
 
 
+def _perm_head_rows(n_heads):
+    """Row order of wqkv_perm: inside every 128-row head the 32-row blocks go 0, 2, 1, 3."""
+    p = np.arange(n_heads * 128)
+    blk = (p % 128) // 32
+    return np.where(blk == 1, p + 32, np.where(blk == 2, p - 32, p))
+
+
+@pytest.mark.parametrize("a_terms,with_lo", [(1, False), (3, False), (2, True)])
+@pytest.mark.parametrize("suffix_lens", [(5, 3, 9), (200, 77, 130)])
+def test_qkv_projection_with_rotary_epilogue(a_terms, with_lo, suffix_lens):
+    print(f"qkv + rope fused a_terms={a_terms} lo={with_lo} S={suffix_lens}", flush=True)
+    hd, d = 128, 256
+    wl = W.tiny_workload("qkvrope", 4, dtype="bf16", n_q_heads=4, n_kv_heads=2, head_dim=hd, d_model=d,
+                         prefix_lens=(16383, 0, 700), suffix_lens=suffix_lens, block_size=16)
+    m = wl.model
+    ctx, _ = _ctx("bf16", head_dim=hd, d_model=d)
+    batch = W.make_batch(wl, DEV)
+    bs, keep = _batch_structs(wl, batch)
+    T = wl.T
+    heads = m.n_q_heads + 2 * m.n_kv_heads
+    full = _rand((T, d), torch.float32, 31)
+    Wn = _rand((heads * hd, d), torch.float32, 32, 0.1)
+    if a_terms == 3:
+        h = full.to(torch.float16); h64 = f64(h)
+        Wt = Wn.to(torch.float16)
+    elif a_terms == 2:
+        hi = full.to(torch.bfloat16); lo = (full - hi.float()).to(torch.bfloat16)
+        h = torch.cat([hi, lo], dim=1).contiguous(); h64 = f64(hi) + f64(lo)
+        Wt = Wn.to(torch.bfloat16)
+    else:
+        h = full.to(torch.bfloat16); h64 = f64(h)
+        Wt = Wn.to(torch.bfloat16)
+    Wp = Wt[torch.as_tensor(_perm_head_rows(heads), device=DEV)].contiguous()
+    bf = torch.bfloat16
+    q = torch.zeros((T + 1, m.n_q_heads, hd), dtype=bf, device=DEV)
+    k = torch.zeros((T + 1, m.n_kv_heads, hd), dtype=bf, device=DEV)
+    v = torch.zeros((T + 1, m.n_kv_heads, hd), dtype=bf, device=DEV)
+    los = [torch.zeros_like(t) for t in (q, k, v)] if with_lo else [None, None, None]
+    ws = torch.empty(cb.confspec_workspace_bytes(ctx, T, wl.B), dtype=torch.uint8, device=DEV)
+    cb.confspec_op_qkv_rope(ctx, bs, 16384, h, a_terms, Wp, q, k, v, ws, q_lo=los[0], k_lo=los[1], v_lo=los[2])
+    torch.cuda.synchronize()
+    a = (h64 @ f64(Wt).T).reshape(T, heads, hd)
+    pos = np.concatenate([L + np.arange(S) for L, S in zip(wl.prefix_lens, wl.suffix_lens)])
+    rq = O.rope(a[:, :m.n_q_heads], pos, m.rope_theta)
+    rk = O.rope(a[:, m.n_q_heads:m.n_q_heads + m.n_kv_heads], pos, m.rope_theta)
+    rv = a[:, m.n_q_heads + m.n_kv_heads:]
+    for got, lo_t, ref in ((q, los[0], rq), (k, los[1], rk), (v, los[2], rv)):
+        val = f64(got[:T]) + (f64(lo_t[:T]) if with_lo else 0.0)
+        tol = 2.0 ** -15 if with_lo else 2.0 ** -8
+        assert np.abs(val - ref).max() <= tol * np.abs(ref).max() + 2e-5 * np.abs(ref).max()
+        assert torch.all(got[T] == 0)
+    cb.confspec_destroy(ctx)
+
+
 def _attention_case(dtype, hq, hkv, hd, prefix_lens, suffix_lens, block_size=16, seed=20, out_terms=1,
                     precise=False):
     wl = W.tiny_workload("attn", seed, dtype=dtype, n_layers=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd,

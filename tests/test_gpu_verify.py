@@ -137,6 +137,24 @@ def test_first_layers_fp16_and_two_term_both_meet_the_bound():
         G.compare(wl, res[flag], ora, f"first_layers_f16={flag}")
 
 
+def test_fused_and_separate_rotary_embedding_agree():
+    print("rope in the projection epilogue / as a kernel of its own", flush=True)
+    wl = _small_bf16("rope", 2008, (700, 64, 0, 3000, 129), (40, 96, 20, 7, 1), n_layers=8)
+    weights, batch, kv = G.build_inputs(wl)
+    ver = Verifier(wl.model, weights)
+    res = {}
+    try:
+        for flag in (0, 1):
+            cb.confspec_tune("fuse_rope", flag)
+            res[flag] = G.run_gpu(wl, weights, batch, kv, verifier=ver)
+    finally:
+        cb.confspec_tune("fuse_rope", 1)
+    ver.close()
+    ora = G.run_oracle(wl, weights, batch, kv, res[1]["taus"], res[1]["vids"])
+    for flag in (0, 1):
+        G.compare(wl, res[flag], ora, f"fuse_rope={flag}")
+
+
 def test_config2_draft_shape_full_size_sampled_traces():
     print("config 2", flush=True)
     G.parity_case(W.config(2), traces=[0, 13, 31])
