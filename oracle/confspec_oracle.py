@@ -254,3 +254,70 @@ def prefix_pass(cfg, model, prefix_ids: Sequence[np.ndarray]):
     k_dense = [[kvs[b][l][0] for b in range(len(traces))] for l in range(cfg.n_layers)]
     v_dense = [[kvs[b][l][1] for b in range(len(traces))] for l in range(cfg.n_layers)]
     return k_dense, v_dense
+
+
+# --------------------------------------------------------------------------- #
+# Two-tier cascade over the k drafted steps of one request (Algorithm 1, Stage 2;
+# Section 4.2, "Cascaded Decision Rule", Eq. 4)
+# --------------------------------------------------------------------------- #
+NOT_REACHED = -1
+
+
+def cascade_request(draft_verdict: Sequence[int], draft_conf: Sequence[float], target_verdict, gamma: float,
+                    accept_index: int = 0):
+    """The verification loop of one request, step by step as the algorithm states it.
+
+    draft_verdict[j], draft_conf[j]: the small model's decision on step j and its confidence.
+    target_verdict: callable j -> the large model's decision on step j; it is called only for the
+    steps the loop escalates (confidence below gamma), in order.
+    Returns (m, decision, escalated): m = number of leading accepted steps; decision[j] = the
+    cascaded decision V of step j for the steps the loop reached (up to and including the first
+    rejection), NOT_REACHED after that; escalated[j] = 1 where the large model was consulted.
+    """
+    k = len(draft_verdict)
+    decision = [NOT_REACHED] * k
+    escalated = [0] * k
+    m = 0
+    for j in range(k):
+        if float(draft_conf[j]) >= float(gamma):      # Eq. 4, first case: keep the small model's decision
+            v = int(draft_verdict[j])
+        else:                                         # second case: the large model decides
+            v = int(target_verdict(j))
+            escalated[j] = 1
+        decision[j] = v
+        if v == accept_index:
+            m += 1
+        else:
+            break                                     # verification stops at the first rejection
+    return m, decision, escalated
+
+
+def cascade_verify(draft, target, block_size: int, suffix_ids, cu_suffix, prefix_lens, verdict_ids, gamma: float,
+                   req_start: Sequence[int]) -> dict:
+    """Cascade over a batch of requests.  draft / target: dicts with cfg, model, kv (each model has its
+    own cache of the same contexts).  Traces req_start[r] .. req_start[r+1]-1 are the drafted steps of
+    request r in order.  The large model's pass runs only for the steps the loop escalates."""
+    B = len(prefix_lens)
+    d = verify(draft["cfg"], draft["model"], draft["kv"], block_size, suffix_ids, cu_suffix, prefix_lens, verdict_ids,
+               [gamma])
+    conf_t = np.full(B, np.nan)
+    verdict_t = np.full(B, NOT_REACHED, dtype=np.int64)
+    logits_t = np.full((B, len(verdict_ids)), np.nan)
+
+    def ask_target(b):
+        t = verify(target["cfg"], target["model"], target["kv"], block_size, suffix_ids, cu_suffix, prefix_lens,
+                   verdict_ids, [gamma], trace_subset=[b])
+        conf_t[b], verdict_t[b], logits_t[b] = t["conf"][0], t["verdict"][0], t["logits"][0]
+        return int(t["verdict"][0])
+
+    R = len(req_start) - 1
+    m = np.zeros(R, dtype=np.int64)
+    decision = np.full(B, NOT_REACHED, dtype=np.int64)
+    escalated = np.zeros(B, dtype=np.uint8)
+    for r in range(R):
+        lo, hi = int(req_start[r]), int(req_start[r + 1])
+        m[r], dec, esc = cascade_request(d["verdict"][lo:hi], d["conf"][lo:hi], lambda j, lo=lo: ask_target(lo + j), gamma)
+        decision[lo:hi] = dec
+        escalated[lo:hi] = esc
+    return dict(accepted_steps=m, decision=decision, escalated=escalated, conf_draft=d["conf"], verdict_draft=d["verdict"],
+                logits_draft=d["logits"], conf_target=conf_t, verdict_target=verdict_t, logits_target=logits_t)
