@@ -1,0 +1,74 @@
+/*
+ * confspec_cascade.h - the two-tier cascade over the drafted steps of a batch of requests
+ * (Section 4.2, "Cascaded Decision Rule", Eq. 4; Algorithm 1, Stage 2).
+ *
+ * Every trace of the batch is one drafted step of one request (context + drafted step + target step +
+ * verification prompt as suffix).  The small model verifies every trace; a decision whose confidence
+ * reaches gamma is kept, the others are escalated to the large model (Eq. 4); within a request the
+ * steps are then walked in order and accepted until the first rejection (the loop of Stage 2), which
+ * gives m, the number of drafted steps that join the context (Stage 3).
+ *
+ * Both models read the same token ids (one tokenizer; the embedding tables may be padded to different
+ * sizes, ids must be valid for both) and have each their own paged cache of the same contexts.  The large model's pass runs on the compacted sub-batch of the traces that can be consulted:
+ * confidence below gamma and no earlier step of the request rejected by a confident small-model decision
+ * (steps after such a rejection are never reached by the loop, so leaving them out changes nothing).
+ *
+ * Unlike confspec_verify this call synchronises the stream once, between the two passes: the size of the
+ * second pass is decided on the device and the host plans its launches from it.
+ */
+#ifndef CONFSPEC_CASCADE_H
+#define CONFSPEC_CASCADE_H
+
+#include "confspec.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CONFSPEC_NOT_REACHED (-1)
+
+/* Requests: traces req_start[r] .. req_start[r+1]-1 are the drafted steps of request r, in order.
+ * req_start[0] = 0, req_start[n_requests] = B, every request has at least one step.
+ * req_start is a dev array, h_req_start a host copy with the same values. */
+typedef struct {
+    int32_t n_requests;
+    const int32_t *req_start;
+    const int32_t *h_req_start;
+} confspec_requests;
+
+/* Outputs, all dev, written by the call.  verdict values are indices into the verdict id list;
+ * index 0 is "accept". */
+typedef struct {
+    float *conf_draft;        /* [B]  confidence of the small model's decision                          */
+    int32_t *verdict_draft;   /* [B]  the small model's decision                                        */
+    float *conf_target;       /* [B]  the large model's confidence, NaN where its pass left the trace out */
+    int32_t *verdict_target;  /* [B]  its decision, CONFSPEC_NOT_REACHED where left out                  */
+    int32_t *decision;        /* [B]  cascaded decision of the steps the loop reaches (the accepted ones and
+                                      the first rejection of each request), CONFSPEC_NOT_REACHED after that */
+    uint8_t *escalated;       /* [B]  1 where the loop consulted the large model                        */
+    uint8_t *target_ran;      /* [B]  1 where the large model's pass included the trace                 */
+    int32_t *accepted_steps;  /* [n_requests]  m                                                        */
+} confspec_cascade_out;
+
+/* Bytes of dev scratch confspec_cascade needs for batches up to max_B traces and max_T suffix tokens with a
+ * large-model block table of max_blocks_per_seq_target entries per trace. */
+size_t confspec_cascade_scratch_bytes(int32_t max_B, int32_t max_T, int32_t max_blocks_per_seq_target);
+
+/* One cascade over `batch`.  draft / target: contexts, packed weights, caches and workspaces (each sized by
+ * confspec_workspace_bytes of its context for the whole batch) of the two models; verdict ids must lie inside both
+ * vocabularies.  gamma in [0, 1] (values above 1 are allowed and escalate everything).  dev_scratch: 256-byte
+ * aligned, >= confspec_cascade_scratch_bytes.  h_n_target (host, may be NULL) receives the number of traces in
+ * the large model's pass.  Errors as in confspec.h, reported on the draft context; the checks of the
+ * request list, the scratch, both caches and both workspaces happen before the first launch. */
+int confspec_cascade(confspec_ctx *draft, const confspec_weights *draft_weights, const confspec_kv *draft_kv,
+                     void *draft_workspace, size_t draft_workspace_bytes, confspec_ctx *target,
+                     const confspec_weights *target_weights, const confspec_kv *target_kv, void *target_workspace,
+                     size_t target_workspace_bytes, const confspec_batch *batch, const confspec_requests *requests,
+                     const int32_t *h_verdict_ids, int32_t n_verdict, float gamma, void *dev_scratch,
+                     size_t scratch_bytes, const confspec_cascade_out *out, int32_t *h_n_target,
+                     confspec_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONFSPEC_CASCADE_H */

@@ -49,6 +49,16 @@ class Batch(C.Structure):
                 ("h_prefix_lens", C.POINTER(C.c_int32))]
 
 
+class Requests(C.Structure):
+    _fields_ = [("n_requests", C.c_int32), ("req_start", C.c_void_p), ("h_req_start", C.POINTER(C.c_int32))]
+
+
+class CascadeOut(C.Structure):
+    _fields_ = [("conf_draft", C.c_void_p), ("verdict_draft", C.c_void_p), ("conf_target", C.c_void_p),
+                ("verdict_target", C.c_void_p), ("decision", C.c_void_p), ("escalated", C.c_void_p),
+                ("target_ran", C.c_void_p), ("accepted_steps", C.c_void_p)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -94,6 +104,11 @@ def _load() -> C.CDLL:
                                              vp, vp, vp, vp, vp]
     lib.confspec_op_copy.restype = C.c_int
     lib.confspec_op_copy.argtypes = [vp, vp, sz, vp]
+    lib.confspec_cascade_scratch_bytes.restype = sz
+    lib.confspec_cascade_scratch_bytes.argtypes = [i32, i32, i32]
+    lib.confspec_cascade.restype = C.c_int
+    lib.confspec_cascade.argtypes = [vp, P(Weights), P(KV), vp, sz, vp, P(Weights), P(KV), vp, sz, P(Batch), P(Requests),
+                                     P(i32), i32, C.c_float, vp, sz, P(CascadeOut), P(i32), vp]
     lib.confspec_tune.restype = C.c_int
     lib.confspec_tune.argtypes = [C.c_char_p, i32]
     return lib
@@ -104,7 +119,8 @@ lib = _load()
 EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec_last_error",
             "confspec_workspace_bytes", "confspec_packed_bytes", "confspec_pack_weights", "confspec_verify",
             "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_qkv_rope", "confspec_op_attention",
-            "confspec_op_verdict_gate", "confspec_op_copy", "confspec_tune"]
+            "confspec_op_verdict_gate", "confspec_op_copy", "confspec_tune", "confspec_cascade_scratch_bytes",
+            "confspec_cascade"]
 
 
 class ConfSpecError(RuntimeError):
@@ -238,6 +254,36 @@ def confspec_op_copy(src, dst, nbytes: int, stream=None) -> None:
     rc = lib.confspec_op_copy(_ptr(src), _ptr(dst), int(nbytes), _stream_handle(stream))
     if rc != OK:
         raise ConfSpecError(rc, f"confspec_op_copy({nbytes})")
+
+
+def confspec_cascade_scratch_bytes(max_B: int, max_T: int, max_blocks_per_seq_target: int) -> int:
+    return int(lib.confspec_cascade_scratch_bytes(max_B, max_T, max_blocks_per_seq_target))
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def confspec_cascade(draft_ctx, draft_w: Weights, draft_kv: KV, draft_ws, target_ctx, target_w: Weights, target_kv: KV,
+                     target_ws, batch: Batch, requests: Requests, verdict_ids: Sequence[int], gamma: float, scratch,
+                     out: CascadeOut, stream=None) -> int:
+    """Returns the number of traces the large model's pass held."""
+    nv = len(verdict_ids)
+    ids = (C.c_int32 * max(nv, 1))(*[int(v) for v in verdict_ids])
+    n_target = C.c_int32(0)
+    _check(draft_ctx, lib.confspec_cascade(draft_ctx, C.byref(draft_w), C.byref(draft_kv), _ptr(draft_ws), _nbytes(draft_ws),
+                                           target_ctx, C.byref(target_w), C.byref(target_kv), _ptr(target_ws),
+                                           _nbytes(target_ws), C.byref(batch), C.byref(requests), ids, nv, float(gamma),
+                                           _ptr(scratch), _nbytes(scratch), C.byref(out), C.byref(n_target),
+                                           _stream_handle(stream)))
+    return int(n_target.value)
+
+
+def make_requests(req_start, h_req_start):
+    """req_start: device int32 tensor [R+1]; h_req_start: the same values on the host.  Returns (Requests, keepalive)."""
+    import numpy as np
+    hr = np.ascontiguousarray(h_req_start, dtype=np.int32)
+    return Requests(len(hr) - 1, _ptr(req_start), hr.ctypes.data_as(C.POINTER(C.c_int32))), hr
 
 
 def confspec_tune(key: str, value: int) -> None:

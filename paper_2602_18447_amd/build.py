@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libconfspec.so")
 
-SOURCES = ["confspec_api.hip", "kernels_small.hip", "path_f32.hip", "gemm_bf16.hip", "attn_bf16.hip"]
+SOURCES = ["confspec_api.hip", "kernels_small.hip", "path_f32.hip", "gemm_bf16.hip", "attn_bf16.hip", "cascade.hip"]
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -25,7 +25,7 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = True, jobs: int = 5) -> str:
+def build(verbose: bool = True, jobs: int = 6) -> str:
     os.makedirs(BUILD_DIR, exist_ok=True)
     hipcc = _hipcc()
 

@@ -8,9 +8,11 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "../../include/confspec.h"
 #include "../../include/confspec_ops.h"
+#include "../../include/confspec_cascade.h"
 #include "kernels.h"
 
 namespace cs {
@@ -726,6 +728,126 @@ int confspec_tune(const char *key, int32_t value) {
     } else {
         return CONFSPEC_E_INVALID_ARG;
     }
+    return CONFSPEC_OK;
+}
+
+// ---- two-tier cascade (Section 4.2, Eq. 4; Algorithm 1, Stage 2) ----
+
+namespace {
+struct CascadeLayout {
+    size_t keep, pos_of, sel_idx, cu_out, plens_out, n_out, ids_out, table_out, logits_d, logits_t, conf_t, verdict_t,
+        accept_t, total;
+};
+CascadeLayout cascade_layout(int64_t B, int64_t T, int64_t max_blocks) {
+    CascadeLayout L;
+    size_t at = 0;
+    auto take = [&](size_t bytes) { size_t o = at; at += (bytes + 255) & ~(size_t)255; return o; };
+    L.keep = take(B);
+    L.pos_of = take(B * 4);
+    L.sel_idx = take(B * 4);
+    L.cu_out = take((B + 1) * 4);
+    L.plens_out = take(B * 4);
+    L.n_out = take(8);
+    L.ids_out = take(T * 4);
+    L.table_out = take(B * max_blocks * 4);
+    L.logits_d = take(B * CONFSPEC_MAX_VERDICT * 4);
+    L.logits_t = take(B * CONFSPEC_MAX_VERDICT * 4);
+    L.conf_t = take(B * 4);
+    L.verdict_t = take(B * 4);
+    L.accept_t = take(B);
+    L.total = at;
+    return L;
+}
+}  // namespace
+
+size_t confspec_cascade_scratch_bytes(int32_t max_B, int32_t max_T, int32_t max_blocks_per_seq_target) {
+    if (max_B < 1 || max_T < 1 || max_blocks_per_seq_target < 1) return 0;
+    return cascade_layout(max_B, max_T, max_blocks_per_seq_target).total;
+}
+
+int confspec_cascade(confspec_ctx *draft, const confspec_weights *wd, const confspec_kv *kvd, void *ws_d, size_t ws_d_bytes,
+                     confspec_ctx *target, const confspec_weights *wt, const confspec_kv *kvt, void *ws_t,
+                     size_t ws_t_bytes, const confspec_batch *batch, const confspec_requests *req,
+                     const int32_t *h_verdict_ids, int32_t n_verdict, float gamma, void *dev_scratch, size_t scratch_bytes,
+                     const confspec_cascade_out *out, int32_t *h_n_target, confspec_stream stream) {
+    confspec_ctx *ctx = draft;
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!target) return fail(ctx, CONFSPEC_E_INVALID_ARG, "target context is null");
+    for (int i = 0; h_verdict_ids && i < n_verdict && i < CONFSPEC_MAX_VERDICT; ++i)
+        if (h_verdict_ids[i] < 0 || h_verdict_ids[i] >= std::min(draft->cfg.vocab, target->cfg.vocab))
+            return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "verdict id %d = %d outside the smaller vocabulary [0, %d)", i,
+                        h_verdict_ids[i], std::min(draft->cfg.vocab, target->cfg.vocab));
+    if (!out || !out->conf_draft || !out->verdict_draft || !out->conf_target || !out->verdict_target || !out->decision ||
+        !out->escalated || !out->target_ran || !out->accepted_steps)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "an output pointer is null");
+    if (!(gamma >= 0.0f)) return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "gamma = %g is negative or not a number", (double)gamma);
+    int rc, max_L = 0;
+    if (!kvd || !kvt) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv is null");
+    int64_t cap_d = (int64_t)kvd->max_blocks_per_seq * kvd->block_size, cap_t = (int64_t)kvt->max_blocks_per_seq * kvt->block_size;
+    if ((rc = check_batch(ctx, batch, std::min(cap_d, cap_t), &max_L)) != CONFSPEC_OK) return rc;
+    if ((rc = check_kv(ctx, kvd, max_L > 0)) != CONFSPEC_OK) return rc;
+    if ((rc = check_kv(target, kvt, max_L > 0)) != CONFSPEC_OK) return fail(ctx, rc, "target: %s", target->err.c_str());
+    const int B = batch->B, T = batch->T;
+    if (!req || !req->req_start || !req->h_req_start) return fail(ctx, CONFSPEC_E_INVALID_ARG, "requests or one of its arrays is null");
+    const int R = req->n_requests;
+    if (R < 1 || R > B) return fail(ctx, CONFSPEC_E_INVALID_ARG, "n_requests = %d outside [1, B = %d]", R, B);
+    if (req->h_req_start[0] != 0 || req->h_req_start[R] != B)
+        return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "req_start must run from 0 to B = %d (got %d .. %d)", B, req->h_req_start[0],
+                    req->h_req_start[R]);
+    for (int r = 0; r < R; ++r)
+        if (req->h_req_start[r + 1] <= req->h_req_start[r])
+            return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "req_start not strictly increasing at request %d (every request needs >= 1 step)", r);
+    CascadeLayout C = cascade_layout(B, T, kvt->max_blocks_per_seq);
+    if ((rc = check_ws(ctx, dev_scratch, scratch_bytes, C.total)) != CONFSPEC_OK) return rc;
+    // the large model's pass is a sub-batch of this one, so a workspace for the whole batch is enough for it
+    if ((rc = check_ws(ctx, ws_t, ws_t_bytes, ws_layout(target->cfg, T, B).total)) != CONFSPEC_OK) return rc;
+    if (!wt || wt->packed != 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "target weights must be packed with confspec_pack_weights");
+
+    hipStream_t s = (hipStream_t)stream;
+    char *sc = (char *)dev_scratch;
+    uint8_t *keep = (uint8_t *)(sc + C.keep);
+    int32_t *pos_of = (int32_t *)(sc + C.pos_of), *sel_idx = (int32_t *)(sc + C.sel_idx);
+    int32_t *cu_out = (int32_t *)(sc + C.cu_out), *plens_out = (int32_t *)(sc + C.plens_out), *n_out = (int32_t *)(sc + C.n_out);
+    int32_t *ids_out = (int32_t *)(sc + C.ids_out), *table_out = (int32_t *)(sc + C.table_out);
+    float *conf_t_c = (float *)(sc + C.conf_t);
+    int32_t *verdict_t_c = (int32_t *)(sc + C.verdict_t);
+
+    // small model on every trace; its gate bit conf >= gamma is taken in the verdict kernel.  Thresholds above 1
+    // keep nothing, which is what any value above 1 means.
+    float tau = gamma > 1.0f ? 1.0f : gamma;
+    const bool keep_nothing = gamma > 1.0f;
+    if ((rc = confspec_verify(draft, wd, kvd, batch, h_verdict_ids, n_verdict, &tau, 1, ws_d, ws_d_bytes,
+                              (float *)(sc + C.logits_d), out->conf_draft, out->verdict_draft, keep, s)) != CONFSPEC_OK)
+        return rc;
+    if (keep_nothing) HIP_TRY(hipMemsetAsync(keep, 0, B, s));
+    HIP_TRY(cs::launch_cascade_select(keep, out->verdict_draft, req->req_start, R, B, batch->cu_suffix, batch->prefix_lens, T,
+                                      out->target_ran, pos_of, sel_idx, cu_out, plens_out, n_out, s));
+    HIP_TRY(cs::launch_cascade_gather(pos_of, batch->cu_suffix, cu_out, batch->suffix_ids, ids_out, kvt->block_table,
+                                      table_out, kvt->max_blocks_per_seq, B, T, s));
+    // The one host round trip of the call: how many traces the large model sees, their suffix offsets and prefix
+    // lengths (the host plans that pass's launches from them).
+    int32_t h_n[2] = {0, 0};
+    HIP_TRY(hipMemcpyAsync(h_n, n_out, sizeof h_n, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    const int n = h_n[0];
+    if (n < 0 || n > B || h_n[1] < 0 || h_n[1] > T) return fail(ctx, CONFSPEC_E_HIP, "selection returned %d traces, %d tokens", n, h_n[1]);
+    if (h_n_target) *h_n_target = n;
+    if (n > 0) {
+        std::vector<int32_t> h_cu(n + 1), h_pl(n);
+        HIP_TRY(hipMemcpyAsync(h_cu.data(), cu_out, (size_t)(n + 1) * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipMemcpyAsync(h_pl.data(), plens_out, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        confspec_batch sub = {n, h_n[1], ids_out, cu_out, plens_out, h_cu.data(), h_pl.data()};
+        confspec_kv kv_sub = *kvt;
+        kv_sub.block_table = table_out;
+        if ((rc = confspec_verify(target, wt, &kv_sub, &sub, h_verdict_ids, n_verdict, &tau, 1, ws_t, ws_t_bytes,
+                                  (float *)(sc + C.logits_t), conf_t_c, verdict_t_c, (uint8_t *)(sc + C.accept_t), s)) !=
+            CONFSPEC_OK)
+            return fail(ctx, rc, "target: %s", target->err.c_str());
+    }
+    HIP_TRY(cs::launch_cascade_merge(keep, out->verdict_draft, pos_of, conf_t_c, verdict_t_c, req->req_start, R, B, n,
+                                     out->conf_target, out->verdict_target, out->decision, out->escalated,
+                                     out->accepted_steps, s));
     return CONFSPEC_OK;
 }
 

@@ -77,3 +77,40 @@ class Verifier:
         outs = outputs or self.alloc_outputs(bs.B, len(verdict_ids), len(taus))
         cb.confspec_verify(self.ctx, self.w, kvs, bs, verdict_ids, taus, ws, *outs, stream=stream)
         return outs
+
+
+class Cascade:
+    """The two-tier cascade over the drafted steps of a batch of requests: a small and a large Verifier that read
+    the same token ids, each with its own cache of the same contexts.  Only buffers are owned here."""
+
+    NAMES = ("conf_draft", "verdict_draft", "conf_target", "verdict_target", "decision", "escalated", "target_ran",
+             "accepted_steps")
+
+    def __init__(self, draft: Verifier, target: Verifier):
+        self.draft, self.target = draft, target
+        self._scratch = None
+
+    def alloc_outputs(self, B: int, R: int):
+        dev = self.draft.device
+        f32, i32, u8 = torch.float32, torch.int32, torch.uint8
+        dts = (f32, i32, f32, i32, i32, u8, u8, i32)
+        return {n: torch.empty(R if n == "accepted_steps" else B, dtype=dt, device=dev) for n, dt in zip(self.NAMES, dts)}
+
+    def run(self, draft_kv, target_kv, batch, h_req_start, verdict_ids: Sequence[int], gamma: float, outputs=None,
+            stream=None):
+        """One cascade; synchronises the stream once inside.  Returns (outputs dict of device tensors, traces the
+        large model's pass held)."""
+        kd, bs, keep = self.draft.bind(draft_kv, batch)
+        kt, _, keep_t = self.target.bind(target_kv, batch)
+        hr = np.ascontiguousarray(h_req_start, dtype=np.int32)
+        req_dev = torch.from_numpy(hr).to(self.draft.device)
+        reqs, keep_r = cb.make_requests(req_dev, hr)
+        need = cb.confspec_cascade_scratch_bytes(bs.B, bs.T, kt.max_blocks_per_seq)
+        if self._scratch is None or self._scratch.numel() < need:
+            self._scratch = torch.empty(need, dtype=torch.uint8, device=self.draft.device)
+        outs = outputs or self.alloc_outputs(bs.B, len(hr) - 1)
+        co = cb.CascadeOut(*[outs[n].data_ptr() for n in self.NAMES])
+        n_target = cb.confspec_cascade(self.draft.ctx, self.draft.w, kd, self.draft.workspace(bs.T, bs.B),
+                                       self.target.ctx, self.target.w, kt, self.target.workspace(bs.T, bs.B), bs, reqs,
+                                       verdict_ids, gamma, self._scratch, co, stream=stream)
+        return outs, n_target

@@ -14,7 +14,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared_symbols():
     names = set()
-    for hdr in ("confspec.h", "confspec_ops.h"):
+    for hdr in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not hdr.endswith(".h"):
+            continue
         text = open(os.path.join(ROOT, "include", hdr)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names |= set(re.findall(r"\b(confspec_[a-z_0-9]+)\s*\(", text))
@@ -24,7 +26,7 @@ def _declared_symbols():
 def test_library_exports_every_declared_symbol():
     declared = _declared_symbols()
     assert {"confspec_create", "confspec_verify", "confspec_pack_weights", "confspec_workspace_bytes",
-            "confspec_op_gemm", "confspec_op_attention", "confspec_op_verdict_gate"} <= declared
+            "confspec_op_gemm", "confspec_op_attention", "confspec_op_verdict_gate", "confspec_cascade"} <= declared
     for name in declared:
         assert hasattr(cb.lib, name), f"{name} declared in include/ but not exported"
     assert set(cb.EXPORTED) == declared
@@ -157,3 +159,35 @@ def test_op_gemm_and_tune_validation():
             cb.confspec_op_copy(src, dst, n, stream=0)
         assert ei.value.code == cb.E_INVALID_ARG
     cb.confspec_destroy(ctx)
+
+
+def test_cascade_validates_before_any_launch():
+    cfg_d, cfg_t = _cfg(), _cfg(n_layers=3, d_model=512, n_q_heads=4, d_ffn=1024)
+    ctx_d, ctx_t = cb.confspec_create(cfg_d), cb.confspec_create(cfg_t)
+    fake, w, kv, batch, keep = _verify_args(cfg_d, B=3, S=(3, 2, 4), L=(5, 0, 7))
+    _, w_t, _, _, keep_t = _verify_args(cfg_t, B=3, S=(3, 2, 4), L=(5, 0, 7))
+    out = cb.CascadeOut(*([fake.data_ptr()] * 8))
+    assert cb.confspec_cascade_scratch_bytes(3, 9, 4) % 256 == 0
+    assert cb.confspec_cascade_scratch_bytes(0, 9, 4) == 0
+
+    def call(req=(0, 2, 3), gamma=0.9, ctx_t=ctx_t, out=out, scratch=fake, kv_t=kv, ws_t=fake):
+        reqs, keep_r = cb.make_requests(fake, np.asarray(req, dtype=np.int32))
+        return cb.confspec_cascade(ctx_d, w, kv, fake, ctx_t, w_t, kv_t, ws_t, batch, reqs, [1, 2], gamma, scratch, out,
+                                   stream=0)
+
+    _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(req=(0, 2, 2, 3)))      # a request without steps
+    _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(req=(0, 2)))            # does not cover the batch
+    _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(req=(1, 3)))
+    _expect(ctx_d, cb.E_INVALID_ARG, lambda: call(req=(0, 1, 2, 3, 4)))    # more requests than traces
+    _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(gamma=-0.1))
+    _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(gamma=float("nan")))
+    _expect(ctx_d, cb.E_INVALID_ARG, lambda: call(ctx_t=None))
+    _expect(ctx_d, cb.E_INVALID_ARG, lambda: call(out=cb.CascadeOut()))
+    _expect(ctx_d, cb.E_WORKSPACE, lambda: call(scratch=_FakeDev(nbytes=256)))
+    _expect(ctx_d, cb.E_WORKSPACE, lambda: call(ws_t=_FakeDev(nbytes=1024)))
+    _expect(ctx_d, cb.E_WORKSPACE, lambda: call(scratch=_FakeDev(addr=0x10010)))
+    _expect(ctx_d, cb.E_UNSUPPORTED, lambda: call(kv_t=cb.make_kv(fake, fake, fake, 8, 32, 4)))
+    ctx_v = cb.confspec_create(_cfg(vocab=2))      # verdict id 2 is outside the large model's vocabulary
+    _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(ctx_t=ctx_v))
+    for c in (ctx_d, ctx_t, ctx_v):
+        cb.confspec_destroy(c)
