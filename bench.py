@@ -51,6 +51,56 @@ def _blas_threads():
     return os.cpu_count()
 
 
+def _time_cascade(W, wl, draft_ver, draft_kv, batch, vids, dev, reps):
+    """Wall time of confspec_cascade calls (they synchronise once inside, so host time is the measure): the small
+    model's pass over every trace, selection, and the large model's pass over the escalated sub-batch.  Requests of
+    1 to 5 drafted steps."""
+    import numpy as np
+    import torch
+
+    from paper_2602_18447_amd.runner import Cascade, Verifier
+
+    wl_t = W.Workload("cascade_target", W.TARGET_SHAPE, wl.seed + 10, wl.prefix_lens, wl.suffix_lens)
+    w_t = W.make_weights(wl_t.model, wl_t.seed, dev)
+    kv_t = W.make_seeded_kv(wl_t, batch, dev)
+    tgt = Verifier(wl_t.model, w_t)
+    casc = Cascade(draft_ver, tgt)
+    req = [0]
+    k = 1
+    while req[-1] < wl.B:
+        req.append(min(req[-1] + k, wl.B))
+        k = k % 5 + 1
+    outs = casc.alloc_outputs(wl.B, len(req) - 1)
+    res = {}
+    for gamma in (0.9, 0.6):
+        for _ in range(2):
+            _, n_t = casc.run(draft_kv, kv_t, batch, req, vids, gamma, outputs=outs)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            casc.run(draft_kv, kv_t, batch, req, vids, gamma, outputs=outs)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        res[f"gamma_{gamma}"] = dict(ms_per_call=round(ms, 3), traces_in_large_pass=n_t,
+                                     escalated=int(outs["escalated"].sum().item()),
+                                     accepted_steps=int(outs["accepted_steps"].sum().item()),
+                                     steps_decided_per_s=round(wl.B / (ms * 1e-3), 1))
+    # the large model alone on the whole batch, for scale
+    o_t = tgt.alloc_outputs(wl.B, len(vids), 1)
+    for _ in range(2):
+        tgt.verify(kv_t, batch, vids, [0.9], outputs=o_t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        tgt.verify(kv_t, batch, vids, [0.9], outputs=o_t)
+    torch.cuda.synchronize()
+    res["large_model_whole_batch_ms"] = round((time.perf_counter() - t0) / reps * 1e3, 3)
+    res["requests"] = len(req) - 1
+    res["large_model"] = dict(layers=wl_t.model.n_layers, d_model=wl_t.model.d_model)
+    tgt.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +112,9 @@ def main():
                     help="confspec_tune setting applied before the run (repeatable), for measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the plain copy kernel (1 GiB, 5 times): the yardstick for HBM byte counters")
+    ap.add_argument("--cascade", action="store_true",
+                    help="also time the two-tier cascade call (this workload's batch, the 32B-shaped model as the large "
+                         "one, gamma 0.9 and 0.6) and report it under \"cascade\"")
     ap.add_argument("--cpu-baseline-traces", type=int, default=6,
                     help="traces of the workload the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -199,6 +252,10 @@ def main():
                          GBps=round(2 * nbytes / (copy_ms * 1e-3) / 1e9, 1))
         del src, dst
 
+    cascade_info = None
+    if args.cascade:
+        cascade_info = _time_cascade(W, wl, ver, kv, batch, vids, dev, max(args.steps // 2, 3))
+
     # ---- CPU oracle on a bounded sample of the same workload (reported baseline only)
     cpu = None
     if args.cpu_baseline_traces > 0:
@@ -225,6 +282,7 @@ def main():
                    "launch": "hip_graph_replay" if graph_ok else "eager", "eager_ms_per_step": round(eager_ms, 4),
                    **({"tune": args.tune} if args.tune else {})},
         "roofline": roofline, "cpu_baseline": cpu, **({"copy_calibration": copy_info} if copy_info else {}),
+        **({"cascade": cascade_info} if cascade_info else {}),
     }))
 
 

@@ -21,4 +21,6 @@ from .synth import (  # noqa: F401
     pages_from_dense,
     draw_verdict_ids,
     torch_dtype,
+    DRAFT_SHAPE,
+    TARGET_SHAPE,
 )

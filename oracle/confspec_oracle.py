@@ -293,16 +293,24 @@ def cascade_request(draft_verdict: Sequence[int], draft_conf: Sequence[float], t
 
 
 def cascade_verify(draft, target, block_size: int, suffix_ids, cu_suffix, prefix_lens, verdict_ids, gamma: float,
-                   req_start: Sequence[int]) -> dict:
+                   req_start: Sequence[int], request_subset: Optional[Sequence[int]] = None) -> dict:
     """Cascade over a batch of requests.  draft / target: dicts with cfg, model, kv (each model has its
     own cache of the same contexts).  Traces req_start[r] .. req_start[r+1]-1 are the drafted steps of
-    request r in order.  The large model's pass runs only for the steps the loop escalates."""
+    request r in order.  The large model's pass runs only for the steps the loop escalates.
+    request_subset: evaluate these requests only (requests are independent); the entries of all other
+    requests and traces stay NaN / NOT_REACHED."""
     B = len(prefix_lens)
+    R = len(req_start) - 1
+    which = list(range(R)) if request_subset is None else [int(r) for r in request_subset]
+    tr = [b for r in which for b in range(int(req_start[r]), int(req_start[r + 1]))]
     d = verify(draft["cfg"], draft["model"], draft["kv"], block_size, suffix_ids, cu_suffix, prefix_lens, verdict_ids,
-               [gamma])
+               [gamma], trace_subset=tr)
+    nv = len(verdict_ids)
+    conf_d, verdict_d, logits_d = np.full(B, np.nan), np.full(B, NOT_REACHED, dtype=np.int64), np.full((B, nv), np.nan)
+    conf_d[tr], verdict_d[tr], logits_d[tr] = d["conf"], d["verdict"], d["logits"]
     conf_t = np.full(B, np.nan)
     verdict_t = np.full(B, NOT_REACHED, dtype=np.int64)
-    logits_t = np.full((B, len(verdict_ids)), np.nan)
+    logits_t = np.full((B, nv), np.nan)
 
     def ask_target(b):
         t = verify(target["cfg"], target["model"], target["kv"], block_size, suffix_ids, cu_suffix, prefix_lens,
@@ -310,14 +318,13 @@ def cascade_verify(draft, target, block_size: int, suffix_ids, cu_suffix, prefix
         conf_t[b], verdict_t[b], logits_t[b] = t["conf"][0], t["verdict"][0], t["logits"][0]
         return int(t["verdict"][0])
 
-    R = len(req_start) - 1
-    m = np.zeros(R, dtype=np.int64)
+    m = np.full(R, NOT_REACHED, dtype=np.int64)
     decision = np.full(B, NOT_REACHED, dtype=np.int64)
     escalated = np.zeros(B, dtype=np.uint8)
-    for r in range(R):
+    for r in which:
         lo, hi = int(req_start[r]), int(req_start[r + 1])
-        m[r], dec, esc = cascade_request(d["verdict"][lo:hi], d["conf"][lo:hi], lambda j, lo=lo: ask_target(lo + j), gamma)
+        m[r], dec, esc = cascade_request(verdict_d[lo:hi], conf_d[lo:hi], lambda j, lo=lo: ask_target(lo + j), gamma)
         decision[lo:hi] = dec
         escalated[lo:hi] = esc
-    return dict(accepted_steps=m, decision=decision, escalated=escalated, conf_draft=d["conf"], verdict_draft=d["verdict"],
-                logits_draft=d["logits"], conf_target=conf_t, verdict_target=verdict_t, logits_target=logits_t)
+    return dict(accepted_steps=m, decision=decision, escalated=escalated, conf_draft=conf_d, verdict_draft=verdict_d,
+                logits_draft=logits_d, conf_target=conf_t, verdict_target=verdict_t, logits_target=logits_t)

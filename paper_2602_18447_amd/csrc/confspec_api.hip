@@ -122,13 +122,14 @@ WsLayout ws_layout(const confspec_model_cfg &c, int64_t T, int64_t B) {
         w.plan2_counts = take(256);
         w.plan2_tiles = take((size_t)w.max_tiles2 * sizeof(cs::AttnTile));
         w.plan2_items = take((size_t)w.max_items2 * sizeof(cs::AttnItem));
-        // partial products of the split-K GEMMs those B rows go through (both activation forms)
-        int Bi = (int)B;
+        // partial products of the split-K GEMMs that short row counts take (the B rows of the last layer, a whole
+        // pass over few tokens), in both activation widths
         size_t sk = 0;
         for (int t = 1; t <= 2; ++t) {
-            sk = std::max(sk, cs::gemm_splitk_bytes(Bi, c.d_model, (int)qw * t));
-            sk = std::max(sk, cs::gemm_splitk_bytes(Bi, 2 * c.d_ffn, c.d_model * t));
-            sk = std::max(sk, cs::gemm_splitk_bytes(Bi, c.d_model, c.d_ffn * t));
+            sk = std::max(sk, cs::gemm_splitk_max_bytes((int)T, (int)(qw + 2 * kw), c.d_model * t));
+            sk = std::max(sk, cs::gemm_splitk_max_bytes((int)T, c.d_model, (int)qw * t));
+            sk = std::max(sk, cs::gemm_splitk_max_bytes((int)T, 2 * c.d_ffn, c.d_model * t));
+            sk = std::max(sk, cs::gemm_splitk_max_bytes((int)T, c.d_model, c.d_ffn * t));
         }
         w.splitk_bytes = sk;
         w.splitk = take(std::max<size_t>(sk, 256));
@@ -485,15 +486,17 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
         const int wide = tm == 2 ? 2 : 1;      // buffer width multiplier of the activation format
         bool prec = c.dtype == CONFSPEC_DTYPE_BF16 && l < g_attn_precise_layers;
         bool last = prune && l == c.n_layers - 1;
+        float *sk = c.dtype == CONFSPEC_DTYPE_BF16 ? (float *)(ws + L.splitk) : nullptr;   // for outputs of few tiles
+        size_t skb = sk ? L.splitk_bytes : 0;
         HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, tm, s));
         if (rope_fused) {
             cs::RopeArgs ra = {(const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin), ws + L.q, ws + L.ksuf,
                                ws + L.vsuf, prec ? ws + L.q_lo : nullptr, prec ? ws + L.ksuf_lo : nullptr,
                                prec ? ws + L.vsuf_lo : nullptr, c.n_q_heads, c.n_kv_heads};
             HIP_TRY(cs::launch_gemm_bf16_rope((const cs::bf16 *)h, (const cs::bf16 *)(tm == 3 ? wqkv : w->wqkv_perm[l]), T,
-                                              qw + 2 * kw, d, tm, ra, s));
+                                              qw + 2 * kw, d, tm, ra, sk, skb, s));
         } else {
-            if ((rc = run_gemm(ctx, h, wqkv, qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, tm, 1, s))) return rc;
+            if ((rc = run_gemm(ctx, h, wqkv, qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, tm, 1, s, sk, skb))) return rc;
             HIP_TRY(cs::launch_rope_split(c.dtype, qkv, (const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin),
                                           ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
                                           prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, T, c.n_q_heads,
@@ -512,8 +515,6 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
             HIP_TRY(cs::launch_gather_rows(ws + L.attn, ws + L.attn_last, last_row, B, T, (size_t)qw * eb * wide, s));
             attn = ws + L.attn_last;
         }
-        float *sk = last ? (float *)(ws + L.splitk) : nullptr;     // short outputs take the split-K path
-        size_t skb = last ? L.splitk_bytes : 0;
         if ((rc = run_gemm(ctx, attn, wo, xr, rows, d, qw, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
         HIP_TRY(cs::launch_rmsnorm(c.dtype, xr, w->mlp_norm[l], hr, rows, d, c.rms_eps, tm, s));
         if ((rc = run_gemm(ctx, hr, wgu, act, rows, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s, sk, skb))) return rc;
@@ -630,7 +631,8 @@ int confspec_op_qkv_rope(confspec_ctx *ctx, const confspec_batch *batch, int32_t
     cs::RopeArgs ra = {(const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin), dev_q, dev_k, dev_v,
                        dev_q_lo, dev_k_lo, dev_v_lo, c.n_q_heads, c.n_kv_heads};
     HIP_TRY(cs::launch_gemm_bf16_rope((const cs::bf16 *)dev_h, (const cs::bf16 *)dev_wqkv_perm, batch->T,
-                                      (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, c.d_model, a_terms, ra, s));
+                                      (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, c.d_model, a_terms, ra,
+                                      (float *)(ws + L.splitk), L.splitk_bytes, s));
     return CONFSPEC_OK;
 }
 

@@ -455,15 +455,25 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
 // is a workgroup that stores its partial product, and a second kernel adds the slices in a fixed order
 // and applies the epilogue.
 int gemm_splitk_factor(int M, int N, int K_total) {
-    if (M > 128 || N % 128 != 0) return 1;
-    int tiles_n = N / 128, nk = K_total / 64;
-    int want = (384 + tiles_n / 2) / tiles_n;            // about 384 workgroups
+    if (N % 128 != 0) return 1;
+    int tiles = ((M + 127) / 128) * (N / 128), nk = K_total / 64;
+    if (M > 128 && tiles >= 256) return 1;               // enough 128 x 128 tiles to fill the chip without a split
+    int want = (384 + tiles / 2) / tiles;                // about 384 workgroups
     int s = std::min(want, nk / 4);                      // at least 4 k-tiles per slice
     return std::max(1, std::min(s, 64));
 }
 size_t gemm_splitk_bytes(int M, int N, int K_total) {
     int s = gemm_splitk_factor(M, N, K_total);
     return s > 1 ? (size_t)s * M * N * 4 : 0;
+}
+// Largest gemm_splitk_bytes over all row counts up to max_M (the factor changes with the number of 128-row tiles).
+size_t gemm_splitk_max_bytes(int max_M, int N, int K_total) {
+    size_t best = 0;
+    for (int tm = 1; tm <= (max_M + 127) / 128; ++tm) {
+        best = std::max(best, gemm_splitk_bytes(std::min(tm * 128, max_M), N, K_total));
+        if (tm * (N / 128) >= 256) break;
+    }
+    return best;
 }
 
 template <int EPI>
@@ -514,6 +524,59 @@ __global__ void splitk_reduce_kernel(const float *__restrict__ part, int splits,
     }
 }
 
+// Sum of the split-K slices of a QKV projection made with the reordered weight rows (see RopeArgs), rotation
+// of q and k, and the q / k / v split.  Inside a head the reordered columns are [0..31 | 64..95 | 32..63 | 96..127]
+// of the original order, so a column and its rotation partner lie 32 apart.  One thread per 4 columns + 4 partners.
+__global__ void splitk_reduce_rope_kernel(const float *__restrict__ part, int splits, int M, int N, RopeArgs rope) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x, m = blockIdx.y;
+    int per_row = (N / 128) * 16;
+    if (idx >= per_row) return;
+    int head = idx >> 4, g = (idx >> 3) & 1, j = idx & 7;
+    int pc = head * 128 + g * 64 + j * 4, c0 = g * 32 + j * 4;
+    size_t plane = (size_t)M * N;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
+#pragma unroll 4
+    for (int sp = 0; sp < splits; ++sp) {
+        const float *p = part + sp * plane + (size_t)m * N + pc;
+        a += *reinterpret_cast<const f32x4 *>(p);
+        b += *reinterpret_cast<const f32x4 *>(p + 32);
+    }
+    const bool is_q = head < rope.Hq, is_v = head >= rope.Hq + rope.Hkv;
+    const int hh = is_q ? head : is_v ? head - rope.Hq - rope.Hkv : head - rope.Hq;
+    const int heads = is_q ? rope.Hq : rope.Hkv;
+    bf16 *dst_hi = reinterpret_cast<bf16 *>(is_q ? rope.q : is_v ? rope.v : rope.k);
+    bf16 *dst_lo = reinterpret_cast<bf16 *>(is_q ? rope.q_lo : is_v ? rope.v_lo : rope.k_lo);
+    if (!is_v) {
+        f32x4 c = *reinterpret_cast<const f32x4 *>(rope.cos_t + (size_t)m * 64 + c0);
+        f32x4 sn = *reinterpret_cast<const f32x4 *>(rope.sin_t + (size_t)m * 64 + c0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float lo_ = a[q], hi_ = b[q];
+            a[q] = lo_ * c[q] - hi_ * sn[q];
+            b[q] = hi_ * c[q] + lo_ * sn[q];
+        }
+    }
+    size_t o = ((size_t)m * heads + hh) * 128 + c0;
+    unsigned ha[4], hb[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        ha[q] = __bfloat16_as_ushort(__float2bfloat16(a[q]));
+        hb[q] = __bfloat16_as_ushort(__float2bfloat16(b[q]));
+    }
+    *reinterpret_cast<uint2 *>(dst_hi + o) = uint2{ha[0] | (ha[1] << 16), ha[2] | (ha[3] << 16)};
+    *reinterpret_cast<uint2 *>(dst_hi + o + 64) = uint2{hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16)};
+    if (dst_lo) {
+        unsigned la[4], lb[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            la[q] = __bfloat16_as_ushort(__float2bfloat16(a[q] - __bfloat162float(__ushort_as_bfloat16((unsigned short)ha[q]))));
+            lb[q] = __bfloat16_as_ushort(__float2bfloat16(b[q] - __bfloat162float(__ushort_as_bfloat16((unsigned short)hb[q]))));
+        }
+        *reinterpret_cast<uint2 *>(dst_lo + o) = uint2{la[0] | (la[1] << 16), la[2] | (la[3] << 16)};
+        *reinterpret_cast<uint2 *>(dst_lo + o + 64) = uint2{lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16)};
+    }
+}
+
 template <int A_FMT>
 static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, int M, int N, int K, int splits,
                                      hipStream_t s) {
@@ -526,9 +589,9 @@ static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    int tiles_n = N / 128;
-    dim3 grid(((tiles_n + 7) / 8) * 8, splits);
-    kern<<<grid, 256, smem, s>>>(A, W, part, M, N, K, 1, tiles_n, 0, 1, 1, RopeArgs{});
+    int tiles_m = (M + 127) / 128, tiles_n = N / 128;
+    dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8, splits);
+    kern<<<grid, 256, smem, s>>>(A, W, part, M, N, K, tiles_m, tiles_n, 0, tiles_m, 1, RopeArgs{});
     return hipGetLastError();
 }
 
@@ -556,7 +619,18 @@ hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int 
 // QKV projection with the rotation in the epilogue (see RopeArgs): the default tile choice, both shapes
 // have 64-column wave tiles.
 hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms, const RopeArgs &rope,
-                                 hipStream_t s) {
+                                 float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s) {
+    int k_total = K * (a_terms == 2 ? 2 : 1);
+    int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, k_total) : 1;
+    if (splits > 1 && splitk_ws && gemm_splitk_bytes(M, N, k_total) <= splitk_ws_bytes) {
+        hipError_t e = a_terms == 2   ? launch_splitk_main<2>(A, W_perm, splitk_ws, M, N, K, splits, s)
+                       : a_terms == 3 ? launch_splitk_main<3>(A, W_perm, splitk_ws, M, N, K, splits, s)
+                                      : launch_splitk_main<1>(A, W_perm, splitk_ws, M, N, K, splits, s);
+        if (e != hipSuccess) return e;
+        dim3 grid(((N / 128) * 16 + 255) / 256, M);
+        splitk_reduce_rope_kernel<<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, rope);
+        return hipGetLastError();
+    }
     int tm = (M + 255) / 256, tn = N / 256;
     if (N % 256 == 0 && (long)tm * tn >= 192)
         return launch_tile<256, 256, 2, 4, 64, 2, EPI_ROPE>(A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);

@@ -104,14 +104,16 @@ hipError_t launch_gemm_f32(const float *A, const float *W, void *out, int M, int
 // Activation formats (a_terms / out_terms): 1 = bf16; 2 = two bf16 terms, A is [M, 2K] = hi | lo and a
 // SwiGLU result is written as [M, 2 * N/2] = hi | lo; 3 = fp16 (A and W hold IEEE half values, a SwiGLU
 // result is written as fp16).
-// splitk_ws (may be null): scratch for the split-K path that short outputs (M <= 128) take; it needs
-// gemm_splitk_bytes(M, N, K * a_terms) bytes, otherwise the call falls back to one workgroup per tile.
+// splitk_ws (may be null): scratch for the split-K path that outputs with too few 128 x 128 tiles to fill the
+// chip take (gemm_splitk_factor > 1); it needs gemm_splitk_bytes(M, N, K * a_terms) bytes, otherwise the call
+// falls back to one workgroup per tile.
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
                             int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
 hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms, const RopeArgs &rope,
-                                 hipStream_t s);
+                                 float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
 int gemm_splitk_factor(int M, int N, int K_total);
 size_t gemm_splitk_bytes(int M, int N, int K_total);
+size_t gemm_splitk_max_bytes(int max_M, int N, int K_total);   // largest gemm_splitk_bytes over M <= max_M
 
 // ---- attention ----
 struct AttnArgs {

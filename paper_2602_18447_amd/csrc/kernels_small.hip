@@ -131,11 +131,70 @@ __global__ void rmsnorm_kernel(const float *__restrict__ x, const T *__restrict_
     }
 }
 
+// 16-bit outputs, rows of at most NV * 256 elements: the row stays in registers between the two sweeps (every
+// load of a lane is in flight at once), gains are read 4 at a time and the outputs leave as 8-byte stores.
+// Same arithmetic, in the same order, as the generic kernel above.
+template <int NV>
+__global__ __launch_bounds__(256) void rmsnorm_bf16_rows_kernel(const float *__restrict__ x, const bf16 *__restrict__ g,
+                                                                bf16 *__restrict__ out, int n_rows, int d, float eps, int terms) {
+    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int row = blockIdx.x * 4 + wave;
+    if (row >= n_rows) return;
+    const float4 *xr = (const float4 *)(x + (size_t)row * d);
+    const int nv = d >> 2;
+    float4 v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        int j = lane + 64 * i;
+        v[i] = j < nv ? xr[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+    ss = wave_sum(ss);
+    float r = 1.0f / sqrtf(ss / (float)d + eps);
+    bf16 *o = out + (size_t)row * d * (terms == 2 ? 2 : 1);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        int j = lane + 64 * i;
+        if (j >= nv) continue;
+        int c = j << 2;
+        uint2 gp = *reinterpret_cast<const uint2 *>(g + c);
+        float gv[4] = {__uint_as_float(gp.x << 16), __uint_as_float(gp.x & 0xffff0000u), __uint_as_float(gp.y << 16),
+                       __uint_as_float(gp.y & 0xffff0000u)};
+        float y[4] = {v[i].x * r * gv[0], v[i].y * r * gv[1], v[i].z * r * gv[2], v[i].w * r * gv[3]};
+        unsigned hi[4], lo[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (terms == 3) {
+                hi[q] = __half_as_ushort(__float2half_rn(y[q]));
+                lo[q] = 0;
+            } else {
+                bf16 h = __float2bfloat16(y[q]);
+                hi[q] = __bfloat16_as_ushort(h);
+                lo[q] = __bfloat16_as_ushort(__float2bfloat16(y[q] - __bfloat162float(h)));
+            }
+        }
+        *reinterpret_cast<uint2 *>(o + c) = uint2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+        if (terms == 2) *reinterpret_cast<uint2 *>(o + d + c) = uint2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+    }
+}
+
 hipError_t launch_rmsnorm(int dtype, const float *x, const void *g, void *out, int T, int d, float eps,
                           int terms, hipStream_t s) {
     int blocks = (T + 3) / 4;
-    if (dtype == 0) rmsnorm_kernel<float><<<blocks, 256, 0, s>>>(x, (const float *)g, (float *)out, T, d, eps, 1);
-    else rmsnorm_kernel<bf16><<<blocks, 256, 0, s>>>(x, (const bf16 *)g, (bf16 *)out, T, d, eps, terms);
+    const bool vec = d % 4 == 0 && (((uintptr_t)g | (uintptr_t)out) & 7) == 0;   // 8-byte gain loads and output stores
+    if (dtype == 0) {
+        rmsnorm_kernel<float><<<blocks, 256, 0, s>>>(x, (const float *)g, (float *)out, T, d, eps, 1);
+    } else if (!vec) {
+        rmsnorm_kernel<bf16><<<blocks, 256, 0, s>>>(x, (const bf16 *)g, (bf16 *)out, T, d, eps, terms);
+    } else if (d <= 8 * 256) {
+        rmsnorm_bf16_rows_kernel<8><<<blocks, 256, 0, s>>>(x, (const bf16 *)g, (bf16 *)out, T, d, eps, terms);
+    } else if (d <= 24 * 256) {
+        rmsnorm_bf16_rows_kernel<24><<<blocks, 256, 0, s>>>(x, (const bf16 *)g, (bf16 *)out, T, d, eps, terms);
+    } else {
+        rmsnorm_kernel<bf16><<<blocks, 256, 0, s>>>(x, (const bf16 *)g, (bf16 *)out, T, d, eps, terms);
+    }
     return hipGetLastError();
 }
 

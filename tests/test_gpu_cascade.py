@@ -148,3 +148,79 @@ def test_cascade_matches_oracle_on_ragged_requests(dtype):
     torch.cuda.synchronize()
     _check(wl_d, res, n_target, ora, gammas[2], single, tol)
     assert n_target == int(res["escalated"].sum())         # with one step per request every selected trace is consulted
+
+
+def _loop_closed_form(keep, verdict_d, verdict_t, req_start):
+    """Outcome of every request from per-trace decisions: V = the small model's where kept, else the large one's;
+    m = leading accepts."""
+    v = np.where(keep, verdict_d, verdict_t)
+    m = []
+    for lo, hi in zip(req_start[:-1], req_start[1:]):
+        m.append(int(np.cumprod(v[lo:hi] == 0).sum()))
+    return v, np.asarray(m)
+
+
+def test_cascade_full_size_draft_and_target_shapes():
+    """The 1.5B-shaped small model and the 32B-shaped large model on config 2's batch, in the launch configuration
+    the benchmark times.  Sampled requests against the oracle; every request against the two models' separate
+    full-batch passes (each of which has its own sampled oracle parity test) and the properties of the loop."""
+    print("cascade, full-size shapes", flush=True)
+    wl_d = W.config(2)
+    wl_t = W.Workload("cascade_target_b32_L2048_S96", W.TARGET_SHAPE, 1012, wl_d.prefix_lens, wl_d.suffix_lens)
+    batch, sd, st = _sides(wl_d, wl_t)
+    vids = W.draw_verdict_ids(wl_d)
+    req_start = [0, 1, 3, 6, 10, 15, 20, 24, 27, 29, 31, 32]
+    tol = G.TOL["bf16"]
+    casc = Cascade(sd["ver"], st["ver"])
+    ids, cu, pl = batch.suffix_ids.cpu().numpy(), batch.h_cu_suffix, batch.h_prefix_lens
+    full = {}
+    for k, side in (("d", sd), ("t", st)):
+        lg, cf, vd, _ = side["ver"].verify(side["kv"], batch, vids, [0.9])
+        torch.cuda.synchronize()
+        full[k] = dict(logits=lg.cpu().numpy().astype(np.float64), conf=cf.cpu().numpy(), verdict=vd.cpu().numpy())
+    gap_t = np.abs(full["t"]["logits"][:, 0] - full["t"]["logits"][:, 1])
+    for gamma in (0.9, 0.6):
+        res, n_target = casc.run(sd["kv"], st["kv"], batch, req_start, vids, gamma)
+        torch.cuda.synchronize()
+        g = {k: v.cpu().numpy() for k, v in res.items()}
+        # the small model's pass is the same launch sequence as the separate call: identical bits
+        assert np.array_equal(g["conf_draft"], full["d"]["conf"]) and np.array_equal(g["verdict_draft"], full["d"]["verdict"])
+        keep = full["d"]["conf"] >= np.float32(gamma)
+        ran = g["target_ran"].astype(bool)
+        assert n_target == int(ran.sum()) and not (ran & keep).any()
+        assert np.array_equal(ran, _target_ran_rule(full["d"]["conf"], full["d"]["verdict"], np.float32(gamma), req_start))
+        # the large model on the compacted sub-batch against its pass over the whole batch
+        assert np.abs(g["conf_target"][ran] - full["t"]["conf"][ran]).max(initial=0.0) <= 6e-3
+        decided = gap_t > 2 * tol["logit"]
+        assert np.array_equal(g["verdict_target"][ran & decided], full["t"]["verdict"][ran & decided])
+        v, m = _loop_closed_form(keep, full["d"]["verdict"], g["verdict_target"], req_start)
+        assert np.array_equal(g["accepted_steps"], m)
+        for r, (lo, hi) in enumerate(zip(req_start[:-1], req_start[1:])):
+            reach = min(m[r] + 1, hi - lo)
+            assert np.array_equal(g["decision"][lo:lo + reach], v[lo:lo + reach])
+            assert np.all(g["decision"][lo + reach:hi] == O.NOT_REACHED)
+            assert np.array_equal(g["escalated"][lo:lo + reach].astype(bool), ~keep[lo:lo + reach])
+            assert not g["escalated"][lo + reach:hi].any()
+        print(f"gamma={gamma}: in the large model's pass {n_target}/{wl_d.B}, escalated {int(g['escalated'].sum())}, "
+              f"accepted {g['accepted_steps'].tolist()}", flush=True)
+        if gamma == 0.9:
+            sample = [0, 10]                                   # two single-step requests
+            ora = O.cascade_verify(sd["ora"], st["ora"], wl_d.block_size, ids, cu, pl, vids, gamma, req_start,
+                                   request_subset=sample)
+            for r in sample:
+                lo, hi = req_start[r], req_start[r + 1]
+                assert np.abs(g["conf_draft"][lo:hi] - ora["conf_draft"][lo:hi]).max() <= tol["conf"]
+                asked = ~np.isnan(ora["conf_target"][lo:hi])
+                assert np.abs(g["conf_target"][lo:hi][asked] - ora["conf_target"][lo:hi][asked]).max(initial=0.0) <= tol["conf"]
+                gap = np.abs(np.diff(np.sort(ora["logits_draft"][lo:hi], axis=1)[:, -2:], axis=1))[:, 0]
+                clear = (np.abs(ora["conf_draft"][lo:hi] - gamma) > tol["band"]) & (gap > 2 * tol["logit"])
+                lt = np.sort(np.nan_to_num(ora["logits_target"][lo:hi]), axis=1)
+                clear &= ~asked | ((lt[:, -1] - lt[:, -2]) > 2 * tol["logit"])
+                print(f"request {r}: oracle m={ora['accepted_steps'][r]} gpu m={g['accepted_steps'][r]} clear={clear.all()}",
+                      flush=True)
+                if clear.all():
+                    assert g["accepted_steps"][r] == ora["accepted_steps"][r]
+                    assert np.array_equal(g["decision"][lo:hi], ora["decision"][lo:hi])
+                    assert np.array_equal(g["escalated"][lo:hi], ora["escalated"][lo:hi])
+    sd["ver"].close()
+    st["ver"].close()

@@ -154,7 +154,7 @@ def test_gemm_fp32_all_epilogues():
     cb.confspec_destroy(ctx)
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 1536), ("fp32", 256), ("bf16", 5120)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 1536), ("fp32", 256), ("bf16", 5120), ("bf16", 6400)])
 def test_rmsnorm(dtype, d):
     print(f"rmsnorm {dtype} d={d}", flush=True)
     ctx, base = _ctx(dtype, d_model=d, head_dim=128 if dtype == "bf16" else 64, n_kv_heads=2 if dtype == "bf16" else 4)
@@ -216,9 +216,10 @@ def _perm_head_rows(n_heads):
 
 @pytest.mark.parametrize("a_terms,with_lo", [(1, False), (3, False), (2, True)])
 @pytest.mark.parametrize("suffix_lens", [(5, 3, 9), (200, 77, 130)])
-def test_qkv_projection_with_rotary_epilogue(a_terms, with_lo, suffix_lens):
-    print(f"qkv + rope fused a_terms={a_terms} lo={with_lo} S={suffix_lens}", flush=True)
-    hd, d = 128, 256
+@pytest.mark.parametrize("d", [256, 1024])      # 1024: enough k-tiles for the split-K path at these row counts
+def test_qkv_projection_with_rotary_epilogue(a_terms, with_lo, suffix_lens, d):
+    print(f"qkv + rope fused a_terms={a_terms} lo={with_lo} S={suffix_lens} d={d}", flush=True)
+    hd = 128
     wl = W.tiny_workload("qkvrope", 4, dtype="bf16", n_q_heads=4, n_kv_heads=2, head_dim=hd, d_model=d,
                          prefix_lens=(16383, 0, 700), suffix_lens=suffix_lens, block_size=16)
     m = wl.model
@@ -455,10 +456,10 @@ def test_gemm_bf16_wide_output_split_into_two_launches(epi):
     cb.confspec_destroy(ctx)
 
 
-@pytest.mark.parametrize("M", [1, 32, 128])
+@pytest.mark.parametrize("M", [1, 32, 128, 300, 1000])
 @pytest.mark.parametrize("epi,a_terms", [("store", 1), ("resid", 1), ("swiglu", 1), ("resid", 2), ("swiglu", 2)])
 def test_gemm_bf16_split_k_for_short_outputs(M, epi, a_terms):
-    """M <= 128 with scratch: k slices as separate workgroups, added in a fixed order."""
+    """Outputs of few tiles, with scratch: k slices as separate workgroups, added in a fixed order."""
     print(f"gemm bf16 split-K M={M} {epi} a_terms={a_terms}", flush=True)
     ctx, _ = _ctx("bf16")
     N, K = 512, 2240                                  # 35 k-tiles: slices of unequal length

@@ -77,3 +77,12 @@ def test_cascade_verify_consults_the_large_model_lazily():
         assert np.array_equal(asked, r["escalated"].astype(bool))          # no pass of the large model that was not needed
         assert np.allclose(r["conf_target"][asked], full_t["conf"][asked], atol=1e-12)
     assert res[0.0]["escalated"].sum() == 0 and res[2.0]["escalated"].sum() >= 3
+    # requests are independent: evaluating a subset of them gives the same entries as the full run
+    sub = O.cascade_verify(sides[0], sides[1], wl_d.block_size, ids, cu, pl, vids, 0.55, req_start, request_subset=[2, 0])
+    full = res[0.55]
+    for q in (0, 2):
+        lo, hi = req_start[q], req_start[q + 1]
+        assert sub["accepted_steps"][q] == full["accepted_steps"][q]
+        for k in ("decision", "escalated", "conf_draft", "verdict_draft", "conf_target", "verdict_target"):
+            assert np.array_equal(sub[k][lo:hi], full[k][lo:hi], equal_nan=True), k
+    assert sub["accepted_steps"][1] == O.NOT_REACHED and np.isnan(sub["conf_draft"][2])
