@@ -256,6 +256,43 @@ def prefix_pass(cfg, model, prefix_ids: Sequence[np.ndarray]):
     return k_dense, v_dense
 
 
+def append_rows(cfg, model, kv, block_size: int, suffix_ids, cu_suffix, prefix_lens, n_append: Sequence[int],
+                trace_subset: Optional[Sequence[int]] = None) -> dict:
+    """Keys and values that join the context when the first n_append[b] suffix tokens of trace b are
+    accepted (Algorithm 1, Stage 3: context <- context + accepted draft steps).
+
+    They are the keys (rotated to positions L_b .. L_b + n_append[b] - 1) and values the pass itself
+    computes for those tokens in every layer, on top of the cached context; logical row L_b + t of
+    trace b receives the pair of suffix token t.
+    Returns dict(traces, k, v) with k[l][i], v[l][i]: [n_append[b_i], Hkv, hd] for the i-th listed trace.
+    """
+    suffix_ids = np.asarray(suffix_ids)
+    cu = np.asarray(cu_suffix, dtype=np.int64)
+    Ls = np.asarray(prefix_lens, dtype=np.int64)
+    which = list(range(len(Ls))) if trace_subset is None else list(trace_subset)
+    traces = []
+    for b in which:
+        L = int(Ls[b])
+        n = int(n_append[b])
+        if n < 0 or n > cu[b + 1] - cu[b]:
+            raise ValueError(f"n_append[{b}] = {n} outside [0, S_b]")
+        blk_ids = np.asarray(kv.block_table[b][:(L + block_size - 1) // block_size], dtype=np.int64)
+        empty = np.zeros((0, cfg.n_kv_heads, cfg.head_dim))
+
+        def k_prefix(l, blk_ids=blk_ids, L=L):
+            return gather_prefix(kv.k_blocks(l, blk_ids), L) if L else empty
+
+        def v_prefix(l, blk_ids=blk_ids, L=L):
+            return gather_prefix(kv.v_blocks(l, blk_ids), L) if L else empty
+
+        # only the accepted tokens are run: causal attention makes them independent of what follows
+        traces.append(dict(ids=suffix_ids[cu[b]:cu[b] + n], L=L, k_prefix=k_prefix, v_prefix=v_prefix))
+    _, kvs = forward(cfg, model, traces, keep_kv=True)
+    return dict(traces=np.asarray(which, dtype=np.int32),
+                k=[[kvs[i][l][0] for i in range(len(which))] for l in range(cfg.n_layers)],
+                v=[[kvs[i][l][1] for i in range(len(which))] for l in range(cfg.n_layers)])
+
+
 # --------------------------------------------------------------------------- #
 # Two-tier cascade over the k drafted steps of one request (Algorithm 1, Stage 2;
 # Section 4.2, "Cascaded Decision Rule", Eq. 4)
