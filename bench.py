@@ -115,6 +115,9 @@ def main():
     ap.add_argument("--cascade", action="store_true",
                     help="also time the two-tier cascade call (this workload's batch, the 32B-shaped model as the large "
                          "one, gamma 0.9 and 0.6) and report it under \"cascade\"")
+    ap.add_argument("--append", type=int, default=0, metavar="N",
+                    help="also time the pass with write-back of the first N suffix tokens of every trace into the "
+                         "cache and report it under \"append\"")
     ap.add_argument("--cpu-baseline-traces", type=int, default=6,
                     help="traces of the workload the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -252,6 +255,25 @@ def main():
                          GBps=round(2 * nbytes / (copy_ms * 1e-3) / 1e9, 1))
         del src, dst
 
+    append_info = None
+    if args.append > 0:
+        n_app = np.minimum(np.asarray(wl.suffix_lens), args.append).astype(np.int32)
+        batch_a = W.make_batch(wl, dev, extra_rows=n_app)           # same ids and blocks, a block table with room
+        kv_a = W.make_seeded_kv(wl, batch_a, dev)
+        for _ in range(3):
+            ver.verify_append(kv_a, batch_a, n_app, vids, taus, outputs=outs)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            ver.verify_append(kv_a, batch_a, n_app, vids, taus, outputs=outs)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_a = e0.elapsed_time(e1) / args.steps
+        rows = int(n_app.sum())
+        append_info = dict(ms_per_step=round(ms_a, 4), launch="eager", tokens_appended=rows,
+                           bytes_written=rows * m.n_layers * 2 * m.n_kv_heads * m.head_dim * (2 if m.dtype == "bf16" else 4),
+                           extra_ms_vs_eager_pass=round(ms_a - eager_ms, 4))
+
     cascade_info = None
     if args.cascade:
         cascade_info = _time_cascade(W, wl, ver, kv, batch, vids, dev, max(args.steps // 2, 3))
@@ -282,7 +304,7 @@ def main():
                    "launch": "hip_graph_replay" if graph_ok else "eager", "eager_ms_per_step": round(eager_ms, 4),
                    **({"tune": args.tune} if args.tune else {})},
         "roofline": roofline, "cpu_baseline": cpu, **({"copy_calibration": copy_info} if copy_info else {}),
-        **({"cascade": cascade_info} if cascade_info else {}),
+        **({"cascade": cascade_info} if cascade_info else {}), **({"append": append_info} if append_info else {}),
     }))
 
 

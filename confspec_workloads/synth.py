@@ -195,8 +195,10 @@ class Batch:
     h_prefix_lens: np.ndarray
 
 
-def make_batch(wl: Workload, device="cpu", spare_blocks: int = 3) -> Batch:
-    """Uniform random suffix ids; physical blocks handed out by a seeded permutation."""
+def make_batch(wl: Workload, device="cpu", spare_blocks: int = 3, extra_rows=0) -> Batch:
+    """Uniform random suffix ids; physical blocks handed out by a seeded permutation.
+    extra_rows (int or one per trace): rows past the prefix that the block table also covers, for callers
+    that append to the cache."""
     V = wl.model.vocab
     rng = _np_rng(wl.seed, "batch")
     S = np.asarray(wl.suffix_lens, dtype=np.int64)
@@ -205,7 +207,7 @@ def make_batch(wl: Workload, device="cpu", spare_blocks: int = 3) -> Batch:
     cu[1:] = np.cumsum(S)
     ids = rng.integers(0, V, size=int(cu[-1]), dtype=np.int64).astype(np.int32)
     bs = wl.block_size
-    need = (L + bs - 1) // bs
+    need = (L + np.broadcast_to(np.asarray(extra_rows, dtype=np.int64), L.shape) + bs - 1) // bs
     n_blocks = int(need.sum()) + spare_blocks
     max_blocks = max(1, int(need.max()) if len(need) else 1)
     perm = rng.permutation(n_blocks).astype(np.int32)

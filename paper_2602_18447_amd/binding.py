@@ -104,6 +104,9 @@ def _load() -> C.CDLL:
                                              vp, vp, vp, vp, vp]
     lib.confspec_op_copy.restype = C.c_int
     lib.confspec_op_copy.argtypes = [vp, vp, sz, vp]
+    lib.confspec_verify_append.restype = C.c_int
+    lib.confspec_verify_append.argtypes = [vp, P(Weights), P(KV), P(Batch), vp, P(i32), P(i32), i32, P(C.c_float), i32,
+                                           vp, sz, vp, vp, vp, vp, vp]
     lib.confspec_cascade_scratch_bytes.restype = sz
     lib.confspec_cascade_scratch_bytes.argtypes = [i32, i32, i32]
     lib.confspec_cascade.restype = C.c_int
@@ -120,7 +123,7 @@ EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec
             "confspec_workspace_bytes", "confspec_packed_bytes", "confspec_pack_weights", "confspec_verify",
             "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_qkv_rope", "confspec_op_attention",
             "confspec_op_verdict_gate", "confspec_op_copy", "confspec_tune", "confspec_cascade_scratch_bytes",
-            "confspec_cascade"]
+            "confspec_cascade", "confspec_verify_append"]
 
 
 class ConfSpecError(RuntimeError):
@@ -198,6 +201,20 @@ def confspec_verify(ctx, w: Weights, kv: KV, batch: Batch, verdict_ids: Sequence
     _check(ctx, lib.confspec_verify(ctx, C.byref(w), C.byref(kv), C.byref(batch), ids, nv, tau, nt,
                                     _ptr(workspace), ws_bytes, _ptr(logits), _ptr(conf), _ptr(verdict),
                                     _ptr(accept), _stream_handle(stream)))
+
+
+def confspec_verify_append(ctx, w: Weights, kv: KV, batch: Batch, n_append, h_n_append, verdict_ids: Sequence[int],
+                           taus: Sequence[float], workspace, logits, conf, verdict, accept, stream=None) -> None:
+    """n_append: device int32 tensor [B]; h_n_append: the same counts as a host int32 numpy array."""
+    import numpy as np
+    nv, nt = len(verdict_ids), len(taus)
+    ids = (C.c_int32 * max(nv, 1))(*[int(v) for v in verdict_ids])
+    tau = (C.c_float * max(nt, 1))(*[float(t) for t in taus])
+    hn = None if h_n_append is None else np.ascontiguousarray(h_n_append, dtype=np.int32)
+    hp = None if hn is None else hn.ctypes.data_as(C.POINTER(C.c_int32))
+    _check(ctx, lib.confspec_verify_append(ctx, C.byref(w), C.byref(kv), C.byref(batch), _ptr(n_append), hp, ids, nv,
+                                           tau, nt, _ptr(workspace), _nbytes(workspace), _ptr(logits), _ptr(conf),
+                                           _ptr(verdict), _ptr(accept), _stream_handle(stream)))
 
 
 def confspec_op_gemm(ctx, A, W, out, M: int, N: int, K: int, epilogue: int, a_terms: int = 1, out_terms: int = 1,

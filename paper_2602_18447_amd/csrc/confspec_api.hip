@@ -13,6 +13,7 @@
 #include "../../include/confspec.h"
 #include "../../include/confspec_ops.h"
 #include "../../include/confspec_cascade.h"
+#include "../../include/confspec_append.h"
 #include "kernels.h"
 
 namespace cs {
@@ -419,11 +420,13 @@ int confspec_pack_weights(confspec_ctx *ctx, const confspec_weights *in, void *d
     return CONFSPEC_OK;
 }
 
-int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
-                    const confspec_batch *batch, const int32_t *h_verdict_ids, int32_t n_verdict,
-                    const float *h_tau, int32_t n_tau, void *dev_workspace, size_t workspace_bytes,
-                    float *dev_verdict_logits, float *dev_conf, int32_t *dev_verdict, uint8_t *dev_accept,
-                    confspec_stream stream) {
+// The pass; with dev_n_append it also writes the keys and values of the first n_append[b] suffix tokens of every
+// trace back into the cache (h_n_append: the same counts on the host, for validation).
+static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
+                       const confspec_batch *batch, const int32_t *h_verdict_ids, int32_t n_verdict,
+                       const float *h_tau, int32_t n_tau, void *dev_workspace, size_t workspace_bytes,
+                       float *dev_verdict_logits, float *dev_conf, int32_t *dev_verdict, uint8_t *dev_accept,
+                       const int32_t *dev_n_append, const int32_t *h_n_append, confspec_stream stream) {
     if (!ctx) return CONFSPEC_E_INVALID_ARG;
     const confspec_model_cfg &c = ctx->cfg;
     if (!w) return fail(ctx, CONFSPEC_E_INVALID_ARG, "weights is null");
@@ -446,6 +449,17 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
     if ((rc = check_verdict(ctx, h_verdict_ids, n_verdict, h_tau, n_tau, &va)) != CONFSPEC_OK) return rc;
     WsLayout L = ws_layout(c, batch->T, batch->B);
     if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
+    if (dev_n_append) {
+        if (!h_n_append) return fail(ctx, CONFSPEC_E_INVALID_ARG, "h_n_append is null");
+        if (!kv->k_pages || !kv->v_pages) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv pages are null");
+        for (int b = 0; b < batch->B; ++b) {
+            int n = h_n_append[b], S = batch->h_cu_suffix[b + 1] - batch->h_cu_suffix[b];
+            if (n < 0 || n > S) return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "n_append[%d] = %d outside [0, S_b = %d]", b, n, S);
+            if ((int64_t)batch->h_prefix_lens[b] + n > max_prefix)
+                return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "trace %d: %d cached + %d appended rows exceed the block table's %lld",
+                            b, batch->h_prefix_lens[b], n, (long long)max_prefix);
+        }
+    }
 
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)dev_workspace;
@@ -505,6 +519,15 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
         cs::AttnArgs a = make_attn_args(c, kv, batch, l, ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
                                         prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, ws + L.attn, tm);
         if ((rc = run_attention(ctx, a, ws, L, last ? pc_last : pc, last, s))) return rc;
+        if (dev_n_append) {
+            // after this layer's attention has read the pages (it never reads rows at or past L_b anyway)
+            size_t layer_bytes = (size_t)kv->n_blocks * c.n_kv_heads * kv->block_size * c.head_dim * eb;
+            HIP_TRY(cs::launch_kv_append(ws + L.ksuf, ws + L.vsuf, (char *)const_cast<void *>(kv->k_pages) + layer_bytes * l,
+                                         (char *)const_cast<void *>(kv->v_pages) + layer_bytes * l, kv->block_table,
+                                         batch->cu_suffix, batch->prefix_lens, dev_n_append,
+                                         (const int32_t *)(ws + L.tok_trace), B, T, c.n_kv_heads, (size_t)c.head_dim * eb,
+                                         kv->block_size, kv->max_blocks_per_seq, kv->n_blocks, s));
+        }
         float *xr = x;             // residual stream the rest of the layer works on
         const void *attn = ws + L.attn;
         void *hr = h, *act = ws + L.act;
@@ -527,6 +550,26 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
         HIP_TRY(cs::launch_verdict(c.dtype, x, last_row, w->final_norm, w->lm_head, va, B, T, d, c.rms_eps,
                                    dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
     return CONFSPEC_OK;
+}
+
+int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
+                    const confspec_batch *batch, const int32_t *h_verdict_ids, int32_t n_verdict,
+                    const float *h_tau, int32_t n_tau, void *dev_workspace, size_t workspace_bytes,
+                    float *dev_verdict_logits, float *dev_conf, int32_t *dev_verdict, uint8_t *dev_accept,
+                    confspec_stream stream) {
+    return verify_impl(ctx, w, kv, batch, h_verdict_ids, n_verdict, h_tau, n_tau, dev_workspace, workspace_bytes,
+                       dev_verdict_logits, dev_conf, dev_verdict, dev_accept, nullptr, nullptr, stream);
+}
+
+int confspec_verify_append(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
+                           const confspec_batch *batch, const int32_t *dev_n_append, const int32_t *h_n_append,
+                           const int32_t *h_verdict_ids, int32_t n_verdict, const float *h_tau, int32_t n_tau,
+                           void *dev_workspace, size_t workspace_bytes, float *dev_verdict_logits, float *dev_conf,
+                           int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!dev_n_append || !h_n_append) return fail(ctx, CONFSPEC_E_INVALID_ARG, "n_append is null");
+    return verify_impl(ctx, w, kv, batch, h_verdict_ids, n_verdict, h_tau, n_tau, dev_workspace, workspace_bytes,
+                       dev_verdict_logits, dev_conf, dev_verdict, dev_accept, dev_n_append, h_n_append, stream);
 }
 
 // ---- single-step entry points ------------------------------------------------------------------

@@ -144,6 +144,13 @@ hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const Attn
                             int n_items_host, int max_xcd_items, int n_tiles_host, bool any_split, float *part_o,
                             float *part_ml, hipStream_t s);
 
+// Suffix keys / values [T, Hkv, hd] of the tokens i < n_append[b] of every trace into rows L_b + i of the paged cache
+// of one layer (k_pages / v_pages point at that layer).
+hipError_t launch_kv_append(const void *ksuf, const void *vsuf, void *k_pages, void *v_pages, const int32_t *table,
+                            const int32_t *cu, const int32_t *plens, const int32_t *n_append, const int32_t *tok_trace,
+                            int B, int T, int Hkv, size_t head_row_bytes, int block_size, int max_blocks, int n_blocks,
+                            hipStream_t s);
+
 // ---- cascade (cascade.hip) ----
 hipError_t launch_cascade_select(const uint8_t *keep, const int32_t *verdict_d, const int32_t *req_start, int R, int B,
                                  const int32_t *cu, const int32_t *plens, int T, uint8_t *target_ran, int32_t *pos_of,

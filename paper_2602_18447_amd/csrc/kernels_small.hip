@@ -214,6 +214,43 @@ hipError_t launch_gather_rows(const void *src, void *dst, const int32_t *rows, i
 }
 
 // ------------------------------------------------------------------------------------------------
+// Write-back of suffix keys and values into the paged cache: suffix token i of trace b (i < n_append[b]) goes to
+// logical row L_b + i of that trace, found through the block table.  One workgroup per suffix token; a row of one
+// kv head is row16 16-byte vectors.
+__global__ void kv_append_kernel(const u32x4_t *__restrict__ ksuf, const u32x4_t *__restrict__ vsuf,
+                                 u32x4_t *__restrict__ k_pages, u32x4_t *__restrict__ v_pages,
+                                 const int32_t *__restrict__ table, const int32_t *__restrict__ cu,
+                                 const int32_t *__restrict__ plens, const int32_t *__restrict__ n_append,
+                                 const int32_t *__restrict__ tok_trace, int B, int T, int Hkv, int row16, int block_size,
+                                 int max_blocks, int n_blocks) {
+    int t = blockIdx.x;
+    int b = min(max(tok_trace[t], 0), B - 1);
+    int i = t - cu[b];
+    if (i < 0 || i >= n_append[b]) return;
+    int row = plens[b] + i;
+    if (row < 0 || row >= max_blocks * block_size) return;
+    int blk = min(max(table[(size_t)b * max_blocks + row / block_size], 0), n_blocks - 1);
+    int slot = row % block_size;
+    for (int e = threadIdx.x; e < Hkv * row16; e += blockDim.x) {
+        int c = e / row16, j = e - c * row16;
+        size_t src = ((size_t)t * Hkv + c) * row16 + j;
+        size_t dst = (((size_t)blk * Hkv + c) * block_size + slot) * row16 + j;
+        k_pages[dst] = ksuf[src];
+        v_pages[dst] = vsuf[src];
+    }
+}
+
+hipError_t launch_kv_append(const void *ksuf, const void *vsuf, void *k_pages, void *v_pages, const int32_t *table,
+                            const int32_t *cu, const int32_t *plens, const int32_t *n_append, const int32_t *tok_trace,
+                            int B, int T, int Hkv, size_t head_row_bytes, int block_size, int max_blocks, int n_blocks,
+                            hipStream_t s) {
+    kv_append_kernel<<<T, 128, 0, s>>>((const u32x4_t *)ksuf, (const u32x4_t *)vsuf, (u32x4_t *)k_pages, (u32x4_t *)v_pages,
+                                       table, cu, plens, n_append, tok_trace, B, T, Hkv, (int)(head_row_bytes / 16),
+                                       block_size, max_blocks, n_blocks);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // Plain copy, 16 bytes per lane per step: reads n16 * 16 bytes and writes as many.  Its known
 // traffic is the yardstick that hardware byte counters of the other kernels are scaled by.
 __global__ void copy16_kernel(const u32x4_t *__restrict__ src, u32x4_t *__restrict__ dst, size_t n16) {

@@ -78,6 +78,18 @@ class Verifier:
         cb.confspec_verify(self.ctx, self.w, kvs, bs, verdict_ids, taus, ws, *outs, stream=stream)
         return outs
 
+    def verify_append(self, kv, batch, n_append, verdict_ids: Sequence[int], taus: Sequence[float], outputs=None,
+                      stream=None):
+        """verify() that also writes the keys / values of the first n_append[b] suffix tokens of every trace into the
+        cache pages (kv is modified).  n_append: host integers, one per trace."""
+        kvs, bs, keep = self.bind(kv, batch)
+        hn = np.ascontiguousarray(n_append, dtype=np.int32)
+        dn = torch.from_numpy(hn).to(self.device)
+        ws = self.workspace(bs.T, bs.B)
+        outs = outputs or self.alloc_outputs(bs.B, len(verdict_ids), len(taus))
+        cb.confspec_verify_append(self.ctx, self.w, kvs, bs, dn, hn, verdict_ids, taus, ws, *outs, stream=stream)
+        return outs
+
 
 class Cascade:
     """The two-tier cascade over the drafted steps of a batch of requests: a small and a large Verifier that read
