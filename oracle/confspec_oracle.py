@@ -329,13 +329,60 @@ def cascade_request(draft_verdict: Sequence[int], draft_conf: Sequence[float], t
     return m, decision, escalated
 
 
+def tree_request(parent: Sequence[int], draft_verdict: Sequence[int], draft_conf: Sequence[float], target, gamma: float,
+                 accept_index: int = 0):
+    """Tree-structured drafting for one request (Section 4.3, Eq. 5).
+
+    Node j is a candidate step; parent[j] is the node it continues (an earlier index), -1 for a candidate
+    of the first layer.  Layer by layer, cascaded verification (Eq. 4) is applied to every candidate that
+    continues the step chosen so far; among those that pass, the one with the highest confidence - the
+    small model's where its decision was kept, the large model's where it was consulted - is chosen and
+    the walk goes on with its children.  It ends at a layer where nothing passes (or at a leaf).
+    target: callable j -> (decision, confidence) of the large model, called only for candidates of a
+    reached layer whose small-model confidence is below gamma.  Ties go to the lowest index.
+    Returns (path, decision, escalated, conf_used): the chosen nodes in order; per node the cascaded
+    decision (NOT_REACHED for nodes of layers the walk never looked at), whether the large model was
+    consulted, and the confidence that entered the selection (NaN if not reached).
+    """
+    n = len(parent)
+    decision = [NOT_REACHED] * n
+    escalated = [0] * n
+    conf_used = [float("nan")] * n
+    path = []
+    cur = -1
+    while True:
+        layer = [j for j in range(n) if parent[j] == cur]
+        if not layer:
+            break
+        best = None
+        for j in layer:
+            if draft_conf[j] >= gamma:
+                v, p = int(draft_verdict[j]), float(draft_conf[j])
+            else:
+                v, p = target(j)
+                v, p = int(v), float(p)
+                escalated[j] = 1
+            decision[j], conf_used[j] = v, p
+            if v == accept_index and (best is None or p > conf_used[best]):
+                best = j
+        if best is None:
+            break
+        path.append(best)
+        cur = best
+    return path, decision, escalated, conf_used
+
+
 def cascade_verify(draft, target, block_size: int, suffix_ids, cu_suffix, prefix_lens, verdict_ids, gamma: float,
-                   req_start: Sequence[int], request_subset: Optional[Sequence[int]] = None) -> dict:
+                   req_start: Sequence[int], request_subset: Optional[Sequence[int]] = None,
+                   parent: Optional[Sequence[int]] = None) -> dict:
     """Cascade over a batch of requests.  draft / target: dicts with cfg, model, kv (each model has its
     own cache of the same contexts).  Traces req_start[r] .. req_start[r+1]-1 are the drafted steps of
     request r in order.  The large model's pass runs only for the steps the loop escalates.
     request_subset: evaluate these requests only (requests are independent); the entries of all other
-    requests and traces stay NaN / NOT_REACHED."""
+    requests and traces stay NaN / NOT_REACHED.
+    parent (tree-structured drafting, Section 4.3): parent[b] = the trace that candidate b continues (a batch
+    index inside the same request, smaller than b), -1 for first-layer candidates; then the result also has
+    selected [B] (1 on the chosen path), conf_used [B], and accepted_steps is the length of the chosen path."""
     B = len(prefix_lens)
     R = len(req_start) - 1
     which = list(range(R)) if request_subset is None else [int(r) for r in request_subset]
@@ -358,10 +405,23 @@ def cascade_verify(draft, target, block_size: int, suffix_ids, cu_suffix, prefix
     m = np.full(R, NOT_REACHED, dtype=np.int64)
     decision = np.full(B, NOT_REACHED, dtype=np.int64)
     escalated = np.zeros(B, dtype=np.uint8)
+    selected = np.zeros(B, dtype=np.uint8)
+    conf_used = np.full(B, np.nan)
     for r in which:
         lo, hi = int(req_start[r]), int(req_start[r + 1])
-        m[r], dec, esc = cascade_request(verdict_d[lo:hi], conf_d[lo:hi], lambda j, lo=lo: ask_target(lo + j), gamma)
+        if parent is None:
+            m[r], dec, esc = cascade_request(verdict_d[lo:hi], conf_d[lo:hi], lambda j, lo=lo: ask_target(lo + j), gamma)
+        else:
+            local = [int(parent[b]) - lo if parent[b] >= 0 else -1 for b in range(lo, hi)]
+            path, dec, esc, used = tree_request(local, verdict_d[lo:hi], conf_d[lo:hi],
+                                                lambda j, lo=lo: (ask_target(lo + j), conf_t[lo + j]), gamma)
+            m[r] = len(path)
+            selected[[lo + j for j in path]] = 1
+            conf_used[lo:hi] = used
         decision[lo:hi] = dec
         escalated[lo:hi] = esc
-    return dict(accepted_steps=m, decision=decision, escalated=escalated, conf_draft=conf_d, verdict_draft=verdict_d,
-                logits_draft=logits_d, conf_target=conf_t, verdict_target=verdict_t, logits_target=logits_t)
+    out = dict(accepted_steps=m, decision=decision, escalated=escalated, conf_draft=conf_d, verdict_draft=verdict_d,
+               logits_draft=logits_d, conf_target=conf_t, verdict_target=verdict_t, logits_target=logits_t)
+    if parent is not None:
+        out.update(selected=selected, conf_used=conf_used)
+    return out
