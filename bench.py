@@ -118,6 +118,9 @@ def main():
     ap.add_argument("--append", type=int, default=0, metavar="N",
                     help="also time the pass with write-back of the first N suffix tokens of every trace into the "
                          "cache and report it under \"append\"")
+    ap.add_argument("--shared-prefix", type=int, default=0, metavar="W",
+                    help="also time the pass with groups of W traces reading the same context pages (the W candidates of "
+                         "one step in tree-structured drafting) and report it under \"shared_prefix\"")
     ap.add_argument("--cpu-baseline-traces", type=int, default=6,
                     help="traces of the workload the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -274,6 +277,28 @@ def main():
                            bytes_written=rows * m.n_layers * 2 * m.n_kv_heads * m.head_dim * (2 if m.dtype == "bf16" else 4),
                            extra_ms_vs_eager_pass=round(ms_a - eager_ms, 4))
 
+    shared_info = None
+    if args.shared_prefix > 1:
+        import copy
+        Wd = args.shared_prefix
+        batch_s = copy.copy(batch)
+        table = batch.block_table.clone()
+        for b in range(wl.B):
+            table[b] = batch.block_table[b - b % Wd]         # prefix lengths are equal inside a group in this workload
+        batch_s.block_table = table
+        for _ in range(3):
+            ver.verify(kv, batch_s, vids, taus, outputs=outs)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            ver.verify(kv, batch_s, vids, taus, outputs=outs)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_s = e0.elapsed_time(e1) / args.steps
+        shared_info = dict(group=Wd, ms_per_step=round(ms_s, 4), launch="eager", distinct_pages_ms_per_step=round(eager_ms, 4),
+                           context_bytes_distinct=int(sum(wl.prefix_lens)) * m.n_layers * 2 * m.n_kv_heads * m.head_dim * 2,
+                           context_bytes_shared=int(sum(wl.prefix_lens[::Wd])) * m.n_layers * 2 * m.n_kv_heads * m.head_dim * 2)
+
     cascade_info = None
     if args.cascade:
         cascade_info = _time_cascade(W, wl, ver, kv, batch, vids, dev, max(args.steps // 2, 3))
@@ -305,6 +330,7 @@ def main():
                    **({"tune": args.tune} if args.tune else {})},
         "roofline": roofline, "cpu_baseline": cpu, **({"copy_calibration": copy_info} if copy_info else {}),
         **({"cascade": cascade_info} if cascade_info else {}), **({"append": append_info} if append_info else {}),
+        **({"shared_prefix": shared_info} if shared_info else {}),
     }))
 
 

@@ -8,6 +8,11 @@
  * steps are then walked in order and accepted until the first rejection (the loop of Stage 2), which
  * gives m, the number of drafted steps that join the context (Stage 3).
  *
+ * Tree-structured drafting (Section 4.3, Eq. 5): with a parent array the traces of a request form a tree of candidate
+ * steps.  Cascaded verification is applied to every candidate; layer by layer, among the candidates that continue
+ * the step chosen so far and pass, the one with the highest confidence (the small model's where its decision was
+ * kept, the large model's where it was consulted; lowest index on ties) is chosen, until nothing passes.
+ *
  * Both models read the same token ids (one tokenizer; the embedding tables may be padded to different
  * sizes, ids must be valid for both) and have each their own paged cache of the same contexts.  The large model's pass runs on the compacted sub-batch of the traces that can be consulted:
  * confidence below gamma and no earlier step of the request rejected by a confident small-model decision
@@ -34,6 +39,11 @@ typedef struct {
     int32_t n_requests;
     const int32_t *req_start;
     const int32_t *h_req_start;
+    /* Candidate trees, or both NULL for chains (step j continues step j-1): parent[b] = the trace that candidate b
+     * continues, an earlier trace of the same request, or -1 for a candidate that continues the context itself.
+     * dev int32 [B] and a host copy. */
+    const int32_t *parent;
+    const int32_t *h_parent;
 } confspec_requests;
 
 /* Outputs, all dev, written by the call.  verdict values are indices into the verdict id list;
@@ -43,11 +53,15 @@ typedef struct {
     int32_t *verdict_draft;   /* [B]  the small model's decision                                        */
     float *conf_target;       /* [B]  the large model's confidence, NaN where its pass left the trace out */
     int32_t *verdict_target;  /* [B]  its decision, CONFSPEC_NOT_REACHED where left out                  */
-    int32_t *decision;        /* [B]  cascaded decision of the steps the loop reaches (the accepted ones and
-                                      the first rejection of each request), CONFSPEC_NOT_REACHED after that */
+    int32_t *decision;        /* [B]  cascaded decision of the steps the walk reaches (a chain: the accepted ones
+                                      and the first rejection; a tree: every candidate that continues a chosen
+                                      step or the context), CONFSPEC_NOT_REACHED elsewhere                */
     uint8_t *escalated;       /* [B]  1 where the loop consulted the large model                        */
     uint8_t *target_ran;      /* [B]  1 where the large model's pass included the trace                 */
-    int32_t *accepted_steps;  /* [n_requests]  m                                                        */
+    int32_t *accepted_steps;  /* [n_requests]  m = number of chosen steps                               */
+    uint8_t *selected;        /* [B]  1 on the chosen steps (a chain: the first m); may be NULL         */
+    float *conf_used;         /* [B]  the confidence that entered the selection (kept: the small model's,
+                                      escalated: the large model's), NaN where not reached; may be NULL */
 } confspec_cascade_out;
 
 /* Bytes of dev scratch confspec_cascade needs for batches up to max_B traces and max_T suffix tokens with a

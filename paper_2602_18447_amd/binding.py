@@ -50,13 +50,15 @@ class Batch(C.Structure):
 
 
 class Requests(C.Structure):
-    _fields_ = [("n_requests", C.c_int32), ("req_start", C.c_void_p), ("h_req_start", C.POINTER(C.c_int32))]
+    _fields_ = [("n_requests", C.c_int32), ("req_start", C.c_void_p), ("h_req_start", C.POINTER(C.c_int32)),
+                ("parent", C.c_void_p), ("h_parent", C.POINTER(C.c_int32))]
 
 
 class CascadeOut(C.Structure):
     _fields_ = [("conf_draft", C.c_void_p), ("verdict_draft", C.c_void_p), ("conf_target", C.c_void_p),
                 ("verdict_target", C.c_void_p), ("decision", C.c_void_p), ("escalated", C.c_void_p),
-                ("target_ran", C.c_void_p), ("accepted_steps", C.c_void_p)]
+                ("target_ran", C.c_void_p), ("accepted_steps", C.c_void_p), ("selected", C.c_void_p),
+                ("conf_used", C.c_void_p)]
 
 
 def _load() -> C.CDLL:
@@ -296,11 +298,14 @@ def confspec_cascade(draft_ctx, draft_w: Weights, draft_kv: KV, draft_ws, target
     return int(n_target.value)
 
 
-def make_requests(req_start, h_req_start):
-    """req_start: device int32 tensor [R+1]; h_req_start: the same values on the host.  Returns (Requests, keepalive)."""
+def make_requests(req_start, h_req_start, parent=None, h_parent=None):
+    """req_start: device int32 tensor [R+1]; h_req_start: the same values on the host; parent / h_parent: the
+    candidate trees (device tensor [B] and host copy) or None for chains.  Returns (Requests, keepalive)."""
     import numpy as np
     hr = np.ascontiguousarray(h_req_start, dtype=np.int32)
-    return Requests(len(hr) - 1, _ptr(req_start), hr.ctypes.data_as(C.POINTER(C.c_int32))), hr
+    hp = None if h_parent is None else np.ascontiguousarray(h_parent, dtype=np.int32)
+    hp_ptr = None if hp is None else hp.ctypes.data_as(C.POINTER(C.c_int32))
+    return Requests(len(hr) - 1, _ptr(req_start), hr.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(parent), hp_ptr), (hr, hp)
 
 
 def confspec_tune(key: str, value: int) -> None:

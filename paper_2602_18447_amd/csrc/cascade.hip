@@ -1,4 +1,5 @@
-// Two-tier cascade over the drafted steps of a batch of requests (Section 4.2, Eq. 4; Algorithm 1, Stage 2):
+// Two-tier cascade over the drafted steps of a batch of requests (Section 4.2, Eq. 4; Algorithm 1, Stage 2; candidate
+// trees: Section 4.3, Eq. 5):
 // selection and compaction of the traces the large model has to see, and the walk over each request's steps
 // once both models have spoken.  The two forward passes themselves are confspec_verify calls.
 #include "kernels.h"
@@ -6,15 +7,23 @@
 
 namespace cs {
 
-// Which traces can the loop of Stage 2 escalate?  Step j of a request is consulted by the loop only if every
-// earlier step was accepted; it goes to the large model if its small-model confidence is below gamma.  Before
-// the large model has run, "accepted" is unknown for the escalated steps, but a confident rejection by the small
-// model is final: steps after it are never reached.  keep[b] is the small model's gate bit (confidence >= gamma).
-// One thread per request; then an exclusive scan over the traces compacts the selected ones.
+// Which traces can the walk of Stage 2 escalate?  A candidate is looked at only if the step it continues was chosen,
+// and it goes to the large model if its small-model confidence is below gamma.  Before the large model has run,
+// "chosen" is unknown for the escalated steps, but a confident rejection by the small model is final: nothing that
+// continues such a step is ever reached.  keep[b] is the small model's gate bit (confidence >= gamma).
+// parent (may be null): the trace that b continues, -1 for a first-layer candidate; null = every request is a chain.
+// One thread per request walks its traces in index order (parents come first); open_flag is per-trace scratch.
+// Then an exclusive scan over the traces compacts the selected ones.
+__device__ __forceinline__ int parent_of(const int32_t *parent, int b, int lo) {
+    int p = parent ? parent[b] : (b > lo ? b - 1 : -1);
+    return (p >= lo && p < b) ? p : -1;          // anything else counts as "continues the context itself"
+}
+
 __global__ __launch_bounds__(256) void cascade_select_kernel(const uint8_t *__restrict__ keep, const int32_t *__restrict__ verdict_d,
-                                                              const int32_t *__restrict__ req_start, int R, int B,
-                                                              const int32_t *__restrict__ cu, const int32_t *__restrict__ plens,
-                                                              int T, uint8_t *__restrict__ target_ran,
+                                                              const int32_t *__restrict__ req_start, const int32_t *__restrict__ parent,
+                                                              int R, int B, const int32_t *__restrict__ cu,
+                                                              const int32_t *__restrict__ plens, int T, uint8_t *open_flag,
+                                                              uint8_t *__restrict__ target_ran,
                                                               int32_t *__restrict__ pos_of, int32_t *__restrict__ sel_idx,
                                                               int32_t *__restrict__ cu_out, int32_t *__restrict__ plens_out,
                                                               int32_t *__restrict__ n_out) {
@@ -23,11 +32,11 @@ __global__ __launch_bounds__(256) void cascade_select_kernel(const uint8_t *__re
     int tid = threadIdx.x;
     for (int r = tid; r < R; r += 256) {
         int lo = min(max(req_start[r], 0), B), hi = min(max(req_start[r + 1], lo), B);
-        bool open = true;       // no confident rejection so far
         for (int b = lo; b < hi; ++b) {
-            bool kept = keep[b] != 0;
-            target_ran[b] = (open && !kept) ? 1 : 0;
-            if (kept && verdict_d[b] != 0) open = false;
+            int p = parent_of(parent, b, lo);
+            bool open = p < 0 ? true : (open_flag[p] != 0 && !(keep[p] != 0 && verdict_d[p] != 0));
+            open_flag[b] = open ? 1 : 0;
+            target_ran[b] = (open && keep[b] == 0) ? 1 : 0;
         }
     }
     if (tid == 0) carry[0] = carry[1] = 0;
@@ -87,14 +96,17 @@ __global__ __launch_bounds__(256) void cascade_gather_kernel(const int32_t *__re
     for (int i = threadIdx.x; i < max_blocks; i += blockDim.x) table_out[(size_t)p * max_blocks + i] = table[(size_t)b * max_blocks + i];
 }
 
-// The loop of Stage 2 per request, with both models' decisions known; and the large model's results scattered
-// back to the traces of the full batch.
+// The walk of Stage 2 per request, with both models' decisions known (a chain: accept until the first rejection; a
+// tree: among the accepted candidates that continue the chosen step take the most confident one, Eq. 5); and the
+// large model's results scattered back to the traces of the full batch.
 __global__ __launch_bounds__(256) void cascade_merge_kernel(const uint8_t *__restrict__ keep, const int32_t *__restrict__ verdict_d,
-                                                             const int32_t *__restrict__ pos_of,
+                                                             const float *__restrict__ conf_d, const int32_t *__restrict__ pos_of,
                                                              const float *__restrict__ conf_t_c, const int32_t *__restrict__ verdict_t_c,
-                                                             const int32_t *__restrict__ req_start, int R, int B, int n_target,
+                                                             const int32_t *__restrict__ req_start, const int32_t *__restrict__ parent,
+                                                             int R, int B, int n_target,
                                                              float *__restrict__ conf_t, int32_t *__restrict__ verdict_t,
                                                              int32_t *__restrict__ decision, uint8_t *__restrict__ escalated,
+                                                             uint8_t *__restrict__ selected, float *__restrict__ conf_used,
                                                              int32_t *__restrict__ accepted) {
     int gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid < B) {
@@ -105,33 +117,52 @@ __global__ __launch_bounds__(256) void cascade_merge_kernel(const uint8_t *__res
     }
     if (gid < R) {
         int lo = min(max(req_start[gid], 0), B), hi = min(max(req_start[gid + 1], lo), B);
-        int m = 0;
-        bool open = true;
         for (int b = lo; b < hi; ++b) {
-            int v = -1, esc = 0;
-            if (open) {
+            decision[b] = -1;
+            escalated[b] = 0;
+            if (selected) selected[b] = 0;
+            if (conf_used) conf_used[b] = NAN;
+        }
+        int m = 0, cur = -1;
+        for (int depth = 0; depth < hi - lo; ++depth) {          // a chosen node has a larger index than its parent
+            int best = -1;
+            float best_p = 0.f;
+            for (int b = max(cur + 1, lo); b < hi; ++b) {
+                if (parent_of(parent, b, lo) != cur) continue;
+                int v;
+                float pu;
                 if (keep[b]) {
                     v = verdict_d[b];
+                    pu = conf_d[b];
                 } else {
                     int p = pos_of[b];
-                    v = (p >= 0 && p < n_target) ? verdict_t_c[p] : -1;   // selected by construction
-                    esc = 1;
+                    bool has = p >= 0 && p < n_target;           // selected by construction
+                    v = has ? verdict_t_c[p] : -1;
+                    pu = has ? conf_t_c[p] : NAN;
+                    escalated[b] = 1;
                 }
-                if (v == 0) ++m;
-                else open = false;
+                decision[b] = v;
+                if (conf_used) conf_used[b] = pu;
+                if (v == 0 && (best < 0 || pu > best_p)) {
+                    best = b;
+                    best_p = pu;
+                }
             }
-            decision[b] = v;
-            escalated[b] = (uint8_t)esc;
+            if (best < 0) break;
+            if (selected) selected[best] = 1;
+            ++m;
+            cur = best;
         }
         accepted[gid] = m;
     }
 }
 
-hipError_t launch_cascade_select(const uint8_t *keep, const int32_t *verdict_d, const int32_t *req_start, int R, int B,
-                                 const int32_t *cu, const int32_t *plens, int T, uint8_t *target_ran, int32_t *pos_of,
-                                 int32_t *sel_idx, int32_t *cu_out, int32_t *plens_out, int32_t *n_out, hipStream_t s) {
-    cascade_select_kernel<<<1, 256, 0, s>>>(keep, verdict_d, req_start, R, B, cu, plens, T, target_ran, pos_of, sel_idx,
-                                            cu_out, plens_out, n_out);
+hipError_t launch_cascade_select(const uint8_t *keep, const int32_t *verdict_d, const int32_t *req_start, const int32_t *parent,
+                                 int R, int B, const int32_t *cu, const int32_t *plens, int T, uint8_t *open_flag,
+                                 uint8_t *target_ran, int32_t *pos_of, int32_t *sel_idx, int32_t *cu_out, int32_t *plens_out,
+                                 int32_t *n_out, hipStream_t s) {
+    cascade_select_kernel<<<1, 256, 0, s>>>(keep, verdict_d, req_start, parent, R, B, cu, plens, T, open_flag, target_ran,
+                                            pos_of, sel_idx, cu_out, plens_out, n_out);
     return hipGetLastError();
 }
 
@@ -142,13 +173,15 @@ hipError_t launch_cascade_gather(const int32_t *pos_of, const int32_t *cu, const
     return hipGetLastError();
 }
 
-hipError_t launch_cascade_merge(const uint8_t *keep, const int32_t *verdict_d, const int32_t *pos_of, const float *conf_t_c,
-                                const int32_t *verdict_t_c, const int32_t *req_start, int R, int B, int n_target,
-                                float *conf_t, int32_t *verdict_t, int32_t *decision, uint8_t *escalated, int32_t *accepted,
+hipError_t launch_cascade_merge(const uint8_t *keep, const int32_t *verdict_d, const float *conf_d, const int32_t *pos_of,
+                                const float *conf_t_c, const int32_t *verdict_t_c, const int32_t *req_start,
+                                const int32_t *parent, int R, int B, int n_target, float *conf_t, int32_t *verdict_t,
+                                int32_t *decision, uint8_t *escalated, uint8_t *selected, float *conf_used, int32_t *accepted,
                                 hipStream_t s) {
     int n = B > R ? B : R;
-    cascade_merge_kernel<<<(n + 255) / 256, 256, 0, s>>>(keep, verdict_d, pos_of, conf_t_c, verdict_t_c, req_start, R, B,
-                                                          n_target, conf_t, verdict_t, decision, escalated, accepted);
+    cascade_merge_kernel<<<(n + 255) / 256, 256, 0, s>>>(keep, verdict_d, conf_d, pos_of, conf_t_c, verdict_t_c, req_start,
+                                                          parent, R, B, n_target, conf_t, verdict_t, decision, escalated,
+                                                          selected, conf_used, accepted);
     return hipGetLastError();
 }
 

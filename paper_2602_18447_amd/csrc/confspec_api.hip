@@ -780,7 +780,7 @@ int confspec_tune(const char *key, int32_t value) {
 
 namespace {
 struct CascadeLayout {
-    size_t keep, pos_of, sel_idx, cu_out, plens_out, n_out, ids_out, table_out, logits_d, logits_t, conf_t, verdict_t,
+    size_t keep, open_flag, pos_of, sel_idx, cu_out, plens_out, n_out, ids_out, table_out, logits_d, logits_t, conf_t, verdict_t,
         accept_t, total;
 };
 CascadeLayout cascade_layout(int64_t B, int64_t T, int64_t max_blocks) {
@@ -788,6 +788,7 @@ CascadeLayout cascade_layout(int64_t B, int64_t T, int64_t max_blocks) {
     size_t at = 0;
     auto take = [&](size_t bytes) { size_t o = at; at += (bytes + 255) & ~(size_t)255; return o; };
     L.keep = take(B);
+    L.open_flag = take(B);
     L.pos_of = take(B * 4);
     L.sel_idx = take(B * 4);
     L.cu_out = take((B + 1) * 4);
@@ -842,6 +843,13 @@ int confspec_cascade(confspec_ctx *draft, const confspec_weights *wd, const conf
     for (int r = 0; r < R; ++r)
         if (req->h_req_start[r + 1] <= req->h_req_start[r])
             return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "req_start not strictly increasing at request %d (every request needs >= 1 step)", r);
+    if ((req->parent == nullptr) != (req->h_parent == nullptr))
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "parent and h_parent must both be given or both be null");
+    for (int r = 0; req->h_parent && r < R; ++r)
+        for (int b = req->h_req_start[r]; b < req->h_req_start[r + 1]; ++b)
+            if (req->h_parent[b] != -1 && (req->h_parent[b] < req->h_req_start[r] || req->h_parent[b] >= b))
+                return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "parent[%d] = %d: must be -1 or an earlier trace of the same request", b,
+                            req->h_parent[b]);
     CascadeLayout C = cascade_layout(B, T, kvt->max_blocks_per_seq);
     if ((rc = check_ws(ctx, dev_scratch, scratch_bytes, C.total)) != CONFSPEC_OK) return rc;
     // the large model's pass is a sub-batch of this one, so a workspace for the whole batch is enough for it
@@ -865,8 +873,9 @@ int confspec_cascade(confspec_ctx *draft, const confspec_weights *wd, const conf
                               (float *)(sc + C.logits_d), out->conf_draft, out->verdict_draft, keep, s)) != CONFSPEC_OK)
         return rc;
     if (keep_nothing) HIP_TRY(hipMemsetAsync(keep, 0, B, s));
-    HIP_TRY(cs::launch_cascade_select(keep, out->verdict_draft, req->req_start, R, B, batch->cu_suffix, batch->prefix_lens, T,
-                                      out->target_ran, pos_of, sel_idx, cu_out, plens_out, n_out, s));
+    HIP_TRY(cs::launch_cascade_select(keep, out->verdict_draft, req->req_start, req->parent, R, B, batch->cu_suffix,
+                                      batch->prefix_lens, T, (uint8_t *)(sc + C.open_flag), out->target_ran, pos_of, sel_idx,
+                                      cu_out, plens_out, n_out, s));
     HIP_TRY(cs::launch_cascade_gather(pos_of, batch->cu_suffix, cu_out, batch->suffix_ids, ids_out, kvt->block_table,
                                       table_out, kvt->max_blocks_per_seq, B, T, s));
     // The one host round trip of the call: how many traces the large model sees, their suffix offsets and prefix
@@ -890,9 +899,9 @@ int confspec_cascade(confspec_ctx *draft, const confspec_weights *wd, const conf
             CONFSPEC_OK)
             return fail(ctx, rc, "target: %s", target->err.c_str());
     }
-    HIP_TRY(cs::launch_cascade_merge(keep, out->verdict_draft, pos_of, conf_t_c, verdict_t_c, req->req_start, R, B, n,
-                                     out->conf_target, out->verdict_target, out->decision, out->escalated,
-                                     out->accepted_steps, s));
+    HIP_TRY(cs::launch_cascade_merge(keep, out->verdict_draft, out->conf_draft, pos_of, conf_t_c, verdict_t_c, req->req_start,
+                                     req->parent, R, B, n, out->conf_target, out->verdict_target, out->decision,
+                                     out->escalated, out->selected, out->conf_used, out->accepted_steps, s));
     return CONFSPEC_OK;
 }
 

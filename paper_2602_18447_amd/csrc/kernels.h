@@ -152,15 +152,17 @@ hipError_t launch_kv_append(const void *ksuf, const void *vsuf, void *k_pages, v
                             hipStream_t s);
 
 // ---- cascade (cascade.hip) ----
-hipError_t launch_cascade_select(const uint8_t *keep, const int32_t *verdict_d, const int32_t *req_start, int R, int B,
-                                 const int32_t *cu, const int32_t *plens, int T, uint8_t *target_ran, int32_t *pos_of,
-                                 int32_t *sel_idx, int32_t *cu_out, int32_t *plens_out, int32_t *n_out, hipStream_t s);
+hipError_t launch_cascade_select(const uint8_t *keep, const int32_t *verdict_d, const int32_t *req_start, const int32_t *parent,
+                                 int R, int B, const int32_t *cu, const int32_t *plens, int T, uint8_t *open_flag,
+                                 uint8_t *target_ran, int32_t *pos_of, int32_t *sel_idx, int32_t *cu_out, int32_t *plens_out,
+                                 int32_t *n_out, hipStream_t s);
 hipError_t launch_cascade_gather(const int32_t *pos_of, const int32_t *cu, const int32_t *cu_out, const int32_t *ids,
                                  int32_t *ids_out, const int32_t *table, int32_t *table_out, int max_blocks, int B, int T,
                                  hipStream_t s);
-hipError_t launch_cascade_merge(const uint8_t *keep, const int32_t *verdict_d, const int32_t *pos_of, const float *conf_t_c,
-                                const int32_t *verdict_t_c, const int32_t *req_start, int R, int B, int n_target,
-                                float *conf_t, int32_t *verdict_t, int32_t *decision, uint8_t *escalated, int32_t *accepted,
+hipError_t launch_cascade_merge(const uint8_t *keep, const int32_t *verdict_d, const float *conf_d, const int32_t *pos_of,
+                                const float *conf_t_c, const int32_t *verdict_t_c, const int32_t *req_start,
+                                const int32_t *parent, int R, int B, int n_target, float *conf_t, int32_t *verdict_t,
+                                int32_t *decision, uint8_t *escalated, uint8_t *selected, float *conf_used, int32_t *accepted,
                                 hipStream_t s);
 
 }  // namespace cs

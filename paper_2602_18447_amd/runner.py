@@ -96,7 +96,7 @@ class Cascade:
     the same token ids, each with its own cache of the same contexts.  Only buffers are owned here."""
 
     NAMES = ("conf_draft", "verdict_draft", "conf_target", "verdict_target", "decision", "escalated", "target_ran",
-             "accepted_steps")
+             "accepted_steps", "selected", "conf_used")
 
     def __init__(self, draft: Verifier, target: Verifier):
         self.draft, self.target = draft, target
@@ -105,18 +105,20 @@ class Cascade:
     def alloc_outputs(self, B: int, R: int):
         dev = self.draft.device
         f32, i32, u8 = torch.float32, torch.int32, torch.uint8
-        dts = (f32, i32, f32, i32, i32, u8, u8, i32)
+        dts = (f32, i32, f32, i32, i32, u8, u8, i32, u8, f32)
         return {n: torch.empty(R if n == "accepted_steps" else B, dtype=dt, device=dev) for n, dt in zip(self.NAMES, dts)}
 
     def run(self, draft_kv, target_kv, batch, h_req_start, verdict_ids: Sequence[int], gamma: float, outputs=None,
-            stream=None):
-        """One cascade; synchronises the stream once inside.  Returns (outputs dict of device tensors, traces the
-        large model's pass held)."""
+            stream=None, parent=None):
+        """One cascade; synchronises the stream once inside.  parent: host integers [B] for candidate trees, None for
+        chains.  Returns (outputs dict of device tensors, traces the large model's pass held)."""
         kd, bs, keep = self.draft.bind(draft_kv, batch)
         kt, _, keep_t = self.target.bind(target_kv, batch)
         hr = np.ascontiguousarray(h_req_start, dtype=np.int32)
         req_dev = torch.from_numpy(hr).to(self.draft.device)
-        reqs, keep_r = cb.make_requests(req_dev, hr)
+        hp = None if parent is None else np.ascontiguousarray(parent, dtype=np.int32)
+        par_dev = None if hp is None else torch.from_numpy(hp).to(self.draft.device)
+        reqs, keep_r = cb.make_requests(req_dev, hr, par_dev, hp)
         need = cb.confspec_cascade_scratch_bytes(bs.B, bs.T, kt.max_blocks_per_seq)
         if self._scratch is None or self._scratch.numel() < need:
             self._scratch = torch.empty(need, dtype=torch.uint8, device=self.draft.device)

@@ -166,12 +166,12 @@ def test_cascade_validates_before_any_launch():
     ctx_d, ctx_t = cb.confspec_create(cfg_d), cb.confspec_create(cfg_t)
     fake, w, kv, batch, keep = _verify_args(cfg_d, B=3, S=(3, 2, 4), L=(5, 0, 7))
     _, w_t, _, _, keep_t = _verify_args(cfg_t, B=3, S=(3, 2, 4), L=(5, 0, 7))
-    out = cb.CascadeOut(*([fake.data_ptr()] * 8))
+    out = cb.CascadeOut(*([fake.data_ptr()] * 10))
     assert cb.confspec_cascade_scratch_bytes(3, 9, 4) % 256 == 0
     assert cb.confspec_cascade_scratch_bytes(0, 9, 4) == 0
 
-    def call(req=(0, 2, 3), gamma=0.9, ctx_t=ctx_t, out=out, scratch=fake, kv_t=kv, ws_t=fake):
-        reqs, keep_r = cb.make_requests(fake, np.asarray(req, dtype=np.int32))
+    def call(req=(0, 2, 3), gamma=0.9, ctx_t=ctx_t, out=out, scratch=fake, kv_t=kv, ws_t=fake, parent=None):
+        reqs, keep_r = cb.make_requests(fake, np.asarray(req, dtype=np.int32), None if parent is None else fake, parent)
         return cb.confspec_cascade(ctx_d, w, kv, fake, ctx_t, w_t, kv_t, ws_t, batch, reqs, [1, 2], gamma, scratch, out,
                                    stream=0)
 
@@ -179,6 +179,9 @@ def test_cascade_validates_before_any_launch():
     _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(req=(0, 2)))            # does not cover the batch
     _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(req=(1, 3)))
     _expect(ctx_d, cb.E_INVALID_ARG, lambda: call(req=(0, 1, 2, 3, 4)))    # more requests than traces
+    _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(parent=[-1, 1, -1]))   # a trace cannot continue itself
+    _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(parent=[-1, 0, 1]))    # nor a trace of another request
+    _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(parent=[-2, 0, -1]))
     _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(gamma=-0.1))
     _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(gamma=float("nan")))
     _expect(ctx_d, cb.E_INVALID_ARG, lambda: call(ctx_t=None))

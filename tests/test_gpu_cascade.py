@@ -224,3 +224,95 @@ def test_cascade_full_size_draft_and_target_shapes():
                     assert np.array_equal(g["escalated"][lo:hi], ora["escalated"][lo:hi])
     sd["ver"].close()
     st["ver"].close()
+
+
+def _layers_clear(parent, lo, hi, ora, tol):
+    """True if, in every layer the oracle's walk looked at, the accepted candidates' confidences are far enough apart
+    that both precisions rank them alike."""
+    reached = ora["decision"][lo:hi] != O.NOT_REACHED
+    for cur in [-1] + [lo + j for j in np.flatnonzero(ora["selected"][lo:hi])]:
+        kids = [b for b in range(lo, hi) if parent[b] == cur and reached[b - lo] and ora["decision"][b] == 0]
+        ps = sorted(ora["conf_used"][b] for b in kids)
+        if any(b - a <= 2 * tol["conf"] for a, b in zip(ps[:-1], ps[1:])):
+            return False
+    return True
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_cascade_over_candidate_trees_matches_oracle(dtype):
+    """Tree-structured drafting (Section 4.3, Eq. 5): random forests, siblings share their context pages."""
+    print(f"cascade over trees {dtype}", flush=True)
+    rng = np.random.Generator(np.random.Philox(key=777))
+    sizes = [1, 4, 7, 3, 6, 2, 8]                                       # candidates per request
+    req_start = [0] + list(np.cumsum(sizes))
+    B = req_start[-1]
+    parent = np.full(B, -1, dtype=np.int32)
+    depth = np.zeros(B, dtype=np.int64)
+    for lo, hi in zip(req_start[:-1], req_start[1:]):
+        for b in range(lo + 1, hi):
+            parent[b] = int(rng.integers(lo - 1, b)) if rng.random() < 0.75 else -1
+            if parent[b] < lo:
+                parent[b] = -1
+            depth[b] = 0 if parent[b] < 0 else depth[parent[b]] + 1
+    base = {r: int(rng.integers(0, 300)) for r in range(len(sizes))}
+    req_of = np.repeat(np.arange(len(sizes)), sizes)
+    prefix = [base[int(req_of[b])] + 37 * int(depth[b]) for b in range(B)]   # siblings: equal context length
+    suffix = [int(v) for v in rng.integers(1, 70, size=B)]
+    wl_d, wl_t = _pair(3300, prefix, suffix, dtype)
+    batch, sd, st = _sides(wl_d, wl_t)
+    # candidates that continue the same step share that step's context: same block-table row
+    table = batch.block_table.clone()
+    first = {}
+    for b in range(B):
+        key = (int(req_of[b]), int(parent[b]))
+        if key in first:
+            table[b] = table[first[key]]
+        else:
+            first[key] = b
+    batch.block_table = table
+    for side in (sd, st):
+        side["ora"]["kv"] = W.OracleKVView(side["kv"], batch)
+    vids = W.draw_verdict_ids(wl_d)
+    casc = Cascade(sd["ver"], st["ver"])
+    ids, cu, pl = batch.suffix_ids.cpu().numpy(), batch.h_cu_suffix, batch.h_prefix_lens
+    probe = O.verify(wl_d.model, sd["ora"]["model"], sd["ora"]["kv"], wl_d.block_size, ids, cu, pl, vids, [0.5])
+    tol = G.TOL[dtype]
+    compared = total = 0
+    gammas = [0.0] + _gammas_in_gaps(probe["conf"], want=(0.2, 0.4, 0.6, 0.8), min_gap=3 * tol["band"]) + [1.5]
+    for gamma in gammas:
+        ora = O.cascade_verify(sd["ora"], st["ora"], wl_d.block_size, ids, cu, pl, vids, gamma, req_start, parent=parent)
+        res, n_target = casc.run(sd["kv"], st["kv"], batch, req_start, vids, gamma, parent=parent)
+        torch.cuda.synchronize()
+        g = {k: v.cpu().numpy() for k, v in res.items()}
+        gap_d = np.abs(np.diff(np.sort(ora["logits_draft"], axis=1)[:, -2:], axis=1))[:, 0]
+        clear = (np.abs(ora["conf_draft"] - gamma) > tol["band"]) & (gap_d > 2 * tol["logit"])
+        asked = ~np.isnan(ora["conf_target"])
+        lt = np.sort(np.nan_to_num(ora["logits_target"]), axis=1)
+        clear &= ~asked | ((lt[:, -1] - lt[:, -2]) > 2 * tol["logit"])
+        for r, (lo, hi) in enumerate(zip(req_start[:-1], req_start[1:])):
+            total += 1
+            reached = ora["decision"][lo:hi] != O.NOT_REACHED
+            if not clear[lo:hi][reached].all() or not _layers_clear(parent, lo, hi, ora, tol):
+                continue
+            compared += 1
+            assert g["accepted_steps"][r] == ora["accepted_steps"][r], (r, gamma)
+            for k in ("decision", "escalated", "selected"):
+                assert np.array_equal(g[k][lo:hi], ora[k][lo:hi]), (k, r, gamma)
+            assert np.abs(g["conf_used"][lo:hi][reached] - ora["conf_used"][lo:hi][reached]).max() <= tol["conf"]
+            assert np.isnan(g["conf_used"][lo:hi][~reached]).all()
+        # structure that holds for every request
+        ran = g["target_ran"].astype(bool)
+        assert n_target == int(ran.sum()) and np.all(g["escalated"] <= g["target_ran"])
+        for r, (lo, hi) in enumerate(zip(req_start[:-1], req_start[1:])):
+            chosen = [lo + j for j in np.flatnonzero(g["selected"][lo:hi])]
+            assert len(chosen) == g["accepted_steps"][r]
+            cur = -1
+            for b in chosen:                                            # a path from the context downwards
+                assert parent[b] == cur and g["decision"][b] == 0
+                cur = b
+            for b in range(lo, hi):                                     # looked at iff it continues the path
+                assert (g["decision"][b] != O.NOT_REACHED) == (parent[b] == -1 or parent[b] in chosen)
+        print(f"trees gamma={gamma:.4f}: in the large model's pass {n_target}/{B}, chosen steps {g['accepted_steps'].tolist()}",
+              flush=True)
+    print(f"requests compared bit for bit: {compared}/{total}", flush=True)
+    assert compared >= 0.4 * total          # small random models decide many steps by less than the logit bound
