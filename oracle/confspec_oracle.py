@@ -294,6 +294,85 @@ def append_rows(cfg, model, kv, block_size: int, suffix_ids, cu_suffix, prefix_l
 
 
 # --------------------------------------------------------------------------- #
+# Generation (Algorithm 1: the generate calls of both models) and the
+# full-vocabulary reading of the confidence
+# --------------------------------------------------------------------------- #
+def head_stats(x_last: np.ndarray, final_norm: np.ndarray, lm_head: np.ndarray, eps: float):
+    """(token, max_logit, lse) at one position: z = W_lm . RMSNorm(x_last) over the whole vocabulary,
+    token = argmax z (lowest index on ties), lse = log sum_v exp z_v.  The probability of any token v under
+    the full softmax is exp(z_v - lse)."""
+    z = np.asarray(lm_head, dtype=np.float64) @ rmsnorm(x_last, final_norm, eps)
+    tok = int(np.argmax(z))
+    zmax = float(z[tok])
+    return tok, zmax, zmax + math.log(float(np.sum(np.exp(z - zmax))))
+
+
+def next_token(cfg, model, kv, block_size: int, suffix_ids, cu_suffix, prefix_lens,
+               verdict_ids: Optional[Sequence[int]] = None, trace_subset: Optional[Sequence[int]] = None) -> dict:
+    """Greedy next token after the last suffix position of every listed trace, with the statistics of the
+    full-vocabulary softmax.  With verdict_ids it also returns conf_full: the largest full-vocabulary
+    probability among the verdict tokens (the other reading of "the corresponding softmax probability"
+    after Eq. 3; the restricted confidence is this value renormalised over the verdict tokens).
+    model needs lm_head_full() -> [V, d]."""
+    suffix_ids = np.asarray(suffix_ids)
+    cu = np.asarray(cu_suffix, dtype=np.int64)
+    Ls = np.asarray(prefix_lens, dtype=np.int64)
+    which = list(range(len(Ls))) if trace_subset is None else list(trace_subset)
+    empty = np.zeros((0, cfg.n_kv_heads, cfg.head_dim))
+    traces = []
+    for b in which:
+        L = int(Ls[b])
+        blk_ids = np.asarray(kv.block_table[b][:(L + block_size - 1) // block_size], dtype=np.int64)
+        traces.append(dict(ids=suffix_ids[cu[b]:cu[b + 1]], L=L,
+                           k_prefix=lambda l, blk_ids=blk_ids, L=L: gather_prefix(kv.k_blocks(l, blk_ids), L) if L else empty,
+                           v_prefix=lambda l, blk_ids=blk_ids, L=L: gather_prefix(kv.v_blocks(l, blk_ids), L) if L else empty))
+    xs, _ = forward(cfg, model, traces)
+    g = np.asarray(model.final_norm, dtype=np.float64)
+    head = np.asarray(model.lm_head_full(), dtype=np.float64)
+    tok, zmax, lse, conf_full = [], [], [], []
+    for x in xs:
+        t, m, s = head_stats(x[-1], g, head, cfg.rms_eps)
+        tok.append(t); zmax.append(m); lse.append(s)
+        if verdict_ids is not None:
+            zv = verdict_logits(x[-1], g, head[np.asarray(verdict_ids)], cfg.rms_eps)
+            conf_full.append(float(np.exp(np.max(zv) - s)))
+    out = dict(traces=np.asarray(which, dtype=np.int32), token=np.asarray(tok, dtype=np.int64),
+               max_logit=np.asarray(zmax), lse=np.asarray(lse))
+    if verdict_ids is not None:
+        out["conf_full"] = np.asarray(conf_full)
+    return out
+
+
+def generate_greedy(cfg, model, k_ctx, v_ctx, first_ids: Sequence[int], n_steps: int):
+    """n_steps greedy tokens per trace, one position at a time on a growing context.
+
+    k_ctx[l][b], v_ctx[l][b]: [L_b, Hkv, hd] cached context of trace b; first_ids[b]: the token at position L_b
+    (the last token so far, whose keys / values are not cached yet).  Each step runs that one token through the
+    layers on top of the cache, appends its keys / values to the context, and takes the arg max of the
+    full-vocabulary logits as the next token.
+    Returns (tokens [B, n_steps], max_logit, lse, k_ctx, v_ctx) with the grown contexts (each L_b + n_steps rows)."""
+    B = len(first_ids)
+    k = [[np.asarray(k_ctx[l][b], dtype=np.float64) for b in range(B)] for l in range(cfg.n_layers)]
+    v = [[np.asarray(v_ctx[l][b], dtype=np.float64) for b in range(B)] for l in range(cfg.n_layers)]
+    g = np.asarray(model.final_norm, dtype=np.float64)
+    head = np.asarray(model.lm_head_full(), dtype=np.float64)
+    cur = [int(t) for t in first_ids]
+    toks = np.zeros((B, n_steps), dtype=np.int64)
+    zmax, lse = np.zeros((B, n_steps)), np.zeros((B, n_steps))
+    for i in range(n_steps):
+        traces = [dict(ids=np.asarray([cur[b]]), L=k[0][b].shape[0], k_prefix=lambda l, b=b: k[l][b],
+                       v_prefix=lambda l, b=b: v[l][b]) for b in range(B)]
+        xs, kvs = forward(cfg, model, traces, keep_kv=True)
+        for b in range(B):
+            for l in range(cfg.n_layers):
+                k[l][b] = np.concatenate([k[l][b], kvs[b][l][0]])
+                v[l][b] = np.concatenate([v[l][b], kvs[b][l][1]])
+            toks[b, i], zmax[b, i], lse[b, i] = head_stats(xs[b][-1], g, head, cfg.rms_eps)
+            cur[b] = int(toks[b, i])
+    return toks, zmax, lse, k, v
+
+
+# --------------------------------------------------------------------------- #
 # Two-tier cascade over the k drafted steps of one request (Algorithm 1, Stage 2;
 # Section 4.2, "Cascaded Decision Rule", Eq. 4)
 # --------------------------------------------------------------------------- #

@@ -35,6 +35,9 @@ class DictModel:
     def lm_head_rows(self, ids):
         return self.lm_head[np.asarray(ids, dtype=np.int64)]
 
+    def lm_head_full(self):
+        return self.lm_head
+
     def layer(self, l):
         return self.layers[l]
 
