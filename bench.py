@@ -121,6 +121,9 @@ def main():
     ap.add_argument("--shared-prefix", type=int, default=0, metavar="W",
                     help="also time the pass with groups of W traces reading the same context pages (the W candidates of "
                          "one step in tree-structured drafting) and report it under \"shared_prefix\"")
+    ap.add_argument("--decode", type=int, default=0, metavar="N",
+                    help="also time N greedy generation steps (one new token per trace, keys / values appended, "
+                         "full-vocabulary head) on this workload's contexts and report them under \"decode\"")
     ap.add_argument("--cpu-baseline-traces", type=int, default=6,
                     help="traces of the workload the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -299,6 +302,28 @@ def main():
                            context_bytes_distinct=int(sum(wl.prefix_lens)) * m.n_layers * 2 * m.n_kv_heads * m.head_dim * 2,
                            context_bytes_shared=int(sum(wl.prefix_lens[::Wd])) * m.n_layers * 2 * m.n_kv_heads * m.head_dim * 2)
 
+    decode_info = None
+    if args.decode > 0:
+        nst = args.decode
+        batch_d = W.make_batch(wl, dev, extra_rows=2 * nst)
+        kv_d = W.make_seeded_kv(wl, batch_d, dev)
+        first = batch_d.suffix_ids[batch_d.cu_suffix[:-1].long()].contiguous()      # one starting token per trace
+        L0 = batch_d.h_prefix_lens
+        ver.generate_greedy(kv_d, batch_d.block_table, batch_d.n_blocks, batch_d.max_blocks_per_seq, first, L0, nst)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        toks, _, _ = ver.generate_greedy(kv_d, batch_d.block_table, batch_d.n_blocks, batch_d.max_blocks_per_seq, first,
+                                         L0 + nst, nst)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        wbytes = sum(t.numel() * t.element_size() for l in range(m.n_layers)
+                     for t in (weights.wqkv[l], weights.wo[l], weights.w_gate_up[l], weights.w_down[l]))
+        wbytes += weights.lm_head.numel() * weights.lm_head.element_size()
+        kvbytes = int(sum(wl.prefix_lens)) * m.n_layers * 2 * m.n_kv_heads * m.head_dim * weights.lm_head.element_size()
+        decode_info = dict(steps=nst, ms_per_step=round(dt / nst * 1e3, 4), tokens_per_s=round(wl.B * nst / dt, 1),
+                           launch="eager", algorithmic_bytes_per_step=wbytes + kvbytes,
+                           achieved_TBps=round((wbytes + kvbytes) / (dt / nst) / 1e12, 3))
+
     cascade_info = None
     if args.cascade:
         cascade_info = _time_cascade(W, wl, ver, kv, batch, vids, dev, max(args.steps // 2, 3))
@@ -330,7 +355,7 @@ def main():
                    **({"tune": args.tune} if args.tune else {})},
         "roofline": roofline, "cpu_baseline": cpu, **({"copy_calibration": copy_info} if copy_info else {}),
         **({"cascade": cascade_info} if cascade_info else {}), **({"append": append_info} if append_info else {}),
-        **({"shared_prefix": shared_info} if shared_info else {}),
+        **({"shared_prefix": shared_info} if shared_info else {}), **({"decode": decode_info} if decode_info else {}),
     }))
 
 

@@ -297,14 +297,18 @@ def append_rows(cfg, model, kv, block_size: int, suffix_ids, cu_suffix, prefix_l
 # Generation (Algorithm 1: the generate calls of both models) and the
 # full-vocabulary reading of the confidence
 # --------------------------------------------------------------------------- #
-def head_stats(x_last: np.ndarray, final_norm: np.ndarray, lm_head: np.ndarray, eps: float):
+def head_stats(x_last: np.ndarray, final_norm: np.ndarray, lm_head: np.ndarray, eps: float, want_margin: bool = False):
     """(token, max_logit, lse) at one position: z = W_lm . RMSNorm(x_last) over the whole vocabulary,
     token = argmax z (lowest index on ties), lse = log sum_v exp z_v.  The probability of any token v under
-    the full softmax is exp(z_v - lse)."""
+    the full softmax is exp(z_v - lse).  With want_margin a fourth value: max_logit minus the second largest
+    logit (how clearly the arg max is decided; for tests)."""
     z = np.asarray(lm_head, dtype=np.float64) @ rmsnorm(x_last, final_norm, eps)
     tok = int(np.argmax(z))
     zmax = float(z[tok])
-    return tok, zmax, zmax + math.log(float(np.sum(np.exp(z - zmax))))
+    out = (tok, zmax, zmax + math.log(float(np.sum(np.exp(z - zmax)))))
+    if want_margin:
+        out += (zmax - float(np.max(np.delete(z, tok))),)
+    return out
 
 
 def next_token(cfg, model, kv, block_size: int, suffix_ids, cu_suffix, prefix_lens,
@@ -329,28 +333,29 @@ def next_token(cfg, model, kv, block_size: int, suffix_ids, cu_suffix, prefix_le
     xs, _ = forward(cfg, model, traces)
     g = np.asarray(model.final_norm, dtype=np.float64)
     head = np.asarray(model.lm_head_full(), dtype=np.float64)
-    tok, zmax, lse, conf_full = [], [], [], []
+    tok, zmax, lse, conf_full, margin = [], [], [], [], []
     for x in xs:
-        t, m, s = head_stats(x[-1], g, head, cfg.rms_eps)
-        tok.append(t); zmax.append(m); lse.append(s)
+        t, m, s, mg = head_stats(x[-1], g, head, cfg.rms_eps, want_margin=True)
+        tok.append(t); zmax.append(m); lse.append(s); margin.append(mg)
         if verdict_ids is not None:
             zv = verdict_logits(x[-1], g, head[np.asarray(verdict_ids)], cfg.rms_eps)
             conf_full.append(float(np.exp(np.max(zv) - s)))
     out = dict(traces=np.asarray(which, dtype=np.int32), token=np.asarray(tok, dtype=np.int64),
-               max_logit=np.asarray(zmax), lse=np.asarray(lse))
+               max_logit=np.asarray(zmax), lse=np.asarray(lse), margin=np.asarray(margin))
     if verdict_ids is not None:
         out["conf_full"] = np.asarray(conf_full)
     return out
 
 
-def generate_greedy(cfg, model, k_ctx, v_ctx, first_ids: Sequence[int], n_steps: int):
+def generate_greedy(cfg, model, k_ctx, v_ctx, first_ids: Sequence[int], n_steps: int, want_margin: bool = False):
     """n_steps greedy tokens per trace, one position at a time on a growing context.
 
     k_ctx[l][b], v_ctx[l][b]: [L_b, Hkv, hd] cached context of trace b; first_ids[b]: the token at position L_b
     (the last token so far, whose keys / values are not cached yet).  Each step runs that one token through the
     layers on top of the cache, appends its keys / values to the context, and takes the arg max of the
     full-vocabulary logits as the next token.
-    Returns (tokens [B, n_steps], max_logit, lse, k_ctx, v_ctx) with the grown contexts (each L_b + n_steps rows)."""
+    Returns (tokens [B, n_steps], max_logit, lse, k_ctx, v_ctx) with the grown contexts (each L_b + n_steps rows);
+    with want_margin a sixth value, the arg max's lead over the second largest logit at every step."""
     B = len(first_ids)
     k = [[np.asarray(k_ctx[l][b], dtype=np.float64) for b in range(B)] for l in range(cfg.n_layers)]
     v = [[np.asarray(v_ctx[l][b], dtype=np.float64) for b in range(B)] for l in range(cfg.n_layers)]
@@ -358,7 +363,7 @@ def generate_greedy(cfg, model, k_ctx, v_ctx, first_ids: Sequence[int], n_steps:
     head = np.asarray(model.lm_head_full(), dtype=np.float64)
     cur = [int(t) for t in first_ids]
     toks = np.zeros((B, n_steps), dtype=np.int64)
-    zmax, lse = np.zeros((B, n_steps)), np.zeros((B, n_steps))
+    zmax, lse, margin = np.zeros((B, n_steps)), np.zeros((B, n_steps)), np.zeros((B, n_steps))
     for i in range(n_steps):
         traces = [dict(ids=np.asarray([cur[b]]), L=k[0][b].shape[0], k_prefix=lambda l, b=b: k[l][b],
                        v_prefix=lambda l, b=b: v[l][b]) for b in range(B)]
@@ -367,9 +372,9 @@ def generate_greedy(cfg, model, k_ctx, v_ctx, first_ids: Sequence[int], n_steps:
             for l in range(cfg.n_layers):
                 k[l][b] = np.concatenate([k[l][b], kvs[b][l][0]])
                 v[l][b] = np.concatenate([v[l][b], kvs[b][l][1]])
-            toks[b, i], zmax[b, i], lse[b, i] = head_stats(xs[b][-1], g, head, cfg.rms_eps)
+            toks[b, i], zmax[b, i], lse[b, i], margin[b, i] = head_stats(xs[b][-1], g, head, cfg.rms_eps, want_margin=True)
             cur[b] = int(toks[b, i])
-    return toks, zmax, lse, k, v
+    return (toks, zmax, lse, k, v, margin) if want_margin else (toks, zmax, lse, k, v)
 
 
 # --------------------------------------------------------------------------- #

@@ -61,6 +61,10 @@ class CascadeOut(C.Structure):
                 ("conf_used", C.c_void_p)]
 
 
+class HeadOut(C.Structure):
+    _fields_ = [("token", C.c_void_p), ("max_logit", C.c_void_p), ("lse", C.c_void_p), ("conf_full", C.c_void_p)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -109,6 +113,11 @@ def _load() -> C.CDLL:
     lib.confspec_verify_append.restype = C.c_int
     lib.confspec_verify_append.argtypes = [vp, P(Weights), P(KV), P(Batch), vp, P(i32), P(i32), i32, P(C.c_float), i32,
                                            vp, sz, vp, vp, vp, vp, vp]
+    lib.confspec_head_scratch_bytes.restype = sz
+    lib.confspec_head_scratch_bytes.argtypes = [vp, i32]
+    lib.confspec_generate_step.restype = C.c_int
+    lib.confspec_generate_step.argtypes = [vp, P(Weights), P(KV), P(Batch), vp, P(i32), P(i32), i32, vp, sz, vp, sz,
+                                           P(HeadOut), vp]
     lib.confspec_cascade_scratch_bytes.restype = sz
     lib.confspec_cascade_scratch_bytes.argtypes = [i32, i32, i32]
     lib.confspec_cascade.restype = C.c_int
@@ -125,7 +134,7 @@ EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec
             "confspec_workspace_bytes", "confspec_packed_bytes", "confspec_pack_weights", "confspec_verify",
             "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_qkv_rope", "confspec_op_attention",
             "confspec_op_verdict_gate", "confspec_op_copy", "confspec_tune", "confspec_cascade_scratch_bytes",
-            "confspec_cascade", "confspec_verify_append"]
+            "confspec_cascade", "confspec_verify_append", "confspec_head_scratch_bytes", "confspec_generate_step"]
 
 
 class ConfSpecError(RuntimeError):
@@ -217,6 +226,23 @@ def confspec_verify_append(ctx, w: Weights, kv: KV, batch: Batch, n_append, h_n_
     _check(ctx, lib.confspec_verify_append(ctx, C.byref(w), C.byref(kv), C.byref(batch), _ptr(n_append), hp, ids, nv,
                                            tau, nt, _ptr(workspace), _nbytes(workspace), _ptr(logits), _ptr(conf),
                                            _ptr(verdict), _ptr(accept), _stream_handle(stream)))
+
+
+def confspec_head_scratch_bytes(ctx, max_B: int) -> int:
+    return int(lib.confspec_head_scratch_bytes(ctx, max_B))
+
+
+def confspec_generate_step(ctx, w: Weights, kv: KV, batch: Batch, n_append, h_n_append, verdict_ids, workspace,
+                           head_scratch, out: HeadOut, stream=None) -> None:
+    """n_append / h_n_append: device tensor and host int32 array, or both None; verdict_ids: sequence or None."""
+    import numpy as np
+    nv = 0 if verdict_ids is None else len(verdict_ids)
+    ids = None if verdict_ids is None else (C.c_int32 * max(nv, 1))(*[int(v) for v in verdict_ids])
+    hn = None if h_n_append is None else np.ascontiguousarray(h_n_append, dtype=np.int32)
+    hp = None if hn is None else hn.ctypes.data_as(C.POINTER(C.c_int32))
+    _check(ctx, lib.confspec_generate_step(ctx, C.byref(w), C.byref(kv), C.byref(batch), _ptr(n_append), hp, ids, nv,
+                                           _ptr(workspace), _nbytes(workspace), _ptr(head_scratch), _nbytes(head_scratch),
+                                           C.byref(out), _stream_handle(stream)))
 
 
 def confspec_op_gemm(ctx, A, W, out, M: int, N: int, K: int, epilogue: int, a_terms: int = 1, out_terms: int = 1,

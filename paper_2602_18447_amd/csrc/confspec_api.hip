@@ -14,6 +14,7 @@
 #include "../../include/confspec_ops.h"
 #include "../../include/confspec_cascade.h"
 #include "../../include/confspec_append.h"
+#include "../../include/confspec_generate.h"
 #include "kernels.h"
 
 namespace cs {
@@ -138,6 +139,33 @@ WsLayout ws_layout(const confspec_model_cfg &c, int64_t T, int64_t B) {
     w.total = at;
     return w;
 }
+
+// Scratch of the full-vocabulary head for B rows: the last rows of the residual stream, their normalised form (two
+// bf16 terms for a bf16 model), the logits [B, vocab], and the verdict outputs the full-vocabulary confidence needs.
+struct HeadLayout {
+    size_t x, y, logits, v_logits, v_conf, v_verdict, v_accept, total;
+};
+HeadLayout head_layout(const confspec_model_cfg &c, int64_t B) {
+    HeadLayout h;
+    size_t at = 0;
+    auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes); return o; };
+    h.x = take((size_t)B * c.d_model * 4);
+    h.y = take((size_t)B * c.d_model * 4);           // fp32 rows, or hi | lo bf16 rows: the same size
+    h.logits = take((size_t)B * c.vocab * 4);
+    h.v_logits = take((size_t)B * CONFSPEC_MAX_VERDICT * 4);
+    h.v_conf = take((size_t)B * 4);
+    h.v_verdict = take((size_t)B * 4);
+    h.v_accept = take((size_t)B);
+    h.total = at;
+    return h;
+}
+// What a call wants beyond the verdict outputs.
+struct PassExtras {
+    const int32_t *dev_n_append = nullptr, *h_n_append = nullptr;   // write-back of suffix keys / values
+    const confspec_head_out *head = nullptr;                        // full-vocabulary head at the last positions
+    void *head_scratch = nullptr;
+    size_t head_scratch_bytes = 0;
+};
 
 int check_batch(const confspec_ctx *ctx, const confspec_batch *b, int64_t max_prefix, int *max_L_out) {
     if (!b) return fail(ctx, CONFSPEC_E_INVALID_ARG, "batch is null");
@@ -426,11 +454,13 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
                        const confspec_batch *batch, const int32_t *h_verdict_ids, int32_t n_verdict,
                        const float *h_tau, int32_t n_tau, void *dev_workspace, size_t workspace_bytes,
                        float *dev_verdict_logits, float *dev_conf, int32_t *dev_verdict, uint8_t *dev_accept,
-                       const int32_t *dev_n_append, const int32_t *h_n_append, confspec_stream stream) {
+                       const PassExtras &ex, confspec_stream stream) {
     if (!ctx) return CONFSPEC_E_INVALID_ARG;
     const confspec_model_cfg &c = ctx->cfg;
+    const int32_t *dev_n_append = ex.dev_n_append, *h_n_append = ex.h_n_append;
+    const bool want_verdict = h_verdict_ids != nullptr;     // a generation step may come without verdict tokens
     if (!w) return fail(ctx, CONFSPEC_E_INVALID_ARG, "weights is null");
-    if (!dev_verdict_logits || !dev_conf || !dev_verdict || !dev_accept)
+    if (!ex.head && (!dev_verdict_logits || !dev_conf || !dev_verdict || !dev_accept))
         return fail(ctx, CONFSPEC_E_INVALID_ARG, "an output pointer is null");
     if (w->packed != 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "weights must be packed with confspec_pack_weights");
     if (!w->embed || !w->lm_head || !w->final_norm) return fail(ctx, CONFSPEC_E_INVALID_ARG, "embed, lm_head or final_norm is null");
@@ -445,10 +475,21 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     int64_t max_prefix = (int64_t)kv->max_blocks_per_seq * kv->block_size;
     if ((rc = check_batch(ctx, batch, max_prefix, &max_L)) != CONFSPEC_OK) return rc;
     if ((rc = check_kv(ctx, kv, max_L > 0)) != CONFSPEC_OK) return rc;
-    cs::VerdictArgs va;
-    if ((rc = check_verdict(ctx, h_verdict_ids, n_verdict, h_tau, n_tau, &va)) != CONFSPEC_OK) return rc;
+    cs::VerdictArgs va = {};
+    if (want_verdict && (rc = check_verdict(ctx, h_verdict_ids, n_verdict, h_tau, n_tau, &va)) != CONFSPEC_OK) return rc;
     WsLayout L = ws_layout(c, batch->T, batch->B);
     if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
+    HeadLayout HL = {};
+    if (ex.head) {
+        if (!ex.head->token || !ex.head->max_logit || !ex.head->lse) return fail(ctx, CONFSPEC_E_INVALID_ARG, "a head output pointer is null");
+        if (ex.head->conf_full && !want_verdict)
+            return fail(ctx, CONFSPEC_E_INVALID_ARG, "conf_full needs verdict ids");
+        if (c.dtype == CONFSPEC_DTYPE_BF16 ? (c.vocab % 128 != 0) : (c.vocab % 64 != 0))
+            return fail(ctx, CONFSPEC_E_UNSUPPORTED, "the full-vocabulary head needs vocab %% %d == 0 (got %d)",
+                        c.dtype == CONFSPEC_DTYPE_BF16 ? 128 : 64, c.vocab);
+        HL = head_layout(c, batch->B);
+        if ((rc = check_ws(ctx, ex.head_scratch, ex.head_scratch_bytes, HL.total)) != CONFSPEC_OK) return rc;
+    }
     if (dev_n_append) {
         if (!h_n_append) return fail(ctx, CONFSPEC_E_INVALID_ARG, "h_n_append is null");
         if (!kv->k_pages || !kv->v_pages) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv pages are null");
@@ -543,12 +584,39 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         if ((rc = run_gemm(ctx, hr, wgu, act, rows, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s, sk, skb))) return rc;
         if ((rc = run_gemm(ctx, act, wdn, xr, rows, d, c.d_ffn, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
     }
-    if (prune)
-        HIP_TRY(cs::launch_verdict(c.dtype, (const float *)(ws + L.x_last), nullptr, w->final_norm, w->lm_head, va, B, B, d,
-                                   c.rms_eps, dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
-    else
-        HIP_TRY(cs::launch_verdict(c.dtype, x, last_row, w->final_norm, w->lm_head, va, B, T, d, c.rms_eps,
-                                   dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
+    if (ex.head) {   // verdict outputs, if any, go to the head's scratch
+        char *hs = (char *)ex.head_scratch;
+        dev_verdict_logits = (float *)(hs + HL.v_logits);
+        dev_conf = (float *)(hs + HL.v_conf);
+        dev_verdict = (int32_t *)(hs + HL.v_verdict);
+        dev_accept = (uint8_t *)(hs + HL.v_accept);
+    }
+    if (want_verdict) {
+        if (prune)
+            HIP_TRY(cs::launch_verdict(c.dtype, (const float *)(ws + L.x_last), nullptr, w->final_norm, w->lm_head, va, B, B, d,
+                                       c.rms_eps, dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
+        else
+            HIP_TRY(cs::launch_verdict(c.dtype, x, last_row, w->final_norm, w->lm_head, va, B, T, d, c.rms_eps,
+                                       dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
+    }
+    if (ex.head) {
+        // Logits of the whole vocabulary at the last position of every trace: final norm of those B rows (two bf16
+        // terms, so the operand carries ~16 mantissa bits), one GEMM against the head, then arg max / log-sum-exp.
+        char *hs = (char *)ex.head_scratch;
+        const float *xl = (const float *)(ws + L.x_last);
+        if (!prune) {
+            HIP_TRY(cs::launch_gather_rows(x, hs + HL.x, last_row, B, T, (size_t)d * 4, s));
+            xl = (const float *)(hs + HL.x);
+        }
+        const bool bf = c.dtype == CONFSPEC_DTYPE_BF16;
+        HIP_TRY(cs::launch_rmsnorm(c.dtype, xl, w->final_norm, hs + HL.y, B, d, c.rms_eps, bf ? 2 : 1, s));
+        if ((rc = run_gemm(ctx, hs + HL.y, w->lm_head, hs + HL.logits, B, c.vocab, d, cs::EPI_STORE_F32, bf ? 2 : 1, 1, s,
+                           bf ? (float *)(ws + L.splitk) : nullptr, bf ? L.splitk_bytes : 0)))
+            return rc;
+        HIP_TRY(cs::launch_head_reduce((const float *)(hs + HL.logits), B, c.vocab, want_verdict ? dev_verdict_logits : nullptr,
+                                       va.n_verdict, ex.head->token, ex.head->max_logit, ex.head->lse,
+                                       want_verdict ? ex.head->conf_full : nullptr, s));
+    }
     return CONFSPEC_OK;
 }
 
@@ -557,8 +625,9 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
                     const float *h_tau, int32_t n_tau, void *dev_workspace, size_t workspace_bytes,
                     float *dev_verdict_logits, float *dev_conf, int32_t *dev_verdict, uint8_t *dev_accept,
                     confspec_stream stream) {
+    if (ctx && !h_verdict_ids) return fail(ctx, CONFSPEC_E_INVALID_ARG, "verdict ids or tau pointer is null");
     return verify_impl(ctx, w, kv, batch, h_verdict_ids, n_verdict, h_tau, n_tau, dev_workspace, workspace_bytes,
-                       dev_verdict_logits, dev_conf, dev_verdict, dev_accept, nullptr, nullptr, stream);
+                       dev_verdict_logits, dev_conf, dev_verdict, dev_accept, PassExtras{}, stream);
 }
 
 int confspec_verify_append(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
@@ -568,8 +637,37 @@ int confspec_verify_append(confspec_ctx *ctx, const confspec_weights *w, const c
                            int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream) {
     if (!ctx) return CONFSPEC_E_INVALID_ARG;
     if (!dev_n_append || !h_n_append) return fail(ctx, CONFSPEC_E_INVALID_ARG, "n_append is null");
+    if (!h_verdict_ids) return fail(ctx, CONFSPEC_E_INVALID_ARG, "verdict ids or tau pointer is null");
+    PassExtras ex;
+    ex.dev_n_append = dev_n_append;
+    ex.h_n_append = h_n_append;
     return verify_impl(ctx, w, kv, batch, h_verdict_ids, n_verdict, h_tau, n_tau, dev_workspace, workspace_bytes,
-                       dev_verdict_logits, dev_conf, dev_verdict, dev_accept, dev_n_append, h_n_append, stream);
+                       dev_verdict_logits, dev_conf, dev_verdict, dev_accept, ex, stream);
+}
+
+size_t confspec_head_scratch_bytes(const confspec_ctx *ctx, int32_t max_B) {
+    if (!ctx || max_B < 1) return 0;
+    return head_layout(ctx->cfg, max_B).total;
+}
+
+int confspec_generate_step(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
+                           const confspec_batch *batch, const int32_t *dev_n_append, const int32_t *h_n_append,
+                           const int32_t *h_verdict_ids, int32_t n_verdict, void *dev_workspace, size_t workspace_bytes,
+                           void *dev_head_scratch, size_t head_scratch_bytes, const confspec_head_out *out,
+                           confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!out) return fail(ctx, CONFSPEC_E_INVALID_ARG, "out is null");
+    if ((dev_n_append == nullptr) != (h_n_append == nullptr))
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "dev_n_append and h_n_append must both be given or both be null");
+    PassExtras ex;
+    ex.dev_n_append = dev_n_append;
+    ex.h_n_append = h_n_append;
+    ex.head = out;
+    ex.head_scratch = dev_head_scratch;
+    ex.head_scratch_bytes = head_scratch_bytes;
+    const float tau = 0.5f;   // the gate bit is not an output of this call
+    return verify_impl(ctx, w, kv, batch, h_verdict_ids, n_verdict, &tau, 1, dev_workspace, workspace_bytes, nullptr, nullptr,
+                       nullptr, nullptr, ex, stream);
 }
 
 // ---- single-step entry points ------------------------------------------------------------------

@@ -95,6 +95,10 @@ hipError_t launch_verdict(int dtype, const float *x, const int32_t *last_row, co
                           const void *lm_head, VerdictArgs va, int B, int T, int d, float eps, float *logits,
                           float *conf, int32_t *verdict, uint8_t *accept, hipStream_t s);
 
+// Arg max / max / log-sum-exp of every row of logits [B, V]; conf_full (may be null) from verdict_logits [B, n_verdict].
+hipError_t launch_head_reduce(const float *logits, int B, int V, const float *verdict_logits, int n_verdict, int32_t *token,
+                              float *max_logit, float *lse, float *conf_full, hipStream_t s);
+
 // ---- GEMM: C[M,N] = A[M,K] . W[N,K]^T with an epilogue ----
 //  EPI_STORE_F32: out fp32 [M,N]
 //  EPI_RESID_F32: out fp32 [M,N] += result (in place)

@@ -429,6 +429,57 @@ __global__ void verdict_kernel(const float *__restrict__ x, const int32_t *__res
     }
 }
 
+// Full-vocabulary statistics of one row of logits: arg max (lowest index on ties), its logit, and
+// lse = log sum_v exp z_v.  With verdict logits (fp32, n_verdict per row) also the largest full-vocabulary
+// probability among the verdict tokens, exp(max_v z_v - lse).  One workgroup per row.
+__global__ __launch_bounds__(256) void head_reduce_kernel(const float *__restrict__ logits, int V, const float *__restrict__ verdict_logits,
+                                                           int n_verdict, int32_t *__restrict__ token, float *__restrict__ max_logit,
+                                                           float *__restrict__ lse, float *__restrict__ conf_full) {
+    __shared__ float s_m[4], s_s[4];
+    __shared__ int s_i[4];
+    int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float *z = logits + (size_t)b * V;
+    float m = -INFINITY;
+    int idx = 0x7fffffff;
+    for (int j = threadIdx.x; j < V; j += 256) {
+        float v = z[j];
+        if (v > m) { m = v; idx = j; }            // j grows per thread, so a thread keeps its lowest index
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        float om = __shfl_xor(m, off);
+        int oi = __shfl_xor(idx, off);
+        if (om > m || (om == m && oi < idx)) { m = om; idx = oi; }
+    }
+    if (lane == 0) { s_m[wave] = m; s_i[wave] = idx; }
+    __syncthreads();
+    m = s_m[0]; idx = s_i[0];
+    for (int w = 1; w < 4; ++w)
+        if (s_m[w] > m || (s_m[w] == m && s_i[w] < idx)) { m = s_m[w]; idx = s_i[w]; }
+    float sum = 0.f;
+    for (int j = threadIdx.x; j < V; j += 256) sum += __expf(z[j] - m);
+    sum = wave_sum(sum);
+    if (lane == 0) s_s[wave] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float l = m + logf(s_s[0] + s_s[1] + s_s[2] + s_s[3]);
+        token[b] = idx;
+        max_logit[b] = m;
+        lse[b] = l;
+        if (conf_full && verdict_logits) {
+            float zv = verdict_logits[(size_t)b * n_verdict];
+            for (int v = 1; v < n_verdict; ++v) zv = fmaxf(zv, verdict_logits[(size_t)b * n_verdict + v]);
+            conf_full[b] = expf(zv - l);
+        }
+    }
+}
+
+hipError_t launch_head_reduce(const float *logits, int B, int V, const float *verdict_logits, int n_verdict, int32_t *token,
+                              float *max_logit, float *lse, float *conf_full, hipStream_t s) {
+    head_reduce_kernel<<<B, 256, 0, s>>>(logits, V, verdict_logits, n_verdict, token, max_logit, lse, conf_full);
+    return hipGetLastError();
+}
+
 hipError_t launch_verdict(int dtype, const float *x, const int32_t *last_row, const void *final_norm,
                           const void *lm_head, VerdictArgs va, int B, int T, int d, float eps, float *logits,
                           float *conf, int32_t *verdict, uint8_t *accept, hipStream_t s) {

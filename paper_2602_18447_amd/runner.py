@@ -90,6 +90,54 @@ class Verifier:
         cb.confspec_verify_append(self.ctx, self.w, kvs, bs, dn, hn, verdict_ids, taus, ws, *outs, stream=stream)
         return outs
 
+    def head_scratch(self, B: int) -> torch.Tensor:
+        need = cb.confspec_head_scratch_bytes(self.ctx, B)
+        if getattr(self, "_head", None) is None or self._head.numel() < need:
+            self._head = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._head
+
+    def generate_step(self, kv, batch, n_append=None, verdict_ids=None, outputs=None, stream=None):
+        """The pass plus the full-vocabulary head at the last position: returns dict(token, max_logit, lse[, conf_full])
+        of device tensors.  n_append: host integers per trace for write-back of the new tokens' keys / values."""
+        kvs, bs, keep = self.bind(kv, batch)
+        dev = self.device
+        outs = outputs or dict(token=torch.empty(bs.B, dtype=torch.int32, device=dev),
+                               max_logit=torch.empty(bs.B, dtype=torch.float32, device=dev),
+                               lse=torch.empty(bs.B, dtype=torch.float32, device=dev))
+        if verdict_ids is not None and "conf_full" not in outs:
+            outs["conf_full"] = torch.empty(bs.B, dtype=torch.float32, device=dev)
+        hn = None if n_append is None else np.ascontiguousarray(n_append, dtype=np.int32)
+        dn = None if hn is None else torch.from_numpy(hn).to(dev)
+        ho = cb.HeadOut(outs["token"].data_ptr(), outs["max_logit"].data_ptr(), outs["lse"].data_ptr(),
+                        outs["conf_full"].data_ptr() if verdict_ids is not None else None)
+        cb.confspec_generate_step(self.ctx, self.w, kvs, bs, dn, hn, verdict_ids, self.workspace(bs.T, bs.B),
+                                  self.head_scratch(bs.B), ho, stream=stream)
+        return outs
+
+    def generate_greedy(self, kv, block_table, n_blocks: int, max_blocks_per_seq: int, first_ids, prefix_lens, n_steps: int):
+        """n_steps greedy tokens per trace on a growing cache, one token per trace and step; nothing here waits for the
+        GPU.  first_ids: device int32 [B], the token at position L_b (not cached yet); prefix_lens: host integers.
+        The block table must cover L_b + n_steps rows.  Returns (tokens [n_steps, B], max_logit, lse) device tensors."""
+        from types import SimpleNamespace
+        dev = self.device
+        B = len(prefix_lens)
+        L0 = np.ascontiguousarray(prefix_lens, dtype=np.int32)
+        toks = torch.empty(n_steps, B, dtype=torch.int32, device=dev)
+        zmax = torch.empty(n_steps, B, dtype=torch.float32, device=dev)
+        lse = torch.empty(n_steps, B, dtype=torch.float32, device=dev)
+        cu = np.arange(B + 1, dtype=np.int32)
+        cu_dev = torch.from_numpy(cu).to(dev)
+        ones = np.ones(B, dtype=np.int32)
+        cur = first_ids
+        for i in range(n_steps):
+            hl = L0 + i
+            batch = SimpleNamespace(suffix_ids=cur, cu_suffix=cu_dev, prefix_lens=torch.from_numpy(hl).to(dev),
+                                    block_table=block_table, n_blocks=n_blocks, max_blocks_per_seq=max_blocks_per_seq,
+                                    block_size=kv.block_size, h_cu_suffix=cu, h_prefix_lens=hl)
+            self.generate_step(kv, batch, n_append=ones, outputs=dict(token=toks[i], max_logit=zmax[i], lse=lse[i]))
+            cur = toks[i]
+        return toks, zmax, lse
+
 
 class Cascade:
     """The two-tier cascade over the drafted steps of a batch of requests: a small and a large Verifier that read
