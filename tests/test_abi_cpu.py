@@ -63,6 +63,14 @@ def test_workspace_size_is_monotone_and_aligned():
     cb.confspec_destroy(ctx)
 
 
+def _no_gpu_here():
+    """The calls below hand made-up addresses to the library and rely on validation stopping them before any launch;
+    a mistake in such a test must never reach a real GPU, so they only run where there is none."""
+    import torch
+    if torch.cuda.device_count() > 0:
+        pytest.skip("fake-pointer validation tests run on machines without a GPU only")
+
+
 class _FakeDev:
     """Stands in for a device tensor: a fixed fake address, never dereferenced because every call in
     this file must fail validation before the first launch."""
@@ -99,6 +107,7 @@ def _expect(ctx, code, fn):
 
 
 def test_verify_validates_before_any_launch():
+    _no_gpu_here()
     cfg = _cfg()
     ctx = cb.confspec_create(cfg)
     fake, w, kv, batch, keep = _verify_args(cfg)
@@ -142,6 +151,7 @@ def test_verify_validates_before_any_launch():
 
 
 def test_op_gemm_and_tune_validation():
+    _no_gpu_here()
     ctx = cb.confspec_create(_cfg())
     fake = _FakeDev()
     _expect(ctx, cb.E_UNSUPPORTED, lambda: cb.confspec_op_gemm(ctx, fake, fake, fake, 8, 100, 64, 0, stream=0))
@@ -162,6 +172,7 @@ def test_op_gemm_and_tune_validation():
 
 
 def test_cascade_validates_before_any_launch():
+    _no_gpu_here()
     cfg_d, cfg_t = _cfg(), _cfg(n_layers=3, d_model=512, n_q_heads=4, d_ffn=1024)
     ctx_d, ctx_t = cb.confspec_create(cfg_d), cb.confspec_create(cfg_t)
     fake, w, kv, batch, keep = _verify_args(cfg_d, B=3, S=(3, 2, 4), L=(5, 0, 7))
@@ -194,3 +205,41 @@ def test_cascade_validates_before_any_launch():
     _expect(ctx_d, cb.E_OUT_OF_RANGE, lambda: call(ctx_t=ctx_v))
     for c in (ctx_d, ctx_t, ctx_v):
         cb.confspec_destroy(c)
+
+
+def test_append_and_generate_validate_before_any_launch():
+    _no_gpu_here()
+    cfg = _cfg()
+    ctx = cb.confspec_create(cfg)
+    fake, w, kv, batch, keep = _verify_args(cfg, B=2, S=(3, 2), L=(5, 0))
+    out = (fake, fake, fake, fake)
+
+    def append(n, dev=fake):
+        return cb.confspec_verify_append(ctx, w, kv, batch, dev, None if n is None else np.asarray(n, dtype=np.int32),
+                                         [1, 2], [0.9], fake, *out, stream=0)
+
+    _expect(ctx, cb.E_INVALID_ARG, lambda: append(None))
+    _expect(ctx, cb.E_INVALID_ARG, lambda: append([1, 1], dev=None))
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: append([4, 0]))              # more than the suffix holds
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: append([0, -1]))
+    kv_small = cb.make_kv(fake, fake, fake, 8, 16, 1)                    # 16 rows per trace at most
+    batch_full, keep_full = cb.make_batch(fake, fake, fake, np.array([0, 3, 5], dtype=np.int32), np.array([14, 0], dtype=np.int32))
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: cb.confspec_verify_append(
+        ctx, w, kv_small, batch_full, fake, np.array([3, 0], dtype=np.int32), [1, 2], [0.9], fake, *out, stream=0))
+
+    head = cb.HeadOut(fake.data_ptr(), fake.data_ptr(), fake.data_ptr(), None)
+    assert cb.confspec_head_scratch_bytes(ctx, 2) % 256 == 0 and cb.confspec_head_scratch_bytes(ctx, 0) == 0
+    assert cb.confspec_head_scratch_bytes(ctx, 4) > cb.confspec_head_scratch_bytes(ctx, 2) >= 2 * 1000 * 4
+
+    def gen(head=head, scratch=fake, vids=None, n=None, dev_n=None, ctx=ctx):
+        return cb.confspec_generate_step(ctx, w, kv, batch, dev_n, n, vids, fake, scratch, head, stream=0)
+
+    _expect(ctx, cb.E_UNSUPPORTED, gen)                                  # vocab 1000 is not a multiple of 128
+    ctx2 = cb.confspec_create(_cfg(vocab=1024))
+    _expect(ctx2, cb.E_WORKSPACE, lambda: gen(scratch=_FakeDev(nbytes=1024), ctx=ctx2))
+    _expect(ctx2, cb.E_INVALID_ARG, lambda: gen(head=cb.HeadOut(), ctx=ctx2))
+    _expect(ctx2, cb.E_INVALID_ARG, lambda: gen(head=cb.HeadOut(*([fake.data_ptr()] * 4)), ctx=ctx2))   # conf_full without verdict ids
+    _expect(ctx2, cb.E_INVALID_ARG, lambda: gen(n=np.array([1, 1], dtype=np.int32), ctx=ctx2))          # host counts without device counts
+    _expect(ctx2, cb.E_OUT_OF_RANGE, lambda: gen(vids=[1, 5000], ctx=ctx2))
+    cb.confspec_destroy(ctx)
+    cb.confspec_destroy(ctx2)
