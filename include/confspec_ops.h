@@ -102,7 +102,8 @@ int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_
  * in the last layer, compute attention rows, output projection and MLP for the last position of each trace only
  * (the only rows the verdict head reads; 0 computes every row).  Launch-shape tunables for
  * measurements: "gemm_tile" (0 heuristic, 1..6 = fixed workgroup tile / pipeline shape of the bf16 GEMM),
- * "gemm_group_m" (0 heuristic, else tile rows per band of the GEMM's tile order),
+ * "gemm_group_m" (0 heuristic, else tile rows per band of the GEMM's tile order), "gemm_splitk" (0 heuristic,
+ * 1..64 = split-K factor of every bf16 GEMM that is given scratch; 1 = never split),
  * "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
  * "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = equal key-range pieces with that split factor,
  * 5 = front-loaded pieces).  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a

@@ -20,6 +20,7 @@
 namespace cs {
 void gemm_set_tile(int t);
 void gemm_set_group_m(int g);
+void gemm_set_splitk(int s);
 void attn_set_tune(int target_items, int min_chunks);
 void attn_get_tune(int *target_items, int *min_chunks);
 void attn_set_split(int s);
@@ -844,6 +845,9 @@ int confspec_tune(const char *key, int32_t value) {
     } else if (!strcmp(key, "gemm_group_m")) {
         if (value < 0 || value > 65536) return CONFSPEC_E_INVALID_ARG;
         cs::gemm_set_group_m(value);
+    } else if (!strcmp(key, "gemm_splitk")) {
+        if (value < 0 || value > 64) return CONFSPEC_E_INVALID_ARG;
+        cs::gemm_set_splitk(value);
     } else if (!strcmp(key, "split_layers")) {
         if (value < -1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
         g_split_layers = value;

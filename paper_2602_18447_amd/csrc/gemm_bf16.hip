@@ -43,8 +43,10 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 struct GemmTune {
     int tile;      // 0 = heuristic; see launch_epi for the ids
     int group_m;   // 0 = heuristic; otherwise tile rows per band of the tile order
+    int splitk;    // 0 = heuristic; otherwise the split-K factor of every GEMM that has scratch (1 = never split)
 };
-static GemmTune g_gemm_tune = {0, 0};
+static GemmTune g_gemm_tune = {0, 0, 0};
+void gemm_set_splitk(int s) { g_gemm_tune.splitk = s; }
 void gemm_set_tile(int t) { g_gemm_tune.tile = t; }
 void gemm_set_group_m(int g) { g_gemm_tune.group_m = g; }
 
@@ -457,6 +459,7 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
 int gemm_splitk_factor(int M, int N, int K_total) {
     if (N % 128 != 0) return 1;
     int tiles = ((M + 127) / 128) * (N / 128), nk = K_total / 64;
+    if (g_gemm_tune.splitk > 0) return std::max(1, std::min(g_gemm_tune.splitk, nk / 4));
     if (M > 128 && tiles >= 256) return 1;               // enough 128 x 128 tiles to fill the chip without a split
     int want = (384 + tiles / 2) / tiles;                // about 384 workgroups
     int s = std::min(want, nk / 4);                      // at least 4 k-tiles per slice

@@ -163,6 +163,9 @@ def test_op_gemm_and_tune_validation():
     cb.confspec_tune("gemm_tile", 0)
     with pytest.raises(cb.ConfSpecError):
         cb.confspec_tune("gemm_tile", 99)
+    cb.confspec_tune("gemm_splitk", 0)
+    with pytest.raises(cb.ConfSpecError):
+        cb.confspec_tune("gemm_splitk", 65)
     for src, dst, n in [(None, fake, 64), (fake, None, 64), (fake, fake, 0), (fake, fake, 24),
                         (_FakeDev(0x10008), fake, 64)]:
         with pytest.raises(cb.ConfSpecError) as ei:
