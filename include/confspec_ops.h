@@ -34,9 +34,9 @@ extern "C" {
  * arrays of the context's dtype (row-major, K contiguous).  Requires N % 128 == 0 and K % 64 == 0 for
  * bf16, N % 64 == 0 and K % 16 == 0 for fp32; any M >= 1.  out_terms != 1 is valid with the SwiGLU
  * epilogue only (2: out is [M, 2 * N/2]; 3: out holds half values).  dev_scratch (may be NULL) is dev memory the call may use for
- * partial products: with at least confspec_op_gemm_scratch_bytes() bytes a bf16 GEMM with M <= 128 cuts
- * the k range into slices that run as separate workgroups and are added in a fixed order; without it
- * such a GEMM runs one workgroup per 128 output columns.  16-byte aligned. */
+ * partial products: with at least confspec_op_gemm_scratch_bytes() bytes a bf16 GEMM whose output has too few
+ * 128 x 128 tiles to fill the chip cuts the k range into slices that run as separate workgroups and are added in
+ * a fixed order; without it such a GEMM runs one workgroup per tile.  16-byte aligned. */
 int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, void *dev_out, int32_t M,
                      int32_t N, int32_t K, int32_t epilogue, int32_t a_terms, int32_t out_terms,
                      void *dev_scratch, size_t scratch_bytes, confspec_stream stream);
@@ -98,10 +98,14 @@ int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_
  * the GEMM activations as two bf16 terms (default -1 = ceil(n_layers / 7), doubled when d_model > 4096).  "attn_precise_layers"
  * (default 1): number of leading layers whose attention runs the two-term variant.  "first_layers_f16" (default 1; read by
  * confspec_pack_weights, which then makes the half copies, and by confspec_verify).  "fuse_rope" (default 1): confspec_verify runs the QKV projection of a bf16 model with the rotary
- * embedding in its epilogue (0: projection to fp32, then a separate kernel).  "prune_last_layer" (default 1):
+ * embedding in its epilogue (0: projection to fp32, then a separate kernel).  "prefetch_down" (default 1): while the
+ * gate/up projection of a bf16 layer runs, its workgroups also read the down projection's weights once, front to
+ * back, so that they sit in the last-level cache when the down projection's strided tile loads ask for them (a hint:
+ * results are bit-identical with 0).  "prune_last_layer" (default 1):
  * in the last layer, compute attention rows, output projection and MLP for the last position of each trace only
  * (the only rows the verdict head reads; 0 computes every row).  Launch-shape tunables for
- * measurements: "gemm_tile" (0 heuristic, 1..6 = fixed workgroup tile / pipeline shape of the bf16 GEMM),
+ * measurements: "gemm_tile" (0 heuristic, 1..7 = fixed workgroup tile / pipeline shape of the bf16 GEMM; a shape
+ * that does not divide N falls back to 128x128),
  * "gemm_group_m" (0 heuristic, else tile rows per band of the GEMM's tile order), "gemm_splitk" (0 heuristic,
  * 1..64 = split-K factor of every bf16 GEMM that is given scratch; 1 = never split),
  * "attn_target_items" (concurrent workgroup slots assumed by the attention planner),

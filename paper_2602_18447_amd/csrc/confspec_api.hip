@@ -45,6 +45,8 @@ static int g_prune_last_layer = 1;
 static int g_first_layers_f16 = 1;
 // 1: bf16 models run the QKV projection with the rotary embedding in its epilogue (reordered weight rows)
 static int g_fuse_rope = 1;
+// The gate/up projection warms the last-level cache with the down projection's weights (process-wide switch).
+static int g_prefetch_down = 1;
 
 static int split_layers_for(const confspec_model_cfg &c) {
     if (g_split_layers >= 0) return g_split_layers;
@@ -241,12 +243,13 @@ int check_ws(const confspec_ctx *ctx, const void *ws, size_t have, size_t need) 
     } while (0)
 
 int run_gemm(confspec_ctx *ctx, const void *A, const void *W, void *out, int M, int N, int K, int epi,
-             int a_terms, int out_terms, hipStream_t s, float *splitk_ws = nullptr, size_t splitk_bytes = 0) {
+             int a_terms, int out_terms, hipStream_t s, float *splitk_ws = nullptr, size_t splitk_bytes = 0,
+             const cs::PrefetchArgs *pf = nullptr) {
     if (ctx->cfg.dtype == CONFSPEC_DTYPE_FP32) {
         HIP_TRY(cs::launch_gemm_f32((const float *)A, (const float *)W, out, M, N, K, epi, s));
     } else {
         HIP_TRY(cs::launch_gemm_bf16((const cs::bf16 *)A, (const cs::bf16 *)W, out, M, N, K, epi, a_terms, out_terms,
-                                     splitk_ws, splitk_bytes, s));
+                                     splitk_ws, splitk_bytes, s, pf));
     }
     return CONFSPEC_OK;
 }
@@ -582,7 +585,12 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         }
         if ((rc = run_gemm(ctx, attn, wo, xr, rows, d, qw, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
         HIP_TRY(cs::launch_rmsnorm(c.dtype, xr, w->mlp_norm[l], hr, rows, d, c.rms_eps, tm, s));
-        if ((rc = run_gemm(ctx, hr, wgu, act, rows, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s, sk, skb))) return rc;
+        // the gate/up projection is compute-bound: while it runs it also pulls the down projection's weights, which
+        // that kernel reads in strided pieces, into the last-level cache
+        cs::PrefetchArgs pf;
+        pf.ptr = g_prefetch_down ? wdn : nullptr;
+        pf.n16 = g_prefetch_down ? (unsigned)((size_t)d * c.d_ffn * eb / 16) : 0u;
+        if ((rc = run_gemm(ctx, hr, wgu, act, rows, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s, sk, skb, &pf))) return rc;
         if ((rc = run_gemm(ctx, act, wdn, xr, rows, d, c.d_ffn, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
     }
     if (ex.head) {   // verdict outputs, if any, go to the head's scratch
@@ -840,7 +848,7 @@ int confspec_tune(const char *key, int32_t value) {
     int ti, mc;
     cs::attn_get_tune(&ti, &mc);
     if (!strcmp(key, "gemm_tile")) {
-        if (value < 0 || value > 6) return CONFSPEC_E_INVALID_ARG;
+        if (value < 0 || value > 7) return CONFSPEC_E_INVALID_ARG;
         cs::gemm_set_tile(value);
     } else if (!strcmp(key, "gemm_group_m")) {
         if (value < 0 || value > 65536) return CONFSPEC_E_INVALID_ARG;
@@ -851,6 +859,9 @@ int confspec_tune(const char *key, int32_t value) {
     } else if (!strcmp(key, "split_layers")) {
         if (value < -1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
         g_split_layers = value;
+    } else if (!strcmp(key, "prefetch_down")) {
+        if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
+        g_prefetch_down = value;
     } else if (!strcmp(key, "fuse_rope")) {
         if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
         g_fuse_rope = value;

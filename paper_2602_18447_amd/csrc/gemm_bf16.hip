@@ -67,7 +67,8 @@ __device__ inline f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_FMT>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W,
                                                          void *out_v, int M, int N, int K,
-                                                         int tiles_m, int tiles_n, int n_base, int group_m, int out_fmt, RopeArgs rope) {
+                                                         int tiles_m, int tiles_n, int n_base, int group_m, int out_fmt, RopeArgs rope,
+                                                         PrefetchArgs pf) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int A_TERMS = A_FMT == 2 ? 2 : 1;
     constexpr bool F16 = A_FMT == 3;
@@ -217,6 +218,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     // instruction in about 16 cycles whatever its width.  Each wavefront therefore transposes one 32-row
     // block at a time through a private piece of LDS (the operand stages are dead by now) and moves
     // 16 bytes per lane to and from global memory.
+    // Warm-up of memory the next kernel will read (the down projection's weights while the gate/up projection, which
+    // leaves HBM idle, finishes a tile): every workgroup reads its slice once, front to back, so the data is in the
+    // last-level cache when that kernel's strided tile loads ask for it.  The values are not used.
+    constexpr int PF_VEC = 5;
+    u32x4 pfv[PF_VEC];
+    const bool do_pf = EPI == EPI_SWIGLU && pf.n16 != 0;
+    if (do_pf) {
+        constexpr unsigned NTHR = 64 * NW;
+        unsigned per = min((pf.n16 + (unsigned)n_tiles - 1) / (unsigned)n_tiles, (unsigned)PF_VEC * NTHR);
+        unsigned base = (unsigned)lid * per;
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(pf.ptr);
+#pragma unroll
+        for (int i = 0; i < PF_VEC; ++i) {
+            unsigned off = (unsigned)i * NTHR + (unsigned)tid;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            pfv[i] = (off < per && base + off < pf.n16) ? src[base + off] : z;
+        }
+    }
     constexpr int WNO = (EPI == EPI_SWIGLU) ? WN / 2 : WN;   // output columns of a wave tile
     constexpr int SROW = WNO + 8;                            // staging row stride in words; 4 * SROW % 64 == 32,
                                                              // so the two row groups of a write hit disjoint banks
@@ -356,6 +375,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
     }
+    if (do_pf) {
+#pragma unroll
+        for (int i = 0; i < PF_VEC; ++i) asm volatile("" ::"v"(pfv[i]));   // the loads must not be dropped as unused
+    }
 }
 
 // The number of activation terms is a template parameter, so the one-term and the two-term launches
@@ -363,7 +386,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
 // Launches the kernel on the column range [n_base, n_base + n_cols) of the N columns.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_FMT>
 static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base, int n_cols,
-                              int out_terms, hipStream_t s, const RopeArgs *rope = nullptr) {
+                              int out_terms, hipStream_t s, const RopeArgs *rope = nullptr, const PrefetchArgs *pf = nullptr) {
     constexpr int smem = NS * (BM + BN) * BK * 2;
     static bool attr_set = false;
     auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, A_FMT>;
@@ -387,44 +410,56 @@ static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, in
     }
     group_m = std::max(1, std::min(group_m, tiles_m));
     kern<<<grid, 64 * WAVES_M * WAVES_N, smem, s>>>(A, W, out, M, N, K, tiles_m, tiles_n, n_base, group_m, out_terms,
-                                                    rope ? *rope : RopeArgs{});
+                                                    rope ? *rope : RopeArgs{}, pf ? *pf : PrefetchArgs{});
     return hipGetLastError();
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI>
 static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base, int n_cols,
-                              int a_fmt, int out_fmt, hipStream_t s, const RopeArgs *rope = nullptr) {
+                              int a_fmt, int out_fmt, hipStream_t s, const RopeArgs *rope = nullptr,
+                              const PrefetchArgs *pf = nullptr) {
     if (a_fmt == 2)
-        return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope);
+        return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
     if (a_fmt == 3) {
-        // fp16 operands: built for the two tile shapes the default choice uses
+        // fp16 operands: built for the tile shapes the default choice uses
         constexpr bool has_f16 = BK == 64 && NS == 2 && ((BM == 128 && BN == 128 && WAVES_M == 2 && WAVES_N == 2) ||
-                                                           (BM == 256 && BN == 256 && WAVES_M == 2 && WAVES_N == 4));
+                                                           (BM == 256 && BN == 256 && WAVES_M == 2 && WAVES_N == 4) ||
+                                                           (BM == 192 && BN == 96 && WAVES_M == 2 && WAVES_N == 3));
         if constexpr (has_f16)
-            return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 3>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope);
+            return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 3>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
         else
             return hipErrorInvalidValue;
     }
-    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope);
+    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
 }
 
 // Tile ids: 1 = 128x128 / 4 waves, 2 = 256x256 / 4 waves, 3 = 256x128 / 4 waves, 4 = 256x256 / 8 waves
-// (all BK 64 x 2 stages); 5 = 128x128 / 4 waves and 6 = 256x256 / 8 waves with BK 32 x 4 stages.
-// Measured on the draft-model shapes: 4 is the fastest for the wide gate/up projection, 1 for the
+// (all BK 64 x 2 stages); 5 = 128x128 / 4 waves and 6 = 256x256 / 8 waves with BK 32 x 4 stages;
+// 7 = 192x96 / 6 waves (2 x 3, wave tile 96 x 32), BK 64 x 2 stages, for N % 96 == 0 and no SwiGLU.
+// Measured on the draft-model shapes: 4 is the fastest for the wide gate/up projection, 1 or 7 for the
 // others; the deeper pipelines (5, 6) pay more barriers than they hide latency.
 template <int EPI>
 static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
-                             int out_terms, hipStream_t s) {
+                             int out_terms, hipStream_t s, const PrefetchArgs *pf = nullptr) {
     int tile = g_gemm_tune.tile;
-    if (a_terms == 3 && tile != 1 && tile != 4) tile = 0;   // fp16 operands exist for the default shapes only
+    if (a_terms == 3 && tile != 1 && tile != 4 && tile != 7) tile = 0;   // fp16 operands exist for the default shapes only
     if (tile == 0) {
         // Wide outputs take 256x256 tiles, one workgroup per CU, in rounds of 256 tiles.  A last round
         // that would be less than half full costs as much as a full one, so those columns are cut off
         // and done by a second launch with 128x128 tiles (two workgroups per CU), which is shorter.
         int tm = (M + 255) / 256, tn = N / 256;
         long t256 = (long)tm * tn;
-        if (N % 256 != 0 || t256 < 192)
+        if (N % 256 != 0 || t256 < 192) {
+            // 128x128 tiles run two per CU; a count a little above 256 leaves most CUs with one workgroup, which
+            // runs at well under the rate of two.  If the same output is at most 256 tiles of 192x96 (the same
+            // flop per staged byte), one such tile per CU is the better cut: 3072 x 1536 = 288 -> 256 tiles.
+            if constexpr (EPI != EPI_SWIGLU) {
+                long t128 = (long)((M + 127) / 128) * (N / 128), t192 = (long)((M + 191) / 192) * (N / 96);
+                if (N % 96 == 0 && t128 > 256 && t128 <= 384 && t192 <= 256)
+                    return launch_tile<192, 96, 2, 3, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+            }
             return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        }
         long rounds = t256 / 256;
         int n1 = tn;
         if (rounds >= 1 && t256 - rounds * 256 > 0) {
@@ -432,7 +467,7 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
             if ((long)(tn - full) * tm <= 128) n1 = full;
         }
         if (n1 > 0) {
-            hipError_t e = launch_tile<256, 256, 2, 4, 64, 2, EPI>(A, W, out, M, N, K, 0, n1 * 256, a_terms, out_terms, s);
+            hipError_t e = launch_tile<256, 256, 2, 4, 64, 2, EPI>(A, W, out, M, N, K, 0, n1 * 256, a_terms, out_terms, s, nullptr, pf);
             if (e != hipSuccess) return e;
         }
         if (n1 < tn)
@@ -441,12 +476,16 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
         return hipSuccess;
     }
     if ((tile == 2 || tile == 4 || tile == 6) && N % 256 != 0) tile = 1;
+    if (tile == 7 && (N % 96 != 0 || EPI == EPI_SWIGLU)) tile = 1;
     switch (tile) {
         case 2: return launch_tile<256, 256, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
         case 3: return launch_tile<256, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
         case 4: return launch_tile<256, 256, 2, 4, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
         case 5: return launch_tile<128, 128, 2, 2, 32, 4, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
         case 6: return launch_tile<256, 256, 2, 4, 32, 4, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        case 7:
+            if constexpr (EPI != EPI_SWIGLU) return launch_tile<192, 96, 2, 3, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+            else return hipErrorInvalidValue;   // not reached: a SwiGLU column pair needs 64-column wave tiles
         default: return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
     }
 }
@@ -594,12 +633,12 @@ static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, 
     }
     int tiles_m = (M + 127) / 128, tiles_n = N / 128;
     dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8, splits);
-    kern<<<grid, 256, smem, s>>>(A, W, part, M, N, K, tiles_m, tiles_n, 0, tiles_m, 1, RopeArgs{});
+    kern<<<grid, 256, smem, s>>>(A, W, part, M, N, K, tiles_m, tiles_n, 0, tiles_m, 1, RopeArgs{}, PrefetchArgs{});
     return hipGetLastError();
 }
 
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
-                            int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s) {
+                            int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s, const PrefetchArgs *pf) {
     int k_total = K * (a_terms == 2 ? 2 : 1);
     int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, k_total) : 1;
     if (splits > 1 && splitk_ws && gemm_splitk_bytes(M, N, k_total) <= splitk_ws_bytes) {
@@ -616,7 +655,7 @@ hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int 
     }
     if (epi == EPI_STORE_F32) return launch_epi<EPI_STORE_F32>(A, W, out, M, N, K, a_terms, out_terms, s);
     if (epi == EPI_RESID_F32) return launch_epi<EPI_RESID_F32>(A, W, out, M, N, K, a_terms, out_terms, s);
-    return launch_epi<EPI_SWIGLU>(A, W, out, M, N, K, a_terms, out_terms, s);
+    return launch_epi<EPI_SWIGLU>(A, W, out, M, N, K, a_terms, out_terms, s, pf);
 }
 
 // QKV projection with the rotation in the epilogue (see RopeArgs): the default tile choice, both shapes

@@ -111,8 +111,15 @@ hipError_t launch_gemm_f32(const float *A, const float *W, void *out, int M, int
 // splitk_ws (may be null): scratch for the split-K path that outputs with too few 128 x 128 tiles to fill the
 // chip take (gemm_splitk_factor > 1); it needs gemm_splitk_bytes(M, N, K * a_terms) bytes, otherwise the call
 // falls back to one workgroup per tile.
+// pf (may be null; used by the SwiGLU epilogue's wide kernel only): memory the kernel reads once, front to back,
+// while it works, so that it sits in the last-level cache for the kernel that follows; n16 = 16-byte vectors.
+struct PrefetchArgs {
+    const void *ptr = nullptr;
+    unsigned n16 = 0;
+};
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
-                            int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
+                            int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s,
+                            const PrefetchArgs *pf = nullptr);
 hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms, const RopeArgs &rope,
                                  float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
 int gemm_splitk_factor(int M, int N, int K_total);

@@ -43,8 +43,8 @@ def _pack_rows(F):
 
 
 # --------------------------------------------------------------------------- #
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
-@pytest.mark.parametrize("M,N,K", [(300, 512, 192), (1, 256, 64), (257, 768, 1024), (512, 256, 320)])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("M,N,K", [(300, 512, 192), (1, 256, 64), (257, 768, 1024), (512, 256, 320), (400, 384, 128)])
 def test_gemm_bf16_store_and_residual(tile, M, N, K):
     print(f"gemm bf16 tile={tile} M={M} N={N} K={K}", flush=True)
     ctx, _ = _ctx("bf16")
@@ -456,6 +456,39 @@ def test_gemm_bf16_wide_output_split_into_two_launches(epi):
     cb.confspec_destroy(ctx)
 
 
+@pytest.mark.parametrize("a_terms", [1, 2])
+@pytest.mark.parametrize("M", [3072, 2990])
+def test_gemm_bf16_default_cut_into_one_tile_per_cu(M, a_terms):
+    """A little more than 256 tiles of 128x128 that are at most 256 tiles of 192x96: the default choice takes the
+    latter (residual and store epilogues)."""
+    print(f"gemm bf16 192x96 cut M={M} a_terms={a_terms}", flush=True)
+    ctx, _ = _ctx("bf16")
+    N, K = 1536, 320
+    full = _rand((M, K), torch.float32, 61)
+    if a_terms == 2:
+        hi = full.to(torch.bfloat16)
+        lo = (full - hi.float()).to(torch.bfloat16)
+        A = torch.cat([hi, lo], dim=1).contiguous()
+        a64 = f64(hi) + f64(lo)
+    else:
+        A = full.to(torch.bfloat16)
+        a64 = f64(A)
+    Wt = _rand((N, K), torch.bfloat16, 62, 0.05)
+    ref = a64 @ f64(Wt).T
+    x0 = _rand((M + 2, N), torch.float32, 63)
+    x = x0.clone()
+    cb.confspec_op_gemm(ctx, A, Wt, x, M, N, K, cb.EPI_RESID_F32, a_terms=a_terms)
+    torch.cuda.synchronize()
+    assert np.abs(f64(x[:M]) - (ref + f64(x0[:M]))).max() <= 2e-5 * max(np.abs(ref).max(), 4.0)
+    assert torch.equal(x[M:], x0[M:])
+    out = torch.full((M + 2, N), 7.0, dtype=torch.float32, device=DEV)
+    cb.confspec_op_gemm(ctx, A, Wt, out, M, N, K, cb.EPI_STORE_F32, a_terms=a_terms)
+    torch.cuda.synchronize()
+    assert np.abs(f64(out[:M]) - ref).max() <= 2e-5 * np.abs(ref).max()
+    assert torch.all(out[M:] == 7.0)
+    cb.confspec_destroy(ctx)
+
+
 @pytest.mark.parametrize("M", [1, 32, 128, 300, 1000])
 @pytest.mark.parametrize("epi,a_terms", [("store", 1), ("resid", 1), ("swiglu", 1), ("resid", 2), ("swiglu", 2)])
 def test_gemm_bf16_split_k_for_short_outputs(M, epi, a_terms):
@@ -502,7 +535,8 @@ def test_gemm_bf16_split_k_for_short_outputs(M, epi, a_terms):
     cb.confspec_destroy(ctx)
 
 
-@pytest.mark.parametrize("M,N,K,scratch", [(300, 512, 192, False), (700, 256 * 90, 128, False), (32, 512, 2240, True)])
+@pytest.mark.parametrize("M,N,K,scratch", [(300, 512, 192, False), (700, 256 * 90, 128, False), (32, 512, 2240, True),
+                                           (3072, 1536, 128, False)])   # the last: one 192x96 tile per CU
 def test_gemm_fp16_operands_all_epilogues(M, N, K, scratch):
     """Activation format 3: A and W hold IEEE half values, the SwiGLU result is written as half."""
     print(f"gemm fp16 operands M={M} N={N} K={K} scratch={scratch}", flush=True)

@@ -155,6 +155,23 @@ def test_fused_and_separate_rotary_embedding_agree():
         G.compare(wl, res[flag], ora, f"fuse_rope={flag}")
 
 
+def test_weight_prefetch_hint_changes_no_bit():
+    print("down-projection weight prefetch on / off", flush=True)
+    wl = _small_bf16("prefetch", 2009, (700, 64, 0, 3000, 129), (40, 96, 20, 7, 1), n_layers=6, d_ffn=2048)
+    weights, batch, kv = G.build_inputs(wl)
+    ver = Verifier(wl.model, weights)
+    res = {}
+    try:
+        for flag in (0, 1):
+            cb.confspec_tune("prefetch_down", flag)
+            res[flag] = G.run_gpu(wl, weights, batch, kv, verifier=ver)
+    finally:
+        cb.confspec_tune("prefetch_down", 1)
+    ver.close()
+    for k in ("logits", "conf", "verdict", "accept"):
+        assert np.array_equal(res[0][k], res[1][k])
+
+
 def test_config2_draft_shape_full_size_sampled_traces():
     print("config 2", flush=True)
     G.parity_case(W.config(2), traces=[0, 13, 31])
