@@ -994,16 +994,15 @@ int confspec_cascade(confspec_ctx *draft, const confspec_weights *wd, const conf
     // The one host round trip of the call: how many traces the large model sees, their suffix offsets and prefix
     // lengths (the host plans that pass's launches from them).
     int32_t h_n[2] = {0, 0};
+    std::vector<int32_t> h_cu(B + 1), h_pl(B);
     HIP_TRY(hipMemcpyAsync(h_n, n_out, sizeof h_n, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(h_cu.data(), cu_out, (size_t)(B + 1) * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(h_pl.data(), plens_out, (size_t)B * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     const int n = h_n[0];
     if (n < 0 || n > B || h_n[1] < 0 || h_n[1] > T) return fail(ctx, CONFSPEC_E_HIP, "selection returned %d traces, %d tokens", n, h_n[1]);
     if (h_n_target) *h_n_target = n;
     if (n > 0) {
-        std::vector<int32_t> h_cu(n + 1), h_pl(n);
-        HIP_TRY(hipMemcpyAsync(h_cu.data(), cu_out, (size_t)(n + 1) * 4, hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipMemcpyAsync(h_pl.data(), plens_out, (size_t)n * 4, hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipStreamSynchronize(s));
         confspec_batch sub = {n, h_n[1], ids_out, cu_out, plens_out, h_cu.data(), h_pl.data()};
         confspec_kv kv_sub = *kvt;
         kv_sub.block_table = table_out;
