@@ -244,12 +244,13 @@ int check_ws(const confspec_ctx *ctx, const void *ws, size_t have, size_t need) 
 
 int run_gemm(confspec_ctx *ctx, const void *A, const void *W, void *out, int M, int N, int K, int epi,
              int a_terms, int out_terms, hipStream_t s, float *splitk_ws = nullptr, size_t splitk_bytes = 0,
-             const cs::PrefetchArgs *pf = nullptr) {
+             const cs::PrefetchArgs *pf = nullptr, const cs::NormAfter *norm = nullptr, bool *norm_done = nullptr) {
+    if (norm_done) *norm_done = false;
     if (ctx->cfg.dtype == CONFSPEC_DTYPE_FP32) {
         HIP_TRY(cs::launch_gemm_f32((const float *)A, (const float *)W, out, M, N, K, epi, s));
     } else {
         HIP_TRY(cs::launch_gemm_bf16((const cs::bf16 *)A, (const cs::bf16 *)W, out, M, N, K, epi, a_terms, out_terms,
-                                     splitk_ws, splitk_bytes, s, pf));
+                                     splitk_ws, splitk_bytes, s, pf, norm, norm_done));
     }
     return CONFSPEC_OK;
 }
@@ -525,29 +526,35 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     HIP_TRY(cs::launch_embed(c.dtype, batch->suffix_ids, w->embed, x, T, d, c.vocab, s));
     const int32_t *last_row = (const int32_t *)(ws + L.last_row);
     size_t eb = elem_bytes(c.dtype);
+    // Activation format of a layer's GEMMs (see gemm_bf16.hip): the first layers run on fp16 operands when the
+    // packed weights carry fp16 copies (3), else with two bf16 terms (2); the rest is plain bf16 (1).
+    // The projection kernel that rotates q and k itself reads wqkv with reordered rows (the half copy has that
+    // order too, so fp16 layers depend on it).
+    auto rope_fused_in = [&](int l) {
+        return c.dtype == CONFSPEC_DTYPE_BF16 && g_fuse_rope && c.head_dim == 128 && w->wqkv_perm && w->wqkv_perm[l];
+    };
+    auto format_of = [&](int l) {
+        if (!(c.dtype == CONFSPEC_DTYPE_BF16 && l < split_layers_for(c))) return 1;
+        if (rope_fused_in(l) && g_first_layers_f16 && l < w->n_f16_layers && w->wqkv_f16 && w->wo_f16 && w->w_gate_up_f16 &&
+            w->w_down_f16 && w->wqkv_f16[l] && w->wo_f16[l] && w->w_gate_up_f16[l] && w->w_down_f16[l])
+            return 3;
+        return 2;
+    };
+    bool attn_norm_done = false;   // the previous layer's down projection already wrote this layer's normalised input
     for (int l = 0; l < c.n_layers; ++l) {
-        // Activation format of this layer's GEMMs (see gemm_bf16.hip): the first layers run on fp16 operands
-        // when the packed weights carry fp16 copies, else with two bf16 terms; the rest is plain bf16.
-        int tm = 1;
+        const int tm = format_of(l);
         const void *wqkv = w->wqkv[l], *wo = w->wo[l], *wgu = w->w_gate_up[l], *wdn = w->w_down[l];
-        // the projection kernel that rotates q and k itself reads wqkv with reordered rows (the half copy has
-        // that order too, so fp16 layers depend on it)
-        const bool rope_fused = c.dtype == CONFSPEC_DTYPE_BF16 && g_fuse_rope && c.head_dim == 128 && w->wqkv_perm &&
-                                w->wqkv_perm[l];
-        if (c.dtype == CONFSPEC_DTYPE_BF16 && l < split_layers_for(c)) {
-            tm = 2;
-            if (rope_fused && g_first_layers_f16 && l < w->n_f16_layers && w->wqkv_f16 && w->wo_f16 && w->w_gate_up_f16 && w->w_down_f16 &&
-                w->wqkv_f16[l] && w->wo_f16[l] && w->w_gate_up_f16[l] && w->w_down_f16[l]) {
-                tm = 3;
-                wqkv = w->wqkv_f16[l]; wo = w->wo_f16[l]; wgu = w->w_gate_up_f16[l]; wdn = w->w_down_f16[l];
-            }
+        const bool rope_fused = rope_fused_in(l);
+        if (tm == 3) {
+            wqkv = w->wqkv_f16[l]; wo = w->wo_f16[l]; wgu = w->w_gate_up_f16[l]; wdn = w->w_down_f16[l];
         }
         const int wide = tm == 2 ? 2 : 1;      // buffer width multiplier of the activation format
         bool prec = c.dtype == CONFSPEC_DTYPE_BF16 && l < g_attn_precise_layers;
         bool last = prune && l == c.n_layers - 1;
         float *sk = c.dtype == CONFSPEC_DTYPE_BF16 ? (float *)(ws + L.splitk) : nullptr;   // for outputs of few tiles
         size_t skb = sk ? L.splitk_bytes : 0;
-        HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, tm, s));
+        if (!attn_norm_done) HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, tm, s));
+        attn_norm_done = false;
         if (rope_fused) {
             cs::RopeArgs ra = {(const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin), ws + L.q, ws + L.ksuf,
                                ws + L.vsuf, prec ? ws + L.q_lo : nullptr, prec ? ws + L.ksuf_lo : nullptr,
@@ -583,15 +590,25 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
             HIP_TRY(cs::launch_gather_rows(ws + L.attn, ws + L.attn_last, last_row, B, T, (size_t)qw * eb * wide, s));
             attn = ws + L.attn_last;
         }
-        if ((rc = run_gemm(ctx, attn, wo, xr, rows, d, qw, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
-        HIP_TRY(cs::launch_rmsnorm(c.dtype, xr, w->mlp_norm[l], hr, rows, d, c.rms_eps, tm, s));
+        // A residual projection that takes the split-K path (few rows) writes the following RMSNorm along with the
+        // residual update; otherwise the RMSNorm is a kernel of its own.
+        cs::NormAfter na;
+        na.g = w->mlp_norm[l]; na.h = hr; na.eps = c.rms_eps; na.terms = tm;
+        bool mlp_norm_done = false;
+        if ((rc = run_gemm(ctx, attn, wo, xr, rows, d, qw, cs::EPI_RESID_F32, tm, 1, s, sk, skb, nullptr, &na, &mlp_norm_done))) return rc;
+        if (!mlp_norm_done) HIP_TRY(cs::launch_rmsnorm(c.dtype, xr, w->mlp_norm[l], hr, rows, d, c.rms_eps, tm, s));
         // the gate/up projection is compute-bound: while it runs it also pulls the down projection's weights, which
         // that kernel reads in strided pieces, into the last-level cache
         cs::PrefetchArgs pf;
         pf.ptr = g_prefetch_down ? wdn : nullptr;
         pf.n16 = g_prefetch_down ? (unsigned)((size_t)d * c.d_ffn * eb / 16) : 0u;
         if ((rc = run_gemm(ctx, hr, wgu, act, rows, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s, sk, skb, &pf))) return rc;
-        if ((rc = run_gemm(ctx, act, wdn, xr, rows, d, c.d_ffn, cs::EPI_RESID_F32, tm, 1, s, sk, skb))) return rc;
+        cs::NormAfter nb;
+        const bool has_next = !last && l + 1 < c.n_layers;        // rows == T: the next layer normalises the same rows
+        if (has_next) { nb.g = w->attn_norm[l + 1]; nb.h = h; nb.eps = c.rms_eps; nb.terms = format_of(l + 1); }
+        if ((rc = run_gemm(ctx, act, wdn, xr, rows, d, c.d_ffn, cs::EPI_RESID_F32, tm, 1, s, sk, skb, nullptr,
+                           has_next ? &nb : nullptr, &attn_norm_done)))
+            return rc;
     }
     if (ex.head) {   // verdict outputs, if any, go to the head's scratch
         char *hs = (char *)ex.head_scratch;

@@ -619,6 +619,67 @@ __global__ void splitk_reduce_rope_kernel(const float *__restrict__ part, int sp
     }
 }
 
+// Split-K slices of a residual projection summed in their fixed order, added to the residual stream, and the RMSNorm
+// of the updated row (the operand of the next projection) taken in the same kernel: one workgroup per row keeps the
+// row in registers between the two steps.  N <= 6144, N % 4 == 0.  Output formats as in the RMSNorm kernel:
+// terms 1 bf16, 2 hi | lo, 3 fp16.
+__global__ __launch_bounds__(256) void splitk_reduce_resid_norm_kernel(const float *__restrict__ part, int splits, int M, int N,
+                                                                        float *__restrict__ x, const bf16 *__restrict__ g,
+                                                                        bf16 *__restrict__ h, float eps, int terms) {
+    constexpr int NV = 6;
+    __shared__ float red[4];
+    int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    size_t plane = (size_t)M * N;
+    const int nv = N >> 2;
+    f32x4 v[NV];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        int j = tid + 256 * i;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (j < nv) {
+            const float *p0 = part + (size_t)r * N + 4 * j;
+#pragma unroll 8
+            for (int sp = 0; sp < splits; ++sp) acc += *reinterpret_cast<const f32x4 *>(p0 + sp * plane);
+            f32x4 *dst = reinterpret_cast<f32x4 *>(x + (size_t)r * N + 4 * j);
+            acc += *dst;
+            *dst = acc;
+        }
+        v[i] = acc;
+        ss += acc[0] * acc[0] + acc[1] * acc[1] + acc[2] * acc[2] + acc[3] * acc[3];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    if (lane == 0) red[wave] = ss;
+    __syncthreads();
+    float rinv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)N + eps);
+    bf16 *o = h + (size_t)r * N * (terms == 2 ? 2 : 1);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        int j = tid + 256 * i;
+        if (j >= nv) continue;
+        int c = j << 2;
+        uint2 gp = *reinterpret_cast<const uint2 *>(g + c);
+        float gv[4] = {__uint_as_float(gp.x << 16), __uint_as_float(gp.x & 0xffff0000u), __uint_as_float(gp.y << 16),
+                       __uint_as_float(gp.y & 0xffff0000u)};
+        unsigned hi[4], lo[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float y = v[i][q] * rinv * gv[q];
+            if (terms == 3) {
+                hi[q] = __half_as_ushort(__float2half_rn(y));
+                lo[q] = 0;
+            } else {
+                bf16 hh = __float2bfloat16(y);
+                hi[q] = __bfloat16_as_ushort(hh);
+                lo[q] = __bfloat16_as_ushort(__float2bfloat16(y - __bfloat162float(hh)));
+            }
+        }
+        *reinterpret_cast<uint2 *>(o + c) = uint2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+        if (terms == 2) *reinterpret_cast<uint2 *>(o + N + c) = uint2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+    }
+}
+
 template <int A_FMT>
 static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, int M, int N, int K, int splits,
                                      hipStream_t s) {
@@ -638,7 +699,9 @@ static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, 
 }
 
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
-                            int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s, const PrefetchArgs *pf) {
+                            int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s, const PrefetchArgs *pf,
+                            const NormAfter *norm, bool *norm_done) {
+    if (norm_done) *norm_done = false;
     int k_total = K * (a_terms == 2 ? 2 : 1);
     int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, k_total) : 1;
     if (splits > 1 && splitk_ws && gemm_splitk_bytes(M, N, k_total) <= splitk_ws_bytes) {
@@ -648,6 +711,14 @@ hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int 
         if (e != hipSuccess) return e;
         int n_out = epi == EPI_SWIGLU ? N / 2 : N;
         dim3 grid((n_out / 4 + 255) / 256, M);
+        if (epi == EPI_RESID_F32 && norm && norm->g && norm->h && N % 4 == 0 && N <= 6144 &&
+            ((((uintptr_t)norm->g | (uintptr_t)norm->h) & 7) == 0)) {
+            splitk_reduce_resid_norm_kernel<<<M, 256, 0, s>>>(splitk_ws, splits, M, N, reinterpret_cast<float *>(out),
+                                                              reinterpret_cast<const bf16 *>(norm->g),
+                                                              reinterpret_cast<bf16 *>(norm->h), norm->eps, norm->terms);
+            if (norm_done) *norm_done = true;
+            return hipGetLastError();
+        }
         if (epi == EPI_STORE_F32) splitk_reduce_kernel<EPI_STORE_F32><<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, out, out_terms);
         else if (epi == EPI_RESID_F32) splitk_reduce_kernel<EPI_RESID_F32><<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, out, out_terms);
         else splitk_reduce_kernel<EPI_SWIGLU><<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, out, out_terms);

@@ -117,9 +117,18 @@ struct PrefetchArgs {
     const void *ptr = nullptr;
     unsigned n16 = 0;
 };
+// norm (may be null; residual epilogue only): the RMSNorm that follows the projection in the pass.  When the call takes
+// the split-K path, the kernel that adds the slices to the residual stream also writes RMSNorm(updated row) * g to
+// norm->h (format norm->terms) and *norm_done becomes true; otherwise the caller runs the RMSNorm kernel itself.
+struct NormAfter {
+    const void *g = nullptr;
+    void *h = nullptr;
+    float eps = 0.f;
+    int terms = 1;
+};
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
                             int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s,
-                            const PrefetchArgs *pf = nullptr);
+                            const PrefetchArgs *pf = nullptr, const NormAfter *norm = nullptr, bool *norm_done = nullptr);
 hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms, const RopeArgs &rope,
                                  float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
 int gemm_splitk_factor(int M, int N, int K_total);

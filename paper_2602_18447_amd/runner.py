@@ -96,9 +96,10 @@ class Verifier:
             self._head = torch.empty(need, dtype=torch.uint8, device=self.device)
         return self._head
 
-    def generate_step(self, kv, batch, n_append=None, verdict_ids=None, outputs=None, stream=None):
+    def generate_step(self, kv, batch, n_append=None, verdict_ids=None, outputs=None, stream=None, n_append_dev=None):
         """The pass plus the full-vocabulary head at the last position: returns dict(token, max_logit, lse[, conf_full])
-        of device tensors.  n_append: host integers per trace for write-back of the new tokens' keys / values."""
+        of device tensors.  n_append: host integers per trace for write-back of the new tokens' keys / values
+        (n_append_dev: the same counts already on the device, saves the upload)."""
         kvs, bs, keep = self.bind(kv, batch)
         dev = self.device
         outs = outputs or dict(token=torch.empty(bs.B, dtype=torch.int32, device=dev),
@@ -107,7 +108,7 @@ class Verifier:
         if verdict_ids is not None and "conf_full" not in outs:
             outs["conf_full"] = torch.empty(bs.B, dtype=torch.float32, device=dev)
         hn = None if n_append is None else np.ascontiguousarray(n_append, dtype=np.int32)
-        dn = None if hn is None else torch.from_numpy(hn).to(dev)
+        dn = None if hn is None else (n_append_dev if n_append_dev is not None else torch.from_numpy(hn).to(dev))
         ho = cb.HeadOut(outs["token"].data_ptr(), outs["max_logit"].data_ptr(), outs["lse"].data_ptr(),
                         outs["conf_full"].data_ptr() if verdict_ids is not None else None)
         cb.confspec_generate_step(self.ctx, self.w, kvs, bs, dn, hn, verdict_ids, self.workspace(bs.T, bs.B),
@@ -128,13 +129,18 @@ class Verifier:
         cu = np.arange(B + 1, dtype=np.int32)
         cu_dev = torch.from_numpy(cu).to(dev)
         ones = np.ones(B, dtype=np.int32)
+        ones_dev = torch.from_numpy(ones).to(dev)
+        # every step's context lengths, uploaded once: a copy from pageable host memory inside the loop would make
+        # each step wait for the one before
+        lens_host = L0[None, :] + np.arange(n_steps, dtype=np.int32)[:, None]
+        lens_dev = torch.from_numpy(np.ascontiguousarray(lens_host)).to(dev)
         cur = first_ids
         for i in range(n_steps):
-            hl = L0 + i
-            batch = SimpleNamespace(suffix_ids=cur, cu_suffix=cu_dev, prefix_lens=torch.from_numpy(hl).to(dev),
+            batch = SimpleNamespace(suffix_ids=cur, cu_suffix=cu_dev, prefix_lens=lens_dev[i],
                                     block_table=block_table, n_blocks=n_blocks, max_blocks_per_seq=max_blocks_per_seq,
-                                    block_size=kv.block_size, h_cu_suffix=cu, h_prefix_lens=hl)
-            self.generate_step(kv, batch, n_append=ones, outputs=dict(token=toks[i], max_logit=zmax[i], lse=lse[i]))
+                                    block_size=kv.block_size, h_cu_suffix=cu, h_prefix_lens=lens_host[i])
+            self.generate_step(kv, batch, n_append=ones, n_append_dev=ones_dev,
+                               outputs=dict(token=toks[i], max_logit=zmax[i], lse=lse[i]))
             cur = toks[i]
         return toks, zmax, lse
 

@@ -190,7 +190,9 @@ def test_cascade_full_size_draft_and_target_shapes():
         assert n_target == int(ran.sum()) and not (ran & keep).any()
         assert np.array_equal(ran, _target_ran_rule(full["d"]["conf"], full["d"]["verdict"], np.float32(gamma), req_start))
         # the large model on the compacted sub-batch against its pass over the whole batch
-        assert np.abs(g["conf_target"][ran] - full["t"]["conf"][ran]).max(initial=0.0) <= 6e-3
+        # (two launch configurations of the same model - few rows take split-K paths - each within the confidence
+        # bound of the exact value)
+        assert np.abs(g["conf_target"][ran] - full["t"]["conf"][ran]).max(initial=0.0) <= 2 * tol["conf"]
         decided = gap_t > 2 * tol["logit"]
         assert np.array_equal(g["verdict_target"][ran & decided], full["t"]["verdict"][ran & decided])
         v, m = _loop_closed_form(keep, full["d"]["verdict"], g["verdict_target"], req_start)
