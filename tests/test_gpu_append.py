@@ -169,3 +169,22 @@ def test_append_full_size_config2_sampled_traces():
         assert torch.equal(a, b)
     _check_appended(wl, batch, kv, before, n_app, ora, "append config 2")
     ver.close()
+
+
+def test_append_of_nothing_leaves_the_cache_alone():
+    print("append nothing", flush=True)
+    wl = W.tiny_workload("append0", 5300, dtype="bf16", n_layers=2, d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128,
+                         d_ffn=768, vocab=1024, block_size=16, prefix_lens=(33, 0, 160), suffix_lens=(5, 1, 40), taus=(0.5,))
+    weights = W.make_weights(wl.model, wl.seed, DEV)
+    batch = W.make_batch(wl, DEV)
+    kv = W.make_seeded_kv(wl, batch, DEV)
+    before = (kv.k_pages.clone(), kv.v_pages.clone())
+    ver = Verifier(wl.model, weights)
+    vids = W.draw_verdict_ids(wl)
+    plain = [t.clone() for t in ver.verify(kv, batch, vids, [0.5])]
+    outs = ver.verify_append(kv, batch, np.zeros(3, dtype=np.int32), vids, [0.5])
+    torch.cuda.synchronize()
+    assert torch.equal(kv.k_pages, before[0]) and torch.equal(kv.v_pages, before[1])
+    for a, b in zip(plain, outs):
+        assert torch.equal(a, b)
+    ver.close()

@@ -318,3 +318,19 @@ def test_cascade_over_candidate_trees_matches_oracle(dtype):
               flush=True)
     print(f"requests compared bit for bit: {compared}/{total}", flush=True)
     assert compared >= 0.4 * total          # small random models decide many steps by less than the logit bound
+
+
+def test_cascade_single_trace_batch():
+    """The smallest batch: one request with one drafted step, kept (gamma 0) and escalated (gamma above 1)."""
+    print("cascade, one trace", flush=True)
+    wl_d, wl_t = _pair(3400, (45,), (9,), "bf16")
+    batch, sd, st = _sides(wl_d, wl_t)
+    vids = W.draw_verdict_ids(wl_d)
+    casc = Cascade(sd["ver"], st["ver"])
+    ids, cu, pl = batch.suffix_ids.cpu().numpy(), batch.h_cu_suffix, batch.h_prefix_lens
+    for gamma in (0.0, 1.5):
+        ora = O.cascade_verify(sd["ora"], st["ora"], wl_d.block_size, ids, cu, pl, vids, gamma, [0, 1])
+        res, n_target = casc.run(sd["kv"], st["kv"], batch, [0, 1], vids, gamma)
+        torch.cuda.synchronize()
+        assert n_target == (0 if gamma == 0.0 else 1)
+        _check(wl_d, res, n_target, ora, gamma, [0, 1], G.TOL["bf16"])
