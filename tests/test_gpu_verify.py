@@ -195,3 +195,21 @@ def test_config4_ragged_sampled_traces():
 def test_config5_target_shape_sampled_trace():
     print("config 5", flush=True)
     G.parity_case(W.config(5), traces=[9])
+
+
+@pytest.mark.parametrize("seed", [3101, 3102, 3103, 3104, 3105, 3106])
+def test_seeded_random_small_batches(seed):
+    """Random head groupings, batch sizes and lengths (context lengths on and around page and chunk borders,
+    single-token suffixes, empty contexts), every trace against the oracle."""
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    hq, hkv = [(4, 2), (12, 2), (8, 8), (6, 1), (8, 4), (10, 2)][seed % 6]
+    B = int(rng.integers(1, 9))
+    special = [0, 1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1023, 1024]
+    L = [int(rng.choice(special)) if rng.random() < 0.5 else int(rng.integers(0, 1500)) for _ in range(B)]
+    S = [1 if rng.random() < 0.2 else int(rng.integers(1, 200)) for _ in range(B)]
+    n_layers = int(rng.integers(1, 5))
+    print(f"random small batch seed={seed}: heads {hq}/{hkv}, layers {n_layers}, L={L}, S={S}", flush=True)
+    wl = _small_bf16(f"rand{seed}", seed, tuple(L), tuple(S), n_q_heads=hq, n_kv_heads=hkv, d_model=128 * max(hq // 2, 2),
+                     d_ffn=int(rng.choice([512, 768, 1280])), n_layers=n_layers)
+    s, _, _ = G.parity_case(wl)
+    assert s["traces"] == B
