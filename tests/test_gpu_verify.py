@@ -213,3 +213,48 @@ def test_seeded_random_small_batches(seed):
                      d_ffn=int(rng.choice([512, 768, 1280])), n_layers=n_layers)
     s, _, _ = G.parity_case(wl)
     assert s["traces"] == B
+
+
+def test_hip_graph_replays_match_eager_results():
+    """The pass captured once into a HIP graph: several replays, with eager passes on other inputs and
+    synchronisations in between, each give the eager result of their inputs bit for bit."""
+    print("graph capture / replay", flush=True)
+    wl = _small_bf16("graph", 2010, (700, 64, 0, 3000, 129), (40, 96, 20, 7, 1), n_layers=4)
+    weights, batch, kv = G.build_inputs(wl)
+    vids = W.draw_verdict_ids(wl)
+    taus = list(wl.taus)
+    ver = Verifier(wl.model, weights)
+    outs = ver.alloc_outputs(wl.B, len(vids), len(taus))
+    ver.verify(kv, batch, vids, taus, outputs=outs)
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ver.verify(kv, batch, vids, taus, outputs=outs)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ver.verify(kv, batch, vids, taus, outputs=outs)
+    # a second set of suffix ids, written into the captured input buffer between replays
+    ids_a = batch.suffix_ids.clone()
+    ids_b = torch.roll(ids_a, 5)
+    batch.suffix_ids.copy_(ids_b)
+    ver2 = Verifier(wl.model, weights)
+    eager_b = [t.clone() for t in ver2.verify(kv, batch, vids, taus)]
+    torch.cuda.synchronize()
+    for i in range(6):
+        use_b = i % 2 == 1
+        batch.suffix_ids.copy_(ids_b if use_b else ids_a)
+        for t in outs:
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = eager_b if use_b else eager
+        for got, ref in zip(outs, want):
+            assert torch.equal(got, ref), (i, use_b)
+        ver2.verify(kv, batch, vids, taus)                 # eager work of the same library between replays
+        torch.cuda.synchronize()
+    ver.close()
+    ver2.close()
