@@ -128,7 +128,7 @@ def main():
                     help="traces of the workload the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (traces are independent; more GPUs would each take a "
+        print("bench.py: this library runs on one GPU only (traces are independent; more GPUs would each take a "
               "share of the traces with a replica of the weights, no collectives) - rerun with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
