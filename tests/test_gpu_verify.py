@@ -179,7 +179,7 @@ def test_config2_draft_shape_full_size_sampled_traces():
 
 def test_config3_long_cot_tau_sweep_sampled_traces():
     print("config 3", flush=True)
-    s, gpu, _ = G.parity_case(W.config(3), traces=[5, 63])
+    s, gpu, _ = G.parity_case(W.config(3), traces=[0, 5, 7, 21, 33, 40, 63])
     assert len(gpu["taus"]) == 3
 
 
