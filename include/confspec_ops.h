@@ -35,7 +35,8 @@ extern "C" {
  * bf16, N % 64 == 0 and K % 16 == 0 for fp32; any M >= 1.  out_terms != 1 is valid with the SwiGLU
  * epilogue only (2: out is [M, 2 * N/2]; 3: out holds half values).  dev_scratch (may be NULL) is dev memory the call may use for
  * partial products: with at least confspec_op_gemm_scratch_bytes() bytes a bf16 GEMM whose output has too few
- * 128 x 128 tiles to fill the chip cuts the k range into slices that run as separate workgroups and are added in
+ * 128 x 128 tiles to fill the chip, or whose k range is long (K >= 4096 elements) while 256 x 256 tiles cover only
+ * a third to a sixth of the chip, cuts the k range into slices that run as separate workgroups and are added in
  * a fixed order; without it such a GEMM runs one workgroup per tile.  16-byte aligned. */
 int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, void *dev_out, int32_t M,
                      int32_t N, int32_t K, int32_t epilogue, int32_t a_terms, int32_t out_terms,

@@ -495,26 +495,41 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
 // K: a few CUs work for a long time.  Instead the k range is cut into slices, every (tile, slice) pair
 // is a workgroup that stores its partial product, and a second kernel adds the slices in a fixed order
 // and applies the epilogue.
-int gemm_splitk_factor(int M, int N, int K_total) {
+//
+// A second case: a long k range (K_total >= 4096) over an output that 128 x 128 tiles do cover but 256 x 256 tiles
+// fill only a third to a sixth of the chip with.  Tiles of 128 or 192 x 96 are bound by the rate at which their operands
+// arrive from the L2 (a 256 x 256 tile needs half the bytes per flop), so there the k range is cut into 3..6 slices of
+// 256 x 256 tiles, one workgroup per CU, and the reduction pass that follows costs less than the tiles gain
+// (3072 x 1536 x 8960: 97 us with 3 slices against 106 us for 256 tiles of 192 x 96, and the reduction can also
+// normalise the rows for the next GEMM).  *big_tile says which case applies.
+int gemm_splitk_factor(int M, int N, int K_total, bool *big_tile) {
+    if (big_tile) *big_tile = false;
     if (N % 128 != 0) return 1;
     int tiles = ((M + 127) / 128) * (N / 128), nk = K_total / 64;
     if (g_gemm_tune.splitk > 0) return std::max(1, std::min(g_gemm_tune.splitk, nk / 4));
-    if (M > 128 && tiles >= 256) return 1;               // enough 128 x 128 tiles to fill the chip without a split
+    if (M > 128 && tiles >= 256) {                       // enough 128 x 128 tiles to fill the chip without a split
+        int t256 = ((M + 255) / 256) * (N / 256);
+        int s = t256 > 0 ? 256 / t256 : 0;
+        if (big_tile && N % 256 == 0 && nk >= 64 && s >= 3 && s <= 6 && t256 * s >= 192) {
+            *big_tile = true;
+            return s;
+        }
+        return 1;
+    }
     int want = (384 + tiles / 2) / tiles;                // about 384 workgroups
     int s = std::min(want, nk / 4);                      // at least 4 k-tiles per slice
     return std::max(1, std::min(s, 64));
 }
 size_t gemm_splitk_bytes(int M, int N, int K_total) {
-    int s = gemm_splitk_factor(M, N, K_total);
+    bool big;
+    int s = gemm_splitk_factor(M, N, K_total, &big);
     return s > 1 ? (size_t)s * M * N * 4 : 0;
 }
-// Largest gemm_splitk_bytes over all row counts up to max_M (the factor changes with the number of 128-row tiles).
+// Largest gemm_splitk_bytes over all row counts up to max_M (the factor changes with the number of row tiles).
 size_t gemm_splitk_max_bytes(int max_M, int N, int K_total) {
     size_t best = 0;
-    for (int tm = 1; tm <= (max_M + 127) / 128; ++tm) {
+    for (int tm = 1; tm <= (max_M + 127) / 128; ++tm)
         best = std::max(best, gemm_splitk_bytes(std::min(tm * 128, max_M), N, K_total));
-        if (tm * (N / 128) >= 256) break;
-    }
     return best;
 }
 
@@ -680,22 +695,34 @@ __global__ __launch_bounds__(256) void splitk_reduce_resid_norm_kernel(const flo
     }
 }
 
-template <int A_FMT>
-static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, int M, int N, int K, int splits,
-                                     hipStream_t s) {
-    constexpr int smem = 2 * (128 + 128) * 64 * 2;
+template <int A_FMT, int BT, int WAVES_N>
+static hipError_t launch_splitk_tiles(const bf16 *A, const bf16 *W, float *part, int M, int N, int K, int splits,
+                                      hipStream_t s) {
+    constexpr int smem = 2 * (BT + BT) * 64 * 2;
     static bool attr_set = false;
-    auto kern = gemm_bf16_kernel<128, 128, 2, 2, 64, 2, EPI_STORE_F32, A_FMT>;
+    auto kern = gemm_bf16_kernel<BT, BT, 2, WAVES_N, 64, 2, EPI_STORE_F32, A_FMT>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    int tiles_m = (M + 127) / 128, tiles_n = N / 128;
+    int tiles_m = (M + BT - 1) / BT, tiles_n = N / BT;
     dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8, splits);
-    kern<<<grid, 256, smem, s>>>(A, W, part, M, N, K, tiles_m, tiles_n, 0, tiles_m, 1, RopeArgs{}, PrefetchArgs{});
+    kern<<<grid, 128 * WAVES_N, smem, s>>>(A, W, part, M, N, K, tiles_m, tiles_n, 0, tiles_m, 1, RopeArgs{}, PrefetchArgs{});
     return hipGetLastError();
+}
+
+// The partial products of the k slices, one [M, N] fp32 plane per slice; big_tile: 256 x 256 tiles, else 128 x 128.
+static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, int M, int N, int K, int a_terms,
+                                     int splits, bool big_tile, hipStream_t s) {
+    if (big_tile)
+        return a_terms == 2   ? launch_splitk_tiles<2, 256, 4>(A, W, part, M, N, K, splits, s)
+               : a_terms == 3 ? launch_splitk_tiles<3, 256, 4>(A, W, part, M, N, K, splits, s)
+                              : launch_splitk_tiles<1, 256, 4>(A, W, part, M, N, K, splits, s);
+    return a_terms == 2   ? launch_splitk_tiles<2, 128, 2>(A, W, part, M, N, K, splits, s)
+           : a_terms == 3 ? launch_splitk_tiles<3, 128, 2>(A, W, part, M, N, K, splits, s)
+                          : launch_splitk_tiles<1, 128, 2>(A, W, part, M, N, K, splits, s);
 }
 
 hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
@@ -703,11 +730,10 @@ hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int 
                             const NormAfter *norm, bool *norm_done) {
     if (norm_done) *norm_done = false;
     int k_total = K * (a_terms == 2 ? 2 : 1);
-    int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, k_total) : 1;
+    bool big = false;
+    int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, k_total, &big) : 1;
     if (splits > 1 && splitk_ws && gemm_splitk_bytes(M, N, k_total) <= splitk_ws_bytes) {
-        hipError_t e = a_terms == 2   ? launch_splitk_main<2>(A, W, splitk_ws, M, N, K, splits, s)
-                       : a_terms == 3 ? launch_splitk_main<3>(A, W, splitk_ws, M, N, K, splits, s)
-                                      : launch_splitk_main<1>(A, W, splitk_ws, M, N, K, splits, s);
+        hipError_t e = launch_splitk_main(A, W, splitk_ws, M, N, K, a_terms, splits, big, s);
         if (e != hipSuccess) return e;
         int n_out = epi == EPI_SWIGLU ? N / 2 : N;
         dim3 grid((n_out / 4 + 255) / 256, M);
@@ -734,11 +760,10 @@ hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int 
 hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms, const RopeArgs &rope,
                                  float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s) {
     int k_total = K * (a_terms == 2 ? 2 : 1);
-    int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, k_total) : 1;
+    bool big = false;
+    int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, k_total, &big) : 1;
     if (splits > 1 && splitk_ws && gemm_splitk_bytes(M, N, k_total) <= splitk_ws_bytes) {
-        hipError_t e = a_terms == 2   ? launch_splitk_main<2>(A, W_perm, splitk_ws, M, N, K, splits, s)
-                       : a_terms == 3 ? launch_splitk_main<3>(A, W_perm, splitk_ws, M, N, K, splits, s)
-                                      : launch_splitk_main<1>(A, W_perm, splitk_ws, M, N, K, splits, s);
+        hipError_t e = launch_splitk_main(A, W_perm, splitk_ws, M, N, K, a_terms, splits, big, s);
         if (e != hipSuccess) return e;
         dim3 grid(((N / 128) * 16 + 255) / 256, M);
         splitk_reduce_rope_kernel<<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, rope);

@@ -109,8 +109,8 @@ hipError_t launch_gemm_f32(const float *A, const float *W, void *out, int M, int
 // SwiGLU result is written as [M, 2 * N/2] = hi | lo; 3 = fp16 (A and W hold IEEE half values, a SwiGLU
 // result is written as fp16).
 // splitk_ws (may be null): scratch for the split-K path that outputs with too few 128 x 128 tiles to fill the
-// chip take (gemm_splitk_factor > 1); it needs gemm_splitk_bytes(M, N, K * a_terms) bytes, otherwise the call
-// falls back to one workgroup per tile.
+// chip, and long k ranges over few 256 x 256 tiles, take (gemm_splitk_factor > 1); it needs
+// gemm_splitk_bytes(M, N, K * a_terms) bytes, otherwise the call falls back to one workgroup per tile.
 // pf (may be null; used by the SwiGLU epilogue's wide kernel only): memory the kernel reads once, front to back,
 // while it works, so that it sits in the last-level cache for the kernel that follows; n16 = 16-byte vectors.
 struct PrefetchArgs {
@@ -131,7 +131,7 @@ hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int 
                             const PrefetchArgs *pf = nullptr, const NormAfter *norm = nullptr, bool *norm_done = nullptr);
 hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms, const RopeArgs &rope,
                                  float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
-int gemm_splitk_factor(int M, int N, int K_total);
+int gemm_splitk_factor(int M, int N, int K_total, bool *big_tile = nullptr);   // *big_tile: slices of 256 x 256 tiles
 size_t gemm_splitk_bytes(int M, int N, int K_total);
 size_t gemm_splitk_max_bytes(int max_M, int N, int K_total);   // largest gemm_splitk_bytes over M <= max_M
 

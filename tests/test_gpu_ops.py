@@ -535,6 +535,49 @@ def test_gemm_bf16_split_k_for_short_outputs(M, epi, a_terms):
     cb.confspec_destroy(ctx)
 
 
+@pytest.mark.parametrize("M,N,K,a_terms,slices", [(3072, 1536, 4160, 1, 3), (2900, 1536, 4160, 3, 3), (2048, 2048, 4160, 1, 4),
+                                                  (3072, 1536, 2112, 2, 3), (3072, 1536, 1536, 1, 0)])
+def test_gemm_bf16_split_k_long_k_big_tiles(M, N, K, a_terms, slices):
+    """A long k range over an output of few 256 x 256 tiles: 3..6 k slices of such tiles, then the fixed-order sum.
+    `slices` is what the scratch size has to say (0: this shape is not split)."""
+    print(f"gemm bf16 big-tile split-K M={M} N={N} K={K} a_terms={a_terms}", flush=True)
+    ctx, _ = _ctx("bf16")
+    nbytes = cb.confspec_op_gemm_scratch_bytes(ctx, M, N, K, a_terms)
+    assert nbytes == slices * M * N * 4
+    full = _rand((M, K), torch.float32, 71)
+    if a_terms == 2:
+        hi = full.to(torch.bfloat16)
+        lo = (full - hi.float()).to(torch.bfloat16)
+        A = torch.cat([hi, lo], dim=1).contiguous()
+        a64 = f64(hi) + f64(lo)
+        Wt = _rand((N, K), torch.bfloat16, 72, 0.05)
+    elif a_terms == 3:
+        A = full.to(torch.float16)
+        a64 = f64(A)
+        Wt = _rand((N, K), torch.float32, 72, 0.05).to(torch.float16)
+    else:
+        A = full.to(torch.bfloat16)
+        a64 = f64(A)
+        Wt = _rand((N, K), torch.bfloat16, 72, 0.05)
+    ref = a64 @ f64(Wt).T
+    scratch = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=DEV)
+    x0 = _rand((M + 1, N), torch.float32, 73)
+    x = x0.clone()
+    cb.confspec_op_gemm(ctx, A, Wt, x, M, N, K, cb.EPI_RESID_F32, a_terms=a_terms, scratch=scratch)
+    torch.cuda.synchronize()
+    assert np.abs(f64(x[:M]) - (ref + f64(x0[:M]))).max() <= 2e-5 * max(np.abs(ref).max(), 4.0)
+    assert torch.equal(x[M:], x0[M:])
+    again = x0.clone()
+    cb.confspec_op_gemm(ctx, A, Wt, again, M, N, K, cb.EPI_RESID_F32, a_terms=a_terms, scratch=scratch)
+    torch.cuda.synchronize()
+    assert torch.equal(x, again)                      # fixed summation order
+    unsplit = x0.clone()                              # without scratch: one workgroup per tile, the whole k range
+    cb.confspec_op_gemm(ctx, A, Wt, unsplit, M, N, K, cb.EPI_RESID_F32, a_terms=a_terms)
+    torch.cuda.synchronize()
+    assert np.abs(f64(unsplit[:M]) - f64(x[:M])).max() <= 2e-5 * max(np.abs(ref).max(), 4.0)
+    cb.confspec_destroy(ctx)
+
+
 @pytest.mark.parametrize("M,N,K,scratch", [(300, 512, 192, False), (700, 256 * 90, 128, False), (32, 512, 2240, True),
                                            (3072, 1536, 128, False)])   # the last: one 192x96 tile per CU
 def test_gemm_fp16_operands_all_epilogues(M, N, K, scratch):
