@@ -130,10 +130,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     }
     int nk_w = K / BK;             // k-tiles of W
     int nk_all = nk_w * A_TERMS;   // k-tiles of A: hi half, then lo half
-    // Split-K launches (gridDim.y > 1, plain-store epilogue only): slice y takes the k-tiles [kb, kb + nk)
-    // and writes its partial product to the y-th [M, N] plane of the output.
-    const int kb = (int)(((long)blockIdx.y * nk_all) / gridDim.y);
-    const int nk = (int)(((long)(blockIdx.y + 1) * nk_all) / gridDim.y) - kb;
+    // Split-K launches (gridDim.y > 1, plain-store epilogue only): slice y takes the k-tiles y, y + s, y + 2s, ...
+    // (s = gridDim.y) and writes its partial product to the y-th [M, N] plane of the output.  The slices of a tile run
+    // at the same time on the same XCD and walk the k range together, so at any moment they ask for s adjacent 128-byte
+    // lines of an operand row rather than lines a slice length apart (worth 0.4 % of a pass against contiguous slices).
+    const int kstep = gridDim.y;
+    const int kb = blockIdx.y;
+    const int nk = (nk_all - kb + kstep - 1) / kstep;
     if (EPI == EPI_STORE_F32) out_v = reinterpret_cast<float *>(out_v) + (size_t)blockIdx.y * M * N;
     auto issue_loads = [&](int stage, int kt) {
         int kw = (A_TERMS == 2 && kt >= nk_w) ? kt - nk_w : kt;     // W wraps around for the lo half
@@ -168,9 +171,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     // tells that everybody is done with the stage the next loads will overwrite.
 #pragma unroll
     for (int t = 0; t < NS - 1; ++t)
-        if (t < nk) issue_loads(t, kb + t);
+        if (t < nk) issue_loads(t, kb + t * kstep);
     for (int ki = 0; ki < nk; ++ki) {
-        const int kt = kb + ki;
+        const int kt = kb + ki * kstep;
         int after = min(NS - 2, nk - 1 - ki);
         if (after >= 2) CS_WAIT_VMCNT(2 * PER_TILE);
         else if (after == 1) CS_WAIT_VMCNT(PER_TILE);
@@ -195,7 +198,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         // to save registers, and every group of MFMAs waits out its own LDS latency).
         read_frags(0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (ki + NS - 1 < nk) issue_loads((ki + NS - 1) % NS, kt + NS - 1);
+        if (ki + NS - 1 < nk) issue_loads((ki + NS - 1) % NS, kt + (NS - 1) * kstep);
         constexpr int EARLY = 2;   // MFMAs of a k-step issued before the next step's operand reads
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
@@ -515,6 +518,17 @@ int gemm_splitk_factor(int M, int N, int K_total, bool *big_tile) {
             return s;
         }
         return 1;
+    }
+    if (big_tile && M > 256 && N % 256 == 0 && nk >= 64) {
+        // Few tiles, more than 256 rows and a long k range: again 256 x 256 tiles, one workgroup per CU (d_model 5120, d_ffn 27648 over
+        // 480 rows: 38.9 ms per pass against 45.6 ms with 128 x 128 tiles; 288 rows: equal; 192 rows: 28.7 against 24.6 ms,
+        // hence the row bound).
+        int t256 = ((M + 255) / 256) * (N / 256);
+        int s = std::min(std::min(256 / t256, nk / 4), 64);
+        if (s >= 2) {
+            *big_tile = true;
+            return s;
+        }
     }
     int want = (384 + tiles / 2) / tiles;                // about 384 workgroups
     int s = std::min(want, nk / 4);                      // at least 4 k-tiles per slice
