@@ -129,7 +129,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         b_src[j] = reinterpret_cast<const char *>(W + (size_t)(n0 + row) * K + g * 8);
     }
     int nk_w = K / BK;             // k-tiles of W
-    int nk_all = nk_w * A_TERMS;   // k-tiles of A: hi half, then lo half
+    int nk_all = nk_w * A_TERMS;   // k-tiles of the loop: with two-term A, the hi and the lo tile of every W k-tile
     // Split-K launches (gridDim.y > 1, plain-store epilogue only): slice y takes the k-tiles y, y + s, y + 2s, ...
     // (s = gridDim.y) and writes its partial product to the y-th [M, N] plane of the output.  The slices of a tile run
     // at the same time on the same XCD and walk the k range together, so at any moment they ask for s adjacent 128-byte
@@ -139,11 +139,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     const int nk = (nk_all - kb + kstep - 1) / kstep;
     if (EPI == EPI_STORE_F32) out_v = reinterpret_cast<float *>(out_v) + (size_t)blockIdx.y * M * N;
     auto issue_loads = [&](int stage, int kt) {
-        int kw = (A_TERMS == 2 && kt >= nk_w) ? kt - nk_w : kt;     // W wraps around for the lo half
+        // Two-term A: k-tile kt pairs W k-tile kt / 2 with the hi (even kt) or lo (odd kt) half of A, so a W k-tile is
+        // asked for twice in a row (the second time it is still in L2) rather than once per sweep over K.
+        int kw = A_TERMS == 2 ? kt >> 1 : kt;
+        int ka = (A_TERMS == 2 && (kt & 1)) ? nk_w + kw : kw;
         unsigned char *base = smem + stage * STAGE;
 #pragma unroll
         for (int j = 0; j < A_DMA; ++j)
-            __builtin_amdgcn_global_load_lds((const CS_GLOBAL_AS void *)(a_src[j] + (size_t)kt * ROWB),
+            __builtin_amdgcn_global_load_lds((const CS_GLOBAL_AS void *)(a_src[j] + (size_t)ka * ROWB),
                                              (CS_LDS_AS void *)(base + (wave + NW * j) * 1024), 16, 0, 0);
 #pragma unroll
         for (int j = 0; j < B_DMA; ++j)

@@ -33,7 +33,7 @@ constexpr int ATTN_BM = 128;      // q rows per tile (bf16 MFMA kernel): 4 wavef
 constexpr int ATTN_THREADS = 256;
 constexpr int ATTN_BN = 64;       // keys per chunk
 constexpr int ATTN_TARGET_ITEMS = 512;
-constexpr int ATTN_MIN_CHUNKS_PER_ITEM = 8;
+constexpr int ATTN_MIN_CHUNKS_PER_ITEM = 4;   // shortest piece of a tile the planner cuts (decode-shaped batches: 4 is 2.6 % faster than 8)
 
 // Host-side mirror of the planner's counting pass (same arithmetic as the device code).
 struct AttnPlanCounts {

@@ -431,40 +431,72 @@ __global__ void verdict_kernel(const float *__restrict__ x, const int32_t *__res
 
 // Full-vocabulary statistics of one row of logits: arg max (lowest index on ties), its logit, and
 // lse = log sum_v exp z_v.  With verdict logits (fp32, n_verdict per row) also the largest full-vocabulary
-// probability among the verdict tokens, exp(max_v z_v - lse).  One workgroup per row.
-__global__ __launch_bounds__(256) void head_reduce_kernel(const float *__restrict__ logits, int V, const float *__restrict__ verdict_logits,
-                                                           int n_verdict, int32_t *__restrict__ token, float *__restrict__ max_logit,
-                                                           float *__restrict__ lse, float *__restrict__ conf_full) {
-    __shared__ float s_m[4], s_s[4];
-    __shared__ int s_i[4];
+// probability among the verdict tokens, exp(max_v z_v - lse).  One workgroup of 1024 threads per row, one pass:
+// every thread keeps (max, index of the max, sum of exp(z - max)) over its elements, read four at a time where the
+// row allows it, and the triples are merged pairwise; rescaling a sum when its reference maximum moves is the only
+// difference from the two-pass definition.
+struct HeadAcc {
+    float m;     // largest logit seen
+    int idx;     // its index, the lowest on ties
+    float s;     // sum of exp(z - m) over the elements seen
+};
+__device__ __forceinline__ void head_acc_add(HeadAcc &a, float v, int j) {
+    if (v > a.m) {                       // j grows within a thread, so a strict comparison keeps the lowest index
+        a.s = a.s * __expf(a.m - v) + 1.0f;   // exp(-inf) = 0 for the first element
+        a.m = v;
+        a.idx = j;
+    } else if (a.m > -INFINITY) {
+        a.s += __expf(v - a.m);
+    }
+}
+__device__ __forceinline__ HeadAcc head_acc_merge(const HeadAcc &a, const HeadAcc &b) {
+    if (b.m == -INFINITY) return a;
+    if (a.m == -INFINITY) return b;
+    HeadAcc r;
+    bool take_b = b.m > a.m || (b.m == a.m && b.idx < a.idx);
+    r.m = take_b ? b.m : a.m;
+    r.idx = take_b ? b.idx : a.idx;
+    r.s = a.s * __expf(a.m - r.m) + b.s * __expf(b.m - r.m);
+    return r;
+}
+constexpr int HEAD_REDUCE_THREADS = 1024;
+__global__ __launch_bounds__(HEAD_REDUCE_THREADS) void head_reduce_kernel(const float *__restrict__ logits, int V,
+                                                                           const float *__restrict__ verdict_logits, int n_verdict,
+                                                                           int32_t *__restrict__ token, float *__restrict__ max_logit,
+                                                                           float *__restrict__ lse, float *__restrict__ conf_full) {
+    constexpr int NWAVES = HEAD_REDUCE_THREADS / 64;
+    __shared__ float s_m[NWAVES], s_s[NWAVES];
+    __shared__ int s_i[NWAVES];
     int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float *z = logits + (size_t)b * V;
-    float m = -INFINITY;
-    int idx = 0x7fffffff;
-    for (int j = threadIdx.x; j < V; j += 256) {
-        float v = z[j];
-        if (v > m) { m = v; idx = j; }            // j grows per thread, so a thread keeps its lowest index
+    HeadAcc acc = {-INFINITY, 0x7fffffff, 0.f};
+    if ((V & 3) == 0 && (reinterpret_cast<uintptr_t>(z) & 15) == 0) {
+        const float4 *z4 = reinterpret_cast<const float4 *>(z);
+        int n4 = V >> 2;
+#pragma unroll 4
+        for (int j = threadIdx.x; j < n4; j += HEAD_REDUCE_THREADS) {
+            float4 v = z4[j];
+            head_acc_add(acc, v.x, 4 * j);
+            head_acc_add(acc, v.y, 4 * j + 1);
+            head_acc_add(acc, v.z, 4 * j + 2);
+            head_acc_add(acc, v.w, 4 * j + 3);
+        }
+    } else {
+        for (int j = threadIdx.x; j < V; j += HEAD_REDUCE_THREADS) head_acc_add(acc, z[j], j);
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
-        float om = __shfl_xor(m, off);
-        int oi = __shfl_xor(idx, off);
-        if (om > m || (om == m && oi < idx)) { m = om; idx = oi; }
+        HeadAcc o = {__shfl_xor(acc.m, off), __shfl_xor(acc.idx, off), __shfl_xor(acc.s, off)};
+        acc = head_acc_merge(acc, o);
     }
-    if (lane == 0) { s_m[wave] = m; s_i[wave] = idx; }
-    __syncthreads();
-    m = s_m[0]; idx = s_i[0];
-    for (int w = 1; w < 4; ++w)
-        if (s_m[w] > m || (s_m[w] == m && s_i[w] < idx)) { m = s_m[w]; idx = s_i[w]; }
-    float sum = 0.f;
-    for (int j = threadIdx.x; j < V; j += 256) sum += __expf(z[j] - m);
-    sum = wave_sum(sum);
-    if (lane == 0) s_s[wave] = sum;
+    if (lane == 0) { s_m[wave] = acc.m; s_i[wave] = acc.idx; s_s[wave] = acc.s; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        float l = m + logf(s_s[0] + s_s[1] + s_s[2] + s_s[3]);
-        token[b] = idx;
-        max_logit[b] = m;
+        HeadAcc t = {s_m[0], s_i[0], s_s[0]};
+        for (int w = 1; w < NWAVES; ++w) t = head_acc_merge(t, HeadAcc{s_m[w], s_i[w], s_s[w]});
+        float l = t.m + logf(t.s);
+        token[b] = t.idx;
+        max_logit[b] = t.m;
         lse[b] = l;
         if (conf_full && verdict_logits) {
             float zv = verdict_logits[(size_t)b * n_verdict];
@@ -476,7 +508,7 @@ __global__ __launch_bounds__(256) void head_reduce_kernel(const float *__restric
 
 hipError_t launch_head_reduce(const float *logits, int B, int V, const float *verdict_logits, int n_verdict, int32_t *token,
                               float *max_logit, float *lse, float *conf_full, hipStream_t s) {
-    head_reduce_kernel<<<B, 256, 0, s>>>(logits, V, verdict_logits, n_verdict, token, max_logit, lse, conf_full);
+    head_reduce_kernel<<<B, HEAD_REDUCE_THREADS, 0, s>>>(logits, V, verdict_logits, n_verdict, token, max_logit, lse, conf_full);
     return hipGetLastError();
 }
 

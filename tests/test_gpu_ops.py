@@ -377,7 +377,7 @@ def test_attention_bf16_split_kv_merge_matches_unsplit(split):
         err3 = _attention_case("bf16", 8, 8, 128, (130, 2500, 17, 900, 64, 1, 333, 1200, 5), (33, 5, 129, 64, 1, 200, 16, 77, 250))
         assert err2 <= 6e-3 and err3 <= 6e-3
     finally:
-        cb.confspec_tune("attn_min_chunks", 8)
+        cb.confspec_tune("attn_min_chunks", 4)
         cb.confspec_tune("attn_target_items", 512)
         cb.confspec_tune("attn_split", 0)
     print("  max abs err", err, flush=True)
@@ -634,7 +634,7 @@ def test_attention_bf16_fp16_output():
     try:
         err = _attention_case("bf16", 12, 2, 128, (700, 64), (40, 96), out_terms=3)     # through the merge kernel
     finally:
-        cb.confspec_tune("attn_min_chunks", 8)
+        cb.confspec_tune("attn_min_chunks", 4)
         cb.confspec_tune("attn_split", 0)
     assert err <= 6e-3
 
