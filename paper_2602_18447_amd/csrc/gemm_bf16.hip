@@ -444,6 +444,18 @@ static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, in
 // 7 = 192x96 / 6 waves (2 x 3, wave tile 96 x 32), BK 64 x 2 stages, for N % 96 == 0 and no SwiGLU.
 // Measured on the draft-model shapes: 4 is the fastest for the wide gate/up projection, 1 or 7 for the
 // others; the deeper pipelines (5, 6) pay more barriers than they hide latency.
+// 256 x 256 tiles (one workgroup per CU, rounds of 256) or 128 x 128 tiles (two per CU, rounds of 512) for an output
+// that is not split?  Measured time per k-tile of a round: 1.6 us for the large tile however full the round is; for the
+// small tile 1.1 us for a full round, 0.73 us when every CU holds at most one workgroup, in between linearly.
+static bool prefer_256_tiles(int M, int N) {
+    if (N % 256 != 0) return false;
+    long t128 = (long)((M + 127) / 128) * (N / 128), t256 = (long)((M + 255) / 256) * (N / 256);
+    long rem = t128 % 512;
+    double c128 = (double)(t128 / 512) * 1.1 + (rem == 0 ? 0.0 : rem <= 256 ? 0.73 : 0.73 + (double)(rem - 256) / 256.0 * 0.37);
+    double c256 = (double)((t256 + 255) / 256) * 1.6;
+    return c256 < c128;
+}
+
 template <int EPI>
 static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
                              int out_terms, hipStream_t s, const PrefetchArgs *pf = nullptr) {
@@ -455,7 +467,7 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
         // and done by a second launch with 128x128 tiles (two workgroups per CU), which is shorter.
         int tm = (M + 255) / 256, tn = N / 256;
         long t256 = (long)tm * tn;
-        if (N % 256 != 0 || t256 < 192) {
+        if (!prefer_256_tiles(M, N)) {
             // 128x128 tiles run two per CU; a count a little above 256 leaves most CUs with one workgroup, which
             // runs at well under the rate of two.  If the same output is at most 256 tiles of 192x96 (the same
             // flop per staged byte), one such tile per CU is the better cut: 3072 x 1536 = 288 -> 256 tiles.
@@ -507,7 +519,7 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
 // arrive from the L2 (a 256 x 256 tile needs half the bytes per flop), so there the k range is cut into 3..6 slices of
 // 256 x 256 tiles, one workgroup per CU, and the reduction pass that follows costs less than the tiles gain
 // (3072 x 1536 x 8960: 97 us with 3 slices against 106 us for 256 tiles of 192 x 96, and the reduction can also
-// normalise the rows for the next GEMM).  *big_tile says which case applies.
+// normalise the rows for the next GEMM).  From 256 k-tiles on two slices pay as well (1536 x 5120 x 27648).  *big_tile says which case applies.
 int gemm_splitk_factor(int M, int N, int K_total, bool *big_tile) {
     if (big_tile) *big_tile = false;
     if (N % 128 != 0) return 1;
@@ -516,7 +528,7 @@ int gemm_splitk_factor(int M, int N, int K_total, bool *big_tile) {
     if (M > 128 && tiles >= 256) {                       // enough 128 x 128 tiles to fill the chip without a split
         int t256 = ((M + 255) / 256) * (N / 256);
         int s = t256 > 0 ? 256 / t256 : 0;
-        if (big_tile && N % 256 == 0 && nk >= 64 && s >= 3 && s <= 6 && t256 * s >= 192) {
+        if (big_tile && N % 256 == 0 && nk >= 64 && s >= (nk >= 256 ? 2 : 3) && s <= 6 && t256 * s >= 192) {
             *big_tile = true;
             return s;
         }
@@ -786,8 +798,7 @@ hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N
         splitk_reduce_rope_kernel<<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, rope);
         return hipGetLastError();
     }
-    int tm = (M + 255) / 256, tn = N / 256;
-    if (N % 256 == 0 && (long)tm * tn >= 192)
+    if (prefer_256_tiles(M, N))
         return launch_tile<256, 256, 2, 4, 64, 2, EPI_ROPE>(A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
     return launch_tile<128, 128, 2, 2, 64, 2, EPI_ROPE>(A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
 }
