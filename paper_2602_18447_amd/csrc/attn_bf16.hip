@@ -720,18 +720,38 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnT
         int r = tile.row0 + row;
         if (r >= n_rows) return;
         float m_tot = -INFINITY;
-        for (int s = 0; s < tile.n_splits; ++s)
-            m_tot = fmaxf(m_tot, part_ml[((size_t)(tile.part_base + s) * ATTN_BM + row) * 2]);
         float l = 0.f;
         float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int s = 0; s < tile.n_splits; ++s) {
-            size_t rs = (size_t)(tile.part_base + s) * ATTN_BM + row;
-            float m_s = part_ml[rs * 2], l_s = part_ml[rs * 2 + 1];
-            if (m_s == -INFINITY) continue;   // this split saw no visible key for the row
-            float w = __builtin_amdgcn_exp2f(m_s - m_tot);
-            float4 v = *reinterpret_cast<const float4 *>(part_o + rs * HD + hv * 4);
-            l += w * l_s;
-            o.x += w * v.x; o.y += w * v.y; o.z += w * v.z; o.w += w * v.w;
+        if (tile.n_splits == 2) {
+            // the common case, same arithmetic as the loop below with every load issued before the first use
+            size_t rs0 = (size_t)tile.part_base * ATTN_BM + row, rs1 = rs0 + ATTN_BM;
+            float2 ml0 = *reinterpret_cast<const float2 *>(part_ml + rs0 * 2);
+            float2 ml1 = *reinterpret_cast<const float2 *>(part_ml + rs1 * 2);
+            float4 v0 = *reinterpret_cast<const float4 *>(part_o + rs0 * HD + hv * 4);
+            float4 v1 = *reinterpret_cast<const float4 *>(part_o + rs1 * HD + hv * 4);
+            m_tot = fmaxf(fmaxf(m_tot, ml0.x), ml1.x);
+            if (ml0.x != -INFINITY) {
+                float w = __builtin_amdgcn_exp2f(ml0.x - m_tot);
+                l += w * ml0.y;
+                o.x += w * v0.x; o.y += w * v0.y; o.z += w * v0.z; o.w += w * v0.w;
+            }
+            if (ml1.x != -INFINITY) {
+                float w = __builtin_amdgcn_exp2f(ml1.x - m_tot);
+                l += w * ml1.y;
+                o.x += w * v1.x; o.y += w * v1.y; o.z += w * v1.z; o.w += w * v1.w;
+            }
+        } else {
+            for (int s = 0; s < tile.n_splits; ++s)
+                m_tot = fmaxf(m_tot, part_ml[((size_t)(tile.part_base + s) * ATTN_BM + row) * 2]);
+            for (int s = 0; s < tile.n_splits; ++s) {
+                size_t rs = (size_t)(tile.part_base + s) * ATTN_BM + row;
+                float m_s = part_ml[rs * 2], l_s = part_ml[rs * 2 + 1];
+                if (m_s == -INFINITY) continue;   // this split saw no visible key for the row
+                float w = __builtin_amdgcn_exp2f(m_s - m_tot);
+                float4 v = *reinterpret_cast<const float4 *>(part_o + rs * HD + hv * 4);
+                l += w * l_s;
+                o.x += w * v.x; o.y += w * v.y; o.z += w * v.z; o.w += w * v.w;
+            }
         }
         float inv = 1.0f / l;
         int t = r / G, g = r - t * G;
