@@ -96,7 +96,7 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
 int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_stream stream);
 
 /* Process-wide settings.  "split_layers": number of leading layers in which confspec_verify carries
- * the GEMM activations as two bf16 terms (default -1 = ceil(n_layers / 7), doubled when d_model > 4096).  "attn_precise_layers"
+ * the GEMM activations with more than 8 mantissa bits (default -1 = the first half of the layers).  "attn_precise_layers"
  * (default 1): number of leading layers whose attention runs the two-term variant.  "first_layers_f16" (default 1; read by
  * confspec_pack_weights, which then makes the half copies, and by confspec_verify).  "fuse_rope" (default 1): confspec_verify runs the QKV projection of a bf16 model with the rotary
  * embedding in its epilogue (0: projection to fp32, then a separate kernel).  "prefetch_down" (default 1): while the

@@ -738,7 +738,12 @@ static hipError_t launch_splitk_tiles(const bf16 *A, const bf16 *W, float *part,
     }
     int tiles_m = (M + BT - 1) / BT, tiles_n = N / BT;
     dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8, splits);
-    kern<<<grid, 128 * WAVES_N, smem, s>>>(A, W, part, M, N, K, tiles_m, tiles_n, 0, tiles_m, 1, RopeArgs{}, PrefetchArgs{});
+    // tile order as in launch_inst: the tiles an XCD works on at one time (its share of the list; every slice of a tile
+    // lands on the same XCD) form a roughly square block, so that they ask the fabric for the fewest operand panels
+    int group_m = g_gemm_tune.group_m;
+    if (group_m <= 0) group_m = (int)std::lround(std::sqrt((double)std::min((tiles_m * tiles_n + 7) / 8, 32 * std::max(160 * 1024 / smem, 1))));
+    group_m = std::max(1, std::min(group_m, tiles_m));
+    kern<<<grid, 128 * WAVES_N, smem, s>>>(A, W, part, M, N, K, tiles_m, tiles_n, 0, group_m, 1, RopeArgs{}, PrefetchArgs{});
     return hipGetLastError();
 }
 
