@@ -376,7 +376,8 @@ def main():
                        batch.suffix_ids.cpu().numpy(), batch.h_cu_suffix, batch.h_prefix_lens, vids, taus,
                        trace_subset=list(range(n)))
         dt = time.time() - t0
-        dl = float(np.abs(outs[0].cpu().numpy()[:n] - ora["logits"]).max())
+        # eager_logits: the timed pass's own output (the optional legs above reuse the output buffers)
+        dl = float(np.abs(eager_logits.cpu().numpy()[:n] - ora["logits"]).max())
         cpu = dict(value=round(n / dt, 4), unit="verified steps/s", cores=_blas_threads(), kind="oracle",
                    sample=f"first {n} of {wl.B} traces of {wl.name}, fp64 numpy, {dt:.1f} s",
                    max_abs_dlogit_vs_gpu=dl)
