@@ -101,8 +101,8 @@ int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_
  * confspec_pack_weights, which then makes the half copies, and by confspec_verify).  "fuse_rope" (default 1): confspec_verify runs the QKV projection of a bf16 model with the rotary
  * embedding in its epilogue (0: projection to fp32, then a separate kernel).  "prefetch_down" (default 1): while the
  * gate/up projection of a bf16 layer runs, its workgroups also read the down projection's weights once, front to
- * back, so that they sit in the last-level cache when the down projection's strided tile loads ask for them (a hint:
- * results are bit-identical with 0).  "prune_last_layer" (default 1):
+ * back, so that they sit in the last-level cache when the down projection's strided tile loads ask for them (a hint,
+ * given where the down projection runs as one workgroup per tile: results are bit-identical with 0).  "prune_last_layer" (default 1):
  * in the last layer, compute attention rows, output projection and MLP for the last position of each trace only
  * (the only rows the verdict head reads; 0 computes every row).  Launch-shape tunables for
  * measurements: "gemm_tile" (0 heuristic, 1..7 = fixed workgroup tile / pipeline shape of the bf16 GEMM; a shape

@@ -599,9 +599,13 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         if (!mlp_norm_done) HIP_TRY(cs::launch_rmsnorm(c.dtype, xr, w->mlp_norm[l], hr, rows, d, c.rms_eps, tm, s));
         // the gate/up projection is compute-bound: while it runs it also pulls the down projection's weights, which
         // that kernel reads in strided pieces, into the last-level cache
+        // (a down projection cut into k slices of 256 x 256 tiles reads whole 128-byte lines of 256 rows at a time and
+        // does not gain from it: config 2 is 0.5 % faster without the hint, the unsplit shapes 0.1-0.2 % slower)
+        bool big_tiles = false;
+        const bool warm = g_prefetch_down && !(sk && cs::gemm_splitk_factor(rows, d, c.d_ffn * wide, &big_tiles) > 1);
         cs::PrefetchArgs pf;
-        pf.ptr = g_prefetch_down ? wdn : nullptr;
-        pf.n16 = g_prefetch_down ? (unsigned)((size_t)d * c.d_ffn * eb / 16) : 0u;
+        pf.ptr = warm ? wdn : nullptr;
+        pf.n16 = warm ? (unsigned)((size_t)d * c.d_ffn * eb / 16) : 0u;
         if ((rc = run_gemm(ctx, hr, wgu, act, rows, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s, sk, skb, &pf))) return rc;
         cs::NormAfter nb;
         const bool has_next = !last && l + 1 < c.n_layers;        // rows == T: the next layer normalises the same rows
