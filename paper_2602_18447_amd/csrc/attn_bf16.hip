@@ -511,10 +511,11 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             uint2 lo, hi;
-            lo.x = (vr[0][d] & 0xffffu) | (vr[1][d] << 16);
-            lo.y = (vr[2][d] & 0xffffu) | (vr[3][d] << 16);
-            hi.x = (vr[0][d] >> 16) | (vr[1][d] & 0xffff0000u);
-            hi.y = (vr[2][d] >> 16) | (vr[3][d] & 0xffff0000u);
+            // one byte permute per output word (low halves of two keys, high halves of two keys)
+            lo.x = __builtin_amdgcn_perm(vr[1][d], vr[0][d], 0x05040100u);
+            lo.y = __builtin_amdgcn_perm(vr[3][d], vr[2][d], 0x05040100u);
+            hi.x = __builtin_amdgcn_perm(vr[1][d], vr[0][d], 0x07060302u);
+            hi.y = __builtin_amdgcn_perm(vr[3][d], vr[2][d], 0x07060302u);
             *reinterpret_cast<uint2 *>(base + v_dst + (2 * d) * VT_STRIDE) = lo;
             *reinterpret_cast<uint2 *>(base + v_dst + (2 * d + 1) * VT_STRIDE) = hi;
         }
