@@ -519,7 +519,8 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
 // arrive from the L2 (a 256 x 256 tile needs half the bytes per flop), so there the k range is cut into 3..6 slices of
 // 256 x 256 tiles, one workgroup per CU, and the reduction pass that follows costs less than the tiles gain
 // (3072 x 1536 x 8960: 97 us with 3 slices against 106 us for 256 tiles of 192 x 96, and the reduction can also
-// normalise the rows for the next GEMM).  From 256 k-tiles on two slices pay as well (1536 x 5120 x 27648).  *big_tile says which case applies.
+// normalise the rows for the next GEMM).  From 256 k-tiles on two slices pay as well (1536 x 5120 x 27648).
+// *big_tile says which case applies.
 int gemm_splitk_factor(int M, int N, int K_total, bool *big_tile) {
     if (big_tile) *big_tile = false;
     if (N % 128 != 0) return 1;
@@ -535,9 +536,9 @@ int gemm_splitk_factor(int M, int N, int K_total, bool *big_tile) {
         return 1;
     }
     if (big_tile && M > 256 && N % 256 == 0 && nk >= 64) {
-        // Few tiles, more than 256 rows and a long k range: again 256 x 256 tiles, one workgroup per CU (d_model 5120, d_ffn 27648 over
-        // 480 rows: 38.9 ms per pass against 45.6 ms with 128 x 128 tiles; 288 rows: equal; 192 rows: 28.7 against 24.6 ms,
-        // hence the row bound).
+        // Few tiles, more than 256 rows and a long k range: again 256 x 256 tiles, one workgroup per CU (d_model 5120,
+        // d_ffn 27648 over 480 rows: 38.9 ms per pass against 45.6 ms with 128 x 128 tiles; 288 rows: equal; 192 rows:
+        // 28.7 against 24.6 ms, hence the row bound).
         int t256 = ((M + 255) / 256) * (N / 256);
         int s = std::min(std::min(256 / t256, nk / 4), 64);
         if (s >= 2) {
