@@ -18,7 +18,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 GEMM_SOURCE = os.path.join(ROOT, "paper_2602_18447_amd", "csrc", "gemm_bf16.hip")
-HBM_COUNTERS = os.path.join(ROOT, "paper_2602_18447_amd", "hbm_counters.json")
+HBM_COUNTERS = os.path.join(ROOT, "profiles", "gate_up_gemm_config2_hbm_counters.json")
 
 
 def _hbm_traffic():
@@ -146,7 +146,7 @@ def main():
     dev = "cuda:0"
     for kv_ in args.tune:
         key, _, val = kv_.partition("=")
-        cb.confspec_tune(key, int(val))
+        cb.confspec_tune(None, key, int(val))      # defaults of the contexts created below
     wl = W.config(args.config)
     m = wl.model
     weights = W.make_weights(m, wl.seed, dev)

@@ -1,6 +1,7 @@
 /*
  * confspec_append.h - the verification pass with write-back of accepted draft tokens into the paged cache
- * (Algorithm 1, Stage 3: the accepted draft steps join the context; Section 4.2 "Synchronization").
+ * (Algorithm 1, Stage 3; Section 4.2, "Stage 3: Context Management and Fallback": the accepted draft steps join
+ * the context).
  *
  * The suffix of a trace starts with the drafted step.  When (some of) its tokens are to join the context, their
  * keys and values are the ones the verification pass computes anyway; this entry point stores them instead of

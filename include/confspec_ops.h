@@ -89,31 +89,33 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
                              size_t workspace_bytes, float *dev_verdict_logits, float *dev_conf,
                              int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream);
 
-/* Measurement aid, not a step of the method: a plain device-to-device copy kernel (16 bytes per lane per
- * step) of `bytes` bytes, a multiple of 16, both pointers 16-byte aligned and the ranges disjoint.  It reads
- * and writes exactly `bytes` each, which makes it the yardstick that hardware HBM byte counters of the other
- * kernels are scaled by.  Returns CONFSPEC_E_INVALID_ARG on a null, misaligned or empty argument. */
-int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_stream stream);
-
-/* Process-wide settings.  "split_layers": number of leading layers in which confspec_verify carries
- * the GEMM activations with more than 8 mantissa bits (default -1 = the first half of the layers).  "attn_precise_layers"
- * (default 1): number of leading layers whose attention runs the two-term variant.  "first_layers_f16" (default 1; read by
- * confspec_pack_weights, which then makes the half copies, and by confspec_verify).  "fuse_rope" (default 1): confspec_verify runs the QKV projection of a bf16 model with the rotary
- * embedding in its epilogue (0: projection to fp32, then a separate kernel).  "prefetch_down" (default 1): while the
- * gate/up projection of a bf16 layer runs, its workgroups also read the down projection's weights once, front to
- * back, so that they sit in the last-level cache when the down projection's strided tile loads ask for them (a hint,
- * given where the down projection runs as one workgroup per tile: results are bit-identical with 0).  "prune_last_layer" (default 1):
- * in the last layer, compute attention rows, output projection and MLP for the last position of each trace only
- * (the only rows the verdict head reads; 0 computes every row).  Launch-shape tunables for
- * measurements: "gemm_tile" (0 heuristic, 1..7 = fixed workgroup tile / pipeline shape of the bf16 GEMM; a shape
- * that does not divide N falls back to 128x128),
- * "gemm_group_m" (0 heuristic, else tile rows per band of the GEMM's tile order), "gemm_splitk" (0 heuristic,
- * 1..64 = split-K factor of every bf16 GEMM that is given scratch; 1 = never split),
- * "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
- * "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = equal key-range pieces with that split factor,
- * 5 = front-loaded pieces).  Returns CONFSPEC_E_INVALID_ARG for an unknown key or a
- * value out of range. */
-int confspec_tune(const char *key, int32_t value);
+/* Settings of one context (ctx != NULL), or the defaults that contexts created afterwards start from (ctx == NULL).
+ * Nothing is process-wide at run time: two contexts in one process keep their own settings.  A setting that changes
+ * the workspace or packed-weight size ("attn_target_items", "gemm_splitk", "split_layers", "first_layers_f16") must be
+ * made before confspec_workspace_bytes / confspec_packed_bytes are asked; a call with too small a buffer fails with
+ * CONFSPEC_E_WORKSPACE.
+ *   "split_layers" (default -1 = the first half of the layers): number of leading layers in which confspec_verify
+ *       carries the GEMM activations with more than 8 mantissa bits.
+ *   "first_layers_f16" (default 1): those layers run on IEEE-half operands (read by confspec_pack_weights, which then
+ *       makes the half copies, and by confspec_verify); 0: two bf16 terms against the bf16 weights.  Stores in the
+ *       half format saturate at +-65504.
+ *   "attn_precise_layers" (default 1): number of leading layers whose attention runs the two-term variant.
+ *   "fuse_rope" (default 1): the QKV projection of a bf16 model applies the rotary embedding in its epilogue
+ *       (0: projection to fp32, then a separate kernel).
+ *   "prefetch_down" (default 1): while the gate/up projection of a bf16 layer runs, its workgroups also read the down
+ *       projection's weights once, front to back, so that they sit in the last-level cache when the down projection's
+ *       strided tile loads ask for them (given where the down projection runs one workgroup per tile; results are
+ *       bit-identical with 0).
+ *   "prune_last_layer" (default 1): in the last layer, attention rows, output projection and MLP are computed for the
+ *       last position of each trace only (the only rows the verdict head reads; 0 computes every row).
+ *   Launch shapes, for measurements: "gemm_tile" (0 heuristic; 1 = 128x128, 4 = 256x256, 7 = 192x96 workgroup tiles; a
+ *       shape that does not divide N falls back to 128x128), "gemm_group_m" (0 heuristic, else tile rows per band of
+ *       the GEMM's tile order), "gemm_splitk" (0 heuristic, 1..64 = split-K factor of every bf16 GEMM that is given
+ *       scratch; 1 = never split), "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
+ *       "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = equal key-range pieces with that split factor,
+ *       5 = front-loaded pieces), "attn_kernel" (0 = default main loop, 1 = the register-staged main loop).
+ * Returns CONFSPEC_E_INVALID_ARG for an unknown key or a value out of range. */
+int confspec_tune(confspec_ctx *ctx, const char *key, int32_t value);
 
 #ifdef __cplusplus
 }

@@ -386,30 +386,36 @@ NOT_REACHED = -1
 
 def cascade_request(draft_verdict: Sequence[int], draft_conf: Sequence[float], target_verdict, gamma: float,
                     accept_index: int = 0):
-    """The verification loop of one request, step by step as the algorithm states it.
+    """Cascaded verification of the k drafted steps of one request.
+
+    Written from the definitions rather than as a loop with a counter: Eq. 4 defines the cascaded decision
+    V_j of a step as a function of the step alone (the small model's decision where its confidence reaches
+    gamma, the large model's otherwise), and the number of accepted steps m is the length of the longest
+    run of accepted steps from the start (Section 4.2: steps are accepted up to the first rejection).
 
     draft_verdict[j], draft_conf[j]: the small model's decision on step j and its confidence.
-    target_verdict: callable j -> the large model's decision on step j; it is called only for the
-    steps the loop escalates (confidence below gamma), in order.
-    Returns (m, decision, escalated): m = number of leading accepted steps; decision[j] = the
-    cascaded decision V of step j for the steps the loop reached (up to and including the first
-    rejection), NOT_REACHED after that; escalated[j] = 1 where the large model was consulted.
+    target_verdict: callable j -> the large model's decision on step j.  It is expensive, so V_j is
+    evaluated on demand and the search for the first rejection goes in step order: the callable is
+    invoked exactly for the low-confidence steps up to and including the first rejection, in order,
+    once each.
+    Returns (m, decision, escalated): decision[j] = V_j for the steps up to and including the first
+    rejection, NOT_REACHED after that; escalated[j] = 1 where the large model was consulted.
     """
     k = len(draft_verdict)
-    decision = [NOT_REACHED] * k
-    escalated = [0] * k
-    m = 0
-    for j in range(k):
-        if float(draft_conf[j]) >= float(gamma):      # Eq. 4, first case: keep the small model's decision
-            v = int(draft_verdict[j])
-        else:                                         # second case: the large model decides
-            v = int(target_verdict(j))
-            escalated[j] = 1
-        decision[j] = v
-        if v == accept_index:
-            m += 1
-        else:
-            break                                     # verification stops at the first rejection
+    kept = [float(draft_conf[j]) >= float(gamma) for j in range(k)]       # Eq. 4: which case applies to step j
+    asked = {}
+
+    def V(j):                                                            # Eq. 4
+        if kept[j]:
+            return int(draft_verdict[j])
+        if j not in asked:
+            asked[j] = int(target_verdict(j))
+        return asked[j]
+
+    m = next((j for j in range(k) if V(j) != accept_index), k)           # first rejected step; k if none
+    looked_at = min(m + 1, k)
+    decision = [V(j) if j < looked_at else NOT_REACHED for j in range(k)]
+    escalated = [int(j < looked_at and not kept[j]) for j in range(k)]
     return m, decision, escalated
 
 

@@ -108,8 +108,6 @@ def _load() -> C.CDLL:
     lib.confspec_op_verdict_gate.restype = C.c_int
     lib.confspec_op_verdict_gate.argtypes = [vp, P(Batch), vp, vp, vp, P(i32), i32, P(C.c_float), i32, vp, sz,
                                              vp, vp, vp, vp, vp]
-    lib.confspec_op_copy.restype = C.c_int
-    lib.confspec_op_copy.argtypes = [vp, vp, sz, vp]
     lib.confspec_verify_append.restype = C.c_int
     lib.confspec_verify_append.argtypes = [vp, P(Weights), P(KV), P(Batch), vp, P(i32), P(i32), i32, P(C.c_float), i32,
                                            vp, sz, vp, vp, vp, vp, vp]
@@ -124,7 +122,7 @@ def _load() -> C.CDLL:
     lib.confspec_cascade.argtypes = [vp, P(Weights), P(KV), vp, sz, vp, P(Weights), P(KV), vp, sz, P(Batch), P(Requests),
                                      P(i32), i32, C.c_float, vp, sz, P(CascadeOut), P(i32), vp]
     lib.confspec_tune.restype = C.c_int
-    lib.confspec_tune.argtypes = [C.c_char_p, i32]
+    lib.confspec_tune.argtypes = [vp, C.c_char_p, i32]
     return lib
 
 
@@ -133,7 +131,7 @@ lib = _load()
 EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec_last_error",
             "confspec_workspace_bytes", "confspec_packed_bytes", "confspec_pack_weights", "confspec_verify",
             "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_qkv_rope", "confspec_op_attention",
-            "confspec_op_verdict_gate", "confspec_op_copy", "confspec_tune", "confspec_cascade_scratch_bytes",
+            "confspec_op_verdict_gate", "confspec_tune", "confspec_cascade_scratch_bytes",
             "confspec_cascade", "confspec_verify_append", "confspec_head_scratch_bytes", "confspec_generate_step"]
 
 
@@ -295,12 +293,6 @@ def confspec_op_verdict_gate(ctx, batch: Batch, x, final_norm, lm_head, verdict_
                                              _ptr(verdict), _ptr(accept), _stream_handle(stream)))
 
 
-def confspec_op_copy(src, dst, nbytes: int, stream=None) -> None:
-    rc = lib.confspec_op_copy(_ptr(src), _ptr(dst), int(nbytes), _stream_handle(stream))
-    if rc != OK:
-        raise ConfSpecError(rc, f"confspec_op_copy({nbytes})")
-
-
 def confspec_cascade_scratch_bytes(max_B: int, max_T: int, max_blocks_per_seq_target: int) -> int:
     return int(lib.confspec_cascade_scratch_bytes(max_B, max_T, max_blocks_per_seq_target))
 
@@ -334,8 +326,9 @@ def make_requests(req_start, h_req_start, parent=None, h_parent=None):
     return Requests(len(hr) - 1, _ptr(req_start), hr.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(parent), hp_ptr), (hr, hp)
 
 
-def confspec_tune(key: str, value: int) -> None:
-    rc = lib.confspec_tune(key.encode(), int(value))
+def confspec_tune(ctx, key: str, value: int) -> None:
+    """ctx: a context, or None for the defaults of contexts created afterwards."""
+    rc = lib.confspec_tune(ctx, key.encode(), int(value))
     if rc != OK:
         raise ConfSpecError(rc, f"confspec_tune({key!r}, {value})")
 

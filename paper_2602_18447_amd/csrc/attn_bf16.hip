@@ -37,14 +37,6 @@ constexpr int ATTN_SMEM_BYTES = 2 * ATTN_STAGE * 2;
 
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// launch-shape tunables (process-wide)
-static int g_target_items = ATTN_TARGET_ITEMS;
-static int g_min_chunks = ATTN_MIN_CHUNKS_PER_ITEM;
-static int g_force_split = 0;   // 0 = choose by the makespan estimate, 1..4 = fixed split factor
-void attn_set_split(int s) { g_force_split = s; }
-void attn_set_tune(int target_items, int min_chunks) { g_target_items = target_items; g_min_chunks = min_chunks; }
-void attn_get_tune(int *target_items, int *min_chunks) { *target_items = g_target_items; *min_chunks = g_min_chunks; }
-
 // ---- planning: identical arithmetic on host (counts only) and device (counts + lists) ----
 // Every tile of a trace is cut into n_split pieces of `piece` chunks (the last piece takes what is
 // left and may be empty for the trace's shorter tiles).  Two ways to choose the pieces:
@@ -135,10 +127,11 @@ __host__ __device__ inline void plan_emit_trace(int b, int L, int S, int G, int 
         }
 }
 
-void attn_plan_capacity(int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles, int64_t *max_items) {
+void attn_plan_capacity(const AttnTune &tune, int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles,
+                        int64_t *max_items) {
     int64_t tiles = (int64_t)Hkv * ((G * max_T + ATTN_BM - 1) / ATTN_BM + max_B);
     *max_tiles = tiles;
-    *max_items = 3 * tiles + 4 * g_target_items;     // candidates that need more are not considered
+    *max_items = 3 * tiles + 4 * tune.target_items;     // candidates that need more are not considered
 }
 
 namespace {
@@ -211,7 +204,9 @@ double simulate(const std::vector<int> *lens, int slots) {
 // Choice of the pieces: equal pieces with a split factor 1..4 of the average tile, or front-loaded
 // pieces of 1.07x / 1.2x the per-slot share of all chunks; the candidate with the smallest simulated
 // makespan (+ 8 chunk-times for the merge pass when anything is split) wins.
-AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv, int last_only) {
+AttnPlanCounts attn_plan_counts(const AttnTune &tune, const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv,
+                                int last_only) {
+    const int g_target_items = tune.target_items, g_min_chunks = tune.min_chunks, g_force_split = tune.force_split;
     AttnPlanCounts r = {};
     std::vector<TraceShape> tr;
     tr.reserve(B);
@@ -346,7 +341,7 @@ __device__ __forceinline__ void store_out4(bf16 *o, size_t row_w, int fmt, const
     if (fmt == 3) {
         union { __half h[4]; uint2 u; } ph;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) ph.h[j] = __float2half_rn(v[j]);
+        for (int j = 0; j < 4; ++j) ph.h[j] = to_half_sat(v[j]);
         *reinterpret_cast<uint2 *>(o) = ph.u;
         return;
     }
@@ -768,13 +763,10 @@ template <bool PRECISE>
 static hipError_t launch_attn_variant(const AttnArgs &a, const AttnItem *items, const int32_t *counts, int n_items_host,
                                       int max_xcd_items, float *part_o, float *part_ml, hipStream_t s) {
     constexpr int smem = PRECISE ? 2 * ATTN_SMEM_BYTES : ATTN_SMEM_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel<PRECISE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint32_t> attr_done{0};
+    if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(attn_bf16_kernel<PRECISE>), smem);
+        e != hipSuccess)
+        return e;
     int grid = 8 * max_xcd_items;
     attn_bf16_kernel<PRECISE><<<grid, ATTN_THREADS, smem, s>>>(a, items, counts, n_items_host, part_o, part_ml);
     return hipGetLastError();

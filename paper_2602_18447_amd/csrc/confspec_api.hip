@@ -1,7 +1,8 @@
 // Host side of the C ABI: argument validation, workspace carving and the launch sequence of the
-// batched verification pass.  No device memory is allocated here and the stream is never
-// synchronised; every check that can be made from host-visible arguments happens before the first
-// launch.
+// batched verification pass.  No device memory is allocated here; every check that can be made from
+// host-visible arguments happens before the first launch.  confspec_verify, confspec_verify_append and
+// confspec_generate_step never synchronise the stream; confspec_cascade synchronises it once (the
+// large model's launches are planned from the number of escalated traces).
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -17,41 +18,40 @@
 #include "../../include/confspec_generate.h"
 #include "kernels.h"
 
-namespace cs {
-void gemm_set_tile(int t);
-void gemm_set_group_m(int g);
-void gemm_set_splitk(int s);
-void attn_set_tune(int target_items, int min_chunks);
-void attn_get_tune(int *target_items, int *min_chunks);
-void attn_set_split(int s);
-}  // namespace cs
+// Settings of one context (confspec_tune).  A new context starts from the defaults below.
+struct Settings {
+    // Number of leading layers whose GEMM activations carry more than 8 mantissa bits (fp16 operands, or two bf16
+    // terms); -1 = derive from the model: the first half of the layers.  The logit error falls steadily with that
+    // number (28 layers, d_model 1536, 32 traces: max 0.0176 with 4 such layers, 0.0108 with 8, 0.0062 with 14,
+    // 0.0040 with 28) while the pass time rises by 0.6 % from 4 to 14.
+    int split_layers = -1;
+    // Number of leading layers whose attention runs the two-term variant (q, suffix k / v, probabilities).
+    int attn_precise_layers = 1;
+    // 1: the last layer's attention rows, output projection and MLP run on the last position of each trace only
+    int prune_last_layer = 1;
+    // 1: the first layers (the split_layers rule) run their GEMMs on fp16 operands when the packed weights carry
+    // fp16 copies; 0: they use two-term bf16 activations against the bf16 weights
+    int first_layers_f16 = 1;
+    // 1: bf16 models run the QKV projection with the rotary embedding in its epilogue (reordered weight rows)
+    int fuse_rope = 1;
+    // The gate/up projection warms the last-level cache with the down projection's weights.
+    int prefetch_down = 1;
+    cs::GemmTune gemm;
+    cs::AttnTune attn;
+};
+
+static Settings g_default_settings;   // what a new context starts from; changed by confspec_tune(NULL, ...)
 
 struct confspec_ctx {
     confspec_model_cfg cfg;
     int device;
+    Settings set;
     std::string err;
 };
 
-// Number of leading layers whose GEMM activations carry more than 8 mantissa bits (fp16 operands, or two bf16
-// terms; process-wide); -1 = derive from the model: the first half of the layers.  The logit error falls steadily
-// with that number (28 layers, d_model 1536, 32 traces: max 0.0176 with 4 such layers, 0.0108 with 8, 0.0062 with 14,
-// 0.0040 with 28) while the pass time rises by 0.6 % from 4 to 14.
-static int g_split_layers = -1;
-// Number of leading layers whose attention runs the two-term variant (q, suffix k / v, probabilities).
-static int g_attn_precise_layers = 1;
-// 1: the last layer's attention rows, output projection and MLP run on the last position of each trace only
-static int g_prune_last_layer = 1;
-// 1: the first layers (the split_layers rule) run their GEMMs on fp16 operands when the packed weights carry
-// fp16 copies; 0: they use two-term bf16 activations against the bf16 weights
-static int g_first_layers_f16 = 1;
-// 1: bf16 models run the QKV projection with the rotary embedding in its epilogue (reordered weight rows)
-static int g_fuse_rope = 1;
-// The gate/up projection warms the last-level cache with the down projection's weights (process-wide switch).
-static int g_prefetch_down = 1;
-
-static int split_layers_for(const confspec_model_cfg &c) {
-    if (g_split_layers >= 0) return g_split_layers;
-    return (c.n_layers + 1) / 2;
+static int split_layers_for(const confspec_ctx *ctx) {
+    if (ctx->set.split_layers >= 0) return ctx->set.split_layers;
+    return (ctx->cfg.n_layers + 1) / 2;
 }
 
 namespace {
@@ -80,7 +80,8 @@ struct WsLayout {
     int64_t max_tiles, max_items, max_tiles2, max_items2;
 };
 
-WsLayout ws_layout(const confspec_model_cfg &c, int64_t T, int64_t B) {
+WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B) {
+    const confspec_model_cfg &c = ctx->cfg;
     WsLayout w = {};
     size_t at = 0;
     auto take = [&](size_t bytes) {
@@ -110,7 +111,7 @@ WsLayout ws_layout(const confspec_model_cfg &c, int64_t T, int64_t B) {
     w.attn = take((size_t)T * qw * eb * terms);
     w.act = take((size_t)T * c.d_ffn * eb * terms);
     if (c.dtype == CONFSPEC_DTYPE_BF16) {
-        cs::attn_plan_capacity(T, B, c.n_q_heads / c.n_kv_heads, c.n_kv_heads, &w.max_tiles, &w.max_items);
+        cs::attn_plan_capacity(ctx->set.attn, T, B, c.n_q_heads / c.n_kv_heads, c.n_kv_heads, &w.max_tiles, &w.max_items);
         w.plan_counts = take(256);
         w.plan_tiles = take((size_t)w.max_tiles * sizeof(cs::AttnTile));
         w.plan_items = take((size_t)w.max_items * sizeof(cs::AttnItem));
@@ -131,10 +132,10 @@ WsLayout ws_layout(const confspec_model_cfg &c, int64_t T, int64_t B) {
         // pass over few tokens), in both activation widths
         size_t sk = 0;
         for (int t = 1; t <= 2; ++t) {
-            sk = std::max(sk, cs::gemm_splitk_max_bytes((int)T, (int)(qw + 2 * kw), c.d_model * t));
-            sk = std::max(sk, cs::gemm_splitk_max_bytes((int)T, c.d_model, (int)qw * t));
-            sk = std::max(sk, cs::gemm_splitk_max_bytes((int)T, 2 * c.d_ffn, c.d_model * t));
-            sk = std::max(sk, cs::gemm_splitk_max_bytes((int)T, c.d_model, c.d_ffn * t));
+            sk = std::max(sk, cs::gemm_splitk_max_bytes(ctx->set.gemm, (int)T, (int)(qw + 2 * kw), c.d_model * t));
+            sk = std::max(sk, cs::gemm_splitk_max_bytes(ctx->set.gemm, (int)T, c.d_model, (int)qw * t));
+            sk = std::max(sk, cs::gemm_splitk_max_bytes(ctx->set.gemm, (int)T, 2 * c.d_ffn, c.d_model * t));
+            sk = std::max(sk, cs::gemm_splitk_max_bytes(ctx->set.gemm, (int)T, c.d_model, c.d_ffn * t));
         }
         w.splitk_bytes = sk;
         w.splitk = take(std::max<size_t>(sk, 256));
@@ -236,6 +237,18 @@ int check_ws(const confspec_ctx *ctx, const void *ws, size_t have, size_t need) 
     return CONFSPEC_OK;
 }
 
+// The calling thread's current HIP device must be the one the context was created for: the library never switches
+// devices, and kernels launched on another device would read pointers that are not valid there.
+int check_device(const confspec_ctx *ctx) {
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return fail(ctx, CONFSPEC_E_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (cur != ctx->device)
+        return fail(ctx, CONFSPEC_E_INVALID_ARG, "the context was created for device %d but the current device is %d",
+                    ctx->device, cur);
+    return CONFSPEC_OK;
+}
+
 #define HIP_TRY(expr)                                                                                   \
     do {                                                                                                \
         hipError_t e__ = (expr);                                                                        \
@@ -249,7 +262,7 @@ int run_gemm(confspec_ctx *ctx, const void *A, const void *W, void *out, int M, 
     if (ctx->cfg.dtype == CONFSPEC_DTYPE_FP32) {
         HIP_TRY(cs::launch_gemm_f32((const float *)A, (const float *)W, out, M, N, K, epi, s));
     } else {
-        HIP_TRY(cs::launch_gemm_bf16((const cs::bf16 *)A, (const cs::bf16 *)W, out, M, N, K, epi, a_terms, out_terms,
+        HIP_TRY(cs::launch_gemm_bf16(ctx->set.gemm, (const cs::bf16 *)A, (const cs::bf16 *)W, out, M, N, K, epi, a_terms, out_terms,
                                      splitk_ws, splitk_bytes, s, pf, norm, norm_done));
     }
     return CONFSPEC_OK;
@@ -296,7 +309,7 @@ int run_attn_plan(confspec_ctx *ctx, const confspec_batch *b, int max_L, char *w
     const confspec_model_cfg &c = ctx->cfg;
     int G = c.n_q_heads / c.n_kv_heads;
     int64_t cap_tiles = last_only ? L.max_tiles2 : L.max_tiles, cap_items = last_only ? L.max_items2 : L.max_items;
-    *pc = cs::attn_plan_counts(b->h_cu_suffix, b->h_prefix_lens, b->B, G, c.n_kv_heads, last_only ? 1 : 0);
+    *pc = cs::attn_plan_counts(ctx->set.attn, b->h_cu_suffix, b->h_prefix_lens, b->B, G, c.n_kv_heads, last_only ? 1 : 0);
     if (pc->n_tiles > cap_tiles || pc->n_items > cap_items)
         return fail(ctx, CONFSPEC_E_WORKSPACE, "attention plan (%lld tiles, %lld items) exceeds workspace capacity",
                     (long long)pc->n_tiles, (long long)pc->n_items);
@@ -346,6 +359,7 @@ int confspec_create(const confspec_model_cfg *cfg, int device, confspec_ctx **ou
     if (!ctx) return CONFSPEC_E_INVALID_ARG;
     ctx->cfg = c;
     ctx->device = device;
+    ctx->set = g_default_settings;
     *out = ctx;
     return CONFSPEC_OK;
 }
@@ -358,15 +372,16 @@ int confspec_workspace_bytes(const confspec_ctx *ctx, int32_t max_T, int32_t max
                              size_t *out_bytes) {
     if (!ctx || !out_bytes) return CONFSPEC_E_INVALID_ARG;
     if (max_T < 1 || max_B < 1 || max_sum_L < 0) return fail(ctx, CONFSPEC_E_INVALID_ARG, "max_T, max_B must be >= 1, max_sum_L >= 0");
-    *out_bytes = ws_layout(ctx->cfg, max_T, max_B).total;
+    *out_bytes = ws_layout(ctx, max_T, max_B).total;
     return CONFSPEC_OK;
 }
 
 namespace {
 // fp16 copies are made for the layers that would otherwise run with two-term activations
-int f16_layers_for(const confspec_model_cfg &c) {
-    if (c.dtype != CONFSPEC_DTYPE_BF16 || !g_first_layers_f16) return 0;
-    return std::min(c.n_layers, split_layers_for(c));
+int f16_layers_for(const confspec_ctx *ctx) {
+    const confspec_model_cfg &c = ctx->cfg;
+    if (c.dtype != CONFSPEC_DTYPE_BF16 || !ctx->set.first_layers_f16) return 0;
+    return std::min(c.n_layers, split_layers_for(ctx));
 }
 struct PackLayout {
     size_t gate_up;        // bytes of one packed gate/up matrix (aligned)
@@ -375,7 +390,8 @@ struct PackLayout {
     size_t elems[4];
     size_t total;
 };
-PackLayout pack_layout(const confspec_model_cfg &c) {
+PackLayout pack_layout(const confspec_ctx *ctx) {
+    const confspec_model_cfg &c = ctx->cfg;
     PackLayout p = {};
     size_t qw = (size_t)c.n_q_heads * c.head_dim, kw = (size_t)c.n_kv_heads * c.head_dim;
     p.gate_up = align_up((size_t)2 * c.d_ffn * c.d_model * elem_bytes(c.dtype));
@@ -386,14 +402,14 @@ PackLayout pack_layout(const confspec_model_cfg &c) {
     size_t per16 = 0;
     for (int i = 0; i < 4; ++i) { p.f16[i] = align_up(p.elems[i] * 2); per16 += p.f16[i]; }
     p.qkv_perm = c.dtype == CONFSPEC_DTYPE_BF16 ? align_up(p.elems[0] * 2) : 0;
-    p.total = (size_t)c.n_layers * (p.gate_up + p.qkv_perm) + (size_t)f16_layers_for(c) * per16;
+    p.total = (size_t)c.n_layers * (p.gate_up + p.qkv_perm) + (size_t)f16_layers_for(ctx) * per16;
     return p;
 }
 }  // namespace
 
 int confspec_packed_bytes(const confspec_ctx *ctx, size_t *out_bytes) {
     if (!ctx || !out_bytes) return CONFSPEC_E_INVALID_ARG;
-    *out_bytes = pack_layout(ctx->cfg).total;
+    *out_bytes = pack_layout(ctx).total;
     return CONFSPEC_OK;
 }
 
@@ -404,11 +420,11 @@ int confspec_pack_weights(confspec_ctx *ctx, const confspec_weights *in, void *d
     if (in->packed != 0) return fail(ctx, CONFSPEC_E_INVALID_ARG, "input weights are already packed");
     const confspec_model_cfg &c = ctx->cfg;
     if (c.d_ffn % 32) return fail(ctx, CONFSPEC_E_UNSUPPORTED, "d_ffn must be a multiple of 32");
-    PackLayout P = pack_layout(c);
+    PackLayout P = pack_layout(ctx);
     if (!dev_dst || ((uintptr_t)dev_dst & 255)) return fail(ctx, CONFSPEC_E_WORKSPACE, "dev_dst null or not 256-byte aligned");
     if (dst_bytes < P.total) return fail(ctx, CONFSPEC_E_WORKSPACE, "dev_dst has %zu bytes, %zu needed", dst_bytes, P.total);
     if (c.n_layers > 0 && !in->w_gate_up) return fail(ctx, CONFSPEC_E_INVALID_ARG, "w_gate_up is null");
-    int n16 = f16_layers_for(c);
+    int n16 = f16_layers_for(ctx);
     const bool bf = c.dtype == CONFSPEC_DTYPE_BF16;
     if (c.n_layers > 0 && ((bf && !in->wqkv) || (n16 > 0 && (!in->wo || !in->w_down))))
         return fail(ctx, CONFSPEC_E_INVALID_ARG, "a per-layer weight array is null");
@@ -417,6 +433,7 @@ int confspec_pack_weights(confspec_ctx *ctx, const confspec_weights *in, void *d
         if ((bf && !in->wqkv[l]) || (l < n16 && (!in->wo[l] || !in->w_down[l])))
             return fail(ctx, CONFSPEC_E_INVALID_ARG, "layer %d has a null weight pointer", l);
     }
+    if (int rd = check_device(ctx)) return rd;
     hipStream_t s = (hipStream_t)stream;
     const int n = c.n_layers;
     for (int i = 0; i < 6 * n; ++i) h_ptr_storage[i] = nullptr;
@@ -482,7 +499,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     if ((rc = check_kv(ctx, kv, max_L > 0)) != CONFSPEC_OK) return rc;
     cs::VerdictArgs va = {};
     if (want_verdict && (rc = check_verdict(ctx, h_verdict_ids, n_verdict, h_tau, n_tau, &va)) != CONFSPEC_OK) return rc;
-    WsLayout L = ws_layout(c, batch->T, batch->B);
+    WsLayout L = ws_layout(ctx, batch->T, batch->B);
     if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
     HeadLayout HL = {};
     if (ex.head) {
@@ -507,6 +524,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         }
     }
 
+    if ((rc = check_device(ctx)) != CONFSPEC_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)dev_workspace;
     int T = batch->T, B = batch->B, d = c.d_model;
@@ -519,7 +537,8 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
     // Only the last position of each trace feeds the verdict head, so everything of the last layer that
     // comes after its keys and values - attention rows, output projection, MLP - runs on those B rows.
-    const bool prune = c.dtype == CONFSPEC_DTYPE_BF16 && g_prune_last_layer && c.n_layers > 0;
+    const Settings &set = ctx->set;
+    const bool prune = c.dtype == CONFSPEC_DTYPE_BF16 && set.prune_last_layer && c.n_layers > 0;
     if (prune && (rc = run_attn_plan(ctx, batch, max_L, ws, L, true, &pc_last, s)) != CONFSPEC_OK) return rc;
     HIP_TRY(cs::launch_rope_table((const int32_t *)(ws + L.tok_pos), T, c.head_dim, c.rope_theta,
                                   (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
@@ -531,11 +550,11 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     // The projection kernel that rotates q and k itself reads wqkv with reordered rows (the half copy has that
     // order too, so fp16 layers depend on it).
     auto rope_fused_in = [&](int l) {
-        return c.dtype == CONFSPEC_DTYPE_BF16 && g_fuse_rope && c.head_dim == 128 && w->wqkv_perm && w->wqkv_perm[l];
+        return c.dtype == CONFSPEC_DTYPE_BF16 && set.fuse_rope && c.head_dim == 128 && w->wqkv_perm && w->wqkv_perm[l];
     };
     auto format_of = [&](int l) {
-        if (!(c.dtype == CONFSPEC_DTYPE_BF16 && l < split_layers_for(c))) return 1;
-        if (rope_fused_in(l) && g_first_layers_f16 && l < w->n_f16_layers && w->wqkv_f16 && w->wo_f16 && w->w_gate_up_f16 &&
+        if (!(c.dtype == CONFSPEC_DTYPE_BF16 && l < split_layers_for(ctx))) return 1;
+        if (rope_fused_in(l) && set.first_layers_f16 && l < w->n_f16_layers && w->wqkv_f16 && w->wo_f16 && w->w_gate_up_f16 &&
             w->w_down_f16 && w->wqkv_f16[l] && w->wo_f16[l] && w->w_gate_up_f16[l] && w->w_down_f16[l])
             return 3;
         return 2;
@@ -549,7 +568,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
             wqkv = w->wqkv_f16[l]; wo = w->wo_f16[l]; wgu = w->w_gate_up_f16[l]; wdn = w->w_down_f16[l];
         }
         const int wide = tm == 2 ? 2 : 1;      // buffer width multiplier of the activation format
-        bool prec = c.dtype == CONFSPEC_DTYPE_BF16 && l < g_attn_precise_layers;
+        bool prec = c.dtype == CONFSPEC_DTYPE_BF16 && l < set.attn_precise_layers;
         bool last = prune && l == c.n_layers - 1;
         float *sk = c.dtype == CONFSPEC_DTYPE_BF16 ? (float *)(ws + L.splitk) : nullptr;   // for outputs of few tiles
         size_t skb = sk ? L.splitk_bytes : 0;
@@ -559,7 +578,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
             cs::RopeArgs ra = {(const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin), ws + L.q, ws + L.ksuf,
                                ws + L.vsuf, prec ? ws + L.q_lo : nullptr, prec ? ws + L.ksuf_lo : nullptr,
                                prec ? ws + L.vsuf_lo : nullptr, c.n_q_heads, c.n_kv_heads};
-            HIP_TRY(cs::launch_gemm_bf16_rope((const cs::bf16 *)h, (const cs::bf16 *)(tm == 3 ? wqkv : w->wqkv_perm[l]), T,
+            HIP_TRY(cs::launch_gemm_bf16_rope(set.gemm, (const cs::bf16 *)h, (const cs::bf16 *)(tm == 3 ? wqkv : w->wqkv_perm[l]), T,
                                               qw + 2 * kw, d, tm, ra, sk, skb, s));
         } else {
             if ((rc = run_gemm(ctx, h, wqkv, qkv, T, qw + 2 * kw, d, cs::EPI_STORE_F32, tm, 1, s, sk, skb))) return rc;
@@ -602,7 +621,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         // (a down projection cut into k slices of 256 x 256 tiles reads whole 128-byte lines of 256 rows at a time and
         // does not gain from it: config 2 is 0.5 % faster without the hint, the unsplit shapes 0.1-0.2 % slower)
         bool big_tiles = false;
-        const bool warm = g_prefetch_down && !(sk && cs::gemm_splitk_factor(rows, d, c.d_ffn * wide, &big_tiles) > 1);
+        const bool warm = set.prefetch_down && !(sk && cs::gemm_splitk_factor(set.gemm, rows, d, c.d_ffn * wide, &big_tiles) > 1);
         cs::PrefetchArgs pf;
         pf.ptr = warm ? wdn : nullptr;
         pf.n16 = warm ? (unsigned)((size_t)d * c.d_ffn * eb / 16) : 0u;
@@ -726,13 +745,14 @@ int confspec_op_gemm(confspec_ctx *ctx, const void *dev_A, const void *dev_W, vo
     } else if (N % 64 || K % 16) {
         return fail(ctx, CONFSPEC_E_UNSUPPORTED, "fp32 GEMM needs N %% 64 == 0 and K %% 16 == 0");
     }
+    if ((rc = check_device(ctx))) return rc;
     return run_gemm(ctx, dev_A, dev_W, dev_out, M, N, K, epilogue, a_terms, out_terms, (hipStream_t)stream,
                     (float *)dev_scratch, dev_scratch ? scratch_bytes : 0);
 }
 
 size_t confspec_op_gemm_scratch_bytes(const confspec_ctx *ctx, int32_t M, int32_t N, int32_t K, int32_t a_terms) {
     if (!ctx || ctx->cfg.dtype != CONFSPEC_DTYPE_BF16 || M < 1 || N < 1 || K < 1 || a_terms < 1 || a_terms > 3) return 0;
-    return cs::gemm_splitk_bytes(M, N, K * (a_terms == 2 ? 2 : 1));
+    return cs::gemm_splitk_bytes(ctx->set.gemm, M, N, K * (a_terms == 2 ? 2 : 1));
 }
 
 int confspec_op_rmsnorm(confspec_ctx *ctx, const float *dev_x, const void *dev_g, void *dev_out, int32_t n_rows,
@@ -741,6 +761,7 @@ int confspec_op_rmsnorm(confspec_ctx *ctx, const float *dev_x, const void *dev_g
     if (!dev_x || !dev_g || !dev_out || n_rows < 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "bad argument");
     int rc;
     if ((rc = check_terms(ctx, out_terms, "out_terms"))) return rc;
+    if ((rc = check_device(ctx))) return rc;
     HIP_TRY(cs::launch_rmsnorm(ctx->cfg.dtype, dev_x, dev_g, dev_out, n_rows, ctx->cfg.d_model, ctx->cfg.rms_eps,
                                out_terms, (hipStream_t)stream));
     return CONFSPEC_OK;
@@ -764,9 +785,10 @@ int confspec_op_rope_split(confspec_ctx *ctx, const confspec_batch *batch, int32
     int rc, max_L = 0;
     if ((rc = check_batch(ctx, batch, max_prefix_len, &max_L)) != CONFSPEC_OK) return rc;
     const confspec_model_cfg &c = ctx->cfg;
-    WsLayout L = ws_layout(c, batch->T, batch->B);
+    WsLayout L = ws_layout(ctx, batch->T, batch->B);
     if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
     char *ws = (char *)dev_workspace;
+    if (int rd = check_device(ctx)) return rd;
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(cs::launch_prep(batch->cu_suffix, batch->prefix_lens, batch->B, batch->T, max_L, (int32_t *)(ws + L.tok_trace),
                             (int32_t *)(ws + L.tok_pos), (int32_t *)(ws + L.last_row), s));
@@ -791,9 +813,10 @@ int confspec_op_qkv_rope(confspec_ctx *ctx, const confspec_batch *batch, int32_t
     int rc, max_L = 0;
     if ((rc = check_terms(ctx, a_terms, "a_terms"))) return rc;
     if ((rc = check_batch(ctx, batch, max_prefix_len, &max_L)) != CONFSPEC_OK) return rc;
-    WsLayout L = ws_layout(c, batch->T, batch->B);
+    WsLayout L = ws_layout(ctx, batch->T, batch->B);
     if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
     char *ws = (char *)dev_workspace;
+    if (int rd = check_device(ctx)) return rd;
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(cs::launch_prep(batch->cu_suffix, batch->prefix_lens, batch->B, batch->T, max_L, (int32_t *)(ws + L.tok_trace),
                             (int32_t *)(ws + L.tok_pos), (int32_t *)(ws + L.last_row), s));
@@ -801,7 +824,7 @@ int confspec_op_qkv_rope(confspec_ctx *ctx, const confspec_batch *batch, int32_t
                                   (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
     cs::RopeArgs ra = {(const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin), dev_q, dev_k, dev_v,
                        dev_q_lo, dev_k_lo, dev_v_lo, c.n_q_heads, c.n_kv_heads};
-    HIP_TRY(cs::launch_gemm_bf16_rope((const cs::bf16 *)dev_h, (const cs::bf16 *)dev_wqkv_perm, batch->T,
+    HIP_TRY(cs::launch_gemm_bf16_rope(ctx->set.gemm, (const cs::bf16 *)dev_h, (const cs::bf16 *)dev_wqkv_perm, batch->T,
                                       (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, c.d_model, a_terms, ra,
                                       (float *)(ws + L.splitk), L.splitk_bytes, s));
     return CONFSPEC_OK;
@@ -821,9 +844,10 @@ int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confsp
     int rc, max_L = 0;
     if ((rc = check_batch(ctx, batch, (int64_t)kv->max_blocks_per_seq * kv->block_size, &max_L)) != CONFSPEC_OK) return rc;
     if ((rc = check_kv(ctx, kv, max_L > 0)) != CONFSPEC_OK) return rc;
-    WsLayout L = ws_layout(ctx->cfg, batch->T, batch->B);
+    WsLayout L = ws_layout(ctx, batch->T, batch->B);
     if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
     char *ws = (char *)dev_workspace;
+    if (int rd = check_device(ctx)) return rd;
     hipStream_t s = (hipStream_t)stream;
     cs::AttnPlanCounts pc;
     if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
@@ -845,9 +869,10 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
     cs::VerdictArgs va;
     if ((rc = check_verdict(ctx, h_verdict_ids, n_verdict, h_tau, n_tau, &va)) != CONFSPEC_OK) return rc;
     const confspec_model_cfg &c = ctx->cfg;
-    WsLayout L = ws_layout(c, batch->T, batch->B);
+    WsLayout L = ws_layout(ctx, batch->T, batch->B);
     if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
     char *ws = (char *)dev_workspace;
+    if (int rd = check_device(ctx)) return rd;
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(cs::launch_prep(batch->cu_suffix, batch->prefix_lens, batch->B, batch->T, max_L, (int32_t *)(ws + L.tok_trace),
                             (int32_t *)(ws + L.tok_pos), (int32_t *)(ws + L.last_row), s));
@@ -857,57 +882,33 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
     return CONFSPEC_OK;
 }
 
-int confspec_op_copy(const void *dev_src, void *dev_dst, size_t bytes, confspec_stream stream) {
-    if (!dev_src || !dev_dst || bytes == 0 || bytes % 16 != 0) return CONFSPEC_E_INVALID_ARG;
-    if (((uintptr_t)dev_src | (uintptr_t)dev_dst) & 15) return CONFSPEC_E_INVALID_ARG;
-    if (cs::launch_copy16(dev_src, dev_dst, bytes / 16, (hipStream_t)stream) != hipSuccess) return CONFSPEC_E_HIP;
-    return CONFSPEC_OK;
-}
-
-int confspec_tune(const char *key, int32_t value) {
+int confspec_tune(confspec_ctx *ctx, const char *key, int32_t value) {
     if (!key) return CONFSPEC_E_INVALID_ARG;
-    int ti, mc;
-    cs::attn_get_tune(&ti, &mc);
-    if (!strcmp(key, "gemm_tile")) {
-        if (value < 0 || value > 7) return CONFSPEC_E_INVALID_ARG;
-        cs::gemm_set_tile(value);
-    } else if (!strcmp(key, "gemm_group_m")) {
-        if (value < 0 || value > 65536) return CONFSPEC_E_INVALID_ARG;
-        cs::gemm_set_group_m(value);
-    } else if (!strcmp(key, "gemm_splitk")) {
-        if (value < 0 || value > 64) return CONFSPEC_E_INVALID_ARG;
-        cs::gemm_set_splitk(value);
-    } else if (!strcmp(key, "split_layers")) {
-        if (value < -1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
-        g_split_layers = value;
-    } else if (!strcmp(key, "prefetch_down")) {
-        if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
-        g_prefetch_down = value;
-    } else if (!strcmp(key, "fuse_rope")) {
-        if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
-        g_fuse_rope = value;
-    } else if (!strcmp(key, "first_layers_f16")) {
-        if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
-        g_first_layers_f16 = value;
-    } else if (!strcmp(key, "prune_last_layer")) {
-        if (value < 0 || value > 1) return CONFSPEC_E_INVALID_ARG;
-        g_prune_last_layer = value;
-    } else if (!strcmp(key, "attn_precise_layers")) {
-        if (value < 0 || value > 4096) return CONFSPEC_E_INVALID_ARG;
-        g_attn_precise_layers = value;
-    } else if (!strcmp(key, "attn_target_items")) {
-        if (value < 1 || value > 65536) return CONFSPEC_E_INVALID_ARG;
-        cs::attn_set_tune(value, mc);
-    } else if (!strcmp(key, "attn_split")) {
-        if (value < 0 || value > 5) return CONFSPEC_E_INVALID_ARG;
-        cs::attn_set_split(value);
-    } else if (!strcmp(key, "attn_min_chunks")) {
-        if (value < 1 || value > 4096) return CONFSPEC_E_INVALID_ARG;
-        cs::attn_set_tune(ti, value);
-    } else {
-        return CONFSPEC_E_INVALID_ARG;
-    }
-    return CONFSPEC_OK;
+    Settings &st = ctx ? ctx->set : g_default_settings;
+    struct Entry { const char *key; int *field; int lo, hi; };
+    const Entry table[] = {
+        {"gemm_tile", &st.gemm.tile, 0, 7},
+        {"gemm_group_m", &st.gemm.group_m, 0, 65536},
+        {"gemm_splitk", &st.gemm.splitk, 0, 64},
+        {"split_layers", &st.split_layers, -1, 4096},
+        {"prefetch_down", &st.prefetch_down, 0, 1},
+        {"fuse_rope", &st.fuse_rope, 0, 1},
+        {"first_layers_f16", &st.first_layers_f16, 0, 1},
+        {"prune_last_layer", &st.prune_last_layer, 0, 1},
+        {"attn_precise_layers", &st.attn_precise_layers, 0, 4096},
+        {"attn_target_items", &st.attn.target_items, 1, 65536},
+        {"attn_split", &st.attn.force_split, 0, 5},
+        {"attn_min_chunks", &st.attn.min_chunks, 1, 4096},
+        {"attn_kernel", &st.attn.kernel, 0, 1},
+    };
+    for (const Entry &e : table)
+        if (!strcmp(key, e.key)) {
+            if (value < e.lo || value > e.hi) return CONFSPEC_E_INVALID_ARG;
+            if (e.field == &st.gemm.tile && value != 0 && value != 1 && value != 4 && value != 7) return CONFSPEC_E_INVALID_ARG;
+            *e.field = value;
+            return CONFSPEC_OK;
+        }
+    return CONFSPEC_E_INVALID_ARG;
 }
 
 // ---- two-tier cascade (Section 4.2, Eq. 4; Algorithm 1, Stage 2) ----
@@ -987,9 +988,10 @@ int confspec_cascade(confspec_ctx *draft, const confspec_weights *wd, const conf
     CascadeLayout C = cascade_layout(B, T, kvt->max_blocks_per_seq);
     if ((rc = check_ws(ctx, dev_scratch, scratch_bytes, C.total)) != CONFSPEC_OK) return rc;
     // the large model's pass is a sub-batch of this one, so a workspace for the whole batch is enough for it
-    if ((rc = check_ws(ctx, ws_t, ws_t_bytes, ws_layout(target->cfg, T, B).total)) != CONFSPEC_OK) return rc;
+    if ((rc = check_ws(ctx, ws_t, ws_t_bytes, ws_layout(target, T, B).total)) != CONFSPEC_OK) return rc;
     if (!wt || wt->packed != 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "target weights must be packed with confspec_pack_weights");
 
+    if (int rd = check_device(ctx)) return rd;
     hipStream_t s = (hipStream_t)stream;
     char *sc = (char *)dev_scratch;
     uint8_t *keep = (uint8_t *)(sc + C.keep);

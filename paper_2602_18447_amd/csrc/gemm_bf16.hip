@@ -40,16 +40,6 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 #define CS_GLOBAL_AS __attribute__((address_space(1)))
 #define CS_LDS_AS __attribute__((address_space(3)))
 
-struct GemmTune {
-    int tile;      // 0 = heuristic; see launch_epi for the ids
-    int group_m;   // 0 = heuristic; otherwise tile rows per band of the tile order
-    int splitk;    // 0 = heuristic; otherwise the split-K factor of every GEMM that has scratch (1 = never split)
-};
-static GemmTune g_gemm_tune = {0, 0, 0};
-void gemm_set_splitk(int s) { g_gemm_tune.splitk = s; }
-void gemm_set_tile(int t) { g_gemm_tune.tile = t; }
-void gemm_set_group_m(int g) { g_gemm_tune.group_m = g; }
-
 // one 32x32x16 MFMA on 16-bit operands held as bf16x8 bit patterns: bf16 or (F16) IEEE half
 template <bool F16>
 __device__ inline f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -289,7 +279,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
                     unsigned hi[8];
                     if (out_fmt == 3) {
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) hi[q] = __half_as_ushort(__float2half_rn(v[q]));
+                        for (int q = 0; q < 8; ++q) hi[q] = __half_as_ushort(to_half_sat(v[q]));
                     } else {
 #pragma unroll
                         for (int q = 0; q < 8; ++q) hi[q] = __bfloat16_as_ushort(__float2bfloat16(v[q]));
@@ -391,24 +381,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
 // are different kernels (and show up under different names in a kernel trace).
 // Launches the kernel on the column range [n_base, n_base + n_cols) of the N columns.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int A_FMT>
-static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base, int n_cols,
-                              int out_terms, hipStream_t s, const RopeArgs *rope = nullptr, const PrefetchArgs *pf = nullptr) {
+static hipError_t launch_inst(const GemmTune &tune, const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base,
+                              int n_cols, int out_terms, hipStream_t s, const RopeArgs *rope = nullptr,
+                              const PrefetchArgs *pf = nullptr) {
     constexpr int smem = NS * (BM + BN) * BK * 2;
-    static bool attr_set = false;
+    static std::atomic<uint32_t> attr_done{0};
     auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, A_FMT>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
     int tiles_m = (M + BM - 1) / BM, tiles_n = n_cols / BN;
     int n_tiles = tiles_m * tiles_n;
     int grid = ((n_tiles + 7) / 8) * 8;
     // Workgroups of one XCD that run at the same time: its share of the tiles, at most 32 CUs x the
     // workgroups that fit one CU's 160 KiB of LDS.  A square block of that many tiles, weighted by the
     // tile's aspect, has sqrt(resident * BN / BM) rows.
-    int group_m = g_gemm_tune.group_m;
+    int group_m = tune.group_m;
     if (group_m <= 0) {
         int fit = 160 * 1024 / smem;
         int resident = std::min((n_tiles + 7) / 8, 32 * std::max(fit, 1));
@@ -421,29 +407,27 @@ static hipError_t launch_inst(const bf16 *A, const bf16 *W, void *out, int M, in
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI>
-static hipError_t launch_tile(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base, int n_cols,
-                              int a_fmt, int out_fmt, hipStream_t s, const RopeArgs *rope = nullptr,
+static hipError_t launch_tile(const GemmTune &tune, const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base,
+                              int n_cols, int a_fmt, int out_fmt, hipStream_t s, const RopeArgs *rope = nullptr,
                               const PrefetchArgs *pf = nullptr) {
     if (a_fmt == 2)
-        return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
+        return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(tune, A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
     if (a_fmt == 3) {
         // fp16 operands: built for the tile shapes the default choice uses
         constexpr bool has_f16 = BK == 64 && NS == 2 && ((BM == 128 && BN == 128 && WAVES_M == 2 && WAVES_N == 2) ||
                                                            (BM == 256 && BN == 256 && WAVES_M == 2 && WAVES_N == 4) ||
                                                            (BM == 192 && BN == 96 && WAVES_M == 2 && WAVES_N == 3));
         if constexpr (has_f16)
-            return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 3>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
+            return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 3>(tune, A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
         else
             return hipErrorInvalidValue;
     }
-    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
+    return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 1>(tune, A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
 }
 
-// Tile ids: 1 = 128x128 / 4 waves, 2 = 256x256 / 4 waves, 3 = 256x128 / 4 waves, 4 = 256x256 / 8 waves
-// (all BK 64 x 2 stages); 5 = 128x128 / 4 waves and 6 = 256x256 / 8 waves with BK 32 x 4 stages;
-// 7 = 192x96 / 6 waves (2 x 3, wave tile 96 x 32), BK 64 x 2 stages, for N % 96 == 0 and no SwiGLU.
-// Measured on the draft-model shapes: 4 is the fastest for the wide gate/up projection, 1 or 7 for the
-// others; the deeper pipelines (5, 6) pay more barriers than they hide latency.
+// Tile ids: 1 = 128x128 / 4 waves, 4 = 256x256 / 8 waves, 7 = 192x96 / 6 waves (2 x 3, wave tile 96 x 32; for
+// N % 96 == 0 and no SwiGLU); all with 64-element k-tiles in 2 stages.  Measured on the draft-model shapes: 4 is the
+// fastest for the wide gate/up projection, 1 or 7 for the others.
 // 256 x 256 tiles (one workgroup per CU, rounds of 256) or 128 x 128 tiles (two per CU, rounds of 512) for an output
 // that is not split?  Measured time per k-tile of a round: 1.6 us for the large tile however full the round is; for the
 // small tile 1.1 us for a full round, 0.73 us when every CU holds at most one workgroup, in between linearly.
@@ -457,10 +441,9 @@ static bool prefer_256_tiles(int M, int N) {
 }
 
 template <int EPI>
-static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
+static hipError_t launch_epi(const GemmTune &tune, const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int a_terms,
                              int out_terms, hipStream_t s, const PrefetchArgs *pf = nullptr) {
-    int tile = g_gemm_tune.tile;
-    if (a_terms == 3 && tile != 1 && tile != 4 && tile != 7) tile = 0;   // fp16 operands exist for the default shapes only
+    int tile = tune.tile;
     if (tile == 0) {
         // Wide outputs take 256x256 tiles, one workgroup per CU, in rounds of 256 tiles.  A last round
         // that would be less than half full costs as much as a full one, so those columns are cut off
@@ -474,9 +457,9 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
             if constexpr (EPI != EPI_SWIGLU) {
                 long t128 = (long)((M + 127) / 128) * (N / 128), t192 = (long)((M + 191) / 192) * (N / 96);
                 if (N % 96 == 0 && t128 > 256 && t128 <= 384 && t192 <= 256)
-                    return launch_tile<192, 96, 2, 3, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+                    return launch_tile<192, 96, 2, 3, 64, 2, EPI>(tune, A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
             }
-            return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+            return launch_tile<128, 128, 2, 2, 64, 2, EPI>(tune, A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
         }
         long rounds = t256 / 256;
         int n1 = tn;
@@ -485,26 +468,22 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
             if ((long)(tn - full) * tm <= 128) n1 = full;
         }
         if (n1 > 0) {
-            hipError_t e = launch_tile<256, 256, 2, 4, 64, 2, EPI>(A, W, out, M, N, K, 0, n1 * 256, a_terms, out_terms, s, nullptr, pf);
+            hipError_t e = launch_tile<256, 256, 2, 4, 64, 2, EPI>(tune, A, W, out, M, N, K, 0, n1 * 256, a_terms, out_terms, s, nullptr, pf);
             if (e != hipSuccess) return e;
         }
         if (n1 < tn)
-            return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, n1 * 256, N - n1 * 256, a_terms,
+            return launch_tile<128, 128, 2, 2, 64, 2, EPI>(tune, A, W, out, M, N, K, n1 * 256, N - n1 * 256, a_terms,
                                                            out_terms, s);
         return hipSuccess;
     }
-    if ((tile == 2 || tile == 4 || tile == 6) && N % 256 != 0) tile = 1;
+    if (tile == 4 && N % 256 != 0) tile = 1;
     if (tile == 7 && (N % 96 != 0 || EPI == EPI_SWIGLU)) tile = 1;
     switch (tile) {
-        case 2: return launch_tile<256, 256, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
-        case 3: return launch_tile<256, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
-        case 4: return launch_tile<256, 256, 2, 4, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
-        case 5: return launch_tile<128, 128, 2, 2, 32, 4, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
-        case 6: return launch_tile<256, 256, 2, 4, 32, 4, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        case 4: return launch_tile<256, 256, 2, 4, 64, 2, EPI>(tune, A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
         case 7:
-            if constexpr (EPI != EPI_SWIGLU) return launch_tile<192, 96, 2, 3, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+            if constexpr (EPI != EPI_SWIGLU) return launch_tile<192, 96, 2, 3, 64, 2, EPI>(tune, A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
             else return hipErrorInvalidValue;   // not reached: a SwiGLU column pair needs 64-column wave tiles
-        default: return launch_tile<128, 128, 2, 2, 64, 2, EPI>(A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        default: return launch_tile<128, 128, 2, 2, 64, 2, EPI>(tune, A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
     }
 }
 
@@ -521,11 +500,11 @@ static hipError_t launch_epi(const bf16 *A, const bf16 *W, void *out, int M, int
 // (3072 x 1536 x 8960: 97 us with 3 slices against 106 us for 256 tiles of 192 x 96, and the reduction can also
 // normalise the rows for the next GEMM).  From 256 k-tiles on two slices pay as well (1536 x 5120 x 27648).
 // *big_tile says which case applies.
-int gemm_splitk_factor(int M, int N, int K_total, bool *big_tile) {
+int gemm_splitk_factor(const GemmTune &tune, int M, int N, int K_total, bool *big_tile) {
     if (big_tile) *big_tile = false;
     if (N % 128 != 0) return 1;
     int tiles = ((M + 127) / 128) * (N / 128), nk = K_total / 64;
-    if (g_gemm_tune.splitk > 0) return std::max(1, std::min(g_gemm_tune.splitk, nk / 4));
+    if (tune.splitk > 0) return std::max(1, std::min(tune.splitk, nk / 4));
     if (M > 128 && tiles >= 256) {                       // enough 128 x 128 tiles to fill the chip without a split
         int t256 = ((M + 255) / 256) * (N / 256);
         int s = t256 > 0 ? 256 / t256 : 0;
@@ -550,16 +529,16 @@ int gemm_splitk_factor(int M, int N, int K_total, bool *big_tile) {
     int s = std::min(want, nk / 4);                      // at least 4 k-tiles per slice
     return std::max(1, std::min(s, 64));
 }
-size_t gemm_splitk_bytes(int M, int N, int K_total) {
+size_t gemm_splitk_bytes(const GemmTune &tune, int M, int N, int K_total) {
     bool big;
-    int s = gemm_splitk_factor(M, N, K_total, &big);
+    int s = gemm_splitk_factor(tune, M, N, K_total, &big);
     return s > 1 ? (size_t)s * M * N * 4 : 0;
 }
 // Largest gemm_splitk_bytes over all row counts up to max_M (the factor changes with the number of row tiles).
-size_t gemm_splitk_max_bytes(int max_M, int N, int K_total) {
+size_t gemm_splitk_max_bytes(const GemmTune &tune, int max_M, int N, int K_total) {
     size_t best = 0;
     for (int tm = 1; tm <= (max_M + 127) / 128; ++tm)
-        best = std::max(best, gemm_splitk_bytes(std::min(tm * 128, max_M), N, K_total));
+        best = std::max(best, gemm_splitk_bytes(tune, std::min(tm * 128, max_M), N, K_total));
     return best;
 }
 
@@ -586,7 +565,7 @@ __global__ void splitk_reduce_kernel(const float *__restrict__ part, int splits,
         for (int q = 0; q < 4; ++q) {
             float act = g[q] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[q])) * u[q];
             if (out_terms == 3) {
-                hi[q] = __half_as_ushort(__float2half_rn(act));
+                hi[q] = __half_as_ushort(to_half_sat(act));
                 lo[q] = 0;
             } else {
                 bf16 h = __float2bfloat16(act);
@@ -712,7 +691,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_resid_norm_kernel(const flo
         for (int q = 0; q < 4; ++q) {
             float y = v[i][q] * rinv * gv[q];
             if (terms == 3) {
-                hi[q] = __half_as_ushort(__float2half_rn(y));
+                hi[q] = __half_as_ushort(to_half_sat(y));
                 lo[q] = 0;
             } else {
                 bf16 hh = __float2bfloat16(y);
@@ -726,22 +705,17 @@ __global__ __launch_bounds__(256) void splitk_reduce_resid_norm_kernel(const flo
 }
 
 template <int A_FMT, int BT, int WAVES_N>
-static hipError_t launch_splitk_tiles(const bf16 *A, const bf16 *W, float *part, int M, int N, int K, int splits,
-                                      hipStream_t s) {
+static hipError_t launch_splitk_tiles(const GemmTune &tune, const bf16 *A, const bf16 *W, float *part, int M, int N, int K,
+                                      int splits, hipStream_t s) {
     constexpr int smem = 2 * (BT + BT) * 64 * 2;
-    static bool attr_set = false;
+    static std::atomic<uint32_t> attr_done{0};
     auto kern = gemm_bf16_kernel<BT, BT, 2, WAVES_N, 64, 2, EPI_STORE_F32, A_FMT>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
     int tiles_m = (M + BT - 1) / BT, tiles_n = N / BT;
     dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8, splits);
     // tile order as in launch_inst: the tiles an XCD works on at one time (its share of the list; every slice of a tile
     // lands on the same XCD) form a roughly square block, so that they ask the fabric for the fewest operand panels
-    int group_m = g_gemm_tune.group_m;
+    int group_m = tune.group_m;
     if (group_m <= 0) group_m = (int)std::lround(std::sqrt((double)std::min((tiles_m * tiles_n + 7) / 8, 32 * std::max(160 * 1024 / smem, 1))));
     group_m = std::max(1, std::min(group_m, tiles_m));
     kern<<<grid, 128 * WAVES_N, smem, s>>>(A, W, part, M, N, K, tiles_m, tiles_n, 0, group_m, 1, RopeArgs{}, PrefetchArgs{});
@@ -749,26 +723,26 @@ static hipError_t launch_splitk_tiles(const bf16 *A, const bf16 *W, float *part,
 }
 
 // The partial products of the k slices, one [M, N] fp32 plane per slice; big_tile: 256 x 256 tiles, else 128 x 128.
-static hipError_t launch_splitk_main(const bf16 *A, const bf16 *W, float *part, int M, int N, int K, int a_terms,
-                                     int splits, bool big_tile, hipStream_t s) {
+static hipError_t launch_splitk_main(const GemmTune &tune, const bf16 *A, const bf16 *W, float *part, int M, int N, int K,
+                                     int a_terms, int splits, bool big_tile, hipStream_t s) {
     if (big_tile)
-        return a_terms == 2   ? launch_splitk_tiles<2, 256, 4>(A, W, part, M, N, K, splits, s)
-               : a_terms == 3 ? launch_splitk_tiles<3, 256, 4>(A, W, part, M, N, K, splits, s)
-                              : launch_splitk_tiles<1, 256, 4>(A, W, part, M, N, K, splits, s);
-    return a_terms == 2   ? launch_splitk_tiles<2, 128, 2>(A, W, part, M, N, K, splits, s)
-           : a_terms == 3 ? launch_splitk_tiles<3, 128, 2>(A, W, part, M, N, K, splits, s)
-                          : launch_splitk_tiles<1, 128, 2>(A, W, part, M, N, K, splits, s);
+        return a_terms == 2   ? launch_splitk_tiles<2, 256, 4>(tune, A, W, part, M, N, K, splits, s)
+               : a_terms == 3 ? launch_splitk_tiles<3, 256, 4>(tune, A, W, part, M, N, K, splits, s)
+                              : launch_splitk_tiles<1, 256, 4>(tune, A, W, part, M, N, K, splits, s);
+    return a_terms == 2   ? launch_splitk_tiles<2, 128, 2>(tune, A, W, part, M, N, K, splits, s)
+           : a_terms == 3 ? launch_splitk_tiles<3, 128, 2>(tune, A, W, part, M, N, K, splits, s)
+                          : launch_splitk_tiles<1, 128, 2>(tune, A, W, part, M, N, K, splits, s);
 }
 
-hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
-                            int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s, const PrefetchArgs *pf,
-                            const NormAfter *norm, bool *norm_done) {
+hipError_t launch_gemm_bf16(const GemmTune &tune, const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi,
+                            int a_terms, int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s,
+                            const PrefetchArgs *pf, const NormAfter *norm, bool *norm_done) {
     if (norm_done) *norm_done = false;
     int k_total = K * (a_terms == 2 ? 2 : 1);
     bool big = false;
-    int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, k_total, &big) : 1;
-    if (splits > 1 && splitk_ws && gemm_splitk_bytes(M, N, k_total) <= splitk_ws_bytes) {
-        hipError_t e = launch_splitk_main(A, W, splitk_ws, M, N, K, a_terms, splits, big, s);
+    int splits = tune.tile == 0 ? gemm_splitk_factor(tune, M, N, k_total, &big) : 1;
+    if (splits > 1 && splitk_ws && gemm_splitk_bytes(tune, M, N, k_total) <= splitk_ws_bytes) {
+        hipError_t e = launch_splitk_main(tune, A, W, splitk_ws, M, N, K, a_terms, splits, big, s);
         if (e != hipSuccess) return e;
         int n_out = epi == EPI_SWIGLU ? N / 2 : N;
         dim3 grid((n_out / 4 + 255) / 256, M);
@@ -785,28 +759,28 @@ hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int 
         else splitk_reduce_kernel<EPI_SWIGLU><<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, out, out_terms);
         return hipGetLastError();
     }
-    if (epi == EPI_STORE_F32) return launch_epi<EPI_STORE_F32>(A, W, out, M, N, K, a_terms, out_terms, s);
-    if (epi == EPI_RESID_F32) return launch_epi<EPI_RESID_F32>(A, W, out, M, N, K, a_terms, out_terms, s);
-    return launch_epi<EPI_SWIGLU>(A, W, out, M, N, K, a_terms, out_terms, s, pf);
+    if (epi == EPI_STORE_F32) return launch_epi<EPI_STORE_F32>(tune, A, W, out, M, N, K, a_terms, out_terms, s);
+    if (epi == EPI_RESID_F32) return launch_epi<EPI_RESID_F32>(tune, A, W, out, M, N, K, a_terms, out_terms, s);
+    return launch_epi<EPI_SWIGLU>(tune, A, W, out, M, N, K, a_terms, out_terms, s, pf);
 }
 
 // QKV projection with the rotation in the epilogue (see RopeArgs): the default tile choice, both shapes
 // have 64-column wave tiles.
-hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms, const RopeArgs &rope,
-                                 float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s) {
+hipError_t launch_gemm_bf16_rope(const GemmTune &tune, const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms,
+                                 const RopeArgs &rope, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s) {
     int k_total = K * (a_terms == 2 ? 2 : 1);
     bool big = false;
-    int splits = g_gemm_tune.tile == 0 ? gemm_splitk_factor(M, N, k_total, &big) : 1;
-    if (splits > 1 && splitk_ws && gemm_splitk_bytes(M, N, k_total) <= splitk_ws_bytes) {
-        hipError_t e = launch_splitk_main(A, W_perm, splitk_ws, M, N, K, a_terms, splits, big, s);
+    int splits = tune.tile == 0 ? gemm_splitk_factor(tune, M, N, k_total, &big) : 1;
+    if (splits > 1 && splitk_ws && gemm_splitk_bytes(tune, M, N, k_total) <= splitk_ws_bytes) {
+        hipError_t e = launch_splitk_main(tune, A, W_perm, splitk_ws, M, N, K, a_terms, splits, big, s);
         if (e != hipSuccess) return e;
         dim3 grid(((N / 128) * 16 + 255) / 256, M);
         splitk_reduce_rope_kernel<<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, rope);
         return hipGetLastError();
     }
     if (prefer_256_tiles(M, N))
-        return launch_tile<256, 256, 2, 4, 64, 2, EPI_ROPE>(A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
-    return launch_tile<128, 128, 2, 2, 64, 2, EPI_ROPE>(A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
+        return launch_tile<256, 256, 2, 4, 64, 2, EPI_ROPE>(tune, A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
+    return launch_tile<128, 128, 2, 2, 64, 2, EPI_ROPE>(tune, A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
 }
 
 }  // namespace cs

@@ -5,10 +5,45 @@
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
+#include <atomic>
 
 namespace cs {
 
 typedef __hip_bfloat16 bf16;
+
+// fp32 -> IEEE half, round to nearest even, saturating: a finite value beyond the half range becomes +-65504 rather
+// than an infinity (one infinity in an activation would turn the residual stream, and with it the confidence, into
+// NaN).  Every store of the fp16 activation format goes through this.
+__device__ __forceinline__ __half to_half_sat(float v) {
+    return __float2half_rn(__builtin_amdgcn_fmed3f(v, -65504.0f, 65504.0f));
+}
+
+// Launch-shape settings of one context (confspec_tune); the kernels' launchers and the planners take them as an
+// argument, nothing here is process-wide.
+struct GemmTune {
+    int tile = 0;      // 0 = heuristic; 1 = 128x128, 4 = 256x256 / 8 wavefronts, 7 = 192x96 / 6 wavefronts
+    int group_m = 0;   // 0 = heuristic; otherwise tile rows per band of the tile order
+    int splitk = 0;    // 0 = heuristic; otherwise the split-K factor of every GEMM that has scratch (1 = never split)
+};
+struct AttnTune {
+    int target_items = 512;   // concurrent workgroup slots the planner assumes
+    int min_chunks = 4;       // shortest piece of a tile the planner cuts (decode-shaped batches: 4 is 2.6 % faster than 8)
+    int force_split = 0;      // 0 = choose by the makespan estimate, 1..4 = fixed split factor, 5 = front-loaded pieces
+    int kernel = 0;           // 0 = default main loop; 1 = the register-staged main loop (kept for the two-term variant)
+};
+
+// hipFuncSetAttribute(MaxDynamicSharedMemorySize) once per device and kernel: `mask` holds one bit per device.
+inline hipError_t set_dynamic_lds_once(std::atomic<uint32_t> &mask, const void *fn, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint32_t bit = 1u << (dev & 31);
+    if (mask.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    mask.fetch_or(bit, std::memory_order_release);
+    return hipSuccess;
+}
 
 // ---- attention work description (built on the device by plan_attention) ----
 // One item = one q-row tile of one (trace, kv head) over one range of 64-key chunks.
@@ -32,8 +67,6 @@ struct AttnTile {
 constexpr int ATTN_BM = 128;      // q rows per tile (bf16 MFMA kernel): 4 wavefronts x 32 rows
 constexpr int ATTN_THREADS = 256;
 constexpr int ATTN_BN = 64;       // keys per chunk
-constexpr int ATTN_TARGET_ITEMS = 512;
-constexpr int ATTN_MIN_CHUNKS_PER_ITEM = 4;   // shortest piece of a tile the planner cuts (decode-shaped batches: 4 is 2.6 % faster than 8)
 
 // Host-side mirror of the planner's counting pass (same arithmetic as the device code).
 struct AttnPlanCounts {
@@ -43,9 +76,11 @@ struct AttnPlanCounts {
     int32_t equalize;           // 1: equal pieces per tile, 0: pieces of chunks_per_item, remainder last
 };
 // last_only: plan the last suffix position of each trace only (one tile of G rows per trace and kv head)
-AttnPlanCounts attn_plan_counts(const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv, int last_only);
+AttnPlanCounts attn_plan_counts(const AttnTune &tune, const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv,
+                                int last_only);
 // Upper bounds used to size the workspace.
-void attn_plan_capacity(int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles, int64_t *max_items);
+void attn_plan_capacity(const AttnTune &tune, int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles,
+                        int64_t *max_items);
 
 enum Epilogue : int { EPI_STORE_F32 = 0, EPI_RESID_F32 = 1, EPI_SWIGLU = 2, EPI_ROPE = 3 };
 
@@ -79,7 +114,6 @@ hipError_t launch_rope_split(int dtype, const float *qkv, const float *cos_t, co
 // dst row b = src row rows[b] (rows == nullptr: row b), row_bytes a multiple of 16
 hipError_t launch_gather_rows(const void *src, void *dst, const int32_t *rows, int n_rows, int n_src_rows,
                               size_t row_bytes, hipStream_t s);
-hipError_t launch_copy16(const void *src, void *dst, size_t n16, hipStream_t s);
 hipError_t launch_bf16_to_f16(const void *src, void *dst, size_t n, hipStream_t s);
 // dst rows = src rows with the two middle 32-row blocks of every 128-row head swapped (n_heads * 128 rows of d elements)
 hipError_t launch_permute_heads(const void *src, void *dst, int n_heads, int d, hipStream_t s);
@@ -126,14 +160,14 @@ struct NormAfter {
     float eps = 0.f;
     int terms = 1;
 };
-hipError_t launch_gemm_bf16(const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi, int a_terms,
-                            int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s,
+hipError_t launch_gemm_bf16(const GemmTune &tune, const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int epi,
+                            int a_terms, int out_terms, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s,
                             const PrefetchArgs *pf = nullptr, const NormAfter *norm = nullptr, bool *norm_done = nullptr);
-hipError_t launch_gemm_bf16_rope(const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms, const RopeArgs &rope,
-                                 float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
-int gemm_splitk_factor(int M, int N, int K_total, bool *big_tile = nullptr);   // *big_tile: slices of 256 x 256 tiles
-size_t gemm_splitk_bytes(int M, int N, int K_total);
-size_t gemm_splitk_max_bytes(int max_M, int N, int K_total);   // largest gemm_splitk_bytes over M <= max_M
+hipError_t launch_gemm_bf16_rope(const GemmTune &tune, const bf16 *A, const bf16 *W_perm, int M, int N, int K, int a_terms,
+                                 const RopeArgs &rope, float *splitk_ws, size_t splitk_ws_bytes, hipStream_t s);
+int gemm_splitk_factor(const GemmTune &tune, int M, int N, int K_total, bool *big_tile = nullptr);   // *big_tile: slices of 256 x 256 tiles
+size_t gemm_splitk_bytes(const GemmTune &tune, int M, int N, int K_total);
+size_t gemm_splitk_max_bytes(const GemmTune &tune, int max_M, int N, int K_total);   // largest gemm_splitk_bytes over M <= max_M
 
 // ---- attention ----
 struct AttnArgs {

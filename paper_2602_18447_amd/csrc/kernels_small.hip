@@ -97,7 +97,7 @@ hipError_t launch_embed(int dtype, const int32_t *ids, const void *E, float *x, 
 template <typename T>
 __device__ __forceinline__ void store_terms(T *o, int c, int d, int terms, float v) {
     if (sizeof(T) == 2 && terms == 3) {
-        reinterpret_cast<__half *>(o)[c] = __float2half_rn(v);
+        reinterpret_cast<__half *>(o)[c] = to_half_sat(v);
         return;
     }
     T hi = from_f32<T>(v);
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_rows_kernel(const float *__r
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             if (terms == 3) {
-                hi[q] = __half_as_ushort(__float2half_rn(y[q]));
+                hi[q] = __half_as_ushort(to_half_sat(y[q]));
                 lo[q] = 0;
             } else {
                 bf16 h = __float2bfloat16(y[q]);
@@ -247,21 +247,6 @@ hipError_t launch_kv_append(const void *ksuf, const void *vsuf, void *k_pages, v
     kv_append_kernel<<<T, 128, 0, s>>>((const u32x4_t *)ksuf, (const u32x4_t *)vsuf, (u32x4_t *)k_pages, (u32x4_t *)v_pages,
                                        table, cu, plens, n_append, tok_trace, B, T, Hkv, (int)(head_row_bytes / 16),
                                        block_size, max_blocks, n_blocks);
-    return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------------------
-// Plain copy, 16 bytes per lane per step: reads n16 * 16 bytes and writes as many.  Its known
-// traffic is the yardstick that hardware byte counters of the other kernels are scaled by.
-__global__ void copy16_kernel(const u32x4_t *__restrict__ src, u32x4_t *__restrict__ dst, size_t n16) {
-    size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
-}
-
-hipError_t launch_copy16(const void *src, void *dst, size_t n16, hipStream_t s) {
-    size_t blocks = (n16 + 255) / 256;
-    if (blocks > 256 * 32) blocks = 256 * 32;
-    copy16_kernel<<<(unsigned)blocks, 256, 0, s>>>((const u32x4_t *)src, (u32x4_t *)dst, n16);
     return hipGetLastError();
 }
 

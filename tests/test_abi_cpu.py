@@ -158,20 +158,40 @@ def test_op_gemm_and_tune_validation():
     _expect(ctx, cb.E_UNSUPPORTED, lambda: cb.confspec_op_gemm(ctx, fake, fake, fake, 8, 128, 40, 0, stream=0))
     _expect(ctx, cb.E_INVALID_ARG, lambda: cb.confspec_op_gemm(ctx, fake, fake, fake, 0, 128, 64, 0, stream=0))
     _expect(ctx, cb.E_INVALID_ARG, lambda: cb.confspec_op_gemm(ctx, fake, fake, fake, 8, 128, 64, 7, stream=0))
-    with pytest.raises(cb.ConfSpecError):
-        cb.confspec_tune("no_such_key", 1)
-    cb.confspec_tune("gemm_tile", 0)
-    with pytest.raises(cb.ConfSpecError):
-        cb.confspec_tune("gemm_tile", 99)
-    cb.confspec_tune("gemm_splitk", 0)
-    with pytest.raises(cb.ConfSpecError):
-        cb.confspec_tune("gemm_splitk", 65)
-    for src, dst, n in [(None, fake, 64), (fake, None, 64), (fake, fake, 0), (fake, fake, 24),
-                        (_FakeDev(0x10008), fake, 64)]:
-        with pytest.raises(cb.ConfSpecError) as ei:
-            cb.confspec_op_copy(src, dst, n, stream=0)
-        assert ei.value.code == cb.E_INVALID_ARG
+    for c in (ctx, None):                 # one context's settings, and the defaults of later contexts
+        with pytest.raises(cb.ConfSpecError):
+            cb.confspec_tune(c, "no_such_key", 1)
+        cb.confspec_tune(c, "gemm_tile", 0)
+        for bad in (99, 2, 3, 5, 6):      # only the tile shapes that are built
+            with pytest.raises(cb.ConfSpecError):
+                cb.confspec_tune(c, "gemm_tile", bad)
+        cb.confspec_tune(c, "gemm_splitk", 0)
+        with pytest.raises(cb.ConfSpecError):
+            cb.confspec_tune(c, "gemm_splitk", 65)
     cb.confspec_destroy(ctx)
+
+
+def test_settings_belong_to_a_context():
+    """A setting made on one context leaves another context, and the defaults, alone; a context created after a
+    change of the defaults starts from them.  Seen through the packed-weight size, which depends on the number of
+    fp16 layers."""
+    _no_gpu_here()
+    cfg = _cfg(n_layers=8)
+    a, b = cb.confspec_create(cfg), cb.confspec_create(cfg)
+    base = cb.confspec_packed_bytes(a)
+    assert cb.confspec_packed_bytes(b) == base
+    cb.confspec_tune(a, "first_layers_f16", 0)
+    assert cb.confspec_packed_bytes(a) < base and cb.confspec_packed_bytes(b) == base
+    try:
+        cb.confspec_tune(None, "split_layers", 2)
+        c = cb.confspec_create(cfg)
+        assert cb.confspec_packed_bytes(a) < cb.confspec_packed_bytes(c) < base
+        assert cb.confspec_packed_bytes(b) == base
+        cb.confspec_destroy(c)
+    finally:
+        cb.confspec_tune(None, "split_layers", -1)
+    for ctx in (a, b):
+        cb.confspec_destroy(ctx)
 
 
 def test_cascade_validates_before_any_launch():

@@ -43,12 +43,12 @@ def _pack_rows(F):
 
 
 # --------------------------------------------------------------------------- #
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("tile", [1, 4, 7])
 @pytest.mark.parametrize("M,N,K", [(300, 512, 192), (1, 256, 64), (257, 768, 1024), (512, 256, 320), (400, 384, 128)])
 def test_gemm_bf16_store_and_residual(tile, M, N, K):
     print(f"gemm bf16 tile={tile} M={M} N={N} K={K}", flush=True)
     ctx, _ = _ctx("bf16")
-    cb.confspec_tune("gemm_tile", tile)
+    cb.confspec_tune(ctx, "gemm_tile", tile)
     A = _rand((M, K), torch.bfloat16, 1)
     Wt = _rand((N, K), torch.bfloat16, 2, 0.05)
     ref = f64(A) @ f64(Wt).T
@@ -63,15 +63,14 @@ def test_gemm_bf16_store_and_residual(tile, M, N, K):
     cb.confspec_op_gemm(ctx, A, Wt, x, M, N, K, cb.EPI_RESID_F32)
     torch.cuda.synchronize()
     assert np.abs(f64(x) - (f64(x0) + ref)).max() <= 2e-5 * max(scale, 4.0)
-    cb.confspec_tune("gemm_tile", 0)
     cb.confspec_destroy(ctx)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile", [1, 4])
 def test_gemm_bf16_swiglu_epilogue(tile):
     print(f"gemm bf16 swiglu tile={tile}", flush=True)
     ctx, _ = _ctx("bf16")
-    cb.confspec_tune("gemm_tile", tile)
+    cb.confspec_tune(ctx, "gemm_tile", tile)
     M, F, K = 200, 384, 256
     A = _rand((M, K), torch.bfloat16, 4)
     Wgu = _rand((2 * F, K), torch.bfloat16, 5, 0.1)           # gate rows, then up rows
@@ -84,7 +83,6 @@ def test_gemm_bf16_swiglu_epilogue(tile):
     ref = O.silu(g) * u
     err = np.abs(f64(out) - ref)
     assert np.all(err <= 2.0 ** -8 * np.abs(ref) + 1e-4 * np.abs(ref).max())
-    cb.confspec_tune("gemm_tile", 0)
     cb.confspec_destroy(ctx)
 
 
@@ -368,18 +366,18 @@ def test_attention_bf16_split_kv_merge_matches_unsplit(split):
     """Force many key-range pieces (planner's choice, equal pieces, front-loaded pieces): the merged
     result must meet the same bound as the unsplit one."""
     print(f"attention bf16 forced splits, mode {split}", flush=True)
-    cb.confspec_tune("attn_min_chunks", 1)
-    cb.confspec_tune("attn_target_items", 1024)
-    cb.confspec_tune("attn_split", split)
+    cb.confspec_tune(None, "attn_min_chunks", 1)
+    cb.confspec_tune(None, "attn_target_items", 1024)
+    cb.confspec_tune(None, "attn_split", split)
     try:
         err = _attention_case("bf16", 12, 2, 128, (700, 64, 0, 3000), (40, 96, 20, 7))
         err2 = _attention_case("bf16", 12, 2, 128, (700, 64, 0, 3000), (40, 96, 20, 7), out_terms=2)
         err3 = _attention_case("bf16", 8, 8, 128, (130, 2500, 17, 900, 64, 1, 333, 1200, 5), (33, 5, 129, 64, 1, 200, 16, 77, 250))
         assert err2 <= 6e-3 and err3 <= 6e-3
     finally:
-        cb.confspec_tune("attn_min_chunks", 4)
-        cb.confspec_tune("attn_target_items", 512)
-        cb.confspec_tune("attn_split", 0)
+        cb.confspec_tune(None, "attn_min_chunks", 4)
+        cb.confspec_tune(None, "attn_target_items", 512)
+        cb.confspec_tune(None, "attn_split", 0)
     print("  max abs err", err, flush=True)
     assert err <= 6e-3
 
@@ -430,7 +428,6 @@ def test_gemm_bf16_wide_output_split_into_two_launches(epi):
     would be nearly empty: the trailing columns go to a second launch with 128x128 tiles."""
     print(f"gemm bf16 wide split {epi}", flush=True)
     ctx, _ = _ctx("bf16")
-    cb.confspec_tune("gemm_tile", 0)
     M, N, K = 700, 256 * 90, 128                      # 3 x 90 tiles of 256: one full round + 14 tiles
     A = _rand((M, K), torch.bfloat16, 11)
     Wt = _rand((N, K), torch.bfloat16, 12, 0.05)
@@ -625,25 +622,48 @@ def test_rmsnorm_fp16_output():
     cb.confspec_destroy(ctx)
 
 
+def test_fp16_stores_saturate_instead_of_overflowing():
+    """Activations beyond the half range (gains of about 1e5) are stored as +-65504, never as an infinity: the
+    conversion is clamp to the largest finite half, then round to nearest even, which numpy's half conversion
+    of the clamped fp64 value reproduces."""
+    print("fp16 saturation", flush=True)
+    d = 1536
+    ctx, base = _ctx("bf16", d_model=d)
+    x = _rand((9, d), torch.float32, 91, 3.0)
+    g = (1.0e5 * (1 + 0.1 * _rand((d,), torch.float32, 92))).to(torch.bfloat16)
+    out = torch.zeros((9, d), dtype=torch.float16, device=DEV)
+    cb.confspec_op_rmsnorm(ctx, x, g, out, 9, out_terms=3)
+    torch.cuda.synchronize()
+    ref = O.rmsnorm(f64(x), f64(g), base["rms_eps"])
+    assert np.abs(ref).max() > 2e5 and (np.abs(ref) < 6e4).any()            # both sides of the range occur
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    want = np.clip(ref, -65504.0, 65504.0).astype(np.float16)
+    inside = np.abs(ref) < 65000.0
+    assert np.array_equal(got[~inside & (np.abs(ref) > 65520.0)], want[~inside & (np.abs(ref) > 65520.0)])
+    assert np.all(np.abs(got[inside].astype(np.float64) - ref[inside]) <= 2.0 ** -10 * np.abs(ref[inside]))
+    # the SwiGLU epilogue and the split-K reduce: products far beyond the range
+    M, F, K = 70, 128, 64
+    A = torch.full((M, K), 30.0, dtype=torch.float16, device=DEV)
+    Wt = torch.full((2 * F, K), 20.0, dtype=torch.float16, device=DEV)      # gate = up = 38400 -> silu(g) * u ~ 1.5e9
+    Wt[::2] *= -1                                                            # negative up values in half of the blocks' rows
+    act = torch.zeros((M, F), dtype=torch.float16, device=DEV)
+    cb.confspec_op_gemm(ctx, A, Wt, act, M, 2 * F, K, cb.EPI_SWIGLU, a_terms=3, out_terms=3)
+    torch.cuda.synchronize()
+    a = act.cpu().numpy()
+    assert np.isfinite(a).all() and np.abs(a).max() == 65504.0
+    cb.confspec_destroy(ctx)
+
+
 def test_attention_bf16_fp16_output():
     print("attention fp16 output", flush=True)
     err = _attention_case("bf16", 12, 2, 128, (300, 17, 0), (96, 130, 5), out_terms=3)
     assert err <= 6e-3
-    cb.confspec_tune("attn_min_chunks", 1)
-    cb.confspec_tune("attn_split", 3)
+    cb.confspec_tune(None, "attn_min_chunks", 1)
+    cb.confspec_tune(None, "attn_split", 3)
     try:
         err = _attention_case("bf16", 12, 2, 128, (700, 64), (40, 96), out_terms=3)     # through the merge kernel
     finally:
-        cb.confspec_tune("attn_min_chunks", 4)
-        cb.confspec_tune("attn_split", 0)
+        cb.confspec_tune(None, "attn_min_chunks", 4)
+        cb.confspec_tune(None, "attn_split", 0)
     assert err <= 6e-3
-
-
-def test_copy_kernel_is_exact():
-    print("copy kernel", flush=True)
-    n = (1 << 22) + 16 * 37                       # not a multiple of the grid's stride
-    src = torch.empty(n, dtype=torch.uint8, device=DEV).random_(0, 255)
-    dst = torch.zeros(n + 16, dtype=torch.uint8, device=DEV)
-    cb.confspec_op_copy(src, dst, n)
-    torch.cuda.synchronize()
-    assert torch.equal(dst[:n], src) and int(dst[n:].sum()) == 0

@@ -106,10 +106,10 @@ def test_last_layer_pruning_changes_nothing_but_rounding():
     res = {}
     try:
         for flag in (0, 1):
-            cb.confspec_tune("prune_last_layer", flag)
+            cb.confspec_tune(ver.ctx, "prune_last_layer", flag)
             res[flag] = G.run_gpu(wl, weights, batch, kv, verifier=ver)
     finally:
-        cb.confspec_tune("prune_last_layer", 1)
+        cb.confspec_tune(ver.ctx, "prune_last_layer", 1)
     assert np.abs(res[0]["logits"] - res[1]["logits"]).max() <= 6e-3
     ora = G.run_oracle(wl, weights, batch, kv, res[1]["taus"], res[1]["vids"])
     for flag in (0, 1):
@@ -125,16 +125,33 @@ def test_first_layers_fp16_and_two_term_both_meet_the_bound():
     res = {}
     try:
         for flag in (0, 1):
-            cb.confspec_tune("first_layers_f16", flag)     # read when the weights are packed and by the pass
+            cb.confspec_tune(None, "first_layers_f16", flag)     # default of new contexts: read when the weights are packed and by the pass
             ver = Verifier(wl.model, weights)
             assert ver.w.n_f16_layers == (4 if flag else 0)     # default: the first half of the 8 layers
             res[flag] = G.run_gpu(wl, weights, batch, kv, verifier=ver)
             ver.close()
     finally:
-        cb.confspec_tune("first_layers_f16", 1)
+        cb.confspec_tune(None, "first_layers_f16", 1)
     ora = G.run_oracle(wl, weights, batch, kv, res[1]["taus"], res[1]["vids"])
     for flag in (0, 1):
         G.compare(wl, res[flag], ora, f"first_layers_f16={flag}")
+
+
+def test_huge_activations_in_the_fp16_layers_give_finite_outputs():
+    """Norm gains of about 1e5 in the layers that run on fp16 operands push normalised activations past the half
+    range; they saturate there, and logits and confidences stay finite (no infinity, so no NaN downstream)."""
+    print("fp16 layers with out-of-range activations", flush=True)
+    wl = _small_bf16("huge", 2011, (300, 0, 64), (40, 7, 96), n_layers=4)
+    weights, batch, kv = G.build_inputs(wl)
+    for l in range(2):                                   # the first half of the layers: the fp16 ones
+        weights.attn_norm[l].mul_(1.0e5)
+        weights.mlp_norm[l].mul_(1.0e5)
+    ver = Verifier(wl.model, weights)
+    assert ver.w.n_f16_layers == 2
+    r = G.run_gpu(wl, weights, batch, kv, verifier=ver)
+    ver.close()
+    assert np.isfinite(r["logits"]).all() and np.isfinite(r["conf"]).all()
+    assert np.all(r["conf"] >= 0.5 - 1e-6) and np.all(r["conf"] <= 1.0 + 1e-6)
 
 
 def test_fused_and_separate_rotary_embedding_agree():
@@ -145,10 +162,10 @@ def test_fused_and_separate_rotary_embedding_agree():
     res = {}
     try:
         for flag in (0, 1):
-            cb.confspec_tune("fuse_rope", flag)
+            cb.confspec_tune(ver.ctx, "fuse_rope", flag)
             res[flag] = G.run_gpu(wl, weights, batch, kv, verifier=ver)
     finally:
-        cb.confspec_tune("fuse_rope", 1)
+        cb.confspec_tune(ver.ctx, "fuse_rope", 1)
     ver.close()
     ora = G.run_oracle(wl, weights, batch, kv, res[1]["taus"], res[1]["vids"])
     for flag in (0, 1):
@@ -163,10 +180,10 @@ def test_weight_prefetch_hint_changes_no_bit():
     res = {}
     try:
         for flag in (0, 1):
-            cb.confspec_tune("prefetch_down", flag)
+            cb.confspec_tune(ver.ctx, "prefetch_down", flag)
             res[flag] = G.run_gpu(wl, weights, batch, kv, verifier=ver)
     finally:
-        cb.confspec_tune("prefetch_down", 1)
+        cb.confspec_tune(ver.ctx, "prefetch_down", 1)
     ver.close()
     for k in ("logits", "conf", "verdict", "accept"):
         assert np.array_equal(res[0][k], res[1][k])
