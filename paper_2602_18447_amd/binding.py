@@ -121,6 +121,11 @@ def _load() -> C.CDLL:
     lib.confspec_cascade.restype = C.c_int
     lib.confspec_cascade.argtypes = [vp, P(Weights), P(KV), vp, sz, vp, P(Weights), P(KV), vp, sz, P(Batch), P(Requests),
                                      P(i32), i32, C.c_float, vp, sz, P(CascadeOut), P(i32), vp]
+    lib.confspec_static_scratch_need.restype = C.c_int
+    lib.confspec_static_scratch_need.argtypes = [vp, P(Batch), P(sz)]
+    lib.confspec_verify_static.restype = C.c_int
+    lib.confspec_verify_static.argtypes = [vp, P(Weights), P(KV), P(Batch), P(i32), i32, P(C.c_float), i32,
+                                           vp, vp, vp, vp, vp]
     lib.confspec_tune.restype = C.c_int
     lib.confspec_tune.argtypes = [vp, C.c_char_p, i32]
     return lib
@@ -132,7 +137,8 @@ EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec
             "confspec_workspace_bytes", "confspec_packed_bytes", "confspec_pack_weights", "confspec_verify",
             "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_qkv_rope", "confspec_op_attention",
             "confspec_op_verdict_gate", "confspec_tune", "confspec_cascade_scratch_bytes",
-            "confspec_cascade", "confspec_verify_append", "confspec_head_scratch_bytes", "confspec_generate_step"]
+            "confspec_cascade", "confspec_verify_append", "confspec_head_scratch_bytes", "confspec_generate_step",
+            "confspec_static_scratch_need", "confspec_verify_static"]
 
 
 class ConfSpecError(RuntimeError):
@@ -210,6 +216,25 @@ def confspec_verify(ctx, w: Weights, kv: KV, batch: Batch, verdict_ids: Sequence
     _check(ctx, lib.confspec_verify(ctx, C.byref(w), C.byref(kv), C.byref(batch), ids, nv, tau, nt,
                                     _ptr(workspace), ws_bytes, _ptr(logits), _ptr(conf), _ptr(verdict),
                                     _ptr(accept), _stream_handle(stream)))
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def confspec_static_scratch_need(ctx, batch: Batch) -> int:
+    out = C.c_size_t()
+    _check(ctx, lib.confspec_static_scratch_need(ctx, C.byref(batch), C.byref(out)))
+    return out.value
+
+
+def confspec_verify_static(ctx, w: Weights, kv: KV, batch: Batch, verdict_ids: Sequence[int], taus: Sequence[float],
+                           logits, conf, verdict, accept, stream=None) -> None:
+    nv, nt = len(verdict_ids), len(taus)
+    ids = (C.c_int32 * max(nv, 1))(*[int(v) for v in verdict_ids])
+    tau = (C.c_float * max(nt, 1))(*[float(t) for t in taus])
+    _check(ctx, lib.confspec_verify_static(ctx, C.byref(w), C.byref(kv), C.byref(batch), ids, nv, tau, nt,
+                                           _ptr(logits), _ptr(conf), _ptr(verdict), _ptr(accept),
+                                           _stream_handle(stream)))
 
 
 def confspec_verify_append(ctx, w: Weights, kv: KV, batch: Batch, n_append, h_n_append, verdict_ids: Sequence[int],

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -16,7 +17,12 @@
 #include "../../include/confspec_cascade.h"
 #include "../../include/confspec_append.h"
 #include "../../include/confspec_generate.h"
+#include "../../include/confspec_static.h"
 #include "kernels.h"
+
+// Scratch of confspec_verify_static: one array per GPU, part of the loaded code object, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; the device address it yields is what is passed on.
+static __device__ __align__(256) unsigned char scratch[CONFSPEC_STATIC_SCRATCH_BYTES];
 
 // Settings of one context (confspec_tune).  A new context starts from the defaults below.
 struct Settings {
@@ -80,7 +86,11 @@ struct WsLayout {
     int64_t max_tiles, max_items, max_tiles2, max_items2;
 };
 
-WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B) {
+// exact (may be null): lay the workspace out for this batch alone instead of for every batch of up to T tokens in B
+// traces - the attention plans' lists and partial results and the split-K planes are then sized by what this batch's
+// plans and row counts need, which is a small fraction of the general bound (the general bound holds 64 KiB of
+// partial results for each of 3 * tiles + 2048 possible pieces).
+WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B, const confspec_batch *exact = nullptr) {
     const confspec_model_cfg &c = ctx->cfg;
     WsLayout w = {};
     size_t at = 0;
@@ -111,12 +121,22 @@ WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B) {
     w.attn = take((size_t)T * qw * eb * terms);
     w.act = take((size_t)T * c.d_ffn * eb * terms);
     if (c.dtype == CONFSPEC_DTYPE_BF16) {
-        cs::attn_plan_capacity(ctx->set.attn, T, B, c.n_q_heads / c.n_kv_heads, c.n_kv_heads, &w.max_tiles, &w.max_items);
+        const int G = c.n_q_heads / c.n_kv_heads;
+        cs::attn_plan_capacity(ctx->set.attn, T, B, G, c.n_kv_heads, &w.max_tiles, &w.max_items);
+        int64_t part_slots = w.max_items;
+        cs::AttnPlanCounts pe = {}, pe_last = {};
+        if (exact) {
+            pe = cs::attn_plan_counts(ctx->set.attn, exact->h_cu_suffix, exact->h_prefix_lens, exact->B, G, c.n_kv_heads, 0);
+            pe_last = cs::attn_plan_counts(ctx->set.attn, exact->h_cu_suffix, exact->h_prefix_lens, exact->B, G, c.n_kv_heads, 1);
+            w.max_tiles = std::max<int64_t>(pe.n_tiles, 1);
+            w.max_items = std::max<int64_t>(pe.n_items, 1);
+            part_slots = std::max<int64_t>(std::max(pe.n_part_slots, pe_last.n_part_slots), 1);
+        }
         w.plan_counts = take(256);
         w.plan_tiles = take((size_t)w.max_tiles * sizeof(cs::AttnTile));
         w.plan_items = take((size_t)w.max_items * sizeof(cs::AttnItem));
-        w.part_o = take((size_t)w.max_items * cs::ATTN_BM * c.head_dim * 4);
-        w.part_ml = take((size_t)w.max_items * cs::ATTN_BM * 2 * 4);
+        w.part_o = take((size_t)part_slots * cs::ATTN_BM * c.head_dim * 4);
+        w.part_ml = take((size_t)part_slots * cs::ATTN_BM * 2 * 4);
         // the last layer works on the last position of each trace only: B rows, one attention tile per
         // trace and kv head (its items fit the partial buffers above: max_items2 <= max_items)
         w.x_last = take((size_t)B * c.d_model * 4);
@@ -125,6 +145,10 @@ WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B) {
         w.act_last = take((size_t)B * c.d_ffn * eb * terms);
         w.max_tiles2 = (int64_t)B * c.n_kv_heads;
         w.max_items2 = std::min<int64_t>(w.max_items, 3 * w.max_tiles2 + (w.max_items - 3 * w.max_tiles));
+        if (exact) {
+            w.max_tiles2 = std::max<int64_t>(pe_last.n_tiles, 1);
+            w.max_items2 = std::max<int64_t>(pe_last.n_items, 1);
+        }
         w.plan2_counts = take(256);
         w.plan2_tiles = take((size_t)w.max_tiles2 * sizeof(cs::AttnTile));
         w.plan2_items = take((size_t)w.max_items2 * sizeof(cs::AttnItem));
@@ -132,6 +156,15 @@ WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B) {
         // pass over few tokens), in both activation widths
         size_t sk = 0;
         for (int t = 1; t <= 2; ++t) {
+            if (exact) {   // the projections of this batch run on T rows, or on B rows (last layer)
+                for (int rows : {(int)T, (int)B}) {
+                    sk = std::max(sk, cs::gemm_splitk_bytes(ctx->set.gemm, rows, (int)(qw + 2 * kw), c.d_model * t));
+                    sk = std::max(sk, cs::gemm_splitk_bytes(ctx->set.gemm, rows, c.d_model, (int)qw * t));
+                    sk = std::max(sk, cs::gemm_splitk_bytes(ctx->set.gemm, rows, 2 * c.d_ffn, c.d_model * t));
+                    sk = std::max(sk, cs::gemm_splitk_bytes(ctx->set.gemm, rows, c.d_model, c.d_ffn * t));
+                }
+                continue;
+            }
             sk = std::max(sk, cs::gemm_splitk_max_bytes(ctx->set.gemm, (int)T, (int)(qw + 2 * kw), c.d_model * t));
             sk = std::max(sk, cs::gemm_splitk_max_bytes(ctx->set.gemm, (int)T, c.d_model, (int)qw * t));
             sk = std::max(sk, cs::gemm_splitk_max_bytes(ctx->set.gemm, (int)T, 2 * c.d_ffn, c.d_model * t));
@@ -169,6 +202,7 @@ struct PassExtras {
     const confspec_head_out *head = nullptr;                        // full-vocabulary head at the last positions
     void *head_scratch = nullptr;
     size_t head_scratch_bytes = 0;
+    bool exact_layout = false;                                      // workspace laid out for this batch alone
 };
 
 int check_batch(const confspec_ctx *ctx, const confspec_batch *b, int64_t max_prefix, int *max_L_out) {
@@ -499,7 +533,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     if ((rc = check_kv(ctx, kv, max_L > 0)) != CONFSPEC_OK) return rc;
     cs::VerdictArgs va = {};
     if (want_verdict && (rc = check_verdict(ctx, h_verdict_ids, n_verdict, h_tau, n_tau, &va)) != CONFSPEC_OK) return rc;
-    WsLayout L = ws_layout(ctx, batch->T, batch->B);
+    WsLayout L = ws_layout(ctx, batch->T, batch->B, ex.exact_layout ? batch : nullptr);
     if ((rc = check_ws(ctx, dev_workspace, workspace_bytes, L.total)) != CONFSPEC_OK) return rc;
     HeadLayout HL = {};
     if (ex.head) {
@@ -691,6 +725,60 @@ int confspec_verify_append(confspec_ctx *ctx, const confspec_weights *w, const c
     ex.dev_n_append = dev_n_append;
     ex.h_n_append = h_n_append;
     return verify_impl(ctx, w, kv, batch, h_verdict_ids, n_verdict, h_tau, n_tau, dev_workspace, workspace_bytes,
+                       dev_verdict_logits, dev_conf, dev_verdict, dev_accept, ex, stream);
+}
+
+// ---- the pass on the library's own scratch: no allocation anywhere on the way ----
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES];   // device address of `scratch` on each device, looked up on the first call there
+
+int static_scratch_ptr(confspec_ctx *ctx, void **out) {
+    int dev = ctx->device;
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(ctx, CONFSPEC_E_UNSUPPORTED, "device %d: at most %d devices", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;   // this device's copy of the array (the current device is ctx->device: checked by the caller)
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p & 255)) return fail(ctx, CONFSPEC_E_HIP, "static scratch has address %p", p);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CONFSPEC_OK;
+}
+}  // namespace
+
+int confspec_static_scratch_need(const confspec_ctx *ctx, const confspec_batch *batch, size_t *out_bytes) {
+    if (!ctx || !out_bytes) return CONFSPEC_E_INVALID_ARG;
+    int rc;
+    if ((rc = check_batch(ctx, batch, INT32_MAX, nullptr)) != CONFSPEC_OK) return rc;
+    *out_bytes = ws_layout(ctx, batch->T, batch->B, batch).total;
+    return CONFSPEC_OK;
+}
+
+int confspec_verify_static(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
+                           const confspec_batch *batch, const int32_t *h_verdict_ids, int32_t n_verdict,
+                           const float *h_tau, int32_t n_tau, float *dev_verdict_logits, float *dev_conf,
+                           int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!h_verdict_ids) return fail(ctx, CONFSPEC_E_INVALID_ARG, "verdict ids or tau pointer is null");
+    int rc;
+    size_t need = 0;
+    if ((rc = confspec_static_scratch_need(ctx, batch, &need)) != CONFSPEC_OK) return rc;
+    if (need > (size_t)CONFSPEC_STATIC_SCRATCH_BYTES)
+        return fail(ctx, CONFSPEC_E_WORKSPACE,
+                    "a batch of %d tokens in %d traces needs %zu bytes of scratch, the static array holds %zu; use "
+                    "confspec_verify with a workspace",
+                    batch->T, batch->B, need, (size_t)CONFSPEC_STATIC_SCRATCH_BYTES);
+    if ((rc = check_device(ctx)) != CONFSPEC_OK) return rc;
+    void *ptr = nullptr;
+    if ((rc = static_scratch_ptr(ctx, &ptr)) != CONFSPEC_OK) return rc;
+    // Nothing in the workspace has to start at zero: every slice is written by the pass before it is read (plans,
+    // maps, activations, partial products), so the last call's contents are simply overwritten.
+    PassExtras ex;
+    ex.exact_layout = true;
+    return verify_impl(ctx, w, kv, batch, h_verdict_ids, n_verdict, h_tau, n_tau, ptr, (size_t)CONFSPEC_STATIC_SCRATCH_BYTES,
                        dev_verdict_logits, dev_conf, dev_verdict, dev_accept, ex, stream);
 }
 

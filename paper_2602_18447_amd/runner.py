@@ -78,6 +78,13 @@ class Verifier:
         cb.confspec_verify(self.ctx, self.w, kvs, bs, verdict_ids, taus, ws, *outs, stream=stream)
         return outs
 
+    def verify_static(self, kv, batch, verdict_ids: Sequence[int], taus: Sequence[float], outputs, stream=None):
+        """verify() on the library's own scratch array: nothing is allocated on the way (the caller brings the
+        output tensors).  Batches that need more scratch than the array holds are rejected."""
+        kvs, bs, keep = self.bind(kv, batch)
+        cb.confspec_verify_static(self.ctx, self.w, kvs, bs, verdict_ids, taus, *outputs, stream=stream)
+        return outputs
+
     def verify_append(self, kv, batch, n_append, verdict_ids: Sequence[int], taus: Sequence[float], outputs=None,
                       stream=None):
         """verify() that also writes the keys / values of the first n_append[b] suffix tokens of every trace into the
