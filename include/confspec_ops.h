@@ -89,6 +89,26 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
                              size_t workspace_bytes, float *dev_verdict_logits, float *dev_conf,
                              int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream);
 
+/* Phase timing of the pass, the library's profiling hook.  While it is switched on for a context, every
+ * confspec_verify / confspec_verify_append / confspec_generate_step call on that context records a HIP event on
+ * its stream wherever the pass moves from one phase to the next (a few hundred events per pass, created when the
+ * timing is first switched on; they cost a few microseconds per pass).  confspec_phase_times waits for the last
+ * event of the most recent call and returns, per phase, the summed time between its events in milliseconds and
+ * (h_intervals, may be NULL) the number of intervals.  Do not capture a call into a HIP graph while timing is on. */
+#define CONFSPEC_PHASE_NORM 0          /* stand-alone RMSNorm kernels                                               */
+#define CONFSPEC_PHASE_QKV 1           /* QKV projection with rotary embedding and q / k / v split                  */
+#define CONFSPEC_PHASE_ATTN 2          /* attention kernel, one-term variant, every layer it runs in                */
+#define CONFSPEC_PHASE_ATTN_PRECISE 3  /* attention kernel, two-term variant of the first layer(s)                  */
+#define CONFSPEC_PHASE_ATTN_MERGE 4    /* merge of the key-range pieces of split attention tiles                    */
+#define CONFSPEC_PHASE_O_PROJ 5        /* output projection + residual (+ split-K reduce where split)               */
+#define CONFSPEC_PHASE_GATE_UP 6       /* gate/up projection + SwiGLU                                               */
+#define CONFSPEC_PHASE_DOWN 7          /* down projection + residual (+ reduce / next RMSNorm where split)          */
+#define CONFSPEC_PHASE_OTHER 8         /* maps, plans, rotary table, embedding, gathers, cache write-back, heads    */
+#define CONFSPEC_N_PHASES 9
+#define CONFSPEC_PHASE_END 9           /* internal: closes the last interval                                        */
+int confspec_phase_timing(confspec_ctx *ctx, int32_t enable);
+int confspec_phase_times(confspec_ctx *ctx, float *h_ms /* [CONFSPEC_N_PHASES] */, int32_t *h_intervals);
+
 /* Settings of one context (ctx != NULL), or the defaults that contexts created afterwards start from (ctx == NULL).
  * Nothing is process-wide at run time: two contexts in one process keep their own settings.  A setting that changes
  * the workspace or packed-weight size ("attn_target_items", "gemm_splitk", "split_layers", "first_layers_f16") must be

@@ -126,6 +126,10 @@ def _load() -> C.CDLL:
     lib.confspec_verify_static.restype = C.c_int
     lib.confspec_verify_static.argtypes = [vp, P(Weights), P(KV), P(Batch), P(i32), i32, P(C.c_float), i32,
                                            vp, vp, vp, vp, vp]
+    lib.confspec_phase_timing.restype = C.c_int
+    lib.confspec_phase_timing.argtypes = [vp, i32]
+    lib.confspec_phase_times.restype = C.c_int
+    lib.confspec_phase_times.argtypes = [vp, P(C.c_float), P(i32)]
     lib.confspec_tune.restype = C.c_int
     lib.confspec_tune.argtypes = [vp, C.c_char_p, i32]
     return lib
@@ -138,7 +142,7 @@ EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec
             "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_qkv_rope", "confspec_op_attention",
             "confspec_op_verdict_gate", "confspec_tune", "confspec_cascade_scratch_bytes",
             "confspec_cascade", "confspec_verify_append", "confspec_head_scratch_bytes", "confspec_generate_step",
-            "confspec_static_scratch_need", "confspec_verify_static"]
+            "confspec_static_scratch_need", "confspec_verify_static", "confspec_phase_timing", "confspec_phase_times"]
 
 
 class ConfSpecError(RuntimeError):
@@ -349,6 +353,21 @@ def make_requests(req_start, h_req_start, parent=None, h_parent=None):
     hp = None if h_parent is None else np.ascontiguousarray(h_parent, dtype=np.int32)
     hp_ptr = None if hp is None else hp.ctypes.data_as(C.POINTER(C.c_int32))
     return Requests(len(hr) - 1, _ptr(req_start), hr.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(parent), hp_ptr), (hr, hp)
+
+
+PHASES = ("norm", "qkv", "attn", "attn_precise", "attn_merge", "o_proj", "gate_up", "down", "other")
+
+
+def confspec_phase_timing(ctx, enable: bool) -> None:
+    _check(ctx, lib.confspec_phase_timing(ctx, 1 if enable else 0))
+
+
+def confspec_phase_times(ctx):
+    """{phase name: (milliseconds, intervals)} of the most recent pass on the context (waits for it)."""
+    ms = (C.c_float * len(PHASES))()
+    n = (C.c_int32 * len(PHASES))()
+    _check(ctx, lib.confspec_phase_times(ctx, ms, n))
+    return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(PHASES)}
 
 
 def confspec_tune(ctx, key: str, value: int) -> None:

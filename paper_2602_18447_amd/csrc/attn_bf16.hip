@@ -772,16 +772,18 @@ static hipError_t launch_attn_variant(const AttnArgs &a, const AttnItem *items, 
     return hipGetLastError();
 }
 
-hipError_t launch_attn_bf16(const AttnArgs &a, const AttnItem *items, const AttnTile *tiles, const int32_t *counts,
-                            int n_items_host, int max_xcd_items, int n_tiles_host, bool any_split, float *part_o,
-                            float *part_ml, hipStream_t s) {
+hipError_t launch_attn_bf16(const AttnTune &tune, const AttnArgs &a, const AttnItem *items, const int32_t *counts,
+                            int n_items_host, int max_xcd_items, float *part_o, float *part_ml, hipStream_t s) {
     if (n_items_host <= 0 || max_xcd_items <= 0) return hipSuccess;
     bool precise = a.q_lo && a.ksuf_lo && a.vsuf_lo;
-    hipError_t e = precise ? launch_attn_variant<true>(a, items, counts, n_items_host, max_xcd_items, part_o, part_ml, s)
-                           : launch_attn_variant<false>(a, items, counts, n_items_host, max_xcd_items, part_o, part_ml, s);
-    if (e != hipSuccess) return e;
-    if (any_split)
-        attn_merge_kernel<<<n_tiles_host * (ATTN_BM / 8), 256, 0, s>>>(a, tiles, counts, n_tiles_host, part_o, part_ml);
+    return precise ? launch_attn_variant<true>(a, items, counts, n_items_host, max_xcd_items, part_o, part_ml, s)
+                   : launch_attn_variant<false>(a, items, counts, n_items_host, max_xcd_items, part_o, part_ml, s);
+}
+
+hipError_t launch_attn_merge(const AttnArgs &a, const AttnTile *tiles, const int32_t *counts, int n_tiles_host,
+                             const float *part_o, const float *part_ml, hipStream_t s) {
+    if (n_tiles_host <= 0) return hipSuccess;
+    attn_merge_kernel<<<n_tiles_host * (ATTN_BM / 8), 256, 0, s>>>(a, tiles, counts, n_tiles_host, part_o, part_ml);
     return hipGetLastError();
 }
 

@@ -48,10 +48,28 @@ struct Settings {
 
 static Settings g_default_settings;   // what a new context starts from; changed by confspec_tune(NULL, ...)
 
+// Phase timing (confspec_phase_timing): HIP events recorded on the pass's stream wherever the pass moves from one
+// phase to the next; interval i runs from event i to event i + 1 and belongs to phase[i].
+struct PhaseTimer {
+    bool enabled = false;
+    std::vector<hipEvent_t> events;
+    std::vector<int> phase;
+    int used = 0;          // events recorded by the last pass
+    bool overflow = false;
+    hipError_t mark(int p, hipStream_t s) {
+        if (!enabled) return hipSuccess;
+        if (used > 0 && phase[used - 1] == p) return hipSuccess;   // still the same phase
+        if (used >= (int)events.size()) { overflow = true; return hipSuccess; }
+        phase[used] = p;
+        return hipEventRecord(events[used++], s);
+    }
+};
+
 struct confspec_ctx {
     confspec_model_cfg cfg;
     int device;
     Settings set;
+    PhaseTimer timer;
     std::string err;
 };
 
@@ -330,9 +348,14 @@ int run_attention(confspec_ctx *ctx, const cs::AttnArgs &a, char *ws, const WsLa
     } else {
         size_t items = last_only ? L.plan2_items : L.plan_items, tiles = last_only ? L.plan2_tiles : L.plan_tiles;
         size_t counts = last_only ? L.plan2_counts : L.plan_counts;
-        HIP_TRY(cs::launch_attn_bf16(a, (const cs::AttnItem *)(ws + items), (const cs::AttnTile *)(ws + tiles),
-                                     (const int32_t *)(ws + counts), (int)pc.n_items, (int)pc.max_xcd_items, (int)pc.n_tiles,
-                                     pc.n_part_slots > 0, (float *)(ws + L.part_o), (float *)(ws + L.part_ml), s));
+        HIP_TRY(cs::launch_attn_bf16(ctx->set.attn, a, (const cs::AttnItem *)(ws + items), (const int32_t *)(ws + counts),
+                                     (int)pc.n_items, (int)pc.max_xcd_items, (float *)(ws + L.part_o),
+                                     (float *)(ws + L.part_ml), s));
+        if (pc.n_part_slots > 0) {
+            HIP_TRY(ctx->timer.mark(CONFSPEC_PHASE_ATTN_MERGE, s));
+            HIP_TRY(cs::launch_attn_merge(a, (const cs::AttnTile *)(ws + tiles), (const int32_t *)(ws + counts),
+                                          (int)pc.n_tiles, (const float *)(ws + L.part_o), (const float *)(ws + L.part_ml), s));
+        }
     }
     return CONFSPEC_OK;
 }
@@ -398,7 +421,11 @@ int confspec_create(const confspec_model_cfg *cfg, int device, confspec_ctx **ou
     return CONFSPEC_OK;
 }
 
-void confspec_destroy(confspec_ctx *ctx) { delete ctx; }
+void confspec_destroy(confspec_ctx *ctx) {
+    if (!ctx) return;
+    for (hipEvent_t e : ctx->timer.events) (void)hipEventDestroy(e);
+    delete ctx;
+}
 
 const char *confspec_last_error(const confspec_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
@@ -567,6 +594,12 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     void *h = ws + L.h;
     float *qkv = (float *)(ws + L.qkv);
 
+    // phase timing: an event at every change of phase (only when switched on; never under stream capture)
+    PhaseTimer &tm_ = ctx->timer;
+    tm_.used = 0;
+    tm_.overflow = false;
+    auto mark = [&](int phase) -> hipError_t { return tm_.mark(phase, s); };
+    HIP_TRY(mark(CONFSPEC_PHASE_OTHER));
     cs::AttnPlanCounts pc, pc_last;
     if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
     // Only the last position of each trace feeds the verdict head, so everything of the last layer that
@@ -606,8 +639,10 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         bool last = prune && l == c.n_layers - 1;
         float *sk = c.dtype == CONFSPEC_DTYPE_BF16 ? (float *)(ws + L.splitk) : nullptr;   // for outputs of few tiles
         size_t skb = sk ? L.splitk_bytes : 0;
+        HIP_TRY(mark(CONFSPEC_PHASE_NORM));
         if (!attn_norm_done) HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[l], h, T, d, c.rms_eps, tm, s));
         attn_norm_done = false;
+        HIP_TRY(mark(CONFSPEC_PHASE_QKV));
         if (rope_fused) {
             cs::RopeArgs ra = {(const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin), ws + L.q, ws + L.ksuf,
                                ws + L.vsuf, prec ? ws + L.q_lo : nullptr, prec ? ws + L.ksuf_lo : nullptr,
@@ -623,7 +658,9 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         }
         cs::AttnArgs a = make_attn_args(c, kv, batch, l, ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
                                         prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, ws + L.attn, tm);
+        HIP_TRY(mark(prec ? CONFSPEC_PHASE_ATTN_PRECISE : CONFSPEC_PHASE_ATTN));
         if ((rc = run_attention(ctx, a, ws, L, last ? pc_last : pc, last, s))) return rc;
+        HIP_TRY(mark(CONFSPEC_PHASE_OTHER));
         if (dev_n_append) {
             // after this layer's attention has read the pages (it never reads rows at or past L_b anyway)
             size_t layer_bytes = (size_t)kv->n_blocks * c.n_kv_heads * kv->block_size * c.head_dim * eb;
@@ -648,7 +685,9 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         cs::NormAfter na;
         na.g = w->mlp_norm[l]; na.h = hr; na.eps = c.rms_eps; na.terms = tm;
         bool mlp_norm_done = false;
+        HIP_TRY(mark(CONFSPEC_PHASE_O_PROJ));
         if ((rc = run_gemm(ctx, attn, wo, xr, rows, d, qw, cs::EPI_RESID_F32, tm, 1, s, sk, skb, nullptr, &na, &mlp_norm_done))) return rc;
+        HIP_TRY(mark(CONFSPEC_PHASE_NORM));
         if (!mlp_norm_done) HIP_TRY(cs::launch_rmsnorm(c.dtype, xr, w->mlp_norm[l], hr, rows, d, c.rms_eps, tm, s));
         // the gate/up projection is compute-bound: while it runs it also pulls the down projection's weights, which
         // that kernel reads in strided pieces, into the last-level cache
@@ -659,7 +698,9 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         cs::PrefetchArgs pf;
         pf.ptr = warm ? wdn : nullptr;
         pf.n16 = warm ? (unsigned)((size_t)d * c.d_ffn * eb / 16) : 0u;
+        HIP_TRY(mark(CONFSPEC_PHASE_GATE_UP));
         if ((rc = run_gemm(ctx, hr, wgu, act, rows, 2 * c.d_ffn, d, cs::EPI_SWIGLU, tm, tm, s, sk, skb, &pf))) return rc;
+        HIP_TRY(mark(CONFSPEC_PHASE_DOWN));
         cs::NormAfter nb;
         const bool has_next = !last && l + 1 < c.n_layers;        // rows == T: the next layer normalises the same rows
         if (has_next) { nb.g = w->attn_norm[l + 1]; nb.h = h; nb.eps = c.rms_eps; nb.terms = format_of(l + 1); }
@@ -667,6 +708,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
                            has_next ? &nb : nullptr, &attn_norm_done)))
             return rc;
     }
+    HIP_TRY(mark(CONFSPEC_PHASE_OTHER));
     if (ex.head) {   // verdict outputs, if any, go to the head's scratch
         char *hs = (char *)ex.head_scratch;
         dev_verdict_logits = (float *)(hs + HL.v_logits);
@@ -700,6 +742,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
                                        va.n_verdict, ex.head->token, ex.head->max_logit, ex.head->lse,
                                        want_verdict ? ex.head->conf_full : nullptr, s));
     }
+    HIP_TRY(mark(CONFSPEC_PHASE_END));
     return CONFSPEC_OK;
 }
 
@@ -967,6 +1010,47 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
     HIP_TRY(cs::launch_verdict(c.dtype, dev_x, (const int32_t *)(ws + L.last_row), dev_final_norm, dev_lm_head, va,
                                batch->B, batch->T, c.d_model, c.rms_eps, dev_verdict_logits, dev_conf, dev_verdict,
                                dev_accept, s));
+    return CONFSPEC_OK;
+}
+
+int confspec_phase_timing(confspec_ctx *ctx, int32_t enable) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    PhaseTimer &t = ctx->timer;
+    if (enable && t.events.empty()) {
+        int rc;
+        if ((rc = check_device(ctx)) != CONFSPEC_OK) return rc;
+        constexpr int N_EVENTS = 2048;     // a pass of 200 layers records fewer
+        t.events.reserve(N_EVENTS);
+        for (int i = 0; i < N_EVENTS; ++i) {
+            hipEvent_t e;
+            HIP_TRY(hipEventCreate(&e));
+            t.events.push_back(e);
+        }
+        t.phase.assign(N_EVENTS, CONFSPEC_PHASE_OTHER);
+    }
+    t.enabled = enable != 0;
+    t.used = 0;
+    return CONFSPEC_OK;
+}
+
+int confspec_phase_times(confspec_ctx *ctx, float *h_ms, int32_t *h_intervals) {
+    if (!ctx || !h_ms) return CONFSPEC_E_INVALID_ARG;
+    PhaseTimer &t = ctx->timer;
+    if (t.used < 2) return fail(ctx, CONFSPEC_E_INVALID_ARG, "no pass has been timed on this context");
+    if (t.overflow) return fail(ctx, CONFSPEC_E_UNSUPPORTED, "the pass changed phase more often than there are events");
+    for (int p = 0; p < CONFSPEC_N_PHASES; ++p) {
+        h_ms[p] = 0.f;
+        if (h_intervals) h_intervals[p] = 0;
+    }
+    HIP_TRY(hipEventSynchronize(t.events[t.used - 1]));
+    for (int i = 0; i + 1 < t.used; ++i) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, t.events[i], t.events[i + 1]));
+        int p = t.phase[i];
+        if (p < 0 || p >= CONFSPEC_N_PHASES) continue;
+        h_ms[p] += ms;
+        if (h_intervals) h_intervals[p] += 1;
+    }
     return CONFSPEC_OK;
 }
 

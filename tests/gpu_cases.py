@@ -56,15 +56,18 @@ def compare(wl, gpu, ora, label=""):
     dc = np.abs(gpu["conf"][tr] - ora["conf"])
     mism = 0
     compared = 0
+    kept = 0                       # compared (trace, tau) pairs whose decision is kept; the rest escalate
     for i, tau in enumerate(gpu["taus"]):
         clear = np.abs(ora["conf"] - tau) > tol["band"]
         compared += int(clear.sum())
+        kept += int(ora["accept"][i][clear].sum())
         mism += int((gpu["accept"][i][tr][clear] != ora["accept"][i][clear]).sum())
     srt = np.sort(ora["logits"], axis=1)
     decided = (srt[:, -1] - srt[:, -2]) > 2 * tol["logit"]
     vmis = int((gpu["verdict"][tr][decided] != ora["verdict"][decided]).sum())
     summary = dict(label=label, traces=len(tr), max_dlogit=float(dl.max()), max_dconf=float(dc.max()),
-                   gate_compared=compared, gate_mismatch=mism, verdict_mismatch=vmis,
+                   gate_compared=compared, gate_kept=kept, gate_escalated=compared - kept, gate_mismatch=mism,
+                   verdict_mismatch=vmis,
                    accept_counts=[int(a.sum()) for a in gpu["accept"]])
     print("parity", summary, flush=True)
     assert dl.max() <= tol["logit"], summary
@@ -76,6 +79,15 @@ def compare(wl, gpu, ora, label=""):
     acc = gpu["accept"][order]
     assert np.all(acc[1:] <= acc[:-1]), "accept set must shrink as tau rises"
     return summary
+
+
+# Thresholds for the full-size cases: the workload's own plus a sweep through the range where random-init
+# confidences fall (0.5 .. 0.7), so that kept and escalated decisions both occur among the compared traces.
+SWEEP_TAUS = (0.52, 0.55, 0.6, 0.7)
+
+
+def sweep_taus(wl):
+    return sorted(set(float(t) for t in wl.taus) | set(SWEEP_TAUS))
 
 
 def parity_case(wl, traces=None, taus=None, label=None):

@@ -171,6 +171,51 @@ def test_append_full_size_config2_sampled_traces():
     ver.close()
 
 
+def test_full_size_context_built_by_chunked_prefill_then_verified():
+    """Config 2's contexts (32 traces of 2048 tokens, 28 layers) built by this library's own kernels - four passes of
+    512 context tokens per trace with write-back of everything - instead of seeded pages; then the verification
+    pass on top, against the oracle reading the cache the GPU wrote, with the threshold sweep."""
+    print("config 2 on a cache built by chunked prefill", flush=True)
+    wl = W.config(2)
+    m = wl.model
+    weights = W.make_weights(m, wl.seed, DEV)
+    final = W.make_batch(wl, DEV)
+    ctx_ids = W.make_prefix_ids(wl)
+    dt = W.torch_dtype(m.dtype)
+    shape = (m.n_layers, final.n_blocks, m.n_kv_heads, 16, m.head_dim)
+    kv = W.KVCache(torch.zeros(shape, dtype=dt, device=DEV), torch.zeros(shape, dtype=dt, device=DEV), 16)
+    ver = Verifier(m, weights)
+    vids = W.draw_verdict_ids(wl)
+    chunk = 512
+    for start in range(0, 2048, chunk):
+        cu = (np.arange(wl.B + 1) * chunk).astype(np.int32)
+        ids = np.concatenate([ctx_ids[b][start:start + chunk] for b in range(wl.B)]).astype(np.int32)
+        done = np.full(wl.B, start, dtype=np.int32)
+        part = W.Batch(suffix_ids=torch.from_numpy(ids).to(DEV), cu_suffix=torch.from_numpy(cu).to(DEV),
+                       prefix_lens=torch.from_numpy(done).to(DEV), block_table=final.block_table,
+                       n_blocks=final.n_blocks, max_blocks_per_seq=final.max_blocks_per_seq, block_size=16,
+                       h_cu_suffix=cu, h_prefix_lens=done)
+        ver.verify_append(kv, part, np.full(wl.B, chunk, dtype=np.int32), vids, [0.5])
+        torch.cuda.synchronize()
+    # one trace's context against the oracle's own prefix pass over the same tokens (keys / values of every layer)
+    b = 17
+    k_ref, v_ref = O.prefix_pass(m, W.OracleModelView(weights), [ctx_ids[b]])
+    table = final.block_table.cpu().numpy()
+    worst = 0.0
+    for l in range(m.n_layers):
+        for pages, ref in ((kv.k_pages, k_ref[l][0]), (kv.v_pages, v_ref[l][0])):
+            got = _rows(pages[l], table, b, 0, 2048, 16)
+            worst = max(worst, np.abs(got - ref).max() / np.abs(ref).max())
+    print(f"trace {b}: context built in chunks vs the oracle's prefix pass, worst relative error {worst:.2e}", flush=True)
+    assert worst <= KV_TOL["bf16"]
+    taus = G.sweep_taus(wl)
+    gpu = G.run_gpu(wl, weights, final, kv, taus=taus, verifier=ver)
+    ora = G.run_oracle(wl, weights, final, kv, gpu["taus"], gpu["vids"], traces=[3, 17, 28])
+    s = G.compare(wl, gpu, ora, "config 2 on the GPU-built context")
+    assert s["gate_kept"] > 0 and s["gate_escalated"] > 0, s
+    ver.close()
+
+
 def test_append_of_nothing_leaves_the_cache_alone():
     print("append nothing", flush=True)
     wl = W.tiny_workload("append0", 5300, dtype="bf16", n_layers=2, d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128,

@@ -33,11 +33,18 @@ def _pair(seed, prefix_lens, suffix_lens, dtype="bf16"):
     return wl_d, wl_t
 
 
-def _sides(wl_d, wl_t):
+def _sides(wl_d, wl_t, head_scale=1.0):
+    """head_scale: factor on the verdict tokens' rows of both heads (a power of two, so exact in the storage type).
+    The tiny random models of these tests decide most steps by a few hundredths of a logit, inside the band where
+    two precisions may disagree; wider logit gaps put nearly every decision and ranking clear of it, so that the
+    integer outputs are compared on nearly every request instead of a minority."""
     batch = W.make_batch(wl_d, DEV)
+    vids = torch.as_tensor(np.asarray(W.draw_verdict_ids(wl_d), dtype=np.int64), device=DEV)
     out = []
     for wl in (wl_d, wl_t):
         weights = W.make_weights(wl.model, wl.seed, DEV)
+        if head_scale != 1.0:
+            weights.lm_head[vids] = weights.lm_head[vids] * head_scale
         kv = W.make_seeded_kv(wl, batch, DEV)
         out.append(dict(wl=wl, weights=weights, kv=kv, ver=Verifier(wl.model, weights),
                         ora=dict(cfg=wl.model, model=W.OracleModelView(weights), kv=W.OracleKVView(kv, batch))))
@@ -123,7 +130,7 @@ def test_cascade_matches_oracle_on_ragged_requests(dtype):
     prefix[3], suffix[5] = 0, 1
     req_start = [0, 1, 4, 9, 10, 12, 17, 20, 26]            # requests of 1 to 6 drafted steps
     wl_d, wl_t = _pair(3100, prefix, suffix, dtype)
-    batch, sd, st = _sides(wl_d, wl_t)
+    batch, sd, st = _sides(wl_d, wl_t, head_scale=4.0)
     vids = W.draw_verdict_ids(wl_d)
     casc = Cascade(sd["ver"], st["ver"])
     ids, cu, pl = batch.suffix_ids.cpu().numpy(), batch.h_cu_suffix, batch.h_prefix_lens
@@ -140,7 +147,8 @@ def test_cascade_matches_oracle_on_ragged_requests(dtype):
             assert n_target == 0 and not res["escalated"].any()
         if gamma == 1.5:
             assert bool(res["target_ran"].all())           # nothing is confident, so nothing is cut off before the pass
-    assert total >= 0.7 * len(gammas) * (len(req_start) - 1)
+    print(f"requests compared bit for bit: {total}/{len(gammas) * (len(req_start) - 1)}", flush=True)
+    assert total >= 0.9 * len(gammas) * (len(req_start) - 1)
     # a second call on the same buffers with a different request split: single-step requests
     single = list(range(B + 1))
     ora = O.cascade_verify(sd["ora"], st["ora"], wl_d.block_size, ids, cu, pl, vids, gammas[2], single)
@@ -229,14 +237,22 @@ def test_cascade_full_size_draft_and_target_shapes():
 
 
 def _layers_clear(parent, lo, hi, ora, tol):
-    """True if, in every layer the oracle's walk looked at, the accepted candidates' confidences are far enough apart
-    that both precisions rank them alike."""
+    """True if, in every layer the oracle's walk looked at, the accepted candidates are ranked alike by both
+    precisions.  Two sufficient conditions, either will do for a pair: their confidences differ by more than twice
+    the confidence bound; or (two verdict tokens: the confidence is a monotone function of the logit gap |z0 - z1|)
+    their gaps differ by more than four times the logit bound (each gap is off by at most twice that bound)."""
     reached = ora["decision"][lo:hi] != O.NOT_REACHED
+    used = np.where(ora["escalated"].astype(bool)[:, None], np.nan_to_num(ora["logits_target"]), ora["logits_draft"])
+    two = used.shape[1] == 2
+    gap = np.abs(used[:, 0] - used[:, 1]) if two else None
     for cur in [-1] + [lo + j for j in np.flatnonzero(ora["selected"][lo:hi])]:
         kids = [b for b in range(lo, hi) if parent[b] == cur and reached[b - lo] and ora["decision"][b] == 0]
-        ps = sorted(ora["conf_used"][b] for b in kids)
-        if any(b - a <= 2 * tol["conf"] for a, b in zip(ps[:-1], ps[1:])):
-            return False
+        for i, a in enumerate(kids):
+            for b in kids[i + 1:]:
+                by_conf = abs(ora["conf_used"][a] - ora["conf_used"][b]) > 2 * tol["conf"]
+                by_gap = two and abs(gap[a] - gap[b]) > 4 * tol["logit"]
+                if not (by_conf or by_gap):
+                    return False
     return True
 
 
@@ -261,7 +277,7 @@ def test_cascade_over_candidate_trees_matches_oracle(dtype):
     prefix = [base[int(req_of[b])] + 37 * int(depth[b]) for b in range(B)]   # siblings: equal context length
     suffix = [int(v) for v in rng.integers(1, 70, size=B)]
     wl_d, wl_t = _pair(3300, prefix, suffix, dtype)
-    batch, sd, st = _sides(wl_d, wl_t)
+    batch, sd, st = _sides(wl_d, wl_t, head_scale=4.0)
     # candidates that continue the same step share that step's context: same block-table row
     table = batch.block_table.clone()
     first = {}
@@ -286,11 +302,16 @@ def test_cascade_over_candidate_trees_matches_oracle(dtype):
         res, n_target = casc.run(sd["kv"], st["kv"], batch, req_start, vids, gamma, parent=parent)
         torch.cuda.synchronize()
         g = {k: v.cpu().numpy() for k, v in res.items()}
+        # a candidate is clear of every decision boundary if its small-model confidence is outside the band around
+        # gamma and the decision that counts for it - the small model's where kept, the large model's where it was
+        # consulted - is taken by more than twice the logit bound (the small model's arg max does not enter the
+        # outcome of a candidate that escalates)
         gap_d = np.abs(np.diff(np.sort(ora["logits_draft"], axis=1)[:, -2:], axis=1))[:, 0]
-        clear = (np.abs(ora["conf_draft"] - gamma) > tol["band"]) & (gap_d > 2 * tol["logit"])
+        kept = ora["conf_draft"] >= gamma
         asked = ~np.isnan(ora["conf_target"])
         lt = np.sort(np.nan_to_num(ora["logits_target"]), axis=1)
-        clear &= ~asked | ((lt[:, -1] - lt[:, -2]) > 2 * tol["logit"])
+        clear = np.abs(ora["conf_draft"] - gamma) > tol["band"]
+        clear &= np.where(kept, gap_d > 2 * tol["logit"], ~asked | ((lt[:, -1] - lt[:, -2]) > 2 * tol["logit"]))
         for r, (lo, hi) in enumerate(zip(req_start[:-1], req_start[1:])):
             total += 1
             reached = ora["decision"][lo:hi] != O.NOT_REACHED
@@ -317,7 +338,7 @@ def test_cascade_over_candidate_trees_matches_oracle(dtype):
         print(f"trees gamma={gamma:.4f}: in the large model's pass {n_target}/{B}, chosen steps {g['accepted_steps'].tolist()}",
               flush=True)
     print(f"requests compared bit for bit: {compared}/{total}", flush=True)
-    assert compared >= 0.4 * total          # small random models decide many steps by less than the logit bound
+    assert compared >= 0.9 * total
 
 
 def test_cascade_single_trace_batch():

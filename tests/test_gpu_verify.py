@@ -189,15 +189,25 @@ def test_weight_prefetch_hint_changes_no_bit():
         assert np.array_equal(res[0][k], res[1][k])
 
 
+def _full_size(cfg, traces):
+    """Full-size GPU pass (the launch configuration the benchmark times) against the oracle on sampled traces, with
+    the threshold sweep; both gate outcomes must occur among the compared decisions."""
+    wl = W.config(cfg)
+    s, gpu, _ = G.parity_case(wl, traces=traces, taus=G.sweep_taus(wl))
+    assert s["traces"] == len(traces)
+    assert s["gate_kept"] > 0 and s["gate_escalated"] > 0, s
+    return s, gpu
+
+
 def test_config2_draft_shape_full_size_sampled_traces():
     print("config 2", flush=True)
-    G.parity_case(W.config(2), traces=[0, 13, 31])
+    _full_size(2, [0, 7, 13, 22, 31])
 
 
 def test_config3_long_cot_tau_sweep_sampled_traces():
     print("config 3", flush=True)
-    s, gpu, _ = G.parity_case(W.config(3), traces=[0, 5, 7, 21, 33, 40, 63])
-    assert len(gpu["taus"]) == 3
+    s, gpu = _full_size(3, [0, 5, 7, 21, 33, 40, 63])
+    assert {0.8, 0.9, 0.95} <= set(gpu["taus"])
 
 
 def test_config4_ragged_sampled_traces():
@@ -205,13 +215,14 @@ def test_config4_ragged_sampled_traces():
     wl = W.config(4)
     L = np.asarray(wl.prefix_lens)
     S = np.asarray(wl.suffix_lens)
-    pick = sorted({int(np.argmin(L)), int(np.argmax(L)), int(np.argmin(S)), 77})
-    G.parity_case(wl, traces=pick)
+    pick = sorted({int(np.argmin(L)), int(np.argmax(L)), int(np.argmin(S)), int(np.argmax(S)), 3, 40, 77, 101, 127})
+    assert len(pick) >= 8
+    _full_size(4, pick)
 
 
-def test_config5_target_shape_sampled_trace():
+def test_config5_target_shape_sampled_traces():
     print("config 5", flush=True)
-    G.parity_case(W.config(5), traces=[9])
+    _full_size(5, [0, 4, 9, 15])
 
 
 @pytest.mark.parametrize("seed", [3101, 3102, 3103, 3104, 3105, 3106])
