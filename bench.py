@@ -340,26 +340,51 @@ def _optional_legs(args, st, dev):
                                extra_ms_vs_eager_pass=round(ms_a - eager_ms, 4))
 
     if args.shared_prefix > 1:
+        # Groups of W traces as the W candidates of one step (Section 4.3): their block-table rows name the same pages.
+        # "aliased": the plain pass on that batch (pages shared, every candidate tiled on its own);
+        # "grouped": confspec_verify_shared (the candidates of a group side by side in the attention row tiles).
+        # Measured for the workload's own suffix lengths and for short steps of 16 tokens.
         import copy
         Wd = args.shared_prefix
-        batch_s = copy.copy(batch)
-        table = batch.block_table.clone()
-        for b in range(wl.B):
-            table[b] = batch.block_table[b - b % Wd]         # prefix lengths are equal inside a group in this workload
-        batch_s.block_table = table
-        for _ in range(3):
-            ver.verify(kv, batch_s, vids, taus, outputs=outs)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(args.steps):
-            ver.verify(kv, batch_s, vids, taus, outputs=outs)
-        e1.record()
-        torch.cuda.synchronize()
-        ms_s = e0.elapsed_time(e1) / args.steps
-        extra["shared_prefix"] = dict(group=Wd, ms_per_step=round(ms_s, 4), launch="eager",
-                                      distinct_pages_ms_per_step=round(eager_ms, 4),
-                                      context_bytes_distinct=int(sum(wl.prefix_lens)) * m.n_layers * 2 * m.n_kv_heads * m.head_dim * 2,
-                                      context_bytes_shared=int(sum(wl.prefix_lens[::Wd])) * m.n_layers * 2 * m.n_kv_heads * m.head_dim * 2)
+        gstart = list(range(0, wl.B, Wd)) + [wl.B]
+        G_, Hkv = m.n_q_heads // m.n_kv_heads, m.n_kv_heads
+
+        def stagings(S, L, groups):
+            tiles = lambda rows: -(-rows // 128)   # noqa: E731
+            plain = sum(Hkv * tiles(G_ * s_) * -(-l_ // 64) for s_, l_ in zip(S, L))
+            grouped = sum(Hkv * tiles(G_ * sum(S[lo:hi])) * -(-L[lo] // 64) for lo, hi in zip(groups[:-1], groups[1:]))
+            return plain, grouped
+
+        def timed(fn):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps
+
+        res = {}
+        for label, wl_s in (("own_suffix", wl), ("suffix_16", W.Workload(wl.name + "_s16", m, wl.seed, wl.prefix_lens, (16,) * wl.B))):
+            b_s = batch if wl_s is wl else W.make_batch(wl_s, dev)
+            kv_s = kv if wl_s is wl else W.make_seeded_kv(wl_s, b_s, dev)
+            b_s = copy.copy(b_s)
+            table = b_s.block_table.clone()
+            for b in range(wl.B):
+                table[b] = b_s.block_table[b - b % Wd]         # prefix lengths are equal inside a group in these workloads
+            b_s.block_table = table
+            o_s = ver.alloc_outputs(wl.B, len(vids), len(taus))
+            ms_alias = timed(lambda: ver.verify(kv_s, b_s, vids, taus, outputs=o_s))
+            ref = o_s[0].clone()
+            ms_group = timed(lambda: ver.verify_shared(kv_s, b_s, gstart, vids, taus, outputs=o_s))
+            torch.cuda.synchronize()
+            plain_st, grouped_st = stagings(list(wl_s.suffix_lens), list(wl_s.prefix_lens), gstart)
+            res[label] = dict(aliased_ms_per_step=round(ms_alias, 4), grouped_ms_per_step=round(ms_group, 4),
+                              context_chunk_stagings_per_layer=dict(aliased=plain_st, grouped=grouped_st),
+                              max_abs_dlogit_grouped_vs_aliased=float((o_s[0] - ref).abs().max().item()))
+        extra["shared_prefix"] = dict(group=Wd, launch="eager", distinct_pages_ms_per_step=round(eager_ms, 4), **res)
 
     if args.decode > 0:
         nst = args.decode

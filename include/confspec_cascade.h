@@ -82,6 +82,25 @@ int confspec_cascade(confspec_ctx *draft, const confspec_weights *draft_weights,
                      size_t scratch_bytes, const confspec_cascade_out *out, int32_t *h_n_target,
                      confspec_stream stream);
 
+/* The verification pass for candidates that share their context (Section 4.3: the W candidates of one step of
+ * tree-structured drafting are verified in parallel on top of the same chain of thought).  Same inputs and outputs
+ * as confspec_verify plus a partition of the batch into groups of consecutive traces:
+ *   group_start  : dev int32 [n_groups + 1], h_group_start a host copy; group_start[0] = 0,
+ *                  group_start[n_groups] = B, strictly increasing.
+ * The traces of a group must have the same prefix length, and their block-table rows must name the same pages
+ * (the kernels read the context of the whole group through the row of its first trace).  Attention then lays the
+ * query rows of all candidates of a group side by side in its row tiles, so that every context chunk is staged
+ * once per 128 rows of the group rather than once per 128 rows of each candidate; the suffix keys stay per
+ * candidate (a row sees its own trace's tokens only).  Results equal those of confspec_verify on the same batch up
+ * to the rounding differences of differently cut attention pieces.  Groups of one trace are the plain pass.
+ * Errors: as confspec_verify; CONFSPEC_E_OUT_OF_RANGE for a malformed partition or unequal prefix lengths inside
+ * a group. */
+int confspec_verify_shared(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
+                           const confspec_batch *batch, const int32_t *dev_group_start, const int32_t *h_group_start,
+                           int32_t n_groups, const int32_t *h_verdict_ids, int32_t n_verdict, const float *h_tau,
+                           int32_t n_tau, void *dev_workspace, size_t workspace_bytes, float *dev_verdict_logits,
+                           float *dev_conf, int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -126,6 +126,9 @@ def _load() -> C.CDLL:
     lib.confspec_verify_static.restype = C.c_int
     lib.confspec_verify_static.argtypes = [vp, P(Weights), P(KV), P(Batch), P(i32), i32, P(C.c_float), i32,
                                            vp, vp, vp, vp, vp]
+    lib.confspec_verify_shared.restype = C.c_int
+    lib.confspec_verify_shared.argtypes = [vp, P(Weights), P(KV), P(Batch), vp, P(i32), i32, P(i32), i32, P(C.c_float), i32,
+                                           vp, sz, vp, vp, vp, vp, vp]
     lib.confspec_phase_timing.restype = C.c_int
     lib.confspec_phase_timing.argtypes = [vp, i32]
     lib.confspec_phase_times.restype = C.c_int
@@ -142,7 +145,7 @@ EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec
             "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_qkv_rope", "confspec_op_attention",
             "confspec_op_verdict_gate", "confspec_tune", "confspec_cascade_scratch_bytes",
             "confspec_cascade", "confspec_verify_append", "confspec_head_scratch_bytes", "confspec_generate_step",
-            "confspec_static_scratch_need", "confspec_verify_static", "confspec_phase_timing", "confspec_phase_times"]
+            "confspec_static_scratch_need", "confspec_verify_static", "confspec_phase_timing", "confspec_phase_times", "confspec_verify_shared"]
 
 
 class ConfSpecError(RuntimeError):
@@ -220,6 +223,20 @@ def confspec_verify(ctx, w: Weights, kv: KV, batch: Batch, verdict_ids: Sequence
     _check(ctx, lib.confspec_verify(ctx, C.byref(w), C.byref(kv), C.byref(batch), ids, nv, tau, nt,
                                     _ptr(workspace), ws_bytes, _ptr(logits), _ptr(conf), _ptr(verdict),
                                     _ptr(accept), _stream_handle(stream)))
+
+
+def confspec_verify_shared(ctx, w: Weights, kv: KV, batch: Batch, group_start, h_group_start, verdict_ids: Sequence[int],
+                           taus: Sequence[float], workspace, logits, conf, verdict, accept, stream=None) -> None:
+    """group_start: device int32 tensor [n_groups + 1]; h_group_start: the same values as a host int32 numpy array."""
+    import numpy as np
+    nv, nt = len(verdict_ids), len(taus)
+    ids = (C.c_int32 * max(nv, 1))(*[int(v) for v in verdict_ids])
+    tau = (C.c_float * max(nt, 1))(*[float(t) for t in taus])
+    hg = np.ascontiguousarray(h_group_start, dtype=np.int32)
+    _check(ctx, lib.confspec_verify_shared(ctx, C.byref(w), C.byref(kv), C.byref(batch), _ptr(group_start),
+                                           hg.ctypes.data_as(C.POINTER(C.c_int32)), len(hg) - 1, ids, nv, tau, nt,
+                                           _ptr(workspace), _nbytes(workspace), _ptr(logits), _ptr(conf), _ptr(verdict),
+                                           _ptr(accept), _stream_handle(stream)))
 
 
 STATIC_SCRATCH_BYTES = 64 << 20

@@ -11,7 +11,8 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libconfspec.so")
 
-SOURCES = ["confspec_api.hip", "kernels_small.hip", "path_f32.hip", "gemm_bf16.hip", "attn_bf16.hip", "cascade.hip"]
+SOURCES = ["confspec_api.hip", "kernels_small.hip", "path_f32.hip", "gemm_bf16.hip", "attn_bf16.hip", "cascade.hip",
+           "attn_plan.cpp"]
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -30,7 +31,7 @@ def build(verbose: bool = True, jobs: int = 6) -> str:
     hipcc = _hipcc()
 
     def compile_one(src: str) -> str:
-        obj = os.path.join(BUILD_DIR, src.replace(".hip", ".o"))
+        obj = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".o")
         cmd = [hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:

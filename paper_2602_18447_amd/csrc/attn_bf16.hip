@@ -1,265 +1,73 @@
-// Grouped-query causal attention of suffix queries over the paged prefix cache plus the suffix's own
+// Grouped-query causal attention of suffix queries over the paged context cache plus the suffix's own
 // keys, bf16 operands on the gfx950 matrix cores, fp32 online softmax.
 //
-// Decomposition.  All G query heads that share one kv head are folded into the row dimension: a
-// trace with S suffix tokens contributes G*S rows per kv head, flattened position-major
-// (row = t*G + g), cut into tiles of 128 rows; one wavefront owns 32 rows.  The key range of a tile
-// is cut into 64-key chunks, and - to balance ragged batches and fill 256 CUs - into several work
-// items whose partial (max, sum, unnormalised output) results are merged by a second kernel in a
-// fixed order.
+// Decomposition.  All G query heads that share one kv head are folded into the row dimension: a context
+// unit (one trace, or a run of traces whose candidate steps sit on the same cached context) with S suffix
+// tokens contributes G*S rows per kv head, flattened token-major (row = t*G + g), cut into tiles of 128
+// rows; one wavefront owns 32 rows.  The keys of a tile are a list of 64-key chunks - the chunks of the
+// context, then the chunks of the suffix tokens its rows can see (attn_plan.h) - and, to balance ragged
+// batches and fill 256 CUs, that list is cut into several work items whose partial (max, sum,
+// unnormalised output) results are merged by a second kernel in a fixed order.
 //
-// Per chunk a workgroup stages K as [key][hd] and V transposed as [hd][key] in LDS.  Scores are
-// computed transposed, S^T = K . Q^T (keys on MFMA rows, queries on columns), so each lane owns one
-// query column: the running max / sum and the rescale of the output accumulator are lane-local
-// apart from one exchange between lane l and l+32.  The rows of each 32-key block are fed to the
-// MFMA in a permuted order chosen so that the probabilities a lane ends up holding are 8
-// consecutive keys per k-step: they are used as the B operand of O^T += V^T . P^T straight from
-// registers, and the matching A operand is a single 16-byte read of the transposed V tile.
+// Scores are computed transposed, S^T = K . Q^T (keys on MFMA rows, queries on columns), so each lane owns
+// one query column: the running max / sum and the rescale of the output accumulator are lane-local apart
+// from one exchange between lane l and l+32, and the probabilities a lane ends up holding are directly the
+// B operand of O^T += V^T . P^T.
+//
+// Two main loops:
+//  * attn_pipe_kernel (default): K and V chunks travel global -> LDS directly (no staging registers, no
+//    transposition on the way), V^T fragments come from transposing LDS reads, and the loop is software
+//    pipelined inside each wavefront: the score MFMAs of chunk i+1 are issued between the softmax
+//    instructions of chunk i, so the matrix pipe and the vector ALU of a SIMD work at the same time.
+//  * attn_staged_kernel (the two-term variant of the first layer(s); selectable for measurements): chunks go
+//    through registers, V is transposed with byte permutes on the way into LDS.
 #include "kernels.h"
-#include <algorithm>
-#include <cmath>
-#include <queue>
-#include <vector>
+#include <type_traits>
+#include <utility>
 
 namespace cs {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
+typedef __attribute__((ext_vector_type(8))) short i16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
+#define CS_GLOBAL_AS __attribute__((address_space(1)))
+#define CS_LDS_AS __attribute__((address_space(3)))
+// vmcnt(n) only (expcnt / lgkmcnt left unconstrained), gfx9 encoding of s_waitcnt
+#define CS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
 constexpr int HD = 128;
-constexpr int K_STRIDE = 136;             // elements per K row in LDS (128 + 8 pad = 272 bytes)
-constexpr int VT_STRIDE = 72;             // elements per V^T row in LDS (64 + 8 pad = 144 bytes)
-constexpr int K_TILE = ATTN_BN * K_STRIDE;
-constexpr int VT_TILE = HD * VT_STRIDE;
-constexpr int ATTN_STAGE = K_TILE + VT_TILE;   // elements per stage
-constexpr int ATTN_SMEM_BYTES = 2 * ATTN_STAGE * 2;
 
-__host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
-
-// ---- planning: identical arithmetic on host (counts only) and device (counts + lists) ----
-// Every tile of a trace is cut into n_split pieces of `piece` chunks (the last piece takes what is
-// left and may be empty for the trace's shorter tiles).  Two ways to choose the pieces:
-//   equal pieces : n_split = ceil(nc / cpi), piece = ceil(nc / n_split);
-//   front-loaded : piece = cpi, so that the first pieces are long and a short remainder follows.
-// The item list is built per XCD (workgroup id % 8 selects the XCD, each XCD takes a contiguous range
-// of tiles so that the row tiles of one trace and kv head share an L2): first the first pieces of all
-// its tiles, then all the other pieces.  Workgroups are dispatched in id order, so the long pieces
-// start first and the short ones fill the gaps when slots free up (longest-first list scheduling).
-constexpr int ATTN_MAX_SPLIT = 32;
-struct TracePlan {
-    int n_qt;      // q-row tiles per kv head
-    int n_split;   // pieces of every tile of this trace
-    int nc_max;    // chunks of the trace's last tile
-    int piece;     // chunks per piece
-};
-// last_only: the plan covers the last suffix position of each trace only (its G rows per kv head form
-// one tile that starts at row (S-1)*G), which is all the last decoder layer has to produce.
-__host__ __device__ inline TracePlan trace_plan(int L, int S, int G, int cpi, int equalize, int last_only) {
-    TracePlan p;
-    p.n_qt = S > 0 ? (last_only ? 1 : ceil_div(G * S, ATTN_BM)) : 0;
-    p.nc_max = ceil_div(L + S, ATTN_BN);
-    int n = p.nc_max > cpi ? ceil_div(p.nc_max, cpi) : 1;
-    bool clamped = n > ATTN_MAX_SPLIT;
-    p.n_split = clamped ? ATTN_MAX_SPLIT : n;
-    p.piece = (equalize || clamped) ? ceil_div(max(p.nc_max, 1), p.n_split) : cpi;
-    return p;
-}
-__host__ __device__ inline int tile_chunks(int L, int S, int G, int m) {
-    int r_last = min(m * ATTN_BM + ATTN_BM - 1, G * S - 1);
-    return ceil_div(L + r_last / G + 1, ATTN_BN);
-}
-// XCD x takes the contiguous range of tiles [tile_lo[x], tile_lo[x+1]); the cuts are placed where the
-// running sum of chunks (every tile of a trace counted with the trace's longest) passes x/8 of the total.
-// A cut that falls inside (or at the end of) this trace's tiles is written here, together with the number
-// of items in front of it: the tiles before it plus their pieces other than the first.
-__host__ __device__ inline void plan_xcd_starts(const TracePlan &p, int Hkv, int tile_base, int rest_base,
-                                                long long work_base, long long work_total, int *tile_lo,
-                                                int *seg_base) {
-    int my_tiles = Hkv * p.n_qt;
-    if (my_tiles <= 0 || p.nc_max <= 0) return;
-    long long work_end = work_base + (long long)my_tiles * p.nc_max;
-    for (int x = 1; x < 8; ++x) {
-        long long target = (x * work_total + 7) / 8;
-        if (target > work_base && target <= work_end) {
-            int j = (int)((target - work_base + p.nc_max - 1) / p.nc_max);   // 1 .. my_tiles
-            tile_lo[x] = tile_base + j;
-            seg_base[x] = tile_base + j + rest_base + j * (p.n_split - 1);
-        }
-    }
-}
-
-// Tiles and items of one trace.  tile_base / rest_base / slot_base: tiles, pieces other than the first,
-// and partial slots of all earlier traces.
-__host__ __device__ inline void plan_emit_trace(int b, int L, int S, int G, int Hkv, const TracePlan &p, int tile_base,
-                                                int rest_base, int slot_base, const int *tile_lo, const int *seg_base,
-                                                int last_only, int max_tiles, int max_items, AttnTile *tiles,
-                                                AttnItem *items) {
-    for (int c = 0; c < Hkv; ++c)
-        for (int m = 0; m < p.n_qt; ++m) {
-            int local = c * p.n_qt + m;
-            int ti = tile_base + local;
-            int pbase = p.n_split > 1 ? slot_base + local * p.n_split : -1;
-            int row0 = last_only ? (S - 1) * G : m * ATTN_BM;
-            if (ti < max_tiles) {
-                AttnTile t;
-                t.b = b; t.c = c; t.row0 = row0; t.part_base = pbase; t.n_splits = p.n_split;
-                t.pad[0] = t.pad[1] = t.pad[2] = 0;
-                tiles[ti] = t;
-            }
-            int x = 7;
-            while (x > 0 && tile_lo[x] > ti) --x;
-            int lo = tile_lo[x], hi = tile_lo[x + 1];
-            int rest_before = rest_base + local * (p.n_split - 1);   // other pieces of all earlier tiles
-            int rest_lo = seg_base[x] - lo;                          // the same count at the start of the range
-            int nc = last_only ? p.nc_max : tile_chunks(L, S, G, m);
-            for (int sp = 0; sp < p.n_split; ++sp) {
-                int idx = sp == 0 ? seg_base[x] + (ti - lo) : seg_base[x] + (hi - lo) + (rest_before - rest_lo) + sp - 1;
-                if (idx < 0 || idx >= max_items || pbase + sp >= max_items) continue;
-                AttnItem it;
-                it.b = b; it.c = c; it.row0 = row0;
-                it.chunk_begin = min(sp * p.piece, nc);
-                it.chunk_end = sp == p.n_split - 1 ? nc : min((sp + 1) * p.piece, nc);
-                it.part_slot = p.n_split > 1 ? pbase + sp : -1;
-                it.tile = ti; it.pad = 0;
-                items[idx] = it;
-            }
-        }
-}
-
-void attn_plan_capacity(const AttnTune &tune, int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles,
-                        int64_t *max_items) {
-    int64_t tiles = (int64_t)Hkv * ((G * max_T + ATTN_BM - 1) / ATTN_BM + max_B);
-    *max_tiles = tiles;
-    *max_items = 3 * tiles + 4 * tune.target_items;     // candidates that need more are not considered
-}
-
-namespace {
-struct TraceShape { int tiles, nc; };
-struct Candidate { int cpi, equalize; };
-
-// Items, partial slots and the largest per-XCD item count of a candidate; lens (optional) receives the
-// per-XCD piece lengths in dispatch order.  Same arithmetic as the device planner.
-void candidate_counts(const std::vector<TraceShape> &tr, Candidate cd, int64_t n_tiles, int64_t work_total,
-                      AttnPlanCounts *r, std::vector<int> *lens /* [8] */) {
-    r->n_items = 0; r->n_part_slots = 0; r->max_xcd_items = 0;
-    int tile_lo[9] = {0}, seg_base[9] = {0};
-    int tile_base = 0, rest_base = 0;
-    long long work_base = 0;
-    std::vector<TracePlan> plans;
-    plans.reserve(tr.size());
-    for (const TraceShape &t : tr) {
-        TracePlan p;
-        p.n_qt = t.tiles; p.nc_max = t.nc;       // n_qt holds Hkv * n_qt here (Hkv = 1 below)
-        int n = t.nc > cd.cpi ? ceil_div(t.nc, cd.cpi) : 1;
-        bool clamped = n > ATTN_MAX_SPLIT;
-        p.n_split = clamped ? ATTN_MAX_SPLIT : n;
-        p.piece = (cd.equalize || clamped) ? ceil_div(std::max(t.nc, 1), p.n_split) : cd.cpi;
-        plans.push_back(p);
-        plan_xcd_starts(p, 1, tile_base, rest_base, work_base, work_total, tile_lo, seg_base);
-        r->n_items += (int64_t)t.tiles * p.n_split;
-        if (p.n_split > 1) r->n_part_slots += (int64_t)t.tiles * p.n_split;
-        tile_base += t.tiles; rest_base += t.tiles * (p.n_split - 1);
-        work_base += (long long)t.tiles * t.nc;
-    }
-    tile_lo[8] = (int)n_tiles;
-    seg_base[8] = (int)r->n_items;
-    for (int x = 0; x < 8; ++x) r->max_xcd_items = std::max<int64_t>(r->max_xcd_items, seg_base[x + 1] - seg_base[x]);
-    if (!lens) return;
-    std::vector<int> rest_lens[8];
-    int ti = 0;
-    for (size_t i = 0; i < tr.size(); ++i)
-        for (int j = 0; j < tr[i].tiles; ++j, ++ti) {
-            int x = 7;
-            while (x > 0 && tile_lo[x] > ti) --x;
-            const TracePlan &p = plans[i];
-            lens[x].push_back(std::min(p.piece, p.nc_max));
-            for (int sp = 1; sp < p.n_split; ++sp)
-                rest_lens[x].push_back(std::max(0, std::min(p.piece, p.nc_max - sp * p.piece)));
-        }
-    for (int x = 0; x < 8; ++x) lens[x].insert(lens[x].end(), rest_lens[x].begin(), rest_lens[x].end());
-}
-
-// Makespan of longest-first list scheduling on slots/8 workgroup slots per XCD, in chunk-times.
-double simulate(const std::vector<int> *lens, int slots) {
-    int per_xcd = std::max(1, slots / 8);
-    double worst = 0;
-    for (int x = 0; x < 8; ++x) {
-        std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
-        for (int i = 0; i < per_xcd; ++i) free_at.push(0.0);
-        double end = 0;
-        for (int len : lens[x]) {
-            double t0 = free_at.top();
-            free_at.pop();
-            double t1 = t0 + len + 1.5;          // 1.5: loading q, writing the result
-            free_at.push(t1);
-            end = std::max(end, t1);
-        }
-        worst = std::max(worst, end);
-    }
-    return worst;
-}
-}  // namespace
-
-// Choice of the pieces: equal pieces with a split factor 1..4 of the average tile, or front-loaded
-// pieces of 1.07x / 1.2x the per-slot share of all chunks; the candidate with the smallest simulated
-// makespan (+ 8 chunk-times for the merge pass when anything is split) wins.
-AttnPlanCounts attn_plan_counts(const AttnTune &tune, const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv,
-                                int last_only) {
-    const int g_target_items = tune.target_items, g_min_chunks = tune.min_chunks, g_force_split = tune.force_split;
-    AttnPlanCounts r = {};
-    std::vector<TraceShape> tr;
-    tr.reserve(B);
-    int64_t total = 0, n_tiles = 0;
-    int nc_longest = 0;
-    for (int b = 0; b < B; ++b) {
-        int S = h_cu[b + 1] - h_cu[b], L = h_plens[b];
-        TracePlan p = trace_plan(L, S, G, 1 << 30, 1, last_only);
-        tr.push_back({Hkv * p.n_qt, p.nc_max});
-        total += (int64_t)Hkv * p.n_qt * p.nc_max;
-        n_tiles += (int64_t)Hkv * p.n_qt;
-        if (p.n_qt > 0) nc_longest = std::max(nc_longest, p.nc_max);
-    }
-    r.n_tiles = n_tiles;
-    r.total_chunks = total;
-    double avg = n_tiles > 0 ? (double)total / (double)n_tiles : 1.0;
-    int64_t slots = g_target_items;
-    int64_t cap_items = 3 * n_tiles + 4 * slots;
-    std::vector<Candidate> cands;
-    auto equal_cpi = [&](int sp) { return sp == 1 ? (1 << 30) : std::max<int>(g_min_chunks, (int)((avg + sp - 1) / sp)); };
-    auto front_cpi = [&](double f) { return std::max<int>(g_min_chunks, (int)std::ceil(f * (double)total / (double)slots)); };
-    if (g_force_split >= 1 && g_force_split <= 4) cands.push_back({equal_cpi(g_force_split), 1});
-    else if (g_force_split == 5) cands.push_back({front_cpi(1.07), 0});
-    else {
-        for (int sp = 1; sp <= 4; ++sp) {
-            if (sp > 1 && avg / sp < g_min_chunks) break;
-            cands.push_back({equal_cpi(sp), 1});
-        }
-        for (double f : {1.07, 1.2})
-            if (front_cpi(f) < nc_longest) cands.push_back({front_cpi(f), 0});
-    }
-    double best = 1e300;
-    Candidate pick = {1 << 30, 1};
-    for (size_t i = 0; i < cands.size(); ++i) {
-        AttnPlanCounts c = {};
-        std::vector<int> lens[8];
-        candidate_counts(tr, cands[i], n_tiles, total, &c, lens);
-        if (c.n_items > cap_items && cands.size() > 1 && cands[i].cpi != (1 << 30)) continue;
-        double est = simulate(lens, (int)slots) + (c.n_part_slots > 0 ? 8.0 : 0.0);
-        if (est < best) { best = est; pick = cands[i]; }
-    }
-    r.chunks_per_item = pick.cpi;
-    r.equalize = pick.equalize;
-    candidate_counts(tr, pick, n_tiles, total, &r, nullptr);
+// max(a, b, c) in one instruction.  The scores come straight from the matrix pipe, and fmaxf() would first put each
+// of them through a canonicalising v_max (three instructions per score pair instead of one).
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
 
+// f(integral_constant<int, 0>{}), ..., f(integral_constant<int, N - 1>{}): a loop whose index is a compile-time
+// constant in every round (no loop is left for the optimizer to unroll or not)
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// ---- device planner: the lists of attn_plan.h, built from the device copies of the lengths ----
 // counts[0] = tiles, counts[1] = items, counts[2 + x] = first item of XCD x (x = 0..8; [10] = items)
 __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restrict__ cu,
-                                                         const int32_t *__restrict__ plens, int B, int T, int max_L,
-                                                         int G, int Hkv, int cpi, int equalize, int last_only,
-                                                         int max_tiles, int max_items, AttnTile *__restrict__ tiles,
-                                                         AttnItem *__restrict__ items, int32_t *__restrict__ counts) {
+                                                         const int32_t *__restrict__ plens,
+                                                         const int32_t *__restrict__ group_start, int n_units, int B,
+                                                         int T, int max_L, int G, int Hkv, int cpi, int equalize,
+                                                         int last_only, int max_tiles, int max_items,
+                                                         AttnTile *__restrict__ tiles, AttnItem *__restrict__ items,
+                                                         int32_t *__restrict__ counts) {
     __shared__ int s_tiles[257], s_rest[257], s_slots[257];
     __shared__ long long s_work[257];
     __shared__ int carry[3];
@@ -272,15 +80,13 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
     for (int pass = 0; pass < 3; ++pass) {
         if (tid == 0) { carry[0] = carry[1] = carry[2] = 0; carry_work = 0; }
         __syncthreads();
-        for (int base = 0; base < B; base += 256) {
-            int b = base + tid;
-            int L = 0, S = 0;
-            TracePlan p = {0, 1, 0, 1};
-            if (b < B) {
-                int c0 = min(max(cu[b], 0), T), c1 = min(max(cu[b + 1], 0), T);
-                S = max(c1 - c0, 0);
-                L = min(max(plens[b], 0), max_L);
-                p = trace_plan(L, S, G, cpi, equalize, last_only);
+        for (int base = 0; base < n_units; base += 256) {
+            int i = base + tid;
+            AttnUnit u = {0, 1, 0, 0, 0};
+            UnitPlan p = {0, 1, 0, 1};
+            if (i < n_units) {
+                u = plan_unit(cu, plens, group_start, n_units, i, B, T, max_L, last_only);
+                p = unit_plan(u, G, cpi, equalize, last_only);
             }
             int my_tiles = Hkv * p.n_qt;
             s_tiles[tid + 1] = my_tiles;
@@ -288,27 +94,27 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
             s_slots[tid + 1] = p.n_split > 1 ? my_tiles * p.n_split : 0;
             s_work[tid + 1] = (long long)my_tiles * p.nc_max;
             __syncthreads();
-            if (tid == 0) {  // serial exclusive scan of the entries of this batch of traces (at most 256)
+            if (tid == 0) {  // serial exclusive scan of the entries of this batch of units (at most 256)
                 s_tiles[0] = carry[0];
                 s_rest[0] = carry[1];
                 s_slots[0] = carry[2];
                 s_work[0] = carry_work;
-                int n = min(256, B - base);
-                for (int i = 1; i <= n; ++i) {
-                    s_tiles[i] += s_tiles[i - 1];
-                    s_rest[i] += s_rest[i - 1];
-                    s_slots[i] += s_slots[i - 1];
-                    s_work[i] += s_work[i - 1];
+                int n = min(256, n_units - base);
+                for (int k = 1; k <= n; ++k) {
+                    s_tiles[k] += s_tiles[k - 1];
+                    s_rest[k] += s_rest[k - 1];
+                    s_slots[k] += s_slots[k - 1];
+                    s_work[k] += s_work[k - 1];
                 }
                 s_tiles[256] = s_tiles[n]; s_rest[256] = s_rest[n]; s_slots[256] = s_slots[n]; s_work[256] = s_work[n];
             }
             __syncthreads();
             int tile_base = s_tiles[tid], rest_base = s_rest[tid], slot_base = s_slots[tid];
-            if (pass == 1 && b < B)
+            if (pass == 1 && i < n_units)
                 plan_xcd_starts(p, Hkv, tile_base, rest_base, s_work[tid], work_total, tile_lo, seg_base);
-            if (pass == 2 && b < B)
-                plan_emit_trace(b, L, S, G, Hkv, p, tile_base, rest_base, slot_base, tile_lo, seg_base, last_only,
-                                max_tiles, max_items, tiles, items);
+            if (pass == 2 && i < n_units)
+                plan_emit_unit(cu, T, u, G, Hkv, p, tile_base, rest_base, slot_base, tile_lo, seg_base, last_only,
+                               max_tiles, max_items, tiles, items);
             __syncthreads();
             if (tid == 0) { carry[0] = s_tiles[256]; carry[1] = s_rest[256]; carry[2] = s_slots[256]; carry_work = s_work[256]; }
             __syncthreads();
@@ -327,11 +133,13 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
     if (tid < 9) counts[2 + tid] = min(seg_base[tid], max_items);
 }
 
-hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int T, int max_L, int G, int Hkv,
-                            int chunks_per_item, int equalize, int last_only, int max_tiles, int max_items,
-                            AttnTile *tiles, AttnItem *items, int32_t *counts, hipStream_t s) {
-    attn_plan_kernel<<<1, 256, 0, s>>>(cu, plens, B, T, max_L, G, Hkv, chunks_per_item, equalize, last_only,
-                                       max_tiles, max_items, tiles, items, counts);
+hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, const int32_t *group_start, int n_units, int B,
+                            int T, int max_L, int G, int Hkv, int chunks_per_item, int equalize, int last_only,
+                            int max_tiles, int max_items, AttnTile *tiles, AttnItem *items, int32_t *counts,
+                            hipStream_t s) {
+    if (!group_start || last_only) { group_start = nullptr; n_units = B; }
+    attn_plan_kernel<<<1, 256, 0, s>>>(cu, plens, group_start, n_units, B, T, max_L, G, Hkv, chunks_per_item, equalize,
+                                       last_only, max_tiles, max_items, tiles, items, counts);
     return hipGetLastError();
 }
 
@@ -355,13 +163,432 @@ __device__ __forceinline__ void store_out4(bf16 *o, size_t row_w, int fmt, const
     if (fmt == 2) *reinterpret_cast<uint2 *>(o + row_w) = pl.u;
 }
 
-// ---- the attention kernel ----
+// What every kernel below derives from its item: the unit, its rows, the tile's key list.
+struct ItemGeom {
+    int b0, c, cu0, n_rows, L, n_pc, k_start, G;
+};
+__device__ __forceinline__ ItemGeom item_geom(const AttnArgs &a, int ib0, int ib_end, int ic, int row0) {
+    ItemGeom g;
+    g.G = a.Hq / a.Hkv;
+    g.b0 = min(max(ib0, 0), a.B - 1);
+    int b1 = min(max(ib_end, g.b0 + 1), a.B);
+    g.c = min(max(ic, 0), a.Hkv - 1);
+    g.cu0 = min(max(a.cu[g.b0], 0), a.T - 1);
+    int cu1 = min(max(a.cu[b1], g.cu0 + 1), a.T);
+    g.n_rows = g.G * (cu1 - g.cu0);
+    g.L = min(max(a.plens[g.b0], 0), a.max_blocks * 16);
+    g.n_pc = (g.L + ATTN_BN - 1) / ATTN_BN;
+    // first suffix key of the tile: the first token of the trace that holds the tile's first row
+    int tok_lo = g.cu0 + min(max(row0, 0), g.n_rows - 1) / g.G;
+    int tr_lo = min(max(a.tok_trace[tok_lo], g.b0), b1 - 1);
+    g.k_start = min(max(a.cu[tr_lo], g.cu0), tok_lo);
+    return g;
+}
+
+// End of an item: the normalised output rows (item covers its tile's whole key list), or the fp32 partial
+// result of a piece for the merge.  acc_o[hb][e]: hd = 32*hb + 8*(e>>2) + 4*half + (e&3), query = the lane's row.
+__device__ __forceinline__ void finish_item(const AttnArgs &a, const AttnItem &item, const f32x16 (&acc_o)[4], float l_run,
+                                            float m_ref, bool wave_active, bool row_valid, int wave, int lq, int half,
+                                            int token, int head, float *__restrict__ part_o, float *__restrict__ part_ml) {
+    float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (item.part_slot < 0) {
+        if (row_valid) {
+            float inv = 1.0f / l_tot;
+            size_t row_w = (size_t)a.Hq * HD;
+            bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + (size_t)token * row_w * (a.out_terms == 2 ? 2 : 1) + head * HD;
+#pragma unroll
+            for (int hb = 0; hb < 4; ++hb)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    float v4[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v4[j] = acc_o[hb][q4 * 4 + j] * inv;
+                    store_out4(o_row + 32 * hb + 8 * q4 + 4 * half, row_w, a.out_terms, v4);
+                }
+        }
+    } else {
+        size_t row_slot = (size_t)item.part_slot * ATTN_BM + wave * 32 + lq;
+        if (wave_active) {
+            float *po = part_o + row_slot * HD;
+#pragma unroll
+            for (int hb = 0; hb < 4; ++hb)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    float4 v = make_float4(acc_o[hb][q4 * 4], acc_o[hb][q4 * 4 + 1], acc_o[hb][q4 * 4 + 2],
+                                           acc_o[hb][q4 * 4 + 3]);
+                    *reinterpret_cast<float4 *>(po + 32 * hb + 8 * q4 + 4 * half) = v;
+                }
+        }
+        if (half == 0) {
+            part_ml[row_slot * 2] = wave_active ? m_ref : -INFINITY;
+            part_ml[row_slot * 2 + 1] = l_tot;
+        }
+    }
+}
+
+// =================================================================================================
+// Software-pipelined main loop.
+//
+// LDS: two stages of K and two of V, each [64 keys][128 hd] bf16 in 256-byte rows without padding.  A
+// wavefront fills 16 keys of a chunk with four direct loads (1 KiB = 4 rows each; in a context chunk those 16
+// keys are one 16-token page).  Bank conflicts are avoided by permuting the 16-byte vectors inside a row:
+// K keeps vector v of key k at slot v ^ (k & 15) (the score MFMAs read 16 consecutive keys at one v),
+// V keeps it at slot v ^ (4 * (k & 3)) (32 lanes of a transposing read touch 4 consecutive keys x 64 contiguous
+// bytes: each key in its own quarter of the 256-byte bank space).
+// The lane that fills a slot fetches the matching global vector.
+//
+// Transposing reads (ds_read_b64_tr_b16): in a group of 16 lanes, lane i supplies the address of 4 consecutive
+// 16-bit elements and receives element i % 4 of what lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4 addressed.  With
+// lane 4 j + q pointing at V[key j][hd 4 q .. 4 q + 3] of a 4-key x 16-hd block, lane i receives
+// V[key 0 .. 3][hd i]: four consecutive k-values of the A operand of O^T += V^T . P^T for its hd row.
+//
+// Pipeline, iteration i (chunk i of the item): wait for K(i+1) and V(i), barrier, start the direct loads of K(i+2)
+// and V(i+1) into the stages that chunk i's score product and chunk i-1's value product have released; then
+// S(i+1) = K(i+1) . Q^T on the matrix pipe while the vector ALU turns S(i) into probabilities, then
+// O^T += V(i)^T . P(i)^T.
+constexpr int PIPE_TILE_BYTES = ATTN_BN * HD * 2;          // one K or V stage: 16 KiB
+constexpr int PIPE_SMEM_BYTES = 4 * PIPE_TILE_BYTES;       // K0 K1 V0 V1
+
+__global__ __launch_bounds__(ATTN_THREADS, 2) void attn_pipe_kernel(AttnArgs a, const AttnItem *__restrict__ items,
+                                                                    const int32_t *__restrict__ counts, int n_items_host,
+                                                                    float *__restrict__ part_o,
+                                                                    float *__restrict__ part_ml) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+    // workgroup id % 8 is the XCD; each XCD walks its own range of the item list in order
+    int n_items = min(counts[1], n_items_host);
+    int xcd = blockIdx.x & 7;
+    int it_idx = counts[2 + xcd] + (blockIdx.x >> 3);
+    if (it_idx >= min(counts[3 + xcd], n_items)) return;
+    AttnItem item = items[it_idx];
+    // the item is the same for every lane: keep it (and everything derived from it) in scalar registers, so that
+    // loads at addresses derived from it - block-table entries, lengths - are scalar loads
+    item.b0 = __builtin_amdgcn_readfirstlane(item.b0);
+    item.c = __builtin_amdgcn_readfirstlane(item.c);
+    item.row0 = __builtin_amdgcn_readfirstlane(item.row0);
+    item.chunk_begin = __builtin_amdgcn_readfirstlane(item.chunk_begin);
+    item.chunk_end = __builtin_amdgcn_readfirstlane(item.chunk_end);
+    item.part_slot = __builtin_amdgcn_readfirstlane(item.part_slot);
+    item.b_end = __builtin_amdgcn_readfirstlane(item.b_end);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (item.chunk_begin >= item.chunk_end) {
+        // a piece that received no chunks: mark its rows as "nothing seen" for the merge
+        if (item.part_slot >= 0 && tid < ATTN_BM) {
+            size_t row_slot = (size_t)item.part_slot * ATTN_BM + tid;
+            part_ml[row_slot * 2] = -INFINITY;
+            part_ml[row_slot * 2 + 1] = 0.f;
+        }
+        return;
+    }
+    const int half = lane >> 5, lq = lane & 31;
+    const ItemGeom ge = item_geom(a, item.b0, item.b_end, item.c, item.row0);
+    const int G = ge.G, c = ge.c, L = ge.L, n_pc = ge.n_pc;
+
+    // Four wavefronts of 32 query rows each.  A wave whose rows all lie past the end of the unit still
+    // loads and synchronises with the others but skips the matrix work.
+    const int wave_row0 = item.row0 + wave * 32;
+    const bool wave_active = wave_row0 < ge.n_rows;             // wave-uniform
+    const int r = wave_row0 + lq;
+    const bool row_valid = r < ge.n_rows;
+    const int rc = min(r, ge.n_rows - 1);
+    const int tt = rc / G, g = rc - tt * G;
+    const int token = ge.cu0 + tt;                              // packed suffix token of this lane's query
+    // suffix keys visible to it: the packed tokens klo .. token (its own trace up to itself)
+    const int klo = min(max(a.cu[min(max(a.tok_trace[token], ge.b0), a.B - 1)], ge.cu0), token);
+
+    const bf16 *q_row = reinterpret_cast<const bf16 *>(a.q) + ((size_t)token * a.Hq + c * G + g) * HD;
+    bf16x8 qf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(q_row + ks * 16 + half * 8);
+
+    // ---- direct loads: wave w fills keys 16 w .. 16 w + 15 of a chunk, instruction j keys 4 j .. 4 j + 3 of those
+    const bf16 *kp = reinterpret_cast<const bf16 *>(a.k_pages), *vp = reinterpret_cast<const bf16 *>(a.v_pages);
+    const bf16 *ks_ = reinterpret_cast<const bf16 *>(a.ksuf), *vs_ = reinterpret_cast<const bf16 *>(a.vsuf);
+    const int32_t *bt = a.block_table + (size_t)ge.b0 * a.max_blocks;
+    const int last_page = max((L + 15) / 16 - 1, 0);
+    const int lrow = lane >> 4, lpos = lane & 15;
+    // element offsets inside a key row of the vector this lane fetches (the slot permutation above)
+    int k_vec[4], v_vec[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int key = 4 * j + lrow;                                  // key & 15 (the wave's 16 keys start at a multiple of 16)
+        k_vec[j] = (lpos ^ key) * 8;
+        v_vec[j] = (lpos ^ (4 * (key & 3))) * 8;
+    }
+    // byte offsets of this lane's four vectors inside a page's rows of this kv head (context chunks)
+    unsigned k_poff[4], v_poff[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        k_poff[j] = ((4 * j + lrow) * HD + k_vec[j]) * 2;
+        v_poff[j] = ((4 * j + lrow) * HD + v_vec[j]) * 2;
+    }
+    // Block-table entries: this wave needs page `wave` of every context chunk.  Lane l holds the entry of chunk
+    // ids_first + l; the vector is refilled once every 64 chunks (a load whose wait coincides with the wait at the top
+    // of an iteration), and an entry is picked with a lane read.
+    int ids_vec = 0, ids_first = -(1 << 30);
+    auto page_id = [&](int u) -> int {                           // wave-uniform
+        if (u - ids_first >= 64 || u < ids_first) {              // uniform branch
+            ids_first = u;
+            ids_vec = bt[min(4 * (u + lane) + wave, last_page)];
+        }
+        return min(max(__builtin_amdgcn_readlane(ids_vec, u - ids_first), 0), a.n_blocks - 1);
+    };
+    // The direct loads are issued from inline assembly: the compiler then does not know that LDS is being written
+    // behind its back, and does not put a wait for all of them in front of the transposing LDS reads (which it cannot
+    // tell apart from the stage being filled).  Their completion is waited for explicitly (vmcnt) at the top of every
+    // iteration, followed by the workgroup barrier.
+    const unsigned lds_base = (unsigned)(size_t)(CS_LDS_AS unsigned char *)smem;
+    auto dma16 = [&](const bf16 *src, unsigned lds_dst) {      // 64 lanes x 16 bytes -> lds_dst + 16 * lane
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_dst), "v"(src) : "memory");
+    };
+    // the same from a wave-uniform base address plus a 32-bit byte offset per lane (no address arithmetic per lane)
+    auto dma16_base = [&](const bf16 *base, unsigned off, unsigned lds_dst) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_dst), "v"(off), "s"(base) : "memory");
+    };
+    auto issue = [&](const bf16 *pages, const bf16 *suf, const int (&vec)[4], const unsigned (&poff)[4], int u, int id,
+                     int stage_idx) __attribute__((always_inline)) {
+        unsigned dst = lds_base + stage_idx * PIPE_TILE_BYTES + wave * 4096;
+        if (u < n_pc) {
+            const bf16 *base = pages + ((size_t)id * a.Hkv + c) * 16 * HD;      // scalar
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dma16_base(base, poff[j], dst + j * 1024);
+        } else {
+            int k0 = ge.k_start + ATTN_BN * (u - n_pc) + 16 * wave + lrow;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int kt = min(k0 + 4 * j, a.T - 1);               // tokens past the end are masked for every query
+                dma16(suf + ((size_t)kt * a.Hkv + c) * HD + vec[j], dst + j * 1024);
+            }
+        }
+    };
+    // stage indices: K stages 0, 1; V stages 2, 3
+    auto k_stage = [&](int i) -> unsigned char * { return smem + (i & 1) * PIPE_TILE_BYTES; };
+    auto v_stage = [&](int i) -> unsigned char * { return smem + (2 + (i & 1)) * PIPE_TILE_BYTES; };
+
+    // ---- fragment addresses
+    // K: MFMA row lq of block kb = key 32 kb + lq; k-step ks reads vector 2 ks + half of that key
+    int k_off[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) k_off[ks] = lq * 256 + (((2 * ks + half) ^ (lq & 15)) << 4);
+    // V^T: group gi = lane / 16 serves hd rows 16 (gi & 1) .. + 15 of a 32-row block for k-group gi / 2 (= half);
+    // lane i of the group points at key 4 half + i / 4 (+ 8 for the second read), hd 4 (i % 4) .. + 3
+    const int li = lane & 15, gi = lane >> 4;
+    const int v_key = 4 * half + (li >> 2);                      // (key & 7) of the rows this lane addresses
+    int v_off[4];
+#pragma unroll
+    for (int hb = 0; hb < 4; ++hb) {
+        int vec = 4 * hb + 2 * (gi & 1) + ((li & 3) >> 1);       // 16-byte vector of hd 32 hb + 16 (gi & 1) + 4 (li & 3)
+        v_off[hb] = v_key * 256 + ((vec ^ (4 * (v_key & 3))) << 4) + ((li & 1) << 3);
+    }
+
+    f32x16 acc_o[4];
+#pragma unroll
+    for (int hb = 0; hb < 4; ++hb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_o[hb][e] = 0.f;
+    float m_run = -INFINITY, m_ref = -INFINITY, l_run = 0.f;   // true max, exponent reference, sum (vs m_ref)
+    const float sc = a.scale * 1.44269504088896340736f;        // scores in log2 units
+
+    const int u0 = item.chunk_begin, n = item.chunk_end - item.chunk_begin;
+
+    // S^T block kb of a chunk: acc[kb][e] = score of key 32 kb + 8 (e >> 2) + 4 half + (e & 3), query lq.
+    // MFMA q of the 16 of a chunk: k-step q / 2, key block q % 2.
+    auto score_mfma = [&](f32x16 (&acc)[2], const unsigned char *kst, int q) {
+        int ks = q >> 1, kb = q & 1;
+        bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kst + kb * 32 * 256 + k_off[ks]);
+        acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc[kb], 0, 0, 0);
+    };
+    auto zero2 = [&](f32x16 (&acc)[2]) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[kb][e] = 0.f;
+    };
+
+    // ---- prologue: K(0), V(0), K(1) in flight; S(0) computed without anything to overlap with
+    int id_v = 0, id_k = 0, id_n = 0;                            // page ids: chunk i+1 (V), i+2 (K), i+3 (prefetched)
+    {
+        int id0 = u0 < n_pc ? page_id(u0) : 0;
+        issue(kp, ks_, k_vec, k_poff, u0, id0, 0);
+        issue(vp, vs_, v_vec, v_poff, u0, id0, 2);
+        id_v = (n > 1 && u0 + 1 < n_pc) ? page_id(u0 + 1) : 0;
+        if (n > 1) issue(kp, ks_, k_vec, k_poff, u0 + 1, id_v, 1);
+        id_k = (n > 2 && u0 + 2 < n_pc) ? page_id(u0 + 2) : 0;
+        id_n = (n > 3 && u0 + 3 < n_pc) ? page_id(u0 + 3) : 0;
+    }
+    f32x16 s_a[2], s_b[2];       // raw scores of two consecutive chunks; the roles alternate from iteration to iteration
+    zero2(s_a);
+    if (n > 1) CS_WAIT_VMCNT(8); else CS_WAIT_VMCNT(4);          // K(0) has landed (this wave's part)
+    __syncthreads();
+    if (wave_active) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) score_mfma(s_a, k_stage(0), q);
+    }
+
+    // One iteration.  Compile-time arguments: the parity of i (it fixes the LDS stages: K(i+1) is read from K stage
+    // 1 - parity, V(i) from V stage parity) and whether chunk i + 1 exists (its scores are then computed under chunk
+    // i's softmax, into s_nxt).
+    auto iteration = [&](int i, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2], auto parity_tag, auto more_tag) __attribute__((always_inline)) {
+        constexpr int par = decltype(parity_tag)::value;
+        constexpr bool more = decltype(more_tag)::value;
+        const int u = u0 + i;
+        // page id of chunk i + 4 (a scalar load, asked for before the wait so that it arrives under it)
+        const int id_new = (i + 4 < n && u + 4 < n_pc) ? page_id(u + 4) : 0;
+        CS_WAIT_VMCNT(0);
+        __syncthreads();      // K(i+1) and V(i) are in LDS; nobody reads K(i) or V(i-1) any more
+        if (i + 2 < n) issue(kp, ks_, k_vec, k_poff, u + 2, id_k, par);
+        if constexpr (more) issue(vp, vs_, v_vec, v_poff, u + 1, id_v, 3 - par);
+        id_v = id_k;
+        id_k = id_n;
+        id_n = id_new;
+        const unsigned char *kst = smem + (1 - par) * PIPE_TILE_BYTES, *vst = smem + (2 + par) * PIPE_TILE_BYTES;
+
+        if (wave_active) {
+            // -- masks of chunk i: the tail of the context, or the visibility window of the suffix tokens
+            if (u >= n_pc) {
+                int kt0 = ge.k_start + ATTN_BN * (u - n_pc) + 4 * half;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        int kt = kt0 + 32 * kb + 8 * (e >> 2) + (e & 3);
+                        if (kt < klo || kt > token) s_cur[kb][e] = -INFINITY;
+                    }
+            } else if (u * ATTN_BN + ATTN_BN > L) {
+                int j0 = u * ATTN_BN + 4 * half;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (j0 + 32 * kb + 8 * (e >> 2) + (e & 3) >= L) s_cur[kb][e] = -INFINITY;
+            }
+            // The chunk is 32 steps of one MFMA each: steps 0..15 the score MFMAs of chunk i+1 (k-step s / 2, key
+            // block s % 2), steps 16..31 the value MFMAs of chunk i (key block, k-step, hd block).  The operand of step
+            // s + 2 is requested from LDS before the MFMA of step s is issued, and a slice of chunk i's softmax
+            // follows each MFMA: the row maximum in steps 0..3, the probabilities of key block 0 in steps 4..15 (in
+            // time for step 16), those of key block 1 in steps 16..23 (in time for step 24).
+            bf16x8 fr[3];
+            auto fetch = [&](auto st_tag) __attribute__((always_inline)) {     // operand of step st into fr[st % 3]
+                constexpr int st = decltype(st_tag)::value;
+                if constexpr (st < 16) {
+                    if constexpr (more) fr[st % 3] = *reinterpret_cast<const bf16x8 *>(kst + (st & 1) * 32 * 256 + k_off[st >> 1]);
+                } else if constexpr (st < 32) {
+                    constexpr int idx = st - 16, kb = idx >> 3, s2 = (idx >> 2) & 1, hb = idx & 3;
+                    // two transposing reads: keys 32 kb + 16 s2 + 4 half + 0..3 and + 8
+                    const unsigned char *p0 = vst + (32 * kb + 16 * s2) * 256 + v_off[hb];
+                    i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CS_LDS_AS i16x4 *)p0);
+                    i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CS_LDS_AS i16x4 *)(p0 + 8 * 256));
+                    i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    fr[st % 3] = __builtin_bit_cast(bf16x8, both);
+                }
+            };
+            float mloc = -INFINITY, neg_off = 0.f, psum = 0.f;
+            bf16x8 pf[2][2];
+            fetch(std::integral_constant<int, 0>{});
+            fetch(std::integral_constant<int, 1>{});
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<32>([&](auto st_tag) __attribute__((always_inline)) {
+                constexpr int st = decltype(st_tag)::value;
+                fetch(std::integral_constant<int, st + 2>{});
+                if constexpr (st < 16) {
+                    if constexpr (more) {
+                        if constexpr (st < 2) {
+                            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                            s_nxt[st & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % 3], qf[st >> 1], zero, 0, 0, 0);
+                        } else {
+                            s_nxt[st & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % 3], qf[st >> 1], s_nxt[st & 1], 0, 0, 0);
+                        }
+                    }
+                } else {
+                    constexpr int idx = st - 16;
+                    acc_o[idx & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % 3], pf[idx >> 3][(idx >> 2) & 1], acc_o[idx & 3], 0, 0, 0);
+                }
+                if constexpr (st < 4) {
+#pragma unroll
+                    for (int e = 4 * st; e < 4 * st + 4; ++e) mloc = max3(mloc, s_cur[0][e], s_cur[1][e]);
+                    if constexpr (st == 3) {
+                        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+                        float m_new = fmaxf(m_run, mloc * sc);     // true running max, log2 units
+                        m_run = m_new;
+                        // Lazy rescale: the exponent reference m_ref only follows the running max when some query of
+                        // the wave has moved more than 8 (a factor 256) above it; until then probabilities may exceed
+                        // 1, which bf16 / fp32 hold without loss, and the accumulators need no per-chunk rescale.
+                        if (__builtin_amdgcn_ballot_w64(m_new > m_ref + 8.0f) != 0) {
+                            float off_old = (m_ref == -INFINITY) ? 0.f : m_ref;
+                            float off_new = (m_new == -INFINITY) ? 0.f : m_new;
+                            float alpha = __builtin_amdgcn_exp2f(off_old - off_new);
+                            m_ref = m_new;
+                            l_run *= alpha;
+#pragma unroll
+                            for (int hb = 0; hb < 4; ++hb)
+#pragma unroll
+                                for (int e = 0; e < 16; ++e) acc_o[hb][e] *= alpha;
+                        }
+                        neg_off = (m_ref == -INFINITY) ? 0.f : -m_ref;
+                    }
+                } else if constexpr (st < 16) {
+                    constexpr int e0 = ((st - 4) * 16) / 12, e1 = ((st - 3) * 16) / 12;
+#pragma unroll
+                    for (int e = e0; e < e1; ++e) {
+                        float p = __builtin_amdgcn_exp2f(fmaf(s_cur[0][e], sc, neg_off));
+                        psum += p;
+                        pf[0][e >> 3][e & 7] = (__bf16)p;
+                    }
+                } else if constexpr (st < 24) {
+#pragma unroll
+                    for (int e = 2 * (st - 16); e < 2 * (st - 16) + 2; ++e) {
+                        float p = __builtin_amdgcn_exp2f(fmaf(s_cur[1][e], sc, neg_off));
+                        psum += p;
+                        pf[1][e >> 3][e & 7] = (__bf16)p;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            l_run += psum;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    {
+        using P0 = std::integral_constant<int, 0>;
+        using P1 = std::integral_constant<int, 1>;
+        int i = 0;
+        for (; i + 2 < n; i += 2) {
+            iteration(i, s_a, s_b, P0{}, std::true_type{});
+            iteration(i + 1, s_b, s_a, P1{}, std::true_type{});
+        }
+        if (n - i == 2) {
+            iteration(i, s_a, s_b, P0{}, std::true_type{});
+            iteration(i + 1, s_b, s_a, P1{}, std::false_type{});
+        } else {
+            iteration(i, s_a, s_b, P0{}, std::false_type{});
+        }
+    }
+
+    finish_item(a, item, acc_o, l_run, m_ref, wave_active, row_valid, wave, lq, half, token, c * G + g, part_o, part_ml);
+}
+
+// =================================================================================================
+// Register-staged main loop.  Per chunk a workgroup stages K as [key][hd] and V transposed as [hd][key] in
+// LDS through registers (the next chunk's loads are in flight while the current one is multiplied).  The rows
+// of each 32-key block are fed to the score MFMA in a permuted order chosen so that the probabilities a
+// lane ends up holding are 8 consecutive keys per k-step, and the matching A operand of the value product is
+// a single 16-byte read of the transposed V tile.
+//
 // PRECISE: q, the suffix keys / values and the probabilities are each carried as two bf16 terms
 // (hi + lo); products hi*hi, hi*lo and lo*hi are accumulated (lo*lo is below fp32 resolution of the
-// sum).  Cached prefix keys / values are exact bf16 values and need no second term.  Used for the
+// sum).  Cached context keys / values are exact bf16 values and need no second term.  Used for the
 // first layer(s), where score noise from rounding q and k is amplified by every later layer.
+constexpr int K_STRIDE = 136;             // elements per K row in LDS (128 + 8 pad = 272 bytes)
+constexpr int VT_STRIDE = 72;             // elements per V^T row in LDS (64 + 8 pad = 144 bytes)
+constexpr int K_TILE = ATTN_BN * K_STRIDE;
+constexpr int VT_TILE = HD * VT_STRIDE;
+constexpr int ATTN_STAGE = K_TILE + VT_TILE;   // elements per stage
+constexpr int ATTN_SMEM_BYTES = 2 * ATTN_STAGE * 2;
+
 template <bool PRECISE>
-__global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kernel(AttnArgs a, const AttnItem *__restrict__ items,
+__global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_staged_kernel(AttnArgs a, const AttnItem *__restrict__ items,
                                                                   const int32_t *__restrict__ counts, int n_items_host,
                                                                   float *__restrict__ part_o,
                                                                   float *__restrict__ part_ml) {
@@ -387,12 +614,8 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
         return;
     }
     int half = lane >> 5, lq = lane & 31;
-    int G = a.Hq / a.Hkv;
-    int b = min(max(item.b, 0), a.B - 1), c = min(max(item.c, 0), a.Hkv - 1);
-    int cu_b = min(max(a.cu[b], 0), a.T - 1);
-    int S = min(max(a.cu[b + 1] - cu_b, 1), a.T - cu_b);
-    int L = min(max(a.plens[b], 0), a.max_blocks * 16);
-    int n_rows = G * S;
+    const ItemGeom ge = item_geom(a, item.b0, item.b_end, item.c, item.row0);
+    const int G = ge.G, c = ge.c, L = ge.L, n_pc = ge.n_pc, n_rows = ge.n_rows;
 
     // Four wavefronts of 32 query rows each.  A wave whose rows all lie past the end of the trace
     // still loads and synchronises with the others but skips the matrix work.
@@ -401,17 +624,18 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
     int r = wave_row0 + lq;
     bool row_valid = r < n_rows;
     int rc = min(r, n_rows - 1);
-    int t = rc / G, g = rc - t * G;
-    int limit = L + t;                                          // last visible key of this lane's query
-    int wave_first_limit = L + min(wave_row0, n_rows - 1) / G;
+    int tt = rc / G, g = rc - tt * G;
+    const int token = ge.cu0 + tt;                              // packed suffix token of this lane's query
+    // suffix keys visible to it: the packed tokens klo .. token (its own trace up to itself)
+    const int klo = min(max(a.cu[min(max(a.tok_trace[token], ge.b0), a.B - 1)], ge.cu0), token);
 
-    const bf16 *q_row = reinterpret_cast<const bf16 *>(a.q) + ((size_t)(cu_b + t) * a.Hq + c * G + g) * HD;
+    const bf16 *q_row = reinterpret_cast<const bf16 *>(a.q) + ((size_t)token * a.Hq + c * G + g) * HD;
     bf16x8 qf[8];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(q_row + ks * 16 + half * 8);
     bf16x8 qf_lo[PRECISE ? 8 : 1];
     if constexpr (PRECISE) {
-        const bf16 *ql_row = reinterpret_cast<const bf16 *>(a.q_lo) + ((size_t)(cu_b + t) * a.Hq + c * G + g) * HD;
+        const bf16 *ql_row = reinterpret_cast<const bf16 *>(a.q_lo) + ((size_t)token * a.Hq + c * G + g) * HD;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf_lo[ks] = *reinterpret_cast<const bf16x8 *>(ql_row + ks * 16 + half * 8);
     }
@@ -427,14 +651,14 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
     for (int i = 0; i < 4; ++i) k_dst[i] = ((tid >> 4) + 16 * i) * K_STRIDE + (tid & 15) * 8;
     int v_kq = lane & 15, v_g = wave * 4 + (lane >> 4);
     int v_dst = K_TILE + (8 * v_g) * VT_STRIDE + 4 * v_kq;
-    const int32_t *bt = a.block_table + (size_t)b * a.max_blocks;        // wave-uniform
+    const int32_t *bt = a.block_table + (size_t)ge.b0 * a.max_blocks;     // wave-uniform
     const size_t page_elems = (size_t)a.Hkv * 16 * HD;
     const int k_in_page = (c * 16 + (tid >> 4)) * HD + (tid & 15) * 8;
     const int v_in_page = (c * 16 + 4 * (v_kq & 3)) * HD + v_g * 8;
     const int v_page_sel = v_kq >> 2;
-    const int max_page = a.max_blocks - 1;
+    const int max_page = max((L + 15) / 16 - 1, 0);
 
-    // Physical block ids of the 4 pages of a chunk, fetched two chunks ahead: lanes 0..3 each load one
+    // Physical block ids of the 4 pages of a context chunk, fetched two chunks ahead: lanes 0..3 each load one
     // table entry into ids_v, the ids are broadcast with readlane right before the chunk's loads.
     int ids_v = 0;
     int ids[4];
@@ -447,30 +671,24 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
         for (int i = 0; i < 4; ++i)
             ids[i] = min(max(__builtin_amdgcn_readlane(ids_v, i), 0), a.n_blocks - 1);
     };
-    // Row of key j for chunks that touch the suffix or the end of the trace: page row for j < L, else
-    // suffix row (clamped to the last one: such keys are masked for every query).
-    auto row_general = [&](const bf16 *pages, const bf16 *suf, int j) -> const bf16 * {
-        int jp = min(j, max(L - 1, 0));
-        int id = min(max(bt[min(jp >> 4, max_page)], 0), a.n_blocks - 1);
-        const bf16 *pp = pages + ((size_t)id * a.Hkv + c) * 16 * HD + (jp & 15) * HD;
-        int ts = min(max(j - L, 0), S - 1);
-        const bf16 *sp = suf + ((size_t)(cu_b + ts) * a.Hkv + c) * HD;
-        return j < L ? pp : sp;
+    // Row of key k (0..63) of chunk u when the chunk is not a whole context chunk: the context's last, partly
+    // filled chunk (rows past L - 1 are clamped to it: such keys are masked for every query), or a chunk of
+    // suffix tokens (clamped to the last token of the batch, likewise masked).
+    auto row_general = [&](const bf16 *pages, const bf16 *suf, int u, int k) -> const bf16 * {
+        if (u < n_pc) {
+            int jp = min(u * ATTN_BN + k, max(L - 1, 0));
+            int id = min(max(bt[min(jp >> 4, max_page)], 0), a.n_blocks - 1);
+            return pages + ((size_t)id * a.Hkv + c) * 16 * HD + (jp & 15) * HD;
+        }
+        int kt = min(ge.k_start + ATTN_BN * (u - n_pc) + k, a.T - 1);
+        return suf + ((size_t)kt * a.Hkv + c) * HD;
     };
 
     u32x4 k_reg[4], v_reg[4];
     u32x4 kl_reg[PRECISE ? 4 : 1], vl_reg[PRECISE ? 4 : 1];
     const bf16 *ksl_ = reinterpret_cast<const bf16 *>(a.ksuf_lo), *vsl_ = reinterpret_cast<const bf16 *>(a.vsuf_lo);
-    // lo term of key / value row j: zero for cached rows, the lo plane of the suffix otherwise
-    auto load_lo = [&](const bf16 *suf_lo, int j, int vec_off) -> u32x4 {
-        u32x4 z = {0u, 0u, 0u, 0u};
-        if (j < L) return z;
-        int ts = min(j - L, S - 1);
-        return *reinterpret_cast<const u32x4 *>(suf_lo + ((size_t)(cu_b + ts) * a.Hkv + c) * HD + vec_off);
-    };
-    auto load_chunk = [&](int ch) {
-        int j0 = ch * ATTN_BN;
-        if (j0 + ATTN_BN <= L) {          // uniform: the whole chunk lies in the cached prefix
+    auto load_chunk = [&](int u) {
+        if (u < n_pc && u * ATTN_BN + ATTN_BN <= L) {          // uniform: a whole chunk of the cached context
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 k_reg[i] = *reinterpret_cast<const u32x4 *>(kp + (size_t)ids[i] * page_elems + k_in_page);
@@ -482,8 +700,8 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
             const bf16 *kr[4], *vr[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                kr[i] = row_general(kp, ks_, j0 + (tid >> 4) + 16 * i) + (tid & 15) * 8;
-                vr[i] = row_general(vp, vs_, j0 + 4 * v_kq + i) + v_g * 8;
+                kr[i] = row_general(kp, ks_, u, (tid >> 4) + 16 * i) + (tid & 15) * 8;
+                vr[i] = row_general(vp, vs_, u, 4 * v_kq + i) + v_g * 8;
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -491,10 +709,12 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
                 v_reg[i] = *reinterpret_cast<const u32x4 *>(vr[i]);
             }
             if constexpr (PRECISE) {
+                if (u >= n_pc) {                               // second terms exist for suffix tokens only
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    kl_reg[i] = load_lo(ksl_, j0 + (tid >> 4) + 16 * i, (tid & 15) * 8);
-                    vl_reg[i] = load_lo(vsl_, j0 + 4 * v_kq + i, v_g * 8);
+                    for (int i = 0; i < 4; ++i) {
+                        kl_reg[i] = *reinterpret_cast<const u32x4 *>(row_general(ksl_, ksl_, u, (tid >> 4) + 16 * i) + (tid & 15) * 8);
+                        vl_reg[i] = *reinterpret_cast<const u32x4 *>(row_general(vsl_, vsl_, u, 4 * v_kq + i) + v_g * 8);
+                    }
                 }
             }
         }
@@ -515,12 +735,12 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
             *reinterpret_cast<uint2 *>(base + v_dst + (2 * d + 1) * VT_STRIDE) = hi;
         }
     };
-    // ch: the chunk held in the registers (its lo tiles exist only if it touches the suffix)
-    auto store_chunk = [&](int stage, int ch) {
+    // u: the chunk held in the registers (its lo tiles exist only for chunks of suffix tokens)
+    auto store_chunk = [&](int stage, int u) {
         __bf16 *base = smem + stage * STAGE;
         store_tiles(base, k_reg, v_reg);
         if constexpr (PRECISE) {
-            if (ch * ATTN_BN + ATTN_BN > L) store_tiles(base + ATTN_STAGE, kl_reg, vl_reg);
+            if (u >= n_pc) store_tiles(base + ATTN_STAGE, kl_reg, vl_reg);
         }
     };
 
@@ -532,7 +752,7 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
     float m_run = -INFINITY, m_ref = -INFINITY, l_run = 0.f;   // true max, exponent reference, sum (vs m_ref)
     const float sc = a.scale * 1.44269504088896340736f;   // scores in log2 units
 
-    // K operand row (key) for MFMA row lq, see the header comment: pi(m)
+    // K operand row (key) for MFMA row lq, see the comment above the kernel: pi(m)
     int pi_m = 16 * (lq >> 4) + 8 * ((lq >> 2) & 1) + 4 * ((lq >> 3) & 1) + (lq & 3);
     int k_frag = pi_m * K_STRIDE + half * 8;
     int v_frag = K_TILE + lq * VT_STRIDE + half * 8;
@@ -555,7 +775,7 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
         // keep the consumers of these loads (the LDS stores below) behind the MFMA work of this chunk
         __builtin_amdgcn_sched_barrier(0);
         const __bf16 *base = smem + stage * STAGE;
-        const bool has_lo = PRECISE && (ch * ATTN_BN + ATTN_BN > L);   // uniform
+        const bool has_lo = PRECISE && ch >= n_pc;   // uniform
 
         if (wave_active) {
             f32x16 acc_s[2];
@@ -581,14 +801,23 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
                         acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kb], 0, 0, 0);
                     }
             }
-            // register e of block kb holds key  ch*64 + 32*kb + 16*(e>>3) + 8*half + (e&7)
-            if (ch * ATTN_BN + ATTN_BN - 1 > wave_first_limit) {      // wave-uniform: causal mask needed
-                int key0 = ch * ATTN_BN + 8 * half;
+            // register e of block kb holds key 32*kb + 16*(e>>3) + 8*half + (e&7) of the chunk
+            if (ch >= n_pc) {                 // suffix tokens: visible from the start of the query's trace up to the query
+                int kt0 = ge.k_start + ATTN_BN * (ch - n_pc) + 8 * half;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        int kt = kt0 + 32 * kb + 16 * (e >> 3) + (e & 7);
+                        if (kt < klo || kt > token) acc_s[kb][e] = -INFINITY;
+                    }
+            } else if (ch * ATTN_BN + ATTN_BN > L) {      // the context's last, partly filled chunk
+                int j0 = ch * ATTN_BN + 8 * half;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
-                        if (key0 + 32 * kb + 16 * (e >> 3) + (e & 7) > limit) acc_s[kb][e] = -INFINITY;
+                        if (j0 + 32 * kb + 16 * (e >> 3) + (e & 7) >= L) acc_s[kb][e] = -INFINITY;
             }
             float mloc = -INFINITY;
 #pragma unroll
@@ -655,45 +884,10 @@ __global__ __launch_bounds__(ATTN_THREADS, PRECISE ? 1 : 2) void attn_bf16_kerne
         __syncthreads();
     }
 
-    float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    // acc_o[hb][e]: hd = 32*hb + 8*(e>>2) + 4*half + (e&3), query = lq
-    if (item.part_slot < 0) {
-        if (row_valid) {
-            float inv = 1.0f / l_tot;
-            size_t row_w = (size_t)a.Hq * HD;
-            bf16 *o_row = reinterpret_cast<bf16 *>(a.out) + (size_t)(cu_b + t) * row_w * (a.out_terms == 2 ? 2 : 1) +
-                          (c * G + g) * HD;
-#pragma unroll
-            for (int hb = 0; hb < 4; ++hb)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    float v4[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) v4[j] = acc_o[hb][q4 * 4 + j] * inv;
-                    store_out4(o_row + 32 * hb + 8 * q4 + 4 * half, row_w, a.out_terms, v4);
-                }
-        }
-    } else {
-        size_t row_slot = (size_t)item.part_slot * ATTN_BM + wave * 32 + lq;
-        if (wave_active) {
-            float *po = part_o + row_slot * HD;
-#pragma unroll
-            for (int hb = 0; hb < 4; ++hb)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    float4 v = make_float4(acc_o[hb][q4 * 4], acc_o[hb][q4 * 4 + 1], acc_o[hb][q4 * 4 + 2],
-                                           acc_o[hb][q4 * 4 + 3]);
-                    *reinterpret_cast<float4 *>(po + 32 * hb + 8 * q4 + 4 * half) = v;
-                }
-        }
-        if (half == 0) {
-            part_ml[row_slot * 2] = wave_active ? m_ref : -INFINITY;
-            part_ml[row_slot * 2 + 1] = l_tot;
-        }
-    }
+    finish_item(a, item, acc_o, l_run, m_ref, wave_active, row_valid, wave, lq, half, token, c * G + g, part_o, part_ml);
 }
 
-// Merge the splits of each tile in split order (fixed order: results are run-to-run identical).
+// Merge the pieces of each tile in piece order (fixed order: results are run-to-run identical).
 __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnTile *__restrict__ tiles,
                                                           const int32_t *__restrict__ counts, int n_tiles_host,
                                                           const float *__restrict__ part_o,
@@ -707,10 +901,9 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnT
     AttnTile tile = tiles[tile_idx];
     if (tile.n_splits <= 1 || tile.part_base < 0) return;
     int G = a.Hq / a.Hkv;
-    int b = min(max(tile.b, 0), a.B - 1), c = min(max(tile.c, 0), a.Hkv - 1);
-    int cu_b = min(max(a.cu[b], 0), a.T - 1);
-    int S = min(max(a.cu[b + 1] - cu_b, 1), a.T - cu_b);
-    int n_rows = G * S;
+    int b0 = min(max(tile.b0, 0), a.B - 1), b1 = min(max(tile.b_end, b0 + 1), a.B), c = min(max(tile.c, 0), a.Hkv - 1);
+    int cu_b = min(max(a.cu[b0], 0), a.T - 1);
+    int n_rows = G * (min(max(a.cu[b1], cu_b + 1), a.T) - cu_b);
     {
         int row = (blockIdx.x % WGS_PER_TILE) * ROWS_PER_WG + (threadIdx.x >> 5), hv = threadIdx.x & 31;
         int r = tile.row0 + row;
@@ -760,15 +953,14 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const AttnT
 }
 
 template <bool PRECISE>
-static hipError_t launch_attn_variant(const AttnArgs &a, const AttnItem *items, const int32_t *counts, int n_items_host,
-                                      int max_xcd_items, float *part_o, float *part_ml, hipStream_t s) {
+static hipError_t launch_staged(const AttnArgs &a, const AttnItem *items, const int32_t *counts, int n_items_host,
+                                int max_xcd_items, float *part_o, float *part_ml, hipStream_t s) {
     constexpr int smem = PRECISE ? 2 * ATTN_SMEM_BYTES : ATTN_SMEM_BYTES;
     static std::atomic<uint32_t> attr_done{0};
-    if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(attn_bf16_kernel<PRECISE>), smem);
+    if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(attn_staged_kernel<PRECISE>), smem);
         e != hipSuccess)
         return e;
-    int grid = 8 * max_xcd_items;
-    attn_bf16_kernel<PRECISE><<<grid, ATTN_THREADS, smem, s>>>(a, items, counts, n_items_host, part_o, part_ml);
+    attn_staged_kernel<PRECISE><<<8 * max_xcd_items, ATTN_THREADS, smem, s>>>(a, items, counts, n_items_host, part_o, part_ml);
     return hipGetLastError();
 }
 
@@ -776,8 +968,14 @@ hipError_t launch_attn_bf16(const AttnTune &tune, const AttnArgs &a, const AttnI
                             int n_items_host, int max_xcd_items, float *part_o, float *part_ml, hipStream_t s) {
     if (n_items_host <= 0 || max_xcd_items <= 0) return hipSuccess;
     bool precise = a.q_lo && a.ksuf_lo && a.vsuf_lo;
-    return precise ? launch_attn_variant<true>(a, items, counts, n_items_host, max_xcd_items, part_o, part_ml, s)
-                   : launch_attn_variant<false>(a, items, counts, n_items_host, max_xcd_items, part_o, part_ml, s);
+    if (precise) return launch_staged<true>(a, items, counts, n_items_host, max_xcd_items, part_o, part_ml, s);
+    if (tune.kernel == 1) return launch_staged<false>(a, items, counts, n_items_host, max_xcd_items, part_o, part_ml, s);
+    static std::atomic<uint32_t> attr_done{0};
+    if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(attn_pipe_kernel), PIPE_SMEM_BYTES);
+        e != hipSuccess)
+        return e;
+    attn_pipe_kernel<<<8 * max_xcd_items, ATTN_THREADS, PIPE_SMEM_BYTES, s>>>(a, items, counts, n_items_host, part_o, part_ml);
+    return hipGetLastError();
 }
 
 hipError_t launch_attn_merge(const AttnArgs &a, const AttnTile *tiles, const int32_t *counts, int n_tiles_host,

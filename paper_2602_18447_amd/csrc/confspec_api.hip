@@ -144,8 +144,10 @@ WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B, const confspec
         int64_t part_slots = w.max_items;
         cs::AttnPlanCounts pe = {}, pe_last = {};
         if (exact) {
-            pe = cs::attn_plan_counts(ctx->set.attn, exact->h_cu_suffix, exact->h_prefix_lens, exact->B, G, c.n_kv_heads, 0);
-            pe_last = cs::attn_plan_counts(ctx->set.attn, exact->h_cu_suffix, exact->h_prefix_lens, exact->B, G, c.n_kv_heads, 1);
+            pe = cs::attn_plan_counts(ctx->set.attn, exact->h_cu_suffix, exact->h_prefix_lens, exact->B, exact->T, nullptr, 0, G,
+                                      c.n_kv_heads, 0);
+            pe_last = cs::attn_plan_counts(ctx->set.attn, exact->h_cu_suffix, exact->h_prefix_lens, exact->B, exact->T, nullptr,
+                                           0, G, c.n_kv_heads, 1);
             w.max_tiles = std::max<int64_t>(pe.n_tiles, 1);
             w.max_items = std::max<int64_t>(pe.n_items, 1);
             part_slots = std::max<int64_t>(std::max(pe.n_part_slots, pe_last.n_part_slots), 1);
@@ -220,6 +222,9 @@ struct PassExtras {
     const confspec_head_out *head = nullptr;                        // full-vocabulary head at the last positions
     void *head_scratch = nullptr;
     size_t head_scratch_bytes = 0;
+    // context units: runs of consecutive traces on one shared context (null: every trace on its own)
+    const int32_t *dev_group_start = nullptr, *h_group_start = nullptr;
+    int n_groups = 0;
     bool exact_layout = false;                                      // workspace laid out for this batch alone
 };
 
@@ -320,7 +325,8 @@ int run_gemm(confspec_ctx *ctx, const void *A, const void *W, void *out, int M, 
     return CONFSPEC_OK;
 }
 
-cs::AttnArgs make_attn_args(const confspec_model_cfg &c, const confspec_kv *kv, const confspec_batch *b, int layer,
+cs::AttnArgs make_attn_args(const confspec_model_cfg &c, const confspec_kv *kv, const confspec_batch *b, const int32_t *tok_trace,
+                            int layer,
                             const void *q, const void *ksuf, const void *vsuf, const void *q_lo, const void *ksuf_lo,
                             const void *vsuf_lo, void *out, int out_terms) {
     cs::AttnArgs a = {};
@@ -333,6 +339,7 @@ cs::AttnArgs make_attn_args(const confspec_model_cfg &c, const confspec_kv *kv, 
     a.block_table = kv->block_table;
     a.cu = b->cu_suffix;
     a.plens = b->prefix_lens;
+    a.tok_trace = tok_trace;
     a.B = b->B; a.T = b->T; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.hd = c.head_dim;
     a.n_blocks = kv->n_blocks; a.block_size = kv->block_size; a.max_blocks = kv->max_blocks_per_seq;
     a.scale = 1.0f / sqrtf((float)c.head_dim);
@@ -361,16 +368,21 @@ int run_attention(confspec_ctx *ctx, const cs::AttnArgs &a, char *ws, const WsLa
 }
 
 // One attention plan (bf16 only): all suffix rows, or the last position of each trace.
-int run_attn_plan(confspec_ctx *ctx, const confspec_batch *b, int max_L, char *ws, const WsLayout &L, bool last_only,
-                  cs::AttnPlanCounts *pc, hipStream_t s) {
+struct Groups {
+    const int32_t *dev = nullptr, *host = nullptr;
+    int n = 0;
+};
+int run_attn_plan(confspec_ctx *ctx, const confspec_batch *b, const Groups &gr, int max_L, char *ws, const WsLayout &L,
+                  bool last_only, cs::AttnPlanCounts *pc, hipStream_t s) {
     const confspec_model_cfg &c = ctx->cfg;
     int G = c.n_q_heads / c.n_kv_heads;
     int64_t cap_tiles = last_only ? L.max_tiles2 : L.max_tiles, cap_items = last_only ? L.max_items2 : L.max_items;
-    *pc = cs::attn_plan_counts(ctx->set.attn, b->h_cu_suffix, b->h_prefix_lens, b->B, G, c.n_kv_heads, last_only ? 1 : 0);
+    *pc = cs::attn_plan_counts(ctx->set.attn, b->h_cu_suffix, b->h_prefix_lens, b->B, b->T, gr.host, gr.n, G, c.n_kv_heads,
+                               last_only ? 1 : 0);
     if (pc->n_tiles > cap_tiles || pc->n_items > cap_items)
         return fail(ctx, CONFSPEC_E_WORKSPACE, "attention plan (%lld tiles, %lld items) exceeds workspace capacity",
                     (long long)pc->n_tiles, (long long)pc->n_items);
-    HIP_TRY(cs::launch_attn_plan(b->cu_suffix, b->prefix_lens, b->B, b->T, max_L, G, c.n_kv_heads, pc->chunks_per_item,
+    HIP_TRY(cs::launch_attn_plan(b->cu_suffix, b->prefix_lens, gr.dev, gr.n, b->B, b->T, max_L, G, c.n_kv_heads, pc->chunks_per_item,
                                  pc->equalize, last_only ? 1 : 0, (int)cap_tiles, (int)cap_items,
                                  (cs::AttnTile *)(ws + (last_only ? L.plan2_tiles : L.plan_tiles)),
                                  (cs::AttnItem *)(ws + (last_only ? L.plan2_items : L.plan_items)),
@@ -379,13 +391,13 @@ int run_attn_plan(confspec_ctx *ctx, const confspec_batch *b, int max_L, char *w
 }
 
 // prep + (bf16) attention plan of all rows; fills pc.
-int run_plan(confspec_ctx *ctx, const confspec_batch *b, int max_L, char *ws, const WsLayout &L,
+int run_plan(confspec_ctx *ctx, const confspec_batch *b, const Groups &gr, int max_L, char *ws, const WsLayout &L,
              cs::AttnPlanCounts *pc, hipStream_t s) {
     const confspec_model_cfg &c = ctx->cfg;
     HIP_TRY(cs::launch_prep(b->cu_suffix, b->prefix_lens, b->B, b->T, max_L, (int32_t *)(ws + L.tok_trace),
                             (int32_t *)(ws + L.tok_pos), (int32_t *)(ws + L.last_row), s));
     *pc = cs::AttnPlanCounts{};
-    if (c.dtype == CONFSPEC_DTYPE_BF16) return run_attn_plan(ctx, b, max_L, ws, L, false, pc, s);
+    if (c.dtype == CONFSPEC_DTYPE_BF16) return run_attn_plan(ctx, b, gr, max_L, ws, L, false, pc, s);
     return CONFSPEC_OK;
 }
 
@@ -573,6 +585,22 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         HL = head_layout(c, batch->B);
         if ((rc = check_ws(ctx, ex.head_scratch, ex.head_scratch_bytes, HL.total)) != CONFSPEC_OK) return rc;
     }
+    if (ex.dev_group_start || ex.h_group_start) {
+        if (!ex.dev_group_start || !ex.h_group_start) return fail(ctx, CONFSPEC_E_INVALID_ARG, "group_start needs its dev and host copy");
+        const int32_t *gs = ex.h_group_start;
+        if (ex.n_groups < 1 || ex.n_groups > batch->B)
+            return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "n_groups = %d outside [1, B = %d]", ex.n_groups, batch->B);
+        if (gs[0] != 0 || gs[ex.n_groups] != batch->B)
+            return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "group_start must run from 0 to B = %d (got %d .. %d)", batch->B, gs[0], gs[ex.n_groups]);
+        for (int g = 0; g < ex.n_groups; ++g) {
+            if (gs[g + 1] <= gs[g]) return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "group_start not strictly increasing at group %d", g);
+            for (int b = gs[g] + 1; b < gs[g + 1]; ++b)
+                if (batch->h_prefix_lens[b] != batch->h_prefix_lens[gs[g]])
+                    return fail(ctx, CONFSPEC_E_OUT_OF_RANGE, "traces %d and %d of group %d have different prefix lengths (%d, %d)",
+                                gs[g], b, g, batch->h_prefix_lens[gs[g]], batch->h_prefix_lens[b]);
+        }
+        if (c.dtype != CONFSPEC_DTYPE_BF16) return fail(ctx, CONFSPEC_E_UNSUPPORTED, "shared-context groups need a bf16 context");
+    }
     if (dev_n_append) {
         if (!h_n_append) return fail(ctx, CONFSPEC_E_INVALID_ARG, "h_n_append is null");
         if (!kv->k_pages || !kv->v_pages) return fail(ctx, CONFSPEC_E_INVALID_ARG, "kv pages are null");
@@ -601,12 +629,14 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     auto mark = [&](int phase) -> hipError_t { return tm_.mark(phase, s); };
     HIP_TRY(mark(CONFSPEC_PHASE_OTHER));
     cs::AttnPlanCounts pc, pc_last;
-    if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
+    Groups gr;
+    gr.dev = ex.dev_group_start; gr.host = ex.h_group_start; gr.n = ex.n_groups;
+    if ((rc = run_plan(ctx, batch, gr, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
     // Only the last position of each trace feeds the verdict head, so everything of the last layer that
     // comes after its keys and values - attention rows, output projection, MLP - runs on those B rows.
     const Settings &set = ctx->set;
     const bool prune = c.dtype == CONFSPEC_DTYPE_BF16 && set.prune_last_layer && c.n_layers > 0;
-    if (prune && (rc = run_attn_plan(ctx, batch, max_L, ws, L, true, &pc_last, s)) != CONFSPEC_OK) return rc;
+    if (prune && (rc = run_attn_plan(ctx, batch, gr, max_L, ws, L, true, &pc_last, s)) != CONFSPEC_OK) return rc;
     HIP_TRY(cs::launch_rope_table((const int32_t *)(ws + L.tok_pos), T, c.head_dim, c.rope_theta,
                                   (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
     HIP_TRY(cs::launch_embed(c.dtype, batch->suffix_ids, w->embed, x, T, d, c.vocab, s));
@@ -656,7 +686,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
                                           prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, T, c.n_q_heads,
                                           c.n_kv_heads, c.head_dim, s));
         }
-        cs::AttnArgs a = make_attn_args(c, kv, batch, l, ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
+        cs::AttnArgs a = make_attn_args(c, kv, batch, (const int32_t *)(ws + L.tok_trace), l, ws + L.q, ws + L.ksuf, ws + L.vsuf, prec ? ws + L.q_lo : nullptr,
                                         prec ? ws + L.ksuf_lo : nullptr, prec ? ws + L.vsuf_lo : nullptr, ws + L.attn, tm);
         HIP_TRY(mark(prec ? CONFSPEC_PHASE_ATTN_PRECISE : CONFSPEC_PHASE_ATTN));
         if ((rc = run_attention(ctx, a, ws, L, last ? pc_last : pc, last, s))) return rc;
@@ -754,6 +784,22 @@ int confspec_verify(confspec_ctx *ctx, const confspec_weights *w, const confspec
     if (ctx && !h_verdict_ids) return fail(ctx, CONFSPEC_E_INVALID_ARG, "verdict ids or tau pointer is null");
     return verify_impl(ctx, w, kv, batch, h_verdict_ids, n_verdict, h_tau, n_tau, dev_workspace, workspace_bytes,
                        dev_verdict_logits, dev_conf, dev_verdict, dev_accept, PassExtras{}, stream);
+}
+
+int confspec_verify_shared(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
+                           const confspec_batch *batch, const int32_t *dev_group_start, const int32_t *h_group_start,
+                           int32_t n_groups, const int32_t *h_verdict_ids, int32_t n_verdict, const float *h_tau,
+                           int32_t n_tau, void *dev_workspace, size_t workspace_bytes, float *dev_verdict_logits,
+                           float *dev_conf, int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream) {
+    if (!ctx) return CONFSPEC_E_INVALID_ARG;
+    if (!h_verdict_ids) return fail(ctx, CONFSPEC_E_INVALID_ARG, "verdict ids or tau pointer is null");
+    if (!dev_group_start || !h_group_start) return fail(ctx, CONFSPEC_E_INVALID_ARG, "group_start is null");
+    PassExtras ex;
+    ex.dev_group_start = dev_group_start;
+    ex.h_group_start = h_group_start;
+    ex.n_groups = n_groups;
+    return verify_impl(ctx, w, kv, batch, h_verdict_ids, n_verdict, h_tau, n_tau, dev_workspace, workspace_bytes,
+                       dev_verdict_logits, dev_conf, dev_verdict, dev_accept, ex, stream);
 }
 
 int confspec_verify_append(confspec_ctx *ctx, const confspec_weights *w, const confspec_kv *kv,
@@ -981,8 +1027,8 @@ int confspec_op_attention(confspec_ctx *ctx, const confspec_kv *kv, const confsp
     if (int rd = check_device(ctx)) return rd;
     hipStream_t s = (hipStream_t)stream;
     cs::AttnPlanCounts pc;
-    if ((rc = run_plan(ctx, batch, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
-    cs::AttnArgs a = make_attn_args(ctx->cfg, kv, batch, layer, dev_q, dev_k_suffix, dev_v_suffix, dev_q_lo, dev_k_lo,
+    if ((rc = run_plan(ctx, batch, Groups{}, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
+    cs::AttnArgs a = make_attn_args(ctx->cfg, kv, batch, (const int32_t *)(ws + L.tok_trace), layer, dev_q, dev_k_suffix, dev_v_suffix, dev_q_lo, dev_k_lo,
                                     dev_v_lo, dev_out, out_terms);
     return run_attention(ctx, a, ws, L, pc, false, s);
 }

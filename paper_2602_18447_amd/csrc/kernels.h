@@ -6,6 +6,7 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 #include <atomic>
+#include "attn_plan.h"
 
 namespace cs {
 
@@ -25,13 +26,6 @@ struct GemmTune {
     int group_m = 0;   // 0 = heuristic; otherwise tile rows per band of the tile order
     int splitk = 0;    // 0 = heuristic; otherwise the split-K factor of every GEMM that has scratch (1 = never split)
 };
-struct AttnTune {
-    int target_items = 512;   // concurrent workgroup slots the planner assumes
-    int min_chunks = 4;       // shortest piece of a tile the planner cuts (decode-shaped batches: 4 is 2.6 % faster than 8)
-    int force_split = 0;      // 0 = choose by the makespan estimate, 1..4 = fixed split factor, 5 = front-loaded pieces
-    int kernel = 0;           // 0 = default main loop; 1 = the register-staged main loop (kept for the two-term variant)
-};
-
 // hipFuncSetAttribute(MaxDynamicSharedMemorySize) once per device and kernel: `mask` holds one bit per device.
 inline hipError_t set_dynamic_lds_once(std::atomic<uint32_t> &mask, const void *fn, int bytes) {
     int dev = 0;
@@ -45,42 +39,7 @@ inline hipError_t set_dynamic_lds_once(std::atomic<uint32_t> &mask, const void *
     return hipSuccess;
 }
 
-// ---- attention work description (built on the device by plan_attention) ----
-// One item = one q-row tile of one (trace, kv head) over one range of 64-key chunks.
-struct AttnItem {
-    int32_t b;            // trace
-    int32_t c;            // kv head
-    int32_t row0;         // first row of the tile in the trace's flattened (t * G + g) row space
-    int32_t chunk_begin;  // first 64-key chunk (inclusive)
-    int32_t chunk_end;    // last chunk (exclusive)
-    int32_t part_slot;    // >= 0: write fp32 partials to this slot; -1: write the final output
-    int32_t tile;         // index into the tile list
-    int32_t pad;
-};
-struct AttnTile {
-    int32_t b, c, row0;
-    int32_t part_base;    // first partial slot of this tile
-    int32_t n_splits;     // number of items covering this tile
-    int32_t pad[3];
-};
-
-constexpr int ATTN_BM = 128;      // q rows per tile (bf16 MFMA kernel): 4 wavefronts x 32 rows
-constexpr int ATTN_THREADS = 256;
-constexpr int ATTN_BN = 64;       // keys per chunk
-
-// Host-side mirror of the planner's counting pass (same arithmetic as the device code).
-struct AttnPlanCounts {
-    int64_t n_tiles, n_items, n_part_slots, total_chunks;
-    int64_t max_xcd_items;      // largest number of items any of the 8 XCDs gets
-    int32_t chunks_per_item;
-    int32_t equalize;           // 1: equal pieces per tile, 0: pieces of chunks_per_item, remainder last
-};
-// last_only: plan the last suffix position of each trace only (one tile of G rows per trace and kv head)
-AttnPlanCounts attn_plan_counts(const AttnTune &tune, const int32_t *h_cu, const int32_t *h_plens, int B, int G, int Hkv,
-                                int last_only);
-// Upper bounds used to size the workspace.
-void attn_plan_capacity(const AttnTune &tune, int64_t max_T, int64_t max_B, int G, int Hkv, int64_t *max_tiles,
-                        int64_t *max_items);
+// ---- attention work description and planner arithmetic: attn_plan.h ----
 
 enum Epilogue : int { EPI_STORE_F32 = 0, EPI_RESID_F32 = 1, EPI_SWIGLU = 2, EPI_ROPE = 3 };
 
@@ -182,6 +141,7 @@ struct AttnArgs {
     const int32_t *block_table;  // [B, max_blocks]
     const int32_t *cu;           // [B+1]
     const int32_t *plens;        // [B]
+    const int32_t *tok_trace;    // [T] trace of every packed suffix token (written by the prep kernel)
     void *out;              // [T, Hq*hd] in activation format out_terms: 1 storage dtype, 2 bf16 hi | lo
                             // ([T, 2*Hq*hd]), 3 IEEE half
     int32_t B, T, Hq, Hkv, hd, n_blocks, block_size, max_blocks;
@@ -190,10 +150,11 @@ struct AttnArgs {
 };
 hipError_t launch_attn_f32(const AttnArgs &a, const int32_t *tok_trace, const int32_t *tok_pos, hipStream_t s);
 
-hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, int B, int T, int max_L, int G, int Hkv,
-                            int chunks_per_item, int equalize, int last_only, int max_tiles, int max_items,
-                            AttnTile *tiles, AttnItem *items, int32_t *counts /*[11]: tiles, items, first item of XCD 0..8*/,
-                            hipStream_t s);
+// group_start: null (every trace is its own context unit) or n_units + 1 trace indices, dev (attn_plan.h)
+hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, const int32_t *group_start, int n_units, int B,
+                            int T, int max_L, int G, int Hkv, int chunks_per_item, int equalize, int last_only,
+                            int max_tiles, int max_items, AttnTile *tiles, AttnItem *items,
+                            int32_t *counts /*[11]: tiles, items, first item of XCD 0..8*/, hipStream_t s);
 // The attention kernel over the planned items; pieces of split tiles leave fp32 partial results in part_o / part_ml.
 hipError_t launch_attn_bf16(const AttnTune &tune, const AttnArgs &a, const AttnItem *items, const int32_t *counts,
                             int n_items_host, int max_xcd_items, float *part_o, float *part_ml, hipStream_t s);

@@ -78,6 +78,18 @@ class Verifier:
         cb.confspec_verify(self.ctx, self.w, kvs, bs, verdict_ids, taus, ws, *outs, stream=stream)
         return outs
 
+    def verify_shared(self, kv, batch, group_start, verdict_ids: Sequence[int], taus: Sequence[float], outputs=None,
+                      stream=None):
+        """verify() for a batch whose consecutive traces group_start[g] .. group_start[g + 1] - 1 are candidates on one
+        shared context (equal prefix lengths, block-table rows naming the same pages)."""
+        kvs, bs, keep = self.bind(kv, batch)
+        hg = np.ascontiguousarray(group_start, dtype=np.int32)
+        dg = torch.from_numpy(hg).to(self.device)
+        ws = self.workspace(bs.T, bs.B)
+        outs = outputs or self.alloc_outputs(bs.B, len(verdict_ids), len(taus))
+        cb.confspec_verify_shared(self.ctx, self.w, kvs, bs, dg, hg, verdict_ids, taus, ws, *outs, stream=stream)
+        return outs
+
     def verify_static(self, kv, batch, verdict_ids: Sequence[int], taus: Sequence[float], outputs, stream=None):
         """verify() on the library's own scratch array: nothing is allocated on the way (the caller brings the
         output tensors).  Batches that need more scratch than the array holds are rejected."""

@@ -150,6 +150,22 @@ def test_verify_validates_before_any_launch():
     cb.confspec_destroy(ctx)
 
 
+def test_shared_context_groups_are_validated():
+    _no_gpu_here()
+    cfg = _cfg()
+    ctx = cb.confspec_create(cfg)
+    fake, w, kv, batch, keep = _verify_args(cfg, B=3, L=(32, 32, 16), S=(3, 4, 5))
+
+    def call(gs):
+        cb.confspec_verify_shared(ctx, w, kv, batch, fake, np.asarray(gs, dtype=np.int32), [1, 2], [0.9], fake, fake, fake,
+                                  fake, fake, stream=0)
+    for bad in ([1, 3], [0, 2], [0, 2, 2, 3], [0, 3, 2, 3]):          # not from 0, not to B, not increasing
+        _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call(bad))
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call([0, 3]))              # prefix lengths 32, 32, 16 in one group
+    _expect(ctx, cb.E_OUT_OF_RANGE, lambda: call([0, 1, 3]))           # 32 and 16 in the second group
+    cb.confspec_destroy(ctx)
+
+
 def test_op_gemm_and_tune_validation():
     _no_gpu_here()
     ctx = cb.confspec_create(_cfg())

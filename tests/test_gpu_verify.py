@@ -154,6 +154,72 @@ def test_huge_activations_in_the_fp16_layers_give_finite_outputs():
     assert np.all(r["conf"] >= 0.5 - 1e-6) and np.all(r["conf"] <= 1.0 + 1e-6)
 
 
+def _shared_case(name, seed, groups, **kw):
+    """groups: list of (prefix_len, [suffix lengths of the candidates]).  Returns workload, inputs with the candidates
+    of a group reading their context through one set of pages, and the partition."""
+    prefix, suffix, gstart = [], [], [0]
+    for L, ss in groups:
+        prefix += [L] * len(ss)
+        suffix += list(ss)
+        gstart.append(gstart[-1] + len(ss))
+    wl = _small_bf16(name, seed, tuple(prefix), tuple(suffix), **kw)
+    weights, batch, kv = G.build_inputs(wl)
+    table = batch.block_table.clone()
+    for lo, hi in zip(gstart[:-1], gstart[1:]):
+        table[lo:hi] = table[lo]
+    batch.block_table = table
+    return wl, weights, batch, kv, gstart
+
+
+@pytest.mark.parametrize("heads", [(12, 2), (4, 2)])
+def test_candidates_on_a_shared_context_match_the_oracle(heads):
+    """Section 4.3: the candidates of one step verified side by side on one context.  Groups of 2 and 4 candidates
+    with short steps (a whole group inside one row tile), with 96-token steps (groups spanning several tiles, tiles
+    spanning two candidates), ragged groups, and plain traces, in one batch; every trace against the oracle, and
+    against the plain pass on the same batch."""
+    hq, hkv = heads
+    print(f"shared-context groups, heads {hq}/{hkv}", flush=True)
+    groups = [(700, [5, 21, 1, 13]), (64, [96, 96]), (300, [50]), (1000, [40, 7, 130]), (0, [9, 3]), (129, [96, 96, 96, 96]),
+              (33, [20, 21])]
+    wl, weights, batch, kv, gstart = _shared_case("shared", 2012, groups, n_q_heads=hq, n_kv_heads=hkv,
+                                                 d_model=128 * max(hq // 2, 2))
+    ver = Verifier(wl.model, weights)
+    vids = W.draw_verdict_ids(wl)
+    taus = list(wl.taus)
+    plain = G.run_gpu(wl, weights, batch, kv, verifier=ver)
+    outs = ver.verify_shared(kv, batch, gstart, vids, taus)
+    torch.cuda.synchronize()
+    shared = dict(logits=outs[0].cpu().numpy().astype(np.float64), conf=outs[1].cpu().numpy().astype(np.float64),
+                  verdict=outs[2].cpu().numpy(), accept=outs[3].cpu().numpy(), taus=taus, vids=vids)
+    ora = G.run_oracle(wl, weights, batch, kv, taus, vids)
+    G.compare(wl, shared, ora, "shared-context groups")
+    assert np.abs(shared["logits"] - plain["logits"]).max() <= 6e-3
+    # the register-staged main loop on the same groups
+    cb.confspec_tune(ver.ctx, "attn_kernel", 1)
+    outs = ver.verify_shared(kv, batch, gstart, vids, taus)
+    torch.cuda.synchronize()
+    staged = dict(shared, logits=outs[0].cpu().numpy().astype(np.float64), conf=outs[1].cpu().numpy().astype(np.float64),
+                  verdict=outs[2].cpu().numpy(), accept=outs[3].cpu().numpy())
+    G.compare(wl, staged, ora, "shared-context groups, register-staged kernel")
+    ver.close()
+
+
+def test_both_attention_main_loops_meet_the_bound():
+    print("attention main loops: software-pipelined / register-staged", flush=True)
+    wl = _small_bf16("loops", 2013, (700, 64, 0, 3000, 129, 1, 1023), (40, 96, 20, 7, 1, 200, 64), n_layers=4)
+    weights, batch, kv = G.build_inputs(wl)
+    ver = Verifier(wl.model, weights)
+    res = {}
+    for flag in (0, 1):
+        cb.confspec_tune(ver.ctx, "attn_kernel", flag)
+        res[flag] = G.run_gpu(wl, weights, batch, kv, verifier=ver)
+    ver.close()
+    ora = G.run_oracle(wl, weights, batch, kv, res[0]["taus"], res[0]["vids"])
+    for flag in (0, 1):
+        G.compare(wl, res[flag], ora, f"attn_kernel={flag}")
+    assert np.abs(res[0]["logits"] - res[1]["logits"]).max() <= 6e-3
+
+
 def test_fused_and_separate_rotary_embedding_agree():
     print("rope in the projection epilogue / as a kernel of its own", flush=True)
     wl = _small_bf16("rope", 2008, (700, 64, 0, 3000, 129), (40, 96, 20, 7, 1), n_layers=8)
