@@ -89,6 +89,13 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
                              size_t workspace_bytes, float *dev_verdict_logits, float *dev_conf,
                              int32_t *dev_verdict, uint8_t *dev_accept, confspec_stream stream);
 
+/* The slices the pass carves its workspace into, in carving order: byte offsets and lengths (host arrays of *n
+ * entries on entry, *n = number of slices on return, at most 48) and the total.  exact == NULL: the layout behind
+ * confspec_workspace_bytes(T, B); otherwise the layout for that one batch (confspec_static_scratch_need).  For
+ * checks of the layout on the host; nothing is launched. */
+int confspec_op_workspace_slices(const confspec_ctx *ctx, int32_t T, int32_t B, const confspec_batch *exact,
+                                 size_t *h_offsets, size_t *h_bytes, int32_t *n, size_t *total);
+
 /* Phase timing of the pass, the library's profiling hook.  While it is switched on for a context, every
  * confspec_verify / confspec_verify_append / confspec_generate_step call on that context records a HIP event on
  * its stream wherever the pass moves from one phase to the next (a few hundred events per pass, created when the

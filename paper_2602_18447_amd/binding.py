@@ -129,6 +129,8 @@ def _load() -> C.CDLL:
     lib.confspec_verify_shared.restype = C.c_int
     lib.confspec_verify_shared.argtypes = [vp, P(Weights), P(KV), P(Batch), vp, P(i32), i32, P(i32), i32, P(C.c_float), i32,
                                            vp, sz, vp, vp, vp, vp, vp]
+    lib.confspec_op_workspace_slices.restype = C.c_int
+    lib.confspec_op_workspace_slices.argtypes = [vp, i32, i32, P(Batch), P(sz), P(sz), P(i32), P(sz)]
     lib.confspec_phase_timing.restype = C.c_int
     lib.confspec_phase_timing.argtypes = [vp, i32]
     lib.confspec_phase_times.restype = C.c_int
@@ -145,7 +147,7 @@ EXPORTED = ["confspec_version", "confspec_create", "confspec_destroy", "confspec
             "confspec_op_gemm", "confspec_op_gemm_scratch_bytes", "confspec_op_rmsnorm", "confspec_op_rope_split", "confspec_op_qkv_rope", "confspec_op_attention",
             "confspec_op_verdict_gate", "confspec_tune", "confspec_cascade_scratch_bytes",
             "confspec_cascade", "confspec_verify_append", "confspec_head_scratch_bytes", "confspec_generate_step",
-            "confspec_static_scratch_need", "confspec_verify_static", "confspec_phase_timing", "confspec_phase_times", "confspec_verify_shared"]
+            "confspec_static_scratch_need", "confspec_verify_static", "confspec_phase_timing", "confspec_phase_times", "confspec_verify_shared", "confspec_op_workspace_slices"]
 
 
 class ConfSpecError(RuntimeError):

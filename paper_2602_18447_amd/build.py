@@ -53,5 +53,37 @@ def build(verbose: bool = True, jobs: int = 6) -> str:
     return LIB_PATH
 
 
+SAN_DIR = os.path.join(BUILD_DIR, "san")
+HOST_CHECK = os.path.join(SAN_DIR, "host_check")
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+             "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def build_host_check(verbose: bool = True, jobs: int = 6) -> str:
+    """csrc/host_check.cpp and the whole host side of the library compiled with AddressSanitizer and UBSan (the device
+    code is compiled as usual and never runs in the checker).  Returns the path of the executable."""
+    os.makedirs(SAN_DIR, exist_ok=True)
+    hipcc = _hipcc()
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(SAN_DIR, os.path.splitext(src)[0] + ".o")
+        cmd = [hipcc, *HIPCC_FLAGS, *SAN_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitizer build) failed for {src}:\n{r.stdout}\n{r.stderr}")
+        return obj
+
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(compile_one, SOURCES + ["host_check.cpp"]))
+    cmd = [hipcc, "--offload-arch=gfx950", *SAN_FLAGS, "-o", HOST_CHECK, *objs]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link of the host checker failed:\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print(f"built {HOST_CHECK}")
+    return HOST_CHECK
+
+
 if __name__ == "__main__":
     build()
+    build_host_check()

@@ -365,7 +365,6 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attn_pipe_kernel(AttnArgs a, 
     };
     // stage indices: K stages 0, 1; V stages 2, 3
     auto k_stage = [&](int i) -> unsigned char * { return smem + (i & 1) * PIPE_TILE_BYTES; };
-    auto v_stage = [&](int i) -> unsigned char * { return smem + (2 + (i & 1)) * PIPE_TILE_BYTES; };
 
     // ---- fragment addresses
     // K: MFMA row lq of block kb = key 32 kb + lq; k-step ks reads vector 2 ks + half of that key

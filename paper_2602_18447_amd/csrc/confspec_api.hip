@@ -102,6 +102,8 @@ struct WsLayout {
     size_t splitk, splitk_bytes;                                                        // split-K partial products
     size_t total;
     int64_t max_tiles, max_items, max_tiles2, max_items2;
+    size_t slice_off[48], slice_len[48];   // every slice as it was carved, for checks of the layout
+    int n_slices;
 };
 
 // exact (may be null): lay the workspace out for this batch alone instead of for every batch of up to T tokens in B
@@ -115,6 +117,7 @@ WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B, const confspec
     auto take = [&](size_t bytes) {
         size_t o = at;
         at = align_up(at + bytes);
+        if (w.n_slices < 48) { w.slice_off[w.n_slices] = o; w.slice_len[w.n_slices] = bytes; ++w.n_slices; }
         return o;
     };
     size_t eb = elem_bytes(c.dtype);
@@ -1056,6 +1059,21 @@ int confspec_op_verdict_gate(confspec_ctx *ctx, const confspec_batch *batch, con
     HIP_TRY(cs::launch_verdict(c.dtype, dev_x, (const int32_t *)(ws + L.last_row), dev_final_norm, dev_lm_head, va,
                                batch->B, batch->T, c.d_model, c.rms_eps, dev_verdict_logits, dev_conf, dev_verdict,
                                dev_accept, s));
+    return CONFSPEC_OK;
+}
+
+int confspec_op_workspace_slices(const confspec_ctx *ctx, int32_t T, int32_t B, const confspec_batch *exact, size_t *h_offsets,
+                                 size_t *h_bytes, int32_t *n, size_t *total) {
+    if (!ctx || !h_offsets || !h_bytes || !n || !total) return CONFSPEC_E_INVALID_ARG;
+    if (T < 1 || B < 1) return fail(ctx, CONFSPEC_E_INVALID_ARG, "T and B must be >= 1");
+    int rc;
+    if (exact && (rc = check_batch(ctx, exact, INT32_MAX, nullptr)) != CONFSPEC_OK) return rc;
+    if (exact && (exact->T != T || exact->B != B)) return fail(ctx, CONFSPEC_E_INVALID_ARG, "exact batch has other T / B");
+    WsLayout L = ws_layout(ctx, T, B, exact);
+    if (*n < L.n_slices) return fail(ctx, CONFSPEC_E_WORKSPACE, "%d slices, room for %d", L.n_slices, *n);
+    for (int i = 0; i < L.n_slices; ++i) { h_offsets[i] = L.slice_off[i]; h_bytes[i] = L.slice_len[i]; }
+    *n = L.n_slices;
+    *total = L.total;
     return CONFSPEC_OK;
 }
 
