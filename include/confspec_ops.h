@@ -138,7 +138,8 @@ int confspec_phase_times(confspec_ctx *ctx, float *h_ms /* [CONFSPEC_N_PHASES] *
  *   Launch shapes, for measurements: "gemm_tile" (0 heuristic; 1 = 128x128, 4 = 256x256, 7 = 192x96 workgroup tiles; a
  *       shape that does not divide N falls back to 128x128), "gemm_group_m" (0 heuristic, else tile rows per band of
  *       the GEMM's tile order), "gemm_splitk" (0 heuristic, 1..64 = split-K factor of every bf16 GEMM that is given
- *       scratch; 1 = never split), "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
+ *       scratch; 1 = never split), "gemm_short_tile" (default 1: split-K products of at most 32 rows use 32 x 128 tiles with
+ *       four LDS stages; 0: 128 x 128 tiles with two), "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
  *       "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = equal key-range pieces with that split factor,
  *       5 = front-loaded pieces), "attn_kernel" (0 = default main loop, 1 = the register-staged main loop).
  * Returns CONFSPEC_E_INVALID_ARG for an unknown key or a value out of range. */

@@ -1126,6 +1126,7 @@ int confspec_tune(confspec_ctx *ctx, const char *key, int32_t value) {
         {"gemm_tile", &st.gemm.tile, 0, 7},
         {"gemm_group_m", &st.gemm.group_m, 0, 65536},
         {"gemm_splitk", &st.gemm.splitk, 0, 64},
+        {"gemm_short_tile", &st.gemm.short_tile, 0, 1},
         {"split_layers", &st.split_layers, -1, 4096},
         {"prefetch_down", &st.prefetch_down, 0, 1},
         {"fuse_rope", &st.fuse_rope, 0, 1},

@@ -722,6 +722,23 @@ static hipError_t launch_splitk_tiles(const GemmTune &tune, const bf16 *A, const
     return hipGetLastError();
 }
 
+// At most 32 rows (a generation step with one token per trace, the last layer's one row per trace): 32 x 128 tiles
+// with four LDS stages, so that a workgroup keeps three k-tiles of its weight panel (60 KiB) in flight - such a
+// product is a stream of the weight matrix, and the 128-row tile's two stages leave it latency-bound.
+template <int A_FMT>
+static hipError_t launch_splitk_short(const GemmTune &tune, const bf16 *A, const bf16 *W, float *part, int M, int N, int K,
+                                      int splits, hipStream_t s) {
+    constexpr int BM = 32, BN = 128, NS = 4;
+    constexpr int smem = NS * (BM + BN) * 64 * 2;
+    static std::atomic<uint32_t> attr_done{0};
+    auto kern = gemm_bf16_kernel<BM, BN, 1, 2, 64, NS, EPI_STORE_F32, A_FMT>;
+    if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
+    int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8, splits);
+    kern<<<grid, 128, smem, s>>>(A, W, part, M, N, K, tiles_m, tiles_n, 0, 1, 1, RopeArgs{}, PrefetchArgs{});
+    return hipGetLastError();
+}
+
 // The partial products of the k slices, one [M, N] fp32 plane per slice; big_tile: 256 x 256 tiles, else 128 x 128.
 static hipError_t launch_splitk_main(const GemmTune &tune, const bf16 *A, const bf16 *W, float *part, int M, int N, int K,
                                      int a_terms, int splits, bool big_tile, hipStream_t s) {
@@ -729,6 +746,10 @@ static hipError_t launch_splitk_main(const GemmTune &tune, const bf16 *A, const 
         return a_terms == 2   ? launch_splitk_tiles<2, 256, 4>(tune, A, W, part, M, N, K, splits, s)
                : a_terms == 3 ? launch_splitk_tiles<3, 256, 4>(tune, A, W, part, M, N, K, splits, s)
                               : launch_splitk_tiles<1, 256, 4>(tune, A, W, part, M, N, K, splits, s);
+    if (M <= 32 && tune.short_tile)
+        return a_terms == 2   ? launch_splitk_short<2>(tune, A, W, part, M, N, K, splits, s)
+               : a_terms == 3 ? launch_splitk_short<3>(tune, A, W, part, M, N, K, splits, s)
+                              : launch_splitk_short<1>(tune, A, W, part, M, N, K, splits, s);
     return a_terms == 2   ? launch_splitk_tiles<2, 128, 2>(tune, A, W, part, M, N, K, splits, s)
            : a_terms == 3 ? launch_splitk_tiles<3, 128, 2>(tune, A, W, part, M, N, K, splits, s)
                           : launch_splitk_tiles<1, 128, 2>(tune, A, W, part, M, N, K, splits, s);

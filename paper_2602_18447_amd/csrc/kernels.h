@@ -25,6 +25,7 @@ struct GemmTune {
     int tile = 0;      // 0 = heuristic; 1 = 128x128, 4 = 256x256 / 8 wavefronts, 7 = 192x96 / 6 wavefronts
     int group_m = 0;   // 0 = heuristic; otherwise tile rows per band of the tile order
     int splitk = 0;    // 0 = heuristic; otherwise the split-K factor of every GEMM that has scratch (1 = never split)
+    int short_tile = 1;   // 1 = split-K products of at most 32 rows use 32 x 128 tiles with four LDS stages
 };
 // hipFuncSetAttribute(MaxDynamicSharedMemorySize) once per device and kernel: `mask` holds one bit per device.
 inline hipError_t set_dynamic_lds_once(std::atomic<uint32_t> &mask, const void *fn, int bytes) {
