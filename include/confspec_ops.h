@@ -141,7 +141,8 @@ int confspec_phase_times(confspec_ctx *ctx, float *h_ms /* [CONFSPEC_N_PHASES] *
  *       scratch; 1 = never split), "gemm_short_tile" (default 1: split-K products of at most 32 rows use 32 x 128 tiles with
  *       four LDS stages; 0: 128 x 128 tiles with two), "attn_target_items" (concurrent workgroup slots assumed by the attention planner),
  *       "attn_min_chunks", "attn_split" (0 = planner's choice, 1..4 = equal key-range pieces with that split factor,
- *       5 = front-loaded pieces), "attn_kernel" (0 = default main loop, 1 = the register-staged main loop).
+ *       5 = front-loaded pieces), "attn_kernel" (0 = the software-pipelined main loop, the register-staged one for
+ *       items of fewer than 12 chunks on average; 1 = always the register-staged loop; 2 = always the pipelined one).
  * Returns CONFSPEC_E_INVALID_ARG for an unknown key or a value out of range. */
 int confspec_tune(confspec_ctx *ctx, const char *key, int32_t value);
 

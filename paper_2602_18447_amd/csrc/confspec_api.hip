@@ -359,7 +359,8 @@ int run_attention(confspec_ctx *ctx, const cs::AttnArgs &a, char *ws, const WsLa
         size_t items = last_only ? L.plan2_items : L.plan_items, tiles = last_only ? L.plan2_tiles : L.plan_tiles;
         size_t counts = last_only ? L.plan2_counts : L.plan_counts;
         HIP_TRY(cs::launch_attn_bf16(ctx->set.attn, a, (const cs::AttnItem *)(ws + items), (const int32_t *)(ws + counts),
-                                     (int)pc.n_items, (int)pc.max_xcd_items, (float *)(ws + L.part_o),
+                                     (int)pc.n_items, (int)pc.max_xcd_items,
+                                     (int)(pc.total_chunks / std::max<int64_t>(pc.n_items, 1)), (float *)(ws + L.part_o),
                                      (float *)(ws + L.part_ml), s));
         if (pc.n_part_slots > 0) {
             HIP_TRY(ctx->timer.mark(CONFSPEC_PHASE_ATTN_MERGE, s));
@@ -1136,7 +1137,7 @@ int confspec_tune(confspec_ctx *ctx, const char *key, int32_t value) {
         {"attn_target_items", &st.attn.target_items, 1, 65536},
         {"attn_split", &st.attn.force_split, 0, 5},
         {"attn_min_chunks", &st.attn.min_chunks, 1, 4096},
-        {"attn_kernel", &st.attn.kernel, 0, 1},
+        {"attn_kernel", &st.attn.kernel, 0, 2},
     };
     for (const Entry &e : table)
         if (!strcmp(key, e.key)) {

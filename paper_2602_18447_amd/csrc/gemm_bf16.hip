@@ -526,7 +526,8 @@ int gemm_splitk_factor(const GemmTune &tune, int M, int N, int K_total, bool *bi
         }
     }
     int want = (384 + tiles / 2) / tiles;                // about 384 workgroups
-    int s = std::min(want, nk / 4);                      // at least 4 k-tiles per slice
+    // at least 4 k-tiles per slice; 2 for the 32-row tile, whose four LDS stages keep a short slice streaming
+    int s = std::min(want, nk / ((M <= 32 && tune.short_tile) ? 2 : 4));
     return std::max(1, std::min(s, 64));
 }
 size_t gemm_splitk_bytes(const GemmTune &tune, int M, int N, int K_total) {

@@ -157,8 +157,9 @@ hipError_t launch_attn_plan(const int32_t *cu, const int32_t *plens, const int32
                             int max_tiles, int max_items, AttnTile *tiles, AttnItem *items,
                             int32_t *counts /*[11]: tiles, items, first item of XCD 0..8*/, hipStream_t s);
 // The attention kernel over the planned items; pieces of split tiles leave fp32 partial results in part_o / part_ml.
+// avg_chunks: average number of key chunks per item (chooses the main loop)
 hipError_t launch_attn_bf16(const AttnTune &tune, const AttnArgs &a, const AttnItem *items, const int32_t *counts,
-                            int n_items_host, int max_xcd_items, float *part_o, float *part_ml, hipStream_t s);
+                            int n_items_host, int max_xcd_items, int avg_chunks, float *part_o, float *part_ml, hipStream_t s);
 // Combines the partial results of every split tile in piece order and writes the output rows.
 hipError_t launch_attn_merge(const AttnArgs &a, const AttnTile *tiles, const int32_t *counts, int n_tiles_host,
                              const float *part_o, const float *part_ml, hipStream_t s);
