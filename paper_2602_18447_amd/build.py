@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libconfspec.so")
 
-SOURCES = ["confspec_api.hip", "kernels_small.hip", "path_f32.hip", "gemm_bf16.hip", "attn_bf16.hip", "cascade.hip",
+SOURCES = ["confspec_api.hip", "kernels_small.hip", "path_f32.hip", "gemm_bf16.hip", "attn_bf16.hip", "decode_bf16.hip", "cascade.hip",
            "attn_plan.cpp"]
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions.

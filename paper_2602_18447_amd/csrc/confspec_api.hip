@@ -42,6 +42,9 @@ struct Settings {
     int fuse_rope = 1;
     // The gate/up projection warms the last-level cache with the down projection's weights.
     int prefetch_down = 1;
+    // 1: a bf16 pass with one new token per trace and at most 32 traces (a generation step) runs on the kernels
+    // shaped for it (decode_bf16.hip); 0: it runs on the verification pass's kernels
+    int decode_kernels = 1;
     cs::GemmTune gemm;
     cs::AttnTune attn;
 };
@@ -100,11 +103,37 @@ struct WsLayout {
     size_t plan_counts, plan_tiles, plan_items, part_o, part_ml;
     size_t x_last, h_last, attn_last, act_last, plan2_counts, plan2_tiles, plan2_items;   // last layer, last rows only
     size_t splitk, splitk_bytes;                                                        // split-K partial products
+    size_t dec_ctl, dec_ssq;                            // generation-step kernels: control block, partial sums of squares
+    size_t part_o_bytes, part_ml_bytes;
     size_t total;
     int64_t max_tiles, max_items, max_tiles2, max_items2;
     size_t slice_off[48], slice_len[48];   // every slice as it was carved, for checks of the layout
     int n_slices;
 };
+
+// A pass that the generation-step kernels can take, as far as the model and the batch shape decide it: a bf16 model
+// with 128-wide heads, one new token in each of at most 32 traces.
+bool dec_shape_ok(const confspec_model_cfg &c, int64_t T, int64_t B) {
+    if (c.dtype != CONFSPEC_DTYPE_BF16 || T != B || B < 1 || B > cs::DEC_MAX_ROWS) return false;
+    if (c.head_dim != 128 || c.n_kv_heads < 1 || c.n_q_heads % c.n_kv_heads != 0) return false;
+    const int G = c.n_q_heads / c.n_kv_heads;
+    if (G > cs::DEC_MAX_G || B * c.n_kv_heads > cs::DEC_CTL_TILE - cs::DEC_CTL_ATTN) return false;
+    return c.d_model % 64 == 0 && c.d_ffn % 64 == 0 && c.n_layers > 0;
+}
+// Partial planes of the step's four projections (the largest one).
+size_t dec_plane_bytes(const confspec_model_cfg &c) {
+    const int qw = c.n_q_heads * c.head_dim, kw = c.n_kv_heads * c.head_dim;
+    size_t m = cs::dec_gemm_plane_bytes(c.d_model, (qw + 2 * kw) / 16);
+    m = std::max(m, cs::dec_gemm_plane_bytes(qw, c.d_model / 16));
+    m = std::max(m, cs::dec_gemm_plane_bytes(c.d_model, c.d_ffn / 8));
+    m = std::max(m, cs::dec_gemm_plane_bytes(c.d_ffn, c.d_model / 16));
+    return m;
+}
+int64_t dec_pieces(const int32_t *h_prefix_lens, int B) {
+    int64_t n = 0;
+    for (int b = 0; b < B; ++b) n += (std::max(h_prefix_lens[b], 0) + 1 + cs::DEC_PIECE - 1) / cs::DEC_PIECE;
+    return n;
+}
 
 // exact (may be null): lay the workspace out for this batch alone instead of for every batch of up to T tokens in B
 // traces - the attention plans' lists and partial results and the split-K planes are then sized by what this batch's
@@ -158,8 +187,15 @@ WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B, const confspec
         w.plan_counts = take(256);
         w.plan_tiles = take((size_t)w.max_tiles * sizeof(cs::AttnTile));
         w.plan_items = take((size_t)w.max_items * sizeof(cs::AttnItem));
-        w.part_o = take((size_t)part_slots * cs::ATTN_BM * c.head_dim * 4);
-        w.part_ml = take((size_t)part_slots * cs::ATTN_BM * 2 * 4);
+        w.part_o_bytes = (size_t)part_slots * cs::ATTN_BM * c.head_dim * 4;
+        w.part_ml_bytes = (size_t)part_slots * cs::ATTN_BM * 2 * 4;
+        if (exact && dec_shape_ok(c, T, B)) {   // the generation-step attention keeps its pieces' partial results here
+            int64_t np = dec_pieces(exact->h_prefix_lens, exact->B);
+            w.part_o_bytes = std::max(w.part_o_bytes, cs::dec_attn_part_o_bytes(np, c.n_kv_heads));
+            w.part_ml_bytes = std::max(w.part_ml_bytes, cs::dec_attn_part_ml_bytes(np, c.n_kv_heads));
+        }
+        w.part_o = take(w.part_o_bytes);
+        w.part_ml = take(w.part_ml_bytes);
         // the last layer works on the last position of each trace only: B rows, one attention tile per
         // trace and kv head (its items fit the partial buffers above: max_items2 <= max_items)
         w.x_last = take((size_t)B * c.d_model * 4);
@@ -193,8 +229,12 @@ WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B, const confspec
             sk = std::max(sk, cs::gemm_splitk_max_bytes(ctx->set.gemm, (int)T, 2 * c.d_ffn, c.d_model * t));
             sk = std::max(sk, cs::gemm_splitk_max_bytes(ctx->set.gemm, (int)T, c.d_model, c.d_ffn * t));
         }
+        // a general layout serves every smaller batch, generation steps included
+        if (exact ? dec_shape_ok(c, T, B) : dec_shape_ok(c, 1, 1)) sk = std::max(sk, dec_plane_bytes(c));
         w.splitk_bytes = sk;
         w.splitk = take(std::max<size_t>(sk, 256));
+        w.dec_ctl = take((size_t)cs::DEC_CTL_INTS * 4);
+        w.dec_ssq = take((size_t)(c.d_model / 16 + 1) * cs::DEC_MAX_ROWS * 4);
     }
     w.total = at;
     return w;
@@ -632,19 +672,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     tm_.overflow = false;
     auto mark = [&](int phase) -> hipError_t { return tm_.mark(phase, s); };
     HIP_TRY(mark(CONFSPEC_PHASE_OTHER));
-    cs::AttnPlanCounts pc, pc_last;
-    Groups gr;
-    gr.dev = ex.dev_group_start; gr.host = ex.h_group_start; gr.n = ex.n_groups;
-    if ((rc = run_plan(ctx, batch, gr, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
-    // Only the last position of each trace feeds the verdict head, so everything of the last layer that
-    // comes after its keys and values - attention rows, output projection, MLP - runs on those B rows.
     const Settings &set = ctx->set;
-    const bool prune = c.dtype == CONFSPEC_DTYPE_BF16 && set.prune_last_layer && c.n_layers > 0;
-    if (prune && (rc = run_attn_plan(ctx, batch, gr, max_L, ws, L, true, &pc_last, s)) != CONFSPEC_OK) return rc;
-    HIP_TRY(cs::launch_rope_table((const int32_t *)(ws + L.tok_pos), T, c.head_dim, c.rope_theta,
-                                  (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
-    HIP_TRY(cs::launch_embed(c.dtype, batch->suffix_ids, w->embed, x, T, d, c.vocab, s));
-    const int32_t *last_row = (const int32_t *)(ws + L.last_row);
     size_t eb = elem_bytes(c.dtype);
     // Activation format of a layer's GEMMs (see gemm_bf16.hip): the first layers run on fp16 operands when the
     // packed weights carry fp16 copies (3), else with two bf16 terms (2); the rest is plain bf16 (1).
@@ -660,8 +688,106 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
             return 3;
         return 2;
     };
+    // A generation step (one new token per trace, at most 32 traces) runs on the kernels shaped for it when every
+    // layer's operands are single 16-bit values (bf16 or fp16) and the scratch holds its partial results; everything
+    // else, and any step that does not fit, takes the general kernels below.
+    bool use_dec = set.decode_kernels && dec_shape_ok(c, T, B) && !ex.dev_group_start;
+    int64_t dec_np = 0;
+    if (use_dec) {
+        for (int l = 0; l < c.n_layers && use_dec; ++l) use_dec = rope_fused_in(l) && format_of(l) != 2;
+        dec_np = dec_pieces(batch->h_prefix_lens, B);
+        use_dec = use_dec && dec_plane_bytes(c) <= L.splitk_bytes && cs::dec_attn_part_o_bytes(dec_np, c.n_kv_heads) <= L.part_o_bytes &&
+                  cs::dec_attn_part_ml_bytes(dec_np, c.n_kv_heads) <= L.part_ml_bytes;
+    }
+    cs::AttnPlanCounts pc = {}, pc_last = {};
+    Groups gr;
+    gr.dev = ex.dev_group_start; gr.host = ex.h_group_start; gr.n = ex.n_groups;
+    // Only the last position of each trace feeds the verdict head, so everything of the last layer that
+    // comes after its keys and values - attention rows, output projection, MLP - runs on those B rows.
+    const bool prune = c.dtype == CONFSPEC_DTYPE_BF16 && set.prune_last_layer && c.n_layers > 0;
+    if (use_dec) {   // the generation-step attention has its own, fixed cut into pieces: no plan
+        HIP_TRY(cs::launch_prep(batch->cu_suffix, batch->prefix_lens, B, T, max_L, (int32_t *)(ws + L.tok_trace),
+                                (int32_t *)(ws + L.tok_pos), (int32_t *)(ws + L.last_row), s));
+    } else {
+        if ((rc = run_plan(ctx, batch, gr, max_L, ws, L, &pc, s)) != CONFSPEC_OK) return rc;
+        if (prune && (rc = run_attn_plan(ctx, batch, gr, max_L, ws, L, true, &pc_last, s)) != CONFSPEC_OK) return rc;
+    }
+    HIP_TRY(cs::launch_rope_table((const int32_t *)(ws + L.tok_pos), T, c.head_dim, c.rope_theta,
+                                  (float *)(ws + L.rope_cos), (float *)(ws + L.rope_sin), s));
+    HIP_TRY(cs::launch_embed(c.dtype, batch->suffix_ids, w->embed, x, T, d, c.vocab, s));
+    const int32_t *last_row = (const int32_t *)(ws + L.last_row);
+    if (use_dec) {
+        int32_t *ctl = (int32_t *)(ws + L.dec_ctl);
+        HIP_TRY(cs::launch_dec_init(batch->prefix_lens, B, max_L, ctl, s));
+        const size_t layer_bytes = (size_t)kv->n_blocks * c.n_kv_heads * kv->block_size * c.head_dim * eb;
+        // The RMSNorm in front of the QKV and gate/up projections: the residual projection before writes x * gain in
+        // the operand format and per-row partial sums of squares, the consumer scales its result rows (decode_bf16.hip).
+        // The first layer's input comes from the embedding: the RMSNorm kernel, once.
+        float *ssq = (float *)(ws + L.dec_ssq);
+        const int ssq_n = d / 16;
+        HIP_TRY(mark(CONFSPEC_PHASE_NORM));
+        HIP_TRY(cs::launch_rmsnorm(c.dtype, x, w->attn_norm[0], h, T, d, c.rms_eps, format_of(0), s));
+        auto proj = [&](cs::DecGemm &g, const void *X, int ldx, const void *W, int K, int n_ct) {
+            g.X = (const cs::bf16 *)X; g.ldx = ldx; g.W = (const cs::bf16 *)W; g.M = B; g.K = K; g.n_ct = n_ct;
+            cs::dec_gemm_plan(K, n_ct, &g.S, &g.nwg);
+            g.planes = (float *)(ws + L.splitk);
+            g.tile_cnt = ctl + cs::DEC_CTL_TILE;
+        };
+        for (int l = 0; l < c.n_layers; ++l) {
+            const int tm = format_of(l);
+            const bool f16 = tm == 3;
+            const void *wqkv = f16 ? w->wqkv_f16[l] : w->wqkv_perm[l], *wo = f16 ? w->wo_f16[l] : w->wo[l];
+            const void *wgu = f16 ? w->w_gate_up_f16[l] : w->w_gate_up[l], *wdn = f16 ? w->w_down_f16[l] : w->w_down[l];
+            HIP_TRY(mark(CONFSPEC_PHASE_QKV));
+            cs::DecGemm gq = {};
+            proj(gq, h, d, wqkv, d, (qw + 2 * kw) / 16);
+            if (l > 0) { gq.ssq_in = ssq; gq.ssq_n = ssq_n; gq.eps = c.rms_eps; }
+            gq.rope = cs::RopeArgs{(const float *)(ws + L.rope_cos), (const float *)(ws + L.rope_sin), ws + L.q, ws + L.ksuf, ws + L.vsuf,
+                                   ws + L.q_lo, nullptr, nullptr, c.n_q_heads, c.n_kv_heads};
+            gq.perm = 1;
+            if (dev_n_append) {
+                gq.k_pages = (char *)const_cast<void *>(kv->k_pages) + layer_bytes * l;
+                gq.v_pages = (char *)const_cast<void *>(kv->v_pages) + layer_bytes * l;
+                gq.table = kv->block_table; gq.plens = batch->prefix_lens; gq.n_append = dev_n_append;
+                gq.max_blocks = kv->max_blocks_per_seq; gq.n_blocks = kv->n_blocks;
+            }
+            HIP_TRY(cs::launch_dec_gemm(gq, cs::DEC_EPI_ROPE, f16, s));
+            HIP_TRY(mark(CONFSPEC_PHASE_ATTN));
+            cs::DecAttn at = {};
+            at.q = (const cs::bf16 *)(ws + L.q); at.q_lo = (const cs::bf16 *)(ws + L.q_lo);
+            at.ksuf = (const cs::bf16 *)(ws + L.ksuf); at.vsuf = (const cs::bf16 *)(ws + L.vsuf);
+            at.k_pages = kv->k_pages ? (const cs::bf16 *)((const char *)kv->k_pages + layer_bytes * l) : nullptr;
+            at.v_pages = kv->v_pages ? (const cs::bf16 *)((const char *)kv->v_pages + layer_bytes * l) : nullptr;
+            at.table = kv->block_table; at.plens = batch->prefix_lens; at.ctl = ctl;
+            at.out = ws + L.attn; at.out_fmt = tm;
+            at.part_o = (float *)(ws + L.part_o); at.part_ml = (float *)(ws + L.part_ml);
+            at.B = B; at.Hq = c.n_q_heads; at.Hkv = c.n_kv_heads; at.G = c.n_q_heads / c.n_kv_heads;
+            at.max_blocks = kv->max_blocks_per_seq; at.n_blocks = kv->n_blocks; at.max_L = max_L;
+            at.scale_log2 = 1.44269504088896340736f / sqrtf((float)c.head_dim);
+            HIP_TRY(cs::launch_dec_attn(at, (int)dec_np, s));
+            HIP_TRY(mark(CONFSPEC_PHASE_O_PROJ));
+            cs::DecGemm go = {};
+            proj(go, ws + L.attn, qw, wo, qw, d / 16);
+            go.x = x; go.xg_out = h; go.g_next = (const cs::bf16 *)w->mlp_norm[l]; go.ssq_out = ssq; go.xg_fmt = tm;
+            HIP_TRY(cs::launch_dec_gemm(go, cs::DEC_EPI_RESID, f16, s));
+            HIP_TRY(mark(CONFSPEC_PHASE_GATE_UP));
+            cs::DecGemm gg = {};
+            proj(gg, h, d, wgu, d, c.d_ffn / 8);
+            gg.ssq_in = ssq; gg.ssq_n = ssq_n; gg.eps = c.rms_eps;
+            gg.act = ws + L.act; gg.act_fmt = tm;
+            HIP_TRY(cs::launch_dec_gemm(gg, cs::DEC_EPI_SWIGLU, f16, s));
+            HIP_TRY(mark(CONFSPEC_PHASE_DOWN));
+            cs::DecGemm gd = {};
+            proj(gd, ws + L.act, c.d_ffn, wdn, c.d_ffn, d / 16);
+            gd.x = x;
+            if (l + 1 < c.n_layers) {   // the next layer's operand, in that layer's format
+                gd.xg_out = h; gd.g_next = (const cs::bf16 *)w->attn_norm[l + 1]; gd.ssq_out = ssq; gd.xg_fmt = format_of(l + 1);
+            }
+            HIP_TRY(cs::launch_dec_gemm(gd, cs::DEC_EPI_RESID, f16, s));
+        }
+    }
     bool attn_norm_done = false;   // the previous layer's down projection already wrote this layer's normalised input
-    for (int l = 0; l < c.n_layers; ++l) {
+    for (int l = 0; l < c.n_layers && !use_dec; ++l) {
         const int tm = format_of(l);
         const void *wqkv = w->wqkv[l], *wo = w->wo[l], *wgu = w->w_gate_up[l], *wdn = w->w_down[l];
         const bool rope_fused = rope_fused_in(l);
@@ -751,7 +877,10 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         dev_accept = (uint8_t *)(hs + HL.v_accept);
     }
     if (want_verdict) {
-        if (prune)
+        if (use_dec)         // every row is the last row of its trace
+            HIP_TRY(cs::launch_verdict(c.dtype, x, nullptr, w->final_norm, w->lm_head, va, B, B, d, c.rms_eps, dev_verdict_logits,
+                                       dev_conf, dev_verdict, dev_accept, s));
+        else if (prune)
             HIP_TRY(cs::launch_verdict(c.dtype, (const float *)(ws + L.x_last), nullptr, w->final_norm, w->lm_head, va, B, B, d,
                                        c.rms_eps, dev_verdict_logits, dev_conf, dev_verdict, dev_accept, s));
         else
@@ -762,8 +891,8 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         // Logits of the whole vocabulary at the last position of every trace: final norm of those B rows (two bf16
         // terms, so the operand carries ~16 mantissa bits), one GEMM against the head, then arg max / log-sum-exp.
         char *hs = (char *)ex.head_scratch;
-        const float *xl = (const float *)(ws + L.x_last);
-        if (!prune) {
+        const float *xl = use_dec ? x : (const float *)(ws + L.x_last);
+        if (!prune && !use_dec) {
             HIP_TRY(cs::launch_gather_rows(x, hs + HL.x, last_row, B, T, (size_t)d * 4, s));
             xl = (const float *)(hs + HL.x);
         }
@@ -1131,6 +1260,7 @@ int confspec_tune(confspec_ctx *ctx, const char *key, int32_t value) {
         {"split_layers", &st.split_layers, -1, 4096},
         {"prefetch_down", &st.prefetch_down, 0, 1},
         {"fuse_rope", &st.fuse_rope, 0, 1},
+        {"decode_kernels", &st.decode_kernels, 0, 1},
         {"first_layers_f16", &st.first_layers_f16, 0, 1},
         {"prune_last_layer", &st.prune_last_layer, 0, 1},
         {"attn_precise_layers", &st.attn_precise_layers, 0, 4096},

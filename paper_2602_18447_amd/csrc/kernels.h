@@ -171,6 +171,73 @@ hipError_t launch_kv_append(const void *ksuf, const void *vsuf, void *k_pages, v
                             int B, int T, int Hkv, size_t head_row_bytes, int block_size, int max_blocks, int n_blocks,
                             hipStream_t s);
 
+// ---- generation steps: one new token per trace (decode_bf16.hip) ----
+constexpr int DEC_MAX_ROWS = 32;     // traces of a step the decode-shaped kernels take
+constexpr int DEC_PIECE = 256;       // keys per attention workgroup
+constexpr int DEC_MAX_G = 8;         // q heads per kv head
+constexpr int DEC_MAX_KT = 24;       // k-tiles (of 64) of one k slice of a projection: 96 KiB of activations in LDS
+// control block (int32): piece offsets [0 .. B], then the arrival counters
+constexpr int DEC_CTL_ATTN = 64;                         // + trace * Hkv + kv head
+constexpr int DEC_CTL_TILE = DEC_CTL_ATTN + 1024;        // + column group of a sliced projection (<= 256)
+constexpr int DEC_CTL_INTS = DEC_CTL_TILE + 256;
+enum DecEpilogue : int { DEC_EPI_ROPE = 0, DEC_EPI_RESID = 1, DEC_EPI_SWIGLU = 2 };
+
+// One projection of a step: out = X[M, K] . W[N, K]^T, M <= 32, K % 64 == 0, N % 16 == 0, then the epilogue.
+struct DecGemm {
+    const bf16 *X;            // [M, ldx], bf16 or (f16 != 0) IEEE half
+    // ssq_in != null (ROPE, SWIGLU): X holds x * g without the 1 / rms factor of the RMSNorm; ssq_in [ssq_n, 32] are
+    // partial sums of squares of every row (left by the preceding residual projection), the result rows are scaled by
+    // 1 / sqrt(sum / K + eps)
+    const float *ssq_in;
+    int32_t ssq_n;
+    float eps;
+    const bf16 *W;            // [N, K], same element type
+    int32_t ldx, M, K;
+    int32_t n_ct;             // 16-column tiles of the accumulator: N / 16 (ROPE, RESID), N / 16 = F / 8 (SWIGLU)
+    int32_t S, nwg;           // k slices and workgroups per slice (dec_gemm_plan)
+    float *planes;            // S > 1: [S, 32, 16 n_ct] fp32 partial products
+    int32_t *tile_cnt;        // S > 1: nwg arrival counters (zero before and after the launch)
+    // RESID: x [M, N] fp32 += product.  With xg_out (may be null) it also writes the operand of the projection that
+    // follows, x * g_next in format xg_fmt (1 bf16, 3 half) [M, N], and ssq_out [N / 16, 32]: the sum of squares of
+    // each 16 columns of every updated row.
+    float *x;
+    void *xg_out;
+    const bf16 *g_next;
+    float *ssq_out;
+    int32_t xg_fmt;
+    // SWIGLU: W rows are gate / up interleaved in groups of 32; act [M, F] in format act_fmt (1 or 3)
+    void *act;
+    int32_t act_fmt;
+    // ROPE: the QKV projection; perm != 0: W rows of every head reordered [0..31 | 64..95 | 32..63 | 96..127].
+    // q also leaves its second bf16 term in rope.q_lo when that is not null.  With n_append (dev, may be null) the new
+    // key / value row of every trace b with n_append[b] > 0 is also written to row plens[b] of its paged cache.
+    RopeArgs rope;
+    int32_t perm;
+    void *k_pages, *v_pages;  // this layer's pages
+    const int32_t *table, *plens, *n_append;
+    int32_t max_blocks, n_blocks;
+};
+void dec_gemm_plan(int K, int n_ct, int *S, int *nwg);
+size_t dec_gemm_plane_bytes(int K, int n_ct);      // 0 when the projection needs no partial planes
+hipError_t launch_dec_gemm(const DecGemm &a, int epi, bool f16, hipStream_t s);
+
+struct DecAttn {
+    const bf16 *q, *q_lo;             // [B, Hq, 128]; q_lo may be null
+    const bf16 *ksuf, *vsuf;          // [B, Hkv, 128]: key / value of the new token
+    const bf16 *k_pages, *v_pages;    // this layer's pages [n_blocks, Hkv, 16, 128]
+    const int32_t *table, *plens;
+    int32_t *ctl;                     // control block written by launch_dec_init
+    void *out;                        // [B, Hq * 128] in format out_fmt (1 bf16, 3 half; 2: [B, 2 Hq 128] hi | lo)
+    float *part_o, *part_ml;          // per piece: [8, 128] and [8, 2] fp32
+    int32_t B, Hq, Hkv, G, max_blocks, n_blocks, max_L, out_fmt;
+    float scale_log2;                 // log2(e) / sqrt(head_dim)
+};
+hipError_t launch_dec_init(const int32_t *plens, int B, int max_L, int32_t *ctl, hipStream_t s);
+// n_pieces: sum over traces of ceil((L_b + 1) / DEC_PIECE), from the host copy of the lengths
+hipError_t launch_dec_attn(const DecAttn &a, int n_pieces, hipStream_t s);
+inline size_t dec_attn_part_o_bytes(int64_t n_pieces, int Hkv) { return (size_t)n_pieces * Hkv * DEC_MAX_G * 128 * 4; }
+inline size_t dec_attn_part_ml_bytes(int64_t n_pieces, int Hkv) { return (size_t)n_pieces * Hkv * DEC_MAX_G * 2 * 4; }
+
 // ---- cascade (cascade.hip) ----
 hipError_t launch_cascade_select(const uint8_t *keep, const int32_t *verdict_d, const int32_t *req_start, const int32_t *parent,
                                  int R, int B, const int32_t *cu, const int32_t *plens, int T, uint8_t *open_flag,
