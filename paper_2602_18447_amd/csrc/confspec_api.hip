@@ -129,10 +129,11 @@ size_t dec_plane_bytes(const confspec_model_cfg &c) {
     m = std::max(m, cs::dec_gemm_plane_bytes(c.d_ffn, c.d_model / 16));
     return m;
 }
+// Partial-result records of the step's attention: traces x pieces of the longest trace.
 int64_t dec_pieces(const int32_t *h_prefix_lens, int B) {
-    int64_t n = 0;
-    for (int b = 0; b < B; ++b) n += (std::max(h_prefix_lens[b], 0) + 1 + cs::DEC_PIECE - 1) / cs::DEC_PIECE;
-    return n;
+    int max_L = 0;
+    for (int b = 0; b < B; ++b) max_L = std::max(max_L, h_prefix_lens[b]);
+    return (int64_t)B * (max_L / cs::DEC_PIECE + 1);
 }
 
 // exact (may be null): lay the workspace out for this batch alone instead of for every batch of up to T tokens in B
@@ -243,7 +244,7 @@ WsLayout ws_layout(const confspec_ctx *ctx, int64_t T, int64_t B, const confspec
 // Scratch of the full-vocabulary head for B rows: the last rows of the residual stream, their normalised form (two
 // bf16 terms for a bf16 model), the logits [B, vocab], and the verdict outputs the full-vocabulary confidence needs.
 struct HeadLayout {
-    size_t x, y, logits, v_logits, v_conf, v_verdict, v_accept, total;
+    size_t x, y, logits, v_logits, v_conf, v_verdict, v_accept, part, total;
 };
 HeadLayout head_layout(const confspec_model_cfg &c, int64_t B) {
     HeadLayout h;
@@ -256,6 +257,7 @@ HeadLayout head_layout(const confspec_model_cfg &c, int64_t B) {
     h.v_conf = take((size_t)B * 4);
     h.v_verdict = take((size_t)B * 4);
     h.v_accept = take((size_t)B);
+    h.part = take((size_t)256 * cs::DEC_MAX_ROWS * 4 * 4);   // per-workgroup row statistics of the generation-step head
     h.total = at;
     return h;
 }
@@ -718,7 +720,7 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     const int32_t *last_row = (const int32_t *)(ws + L.last_row);
     if (use_dec) {
         int32_t *ctl = (int32_t *)(ws + L.dec_ctl);
-        HIP_TRY(cs::launch_dec_init(batch->prefix_lens, B, max_L, ctl, s));
+        HIP_TRY(cs::launch_dec_init(ctl, s));
         const size_t layer_bytes = (size_t)kv->n_blocks * c.n_kv_heads * kv->block_size * c.head_dim * eb;
         // The RMSNorm in front of the QKV and gate/up projections: the residual projection before writes x * gain in
         // the operand format and per-row partial sums of squares, the consumer scales its result rows (decode_bf16.hip).
@@ -764,7 +766,8 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
             at.B = B; at.Hq = c.n_q_heads; at.Hkv = c.n_kv_heads; at.G = c.n_q_heads / c.n_kv_heads;
             at.max_blocks = kv->max_blocks_per_seq; at.n_blocks = kv->n_blocks; at.max_L = max_L;
             at.scale_log2 = 1.44269504088896340736f / sqrtf((float)c.head_dim);
-            HIP_TRY(cs::launch_dec_attn(at, (int)dec_np, s));
+            at.max_pieces = max_L / cs::DEC_PIECE + 1;
+            HIP_TRY(cs::launch_dec_attn(at, s));
             HIP_TRY(mark(CONFSPEC_PHASE_O_PROJ));
             cs::DecGemm go = {};
             proj(go, ws + L.attn, qw, wo, qw, d / 16);
@@ -898,6 +901,21 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
         }
         const bool bf = c.dtype == CONFSPEC_DTYPE_BF16;
         HIP_TRY(cs::launch_rmsnorm(c.dtype, xl, w->final_norm, hs + HL.y, B, d, c.rms_eps, bf ? 2 : 1, s));
+        if (use_dec && d <= 64 * cs::DEC_MAX_KT && c.vocab % 16 == 0) {
+            // generation step: the head streams once against the B rows, and every workgroup keeps only the running
+            // (max, arg max, sum of exponentials) of its columns - the [B, vocab] logits are never written
+            cs::DecGemm gh = {};
+            gh.X = (const cs::bf16 *)(hs + HL.y); gh.ldx = 2 * d; gh.W = (const cs::bf16 *)w->lm_head; gh.M = B; gh.K = d;
+            gh.n_ct = c.vocab / 16;
+            cs::dec_gemm_plan(d, gh.n_ct, &gh.S, &gh.nwg);
+            gh.head_part = (float *)(hs + HL.part);
+            HIP_TRY(cs::launch_dec_gemm(gh, cs::DEC_EPI_HEAD, false, s));
+            HIP_TRY(cs::launch_dec_head_final(gh.head_part, gh.nwg, B, want_verdict ? dev_verdict_logits : nullptr, va.n_verdict,
+                                              ex.head->token, ex.head->max_logit, ex.head->lse,
+                                              want_verdict ? ex.head->conf_full : nullptr, s));
+            HIP_TRY(mark(CONFSPEC_PHASE_END));
+            return CONFSPEC_OK;
+        }
         if ((rc = run_gemm(ctx, hs + HL.y, w->lm_head, hs + HL.logits, B, c.vocab, d, cs::EPI_STORE_F32, bf ? 2 : 1, 1, s,
                            bf ? (float *)(ws + L.splitk) : nullptr, bf ? L.splitk_bytes : 0)))
             return rc;

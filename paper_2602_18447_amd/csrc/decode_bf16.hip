@@ -3,14 +3,15 @@
 // read exactly once, and attention has one query row per head.  Such a step is a stream of weights and cached
 // keys / values from HBM; what these kernels are built around is keeping that stream going and touching it once.
 //
-// Projections (dec_gemm_kernel).  A workgroup of 8 wavefronts keeps its k range of all 32 activation rows in LDS
-// (at most 24 k-tiles of 64 = 96 KiB, fetched once per workgroup) and walks a list of 16-column tiles of the weight
-// matrix.  Wavefront w owns the k-tiles w, w + 8, ... of that range: it fetches exactly the activation k-tiles it
-// will multiply, and streams the matching weight k-tiles (16 rows x 128 bytes) through a private ring of three LDS
-// slots filled by direct global -> LDS loads, so the main loop has no workgroup barrier and every wavefront always has
-// up to three weight k-tiles in flight, across tile borders.  Per column tile the 8 partial 32 x 16 products are
-// added in wavefront order through LDS and the epilogue runs on the sum: rotary embedding + q / k / v split (+ the
-// write-back of the new key / value row into the paged cache), SwiGLU, or the residual update.
+// Projections (dec_gemm_kernel).  A workgroup of 8 wavefronts walks a list of 16-column tiles of the weight matrix
+// over one k range of at most 24 k-tiles of 64.  Wavefront w owns the k-tiles w, w + 8, w + 16 of that range: it
+// fetches exactly the activation k-tiles it will multiply (32 rows; kept in LDS, or in registers as MFMA operands
+// for the long stream of the language-model head), and streams the matching weight k-tiles (16 rows x 128 bytes)
+// through a private ring of LDS slots filled by direct global -> LDS loads, so the main loop has no workgroup barrier
+// and every wavefront always has its ring's worth of weight k-tiles in flight, across tile borders.
+// Per column tile the 8 partial 32 x 16 products are added in wavefront order through LDS and the epilogue runs on
+// the sum: rotary embedding + q / k / v split (+ the write-back of the new key / value row into the paged cache),
+// SwiGLU, the residual update, or the running arg max / log-sum-exp of the language-model head.
 // A k range longer than 24 k-tiles is cut into slices that run as separate workgroups; they leave fp32 partial planes,
 // and the workgroup that finishes a column group last (a counter per group) adds the planes in slice order and runs
 // the epilogue - the order of the additions is fixed, whoever performs them, so results are bit-identical from run to
@@ -47,11 +48,19 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 namespace {
 
-constexpr int DEC_THREADS = 512, DEC_WAVES = 8, DEC_NSLOT = 3;
-constexpr int DEC_XT = 4096;                 // one activation k-tile in LDS: 32 rows x 128 bytes
-constexpr int DEC_WT = 2048;                 // one weight k-tile: 16 rows x 128 bytes
-constexpr int DEC_RING = DEC_WAVES * DEC_NSLOT * DEC_WT;   // 48 KiB
+constexpr int DEC_THREADS = 512, DEC_WAVES = 8;
+constexpr int DEC_KW = 3;                    // k-tiles a wavefront owns at most (24 per slice / 8 wavefronts)
+constexpr int DEC_XT = 4096;                 // one activation k-tile: 32 rows x 128 bytes = two ring slots
+constexpr int DEC_WT = 2048;                 // one weight k-tile: 16 rows x 128 bytes = one ring slot
 constexpr int DEC_RED = DEC_WAVES * 32 * 16 * 4;           // 16 KiB: the 8 partial products of a column tile
+// Two layouts of the 160 KiB.  Resident activations (XREG = false): the slice's activation k-tiles (up to 96 KiB) stay
+// in LDS and every wavefront has a ring of 3 weight slots; the activations and the first weight k-tiles are requested
+// together, so the stream starts with the kernel.  Activations in registers (XREG = true): a wavefront's share of the
+// rows goes through its ring once into registers and the ring has 8 slots (16 KiB in flight per wavefront); the
+// stream starts one L2 round trip later, which pays for long streams and is what lets two-term activations fit.
+template <bool XREG> constexpr int dec_nslot() { return XREG ? 8 : 3; }
+template <bool XREG> constexpr int dec_ring_bytes() { return DEC_WAVES * dec_nslot<XREG>() * DEC_WT; }
+static_assert(DEC_MAX_KT == DEC_KW * DEC_WAVES && 2 * DEC_KW <= dec_nslot<true>() - 2, "activation k-tiles are staged in the ring");
 
 template <bool F16>
 __device__ inline f32x4 mma16(bf16x8 a, bf16x8 b, f32x4 c) {
@@ -100,25 +109,15 @@ __device__ inline unsigned short to_fmt(float v, int fmt) {   // fmt 3: IEEE hal
 
 }  // namespace
 
-// ---- control block of a step: piece offsets of the attention kernel and the counters -------------------------------
-// ctl[0 .. B]            first piece of every trace (pieces of 128 keys over the L_b cached keys + the new one)
-// ctl[DEC_CTL_ATTN ..]   one arrival counter per (trace, kv head)
-// ctl[DEC_CTL_TILE ..]   one arrival counter per column group of a sliced projection
-__global__ void dec_init_kernel(const int32_t *__restrict__ plens, int B, int max_L, int32_t *__restrict__ ctl, int n_ctl) {
-    __shared__ int32_t np[DEC_MAX_ROWS];
-    int tid = threadIdx.x;
-    if (tid < B) np[tid] = (min(max(plens[tid], 0), max_L) + 1 + DEC_PIECE - 1) / DEC_PIECE;
-    __syncthreads();
-    if (tid == 0) {
-        int acc = 0;
-        for (int b = 0; b < B; ++b) { ctl[b] = acc; acc += np[b]; }
-        ctl[B] = acc;
-    }
-    for (int i = DEC_CTL_ATTN + tid; i < n_ctl; i += blockDim.x) ctl[i] = 0;
+// ---- control block of a step: the arrival counters, zero at the start of every step -------------------------------
+// ctl[DEC_CTL_ATTN ..]   one per (trace, kv head): pieces of the attention kernel
+// ctl[DEC_CTL_TILE ..]   one per column group of a sliced projection
+__global__ void dec_init_kernel(int32_t *__restrict__ ctl, int n_ctl) {
+    for (int i = threadIdx.x; i < n_ctl; i += blockDim.x) ctl[i] = 0;
 }
 
-hipError_t launch_dec_init(const int32_t *plens, int B, int max_L, int32_t *ctl, hipStream_t s) {
-    dec_init_kernel<<<1, 256, 0, s>>>(plens, B, max_L, ctl, DEC_CTL_INTS);
+hipError_t launch_dec_init(int32_t *ctl, hipStream_t s) {
+    dec_init_kernel<<<1, 256, 0, s>>>(ctl, DEC_CTL_INTS);
     return hipGetLastError();
 }
 
@@ -201,53 +200,71 @@ __device__ inline void dec_epilogue(const DecGemm &a, int t, int row, int c, flo
     }
 }
 
-template <int EPI, bool F16, bool NORMX>
+// Running (max, first index of the max, sum of exp(z - max)) of a row of logits.
+struct DecHeadAcc {
+    float m;
+    int idx;
+    float s;
+};
+__device__ inline DecHeadAcc dec_head_merge(DecHeadAcc a, DecHeadAcc b) {   // lowest index on equal maxima
+    DecHeadAcc r;
+    const bool a_first = a.m > b.m || (a.m == b.m && a.idx < b.idx);
+    r.m = a_first ? a.m : b.m;
+    r.idx = a_first ? a.idx : b.idx;
+    r.s = (a.m == -INFINITY ? 0.f : a.s * __expf(a.m - r.m)) + (b.m == -INFINITY ? 0.f : b.s * __expf(b.m - r.m));
+    return r;
+}
+
+template <int EPI, bool F16, bool NORMX, int TERMS, bool XREG>
 __global__ __launch_bounds__(DEC_THREADS) void dec_gemm_kernel(DecGemm a) {
-    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];   // all 160 KiB when a slice has 24 k-tiles
+    static_assert(XREG || TERMS == 1, "two-term activations only fit in registers");
+    constexpr int NSLOT = dec_nslot<XREG>();
+    constexpr int SLOT0 = XREG ? 2 * DEC_KW : 0;                        // slot of unit 0
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int s = blockIdx.x / a.nwg, j = blockIdx.x - s * a.nwg;       // k slice, column group
     const int nk = a.K >> 6;
     const int kt0 = (int)((long)s * nk / a.S), kt1 = (int)((long)(s + 1) * nk / a.S);
     const int nks = kt1 - kt0;                                          // k-tiles of this slice (<= 24)
-    const int nkw = nks > wave ? (nks - wave + DEC_WAVES - 1) / DEC_WAVES : 0;   // ... owned by this wavefront
+    const int nkw = nks > wave ? (nks - wave + DEC_WAVES - 1) / DEC_WAVES : 0;   // ... owned by this wavefront (<= 3)
     const int n_my = (a.n_ct - j + a.nwg - 1) / a.nwg;                  // column tiles j, j + nwg, ...
     const int total = n_my * nkw;                                       // (tile, k-tile) units of this wavefront
 
-    unsigned char *xs = smem;                                           // [nks][32 rows][128 B], swizzled
-    const int x_bytes = nks * DEC_XT;
-    unsigned char *ring = smem + x_bytes + wave * DEC_NSLOT * DEC_WT;   // this wavefront's weight slots
-    float *red = reinterpret_cast<float *>(smem + x_bytes + DEC_RING);
+    // LDS: [resident activations: nks k-tiles] [rings: 8 wavefronts x NSLOT slots] [red]
+    const int x_bytes = XREG ? 0 : nks * DEC_XT;
+    unsigned char *xs = smem;
+    unsigned char *ring = smem + x_bytes + wave * NSLOT * DEC_WT;       // this wavefront's slots
+    float *red = reinterpret_cast<float *>(smem + x_bytes + dec_ring_bytes<XREG>());
     volatile int *s_last = reinterpret_cast<volatile int *>(red);       // arrival flag (after the main loop, red is free)
     const unsigned lds0 = (unsigned)(size_t)(CS_LDS_AS unsigned char *)smem;
+    const unsigned ring0 = (unsigned)(size_t)(CS_LDS_AS unsigned char *)ring;
 
     // Direct-load roles: one instruction fills 8 rows x 128 bytes; lane l sits at row l / 8, 16-byte slot l % 8 and
     // fetches the k-vector that the swizzle (slot = vector ^ ((row >> 1) & 7), row counted inside the tile) puts there.
     const int lr = lane >> 3, lslot = lane & 7;
-    // activations: this wavefront's k-tiles, 4 instructions each (rows past M repeat the last row; never stored)
-    for (int i = 0; i < nkw; ++i) {
-        int q = wave + DEC_WAVES * i;
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            int row = 8 * r4 + lr;
-            int vec = lslot ^ ((row >> 1) & 7);
-            const bf16 *src = a.X + (size_t)min(row, a.M - 1) * a.ldx + (size_t)(kt0 + q) * 64 + vec * 8;
-            dma16(src, lds0 + q * DEC_XT + r4 * 1024);
-        }
-    }
+    // Unit u = (column tile u / nkw, the wavefront's k-tile u % nkw) goes through slot (SLOT0 + u) % NSLOT.
     auto issue_unit = [&](int u) {
         int ti = u / nkw, i = u - ti * nkw;
         int t = j + ti * a.nwg, kt = kt0 + wave + DEC_WAVES * i;
         int rA, rB;
         dec_tile_rows(EPI, t, a.perm, rA, rB);
-        unsigned dst = lds0 + x_bytes + (wave * DEC_NSLOT + u % DEC_NSLOT) * DEC_WT;
+        unsigned dst = ring0 + ((u + SLOT0) % NSLOT) * DEC_WT;
         int vecA = lslot ^ ((lr >> 1) & 7), vecB = lslot ^ (((8 + lr) >> 1) & 7);
         dma16(a.W + (size_t)(rA + lr) * a.K + (size_t)kt * 64 + vecA * 8, dst);
         dma16(a.W + (size_t)(rB + lr) * a.K + (size_t)kt * 64 + vecB * 8, dst + 1024);
     };
+    // activation k-tile i of this wavefront (term: 0 = hi, 1 = lo half of a two-term row) to LDS address dst
+    auto issue_x = [&](int i, int term, unsigned dst) {
 #pragma unroll
-    for (int u = 0; u < DEC_NSLOT; ++u)
-        if (u < total) issue_unit(u);
+        for (int r4 = 0; r4 < 4; ++r4) {
+            int row = 8 * r4 + lr;
+            int vec = lslot ^ ((row >> 1) & 7);
+            const bf16 *src = a.X + (size_t)min(row, a.M - 1) * a.ldx + (size_t)term * a.K +
+                              (size_t)(kt0 + wave + DEC_WAVES * i) * 64 + vec * 8;      // rows past M repeat the last row
+            dma16(src, dst + r4 * 1024);
+        }
+    };
     // fragment addresses: 16 x 16 x 32 MFMA, lane l supplies row l % 16 and the k-vector l / 16 of a 32-wide k-step
     const int fr = lane & 15, fg = lane >> 4;
     int w_off[2], x_off[2][2];
@@ -260,6 +277,42 @@ __global__ __launch_bounds__(DEC_THREADS) void dec_gemm_kernel(DecGemm a) {
             x_off[ks][rb] = row * 128 + (((4 * ks + fg) ^ ((row >> 1) & 7)) << 4);
         }
     }
+    bf16x8 xf[TERMS][DEC_KW][2][2];                                     // XREG: the wavefront's activations as operands
+    if constexpr (XREG) {
+        // through slots 0..5 into registers, once per term; the first two weight units are on their way in slots 6, 7
+#pragma unroll
+        for (int term = 0; term < TERMS; ++term) {
+#pragma unroll
+            for (int i = 0; i < DEC_KW; ++i)
+                if (i < nkw) issue_x(i, term, ring0 + i * DEC_XT);
+            if (term == 0) {
+                if (0 < total) issue_unit(0);
+                if (1 < total) issue_unit(1);
+            }
+            // the staged k-tiles were issued before the weight units of this term (if any): they land first
+            if (term == 0 && total >= 2) dec_wait_vm<4>();
+            else if (term == 0 && total == 1) dec_wait_vm<2>();
+            else dec_wait_vm<0>();
+#pragma unroll
+            for (int i = 0; i < DEC_KW; ++i)
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int rb = 0; rb < 2; ++rb)
+                        xf[term][i][ks][rb] = i < nkw ? *reinterpret_cast<const bf16x8 *>(ring + i * DEC_XT + x_off[ks][rb]) : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            dec_wait_lds();
+        }
+#pragma unroll
+        for (int u = 2; u < NSLOT; ++u)
+            if (u < total) issue_unit(u);
+    } else {
+        // resident: the wavefront's k-tiles into their places, then the first weight units (in order: the activations
+        // have landed whenever a unit has)
+        for (int i = 0; i < nkw; ++i) issue_x(i, 0, lds0 + (wave + DEC_WAVES * i) * DEC_XT);
+#pragma unroll
+        for (int u = 0; u < NSLOT; ++u)
+            if (u < total) issue_unit(u);
+    }
 
     const int row = tid >> 4, c = tid & 15;                             // this thread's element of a 32 x 16 tile
     // NORMX: the operand is x * g without the 1 / rms factor of its row; the factor comes from the partial sums of
@@ -271,31 +324,48 @@ __global__ __launch_bounds__(DEC_THREADS) void dec_gemm_kernel(DecGemm a) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) sqv[e] = c + 16 * e < a.ssq_n ? a.ssq_in[(c + 16 * e) * DEC_MAX_ROWS + min(row, a.M - 1)] : 0.f;
     }
+    DecHeadAcc hacc = {-INFINITY, 0x7fffffff, 0.f};                     // HEAD: this thread's columns so far
     const size_t plane = (size_t)DEC_MAX_ROWS * a.n_ct * 16;
     int u = 0;
     for (int ti = 0; ti < n_my; ++ti) {
         const int t = j + ti * a.nwg;
         f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-        for (int i = 0; i < nkw; ++i, ++u) {
-            int after = min(DEC_NSLOT - 1, total - 1 - u);              // units issued after this one
-            if (after >= 2) dec_wait_vm<4>();
-            else if (after == 1) dec_wait_vm<2>();
-            else dec_wait_vm<0>();
-            const unsigned char *wsl = ring + (u % DEC_NSLOT) * DEC_WT;
-            const unsigned char *xt = xs + (wave + DEC_WAVES * i) * DEC_XT;
-            bf16x8 wf[2], xf[2][2];
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                wf[ks] = *reinterpret_cast<const bf16x8 *>(wsl + w_off[ks]);
-                xf[ks][0] = *reinterpret_cast<const bf16x8 *>(xt + x_off[ks][0]);
-                xf[ks][1] = *reinterpret_cast<const bf16x8 *>(xt + x_off[ks][1]);
-            }
-            dec_wait_lds();                                             // the slot is in registers: refill it
-            if (u + DEC_NSLOT < total) issue_unit(u + DEC_NSLOT);
+        for (int i = 0; i < DEC_KW; ++i) {
+            if (i < nkw) {
+                const int after = min(NSLOT - 1, total - 1 - u);        // units issued after this one
+                switch (after) {
+                    case 7: dec_wait_vm<14>(); break;
+                    case 6: dec_wait_vm<12>(); break;
+                    case 5: dec_wait_vm<10>(); break;
+                    case 4: dec_wait_vm<8>(); break;
+                    case 3: dec_wait_vm<6>(); break;
+                    case 2: dec_wait_vm<4>(); break;
+                    case 1: dec_wait_vm<2>(); break;
+                    default: dec_wait_vm<0>(); break;
+                }
+                const unsigned char *wsl = ring + ((u + SLOT0) % NSLOT) * DEC_WT;
+                bf16x8 wf[2];
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                acc[0] = mma16<F16>(xf[ks][0], wf[ks], acc[0]);
-                acc[1] = mma16<F16>(xf[ks][1], wf[ks], acc[1]);
+                for (int ks = 0; ks < 2; ++ks) wf[ks] = *reinterpret_cast<const bf16x8 *>(wsl + w_off[ks]);
+                if constexpr (!XREG) {
+                    const unsigned char *xt = xs + (wave + DEC_WAVES * i) * DEC_XT;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        xf[0][i][ks][0] = *reinterpret_cast<const bf16x8 *>(xt + x_off[ks][0]);
+                        xf[0][i][ks][1] = *reinterpret_cast<const bf16x8 *>(xt + x_off[ks][1]);
+                    }
+                }
+                dec_wait_lds();                                         // the slot is in registers: refill it
+                if (u + NSLOT < total) issue_unit(u + NSLOT);
+#pragma unroll
+                for (int term = 0; term < TERMS; ++term)
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        acc[0] = mma16<F16>(xf[term][i][ks][0], wf[ks], acc[0]);
+                        acc[1] = mma16<F16>(xf[term][i][ks][1], wf[ks], acc[1]);
+                    }
+                ++u;
             }
         }
         // accumulator layout: column lane % 16, rows 16 rb + 4 (lane / 16) + e
@@ -320,8 +390,35 @@ __global__ __launch_bounds__(DEC_THREADS) void dec_gemm_kernel(DecGemm a) {
                 rinv = 1.0f / sqrtf(sq / (float)a.K + a.eps);
             }
         }
-        if (a.S > 1) xwg_store(a.planes + (size_t)s * plane + (size_t)row * (a.n_ct * 16) + t * 16 + c, v);
-        else dec_epilogue<EPI>(a, t, row, c, v * rinv);
+        if constexpr (EPI == DEC_EPI_HEAD) {
+            // logit of (row, vocabulary entry 16 t + c): into the thread's running statistics (its entries ascend)
+            const int idx = 16 * t + c;
+            if (v > hacc.m) {
+                hacc.s = (hacc.m == -INFINITY ? 0.f : hacc.s * __expf(hacc.m - v)) + 1.0f;
+                hacc.m = v;
+                hacc.idx = idx;
+            } else {
+                hacc.s += __expf(v - hacc.m);
+            }
+        } else {
+            if (a.S > 1) xwg_store(a.planes + (size_t)s * plane + (size_t)row * (a.n_ct * 16) + t * 16 + c, v);
+            else dec_epilogue<EPI>(a, t, row, c, v * rinv);
+        }
+    }
+    if constexpr (EPI == DEC_EPI_HEAD) {
+        // the 16 threads of a row, then one record per (workgroup, row) for the kernel that finishes the rows
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) {
+            DecHeadAcc o = {__shfl_xor(hacc.m, off), __shfl_xor(hacc.idx, off), __shfl_xor(hacc.s, off)};
+            hacc = dec_head_merge(hacc, o);
+        }
+        if (c == 0) {
+            float *rec = a.head_part + ((size_t)j * DEC_MAX_ROWS + row) * 4;
+            rec[0] = hacc.m;
+            rec[1] = __int_as_float(hacc.idx);
+            rec[2] = hacc.s;
+        }
+        return;
     }
     if (a.S > 1) {
         // the slices of column group j: the last one to arrive adds the planes in slice order
@@ -340,6 +437,41 @@ __global__ __launch_bounds__(DEC_THREADS) void dec_gemm_kernel(DecGemm a) {
             dec_epilogue<EPI>(a, t, row, c, v * rinv);
         }
     }
+}
+
+// The rows of the language-model head: the records of all workgroups of dec_gemm_kernel<DEC_EPI_HEAD> merged in
+// workgroup order per row (one wavefront per row).
+__global__ __launch_bounds__(64) void dec_head_final_kernel(const float *__restrict__ part, int nwg, const float *__restrict__ verdict_logits,
+                                                             int n_verdict, int32_t *__restrict__ token, float *__restrict__ max_logit,
+                                                             float *__restrict__ lse, float *__restrict__ conf_full) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    DecHeadAcc acc = {-INFINITY, 0x7fffffff, 0.f};
+    for (int g = lane; g < nwg; g += 64) {
+        const float *rec = part + ((size_t)g * DEC_MAX_ROWS + b) * 4;
+        acc = dec_head_merge(acc, DecHeadAcc{rec[0], __float_as_int(rec[1]), rec[2]});
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        DecHeadAcc o = {__shfl_xor(acc.m, off), __shfl_xor(acc.idx, off), __shfl_xor(acc.s, off)};
+        acc = dec_head_merge(acc, o);
+    }
+    if (lane == 0) {
+        float l = acc.m + logf(acc.s);
+        token[b] = acc.idx;
+        max_logit[b] = acc.m;
+        lse[b] = l;
+        if (conf_full && verdict_logits) {
+            float zv = verdict_logits[(size_t)b * n_verdict];
+            for (int v = 1; v < n_verdict; ++v) zv = fmaxf(zv, verdict_logits[(size_t)b * n_verdict + v]);
+            conf_full[b] = expf(zv - l);
+        }
+    }
+}
+
+hipError_t launch_dec_head_final(const float *part, int nwg, int B, const float *verdict_logits, int n_verdict, int32_t *token,
+                                 float *max_logit, float *lse, float *conf_full, hipStream_t s) {
+    dec_head_final_kernel<<<B, 64, 0, s>>>(part, nwg, verdict_logits, n_verdict, token, max_logit, lse, conf_full);
+    return hipGetLastError();
 }
 
 // Slices and workgroups of a projection.  A k range that fits one slice is never cut (no partial planes, no counters);
@@ -371,15 +503,14 @@ size_t dec_gemm_plane_bytes(int K, int n_ct) {
     return S > 1 ? (size_t)S * DEC_MAX_ROWS * n_ct * 16 * 4 : 0;
 }
 
-template <int EPI, bool F16, bool NORMX>
+template <int EPI, bool F16, bool NORMX, int TERMS, bool XREG = false>
 static hipError_t launch_dec_gemm_inst(const DecGemm &a, hipStream_t s) {
     static std::atomic<uint32_t> attr_done{0};
-    auto kern = dec_gemm_kernel<EPI, F16, NORMX>;
-    constexpr int max_smem = DEC_MAX_KT * DEC_XT + DEC_RING + DEC_RED;   // 160 KiB
+    auto kern = dec_gemm_kernel<EPI, F16, NORMX, TERMS, XREG>;
+    constexpr int max_smem = (XREG ? 0 : DEC_MAX_KT * DEC_XT) + dec_ring_bytes<XREG>() + DEC_RED;     // 160 / 144 KiB
     if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(kern), max_smem); e != hipSuccess) return e;
     const int nk = a.K / 64;
-    const int nks = (nk + a.S - 1) / a.S;
-    const int smem = nks * DEC_XT + DEC_RING + DEC_RED;
+    const int smem = (XREG ? 0 : (nk + a.S - 1) / a.S * DEC_XT) + dec_ring_bytes<XREG>() + DEC_RED;
     kern<<<a.S * a.nwg, DEC_THREADS, smem, s>>>(a);
     return hipGetLastError();
 }
@@ -393,14 +524,17 @@ hipError_t launch_dec_gemm(const DecGemm &a, int epi, bool f16, hipStream_t s) {
     if (!a.X || (nx && a.ssq_n < 1)) return hipErrorInvalidValue;
     switch (epi) {
         case DEC_EPI_ROPE:
-            if (nx) return f16 ? launch_dec_gemm_inst<DEC_EPI_ROPE, true, true>(a, s) : launch_dec_gemm_inst<DEC_EPI_ROPE, false, true>(a, s);
-            return f16 ? launch_dec_gemm_inst<DEC_EPI_ROPE, true, false>(a, s) : launch_dec_gemm_inst<DEC_EPI_ROPE, false, false>(a, s);
+            if (nx) return f16 ? launch_dec_gemm_inst<DEC_EPI_ROPE, true, true, 1>(a, s) : launch_dec_gemm_inst<DEC_EPI_ROPE, false, true, 1>(a, s);
+            return f16 ? launch_dec_gemm_inst<DEC_EPI_ROPE, true, false, 1>(a, s) : launch_dec_gemm_inst<DEC_EPI_ROPE, false, false, 1>(a, s);
         case DEC_EPI_SWIGLU:
-            if (nx) return f16 ? launch_dec_gemm_inst<DEC_EPI_SWIGLU, true, true>(a, s) : launch_dec_gemm_inst<DEC_EPI_SWIGLU, false, true>(a, s);
-            return f16 ? launch_dec_gemm_inst<DEC_EPI_SWIGLU, true, false>(a, s) : launch_dec_gemm_inst<DEC_EPI_SWIGLU, false, false>(a, s);
+            if (nx) return f16 ? launch_dec_gemm_inst<DEC_EPI_SWIGLU, true, true, 1>(a, s) : launch_dec_gemm_inst<DEC_EPI_SWIGLU, false, true, 1>(a, s);
+            return f16 ? launch_dec_gemm_inst<DEC_EPI_SWIGLU, true, false, 1>(a, s) : launch_dec_gemm_inst<DEC_EPI_SWIGLU, false, false, 1>(a, s);
         case DEC_EPI_RESID:
             if (nx) return hipErrorInvalidValue;
-            return f16 ? launch_dec_gemm_inst<DEC_EPI_RESID, true, false>(a, s) : launch_dec_gemm_inst<DEC_EPI_RESID, false, false>(a, s);
+            return f16 ? launch_dec_gemm_inst<DEC_EPI_RESID, true, false, 1>(a, s) : launch_dec_gemm_inst<DEC_EPI_RESID, false, false, 1>(a, s);
+        case DEC_EPI_HEAD:      // two-term bf16 rows [M, 2 K] against the bf16 head, one k slice
+            if (nx || f16 || a.S != 1 || !a.head_part) return hipErrorInvalidValue;
+            return launch_dec_gemm_inst<DEC_EPI_HEAD, false, false, 2, true>(a, s);
     }
     return hipErrorInvalidValue;
 }
@@ -415,8 +549,8 @@ hipError_t launch_dec_gemm(const DecGemm &a, int epi, bool f16, hipStream_t s) {
 // fetches the matching global vector.
 // Transposing reads (ds_read_b64_tr_b16): in a group of 16 lanes, lane i supplies the address of 4 consecutive 16-bit
 // elements and receives element i % 4 of what lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4 addressed.
-// The last piece of a trace is short (with L a multiple of 256 it holds the new token only); those pieces are the
-// first workgroups of the grid, so they finish while the full pieces are still streaming instead of after them.
+// The last piece of a trace is short (with L a multiple of 256 it holds the new token only); the grid starts with the
+// last pieces, so they finish while the full pieces are still streaming instead of after them.
 constexpr int DEC_ATTN_THREADS = 512, DEC_ATTN_WAVES = 8;
 constexpr int DEC_ATTN_WAVE_LDS = 8192;
 constexpr int DEC_ATTN_SMEM = DEC_ATTN_WAVES * DEC_ATTN_WAVE_LDS;
@@ -427,24 +561,14 @@ __global__ __launch_bounds__(DEC_ATTN_THREADS, 2) void dec_attn_kernel(DecAttn a
     __shared__ volatile int s_last;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int h = blockIdx.x % a.Hkv, wi = blockIdx.x / a.Hkv;
-    // lane l holds the first piece of trace l (B <= 32): one load serves the whole search
-    const int first = lane <= a.B ? a.ctl[lane] : 0x7fffffff;
-    const int n_total = __builtin_amdgcn_readlane(first, a.B);
-    if (wi >= n_total) return;                                          // uniform
-    int b, p;
-    if (wi < a.B) {                                                     // the last piece of trace wi
-        b = wi;
-        p = __builtin_amdgcn_readlane(first, b + 1) - __builtin_amdgcn_readlane(first, b) - 1;
-    } else {                                                            // the other pieces, in trace order
-        const int r = wi - a.B;                                         // first[l] - l: pieces before trace l, last ones left out
-        b = __popcll(__ballot(lane < a.B && first - lane <= r)) - 1;
-        p = r - (__builtin_amdgcn_readlane(first, b) - b);
-    }
-    const int p0_ = __builtin_amdgcn_readlane(first, b);
-    const int n_p = __builtin_amdgcn_readlane(first, b + 1) - p0_;
-    const int pi = p0_ + p;                                             // index of the piece's partial results
+    // grid: x = (piece, kv head), pieces from the last one of the longest trace down; y = trace.  Everything a
+    // workgroup needs to find its keys follows from its indices and one load of the trace's length.
+    const int h = blockIdx.x % a.Hkv, b = blockIdx.y;
+    const int p = a.max_pieces - 1 - blockIdx.x / a.Hkv;
     const int L = min(max(a.plens[b], 0), a.max_L);                     // keys 0 .. L-1 are cached, key L is the new token
+    const int n_p = L / DEC_PIECE + 1;                                  // pieces over the L + 1 keys
+    if (p >= n_p) return;                                               // uniform: a shorter trace
+    const int pi = b * a.max_pieces + p;                                // index of the piece's partial results
     const int G = a.G;
     const int key0 = DEC_PIECE * p + 32 * wave;                         // this wavefront's 32 keys
     const bool active = key0 <= L;                                      // wave-uniform
@@ -607,7 +731,7 @@ __global__ __launch_bounds__(DEC_ATTN_THREADS, 2) void dec_attn_kernel(DecAttn a
     if (!xwg_arrive_last(cnt, n_p, &s_last, tid)) return;
     // maxima and sums of all pieces into LDS (every thread needs them), then the weighted sums, 16 loads in flight
     float *ml = reinterpret_cast<float *>(smem);                        // [n_p][8][2]
-    const size_t item0 = (size_t)p0_ * a.Hkv + h;
+    const size_t item0 = (size_t)b * a.max_pieces * a.Hkv + h;
     const int n_ml = min(n_p, DEC_ATTN_SMEM / (DEC_MAX_G * 2 * 4));     // pieces whose (max, sum) fit LDS: 1024
     for (int i = tid; i < n_ml * DEC_MAX_G * 2; i += DEC_ATTN_THREADS) {
         int pp = i / (DEC_MAX_G * 2), r = i - pp * (DEC_MAX_G * 2);
@@ -636,15 +760,15 @@ __global__ __launch_bounds__(DEC_ATTN_THREADS, 2) void dec_attn_kernel(DecAttn a
     }
 }
 
-// n_pieces: all pieces of all traces; the longest trace must not have more pieces than the merge can stage in LDS
-hipError_t launch_dec_attn(const DecAttn &a, int n_pieces, hipStream_t s) {
+// a.max_pieces: pieces of the longest trace, max_L / DEC_PIECE + 1 (no more than the merge can stage in LDS)
+hipError_t launch_dec_attn(const DecAttn &a, hipStream_t s) {
     if (a.B < 1 || a.B > DEC_MAX_ROWS || a.G < 1 || a.G > DEC_MAX_G || a.Hkv < 1 || a.B * a.Hkv > DEC_CTL_TILE - DEC_CTL_ATTN ||
-        n_pieces < a.B || a.max_L / DEC_PIECE + 1 > DEC_ATTN_SMEM / (DEC_MAX_G * 2 * 4))
+        a.max_pieces != a.max_L / DEC_PIECE + 1 || a.max_pieces > DEC_ATTN_SMEM / (DEC_MAX_G * 2 * 4))
         return hipErrorInvalidValue;
     static std::atomic<uint32_t> attr_done{0};
     if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(dec_attn_kernel), DEC_ATTN_SMEM); e != hipSuccess)
         return e;
-    dec_attn_kernel<<<n_pieces * a.Hkv, DEC_ATTN_THREADS, DEC_ATTN_SMEM, s>>>(a);
+    dec_attn_kernel<<<dim3(a.max_pieces * a.Hkv, a.B), DEC_ATTN_THREADS, DEC_ATTN_SMEM, s>>>(a);
     return hipGetLastError();
 }
 

@@ -176,11 +176,11 @@ constexpr int DEC_MAX_ROWS = 32;     // traces of a step the decode-shaped kerne
 constexpr int DEC_PIECE = 256;       // keys per attention workgroup
 constexpr int DEC_MAX_G = 8;         // q heads per kv head
 constexpr int DEC_MAX_KT = 24;       // k-tiles (of 64) of one k slice of a projection: 96 KiB of activations in LDS
-// control block (int32): piece offsets [0 .. B], then the arrival counters
-constexpr int DEC_CTL_ATTN = 64;                         // + trace * Hkv + kv head
+// control block (int32): the arrival counters
+constexpr int DEC_CTL_ATTN = 0;                          // + trace * Hkv + kv head
 constexpr int DEC_CTL_TILE = DEC_CTL_ATTN + 1024;        // + column group of a sliced projection (<= 256)
 constexpr int DEC_CTL_INTS = DEC_CTL_TILE + 256;
-enum DecEpilogue : int { DEC_EPI_ROPE = 0, DEC_EPI_RESID = 1, DEC_EPI_SWIGLU = 2 };
+enum DecEpilogue : int { DEC_EPI_ROPE = 0, DEC_EPI_RESID = 1, DEC_EPI_SWIGLU = 2, DEC_EPI_HEAD = 3 };
 
 // One projection of a step: out = X[M, K] . W[N, K]^T, M <= 32, K % 64 == 0, N % 16 == 0, then the epilogue.
 struct DecGemm {
@@ -208,6 +208,9 @@ struct DecGemm {
     // SWIGLU: W rows are gate / up interleaved in groups of 32; act [M, F] in format act_fmt (1 or 3)
     void *act;
     int32_t act_fmt;
+    // HEAD: X is [M, 2 K] two-term bf16 (hi | lo), W the [vocab, K] head; the logits are never stored: every workgroup
+    // leaves (max, index of the first max, sum of exp(z - max)) of its columns per row in head_part [nwg, 32, 4] fp32
+    float *head_part;
     // ROPE: the QKV projection; perm != 0: W rows of every head reordered [0..31 | 64..95 | 32..63 | 96..127].
     // q also leaves its second bf16 term in rope.q_lo when that is not null.  With n_append (dev, may be null) the new
     // key / value row of every trace b with n_append[b] > 0 is also written to row plens[b] of its paged cache.
@@ -220,21 +223,24 @@ struct DecGemm {
 void dec_gemm_plan(int K, int n_ct, int *S, int *nwg);
 size_t dec_gemm_plane_bytes(int K, int n_ct);      // 0 when the projection needs no partial planes
 hipError_t launch_dec_gemm(const DecGemm &a, int epi, bool f16, hipStream_t s);
+// token / max logit / log-sum-exp (and conf_full, with verdict logits) of B rows from the nwg records per row
+hipError_t launch_dec_head_final(const float *part, int nwg, int B, const float *verdict_logits, int n_verdict, int32_t *token,
+                                 float *max_logit, float *lse, float *conf_full, hipStream_t s);
 
 struct DecAttn {
     const bf16 *q, *q_lo;             // [B, Hq, 128]; q_lo may be null
     const bf16 *ksuf, *vsuf;          // [B, Hkv, 128]: key / value of the new token
     const bf16 *k_pages, *v_pages;    // this layer's pages [n_blocks, Hkv, 16, 128]
     const int32_t *table, *plens;
-    int32_t *ctl;                     // control block written by launch_dec_init
+    int32_t *ctl;                     // control block (launch_dec_init)
     void *out;                        // [B, Hq * 128] in format out_fmt (1 bf16, 3 half; 2: [B, 2 Hq 128] hi | lo)
-    float *part_o, *part_ml;          // per piece: [8, 128] and [8, 2] fp32
+    float *part_o, *part_ml;          // per (trace, piece, kv head): [8, 128] and [8, 2] fp32; B * max_pieces * Hkv of them
     int32_t B, Hq, Hkv, G, max_blocks, n_blocks, max_L, out_fmt;
+    int32_t max_pieces;               // pieces of the longest trace: max_L / DEC_PIECE + 1
     float scale_log2;                 // log2(e) / sqrt(head_dim)
 };
-hipError_t launch_dec_init(const int32_t *plens, int B, int max_L, int32_t *ctl, hipStream_t s);
-// n_pieces: sum over traces of ceil((L_b + 1) / DEC_PIECE), from the host copy of the lengths
-hipError_t launch_dec_attn(const DecAttn &a, int n_pieces, hipStream_t s);
+hipError_t launch_dec_init(int32_t *ctl, hipStream_t s);
+hipError_t launch_dec_attn(const DecAttn &a, hipStream_t s);
 inline size_t dec_attn_part_o_bytes(int64_t n_pieces, int Hkv) { return (size_t)n_pieces * Hkv * DEC_MAX_G * 128 * 4; }
 inline size_t dec_attn_part_ml_bytes(int64_t n_pieces, int Hkv) { return (size_t)n_pieces * Hkv * DEC_MAX_G * 2 * 4; }
 
