@@ -404,7 +404,12 @@ def _optional_legs(args, st, dev):
         kvbytes = int(sum(wl.prefix_lens)) * m.n_layers * 2 * m.n_kv_heads * m.head_dim * weights.lm_head.element_size()
         info = dict(steps=nst, ms_per_step=round(dt / nst * 1e3, 4), tokens_per_s=round(wl.B * nst / dt, 1),
                     launch="eager", algorithmic_bytes_per_step=wbytes + kvbytes,
-                    achieved_TBps=round((wbytes + kvbytes) / (dt / nst) / 1e12, 3))
+                    achieved_TBps=round((wbytes + kvbytes) / (dt / nst) / 1e12, 3),
+                    # the step's own kernels (one token per trace, B <= 32): per layer QKV + rotation + cache write,
+                    # attention, output projection, gate/up + SwiGLU, down projection; around them position / rotary
+                    # tables, embedding, counters, first RMSNorm, final RMSNorm, head with running arg max /
+                    # log-sum-exp, its last reduction
+                    kernel_launches_per_step=5 * m.n_layers + 8 if wl.B <= 32 else None)
         # the same step without the host's launch work: one step (fixed context lengths) captured into a HIP graph and
         # replayed; the replays rewrite the same cache rows with the same values
         from types import SimpleNamespace

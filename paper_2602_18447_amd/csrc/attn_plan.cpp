@@ -31,10 +31,15 @@ UnitPlan shape_plan(const UnitShape &t, Candidate cd) {
     return p;
 }
 
+// Cost of an item beside its chunks, in chunk-times: filling the pipeline, loading q, writing the result - rows of the
+// output (whole tiles) or fp32 partial results (pieces).  From the uniform 64-trace batch: whole tiles 424 us, halves
+// 411 us + 26 us of merging per layer.
+constexpr float ITEM_OVERHEAD_WHOLE = 6.0f, ITEM_OVERHEAD_PIECE = 8.0f;
+
 // Items, partial slots and the largest per-XCD item count of a candidate; lens (optional) receives the
-// per-XCD piece lengths in dispatch order.  Same arithmetic as the list builder.
+// per-XCD item costs (chunks + overhead) in dispatch order.  Same arithmetic as the list builder.
 void candidate_counts(const std::vector<UnitShape> &tr, Candidate cd, int64_t n_tiles, int64_t work_total,
-                      AttnPlanCounts *r, std::vector<int> *lens /* [8] */) {
+                      AttnPlanCounts *r, std::vector<float> *lens /* [8] */) {
     r->n_items = 0; r->n_part_slots = 0; r->max_xcd_items = 0;
     int tile_lo[9] = {0}, seg_base[9] = {0};
     int tile_base = 0, rest_base = 0;
@@ -54,44 +59,82 @@ void candidate_counts(const std::vector<UnitShape> &tr, Candidate cd, int64_t n_
     seg_base[8] = (int)r->n_items;
     for (int x = 0; x < 8; ++x) r->max_xcd_items = std::max<int64_t>(r->max_xcd_items, seg_base[x + 1] - seg_base[x]);
     if (!lens) return;
-    std::vector<int> rest_lens[8];
+    std::vector<float> rest_lens[8];
     int ti = 0;
     for (size_t i = 0; i < tr.size(); ++i)
         for (int j = 0; j < tr[i].tiles; ++j, ++ti) {
             int x = 7;
             while (x > 0 && tile_lo[x] > ti) --x;
             const UnitPlan &p = plans[i];
-            lens[x].push_back(std::min(p.piece, p.nc_max));
+            const float ov = p.n_split > 1 ? ITEM_OVERHEAD_PIECE : ITEM_OVERHEAD_WHOLE;
+            lens[x].push_back((float)std::min(p.piece, p.nc_max) + ov);
             for (int sp = 1; sp < p.n_split; ++sp)
-                rest_lens[x].push_back(std::max(0, std::min(p.piece, p.nc_max - sp * p.piece)));
+                rest_lens[x].push_back((float)std::max(0, std::min(p.piece, p.nc_max - sp * p.piece)) + ov);
         }
     for (int x = 0; x < 8; ++x) lens[x].insert(lens[x].end(), rest_lens[x].begin(), rest_lens[x].end());
 }
 
-// Makespan of longest-first list scheduling on slots/8 workgroup slots per XCD, in chunk-times.
-double simulate(const std::vector<int> *lens, int slots) {
-    int per_xcd = std::max(1, slots / 8);
-    double worst = 0;
+// Makespan of the item list of the busiest XCD, in chunk-times (the time a workgroup takes for one chunk while its CU
+// holds two workgroups).  An XCD has slots / 8 workgroup slots, two per CU; items are handed out in list order as
+// slots free up.  A workgroup that has its CU to itself runs faster - measured about 1.5 times - which decides the
+// value of a last round that does not fill the chip: 96 equal items on 64 slots take 1.67 rounds, not 2.
+double simulate(const std::vector<float> *lens, int slots) {
+    constexpr double ALONE = 1.5;
+    const int n_cu = std::max(1, slots / 16);
+    int x_busy = 0;
+    double most = -1;
     for (int x = 0; x < 8; ++x) {
-        std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
-        for (int i = 0; i < per_xcd; ++i) free_at.push(0.0);
-        double end = 0;
-        for (int len : lens[x]) {
-            double t0 = free_at.top();
-            free_at.pop();
-            double t1 = t0 + len + 1.5;          // 1.5: loading q, writing the result
-            free_at.push(t1);
-            end = std::max(end, t1);
-        }
-        worst = std::max(worst, end);
+        double w = 0;
+        for (float len : lens[x]) w += len;
+        if (w > most) { most = w; x_busy = x; }
     }
-    return worst;
+    const std::vector<float> &q = lens[x_busy];
+    std::vector<double> rem(2 * (size_t)n_cu, -1.0);    // remaining work of slot s of CU c at rem[2 c + s]; < 0: empty
+    size_t next = 0;
+    // free slots are filled in list order, emptier CUs first (the dispatcher spreads workgroups over the CUs)
+    auto fill = [&]() {
+        while (next < q.size()) {
+            int pick = -1, pick_busy = 3;
+            for (int c = 0; c < n_cu; ++c) {
+                const int busy = (rem[2 * c] >= 0) + (rem[2 * c + 1] >= 0);
+                if (busy < 2 && busy < pick_busy) { pick = rem[2 * c] < 0 ? 2 * c : 2 * c + 1; pick_busy = busy; }
+            }
+            if (pick < 0) break;
+            rem[pick] = (double)q[next++];
+        }
+    };
+    fill();
+    double now = 0.0;
+    for (;;) {
+        double dt = -1.0;
+        for (int c = 0; c < n_cu; ++c) {
+            const double speed = (rem[2 * c] >= 0 && rem[2 * c + 1] >= 0) ? 1.0 : ALONE;
+            for (int s = 0; s < 2; ++s)
+                if (rem[2 * c + s] >= 0 && (dt < 0 || rem[2 * c + s] / speed < dt)) dt = rem[2 * c + s] / speed;
+        }
+        if (dt < 0) break;
+        now += dt;
+        for (int c = 0; c < n_cu; ++c) {
+            const double speed = (rem[2 * c] >= 0 && rem[2 * c + 1] >= 0) ? 1.0 : ALONE;
+            for (int s = 0; s < 2; ++s)
+                if (rem[2 * c + s] >= 0) {
+                    rem[2 * c + s] -= dt * speed;
+                    if (rem[2 * c + s] <= 1e-9) rem[2 * c + s] = -1.0;   // done: the slot is free
+                }
+        }
+        fill();
+    }
+    return now;
 }
 }  // namespace
 
 // Choice of the pieces: equal pieces with a split factor 1..4 of the average tile, or front-loaded
-// pieces of 1.07x / 1.2x the per-slot share of all chunks; the candidate with the smallest simulated
-// makespan (+ 8 chunk-times for the merge pass when anything is split) wins.
+// pieces of 1.07x / 1.2x the per-slot share of all chunks (and of twice that share: half as many pieces); the
+// candidate with the smallest simulated makespan plus the cost of its merge pass wins.  The merge pass is a launch
+// (about 4 chunk-times) plus the partial results it reads back, 64 KiB written and read per piece: measured 26 us for
+// 1536 pieces and 90 us for about 4000, against about 1.9 us per chunk-time of the attention kernel - 0.01 chunk-times
+// per piece.  (With a flat 8 chunk-times the ragged 128-trace batch was cut into pieces whose merge cost 2.5 ms per
+// pass to save 1 ms of attention.)
 AttnPlanCounts attn_plan_counts(const AttnTune &tune, const int32_t *h_cu, const int32_t *h_plens, int B, int T,
                                 const int32_t *h_group_start, int n_units, int G, int Hkv, int last_only) {
     AttnPlanCounts r = {};
@@ -123,17 +166,17 @@ AttnPlanCounts attn_plan_counts(const AttnTune &tune, const int32_t *h_cu, const
             if (sp > 1 && avg / sp < tune.min_chunks) break;
             cands.push_back({equal_cpi(sp), 1});
         }
-        for (double f : {1.07, 1.2})
+        for (double f : {1.07, 1.2, 2.14, 2.4})
             if (front_cpi(f) < nc_longest) cands.push_back({front_cpi(f), 0});
     }
     double best = 1e300;
     Candidate pick = {1 << 30, 1};
     for (size_t i = 0; i < cands.size(); ++i) {
         AttnPlanCounts c = {};
-        std::vector<int> lens[8];
+        std::vector<float> lens[8];
         candidate_counts(tr, cands[i], n_tiles, total, &c, lens);
         if (c.n_items > cap_items && cands.size() > 1 && cands[i].cpi != (1 << 30)) continue;
-        double est = simulate(lens, (int)slots) + (c.n_part_slots > 0 ? 8.0 : 0.0);
+        double est = simulate(lens, (int)slots) + (c.n_part_slots > 0 ? 4.0 + 0.01 * (double)c.n_part_slots : 0.0);
         if (est < best) { best = est; pick = cands[i]; }
     }
     r.chunks_per_item = pick.cpi;

@@ -15,6 +15,11 @@
 #include "../../include/confspec_static.h"
 #include "attn_plan.h"
 
+namespace cs {   // decode_bf16.hip: slices and workgroups of a generation step's projection
+void dec_gemm_plan(int K, int n_ct, int *S, int *nwg);
+size_t dec_gemm_plane_bytes(int K, int n_ct);
+}
+
 static int g_fail = 0;
 #define CHECK(cond, ...)                                                         \
     do {                                                                         \
@@ -246,6 +251,29 @@ int main() {
         check_plan(t, b, h[0], h[1], 0, what);
         check_plan(t, b, h[0], h[1], 1, what);
         if (iter % 200 == 0) check_library(draft, b, what);
+    }
+    // slices of the generation step's projections: every k-tile in exactly one slice of at most 24, at most 256
+    // workgroups per launch, no more column groups than column tiles, planes sized for the slices
+    for (int iter = 0; iter < 20000; ++iter) {
+        int K = 64 * (1 + (int)(rng() % 600)), n_ct = 1 + (int)(rng() % 12000);
+        if (iter < 8) {
+            const int shapes[8][2] = {{1536, 128}, {1536, 96}, {1536, 1120}, {8960, 96}, {5120, 448}, {5120, 320}, {5120, 3456}, {27648, 320}};
+            K = shapes[iter][0]; n_ct = shapes[iter][1];
+        }
+        int S = 0, nwg = 0;
+        cs::dec_gemm_plan(K, n_ct, &S, &nwg);
+        const int nk = K / 64;
+        bool ok = S >= 1 && S <= nk && nwg >= 1 && nwg <= n_ct && (long)S * nwg <= 256 + 0L * nk && (nk + S - 1) / S <= 24;
+        int covered = 0;
+        for (int sl = 0; ok && sl < S; ++sl) {
+            int k0 = (int)((long)sl * nk / S), k1 = (int)((long)(sl + 1) * nk / S);
+            ok = k1 > k0 && k1 - k0 <= 24 && k0 == covered;
+            covered = k1;
+        }
+        ok = ok && covered == nk;
+        size_t pb = cs::dec_gemm_plane_bytes(K, n_ct);
+        ok = ok && pb == (S > 1 ? (size_t)S * 32 * n_ct * 16 * 4 : 0);
+        if (!ok) { printf("dec_gemm_plan(K=%d, n_ct=%d) -> S=%d nwg=%d planes=%zu\n", K, n_ct, S, nwg, pb); ++g_fail; }
     }
     if (g_fail) { printf("host_check: %d check(s) failed\n", g_fail); return 1; }
     printf("host_check: ok\n");
