@@ -7,6 +7,12 @@
  * followed by the language-model head over the whole vocabulary at the last position instead of the verdict rows
  * only.  With one new token per trace and write-back of its keys / values it is a decode step; with the drafted or
  * accepted tokens as suffix it is what produces the first token of the next step.
+ *
+ * A step with one new token in each of at most 32 traces of a bf16 model runs on kernels of its own (each weight
+ * matrix streamed once against the activation rows, attention with one query row per head, the head fused with a
+ * running arg max / log-sum-exp so that the [B, vocab] logits are never stored); every other batch takes the
+ * verification pass's kernels and stores the logits in the head scratch.  confspec_tune "decode_kernels" = 0 switches
+ * the former off.
  */
 #ifndef CONFSPEC_GENERATE_H
 #define CONFSPEC_GENERATE_H
@@ -26,7 +32,7 @@ typedef struct {
                               ids are given                                                                      */
 } confspec_head_out;
 
-/* Bytes of dev scratch the head needs for up to max_B traces (the [B, vocab] fp32 logits dominate). */
+/* Bytes of dev scratch the head needs for up to max_B traces (the [B, vocab] fp32 logits of the general path dominate). */
 size_t confspec_head_scratch_bytes(const confspec_ctx *ctx, int32_t max_B);
 
 /* The pass of confspec_verify on `batch`, then the full-vocabulary head at the last suffix position of every trace.

@@ -134,9 +134,11 @@ int confspec_phase_times(confspec_ctx *ctx, float *h_ms /* [CONFSPEC_N_PHASES] *
  *       strided tile loads ask for them (given where the down projection runs one workgroup per tile; results are
  *       bit-identical with 0).
  *   "decode_kernels" (default 1): a bf16 pass with one new token in each of at most 32 traces (a generation step,
- *       Algorithm 1's generate calls) runs on kernels shaped for it - projections that stream each weight matrix once
- *       against the 32 activation rows held in LDS, attention with one query row per head - when every layer's operands
- *       are single 16-bit values and the scratch holds its partial results; 0: such a pass runs on the general kernels.
+ *       Algorithm 1's generate calls) can run on kernels shaped for it - projections that stream each weight matrix once
+ *       against the 32 activation rows, attention with one query row per head - when every layer's operands are single
+ *       16-bit values and the scratch holds its partial results.  1: it does when d_model and the q width are at most
+ *       1536 (where those kernels are the faster ones), 2: whenever the shapes allow, 0: never (such a pass then runs on
+ *       the general kernels).
  *   "prune_last_layer" (default 1): in the last layer, attention rows, output projection and MLP are computed for the
  *       last position of each trace only (the only rows the verdict head reads; 0 computes every row).
  *   Launch shapes, for measurements: "gemm_tile" (0 heuristic; 1 = 128x128, 4 = 256x256, 7 = 192x96 workgroup tiles; a

@@ -42,8 +42,11 @@ struct Settings {
     int fuse_rope = 1;
     // The gate/up projection warms the last-level cache with the down projection's weights.
     int prefetch_down = 1;
-    // 1: a bf16 pass with one new token per trace and at most 32 traces (a generation step) runs on the kernels
-    // shaped for it (decode_bf16.hip); 0: it runs on the verification pass's kernels
+    // A bf16 pass with one new token per trace and at most 32 traces (a generation step) can run on the kernels shaped
+    // for it (decode_bf16.hip).  1: it does when d_model and the q width fit one k slice of those kernels (1536), where
+    // they win (28 layers x 1536: 1.99 against 2.68 ms per step); wider models stay on the verification pass's kernels,
+    // which stream their long k ranges better (64 layers x 5120: 18.7 against 21.6 ms).  2: whenever the shapes allow.
+    // 0: never.
     int decode_kernels = 1;
     cs::GemmTune gemm;
     cs::AttnTune attn;
@@ -693,7 +696,8 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
     // A generation step (one new token per trace, at most 32 traces) runs on the kernels shaped for it when every
     // layer's operands are single 16-bit values (bf16 or fp16) and the scratch holds its partial results; everything
     // else, and any step that does not fit, takes the general kernels below.
-    bool use_dec = set.decode_kernels && dec_shape_ok(c, T, B) && !ex.dev_group_start;
+    bool use_dec = set.decode_kernels && dec_shape_ok(c, T, B) && !ex.dev_group_start &&
+                   (set.decode_kernels == 2 || (d <= 64 * cs::DEC_MAX_KT && qw <= 64 * cs::DEC_MAX_KT));
     int64_t dec_np = 0;
     if (use_dec) {
         for (int l = 0; l < c.n_layers && use_dec; ++l) use_dec = rope_fused_in(l) && format_of(l) != 2;
@@ -766,7 +770,8 @@ static int verify_impl(confspec_ctx *ctx, const confspec_weights *w, const confs
             at.B = B; at.Hq = c.n_q_heads; at.Hkv = c.n_kv_heads; at.G = c.n_q_heads / c.n_kv_heads;
             at.max_blocks = kv->max_blocks_per_seq; at.n_blocks = kv->n_blocks; at.max_L = max_L;
             at.scale_log2 = 1.44269504088896340736f / sqrtf((float)c.head_dim);
-            at.max_pieces = max_L / cs::DEC_PIECE + 1;
+            at.n_iter = cs::dec_attn_rounds(B, c.n_kv_heads, max_L);
+            at.max_pieces = max_L / (cs::DEC_PIECE * at.n_iter) + 1;
             HIP_TRY(cs::launch_dec_attn(at, s));
             HIP_TRY(mark(CONFSPEC_PHASE_O_PROJ));
             cs::DecGemm go = {};
@@ -1278,7 +1283,7 @@ int confspec_tune(confspec_ctx *ctx, const char *key, int32_t value) {
         {"split_layers", &st.split_layers, -1, 4096},
         {"prefetch_down", &st.prefetch_down, 0, 1},
         {"fuse_rope", &st.fuse_rope, 0, 1},
-        {"decode_kernels", &st.decode_kernels, 0, 1},
+        {"decode_kernels", &st.decode_kernels, 0, 2},
         {"first_layers_f16", &st.first_layers_f16, 0, 1},
         {"prune_last_layer", &st.prune_last_layer, 0, 1},
         {"attn_precise_layers", &st.attn_precise_layers, 0, 4096},

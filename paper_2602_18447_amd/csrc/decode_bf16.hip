@@ -474,28 +474,38 @@ hipError_t launch_dec_head_final(const float *part, int nwg, int B, const float 
     return hipGetLastError();
 }
 
-// Slices and workgroups of a projection.  A k range that fits one slice is never cut (no partial planes, no counters);
-// a longer one takes the slice count, from the fewest possible up, that leaves the least work on the longest-running
-// workgroup: rounds of column tiles per workgroup x k-tiles per slice.
+// Slices and workgroups of a projection.  A k range that fits one slice is never cut (no partial planes, no counters):
+// one workgroup per CU, each with its share of the column tiles.  A longer one is cut into S slices of at most 24
+// k-tiles, and S x nwg workgroups run in rounds of 256.  The choice minimises a model of the launch, in units of one
+// column tile over 8 k-tiles (16 KiB of weights per workgroup, about 0.7 us at the rate a CU streams them):
+//   rounds x (4 + tiles per workgroup x units per tile)   a workgroup's fixed cost (activations, first weights) is 4
+//   + tiles per workgroup x ceil(S / 8) x 2                 the last slice of a column group to arrive adds the S planes of
+//                                                           its tiles, eight loads at a time, alone
+// Few column groups with many slices leave that last sum to a handful of workgroups (d_ffn 27648 as 32 slices x 8
+// groups: 200 us per projection); many small workgroups pay the fixed cost once per round.
 void dec_gemm_plan(int K, int n_ct, int *S_out, int *nwg_out) {
     const int nk = K / 64;
     const int s_min = (nk + DEC_MAX_KT - 1) / DEC_MAX_KT;
-    auto groups = [&](int S) {
-        int g = std::min(n_ct, std::max(1, 256 / S));
-        if (g >= 8) g -= g % 8;            // slices of a column group then share an XCD, and with it an L2
-        return g;
-    };
-    int best_s = s_min;
-    if (s_min > 1) {
-        long best = -1;
-        for (int S = s_min; S <= std::min(nk, 2 * s_min + 2); ++S) {
-            int g = groups(S);
-            long cost = (long)((n_ct + g - 1) / g) * ((nk + S - 1) / S);
-            if (best < 0 || cost < best) { best = cost; best_s = S; }
+    if (s_min == 1) {
+        *S_out = 1;
+        *nwg_out = std::min(n_ct, 256);
+        return;
+    }
+    double best = -1;
+    int best_s = s_min, best_g = 1;
+    for (int S = s_min; S <= std::min(nk, 2 * s_min + 2); ++S) {
+        const double units = (double)((nk + S - 1) / S) / 8.0;     // the weights a workgroup streams per tile
+        for (int g = 8; g <= 256; g += 8) {        // multiples of 8: the slices of a column group share an XCD, and with it an L2
+            const int gg = std::min(g, n_ct);
+            const int tiles = (n_ct + gg - 1) / gg;
+            const long rounds = ((long)S * gg + 255) / 256;
+            const double cost = (double)rounds * (4.0 + tiles * units) + tiles * ((S + 7) / 8) * 2.0;
+            if (best < 0 || cost < best) { best = cost; best_s = S; best_g = gg; }
+            if (gg == n_ct) break;
         }
     }
     *S_out = best_s;
-    *nwg_out = groups(best_s);
+    *nwg_out = best_g;
 }
 size_t dec_gemm_plane_bytes(int K, int n_ct) {
     int S, nwg;
@@ -540,8 +550,8 @@ hipError_t launch_dec_gemm(const DecGemm &a, int epi, bool f16, hipStream_t s) {
 }
 
 // ---- attention ------------------------------------------------------------------------------------------------------
-// One workgroup of 8 wavefronts per (trace, kv head, piece of 256 keys); wavefront w takes the two 16-token pages
-// 2 w, 2 w + 1 of the piece.  Keys go straight from global memory into the registers of the score product's first
+// One workgroup of 8 wavefronts per (trace, kv head, piece of n_iter x 256 keys); in each round of 256 keys wavefront
+// w takes the two 16-token pages 2 w, 2 w + 1 and keeps a running (max, sum, O) over its rounds.  Keys go straight from global memory into the registers of the score product's first
 // operand (lane l: token l % 16 of a page, head-dim elements 32 ks + 8 (l / 16) .. + 7), values go global -> LDS
 // (8 KiB per wavefront, rows of 256 bytes) and come back through transposing reads as the first operand of
 // O^T += V^T . P^T.  The 16-byte vector v of token k sits at slot v ^ (2 (k & 7)) of its row, so that the 32 bytes x 8
@@ -556,7 +566,10 @@ constexpr int DEC_ATTN_WAVE_LDS = 8192;
 constexpr int DEC_ATTN_SMEM = DEC_ATTN_WAVES * DEC_ATTN_WAVE_LDS;
 static_assert(DEC_PIECE == 32 * DEC_ATTN_WAVES, "a piece is two pages per wavefront");
 
-__global__ __launch_bounds__(DEC_ATTN_THREADS, 2) void dec_attn_kernel(DecAttn a) {
+// MULTI: the workgroup makes a.n_iter rounds (otherwise exactly one: the compiler then knows that nothing is carried
+// into the round, which keeps the kernel at 96 registers and two workgroups on a CU; the loop form needs 144).
+template <bool MULTI>
+__global__ __launch_bounds__(DEC_ATTN_THREADS, MULTI ? 1 : 2) void dec_attn_kernel(DecAttn a) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     __shared__ volatile int s_last;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -566,21 +579,24 @@ __global__ __launch_bounds__(DEC_ATTN_THREADS, 2) void dec_attn_kernel(DecAttn a
     const int h = blockIdx.x % a.Hkv, b = blockIdx.y;
     const int p = a.max_pieces - 1 - blockIdx.x / a.Hkv;
     const int L = min(max(a.plens[b], 0), a.max_L);                     // keys 0 .. L-1 are cached, key L is the new token
-    const int n_p = L / DEC_PIECE + 1;                                  // pieces over the L + 1 keys
+    const int n_iter = MULTI ? a.n_iter : 1;
+    const int piece_keys = DEC_PIECE * n_iter;                          // a workgroup makes n_iter rounds of 256 keys
+    const int n_p = L / piece_keys + 1;                                 // pieces over the L + 1 keys
     if (p >= n_p) return;                                               // uniform: a shorter trace
     const int pi = b * a.max_pieces + p;                                // index of the piece's partial results
     const int G = a.G;
-    const int key0 = DEC_PIECE * p + 32 * wave;                         // this wavefront's 32 keys
-    const bool active = key0 <= L;                                      // wave-uniform
     unsigned char *vst = smem + wave * DEC_ATTN_WAVE_LDS;
     const unsigned lds_v = (unsigned)(size_t)(CS_LDS_AS unsigned char *)vst;
 
     const int fr = lane & 15, fg = lane >> 4;
-    float m_w = -INFINITY, l_w = 0.f;
+    float m_w = -INFINITY, l_w = 0.f;                                   // running maximum (log2 units) and sum of this wavefront
     f32x4 o_acc[8];
 #pragma unroll
     for (int hb = 0; hb < 8; ++hb) o_acc[hb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (active) {
+    const bool active = piece_keys * p + 32 * wave <= L;                // wave-uniform: the wavefront sees at least one key
+    for (int it = 0; it < n_iter; ++it) {
+        const int key0 = piece_keys * p + DEC_PIECE * it + 32 * wave;   // this wavefront's 32 keys of this round
+        if (key0 > L) break;                                            // wave-uniform; later rounds lie further out
         // A token at or past L comes from the new token's row (token L itself; later ones are masked), so page rows
         // that were never written are not read.
         const bf16 *ks_row = a.ksuf + ((size_t)b * a.Hkv + h) * 128, *vs_row = a.vsuf + ((size_t)b * a.Hkv + h) * 128;
@@ -605,11 +621,13 @@ __global__ __launch_bounds__(DEC_ATTN_THREADS, 2) void dec_attn_kernel(DecAttn a
             for (int ks = 0; ks < 4; ++ks) kf[kb][ks] = *reinterpret_cast<const bf16x8 *>(krow + 32 * ks + 8 * fg);
         }
         // q operand: lane l holds query row l % 16 (rows >= G are zero), head-dim elements 32 ks + 8 (l / 16) .. + 7
+        // (fetched in every round rather than kept: with it live across the loop the kernel needs more than 128
+        // registers and a CU holds one workgroup instead of two)
         bf16x8 q_hi[4], q_lo[4];
         {
             const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
             const size_t qo = ((size_t)b * a.Hq + (size_t)h * G + min(fr, G - 1)) * 128;
-#pragma unroll
+    #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 q_hi[ks] = fr < G ? *reinterpret_cast<const bf16x8 *>(a.q + qo + 32 * ks + 8 * fg) : zero;
                 q_lo[ks] = (fr < G && a.q_lo) ? *reinterpret_cast<const bf16x8 *>(a.q_lo + qo + 32 * ks + 8 * fg) : zero;
@@ -635,19 +653,26 @@ __global__ __launch_bounds__(DEC_ATTN_THREADS, 2) void dec_attn_kernel(DecAttn a
             }
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        m_w = mx;                                        // finite: token key0 <= L is visible to every query row
+        // running maximum: finite from the first round on (token key0 <= L is visible to every query row)
+        const float m_new = fmaxf(m_w, mx);
+        const float alpha = m_w == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_w - m_new);
+        m_w = m_new;
         float ps = 0.f, pv[8];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float pr = __builtin_amdgcn_exp2f(sc[kb][e] - mx);
+                float pr = __builtin_amdgcn_exp2f(sc[kb][e] - m_new);
                 pv[4 * kb + e] = pr;
                 ps += pr;
             }
         ps += __shfl_xor(ps, 16);
         ps += __shfl_xor(ps, 32);
-        l_w = ps;
+        l_w = l_w * alpha + ps;
+        if (it > 0) {
+#pragma unroll
+            for (int hb = 0; hb < 8; ++hb) o_acc[hb] *= alpha;
+        }
         // probabilities as the second operand of O^T += V^T . P^T: k index 8 (l / 16) + i <-> token 4 (l / 16) + i of
         // page 0 (i < 4) or page 1 (i >= 4), which is what the lane already holds; two bf16 terms
         bf16x8 p_hi, p_lo;
@@ -670,7 +695,7 @@ __global__ __launch_bounds__(DEC_ATTN_THREADS, 2) void dec_attn_kernel(DecAttn a
             o_acc[hb] = mma16<false>(vf, p_hi, o_acc[hb]);
             o_acc[hb] = mma16<false>(vf, p_lo, o_acc[hb]);
         }
-        dec_wait_lds();
+        dec_wait_lds();                                  // the value region may be refilled (or reused below)
     }
     // ---- the eight wavefronts' results, combined in wavefront order.  Each leaves O [8 rows][128] fp32, then max and
     // sum per row, in its own value region (its own reads of that region are complete).
@@ -760,15 +785,31 @@ __global__ __launch_bounds__(DEC_ATTN_THREADS, 2) void dec_attn_kernel(DecAttn a
     }
 }
 
-// a.max_pieces: pieces of the longest trace, max_L / DEC_PIECE + 1 (no more than the merge can stage in LDS)
+// Rounds of 256 keys a workgroup makes: the fewest (a power of two up to 16) that keep the grid at about two workgroups
+// per CU - with many (trace, kv head) pairs, pieces of 256 keys make several rounds of short workgroups whose fixed
+// costs (dispatch, lengths and page ids, the merge) add up (16 traces x 8 kv heads x 4096 keys: 67 us per layer).
+int dec_attn_rounds(int B, int Hkv, int max_L) {
+    int n = 1;
+    while (n < 16 && (long)B * Hkv * (max_L / (DEC_PIECE * n) + 1) > 640) n *= 2;
+    return n;
+}
+
+// a.n_iter from dec_attn_rounds; a.max_pieces: pieces of the longest trace, max_L / (DEC_PIECE * n_iter) + 1
 hipError_t launch_dec_attn(const DecAttn &a, hipStream_t s) {
     if (a.B < 1 || a.B > DEC_MAX_ROWS || a.G < 1 || a.G > DEC_MAX_G || a.Hkv < 1 || a.B * a.Hkv > DEC_CTL_TILE - DEC_CTL_ATTN ||
-        a.max_pieces != a.max_L / DEC_PIECE + 1 || a.max_pieces > DEC_ATTN_SMEM / (DEC_MAX_G * 2 * 4))
+        a.n_iter < 1 || a.max_pieces != a.max_L / (DEC_PIECE * a.n_iter) + 1 || a.max_pieces > DEC_ATTN_SMEM / (DEC_MAX_G * 2 * 4))
         return hipErrorInvalidValue;
-    static std::atomic<uint32_t> attr_done{0};
-    if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(dec_attn_kernel), DEC_ATTN_SMEM); e != hipSuccess)
-        return e;
-    dec_attn_kernel<<<dim3(a.max_pieces * a.Hkv, a.B), DEC_ATTN_THREADS, DEC_ATTN_SMEM, s>>>(a);
+    static std::atomic<uint32_t> attr_one{0}, attr_multi{0};
+    const dim3 grid(a.max_pieces * a.Hkv, a.B);
+    if (a.n_iter == 1) {
+        if (hipError_t e = set_dynamic_lds_once(attr_one, reinterpret_cast<const void *>(dec_attn_kernel<false>), DEC_ATTN_SMEM); e != hipSuccess)
+            return e;
+        dec_attn_kernel<false><<<grid, DEC_ATTN_THREADS, DEC_ATTN_SMEM, s>>>(a);
+    } else {
+        if (hipError_t e = set_dynamic_lds_once(attr_multi, reinterpret_cast<const void *>(dec_attn_kernel<true>), DEC_ATTN_SMEM); e != hipSuccess)
+            return e;
+        dec_attn_kernel<true><<<grid, DEC_ATTN_THREADS, DEC_ATTN_SMEM, s>>>(a);
+    }
     return hipGetLastError();
 }
 

@@ -253,7 +253,7 @@ int main() {
         if (iter % 200 == 0) check_library(draft, b, what);
     }
     // slices of the generation step's projections: every k-tile in exactly one slice of at most 24, at most 256
-    // workgroups per launch, no more column groups than column tiles, planes sized for the slices
+    // column groups (one arrival counter each) and no more than there are column tiles, planes sized for the slices
     for (int iter = 0; iter < 20000; ++iter) {
         int K = 64 * (1 + (int)(rng() % 600)), n_ct = 1 + (int)(rng() % 12000);
         if (iter < 8) {
@@ -263,7 +263,7 @@ int main() {
         int S = 0, nwg = 0;
         cs::dec_gemm_plan(K, n_ct, &S, &nwg);
         const int nk = K / 64;
-        bool ok = S >= 1 && S <= nk && nwg >= 1 && nwg <= n_ct && (long)S * nwg <= 256 + 0L * nk && (nk + S - 1) / S <= 24;
+        bool ok = S >= 1 && S <= nk && nwg >= 1 && nwg <= n_ct && nwg <= 256 && (nk + S - 1) / S <= 24;
         int covered = 0;
         for (int sl = 0; ok && sl < S; ++sl) {
             int k0 = (int)((long)sl * nk / S), k1 = (int)((long)(sl + 1) * nk / S);

@@ -236,10 +236,12 @@ struct DecAttn {
     void *out;                        // [B, Hq * 128] in format out_fmt (1 bf16, 3 half; 2: [B, 2 Hq 128] hi | lo)
     float *part_o, *part_ml;          // per (trace, piece, kv head): [8, 128] and [8, 2] fp32; B * max_pieces * Hkv of them
     int32_t B, Hq, Hkv, G, max_blocks, n_blocks, max_L, out_fmt;
-    int32_t max_pieces;               // pieces of the longest trace: max_L / DEC_PIECE + 1
+    int32_t n_iter;                   // rounds of DEC_PIECE keys per workgroup (dec_attn_rounds)
+    int32_t max_pieces;               // pieces of the longest trace: max_L / (DEC_PIECE * n_iter) + 1
     float scale_log2;                 // log2(e) / sqrt(head_dim)
 };
 hipError_t launch_dec_init(int32_t *ctl, hipStream_t s);
+int dec_attn_rounds(int B, int Hkv, int max_L);
 hipError_t launch_dec_attn(const DecAttn &a, hipStream_t s);
 inline size_t dec_attn_part_o_bytes(int64_t n_pieces, int Hkv) { return (size_t)n_pieces * Hkv * DEC_MAX_G * 128 * 4; }
 inline size_t dec_attn_part_ml_bytes(int64_t n_pieces, int Hkv) { return (size_t)n_pieces * Hkv * DEC_MAX_G * 2 * 4; }

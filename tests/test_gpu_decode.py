@@ -33,7 +33,7 @@ def _run(wl, decode_kernels=1):
     return weights, batch, kv, gpu
 
 
-@pytest.mark.parametrize("case", ["borders", "one_trace", "32_traces", "from_prefix_pass"])
+@pytest.mark.parametrize("case", ["borders", "one_trace", "32_traces", "from_prefix_pass", "long_contexts", "longer_contexts"])
 def test_one_token_batches_match_oracle(case):
     print(f"one-token batch: {case}", flush=True)
     if case == "borders":
@@ -43,6 +43,12 @@ def test_one_token_batches_match_oracle(case):
     elif case == "32_traces":
         rng = np.random.default_rng(7103)
         wl = _wl("dec_32", 7103, tuple(int(v) for v in rng.integers(0, 700, 32)))
+    elif case == "long_contexts":      # enough (trace, kv head, 256-key piece) triples that a workgroup makes 2 rounds of 256 keys
+        rng = np.random.default_rng(7107)
+        wl = _wl("dec_long", 7107, tuple(int(v) for v in rng.integers(2000, 4500, 24)) + (511, 512, 513, 1023, 1024, 0))
+    elif case == "longer_contexts":    # ... 4 rounds
+        rng = np.random.default_rng(7108)
+        wl = _wl("dec_longer", 7108, tuple(int(v) for v in rng.integers(3000, 9000, 30)) + (1023, 1024), n_layers=2)
     else:
         wl = _wl("dec_ctx", 7104, (40, 1, 129, 16, 3, 64, 255, 17), kv_source="prefix_pass")
     weights, batch, kv, gpu = _run(wl)
@@ -58,14 +64,17 @@ def test_one_token_batches_match_oracle(case):
 
 def test_one_token_batch_on_a_model_with_sliced_k_ranges():
     # d_model 2048 = 32 k-tiles: every projection's k range is cut into slices whose partial planes the last workgroup
-    # to arrive adds up; 8 q heads per kv head (the most the step's attention takes)
+    # to arrive adds up; 8 q heads per kv head (the most the step's attention takes).  Models this wide take the step
+    # kernels only when asked to (setting 2).
     print("one-token batch, d_model 2048, 16 / 2 heads", flush=True)
     wl = _wl("dec_wide", 7105, (0, 33, 256, 700, 90), n_layers=2, d_model=2048, n_q_heads=16, n_kv_heads=2, d_ffn=2560)
-    weights, batch, kv, gpu = _run(wl)
+    _, _, _, auto = _run(wl, decode_kernels=1)
+    weights, batch, kv, gpu = _run(wl, decode_kernels=2)
     ora = G.run_oracle(wl, weights, batch, kv, gpu["taus"], gpu["vids"])
     G.compare(wl, gpu, ora, wl.name)
     _, _, _, ref = _run(wl, decode_kernels=0)
     assert not np.array_equal(ref["logits"], gpu["logits"])
+    assert np.array_equal(ref["logits"], auto["logits"])      # the default leaves this model on the general kernels
 
 
 def test_one_token_batch_is_repeatable_and_runs_on_the_static_scratch():
