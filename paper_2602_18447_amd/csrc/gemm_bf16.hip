@@ -49,8 +49,29 @@ __device__ inline f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// one 16x16x32 MFMA: the same flops per cycle as the 32x32x16 one at a lower energy per flop - with random operands the
+// matrix pipe alone sustains about 2.08 PFLOP/s with it against 1.85 PFLOP/s (the clock the chip holds under load differs)
+template <bool F16>
+__device__ inline f32x4 mma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
 // vmcnt(n) only (expcnt / lgkmcnt left unconstrained), gfx9 encoding of s_waitcnt
 #define CS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+// Workgroup barrier without the fences of __syncthreads().  Those fences make the compiler wait for every outstanding
+// direct load (a direct load writes LDS), which would cut the prefetch depth of a multi-stage pipeline to one k-tile
+// whatever count the explicit wait in front of the barrier names.  The waits that matter are stated next to each use.
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+// vmcnt(n) and lgkmcnt(0): at most n direct loads of this wavefront in flight, all of its LDS reads returned
+#define CS_WAIT_VMCNT_LDS(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (0 << 8))
+
+// Tiles that keep their operands in a ring of five half-stages (see the kernel) and the dynamic LDS of a tile shape
+constexpr bool ring_tile(int BM, int BN, int BK) { return BM == 256 && BN == 256 && BK == 64; }
+constexpr int gemm_lds_bytes(int BM, int BN, int BK, int NS) { return ring_tile(BM, BN, BK) ? 5 * BM * BK * 2 : NS * (BM + BN) * BK * 2; }
 
 // BK: k extent of one LDS stage (64 or 32 elements); NS: number of LDS stages.  NS - 1 k-tiles are
 // kept in flight: (64, 2) has the fewest barriers, (32, 4) the deepest prefetch for the same LDS budget.
@@ -59,6 +80,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
                                                          void *out_v, int M, int N, int K,
                                                          int tiles_m, int tiles_n, int n_base, int group_m, int out_fmt, RopeArgs rope,
                                                          PrefetchArgs pf) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's name (buffer resources are a device-side type)
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int A_TERMS = A_FMT == 2 ? 2 : 1;
     constexpr bool F16 = A_FMT == 3;
@@ -75,8 +97,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     static_assert(BM % (RPD * NW) == 0 && BN % (RPD * NW) == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
     static_assert(EPI != EPI_SWIGLU || WN % 64 == 0, "SwiGLU needs a gate/up column pair inside one wave tile");
     static_assert(EPI != EPI_ROPE || WN == 64, "the rotation pairs of a head half fill a 64-column wave tile");
-    static_assert(NS >= 2 && NS <= 4, "stages");
+    static_assert(NS >= 2 && NS <= 5, "stages");
     static_assert(MI * NI >= 2, "a k-step has at least two MFMAs");
+    // 256 x 256 tiles take the loop that reads a k-tile's first operands during the previous tile's last k-step
+    // 256 x 256 tiles: 16x16x32 MFMAs, operands in a ring of five half-stage units (NS == 5 counts those units)
+    constexpr bool M16 = ring_tile(BM, BN, BK);
+    static_assert(!M16 || (WAVES_M == 2 && WAVES_N == 4 && NS == 5), "256 x 256 tiles run 8 wavefronts on the ring of five units");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give each XCD a
@@ -94,7 +120,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     int tm = band * group_m + in_band % band_rows, tn = in_band / band_rows;
     int m0 = tm * BM, n0 = n_base + tn * BN;   // a launch may cover the column range [n_base, n_base + tiles_n * BN) only
 
-    int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: LDS targets of the direct loads are then scalar too
     int wy = wave / WAVES_N, wx = wave % WAVES_N;
 
     // Direct-load roles: instruction j of wave w fills rows RPD*(w + NW*j) .. of an operand tile; lane s
@@ -102,21 +129,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     // Swizzle: position = k-vector ^ ((row >> 1) & 7) for 128-byte rows, ^ ((row >> 2) & 3) for 64-byte
     // rows; either way 16 consecutive rows at one k-vector cover all 64 banks once.  A rows past M
     // are clamped (fetched twice, never stored to the output).
+    // The loads are buffer loads: a scalar resource per operand that starts at the tile's first row, a 32-bit byte
+    // offset per lane that is the same for every k-tile, and the k-tile's offset in a scalar register - no vector
+    // instruction is needed to issue one.  (Offsets stay below 256 rows x 2 K x 2 bytes.)
     auto swz = [](int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
     const int rl = lane / VPR, ph = lane % VPR;
     const int lda = K * A_TERMS;
-    const char *a_src[A_DMA], *b_src[B_DMA];
+    const __amdgpu_buffer_rsrc_t a_rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16 *>(A + (size_t)m0 * lda), 0, -1, 0x00020000);
+    const __amdgpu_buffer_rsrc_t b_rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16 *>(W + (size_t)n0 * K), 0, -1, 0x00020000);
+    int a_off[A_DMA], b_off[B_DMA];
 #pragma unroll
     for (int j = 0; j < A_DMA; ++j) {
         int row = RPD * (wave + NW * j) + rl;
         int g = ph ^ swz(row);
-        a_src[j] = reinterpret_cast<const char *>(A + (size_t)min(m0 + row, M - 1) * lda + g * 8);
+        a_off[j] = (min(m0 + row, M - 1) - m0) * lda * 2 + g * 16;
     }
 #pragma unroll
     for (int j = 0; j < B_DMA; ++j) {
         int row = RPD * (wave + NW * j) + rl;
         int g = ph ^ swz(row);
-        b_src[j] = reinterpret_cast<const char *>(W + (size_t)(n0 + row) * K + g * 8);
+        b_off[j] = row * K * 2 + g * 16;
     }
     int nk_w = K / BK;             // k-tiles of W
     int nk_all = nk_w * A_TERMS;   // k-tiles of the loop: with two-term A, the hi and the lo tile of every W k-tile
@@ -128,29 +162,41 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     const int kb = blockIdx.y;
     const int nk = (nk_all - kb + kstep - 1) / kstep;
     if (EPI == EPI_STORE_F32) out_v = reinterpret_cast<float *>(out_v) + (size_t)blockIdx.y * M * N;
-    auto issue_loads = [&](int stage, int kt) {
+    // load j (A: 0 .. A_DMA-1, then W) of k-tile kt into LDS stage `stage`
+    auto issue_one = [&](int stage, int kt, int j) __attribute__((always_inline)) {
         // Two-term A: k-tile kt pairs W k-tile kt / 2 with the hi (even kt) or lo (odd kt) half of A, so a W k-tile is
         // asked for twice in a row (the second time it is still in L2) rather than once per sweep over K.
         int kw = A_TERMS == 2 ? kt >> 1 : kt;
         int ka = (A_TERMS == 2 && (kt & 1)) ? nk_w + kw : kw;
         unsigned char *base = smem + stage * STAGE;
+        if (j < A_DMA)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rs, (CS_LDS_AS void *)(base + (wave + NW * j) * 1024), 16, a_off[j < A_DMA ? j : 0],
+                                                     ka * ROWB, 0, 0);
+        else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rs, (CS_LDS_AS void *)(base + BM * ROWB + (wave + NW * (j - A_DMA)) * 1024), 16,
+                                                     b_off[j >= A_DMA ? j - A_DMA : 0], kw * ROWB, 0, 0);
+    };
+    auto issue_loads = [&](int stage, int kt) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < A_DMA; ++j)
-            __builtin_amdgcn_global_load_lds((const CS_GLOBAL_AS void *)(a_src[j] + (size_t)ka * ROWB),
-                                             (CS_LDS_AS void *)(base + (wave + NW * j) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < B_DMA; ++j)
-            __builtin_amdgcn_global_load_lds((const CS_GLOBAL_AS void *)(b_src[j] + (size_t)kw * ROWB),
-                                             (CS_LDS_AS void *)(base + BM * ROWB + (wave + NW * j) * 1024), 16, 0, 0);
+        for (int j = 0; j < PER_TILE; ++j) issue_one(stage, kt, j);
     };
 
-    f32x16 acc[MI][NI];
+    f32x16 acc[M16 ? 1 : MI][M16 ? 1 : NI];
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < (M16 ? 1 : MI); ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
+        for (int j = 0; j < (M16 ? 1 : NI); ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    // 16x16 blocks: acc16[i][j][e] = C[16 i + 4 (lane / 16) + e][16 j + lane % 16] of the wave tile
+    constexpr int MI16 = M16 ? WM / 16 : 1, NI16 = M16 ? WN / 16 : 1;
+    f32x4 acc16[MI16][NI16];
+#pragma unroll
+    for (int i = 0; i < MI16; ++i)
+#pragma unroll
+        for (int j = 0; j < NI16; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc16[i][j][e] = 0.f;
 
     // MFMA operand reads: row (lane % 32) of each 32-row block, k-vector 2 ks + lane / 32
     const int half = lane >> 5;
@@ -158,6 +204,111 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     const int a_base = arow * ROWB, a_sw = swz(arow);          // rows 32 apart share the swizzle value
     const int b_base = BM * ROWB + brow * ROWB, b_sw = swz(brow);
 
+    // MFMA q of a k-step: accumulator block (q / NI, q % NI)
+    auto mfma_range = [&](const bf16x8 (&a_)[MI], const bf16x8 (&b_)[NI], int q0, int q1) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = q0; q < q1; ++q) acc[q / NI][q % NI] = mma<F16>(a_[q / NI], b_[q % NI], acc[q / NI][q % NI]);
+    };
+    constexpr int KS = BK / 16;   // k-steps of a k-tile
+    constexpr int EARLY = 2;      // MFMAs of a k-step issued before the next step's operand reads
+    if constexpr (M16) {
+        // 256 x 256 tile, 8 wavefronts of 128 x 64, 16x16x32 MFMAs.  A k-tile is 16 slots (k half ks2 = slot / 8, 16-row
+        // block i = slot % 8) of four MFMAs each (the four 16-column blocks).  Operands: the four W fragments of a k half
+        // are double-buffered, the A fragments go through a ring of four (the one of slot s + 3 is requested in slot s);
+        // an A fragment is row lane % 16 of its block, 16-byte k-vector 4 ks2 + lane / 16, at the swizzled position.
+        // One barrier per k-tile, in front of slot 13: before it a wavefront has requested its last operands of the
+        // k-tile (slot 15's in slot 12) and waits for them and for its own direct loads of the next k-tile; after it the
+        // next k-tile is complete in LDS (its first operands are read in slots 13 - 15: the matrix pipe does not drain at
+        // the tile boundary) and the LDS of the current one is free for direct loads.
+        // The direct loads are issued one at a time between the MFMAs: a burst of them queues at the CU's one address
+        // unit, and the wavefronts then wait at their load instructions instead of issuing MFMAs (measured with time stamps:
+        // a third of a k-tile).  To give every load time to land although they are issued evenly, LDS holds 2.5 k-tiles: a
+        // unit is the A or the W part of a k-tile (32 KiB, 4 loads per wavefront), unit u of the stream A(0) W(0) A(1) W(1)
+        // .. lives in ring slot u % 5 of the 160 KiB, so the whole of k-tile t+1 and the A part of k-tile t+2 are in flight
+        // while k-tile t is multiplied.  One load in every second slot: 13, 15 of k-tile t and 1, 3 of k-tile t+1 make unit
+        // 2t+5 (into the slot of A(t), free since the barrier), 5 .. 11 of k-tile t+1 make unit 2t+6 (slot of W(t)); each
+        // has at least 10 slots to land.  At the barrier of k-tile t everything up to unit 2t+3 must have landed: direct
+        // loads complete in order, so at most the four loads of unit 2t+4 may be outstanding.
+        static_assert(A_DMA == 4 && B_DMA == 4, "256 x 256 tile, 8 wavefronts");
+        constexpr int UNIT = BM * ROWB;   // 32 KiB: the A or the W part of a k-tile
+        const int l16 = lane & 15, kq = lane >> 4;
+        const int sw16 = (l16 >> 1) & 7;                                   // blocks start at multiples of 16 rows
+        const int a_row_off = (wy * WM + l16) * ROWB, b_row_off = (wx * WN + l16) * ROWB;
+        int kv_off[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) kv_off[h] = ((4 * h + kq) ^ sw16) * 16;
+        bf16x8 a16[4], b16[2][4];
+        auto read_a = [&](const unsigned char *ua, int s) __attribute__((always_inline)) {   // slot s of the k-tile at ua
+            a16[s & 3] = *reinterpret_cast<const bf16x8 *>(ua + a_row_off + (s & 7) * 16 * ROWB + kv_off[s >> 3]);
+        };
+        auto read_b = [&](const unsigned char *ub, int h, int j) __attribute__((always_inline)) {
+            b16[h][j] = *reinterpret_cast<const bf16x8 *>(ub + b_row_off + j * 16 * ROWB + kv_off[h]);
+        };
+        // direct load j of the A (w == 0) or W (w == 1) part of k-tile t of this workgroup's loop into LDS at dst
+        auto issue = [&](int t, int w, int j, unsigned char *dst) __attribute__((always_inline)) {
+            const int kt = kb + t * kstep;
+            const int kw = A_TERMS == 2 ? kt >> 1 : kt;
+            const int ka = (A_TERMS == 2 && (kt & 1)) ? nk_w + kw : kw;
+            if (w) __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rs, (CS_LDS_AS void *)(dst + (wave + NW * j) * 1024), 16, b_off[j], kw * ROWB, 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rs, (CS_LDS_AS void *)(dst + (wave + NW * j) * 1024), 16, a_off[j], ka * ROWB, 0, 0);
+        };
+        // LDS position of unit u = 2 t + w: ring slot u % 5
+        auto unit_ptr = [&](int u) -> unsigned char * { return smem + (u % 5) * UNIT; };
+        const int n_units = 2 * nk;
+#pragma unroll
+        for (int u = 0; u < 5; ++u)
+            if (u < n_units) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) issue(u >> 1, u & 1, j, unit_ptr(u));
+            }
+        // units 0 and 1 have landed when at most the later ones are outstanding
+        if (n_units >= 5) CS_WAIT_VMCNT_LDS(12);
+        else if (n_units >= 4) CS_WAIT_VMCNT_LDS(8);
+        else CS_WAIT_VMCNT_LDS(0);
+        wg_barrier();
+#pragma unroll
+        for (int s = 0; s < 3; ++s) read_a(smem, s);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) read_b(smem + UNIT, 0, j);
+        for (int ki = 0; ki < nk; ++ki) {
+            const unsigned char *ua = unit_ptr(2 * ki), *ub = unit_ptr(2 * ki + 1);
+            const unsigned char *nua = unit_ptr(2 * ki + 2), *nub = unit_ptr(2 * ki + 3);
+            const bool more = ki + 1 < nk;   // uniform
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (s == 13 && more) {
+                    if (2 * ki + 4 < n_units) CS_WAIT_VMCNT_LDS(4);
+                    else CS_WAIT_VMCNT_LDS(0);
+                    wg_barrier();
+                }
+                // the direct load of this slot, if any: unit and load index
+                int lu = -1, lj = 0;
+                if (s == 13 || s == 15) { lu = 2 * ki + 5; lj = (s - 13) >> 1; }
+                else if (s == 1 || s == 3) { lu = ki >= 1 ? 2 * ki + 3 : -1; lj = 2 + (s >> 1); }
+                else if (s >= 5 && s <= 11 && (s & 1)) { lu = ki >= 1 ? 2 * ki + 4 : -1; lj = (s - 5) >> 1; }
+                const int i = s & 7, h = s >> 3;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    acc16[i][j] = mma16<F16>(a16[s & 3], b16[h][j], acc16[i][j]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (j == 0) {                              // A fragment of slot s + 3
+                        if (s + 3 < 16) read_a(ua, s + 3);
+                        else if (more) read_a(nua, s + 3 - 16);
+                    }
+                    if (j == 1) {                              // W fragments of the next k half
+                        if (s >= 4 && s < 8) read_b(ub, 1, s - 4);
+                        else if (s >= 13 && s < 15 && more) read_b(nub, 0, 2 * (s - 13));
+                    }
+                    if (j == 2 && s >= 13 && s < 15 && more) read_b(nub, 0, 2 * (s - 13) + 1);
+                    if (j == 3 && lu >= 0 && lu < n_units) issue(lu >> 1, lu & 1, lj, unit_ptr(lu));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else
+    {
     // Pipeline: k-tiles kt+1 .. kt+NS-1 are in flight while k-tile kt is multiplied.  Direct loads
     // complete in order per wave, so "at most PER_TILE * r outstanding" means this wave's part of tile
     // kt has landed when r tiles were issued after it; the barrier extends that to every wave and also
@@ -168,10 +319,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
     for (int ki = 0; ki < nk; ++ki) {
         const int kt = kb + ki * kstep;
         int after = min(NS - 2, nk - 1 - ki);
-        if (after >= 2) CS_WAIT_VMCNT(2 * PER_TILE);
-        else if (after == 1) CS_WAIT_VMCNT(PER_TILE);
-        else CS_WAIT_VMCNT(0);
-        __syncthreads();
+        if (after >= 2) CS_WAIT_VMCNT_LDS(2 * PER_TILE);
+        else if (after == 1) CS_WAIT_VMCNT_LDS(PER_TILE);
+        else CS_WAIT_VMCNT_LDS(0);
+        wg_barrier();
         const unsigned char *cur = smem + (ki % NS) * STAGE;
         bf16x8 af[2][MI], bfr[2][NI];
         auto read_frags = [&](int buf, int ks) {
@@ -192,21 +343,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         read_frags(0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (ki + NS - 1 < nk) issue_loads((ki + NS - 1) % NS, kt + (NS - 1) * kstep);
-        constexpr int EARLY = 2;   // MFMAs of a k-step issued before the next step's operand reads
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
+        for (int ks = 0; ks < KS; ++ks) {
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int q = 0; q < EARLY; ++q)
-                acc[q / NI][q % NI] = mma<F16>(af[ks & 1][q / NI], bfr[ks & 1][q % NI], acc[q / NI][q % NI]);
+            mfma_range(af[ks & 1], bfr[ks & 1], 0, EARLY);
             __builtin_amdgcn_sched_barrier(0);
-            if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, ks + 1);
+            if (ks + 1 < KS) read_frags((ks + 1) & 1, ks + 1);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int q = EARLY; q < MI * NI; ++q)
-                acc[q / NI][q % NI] = mma<F16>(af[ks & 1][q / NI], bfr[ks & 1][q % NI], acc[q / NI][q % NI]);
+            mfma_range(af[ks & 1], bfr[ks & 1], EARLY, MI * NI);
         }
         __builtin_amdgcn_sched_barrier(0);
+    }
     }
 
     // ---- epilogue.  The accumulator layout of a 32x32 block gives a lane one column and 16 rows, so
@@ -233,14 +380,36 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         }
     }
     constexpr int WNO = (EPI == EPI_SWIGLU) ? WN / 2 : WN;   // output columns of a wave tile
-    constexpr int SROW = WNO + 8;                            // staging row stride in words; 4 * SROW % 64 == 32,
-                                                             // so the two row groups of a write hit disjoint banks
-    static_assert(NW * 32 * SROW * 4 <= NS * STAGE, "epilogue staging does not fit the operand stages");
+    // staging row stride in words: the row groups of a write (two, 4 rows apart, for 32x32 blocks; four for 16x16 blocks)
+    // hit disjoint banks with 4 * SROW % 64 == 32 or 16
+    constexpr int SROW = M16 ? WNO + 4 : WNO + 8;
+    static_assert(NW * 32 * SROW * 4 <= gemm_lds_bytes(BM, BN, BK, NS), "epilogue staging does not fit the operand stages");
     __syncthreads();                                         // every wavefront is done with the operand stages
     float *stg = reinterpret_cast<float *>(smem) + wave * 32 * SROW;
     const int col_l = lane & 31, row_l = (lane >> 5) * 4;    // C layout: column lane%32, rows 8*(e/4) + 4*(lane/32) + e%4
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
+        if constexpr (M16) {
+            // rows 32 i .. 32 i + 31 of the wave tile are the 16-row blocks 2 i and 2 i + 1
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float *srow = stg + (16 * i2 + 4 * (lane >> 4) + e) * SROW + (lane & 15);
+                    if (EPI == EPI_SWIGLU) {
+                        // columns 64 c .. 64 c + 31 hold gate values and the 32 after them the matching up values
+#pragma unroll
+                        for (int j = 0; j < NI16; ++j)
+                            if ((j & 3) < 2) {
+                                float gte = acc16[2 * i + i2][j][e], up = acc16[2 * i + i2][j + 2][e];
+                                srow[(j >> 2) * 32 + (j & 1) * 16] = gte * __builtin_amdgcn_rcpf(1.0f + __expf(-gte)) * up;
+                            }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < NI16; ++j) srow[j * 16] = acc16[2 * i + i2][j][e];
+                    }
+                }
+        } else
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             float *srow = stg + ((e >> 2) * 8 + row_l + (e & 3)) * SROW + col_l;
@@ -375,6 +544,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
 #pragma unroll
         for (int i = 0; i < PF_VEC; ++i) asm volatile("" ::"v"(pfv[i]));   // the loads must not be dropped as unused
     }
+#endif
 }
 
 // The number of activation terms is a template parameter, so the one-term and the two-term launches
@@ -384,7 +554,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS, int EPI, int
 static hipError_t launch_inst(const GemmTune &tune, const bf16 *A, const bf16 *W, void *out, int M, int N, int K, int n_base,
                               int n_cols, int out_terms, hipStream_t s, const RopeArgs *rope = nullptr,
                               const PrefetchArgs *pf = nullptr) {
-    constexpr int smem = NS * (BM + BN) * BK * 2;
+    constexpr int smem = gemm_lds_bytes(BM, BN, BK, NS);
     static std::atomic<uint32_t> attr_done{0};
     auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, A_FMT>;
     if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
@@ -414,9 +584,9 @@ static hipError_t launch_tile(const GemmTune &tune, const bf16 *A, const bf16 *W
         return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 2>(tune, A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
     if (a_fmt == 3) {
         // fp16 operands: built for the tile shapes the default choice uses
-        constexpr bool has_f16 = BK == 64 && NS == 2 && ((BM == 128 && BN == 128 && WAVES_M == 2 && WAVES_N == 2) ||
-                                                           (BM == 256 && BN == 256 && WAVES_M == 2 && WAVES_N == 4) ||
-                                                           (BM == 192 && BN == 96 && WAVES_M == 2 && WAVES_N == 3));
+        constexpr bool has_f16 = (BK == 64 && NS == 2 && ((BM == 128 && BN == 128 && WAVES_M == 2 && WAVES_N == 2) ||
+                                                            (BM == 192 && BN == 96 && WAVES_M == 2 && WAVES_N == 3))) ||
+                                 (BM == 256 && BN == 256 && WAVES_M == 2);
         if constexpr (has_f16)
             return launch_inst<BM, BN, WAVES_M, WAVES_N, BK, NS, EPI, 3>(tune, A, W, out, M, N, K, n_base, n_cols, out_fmt, s, rope, pf);
         else
@@ -468,7 +638,7 @@ static hipError_t launch_epi(const GemmTune &tune, const bf16 *A, const bf16 *W,
             if ((long)(tn - full) * tm <= 128) n1 = full;
         }
         if (n1 > 0) {
-            hipError_t e = launch_tile<256, 256, 2, 4, 64, 2, EPI>(tune, A, W, out, M, N, K, 0, n1 * 256, a_terms, out_terms, s, nullptr, pf);
+            hipError_t e = launch_tile<256, 256, 2, 4, 64, 5, EPI>(tune, A, W, out, M, N, K, 0, n1 * 256, a_terms, out_terms, s, nullptr, pf);
             if (e != hipSuccess) return e;
         }
         if (n1 < tn)
@@ -479,7 +649,7 @@ static hipError_t launch_epi(const GemmTune &tune, const bf16 *A, const bf16 *W,
     if (tile == 4 && N % 256 != 0) tile = 1;
     if (tile == 7 && (N % 96 != 0 || EPI == EPI_SWIGLU)) tile = 1;
     switch (tile) {
-        case 4: return launch_tile<256, 256, 2, 4, 64, 2, EPI>(tune, A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
+        case 4: return launch_tile<256, 256, 2, 4, 64, 5, EPI>(tune, A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
         case 7:
             if constexpr (EPI != EPI_SWIGLU) return launch_tile<192, 96, 2, 3, 64, 2, EPI>(tune, A, W, out, M, N, K, 0, N, a_terms, out_terms, s);
             else return hipErrorInvalidValue;   // not reached: a SwiGLU column pair needs 64-column wave tiles
@@ -708,9 +878,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_resid_norm_kernel(const flo
 template <int A_FMT, int BT, int WAVES_N>
 static hipError_t launch_splitk_tiles(const GemmTune &tune, const bf16 *A, const bf16 *W, float *part, int M, int N, int K,
                                       int splits, hipStream_t s) {
-    constexpr int smem = 2 * (BT + BT) * 64 * 2;
+    constexpr int SBK = 64, SNS = BT == 256 ? 5 : 2;
+    constexpr int smem = gemm_lds_bytes(BT, BT, SBK, SNS);
     static std::atomic<uint32_t> attr_done{0};
-    auto kern = gemm_bf16_kernel<BT, BT, 2, WAVES_N, 64, 2, EPI_STORE_F32, A_FMT>;
+    auto kern = gemm_bf16_kernel<BT, BT, 2, WAVES_N, SBK, SNS, EPI_STORE_F32, A_FMT>;
     if (hipError_t e = set_dynamic_lds_once(attr_done, reinterpret_cast<const void *>(kern), smem); e != hipSuccess) return e;
     int tiles_m = (M + BT - 1) / BT, tiles_n = N / BT;
     dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8, splits);
@@ -801,7 +972,7 @@ hipError_t launch_gemm_bf16_rope(const GemmTune &tune, const bf16 *A, const bf16
         return hipGetLastError();
     }
     if (prefer_256_tiles(M, N))
-        return launch_tile<256, 256, 2, 4, 64, 2, EPI_ROPE>(tune, A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
+        return launch_tile<256, 256, 2, 4, 64, 5, EPI_ROPE>(tune, A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
     return launch_tile<128, 128, 2, 2, 64, 2, EPI_ROPE>(tune, A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
 }
 
