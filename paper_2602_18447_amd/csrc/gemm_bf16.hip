@@ -1,16 +1,21 @@
 // bf16 x bf16 -> fp32 GEMM on the gfx950 matrix cores: C[M,N] = A[M,K] . W[N,K]^T.
 //
-// Both operands are K-contiguous, which is exactly the per-lane operand shape of
-// v_mfma_f32_32x32x16_bf16 (lane l supplies 8 consecutive k of row/column l%32, k-group l/32).
+// Both operands are K-contiguous, which is exactly the per-lane operand shape of the 16-bit MFMAs: 8 consecutive k of
+// one row / column per lane (v_mfma_f32_32x32x16: row lane % 32, k-group lane / 32; v_mfma_f32_16x16x32: row lane % 16,
+// k-group lane / 16).
 //
-// Data path.  Operand tiles travel global -> LDS directly (global_load_lds_dwordx4): no staging
-// registers, no ds_write instructions, the wave keeps issuing MFMAs while the data lands.  One such
-// instruction fills 1 KiB of LDS in lane order, i.e. 8 tile rows of 64 k (128 bytes) each.  Rows are
-// unpadded; instead the 16-byte k-vector g of row r is kept at position g ^ ((r >> 1) & 7) of its row
-// (the lane that fills a position fetches the matching global vector), so the 16 lanes of one
-// ds_read_b128 phase - 16 consecutive rows, same k-vector - hit 16 different 4-bank groups.
-// Two LDS stages: the loads of k-tile i+1 are issued right after the barrier that frees their stage
-// and have the whole MFMA phase of k-tile i to complete; one vmcnt wait + barrier per k-tile.
+// Data path.  Operand tiles travel global -> LDS directly (buffer_load_dwordx4 ... lds): no staging registers, no
+// ds_write instructions, the wave keeps issuing MFMAs while the data lands.  One such instruction fills 1 KiB of LDS in
+// lane order, i.e. 8 tile rows of 64 k (128 bytes) each; its address is a scalar buffer resource (the tile's first row),
+// a per-lane 32-bit offset that never changes and the k-tile's offset in a scalar register, so issuing one costs no
+// vector instruction.  Rows are unpadded; instead the 16-byte k-vector g of row r is kept at position g ^ ((r >> 1) & 7)
+// of its row (the lane that fills a position fetches the matching global vector), so the 16 lanes of one ds_read_b128
+// phase - 16 consecutive rows, same k-vector - hit 16 different 4-bank groups.
+// Two pipelines: 256 x 256 tiles run 16x16x32 MFMAs on a ring of five half-stage LDS units with the loads spread between
+// the MFMAs (described where it is written); the smaller tiles, of which a CU holds two independent workgroups, keep two
+// (or four) whole stages: the loads of the next k-tile(s) are issued right behind the barrier that frees their stage.
+// Barriers inside the k loops are bare s_barrier instructions with explicit waits: __syncthreads() carries fences that
+// make the compiler wait for every outstanding direct load.
 //
 // Epilogues: plain fp32 store, fp32 residual add in place, or SwiGLU on interleaved gate/up columns
 // with a bf16 result; each wavefront transposes its accumulators through LDS so that global memory is
@@ -599,14 +604,14 @@ static hipError_t launch_tile(const GemmTune &tune, const bf16 *A, const bf16 *W
 // N % 96 == 0 and no SwiGLU); all with 64-element k-tiles in 2 stages.  Measured on the draft-model shapes: 4 is the
 // fastest for the wide gate/up projection, 1 or 7 for the others.
 // 256 x 256 tiles (one workgroup per CU, rounds of 256) or 128 x 128 tiles (two per CU, rounds of 512) for an output
-// that is not split?  Measured time per k-tile of a round: 1.6 us for the large tile however full the round is; for the
+// that is not split?  Measured time per k-tile of a round: 1.4 us for the large tile however full the round is; for the
 // small tile 1.1 us for a full round, 0.73 us when every CU holds at most one workgroup, in between linearly.
 static bool prefer_256_tiles(int M, int N) {
     if (N % 256 != 0) return false;
     long t128 = (long)((M + 127) / 128) * (N / 128), t256 = (long)((M + 255) / 256) * (N / 256);
     long rem = t128 % 512;
     double c128 = (double)(t128 / 512) * 1.1 + (rem == 0 ? 0.0 : rem <= 256 ? 0.73 : 0.73 + (double)(rem - 256) / 256.0 * 0.37);
-    double c256 = (double)((t256 + 255) / 256) * 1.6;
+    double c256 = (double)((t256 + 255) / 256) * 1.4;
     return c256 < c128;
 }
 
