@@ -44,7 +44,8 @@ def _pack_rows(F):
 
 # --------------------------------------------------------------------------- #
 @pytest.mark.parametrize("tile", [1, 4, 7])
-@pytest.mark.parametrize("M,N,K", [(300, 512, 192), (1, 256, 64), (257, 768, 1024), (512, 256, 320), (400, 384, 128)])
+@pytest.mark.parametrize("M,N,K", [(300, 512, 192), (1, 256, 64), (257, 768, 1024), (512, 256, 320), (400, 384, 128),
+                                   (300, 512, 128), (259, 256, 256), (700, 512, 384)])   # 2, 4 and 6 k-tiles: the ring's first rounds
 def test_gemm_bf16_store_and_residual(tile, M, N, K):
     print(f"gemm bf16 tile={tile} M={M} N={N} K={K}", flush=True)
     ctx, _ = _ctx("bf16")
