@@ -976,8 +976,21 @@ hipError_t launch_gemm_bf16_rope(const GemmTune &tune, const bf16 *A, const bf16
         splitk_reduce_rope_kernel<<<grid, 256, 0, s>>>(splitk_ws, splits, M, N, rope);
         return hipGetLastError();
     }
-    if (prefer_256_tiles(M, N))
-        return launch_tile<256, 256, 2, 4, 64, 5, EPI_ROPE>(tune, A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
+    if (prefer_256_tiles(M, N)) {
+        // as in launch_epi: a last round of 256 x 256 tiles that would be less than half full goes to a second launch with
+        // 128 x 128 tiles (18606 rows x 2048 columns: 584 tiles = 2 rounds + 72 tiles)
+        int tm = (M + 255) / 256, tn = N / 256, n1 = tn;
+        long t256 = (long)tm * tn, rounds = t256 / 256;
+        if (rounds >= 1 && t256 - rounds * 256 > 0) {
+            int full = (int)(rounds * 256 / tm);
+            if ((long)(tn - full) * tm <= 128) n1 = full;
+        }
+        if (n1 > 0) {
+            hipError_t e = launch_tile<256, 256, 2, 4, 64, 5, EPI_ROPE>(tune, A, W_perm, nullptr, M, N, K, 0, n1 * 256, a_terms, 1, s, &rope);
+            if (e != hipSuccess || n1 == tn) return e;
+        }
+        return launch_tile<128, 128, 2, 2, 64, 2, EPI_ROPE>(tune, A, W_perm, nullptr, M, N, K, n1 * 256, N - n1 * 256, a_terms, 1, s, &rope);
+    }
     return launch_tile<128, 128, 2, 2, 64, 2, EPI_ROPE>(tune, A, W_perm, nullptr, M, N, K, 0, N, a_terms, 1, s, &rope);
 }
 

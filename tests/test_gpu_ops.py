@@ -213,6 +213,44 @@ def _perm_head_rows(n_heads):
     return np.where(blk == 1, p + 32, np.where(blk == 2, p - 32, p))
 
 
+@pytest.mark.parametrize("a_terms", [1, 3])
+def test_qkv_projection_many_rows_last_round_cut_off(a_terms):
+    """8448 rows x 2048 columns are 264 tiles of 256 x 256: one full round and a last column of 33 tiles, which the
+    launcher hands to a second launch with 128 x 128 tiles; every element against the oracle's projection + rope."""
+    print(f"qkv + rope fused, 8448 rows, a_terms={a_terms}", flush=True)
+    hd, d = 128, 256
+    wl = W.tiny_workload("qkvwide", 33, dtype="bf16", n_q_heads=12, n_kv_heads=2, head_dim=hd, d_model=d,
+                         prefix_lens=tuple(100 * i for i in range(33)), suffix_lens=(256,) * 33, block_size=16)
+    m = wl.model
+    ctx, _ = _ctx("bf16", head_dim=hd, d_model=d, n_q_heads=12, n_kv_heads=2)
+    batch = W.make_batch(wl, DEV)
+    bs, keep = _batch_structs(wl, batch)
+    T = wl.T
+    assert T == 8448
+    heads = m.n_q_heads + 2 * m.n_kv_heads
+    full = _rand((T, d), torch.float32, 41)
+    Wn = _rand((heads * hd, d), torch.float32, 42, 0.1)
+    dt = torch.float16 if a_terms == 3 else torch.bfloat16
+    h, Wt = full.to(dt), Wn.to(dt)
+    Wp = Wt[torch.as_tensor(_perm_head_rows(heads), device=DEV)].contiguous()
+    bf = torch.bfloat16
+    q = torch.zeros((T + 1, m.n_q_heads, hd), dtype=bf, device=DEV)
+    k = torch.zeros((T + 1, m.n_kv_heads, hd), dtype=bf, device=DEV)
+    v = torch.zeros((T + 1, m.n_kv_heads, hd), dtype=bf, device=DEV)
+    ws = torch.empty(cb.confspec_workspace_bytes(ctx, T, wl.B), dtype=torch.uint8, device=DEV)
+    cb.confspec_op_qkv_rope(ctx, bs, 4096, h, a_terms, Wp, q, k, v, ws)
+    torch.cuda.synchronize()
+    a = (f64(h) @ f64(Wt).T).reshape(T, heads, hd)
+    pos = np.concatenate([L + np.arange(S) for L, S in zip(wl.prefix_lens, wl.suffix_lens)])
+    rq = O.rope(a[:, :m.n_q_heads], pos, m.rope_theta)
+    rk = O.rope(a[:, m.n_q_heads:m.n_q_heads + m.n_kv_heads], pos, m.rope_theta)
+    rv = a[:, m.n_q_heads + m.n_kv_heads:]
+    for got, ref in ((q, rq), (k, rk), (v, rv)):
+        assert np.abs(f64(got[:T]) - ref).max() <= (2.0 ** -8 + 2e-5) * np.abs(ref).max()
+        assert torch.all(got[T] == 0)
+    cb.confspec_destroy(ctx)
+
+
 @pytest.mark.parametrize("a_terms,with_lo", [(1, False), (3, False), (2, True)])
 @pytest.mark.parametrize("suffix_lens", [(5, 3, 9), (200, 77, 130)])
 @pytest.mark.parametrize("d", [256, 1024])      # 1024: enough k-tiles for the split-K path at these row counts
