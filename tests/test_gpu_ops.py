@@ -87,12 +87,14 @@ def test_gemm_bf16_swiglu_epilogue(tile):
     cb.confspec_destroy(ctx)
 
 
-def test_two_term_activations_through_gemm_rmsnorm_and_swiglu():
+@pytest.mark.parametrize("tile", [0, 4])      # 4: the 256 x 256 tile's pipeline with the hi / lo k-tiles alternating
+def test_two_term_activations_through_gemm_rmsnorm_and_swiglu(tile):
     """hi | lo operands: the GEMM must return (hi + lo) . W^T, i.e. the product with the activation
     kept to 16 mantissa bits, and the producers must emit hi = bf16(v), lo = bf16(v - hi)."""
-    print("two-term activations", flush=True)
+    print(f"two-term activations, tile {tile}", flush=True)
     d = 512
     ctx, base = _ctx("bf16", d_model=d)
+    cb.confspec_tune(ctx, "gemm_tile", tile)
     M, N, K = 150, 512, d
     x = _rand((M, d), torch.float32, 40, 2.0)
     g = (1 + 0.1 * _rand((d,), torch.float32, 41)).to(torch.bfloat16)
