@@ -454,6 +454,49 @@ def _optional_legs(args, st, dev):
 
     if args.cascade:
         extra["cascade"] = _time_cascade(W, wl, ver, kv, batch, vids, dev, max(args.steps // 2, 3))
+
+    if args.vendor_gemm:
+        # Context, not a target: the vendor BLAS library (through torch.matmul, bf16, no fused epilogue) and this library's
+        # GEMM entry on the workload's four projection shapes, stand-alone, each over rotating weight copies; the first
+        # launches of a shape run before the timed ones.
+        from paper_2602_18447_amd import binding as cb
+        T, d, F = wl.T, m.d_model, m.d_ffn
+        qkv_n = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim
+        shapes = [("qkv", T, qkv_n, d, cb.EPI_STORE_F32), ("o_proj", T, d, m.n_q_heads * m.head_dim, cb.EPI_RESID_F32),
+                  ("gate_up", T, 2 * F, d, cb.EPI_SWIGLU), ("down", T, d, F, cb.EPI_RESID_F32)]
+        ctx = cb.confspec_create(cb.make_model_cfg(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ffn,
+                                                   m.vocab, m.rope_theta, m.rms_eps, m.dtype))
+        res = {}
+        for name, M_, N_, K_, epi in shapes:
+            A = (torch.randn(M_, K_, device=dev) * 0.5).to(torch.bfloat16)
+            Ws = [(torch.randn(N_, K_, device=dev) * 0.02).to(torch.bfloat16) for _ in range(3)]
+            out = (torch.empty(M_, N_ // 2, dtype=torch.bfloat16, device=dev) if epi == cb.EPI_SWIGLU
+                   else torch.zeros(M_, N_, dtype=torch.float32, device=dev))
+            nb = cb.confspec_op_gemm_scratch_bytes(ctx, M_, N_, K_, 1)
+            scr = torch.empty(max(nb, 16), dtype=torch.uint8, device=dev) if nb else None
+
+            def timed_us(fn, iters=20):
+                for i in range(6):
+                    fn(i)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(iters):
+                    fn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / iters * 1e3
+            rows = {}
+            for rep in range(2):                      # twice, alternating, so that neither side always runs first
+                rows.setdefault("vendor_us", []).append(timed_us(lambda i: torch.matmul(A, Ws[i % 3].t())))
+                rows.setdefault("this_us", []).append(timed_us(lambda i: cb.confspec_op_gemm(ctx, A, Ws[i % 3], out, M_, N_, K_, epi, 1, 1, scr)))
+            fl = 2.0 * M_ * N_ * K_
+            v, o = min(rows["vendor_us"]), min(rows["this_us"])
+            res[name] = dict(M=M_, N=N_, K=K_, vendor_us=round(v, 1), vendor_tflops=round(fl / v / 1e6, 1),
+                             this_us=round(o, 1), this_tflops=round(fl / o / 1e6, 1),
+                             note="this library's figure includes its fused epilogue (residual add / SwiGLU)")
+            del A, Ws, out, scr
+        cb.confspec_destroy(ctx)
+        extra["vendor_gemm"] = res
     return extra
 
 
@@ -478,6 +521,9 @@ def main():
                     help="with --config: also time the pass with groups of W traces reading the same context pages")
     ap.add_argument("--decode", type=int, default=0, metavar="N",
                     help="with --config: also time N greedy generation steps (one new token per trace)")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="with --config: also time the workload's four projection shapes stand-alone, with the vendor BLAS "
+                         "library (torch.matmul) and with this library's GEMM entry")
     ap.add_argument("--cpu-baseline-traces", type=int, default=-1,
                     help="traces of the headline workload the CPU oracle is timed on (0 = skip every CPU leg)")
     args = ap.parse_args()
