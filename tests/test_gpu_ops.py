@@ -67,6 +67,39 @@ def test_gemm_bf16_store_and_residual(tile, M, N, K):
     cb.confspec_destroy(ctx)
 
 
+def test_gemm_bf16_seeded_random_shapes():
+    """48 seeded shapes (rows 1..900, 128..1280 columns, 1..20 k-tiles), every tile choice, store / residual epilogue,
+    bf16 and fp16 operands, with and without split-K scratch: every element against the fp64 product."""
+    rng = np.random.default_rng(20260218)
+    ctx, _ = _ctx("bf16")
+    for case in range(48):
+        M = int(rng.integers(1, 901))
+        N = 128 * int(rng.integers(1, 11))
+        K = 64 * int(rng.integers(1, 21))
+        tile = int(rng.choice([0, 1, 4, 7]))
+        epi = int(rng.choice([cb.EPI_STORE_F32, cb.EPI_RESID_F32]))
+        f16 = bool(rng.integers(0, 2))
+        with_scratch = bool(rng.integers(0, 2))
+        print(f"case {case}: M={M} N={N} K={K} tile={tile} epi={epi} f16={f16} scratch={with_scratch}", flush=True)
+        cb.confspec_tune(ctx, "gemm_tile", tile)
+        dt = torch.float16 if f16 else torch.bfloat16
+        A = _rand((M, K), dt, 1000 + case)
+        Wt = _rand((N, K), dt, 2000 + case, 0.05)
+        ref = f64(A) @ f64(Wt).T
+        x0 = _rand((M + 2, N), torch.float32, 3000 + case)           # two guard rows
+        out = x0.clone()
+        scr = None
+        if with_scratch and tile == 0:
+            nb = cb.confspec_op_gemm_scratch_bytes(ctx, M, N, K, 3 if f16 else 1)
+            scr = torch.empty(max(nb, 16), dtype=torch.uint8, device=DEV) if nb else None
+        cb.confspec_op_gemm(ctx, A, Wt, out, M, N, K, epi, 3 if f16 else 1, 1, scr)
+        torch.cuda.synchronize()
+        want = ref + (f64(x0[:M]) if epi == cb.EPI_RESID_F32 else 0.0)
+        assert np.abs(f64(out[:M]) - want).max() <= 2e-5 * max(np.abs(ref).max(), 4.0), case
+        assert torch.equal(out[M:], x0[M:]), case
+    cb.confspec_destroy(ctx)
+
+
 @pytest.mark.parametrize("tile", [1, 4])
 def test_gemm_bf16_swiglu_epilogue(tile):
     print(f"gemm bf16 swiglu tile={tile}", flush=True)
