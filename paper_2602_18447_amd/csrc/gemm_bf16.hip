@@ -243,11 +243,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
 #pragma unroll
         for (int h = 0; h < 2; ++h) kv_off[h] = ((4 * h + kq) ^ sw16) * 16;
         bf16x8 a16[4], b16[2][4];
-        auto read_a = [&](const unsigned char *ua, int s) __attribute__((always_inline)) {   // slot s of the k-tile at ua
-            a16[s & 3] = *reinterpret_cast<const bf16x8 *>(ua + a_row_off + (s & 7) * 16 * ROWB + kv_off[s >> 3]);
+        // this lane's fragment offsets inside a unit for the two k halves; per k-tile they are added to the units' bases
+        // once (five additions), every read is then that pointer plus a constant
+        int a_lane[2], b_lane[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) { a_lane[h] = a_row_off + kv_off[h]; b_lane[h] = b_row_off + kv_off[h]; }
+        auto read_a = [&](const unsigned char *pa, int s) __attribute__((always_inline)) {   // slot s; pa: the k half's pointer
+            a16[s & 3] = *reinterpret_cast<const bf16x8 *>(pa + (s & 7) * 16 * ROWB);
         };
-        auto read_b = [&](const unsigned char *ub, int h, int j) __attribute__((always_inline)) {
-            b16[h][j] = *reinterpret_cast<const bf16x8 *>(ub + b_row_off + j * 16 * ROWB + kv_off[h]);
+        auto read_b = [&](const unsigned char *pb, int h, int j) __attribute__((always_inline)) {
+            b16[h][j] = *reinterpret_cast<const bf16x8 *>(pb + j * 16 * ROWB);
         };
         // direct load j of the A (w == 0) or W (w == 1) part of k-tile t of this workgroup's loop into LDS at dst
         auto issue = [&](int t, int w, int j, unsigned char *dst) __attribute__((always_inline)) {
@@ -272,12 +277,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         else CS_WAIT_VMCNT_LDS(0);
         wg_barrier();
 #pragma unroll
-        for (int s = 0; s < 3; ++s) read_a(smem, s);
+        for (int s = 0; s < 3; ++s) read_a(smem + a_lane[0], s);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) read_b(smem + UNIT, 0, j);
+        for (int j = 0; j < 4; ++j) read_b(smem + UNIT + b_lane[0], 0, j);
+        int sl0 = 0;   // ring slot of unit 2 ki (the A part of the current k-tile); the following units in the next slots
         for (int ki = 0; ki < nk; ++ki) {
-            const unsigned char *ua = unit_ptr(2 * ki), *ub = unit_ptr(2 * ki + 1);
-            const unsigned char *nua = unit_ptr(2 * ki + 2), *nub = unit_ptr(2 * ki + 3);
+            auto next_slot = [](int v) { return v == 4 ? 0 : v + 1; };
+            const int sl1 = next_slot(sl0), sl2 = next_slot(sl1), sl3 = next_slot(sl2), sl4 = next_slot(sl3);   // units 2 ki + 1 .. + 4
+            unsigned char *const u0 = smem + sl0 * UNIT, *const u3 = smem + sl3 * UNIT, *const u4 = smem + sl4 * UNIT;
+            const unsigned char *ua = u0, *ub = smem + sl1 * UNIT;
+            const unsigned char *pa0 = ua + a_lane[0], *pa1 = ua + a_lane[1], *pb1 = ub + b_lane[1];
+            const unsigned char *npa0 = smem + sl2 * UNIT + a_lane[0], *npb0 = u3 + b_lane[0];
             const bool more = ki + 1 < nk;   // uniform
 #pragma unroll
             for (int s = 0; s < 16; ++s) {
@@ -289,9 +299,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
                 }
                 // the direct load of this slot, if any: unit and load index
                 int lu = -1, lj = 0;
+                unsigned char *ldst = u0;                      // unit 2 ki + 5 takes the slot of unit 2 ki
                 if (s == 13 || s == 15) { lu = 2 * ki + 5; lj = (s - 13) >> 1; }
-                else if (s == 1 || s == 3) { lu = ki >= 1 ? 2 * ki + 3 : -1; lj = 2 + (s >> 1); }
-                else if (s >= 5 && s <= 11 && (s & 1)) { lu = ki >= 1 ? 2 * ki + 4 : -1; lj = (s - 5) >> 1; }
+                else if (s == 1 || s == 3) { lu = ki >= 1 ? 2 * ki + 3 : -1; lj = 2 + (s >> 1); ldst = u3; }
+                else if (s >= 5 && s <= 11 && (s & 1)) { lu = ki >= 1 ? 2 * ki + 4 : -1; lj = (s - 5) >> 1; ldst = u4; }
                 const int i = s & 7, h = s >> 3;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -299,18 +310,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
                     acc16[i][j] = mma16<F16>(a16[s & 3], b16[h][j], acc16[i][j]);
                     __builtin_amdgcn_sched_barrier(0);
                     if (j == 0) {                              // A fragment of slot s + 3
-                        if (s + 3 < 16) read_a(ua, s + 3);
-                        else if (more) read_a(nua, s + 3 - 16);
+                        if (s + 3 < 16) read_a(s + 3 < 8 ? pa0 : pa1, s + 3);
+                        else if (more) read_a(npa0, s + 3 - 16);
                     }
                     if (j == 1) {                              // W fragments of the next k half
-                        if (s >= 4 && s < 8) read_b(ub, 1, s - 4);
-                        else if (s >= 13 && s < 15 && more) read_b(nub, 0, 2 * (s - 13));
+                        if (s >= 4 && s < 8) read_b(pb1, 1, s - 4);
+                        else if (s >= 13 && s < 15 && more) read_b(npb0, 0, 2 * (s - 13));
                     }
-                    if (j == 2 && s >= 13 && s < 15 && more) read_b(nub, 0, 2 * (s - 13) + 1);
-                    if (j == 3 && lu >= 0 && lu < n_units) issue(lu >> 1, lu & 1, lj, unit_ptr(lu));
+                    if (j == 2 && s >= 13 && s < 15 && more) read_b(npb0, 0, 2 * (s - 13) + 1);
+                    if (j == 3 && lu >= 0 && lu < n_units) issue(lu >> 1, lu & 1, lj, ldst);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
+            sl0 = sl2;
         }
     } else
     {
